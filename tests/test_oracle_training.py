@@ -1,0 +1,208 @@
+"""Pins for the oracle's training arithmetic (oracle parts B and C): torch CPU library routines
+(embedding_bag, optim.SGD, optim.Adagrad with sparse gradients), closed forms on one row, the bf16 rounding
+rule, and the paper's consistency claim (cached training == uncached synchronous training, bit for bit)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+
+
+def rand_problem(seed, rows=50, D=8, bags=40, max_len=5, allow_empty=True):
+    rng = np.random.default_rng(seed)
+    lens = rng.integers(0 if allow_empty else 1, max_len + 1, size=bags)
+    off = np.zeros(bags + 1, dtype=np.int64)
+    off[1:] = np.cumsum(lens)
+    idx = np.minimum(rng.zipf(1.4, size=int(off[-1])) - 1, rows - 1).astype(np.int64)
+    W = rng.uniform(-0.05, 0.05, size=(rows, D)).astype(np.float32)
+    return W, idx, off, rng
+
+
+def torch_bag(W64, idx, off, sparse=True):
+    emb = torch.nn.EmbeddingBag.from_pretrained(torch.from_numpy(W64.copy()), mode="sum", sparse=sparse,
+                                                freeze=False, include_last_offset=True)
+    return emb
+
+
+def test_forward_matches_torch_embedding_bag():
+    W, idx, off, _ = rand_problem(0)
+    out = oracle.train_iter(W, None, 8, oracle.F32, oracle.SGD, 0.0, 0.0, idx, off, None)
+    ref = torch.nn.functional.embedding_bag(torch.from_numpy(idx), torch.from_numpy(W).double(),
+                                            torch.from_numpy(off), mode="sum", include_last_offset=True)
+    assert np.array_equal(out, ref.float().numpy())
+    # an empty bag gives a zero row
+    lens = np.diff(off)
+    assert (lens == 0).any() and not out[lens == 0].any()
+    # one-hot: the output row is a bit-exact copy of the table row
+    assert len(idx) >= 40
+    out1 = oracle.train_iter(W, None, 8, oracle.F32, oracle.SGD, 0.0, 0.0, idx[:40], np.arange(41), None)
+    assert np.array_equal(out1, W[idx[:40]])
+
+
+@pytest.mark.parametrize("opt_name", ["sgd", "adagrad"])
+def test_update_matches_torch_sparse_optimizers(opt_name):
+    """Five iterations with duplicate rows inside and across bags; torch runs in fp64 on the full table, the
+    oracle stores fp32 and computes in fp64, so they agree to fp32 rounding of the stored values."""
+    D, rows = 8, 50
+    W, _, _, rng = rand_problem(1, rows=rows, D=D)
+    lr, eps = 0.01, 1e-8
+    emb = torch_bag(W.astype(np.float64), None, None)
+    if opt_name == "sgd":
+        opt = torch.optim.SGD(emb.parameters(), lr=lr)
+        S, code = None, oracle.SGD
+    else:
+        opt = torch.optim.Adagrad(emb.parameters(), lr=lr, eps=eps, initial_accumulator_value=0.0, lr_decay=0.0)
+        S, code = np.zeros((rows, D), dtype=np.float32), oracle.ADAGRAD
+    Wo = W.copy()
+    for it in range(5):
+        _, idx, off, r2 = rand_problem(100 + it, rows=rows, D=D)
+        g = r2.standard_normal((len(off) - 1, D)).astype(np.float32)
+        out = oracle.train_iter(Wo, S, D, oracle.F32, code, lr, eps, idx, off, g)
+        opt.zero_grad()
+        o = emb(torch.from_numpy(idx), torch.from_numpy(off))
+        np.testing.assert_allclose(out, o.detach().numpy(), rtol=2e-6, atol=1e-7)
+        o.backward(torch.from_numpy(g).double())
+        opt.step()
+    np.testing.assert_allclose(Wo, emb.weight.detach().numpy(), rtol=1e-5, atol=1e-7)
+    if S is not None:
+        st = opt.state[emb.weight]["sum"].numpy()
+        np.testing.assert_allclose(S, st, rtol=1e-5, atol=1e-9)
+    assert np.abs(Wo - W).max() > 1e-3            # the update did something
+
+
+def test_sgd_closed_form_one_row_duplicates():
+    """w_T = w_0 - lr * sum of all gradients that hit the row (duplicates inside an iteration add up)."""
+    D = 4
+    W = np.array([[0.01, -0.02, 0.03, 0.04], [1, 1, 1, 1]], dtype=np.float32)
+    g = np.array([[1, 2, 3, 4], [10, 20, 30, 40], [0.5, 0.5, 0.5, 0.5]], dtype=np.float32)
+    idx = np.array([0, 0, 0], dtype=np.int64)          # bag0 = {0,0}, bag1 = {0}, bag2 = {}
+    off = np.array([0, 2, 3, 3], dtype=np.int64)
+    out = oracle.train_iter(W, None, D, oracle.F32, oracle.SGD, 0.5, 0.0, idx, off, g)
+    assert np.array_equal(out[0], np.float32(2) * np.array([0.01, -0.02, 0.03, 0.04], dtype=np.float32))
+    assert not out[2].any()
+    G = 2 * g[0].astype(np.float64) + g[1]
+    want = (np.array([0.01, -0.02, 0.03, 0.04], dtype=np.float32).astype(np.float64) - 0.5 * G).astype(np.float32)
+    assert np.array_equal(W[0], want)
+    assert np.array_equal(W[1], np.ones(4, dtype=np.float32))        # untouched row
+
+
+def test_adagrad_coalesces_before_squaring():
+    """Two lookups of one row with gradients a and b: state grows by (a+b)^2, not a^2+b^2."""
+    W = np.zeros((1, 1), dtype=np.float32)
+    S = np.zeros((1, 1), dtype=np.float32)
+    g = np.array([[3.0], [4.0]], dtype=np.float32)
+    oracle.train_iter(W, S, 1, oracle.F32, oracle.ADAGRAD, 0.1, 0.0, np.array([0, 0]), np.array([0, 1, 2]), g)
+    assert S[0, 0] == 49.0
+    assert W[0, 0] == -np.float32(0.1)
+
+
+def test_rowwise_adagrad_closed_form_and_d1_equivalence():
+    D = 4
+    W = np.full((2, D), 0.5, dtype=np.float32)
+    S = np.zeros(2, dtype=np.float32)
+    g = np.array([[1, 2, 3, 4]], dtype=np.float32)
+    oracle.train_iter(W, S, D, oracle.F32, oracle.ADAGRAD_ROWWISE, 0.1, 1e-8, np.array([1]), np.array([0, 1]), g)
+    assert S[0] == 0 and S[1] == np.float32(30.0 / 4.0)
+    lr = np.float64(np.float32(0.1))                       # lr and eps reach the oracle as fp32 values
+    want = 0.5 - lr * g[0].astype(np.float64) / (np.sqrt(np.float64(7.5)) + np.float64(np.float32(1e-8)))
+    assert np.array_equal(W[1], want.astype(np.float32))
+    assert np.array_equal(W[0], np.full(D, 0.5, dtype=np.float32))
+    # D = 1: row-wise and element-wise are the same rule
+    rng = np.random.default_rng(5)
+    Wa = rng.uniform(-1, 1, (20, 1)).astype(np.float32)
+    Wb = Wa.copy()
+    Sa = np.zeros((20, 1), dtype=np.float32)
+    Sb = np.zeros(20, dtype=np.float32)
+    for it in range(4):
+        idx = rng.integers(0, 20, size=30)
+        off = np.arange(31, dtype=np.int64)
+        gg = rng.standard_normal((30, 1)).astype(np.float32)
+        oracle.train_iter(Wa, Sa, 1, oracle.F32, oracle.ADAGRAD, 0.05, 1e-8, idx, off, gg)
+        oracle.train_iter(Wb, Sb, 1, oracle.F32, oracle.ADAGRAD_ROWWISE, 0.05, 1e-8, idx, off, gg)
+    assert np.array_equal(Wa, Wb) and np.array_equal(Sa[:, 0], Sb)
+
+
+def test_bf16_storage_rounds_to_nearest_even():
+    rng = np.random.default_rng(3)
+    w32 = rng.uniform(-0.05, 0.05, size=(64, 8)).astype(np.float32)
+    wb = torch.from_numpy(w32).to(torch.bfloat16)
+    table = wb.view(torch.int16).numpy().view(np.uint16).copy()
+    g = rng.standard_normal((64, 8)).astype(np.float32)
+    idx = np.arange(64, dtype=np.int64)
+    off = np.arange(65, dtype=np.int64)
+    out = oracle.train_iter(table, None, 8, oracle.BF16, oracle.SGD, 0.01, 0.0, idx, off, g)
+    assert np.array_equal(out, wb.float().numpy())                   # exact up-conversion
+    lr = np.float64(np.float32(0.01))
+    want = torch.from_numpy((wb.double().numpy() - lr * g.astype(np.float64)).astype(np.float32)).to(torch.bfloat16)
+    assert np.array_equal(table, want.view(torch.int16).numpy().view(np.uint16))
+    # exact ties go to the even mantissa: 1 + 2^-8 is half-way between bf16(1) and the next value
+    t2 = torch.tensor([[1.0]], dtype=torch.bfloat16).view(torch.int16).numpy().view(np.uint16).copy()
+    oracle.train_iter(t2, None, 1, oracle.BF16, oracle.SGD, 1.0, 0.0, np.array([0]), np.array([0, 1]),
+                      np.array([[-(2.0 ** -8)]], dtype=np.float32))
+    assert t2[0, 0] == 0x3F80
+    oracle.train_iter(t2, None, 1, oracle.BF16, oracle.SGD, 1.0, 0.0, np.array([0]), np.array([0, 1]),
+                      np.array([[-3 * (2.0 ** -8)]], dtype=np.float32))
+    assert t2[0, 0] == 0x3F82                                       # 1 + 3*2^-8 -> 1 + 2*2^-7 (even)
+
+
+def run_uncached(cfg, trace, T):
+    R, D = cfg.total_rows, cfg.dim
+    dt, op = oracle.DTYPES[cfg.weight_dtype], oracle.OPTIMIZERS[cfg.optimizer]
+    W = workloads.init_weights(cfg, 0, R)
+    W = (W.to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16).copy() if dt == oracle.BF16
+         else W.numpy().copy())
+    S = np.zeros(oracle.state_shape(R, D, op), dtype=np.float32)
+    outs = []
+    for i in range(T):
+        g = workloads.upstream_grad(cfg, i, trace.bag_offsets.shape[1] - 1).numpy()
+        outs.append(oracle.train_iter(W, S, D, dt, op, cfg.lr, cfg.eps, trace.iter_ids(i), trace.bag_offsets[i], g))
+    return W, S, outs
+
+
+def run_cached(cfg, trace, T, plan):
+    R, D, C = cfg.total_rows, cfg.dim, cfg.capacity
+    dt, op = oracle.DTYPES[cfg.weight_dtype], oracle.OPTIMIZERS[cfg.optimizer]
+    W = workloads.init_weights(cfg, 0, R)
+    W = (W.to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16).copy() if dt == oracle.BF16
+         else W.numpy().copy())
+    S = np.zeros(oracle.state_shape(R, D, op), dtype=np.float32)
+    cw = np.full((C, D), 0x7FC0 if dt == oracle.BF16 else np.nan, dtype=W.dtype)     # poison: unfetched slots
+    cs = np.full(oracle.state_shape(C, D, op), np.nan, dtype=np.float32)
+    outs = []
+    e_ids = np.zeros(0, np.int64)
+    e_slots = np.zeros(0, np.int32)
+    for i in range(T):
+        a, b = plan.prefetch_off[i], plan.prefetch_off[i + 1]
+        oracle.cache_apply(cw, cs, W, S, D, dt, op, e_ids, e_slots, plan.prefetch_ids[a:b], plan.prefetch_slots[a:b])
+        g = workloads.upstream_grad(cfg, i, trace.bag_offsets.shape[1] - 1).numpy()
+        sl = plan.lookup_slots[trace.iter_offsets[i]:trace.iter_offsets[i + 1]]
+        outs.append(oracle.train_iter(cw, cs, D, dt, op, cfg.lr, cfg.eps, sl, trace.bag_offsets[i], g))
+        a, b = plan.evict_off[i], plan.evict_off[i + 1]
+        e_ids, e_slots = plan.evict_ids[a:b], plan.evict_slots[a:b]
+    oracle.cache_apply(cw, cs, W, S, D, dt, op, e_ids, e_slots, np.zeros(0, np.int64), np.zeros(0, np.int32))
+    return W, S, outs
+
+
+@pytest.mark.parametrize("optimizer,dtype,bag_max,capacity", [
+    ("sgd", "f32", 1, 4096), ("adagrad", "f32", 1, 1400), ("adagrad_rowwise", "bf16", 1, 4096),
+    ("sgd", "f32", 6, 3000), ("adagrad", "bf16", 4, 2600)])
+def test_cached_training_equals_uncached(optimizer, dtype, bag_max, capacity):
+    """The consistency claim of Section 3.2: training through the plan and the cache gives exactly the result
+    of synchronous training on the full table — same pooled outputs every iteration, same final table."""
+    cfg = workloads.get_config(0, optimizer=optimizer, weight_dtype=dtype, bag_max=bag_max, capacity=capacity,
+                               batch=128 if bag_max > 1 else 256, iterations=30)
+    tr = workloads.make_trace(cfg)
+    plan = oracle.plan(tr.ids, tr.iter_offsets, cfg.total_rows, cfg.lookahead, cfg.capacity)
+    Wu, Su, ou = run_uncached(cfg, tr, cfg.iterations)
+    Wc, Sc, oc = run_cached(cfg, tr, cfg.iterations, plan)
+    for a, b in zip(ou, oc):
+        assert np.array_equal(a, b)
+    assert np.array_equal(Wu, Wc) and np.array_equal(Su, Sc)
+    # rows never looked up keep their initial value
+    W0 = workloads.init_weights(cfg, 0, cfg.total_rows)
+    touched = np.zeros(cfg.total_rows, dtype=bool)
+    touched[np.unique(tr.ids)] = True
+    if dtype == "f32":
+        assert np.array_equal(Wu[~touched], W0.numpy()[~touched])
+        assert np.abs(Wu[touched] - W0.numpy()[touched]).max() > 0
