@@ -1,0 +1,189 @@
+/*
+ * bagpipe.h — C ABI of the MI355X (gfx950) embedding-access hot path for lookahead-cached
+ * recommendation-model training (Bagpipe, arXiv 2202.12429).
+ *
+ * The four operations follow the paper's division of labour (Section 3.1 "Design Overview",
+ * Section 3.4): the Oracle Cacher plans, the trainer maintains a cache in GPU memory against
+ * embedding servers, and the trainer runs the embedding forward / backward on cached rows.
+ *
+ *   bp_oracle_plan        lookahead planner (Algorithm 1 "Lookahead Algorithm", Section 3.2)
+ *   bp_cache_apply        trainer-side cache maintenance: write back evicted rows, load prefetched rows
+ *                         (Section 3.4 "Trainer"; the backing table stands in for the embedding servers)
+ *   bp_embbag_fwd         EmbeddingBag-sum forward over cache slots (Section 2.1, embedding lookup)
+ *   bp_embbag_bwd_update  deterministic backward + fused sparse optimizer step on cached rows
+ *
+ * Conventions
+ *   - Every function returns BP_OK (0) or a negative bp_status.  bp_last_error_message() gives detail
+ *     for the calling thread's last failure.
+ *   - The library never allocates or frees device or pinned memory: inputs, outputs and workspaces are
+ *     caller-owned and passed as raw pointers.  "device" below means a pointer the GPU can dereference
+ *     (HBM, or pinned host memory from hipHostMalloc, which is device-visible at the same address);
+ *     "host" means ordinary host memory read or written by the CPU inside the call.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the null stream) of the
+ *     current HIP device.  Only bp_oracle_plan synchronises the stream (it returns counts to the host).
+ *   - Rows are `dim` elements of weight_dtype (fp32, or bf16 with fp32 arithmetic and
+ *     round-to-nearest-even stores).  Row pointers must be 16-byte aligned and dim*sizeof(element)
+ *     must be a multiple of 16 bytes for fp32 (dim % 4 == 0) and bf16 (dim % 8 == 0).
+ *   - Optimizer state: BP_SGD none (pass NULL); BP_ADAGRAD fp32 [rows][dim]; BP_ADAGRAD_ROWWISE
+ *     fp32 [rows].  The state of a cached row travels with the row.
+ */
+#ifndef BAGPIPE_H_
+#define BAGPIPE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum bp_status {
+    BP_OK = 0,
+    BP_ERR_INVALID_ARG = -1,         /* NULL pointer, negative size, unsupported dim/dtype/optimizer */
+    BP_ERR_CAPACITY = -2,            /* one batch's unique rows exceed the cache capacity */
+    BP_ERR_WORKSPACE_TOO_SMALL = -3, /* workspace or list capacity below what the query function reports */
+    BP_ERR_ID_OUT_OF_RANGE = -4,     /* an id outside [0, total_rows) */
+    BP_ERR_HIP = -5,                 /* a HIP runtime call failed */
+    BP_ERR_UNSUPPORTED = -6          /* size beyond a documented limit */
+} bp_status;
+
+enum { BP_F32 = 0, BP_BF16 = 1 };
+enum { BP_SGD = 0, BP_ADAGRAD = 1, BP_ADAGRAD_ROWWISE = 2 };
+
+/* Problem description, passed by pointer to every call (host memory, read during the call only). */
+typedef struct bp_config {
+    int64_t total_rows;   /* R: rows of the backing table; ids are global row numbers in [0, R) */
+    int64_t capacity;     /* C: cache slots, 1 <= C < 2^31 (the paper's mandatory "max cache size", Section 4) */
+    int32_t dim;          /* D */
+    int32_t weight_dtype; /* BP_F32 | BP_BF16 */
+    int32_t optimizer;    /* BP_SGD | BP_ADAGRAD | BP_ADAGRAD_ROWWISE */
+    int32_t lookahead;    /* requested lookahead value: window of this many batches including the current
+                             one (Algorithm 1's LookAheadValue), >= 1 */
+    float lr;             /* learning rate */
+    float eps;            /* Adagrad epsilon */
+} bp_config;
+
+/* ------------------------------------------------------------------------------------------------
+ * (1) Planner.  Algorithm 1 over a whole trace of T batches, plus the two choices the paper leaves
+ * open: the effective lookahead L_eff is the largest L' <= lookahead whose peak cache occupancy is
+ * <= capacity (Section 4, "Automatically Calculating Lookahead"), and cache slots come from a FIFO
+ * ring of free slots (initially 0..C-1; misses of a batch pop in ascending id order, evictions push
+ * in ascending id order after all pops of that batch).
+ *
+ * For batch i (0-based) with sorted distinct ids U_i the plan holds
+ *   keep list      (id, ttl) for every id of U_i; ttl = last batch in [i, i+L_eff-1] that uses the id
+ *   prefetch list  (id, slot) for the ids of U_i not resident before batch i
+ *   evict list     (id, slot) for the ids of U_i with ttl == i, to be written back after batch i
+ *   lookup_slots   cache slot of every lookup of the trace, in lookup order
+ * all lists ascending in id inside a batch, concatenated over batches (CSR offsets on the host).
+ * ------------------------------------------------------------------------------------------------ */
+typedef struct bp_plan {
+    /* device outputs, caller-allocated */
+    int32_t* lookup_slots;    /* [n_lookups] */
+    int64_t* prefetch_ids;    /* [list_capacity] */
+    int32_t* prefetch_slots;  /* [list_capacity] */
+    int64_t* evict_ids;       /* [list_capacity] */
+    int32_t* evict_slots;     /* [list_capacity] */
+    int64_t* keep_ids;        /* [list_capacity] */
+    int32_t* keep_ttl;        /* [list_capacity] */
+    int64_t list_capacity;    /* entries each list can hold; n_lookups is always enough, sum_i |U_i| is needed */
+    /* host outputs, caller-allocated */
+    int64_t* prefetch_offsets; /* [T+1] */
+    int64_t* evict_offsets;    /* [T+1] */
+    int64_t* keep_offsets;     /* [T+1] */
+    int64_t* occupancy;        /* [T] rows resident while batch i trains */
+    /* scalar results */
+    int32_t L_eff;
+    int64_t peak_occupancy;
+    int64_t min_capacity;      /* max_i |U_i|: the smallest capacity for which a plan exists */
+    int64_t n_unique_pairs;    /* sum_i |U_i| */
+} bp_plan;
+
+/* Bytes of device workspace bp_oracle_plan needs for a trace of n_lookups lookups in n_iters batches. */
+int bp_oracle_plan_workspace_bytes(const bp_config* cfg, int64_t n_lookups, int32_t n_iters, size_t* bytes);
+
+/*
+ * ids          device, [n_lookups] global row ids in lookup order, batches concatenated
+ * iter_offsets host, [n_iters+1], non-decreasing, iter_offsets[0] == 0, last == n_lookups
+ * plan         host struct; its pointers as documented above; scalars are written on return
+ * workspace    device, at least bp_oracle_plan_workspace_bytes() bytes, 256-byte aligned
+ * Limits: n_lookups < 2^31, 1 <= n_iters <= 8192.
+ * Errors: BP_ERR_ID_OUT_OF_RANGE; BP_ERR_CAPACITY (plan->min_capacity is set); BP_ERR_WORKSPACE_TOO_SMALL
+ * (also when list_capacity < n_unique_pairs; plan->n_unique_pairs is set).  On error the device outputs
+ * are unspecified.  Synchronises `stream`.
+ */
+int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offsets, int32_t n_iters,
+                   bp_plan* plan, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * (2) Cache maintenance between two batches: first every evicted row (weights and optimizer state) is
+ * copied from its cache slot back to the backing table, then every prefetched row is copied from the
+ * backing table into its slot — in that order, so a slot freed by an eviction may be refilled in the
+ * same call, and a row is only fetched after its last update was written back (Section 3.2,
+ * "Consistency with the Lookahead algorithm").
+ *
+ * cache_w / cache_state     device (HBM), [capacity] rows
+ * backing_w / backing_state device-visible backing table [total_rows] rows (pinned host memory, or HBM)
+ * evict_* / prefetch_*      device, list slices of one batch from bp_plan; n_* may be 0 (pointers then unused)
+ * Entries with id or slot out of range are skipped.  Asynchronous on `stream`.
+ * ------------------------------------------------------------------------------------------------ */
+int bp_cache_apply(const bp_config* cfg, void* cache_w, void* cache_state, void* backing_w, void* backing_state,
+                   const int64_t* evict_ids, const int32_t* evict_slots, int64_t n_evict,
+                   const int64_t* prefetch_ids, const int32_t* prefetch_slots, int64_t n_prefetch, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * (3) Forward: out[b, :] = sum over lookups k in [bag_offsets[b], bag_offsets[b+1]) of cache_w[slot[k], :],
+ * accumulated in fp32 in lookup order; an empty bag gives a zero row.
+ *
+ * lookup_slots device, [n_lookups] slots of this batch's lookups (a slice of bp_plan.lookup_slots)
+ * bag_offsets  device, [bags+1] int64 starting at 0 and ending at n_lookups; NULL means one lookup per bag
+ *              (n_lookups == bags)
+ * out          device, fp32 [bags][dim]
+ * Slots outside [0, capacity) contribute nothing.  Asynchronous on `stream`.
+ * ------------------------------------------------------------------------------------------------ */
+int bp_embbag_fwd(const bp_config* cfg, const void* cache_w, const int32_t* lookup_slots,
+                  const int64_t* bag_offsets, int64_t n_lookups, int64_t bags, float* out, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * (4) Backward + update, deterministic (bit-identical from run to run): lookups are grouped by slot with
+ * a stable radix sort, G[slot, :] = sum of grad_out[bag(k), :] over the slot's lookups is formed in a
+ * fixed order in fp32, and each distinct slot is updated once, in place:
+ *   BP_SGD              w -= lr * G
+ *   BP_ADAGRAD          s += G*G;              w -= lr * G / (sqrt(s) + eps)
+ *   BP_ADAGRAD_ROWWISE  s_row += mean_d G_d^2; w -= lr * G / (sqrt(s_row) + eps)
+ * (gradients of duplicate lookups are added before squaring; any optimizer of this form works because
+ * gradients, not embeddings, are combined — Section 6.)
+ *
+ * grad_out   device, fp32 [bags][dim]
+ * workspace  device, at least bp_embbag_bwd_update_workspace_bytes() bytes, 256-byte aligned
+ * Limits: n_lookups < 2^31, bags < 2^31.  Slots outside [0, capacity) are ignored.  Asynchronous.
+ * ------------------------------------------------------------------------------------------------ */
+int bp_embbag_bwd_update_workspace_bytes(const bp_config* cfg, int64_t n_lookups, int64_t bags, size_t* bytes);
+int bp_embbag_bwd_update(const bp_config* cfg, void* cache_w, void* cache_state, const int32_t* lookup_slots,
+                         const int64_t* bag_offsets, int64_t n_lookups, int64_t bags, const float* grad_out,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * Diagnostics.
+ * ------------------------------------------------------------------------------------------------ */
+const char* bp_error_string(int status);
+const char* bp_last_error_message(void);   /* thread-local, valid until the thread's next failing call */
+int bp_version(void);
+
+/*
+ * Per-kernel timing with HIP events recorded on the launch stream around every kernel launch.
+ * bp_profile_enable(1) starts recording (and clears old records); bp_profile_enable(0) stops.
+ * bp_profile_collect() synchronises the recorded events and adds their durations to per-kernel totals;
+ * bp_profile_get() reads the totals of kernel `id` in [0, bp_profile_num_kernels()).
+ * Recording creates HIP events (no device memory).  Not thread-safe.
+ */
+int bp_profile_enable(int on);
+int bp_profile_collect(void);
+int bp_profile_num_kernels(void);
+const char* bp_profile_kernel_name(int id);
+int bp_profile_get(int id, int64_t* launches, double* total_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BAGPIPE_H_ */

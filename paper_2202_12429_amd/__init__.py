@@ -1,0 +1,16 @@
+"""MI355X-native embedding-access hot path of lookahead-cached recommendation-model training
+(Bagpipe, arXiv 2202.12429): thin ctypes binding over libbagpipe_hip.so.
+
+The functions carry the names of the C ABI (include/bagpipe.h) and only marshal arguments: every step of
+the path runs in the HIP kernels.  torch is used for device memory and streams, nothing else.  There is no
+CPU fallback: importing works without the library (so that tools can inspect the package), but any call
+raises if libbagpipe_hip.so has not been built (python -m paper_2202_12429_amd.build).
+"""
+from .binding import (  # noqa: F401
+    BF16, F32, SGD, ADAGRAD, ADAGRAD_ROWWISE,
+    BagpipeError, Plan, bp_config, library_path, load_library, make_config,
+    bp_oracle_plan, bp_oracle_plan_workspace_bytes, bp_cache_apply, bp_embbag_fwd,
+    bp_embbag_bwd_update, bp_embbag_bwd_update_workspace_bytes,
+    bp_error_string, bp_last_error_message, bp_version,
+    bp_profile_enable, bp_profile_collect, bp_profile_get, profile_totals,
+)

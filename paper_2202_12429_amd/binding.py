@@ -1,0 +1,268 @@
+"""ctypes marshalling for libbagpipe_hip.so.  One Python function per C entry point, same name."""
+from __future__ import annotations
+
+import ctypes
+import dataclasses
+import os
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libbagpipe_hip.so")
+
+F32, BF16 = 0, 1
+SGD, ADAGRAD, ADAGRAD_ROWWISE = 0, 1, 2
+_DTYPES = {"f32": F32, "bf16": BF16}
+_OPTIMIZERS = {"sgd": SGD, "adagrad": ADAGRAD, "adagrad_rowwise": ADAGRAD_ROWWISE}
+
+
+class BagpipeError(RuntimeError):
+    def __init__(self, status: int, message: str, **info):
+        super().__init__(f"bagpipe status {status}: {message}")
+        self.status = status
+        self.info = info
+
+
+class bp_config(ctypes.Structure):
+    _fields_ = [("total_rows", ctypes.c_int64), ("capacity", ctypes.c_int64), ("dim", ctypes.c_int32),
+                ("weight_dtype", ctypes.c_int32), ("optimizer", ctypes.c_int32), ("lookahead", ctypes.c_int32),
+                ("lr", ctypes.c_float), ("eps", ctypes.c_float)]
+
+
+class _bp_plan(ctypes.Structure):
+    _fields_ = [("lookup_slots", ctypes.c_void_p), ("prefetch_ids", ctypes.c_void_p),
+                ("prefetch_slots", ctypes.c_void_p), ("evict_ids", ctypes.c_void_p), ("evict_slots", ctypes.c_void_p),
+                ("keep_ids", ctypes.c_void_p), ("keep_ttl", ctypes.c_void_p), ("list_capacity", ctypes.c_int64),
+                ("prefetch_offsets", ctypes.c_void_p), ("evict_offsets", ctypes.c_void_p),
+                ("keep_offsets", ctypes.c_void_p), ("occupancy", ctypes.c_void_p), ("L_eff", ctypes.c_int32),
+                ("peak_occupancy", ctypes.c_int64), ("min_capacity", ctypes.c_int64),
+                ("n_unique_pairs", ctypes.c_int64)]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads libbagpipe_hip.so.  torch is imported first so that the HIP runtime it ships is the one the
+    library binds to (one runtime per process)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise BagpipeError(-5, f"{_LIB_PATH} is missing: build it with `python -m paper_2202_12429_amd.build` "
+                               "(there is no CPU fallback)")
+    import torch  # noqa: F401
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
+    cfgp = ctypes.POINTER(bp_config)
+    lib.bp_oracle_plan_workspace_bytes.argtypes = [cfgp, i64, i32, ctypes.POINTER(sz)]
+    lib.bp_oracle_plan.argtypes = [cfgp, vp, vp, i32, ctypes.POINTER(_bp_plan), vp, sz, vp]
+    lib.bp_cache_apply.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, i64, vp, vp, i64, vp]
+    lib.bp_embbag_fwd.argtypes = [cfgp, vp, vp, vp, i64, i64, vp, vp]
+    lib.bp_embbag_bwd_update_workspace_bytes.argtypes = [cfgp, i64, i64, ctypes.POINTER(sz)]
+    lib.bp_embbag_bwd_update.argtypes = [cfgp, vp, vp, vp, vp, i64, i64, vp, vp, sz, vp]
+    lib.bp_error_string.argtypes = [ctypes.c_int]
+    lib.bp_error_string.restype = ctypes.c_char_p
+    lib.bp_last_error_message.restype = ctypes.c_char_p
+    lib.bp_profile_kernel_name.argtypes = [ctypes.c_int]
+    lib.bp_profile_kernel_name.restype = ctypes.c_char_p
+    lib.bp_profile_get.argtypes = [ctypes.c_int, ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)]
+    for name in ("bp_oracle_plan_workspace_bytes", "bp_oracle_plan", "bp_cache_apply", "bp_embbag_fwd",
+                 "bp_embbag_bwd_update_workspace_bytes", "bp_embbag_bwd_update", "bp_version", "bp_profile_enable",
+                 "bp_profile_collect", "bp_profile_num_kernels", "bp_profile_get"):
+        getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def _check(status: int, **info):
+    if status != 0:
+        lib = load_library()
+        msg = lib.bp_last_error_message().decode() or lib.bp_error_string(status).decode()
+        raise BagpipeError(status, msg, **info)
+
+
+def make_config(total_rows: int, capacity: int, dim: int, weight_dtype="f32", optimizer="sgd", lookahead: int = 1,
+                lr: float = 0.01, eps: float = 1e-8) -> bp_config:
+    wd = _DTYPES[weight_dtype] if isinstance(weight_dtype, str) else int(weight_dtype)
+    op = _OPTIMIZERS[optimizer] if isinstance(optimizer, str) else int(optimizer)
+    return bp_config(int(total_rows), int(capacity), int(dim), wd, op, int(lookahead), float(lr), float(eps))
+
+
+def _ptr(t) -> Optional[int]:
+    """Device (or pinned-host) address of a torch tensor, a raw integer address, or None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    assert t.is_contiguous(), "tensors passed to the library must be contiguous"
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def bp_error_string(status: int) -> str:
+    return load_library().bp_error_string(status).decode()
+
+
+def bp_last_error_message() -> str:
+    return load_library().bp_last_error_message().decode()
+
+
+def bp_version() -> int:
+    return load_library().bp_version()
+
+
+# ---------------------------------------------------------------------------------------------------
+# (1) planner
+# ---------------------------------------------------------------------------------------------------
+@dataclasses.dataclass
+class Plan:
+    """Result of bp_oracle_plan: device tensors for the lists and the slot map, host arrays for the CSR
+    offsets and the occupancy curve."""
+    L_eff: int
+    peak_occupancy: int
+    min_capacity: int
+    n_unique_pairs: int
+    lookup_slots: "object"       # int32 [N] device
+    prefetch_ids: "object"       # int64 device
+    prefetch_slots: "object"     # int32 device
+    evict_ids: "object"
+    evict_slots: "object"
+    keep_ids: "object"
+    keep_ttl: "object"
+    prefetch_offsets: np.ndarray  # int64 [T+1] host
+    evict_offsets: np.ndarray
+    keep_offsets: np.ndarray
+    occupancy: np.ndarray         # int64 [T] host
+
+
+def bp_oracle_plan_workspace_bytes(cfg: bp_config, n_lookups: int, n_iters: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load_library().bp_oracle_plan_workspace_bytes(ctypes.byref(cfg), int(n_lookups), int(n_iters),
+                                                         ctypes.byref(out)))
+    return int(out.value)
+
+
+def bp_oracle_plan(cfg: bp_config, ids, iter_offsets, list_capacity: Optional[int] = None, workspace=None,
+                   stream=None) -> Plan:
+    """ids: int64 device tensor [N]; iter_offsets: int64 host array [T+1].  Output and workspace tensors are
+    allocated here with torch (the library itself allocates nothing); list tensors are trimmed views."""
+    import torch
+    lib = load_library()
+    iter_offsets = np.ascontiguousarray(iter_offsets, dtype=np.int64)
+    T = iter_offsets.shape[0] - 1
+    N = int(iter_offsets[-1])
+    assert ids.dtype == torch.int64 and ids.numel() == N
+    dev = ids.device
+    cap = N if list_capacity is None else int(list_capacity)
+    if workspace is None:
+        workspace = torch.empty(bp_oracle_plan_workspace_bytes(cfg, N, T), dtype=torch.uint8, device=dev)
+    i32 = dict(dtype=torch.int32, device=dev)
+    i64 = dict(dtype=torch.int64, device=dev)
+    t = dict(lookup_slots=torch.empty(max(N, 1), **i32),
+             prefetch_ids=torch.empty(max(cap, 1), **i64), prefetch_slots=torch.empty(max(cap, 1), **i32),
+             evict_ids=torch.empty(max(cap, 1), **i64), evict_slots=torch.empty(max(cap, 1), **i32),
+             keep_ids=torch.empty(max(cap, 1), **i64), keep_ttl=torch.empty(max(cap, 1), **i32))
+    h = dict(prefetch_offsets=np.zeros(T + 1, np.int64), evict_offsets=np.zeros(T + 1, np.int64),
+             keep_offsets=np.zeros(T + 1, np.int64), occupancy=np.zeros(max(T, 1), np.int64))
+    p = _bp_plan()
+    for k, v in t.items():
+        setattr(p, k, v.data_ptr())
+    for k, v in h.items():
+        setattr(p, k, v.ctypes.data)
+    p.list_capacity = cap
+    st = lib.bp_oracle_plan(ctypes.byref(cfg), _ptr(ids), iter_offsets.ctypes.data, T, ctypes.byref(p),
+                            _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(st, min_capacity=int(p.min_capacity), n_unique_pairs=int(p.n_unique_pairs))
+    n_pf, n_k = int(h["prefetch_offsets"][-1]), int(h["keep_offsets"][-1])
+    return Plan(L_eff=int(p.L_eff), peak_occupancy=int(p.peak_occupancy), min_capacity=int(p.min_capacity),
+                n_unique_pairs=int(p.n_unique_pairs), lookup_slots=t["lookup_slots"][:N],
+                prefetch_ids=t["prefetch_ids"][:n_pf], prefetch_slots=t["prefetch_slots"][:n_pf],
+                evict_ids=t["evict_ids"][:n_pf], evict_slots=t["evict_slots"][:n_pf],
+                keep_ids=t["keep_ids"][:n_k], keep_ttl=t["keep_ttl"][:n_k],
+                prefetch_offsets=h["prefetch_offsets"], evict_offsets=h["evict_offsets"],
+                keep_offsets=h["keep_offsets"], occupancy=h["occupancy"][:T])
+
+
+# ---------------------------------------------------------------------------------------------------
+# (2) cache maintenance
+# ---------------------------------------------------------------------------------------------------
+def bp_cache_apply(cfg: bp_config, cache_w, cache_state, backing_w, backing_state, evict_ids, evict_slots,
+                   prefetch_ids, prefetch_slots, stream=None) -> None:
+    """Lists are device tensors (slices of a Plan); a None or empty list means nothing to do.  backing_* may be
+    pinned host tensors (device-visible) or device tensors."""
+    n_e = 0 if evict_ids is None else int(evict_ids.numel())
+    n_p = 0 if prefetch_ids is None else int(prefetch_ids.numel())
+    _check(load_library().bp_cache_apply(
+        ctypes.byref(cfg), _ptr(cache_w), _ptr(cache_state), _ptr(backing_w), _ptr(backing_state),
+        _ptr(evict_ids) if n_e else None, _ptr(evict_slots) if n_e else None, n_e,
+        _ptr(prefetch_ids) if n_p else None, _ptr(prefetch_slots) if n_p else None, n_p, _stream(stream)))
+
+
+# ---------------------------------------------------------------------------------------------------
+# (3) forward
+# ---------------------------------------------------------------------------------------------------
+def bp_embbag_fwd(cfg: bp_config, cache_w, lookup_slots, bag_offsets, bags: int, out, stream=None) -> None:
+    """bag_offsets None = one lookup per bag.  out: fp32 device tensor [bags, dim], written in place."""
+    n = int(lookup_slots.numel())
+    _check(load_library().bp_embbag_fwd(ctypes.byref(cfg), _ptr(cache_w), _ptr(lookup_slots), _ptr(bag_offsets), n,
+                                        int(bags), _ptr(out), _stream(stream)))
+
+
+# ---------------------------------------------------------------------------------------------------
+# (4) backward + update
+# ---------------------------------------------------------------------------------------------------
+def bp_embbag_bwd_update_workspace_bytes(cfg: bp_config, n_lookups: int, bags: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load_library().bp_embbag_bwd_update_workspace_bytes(ctypes.byref(cfg), int(n_lookups), int(bags),
+                                                               ctypes.byref(out)))
+    return int(out.value)
+
+
+def bp_embbag_bwd_update(cfg: bp_config, cache_w, cache_state, lookup_slots, bag_offsets, bags: int, grad_out,
+                         workspace, stream=None) -> None:
+    n = int(lookup_slots.numel())
+    _check(load_library().bp_embbag_bwd_update(ctypes.byref(cfg), _ptr(cache_w), _ptr(cache_state),
+                                               _ptr(lookup_slots), _ptr(bag_offsets), n, int(bags), _ptr(grad_out),
+                                               _ptr(workspace), int(workspace.numel()), _stream(stream)))
+
+
+# ---------------------------------------------------------------------------------------------------
+# profiling
+# ---------------------------------------------------------------------------------------------------
+def bp_profile_enable(on: bool) -> None:
+    _check(load_library().bp_profile_enable(int(bool(on))))
+
+
+def bp_profile_collect() -> None:
+    _check(load_library().bp_profile_collect())
+
+
+def bp_profile_get(kernel_id: int):
+    n, ms = ctypes.c_int64(0), ctypes.c_double(0.0)
+    _check(load_library().bp_profile_get(int(kernel_id), ctypes.byref(n), ctypes.byref(ms)))
+    return int(n.value), float(ms.value)
+
+
+def profile_totals() -> dict:
+    """{kernel name: (launches, total_ms)} for every kernel with at least one recorded launch."""
+    lib = load_library()
+    out = {}
+    for k in range(lib.bp_profile_num_kernels()):
+        n, ms = bp_profile_get(k)
+        if n:
+            out[lib.bp_profile_kernel_name(k).decode()] = (n, ms)
+    return out

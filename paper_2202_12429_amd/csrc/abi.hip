@@ -1,0 +1,148 @@
+// Status text, argument checks shared by all entry points, and the event-based kernel profiler.
+#include <cstring>
+#include <vector>
+
+#include "common.h"
+
+namespace bp {
+
+static thread_local char t_error[512] = "";
+
+void set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(t_error, sizeof(t_error), fmt, ap);
+    va_end(ap);
+}
+
+int fail(int status, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(t_error, sizeof(t_error), fmt, ap);
+    va_end(ap);
+    return status;
+}
+
+int check_config(const bp_config* cfg) {
+    if (!cfg) return fail(BP_ERR_INVALID_ARG, "cfg is NULL");
+    if (cfg->total_rows < 1) return fail(BP_ERR_INVALID_ARG, "total_rows %lld < 1", (long long)cfg->total_rows);
+    if (cfg->capacity < 1 || cfg->capacity >= (int64_t(1) << 31) - 1)
+        return fail(BP_ERR_INVALID_ARG, "capacity %lld outside [1, 2^31 - 1)", (long long)cfg->capacity);
+    if (cfg->weight_dtype != BP_F32 && cfg->weight_dtype != BP_BF16)
+        return fail(BP_ERR_INVALID_ARG, "unknown weight_dtype %d", cfg->weight_dtype);
+    if (cfg->optimizer != BP_SGD && cfg->optimizer != BP_ADAGRAD && cfg->optimizer != BP_ADAGRAD_ROWWISE)
+        return fail(BP_ERR_INVALID_ARG, "unknown optimizer %d", cfg->optimizer);
+    if (cfg->lookahead < 1) return fail(BP_ERR_INVALID_ARG, "lookahead %d < 1", cfg->lookahead);
+    if (cfg->dim < 1) return fail(BP_ERR_INVALID_ARG, "dim %d < 1", cfg->dim);
+    const size_t rb = row_bytes(cfg);
+    if (rb % 16 != 0) return fail(BP_ERR_INVALID_ARG, "row of %zu bytes is not a multiple of 16 bytes", rb);
+    if (rb > 1024) return fail(BP_ERR_UNSUPPORTED, "row of %zu bytes exceeds 1024 bytes", rb);
+    return BP_OK;
+}
+
+// ---- profiler --------------------------------------------------------------------------------
+bool g_profile_on = false;
+
+namespace {
+struct Span {
+    int id;
+    hipEvent_t a, b;
+};
+std::vector<Span> g_spans;          // recorded, not yet collected
+std::vector<hipEvent_t> g_free;     // recycled events
+int64_t g_count[K_NUM_KERNELS];
+double g_ms[K_NUM_KERNELS];
+hipEvent_t g_open = nullptr;
+
+hipEvent_t get_event() {
+    if (!g_free.empty()) {
+        hipEvent_t e = g_free.back();
+        g_free.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+const char* const kKernelNames[K_NUM_KERNELS] = {
+    "sort_upsweep", "sort_scan", "sort_downsweep", "scan_reduce", "scan_spine", "scan_apply",
+    "plan_keys", "plan_pairs", "plan_hist", "plan_occupancy", "plan_flags", "plan_lists", "plan_ring_jump",
+    "plan_slots", "cache_evict", "cache_prefetch", "embbag_fwd", "bwd_keys", "bwd_items", "bwd_reduce_update",
+    "bwd_combine_update", "fill"};
+}  // namespace
+
+void profile_begin(int /*id*/, hipStream_t s) {
+    g_open = get_event();
+    if (g_open) (void)hipEventRecord(g_open, s);
+}
+
+void profile_end(int id, hipStream_t s) {
+    hipEvent_t b = get_event();
+    if (!g_open || !b) return;
+    (void)hipEventRecord(b, s);
+    g_spans.push_back(Span{id, g_open, b});
+    g_open = nullptr;
+}
+
+}  // namespace bp
+
+using namespace bp;
+
+BP_EXPORT const char* bp_error_string(int status) {
+    switch (status) {
+        case BP_OK: return "ok";
+        case BP_ERR_INVALID_ARG: return "invalid argument";
+        case BP_ERR_CAPACITY: return "cache capacity below one batch's unique rows";
+        case BP_ERR_WORKSPACE_TOO_SMALL: return "workspace or list capacity too small";
+        case BP_ERR_ID_OUT_OF_RANGE: return "id out of range";
+        case BP_ERR_HIP: return "HIP runtime error";
+        case BP_ERR_UNSUPPORTED: return "size beyond a documented limit";
+        default: return "unknown status";
+    }
+}
+
+BP_EXPORT const char* bp_last_error_message(void) { return t_error; }
+
+BP_EXPORT int bp_version(void) { return 100; }
+
+BP_EXPORT int bp_profile_enable(int on) {
+    if (on) {
+        for (auto& s : g_spans) {
+            g_free.push_back(s.a);
+            g_free.push_back(s.b);
+        }
+        g_spans.clear();
+        std::memset(g_count, 0, sizeof(g_count));
+        std::memset(g_ms, 0, sizeof(g_ms));
+    }
+    g_profile_on = on != 0;
+    return BP_OK;
+}
+
+BP_EXPORT int bp_profile_collect(void) {
+    for (auto& s : g_spans) {
+        BP_HIP(hipEventSynchronize(s.b));
+        float ms = 0.f;
+        BP_HIP(hipEventElapsedTime(&ms, s.a, s.b));
+        g_count[s.id] += 1;
+        g_ms[s.id] += ms;
+        g_free.push_back(s.a);
+        g_free.push_back(s.b);
+    }
+    g_spans.clear();
+    return BP_OK;
+}
+
+BP_EXPORT int bp_profile_num_kernels(void) { return K_NUM_KERNELS; }
+
+BP_EXPORT const char* bp_profile_kernel_name(int id) {
+    return id >= 0 && id < K_NUM_KERNELS ? kKernelNames[id] : "";
+}
+
+BP_EXPORT int bp_profile_get(int id, int64_t* launches, double* total_ms) {
+    if (id < 0 || id >= K_NUM_KERNELS) return fail(BP_ERR_INVALID_ARG, "kernel id %d out of range", id);
+    if (launches) *launches = g_count[id];
+    if (total_ms) *total_ms = g_ms[id];
+    return BP_OK;
+}

@@ -1,0 +1,97 @@
+// bp_cache_apply: trainer-side cache maintenance (Section 3.4 "Trainer"; ordering rule of Section 3.2,
+// "Consistency with the Lookahead algorithm").  Two row-copy launches on one stream: write-backs of the
+// evict list first, then loads of the prefetch list.  The backing table is addressed through a
+// device-visible pointer, so when it lives in pinned host memory the copies run as zero-copy PCIe
+// reads / writes issued straight from the wavefronts, 16 bytes per lane, one row per lane group.
+#include "common.h"
+#include "row_access.h"
+
+namespace bp {
+namespace {
+
+// TO_BACKING: backing[id] <- cache[slot]; otherwise cache[slot] <- backing[id].
+template <int GW, bool TO_BACKING>
+__global__ __launch_bounds__(kRowBlock) void cache_copy_rows_kernel(uint4* __restrict__ cache_w, uint4* __restrict__ back_w,
+                                                                    uint4* __restrict__ cache_s, uint4* __restrict__ back_s,
+                                                                    const int64_t* __restrict__ ids,
+                                                                    const int32_t* __restrict__ slots, int64_t n, int64_t R,
+                                                                    int64_t C, int lpr, int slpr, int rowwise) {
+    const int64_t e = ((int64_t)blockIdx.x * kRowBlock + threadIdx.x) / GW;
+    const int c = threadIdx.x % GW;
+    if (e >= n) return;
+    const int64_t g = ids[e];
+    const int64_t s = slots[e];
+    if (g < 0 || g >= R || s < 0 || s >= C) return;
+    if (c < lpr) {
+        if (TO_BACKING) back_w[g * lpr + c] = cache_w[s * lpr + c];
+        else cache_w[s * lpr + c] = back_w[g * lpr + c];
+    }
+    for (int k = c; k < slpr; k += GW) {          // element-wise state: its own row of slpr pieces
+        if (TO_BACKING) back_s[g * slpr + k] = cache_s[s * slpr + k];
+        else cache_s[s * slpr + k] = back_s[g * slpr + k];
+    }
+    if (rowwise && c == 0) {                      // row-wise state: one fp32 per row
+        float* cs = reinterpret_cast<float*>(cache_s);
+        float* bs = reinterpret_cast<float*>(back_s);
+        if (TO_BACKING) bs[g] = cs[s]; else cs[s] = bs[g];
+    }
+}
+
+struct CopyLaunch {
+    const bp_config* cfg;
+    void *cache_w, *cache_s, *back_w, *back_s;
+    const int64_t* ids;
+    const int32_t* slots;
+    int64_t n;
+    bool to_backing;
+    hipStream_t stream;
+    template <int GW, bool BF16>
+    int run() {
+        const int lpr = (int)(row_bytes(cfg) / 16);
+        const int slpr = cfg->optimizer == BP_ADAGRAD ? cfg->dim / 4 : 0;
+        const int rowwise = cfg->optimizer == BP_ADAGRAD_ROWWISE;
+        const dim3 grid((unsigned)ceil_div(n * GW, kRowBlock));
+        if (to_backing)
+            BP_LAUNCH(K_CACHE_EVICT, (cache_copy_rows_kernel<GW, true>), grid, dim3(kRowBlock), 0, stream, (uint4*)cache_w,
+                      (uint4*)back_w, (uint4*)cache_s, (uint4*)back_s, ids, slots, n, cfg->total_rows, cfg->capacity, lpr,
+                      slpr, rowwise);
+        else
+            BP_LAUNCH(K_CACHE_PREFETCH, (cache_copy_rows_kernel<GW, false>), grid, dim3(kRowBlock), 0, stream,
+                      (uint4*)cache_w, (uint4*)back_w, (uint4*)cache_s, (uint4*)back_s, ids, slots, n, cfg->total_rows,
+                      cfg->capacity, lpr, slpr, rowwise);
+        return BP_OK;
+    }
+};
+
+}  // namespace
+}  // namespace bp
+
+using namespace bp;
+
+BP_EXPORT int bp_cache_apply(const bp_config* cfg, void* cache_w, void* cache_state, void* backing_w, void* backing_state,
+                              const int64_t* evict_ids, const int32_t* evict_slots, int64_t n_evict,
+                              const int64_t* prefetch_ids, const int32_t* prefetch_slots, int64_t n_prefetch,
+                              void* stream) {
+    BP_TRY(check_config(cfg));
+    if (n_evict < 0 || n_prefetch < 0) return fail(BP_ERR_INVALID_ARG, "negative list length");
+    if (n_evict + n_prefetch == 0) return BP_OK;
+    if (!cache_w || !backing_w) return fail(BP_ERR_INVALID_ARG, "cache_w or backing_w is NULL");
+    if (cfg->optimizer != BP_SGD && (!cache_state || !backing_state))
+        return fail(BP_ERR_INVALID_ARG, "optimizer state pointers are NULL");
+    if (((uintptr_t)cache_w | (uintptr_t)backing_w | (uintptr_t)cache_state | (uintptr_t)backing_state) & 15)
+        return fail(BP_ERR_INVALID_ARG, "row pointers must be 16-byte aligned");
+    if ((n_evict && (!evict_ids || !evict_slots)) || (n_prefetch && (!prefetch_ids || !prefetch_slots)))
+        return fail(BP_ERR_INVALID_ARG, "a list pointer is NULL");
+    const int lpr = (int)(row_bytes(cfg) / 16);
+    if (n_evict) {
+        CopyLaunch l{cfg, cache_w, cache_state, backing_w, backing_state, evict_ids, evict_slots, n_evict, true,
+                     (hipStream_t)stream};
+        BP_TRY(dispatch_row(lpr, false, l));
+    }
+    if (n_prefetch) {
+        CopyLaunch l{cfg, cache_w, cache_state, backing_w, backing_state, prefetch_ids, prefetch_slots, n_prefetch, false,
+                     (hipStream_t)stream};
+        BP_TRY(dispatch_row(lpr, false, l));
+    }
+    return BP_OK;
+}

@@ -1,0 +1,116 @@
+// Shared host-side plumbing of the library: status/error text, launch + profiling helpers,
+// workspace carving.  No device code here.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstddef>
+#include <cstdint>
+#include <cstdio>
+
+#include "../../include/bagpipe.h"
+
+// Entry points of the C ABI: the only symbols the shared library exports (built with -fvisibility=hidden).
+#define BP_EXPORT extern "C" __attribute__((visibility("default")))
+
+namespace bp {
+
+constexpr int kWave = 64;   // gfx950 wavefront
+
+// ---- error reporting ---------------------------------------------------------------------------
+void set_error(const char* fmt, ...) __attribute__((format(printf, 1, 2)));
+int fail(int status, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+
+#define BP_HIP(expr)                                                                              \
+    do {                                                                                          \
+        hipError_t e_ = (expr);                                                                   \
+        if (e_ != hipSuccess)                                                                     \
+            return ::bp::fail(BP_ERR_HIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), \
+                              __FILE__, __LINE__);                                                \
+    } while (0)
+
+#define BP_TRY(expr)              \
+    do {                          \
+        int s_ = (expr);          \
+        if (s_ != BP_OK) return s_; \
+    } while (0)
+
+int check_config(const bp_config* cfg);
+
+inline size_t elem_bytes(int dtype) { return dtype == BP_F32 ? 4 : 2; }
+inline size_t row_bytes(const bp_config* c) { return (size_t)c->dim * elem_bytes(c->weight_dtype); }
+inline size_t state_row_bytes(const bp_config* c) {
+    return c->optimizer == BP_ADAGRAD ? (size_t)c->dim * 4 : c->optimizer == BP_ADAGRAD_ROWWISE ? 4 : 0;
+}
+
+// ---- workspace carving -------------------------------------------------------------------------
+// Hands out 256-byte aligned pieces of one caller-owned buffer; with base == nullptr it only counts.
+class Carver {
+  public:
+    Carver(void* base, size_t bytes) : base_((char*)base), cap_(bytes) {}
+    template <typename T>
+    T* take(size_t count) {
+        size_t off = (used_ + 255) & ~size_t(255);
+        used_ = off + count * sizeof(T);
+        return base_ ? (T*)(base_ + off) : nullptr;
+    }
+    size_t used() const { return (used_ + 255) & ~size_t(255); }
+    bool fits() const { return used() <= cap_; }
+
+  private:
+    char* base_;
+    size_t cap_;
+    size_t used_ = 0;
+};
+
+// ---- kernel ids for profiling ------------------------------------------------------------------
+enum KernelId {
+    K_SORT_UPSWEEP = 0,
+    K_SORT_SCAN,
+    K_SORT_DOWNSWEEP,
+    K_SCAN_REDUCE,
+    K_SCAN_SPINE,
+    K_SCAN_APPLY,
+    K_PLAN_KEYS,
+    K_PLAN_PAIRS,
+    K_PLAN_HIST,
+    K_PLAN_OCC,
+    K_PLAN_FLAGS,
+    K_PLAN_LISTS,
+    K_PLAN_JUMP,
+    K_PLAN_SLOTS,
+    K_CACHE_EVICT,
+    K_CACHE_PREFETCH,
+    K_FWD,
+    K_BWD_KEYS,
+    K_BWD_ITEMS,
+    K_BWD_REDUCE_UPDATE,
+    K_BWD_COMBINE_UPDATE,
+    K_FILL,
+    K_NUM_KERNELS
+};
+
+extern bool g_profile_on;
+void profile_begin(int id, hipStream_t s);
+void profile_end(int id, hipStream_t s);
+
+// Launch `kernel` and, when profiling is on, bracket it with events on the same stream.
+#define BP_LAUNCH(id, kernel, grid, block, shmem, stream, ...)                      \
+    do {                                                                             \
+        if (::bp::g_profile_on) ::bp::profile_begin((id), (stream));                \
+        hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__);        \
+        if (::bp::g_profile_on) ::bp::profile_end((id), (stream));                  \
+        hipError_t le_ = hipGetLastError();                                          \
+        if (le_ != hipSuccess)                                                       \
+            return ::bp::fail(BP_ERR_HIP, "launch of %s failed: %s", #kernel, hipGetErrorString(le_)); \
+    } while (0)
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline int bits_for(int64_t n) {   // bits needed to represent values in [0, n)
+    int b = 1;
+    while (b < 63 && (int64_t(1) << b) < n) ++b;
+    return b;
+}
+
+}  // namespace bp

@@ -1,0 +1,315 @@
+// Wavefront- and workgroup-level building blocks for gfx950 (64-wide wavefronts) and the two device-wide
+// primitives the planner and the backward pass share: a tiled scan and a stable LSD radix sort.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "common.h"
+
+namespace bp {
+
+// ---------------------------------------------------------------------------------------------
+// wavefront helpers
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
+
+__device__ __forceinline__ uint64_t lanemask_lt() { return (uint64_t(1) << lane_id()) - 1; }
+
+struct AddOp {
+    template <typename T>
+    __device__ __forceinline__ T operator()(T a, T b) const { return a + b; }
+};
+struct MaxOp {
+    template <typename T>
+    __device__ __forceinline__ T operator()(T a, T b) const { return a > b ? a : b; }
+};
+
+template <typename T, typename Op>
+__device__ __forceinline__ T wave_inclusive_scan(T x, Op op) {
+    const int lane = lane_id();
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        T y = __shfl_up(x, off, kWave);
+        if (lane >= off) x = op(y, x);
+    }
+    return x;
+}
+
+// Scan of one value per thread over a workgroup of BLOCK threads (BLOCK % 64 == 0), thread order.
+// `wave_tot` is LDS scratch of BLOCK/64 entries.  Writes the exclusive and inclusive values and the
+// reduction over the whole workgroup.  Ends with a barrier, so wave_tot can be reused at once.
+template <int BLOCK, typename T, typename Op>
+__device__ __forceinline__ void block_scan(T x, Op op, T identity, T* wave_tot, T* exclusive, T* inclusive,
+                                           T* block_total) {
+    constexpr int WAVES = BLOCK / kWave;
+    const int w = threadIdx.x / kWave, lane = lane_id();
+    T inc = wave_inclusive_scan(x, op);
+    T exc = __shfl_up(inc, 1, kWave);
+    if (lane == 0) exc = identity;
+    if (lane == kWave - 1) wave_tot[w] = inc;
+    __syncthreads();
+    T prefix = identity, total = identity;
+#pragma unroll
+    for (int i = 0; i < WAVES; ++i) {
+        T t = wave_tot[i];
+        if (i < w) prefix = op(prefix, t);
+        total = op(total, t);
+    }
+    __syncthreads();
+    *exclusive = op(prefix, exc);
+    *inclusive = op(prefix, inc);
+    *block_total = total;
+}
+
+// ---------------------------------------------------------------------------------------------
+// device-wide scan:  out(i, exclusive_prefix_i, inclusive_prefix_i)  for value_i = in(i), i in [0, n)
+//   pass 1  per-tile reduction                   -> partials[tile]
+//   pass 2  one workgroup scans the partials in place (exclusive) and appends the grand total
+//   pass 3  per-tile scan seeded with its partial
+// A tile is kScanRounds consecutive rounds of 256 consecutive elements, so loads coalesce.
+// Op must be associative and commutative (add, max).
+// ---------------------------------------------------------------------------------------------
+constexpr int kScanBlock = 256;
+constexpr int kScanRounds = 8;
+constexpr int kScanTile = kScanBlock * kScanRounds;
+
+template <typename T, typename Op, typename In>
+__global__ __launch_bounds__(kScanBlock) void scan_reduce_kernel(In in, int64_t n, T* partials, Op op, T identity) {
+    __shared__ T wave_tot[kScanBlock / kWave];
+    const int64_t base = (int64_t)blockIdx.x * kScanTile;
+    T acc = identity;
+#pragma unroll
+    for (int r = 0; r < kScanRounds; ++r) {
+        int64_t i = base + r * kScanBlock + threadIdx.x;
+        if (i < n) acc = op(acc, in(i));
+    }
+    T exc, inc, total;
+    block_scan<kScanBlock>(acc, op, identity, wave_tot, &exc, &inc, &total);
+    if (threadIdx.x == 0) partials[blockIdx.x] = total;
+}
+
+template <typename T, typename Op>
+__global__ __launch_bounds__(1024) void scan_spine_kernel(T* partials, int64_t nparts, Op op, T identity) {
+    __shared__ T wave_tot[1024 / kWave];
+    T carry = identity;
+    for (int64_t base = 0; base < nparts; base += 1024) {
+        int64_t i = base + threadIdx.x;
+        T v = i < nparts ? partials[i] : identity;
+        T exc, inc, total;
+        block_scan<1024>(v, op, identity, wave_tot, &exc, &inc, &total);
+        if (i < nparts) partials[i] = op(carry, exc);
+        carry = op(carry, total);
+    }
+    if (threadIdx.x == 0) partials[nparts] = carry;
+}
+
+template <typename T, typename Op, typename In, typename Out>
+__global__ __launch_bounds__(kScanBlock) void scan_apply_kernel(In in, Out out, int64_t n, const T* partials, Op op,
+                                                                T identity) {
+    __shared__ T wave_tot[kScanBlock / kWave];
+    const int64_t base = (int64_t)blockIdx.x * kScanTile;
+    T carry = partials[blockIdx.x];
+#pragma unroll 1
+    for (int r = 0; r < kScanRounds; ++r) {
+        int64_t i = base + r * kScanBlock + threadIdx.x;
+        T v = i < n ? in(i) : identity;
+        T exc, inc, total;
+        block_scan<kScanBlock>(v, op, identity, wave_tot, &exc, &inc, &total);
+        if (i < n) out(i, op(carry, exc), op(carry, inc));
+        carry = op(carry, total);
+    }
+}
+
+inline int64_t scan_num_tiles(int64_t n) { return n > 0 ? ceil_div(n, kScanTile) : 1; }
+// partials needed by device_scan: one per tile plus the grand total
+inline size_t scan_partials(int64_t n) { return (size_t)scan_num_tiles(n) + 1; }
+
+// Runs the three passes on `stream`.  partials[scan_num_tiles(n)] holds the grand total afterwards.
+template <typename T, typename Op, typename In, typename Out>
+int device_scan(In in, Out out, int64_t n, T* partials, Op op, T identity, hipStream_t stream) {
+    const int64_t tiles = scan_num_tiles(n);
+    BP_LAUNCH(K_SCAN_REDUCE, (scan_reduce_kernel<T, Op, In>), dim3((unsigned)tiles), dim3(kScanBlock), 0, stream, in,
+              n, partials, op, identity);
+    BP_LAUNCH(K_SCAN_SPINE, (scan_spine_kernel<T, Op>), dim3(1), dim3(1024), 0, stream, partials, tiles, op, identity);
+    BP_LAUNCH(K_SCAN_APPLY, (scan_apply_kernel<T, Op, In, Out>), dim3((unsigned)tiles), dim3(kScanBlock), 0, stream, in,
+              out, n, (const T*)partials, op, identity);
+    return BP_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// stable LSD radix sort of (key, 32-bit value) pairs, 8 bits per pass
+//   upsweep    per-tile digit histogram              -> counts[digit][tile]
+//   scan       exclusive scan of counts (digit-major) -> global base of every (digit, tile)
+//   downsweep  per-tile stable ranking in LDS, coalesced scatter
+// Ranking inside a tile: each wavefront owns a contiguous 64*IPT stretch, lane l holds elements
+// j*64+l; for every j the lanes that share a digit find each other with ballots (one per digit bit),
+// rank = running per-wave digit count + number of lower lanes among the peers.
+// ---------------------------------------------------------------------------------------------
+constexpr int kSortBlock = 256;
+constexpr int kRadixBits = 8;
+constexpr int kRadix = 1 << kRadixBits;
+
+template <typename K, int IPT>
+__global__ __launch_bounds__(kSortBlock) void sort_upsweep_kernel(const K* __restrict__ keys, uint32_t n, int shift,
+                                                                  uint32_t mask, uint32_t* __restrict__ counts,
+                                                                  uint32_t ntiles) {
+    __shared__ uint32_t hist[kRadix];
+    hist[threadIdx.x] = 0;
+    __syncthreads();
+    const uint32_t base = blockIdx.x * (kSortBlock * IPT);
+#pragma unroll
+    for (int j = 0; j < IPT; ++j) {
+        uint32_t i = base + j * kSortBlock + threadIdx.x;
+        if (i < n) atomicAdd(&hist[(uint32_t)(keys[i] >> shift) & mask], 1u);
+    }
+    __syncthreads();
+    counts[(size_t)threadIdx.x * ntiles + blockIdx.x] = hist[threadIdx.x];
+}
+
+template <typename K, int IPT>
+__global__ __launch_bounds__(kSortBlock) void sort_downsweep_kernel(const K* __restrict__ kin, K* __restrict__ kout,
+                                                                    const uint32_t* __restrict__ vin,
+                                                                    uint32_t* __restrict__ vout, uint32_t n, int shift,
+                                                                    uint32_t mask, const uint32_t* __restrict__ bases,
+                                                                    uint32_t ntiles) {
+    constexpr int WAVES = kSortBlock / kWave;
+    constexpr int TILE = kSortBlock * IPT;
+    constexpr int WTILE = kWave * IPT;
+    __shared__ uint32_t wcnt[WAVES][kRadix];   // per-wave digit counts, then per-wave exclusive offsets
+    __shared__ uint32_t dstart[kRadix];        // tile-local start of each digit
+    __shared__ uint32_t gbase[kRadix];         // global base of the digit for this tile, minus dstart
+    __shared__ uint32_t wave_tot[WAVES];
+    __shared__ K skeys[TILE];
+    __shared__ uint32_t svals[TILE];
+
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
+#pragma unroll
+    for (int i = 0; i < WAVES; ++i) wcnt[i][tid] = 0;
+    __syncthreads();
+
+    const uint32_t tile_base = blockIdx.x * TILE;
+    const uint32_t wbase = tile_base + w * WTILE;
+    K key[IPT];
+    uint32_t val[IPT];
+    uint32_t rank[IPT];
+#pragma unroll
+    for (int j = 0; j < IPT; ++j) {
+        uint32_t i = wbase + j * kWave + lane;
+        bool valid = i < n;
+        key[j] = valid ? kin[i] : K(~K(0));
+        val[j] = valid ? vin[i] : 0u;
+    }
+    const uint64_t lt = lanemask_lt();
+#pragma unroll
+    for (int j = 0; j < IPT; ++j) {
+        const bool valid = wbase + j * kWave + lane < n;
+        const uint32_t d = (uint32_t)(key[j] >> shift) & mask;
+        uint64_t peers = __ballot(valid);
+#pragma unroll
+        for (int b = 0; b < kRadixBits; ++b) {
+            const bool bit = (d >> b) & 1u;
+            const uint64_t m = __ballot(bit);
+            peers &= bit ? m : ~m;
+        }
+        const uint32_t before = wcnt[w][d];
+        rank[j] = before + (uint32_t)__popcll(peers & lt);
+        __builtin_amdgcn_wave_barrier();
+        if (valid && (peers & lt) == 0) wcnt[w][d] = before + (uint32_t)__popcll(peers);   // lowest peer lane
+        __builtin_amdgcn_wave_barrier();
+    }
+    __syncthreads();
+
+    {   // thread tid owns digit tid: offsets of the waves inside the digit, then digit starts inside the tile
+        uint32_t run = 0;
+#pragma unroll
+        for (int i = 0; i < WAVES; ++i) {
+            uint32_t c = wcnt[i][tid];
+            wcnt[i][tid] = run;
+            run += c;
+        }
+        uint32_t exc, inc, total;
+        block_scan<kSortBlock>(run, AddOp(), 0u, wave_tot, &exc, &inc, &total);
+        dstart[tid] = exc;
+        gbase[tid] = bases[(size_t)tid * ntiles + blockIdx.x] - exc;
+    }
+    __syncthreads();
+
+#pragma unroll
+    for (int j = 0; j < IPT; ++j) {
+        if (wbase + j * kWave + lane < n) {
+            const uint32_t d = (uint32_t)(key[j] >> shift) & mask;
+            const uint32_t pos = dstart[d] + wcnt[w][d] + rank[j];
+            skeys[pos] = key[j];
+            svals[pos] = val[j];
+        }
+    }
+    __syncthreads();
+
+    const uint32_t tile_n = n - tile_base < (uint32_t)TILE ? n - tile_base : (uint32_t)TILE;
+#pragma unroll
+    for (int j = 0; j < IPT; ++j) {
+        const uint32_t pos = j * kSortBlock + tid;
+        if (pos < tile_n) {
+            const K k = skeys[pos];
+            const uint32_t dst = gbase[(uint32_t)(k >> shift) & mask] + pos;
+            kout[dst] = k;
+            vout[dst] = svals[pos];
+        }
+    }
+}
+
+struct LoadU32 {
+    const uint32_t* p;
+    __device__ __forceinline__ uint32_t operator()(int64_t i) const { return p[i]; }
+};
+struct StoreExclusiveU32 {
+    uint32_t* p;
+    __device__ __forceinline__ void operator()(int64_t i, uint32_t exc, uint32_t) const { p[i] = exc; }
+};
+
+template <int IPT>
+inline uint32_t sort_num_tiles(int64_t n) { return (uint32_t)(n > 0 ? ceil_div(n, kSortBlock * IPT) : 1); }
+
+// uint32 words of temporary storage for radix_sort_pairs<.., IPT> of n elements
+template <int IPT>
+inline size_t sort_temp_words(int64_t n) {
+    size_t counts = (size_t)kRadix * sort_num_tiles<IPT>(n);
+    return counts + 64 + scan_partials((int64_t)counts) + 64;
+}
+
+// Sorts n (key, value) pairs by key bits [begin_bit, end_bit), stable.  The data ping-pongs between
+// (keys_a, vals_a) and (keys_b, vals_b); input is in the `a` buffers; *result_in_b tells where the
+// sorted output ended up.  n < 2^32 - kSortBlock*IPT.
+template <typename K, int IPT>
+int radix_sort_pairs(K* keys_a, K* keys_b, uint32_t* vals_a, uint32_t* vals_b, int64_t n, int begin_bit, int end_bit,
+                     uint32_t* temp, hipStream_t stream, bool* result_in_b) {
+    *result_in_b = false;
+    if (n <= 0) return BP_OK;
+    const uint32_t ntiles = sort_num_tiles<IPT>(n);
+    const int64_t ncounts = (int64_t)kRadix * ntiles;
+    uint32_t* counts = temp;
+    uint32_t* partials = temp + ((ncounts + 63) & ~int64_t(63));
+    K* kin = keys_a;
+    K* kout = keys_b;
+    uint32_t* vin = vals_a;
+    uint32_t* vout = vals_b;
+    for (int bit = begin_bit; bit < end_bit; bit += kRadixBits) {
+        const int nb = end_bit - bit < kRadixBits ? end_bit - bit : kRadixBits;
+        const uint32_t mask = (1u << nb) - 1u;
+        BP_LAUNCH(K_SORT_UPSWEEP, (sort_upsweep_kernel<K, IPT>), dim3(ntiles), dim3(kSortBlock), 0, stream,
+                  (const K*)kin, (uint32_t)n, bit, mask, counts, ntiles);
+        BP_TRY((device_scan<uint32_t, AddOp, LoadU32, StoreExclusiveU32>(LoadU32{counts}, StoreExclusiveU32{counts},
+                                                                         ncounts, partials, AddOp(), 0u, stream)));
+        BP_LAUNCH(K_SORT_DOWNSWEEP, (sort_downsweep_kernel<K, IPT>), dim3(ntiles), dim3(kSortBlock), 0, stream,
+                  (const K*)kin, kout, (const uint32_t*)vin, vout, (uint32_t)n, bit, mask, (const uint32_t*)counts,
+                  ntiles);
+        K* tk = kin; kin = kout; kout = tk;
+        uint32_t* tv = vin; vin = vout; vout = tv;
+        *result_in_b = !*result_in_b;
+    }
+    return BP_OK;
+}
+
+}  // namespace bp

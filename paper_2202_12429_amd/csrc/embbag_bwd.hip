@@ -1,0 +1,305 @@
+// bp_embbag_bwd_update: deterministic backward + fused sparse optimizer step on cached rows.
+//
+// Gradients, not embeddings, are combined (Section 6), so any per-row optimizer can follow; the update
+// rules are SGD, element-wise Adagrad and row-wise Adagrad.
+//
+//   1. keys = slot of every lookup, payload = its bag; stable LSD radix sort on the slot bits, so the
+//      lookups of a slot end up adjacent and in lookup order.
+//   2. the sorted array is cut into work items: a new item starts at every change of slot and at every
+//      multiple of kChunk positions (so a slot hit thousands of times by a skewed batch is shared by
+//      many lane groups); item starts are compacted with a scan.
+//   3. one lane group per item adds its gradient rows in order (fp32).  An item that covers its whole
+//      slot applies the update at once; otherwise the sum goes to a partial row addressed by the chunk
+//      boundary it touches.
+//   4. for slots split over several items, the group of the first item adds the partial rows in order
+//      and applies the update.
+// Every order of addition is fixed by the data, never by timing: results are bit-identical run to run.
+#include "common.h"
+#include "device_prims.h"
+#include "row_access.h"
+
+namespace bp {
+namespace {
+
+constexpr int kChunk = 32;        // sorted positions per work item at most
+constexpr int kMaxGridBlocks = 8192;
+
+// ---- 1. keys ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void bwd_keys_kernel(const int32_t* __restrict__ slots, const int64_t* __restrict__ bag_off,
+                                                       int64_t n, int64_t bags, int64_t C, uint32_t* __restrict__ keys,
+                                                       uint32_t* __restrict__ vals) {
+    const int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (k >= n) return;
+    const uint32_t s = (uint32_t)slots[k];
+    keys[k] = s < (uint64_t)C ? s : (uint32_t)C;     // out-of-range slots sort behind every real one
+    uint32_t bag = (uint32_t)k;
+    if (bag_off) {                                   // largest b with bag_off[b] <= k
+        int64_t lo = 0, hi = bags;                   // bag_off[lo] <= k < bag_off[hi]
+        while (hi - lo > 1) {
+            const int64_t mid = (lo + hi) >> 1;
+            if (bag_off[mid] <= k) lo = mid; else hi = mid;
+        }
+        bag = (uint32_t)lo;
+    }
+    vals[k] = bag;
+}
+
+// ---- 2. work items ---------------------------------------------------------------------------
+struct ItemStartIn {
+    const uint32_t* keys;
+    __device__ __forceinline__ uint32_t operator()(int64_t p) const {
+        return (p == 0 || (p % kChunk) == 0 || keys[p] != keys[p - 1]) ? 1u : 0u;
+    }
+};
+struct ItemStartOut {
+    uint32_t* item_start;
+    __device__ __forceinline__ void operator()(int64_t p, uint32_t exc, uint32_t inc) const {
+        if (inc != exc) item_start[exc] = (uint32_t)p;
+    }
+};
+
+// ---- 3./4. reduce and update -----------------------------------------------------------------
+struct UpdateParams {
+    int optimizer;
+    float lr, eps, inv_dim;
+    int lpr;
+    int dim;
+};
+
+template <int GW>
+__device__ __forceinline__ float group_sum(float x) {
+#pragma unroll
+    for (int off = GW / 2; off >= 1; off >>= 1) x += __shfl_xor(x, off, GW);
+    return x;
+}
+
+// Applies one optimizer step to the piece of lane c of row `slot`.  All lanes of the group call this
+// (the row-wise rule reduces over the group); lanes with c >= lpr carry zeros and touch no memory.
+template <int GW, bool BF16>
+__device__ __forceinline__ void apply_update(const UpdateParams& u, uint4* cache_w, float* cache_s, int64_t slot, int c,
+                                             const Piece<BF16>& g) {
+    constexpr int N = Piece<BF16>::N;
+    const bool active = c < u.lpr;
+    Piece<BF16> w;
+    w.zero();
+    if (active) w.decode(cache_w[slot * u.lpr + c]);
+    if (u.optimizer == BP_SGD) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) w.v[i] -= u.lr * g.v[i];
+    } else if (u.optimizer == BP_ADAGRAD) {
+        if (active) {
+            Piece<BF16> s;
+            s.load_f32(cache_s + slot * u.dim, c);
+#pragma unroll
+            for (int i = 0; i < N; ++i) {
+                s.v[i] += g.v[i] * g.v[i];
+                w.v[i] -= u.lr * g.v[i] / (sqrtf(s.v[i]) + u.eps);
+            }
+            s.store_f32(cache_s + slot * u.dim, c);
+        }
+    } else {
+        float ss = 0.f;
+#pragma unroll
+        for (int i = 0; i < N; ++i) ss += g.v[i] * g.v[i];
+        ss = group_sum<GW>(ss);
+        const float s = cache_s[slot] + ss * u.inv_dim;
+        const float den = sqrtf(s) + u.eps;
+#pragma unroll
+        for (int i = 0; i < N; ++i) w.v[i] -= u.lr * g.v[i] / den;
+        if (c == 0) cache_s[slot] = s;
+    }
+    if (active) cache_w[slot * u.lpr + c] = w.encode();
+}
+
+template <int GW, bool BF16>
+__global__ __launch_bounds__(kRowBlock) void bwd_reduce_update_kernel(const uint32_t* __restrict__ keys,
+                                                                     const uint32_t* __restrict__ bag_of,
+                                                                     const uint32_t* __restrict__ item_start,
+                                                                     const uint32_t* __restrict__ n_items_ptr, uint32_t n,
+                                                                     int64_t C, const float* __restrict__ grad,
+                                                                     uint4* cache_w, float* cache_s, float* partial,
+                                                                     UpdateParams u) {
+    const uint32_t W = *n_items_ptr;
+    const int c = threadIdx.x % GW;
+    const bool active = c < u.lpr;
+    const uint32_t groups = gridDim.x * (kRowBlock / GW);
+    for (uint32_t w = (blockIdx.x * kRowBlock + threadIdx.x) / GW; w < W; w += groups) {
+        const uint32_t start = item_start[w];
+        const uint32_t end = w + 1 < W ? item_start[w + 1] : n;
+        const uint32_t slot = keys[start];
+        if ((int64_t)slot >= C) continue;            // sentinel of out-of-range slots
+        const bool head = start == 0 || keys[start - 1] != slot;
+        const bool tail = end == n || keys[end] != slot;
+        Piece<BF16> acc;
+        acc.zero();
+        if (active) {
+            uint32_t p = start;
+            for (; p + 4 <= end; p += 4) {           // four gradient rows in flight, added in order
+                Piece<BF16> t[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) t[j].load_f32(grad + (size_t)bag_of[p + j] * u.dim, c);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc.add(t[j]);
+            }
+            for (; p < end; ++p) {
+                Piece<BF16> t;
+                t.load_f32(grad + (size_t)bag_of[p] * u.dim, c);
+                acc.add(t);
+            }
+        }
+        if (head && tail) {
+            apply_update<GW, BF16>(u, cache_w, cache_s, (int64_t)slot, c, acc);
+        } else if (active) {
+            // head item of a split slot ends on a chunk boundary b*kChunk: row 2b; a later item starts on
+            // boundary b*kChunk: row 2b+1
+            const size_t row = head ? 2 * (size_t)(end / kChunk) : 2 * (size_t)(start / kChunk) + 1;
+            acc.store_f32(partial + row * u.dim, c);
+        }
+    }
+}
+
+template <int GW, bool BF16>
+__global__ __launch_bounds__(kRowBlock) void bwd_combine_update_kernel(const uint32_t* __restrict__ keys,
+                                                                      const uint32_t* __restrict__ item_start,
+                                                                      const uint32_t* __restrict__ n_items_ptr, uint32_t n,
+                                                                      int64_t C, uint4* cache_w, float* cache_s,
+                                                                      const float* __restrict__ partial, UpdateParams u) {
+    const uint32_t W = *n_items_ptr;
+    const int c = threadIdx.x % GW;
+    const bool active = c < u.lpr;
+    const uint32_t groups = gridDim.x * (kRowBlock / GW);
+    for (uint32_t w = (blockIdx.x * kRowBlock + threadIdx.x) / GW; w < W; w += groups) {
+        const uint32_t start = item_start[w];
+        const uint32_t end = w + 1 < W ? item_start[w + 1] : n;
+        const uint32_t slot = keys[start];
+        if ((int64_t)slot >= C) continue;
+        const bool head = start == 0 || keys[start - 1] != slot;
+        const bool tail = end == n || keys[end] != slot;
+        if (!head || tail) continue;                  // only the first item of a split slot works here
+        Piece<BF16> acc;
+        acc.zero();
+        uint32_t b = end / kChunk;                    // end is a chunk boundary because the slot goes on
+        if (active) acc.load_f32(partial + 2 * (size_t)b * u.dim, c);
+        for (;;) {                                    // items starting at boundaries b, b+1, ... of this slot
+            if (active) {
+                Piece<BF16> t;
+                t.load_f32(partial + (2 * (size_t)b + 1) * u.dim, c);
+                acc.add(t);
+            }
+            const uint64_t next = (uint64_t)(b + 1) * kChunk;
+            if (next >= n || keys[next] != slot) break;
+            ++b;
+        }
+        apply_update<GW, BF16>(u, cache_w, cache_s, (int64_t)slot, c, acc);
+    }
+}
+
+// ---- workspace -------------------------------------------------------------------------------
+constexpr int kSmallIPT = 4, kLargeIPT = 16;
+constexpr int64_t kLargeSort = int64_t(1) << 21;
+
+struct BwdWorkspace {
+    uint32_t *keys_a, *keys_b, *vals_a, *vals_b, *sort_temp, *item_start, *scan_partials;
+    float* partial;
+    size_t bytes;
+};
+
+BwdWorkspace carve_bwd(void* base, size_t cap, int64_t n, int dim) {
+    Carver c(base, cap);
+    BwdWorkspace w{};
+    const size_t m = (size_t)(n > 0 ? n : 1);
+    w.keys_a = c.take<uint32_t>(m);
+    w.keys_b = c.take<uint32_t>(m);
+    w.vals_a = c.take<uint32_t>(m);
+    w.vals_b = c.take<uint32_t>(m);
+    w.sort_temp = c.take<uint32_t>(n >= kLargeSort ? sort_temp_words<kLargeIPT>(n) : sort_temp_words<kSmallIPT>(n));
+    w.item_start = c.take<uint32_t>(m + 1);
+    w.scan_partials = c.take<uint32_t>(scan_partials(n));
+    w.partial = c.take<float>((2 * (m / kChunk + 2)) * (size_t)dim);
+    w.bytes = c.used();
+    return w;
+}
+
+struct BwdLaunch {
+    const bp_config* cfg;
+    const BwdWorkspace* w;
+    const uint32_t *skeys, *sbags;
+    const uint32_t* n_items;
+    int64_t n;
+    const float* grad;
+    void* cache_w;
+    void* cache_s;
+    hipStream_t stream;
+    template <int GW, bool BF16>
+    int run() {
+        UpdateParams u{cfg->optimizer, cfg->lr, cfg->eps, 1.0f / (float)cfg->dim, (int)(row_bytes(cfg) / 16), cfg->dim};
+        const int groups_per_block = kRowBlock / GW;
+        int64_t blocks = ceil_div(n, groups_per_block);
+        if (blocks > kMaxGridBlocks) blocks = kMaxGridBlocks;
+        BP_LAUNCH(K_BWD_REDUCE_UPDATE, (bwd_reduce_update_kernel<GW, BF16>), dim3((unsigned)blocks), dim3(kRowBlock), 0, stream,
+                  skeys, sbags, (const uint32_t*)w->item_start, n_items, (uint32_t)n, cfg->capacity, grad, (uint4*)cache_w,
+                  (float*)cache_s, w->partial, u);
+        BP_LAUNCH(K_BWD_COMBINE_UPDATE, (bwd_combine_update_kernel<GW, BF16>), dim3((unsigned)blocks), dim3(kRowBlock), 0,
+                  stream, skeys, (const uint32_t*)w->item_start, n_items, (uint32_t)n, cfg->capacity, (uint4*)cache_w,
+                  (float*)cache_s, (const float*)w->partial, u);
+        return BP_OK;
+    }
+};
+
+int check_bwd_args(const bp_config* cfg, int64_t n, int64_t bags) {
+    BP_TRY(check_config(cfg));
+    if (n < 0 || bags < 0) return fail(BP_ERR_INVALID_ARG, "negative size");
+    if (n >= (int64_t(1) << 31) || bags >= (int64_t(1) << 31)) return fail(BP_ERR_UNSUPPORTED, "size >= 2^31");
+    return BP_OK;
+}
+
+}  // namespace
+}  // namespace bp
+
+using namespace bp;
+
+BP_EXPORT int bp_embbag_bwd_update_workspace_bytes(const bp_config* cfg, int64_t n_lookups, int64_t bags, size_t* bytes) {
+    if (!bytes) return fail(BP_ERR_INVALID_ARG, "bytes is NULL");
+    BP_TRY(check_bwd_args(cfg, n_lookups, bags));
+    *bytes = carve_bwd(nullptr, 0, n_lookups, cfg->dim).bytes;
+    return BP_OK;
+}
+
+BP_EXPORT int bp_embbag_bwd_update(const bp_config* cfg, void* cache_w, void* cache_state, const int32_t* lookup_slots,
+                                    const int64_t* bag_offsets, int64_t n_lookups, int64_t bags, const float* grad_out,
+                                    void* workspace, size_t workspace_bytes, void* stream_) {
+    hipStream_t stream = (hipStream_t)stream_;
+    const int64_t n = n_lookups;
+    BP_TRY(check_bwd_args(cfg, n, bags));
+    if (n == 0) return BP_OK;
+    if (!bag_offsets && n != bags)
+        return fail(BP_ERR_INVALID_ARG, "bag_offsets is NULL but n_lookups %lld != bags %lld", (long long)n, (long long)bags);
+    if (!cache_w || !lookup_slots || !grad_out) return fail(BP_ERR_INVALID_ARG, "NULL pointer");
+    if (cfg->optimizer != BP_SGD && !cache_state) return fail(BP_ERR_INVALID_ARG, "cache_state is NULL");
+    if (((uintptr_t)cache_w | (uintptr_t)cache_state | (uintptr_t)grad_out) & 15)
+        return fail(BP_ERR_INVALID_ARG, "cache_w, cache_state and grad_out must be 16-byte aligned");
+    if (!workspace || ((uintptr_t)workspace & 255)) return fail(BP_ERR_INVALID_ARG, "workspace NULL or not 256-byte aligned");
+    BwdWorkspace w = carve_bwd(workspace, workspace_bytes, n, cfg->dim);
+    if (w.bytes > workspace_bytes)
+        return fail(BP_ERR_WORKSPACE_TOO_SMALL, "workspace %zu < required %zu bytes", workspace_bytes, w.bytes);
+
+    BP_LAUNCH(K_BWD_KEYS, bwd_keys_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, stream, lookup_slots, bag_offsets, n,
+              bags, cfg->capacity, w.keys_a, w.vals_a);
+    bool in_b = false;
+    const int key_bits = bits_for(cfg->capacity + 1);
+    if (n >= kLargeSort)
+        BP_TRY((radix_sort_pairs<uint32_t, kLargeIPT>(w.keys_a, w.keys_b, w.vals_a, w.vals_b, n, 0, key_bits, w.sort_temp,
+                                                      stream, &in_b)));
+    else
+        BP_TRY((radix_sort_pairs<uint32_t, kSmallIPT>(w.keys_a, w.keys_b, w.vals_a, w.vals_b, n, 0, key_bits, w.sort_temp,
+                                                      stream, &in_b)));
+    const uint32_t* skeys = in_b ? w.keys_b : w.keys_a;
+    const uint32_t* sbags = in_b ? w.vals_b : w.vals_a;
+
+    BP_TRY((device_scan<uint32_t, AddOp, ItemStartIn, ItemStartOut>(ItemStartIn{skeys}, ItemStartOut{w.item_start}, n,
+                                                                    w.scan_partials, AddOp(), 0u, stream)));
+    const uint32_t* n_items = w.scan_partials + scan_num_tiles(n);
+
+    BwdLaunch l{cfg, &w, skeys, sbags, n_items, n, grad_out, cache_w, cache_state, stream};
+    return dispatch_row((int)(row_bytes(cfg) / 16), cfg->weight_dtype == BP_BF16, l);
+}

@@ -1,0 +1,88 @@
+// bp_embbag_fwd: EmbeddingBag-sum forward over cache slots (the trainer's embedding lookup, Section 2.1,
+// served from the GPU-resident cache of Section 3.2).  One lane group per bag; every lane owns a
+// 16-byte piece of the row, accumulates in fp32 in lookup order and writes its piece of the pooled row,
+// so both the gathered rows and the output are moved in full 16-byte-per-lane transactions.
+#include "common.h"
+#include "row_access.h"
+
+namespace bp {
+namespace {
+
+template <int GW, bool BF16>
+__global__ __launch_bounds__(kRowBlock) void embbag_fwd_kernel(const uint4* __restrict__ cache_w,
+                                                               const int32_t* __restrict__ slots,
+                                                               const int64_t* __restrict__ bag_off, int64_t bags, int64_t C,
+                                                               int lpr, int dim, float* __restrict__ out) {
+    const int64_t bag = ((int64_t)blockIdx.x * kRowBlock + threadIdx.x) / GW;
+    const int c = threadIdx.x % GW;
+    if (bag >= bags || c >= lpr) return;
+    Piece<BF16> acc;
+    acc.zero();
+    if (bag_off == nullptr) {                       // one lookup per bag: a row copy (exact)
+        const uint32_t s = (uint32_t)slots[bag];
+        if (s < (uint64_t)C) acc.decode(cache_w[(int64_t)s * lpr + c]);
+    } else {
+        int64_t k = bag_off[bag];
+        const int64_t end = bag_off[bag + 1];
+        for (; k + 4 <= end; k += 4) {              // four independent row loads in flight, added in order
+            uint32_t s[4];
+            uint4 raw[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) s[j] = (uint32_t)slots[k + j];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) raw[j] = s[j] < (uint64_t)C ? cache_w[(int64_t)s[j] * lpr + c] : make_uint4(0, 0, 0, 0);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                Piece<BF16> p;
+                p.decode(raw[j]);
+                acc.add(p);
+            }
+        }
+        for (; k < end; ++k) {
+            const uint32_t s = (uint32_t)slots[k];
+            if (s < (uint64_t)C) {
+                Piece<BF16> p;
+                p.decode(cache_w[(int64_t)s * lpr + c]);
+                acc.add(p);
+            }
+        }
+    }
+    acc.store_f32(out + bag * dim, c);
+}
+
+struct FwdLaunch {
+    const bp_config* cfg;
+    const void* cache_w;
+    const int32_t* slots;
+    const int64_t* bag_off;
+    int64_t bags;
+    float* out;
+    hipStream_t stream;
+    template <int GW, bool BF16>
+    int run() {
+        const int lpr = (int)(row_bytes(cfg) / 16);
+        const dim3 grid((unsigned)ceil_div(bags * GW, kRowBlock));
+        BP_LAUNCH(K_FWD, (embbag_fwd_kernel<GW, BF16>), grid, dim3(kRowBlock), 0, stream, (const uint4*)cache_w, slots,
+                  bag_off, bags, cfg->capacity, lpr, cfg->dim, out);
+        return BP_OK;
+    }
+};
+
+}  // namespace
+}  // namespace bp
+
+using namespace bp;
+
+BP_EXPORT int bp_embbag_fwd(const bp_config* cfg, const void* cache_w, const int32_t* lookup_slots,
+                             const int64_t* bag_offsets, int64_t n_lookups, int64_t bags, float* out, void* stream) {
+    BP_TRY(check_config(cfg));
+    if (bags < 0 || n_lookups < 0) return fail(BP_ERR_INVALID_ARG, "negative size");
+    if (bags >= (int64_t(1) << 31) || n_lookups >= (int64_t(1) << 31)) return fail(BP_ERR_UNSUPPORTED, "size >= 2^31");
+    if (bags == 0) return BP_OK;
+    if (!bag_offsets && n_lookups != bags)
+        return fail(BP_ERR_INVALID_ARG, "bag_offsets is NULL but n_lookups %lld != bags %lld", (long long)n_lookups, (long long)bags);
+    if (!cache_w || !out || (n_lookups && !lookup_slots)) return fail(BP_ERR_INVALID_ARG, "NULL pointer");
+    if (((uintptr_t)cache_w | (uintptr_t)out) & 15) return fail(BP_ERR_INVALID_ARG, "cache_w and out must be 16-byte aligned");
+    FwdLaunch l{cfg, cache_w, lookup_slots, bag_offsets, bags, out, (hipStream_t)stream};
+    return dispatch_row((int)(row_bytes(cfg) / 16), cfg->weight_dtype == BP_BF16, l);
+}

@@ -1,0 +1,548 @@
+// bp_oracle_plan: the lookahead planner (Algorithm 1, Section 3.2) as data-parallel passes.
+//
+// Algorithm 1 walks the batches with a dictionary and a set.  The same decisions follow from one fact
+// per (id, batch) pair — the gap to the id's next use:
+//   kept after batch i   <=>  gap < L_eff            (its TTL lies beyond i)
+//   prefetched at i      <=>  first use, or not kept after the previous use
+//   TTL                   =   last use inside [i, i + L_eff - 1]
+// so the planner sorts (id, batch) keys, dedupes them into unique pairs, reads gaps off neighbouring
+// pairs, and derives everything else with scans:
+//   1. keys (id << iter_bits | batch), stable LSD radix sort with the lookup position as payload
+//   2. head flags + scan  -> unique pairs (sorted by id, then batch), pair index of every lookup
+//   3. histogram H[gap][batch] and per-batch unique counts -> occupancy for every candidate lookahead
+//      -> L_eff = largest lookahead whose peak occupancy fits the capacity
+//   4. per-pair flags (miss / evict), TTL, and the pair that fetched the row (max-scan of miss indices)
+//   5. regroup pairs by batch (stable sort on the batch bits) -> lists ascending in id inside a batch,
+//      miss / evict ordinals by one packed scan
+//   6. FIFO free ring without a walk over batches: the x-th miss takes ring position x; positions below
+//      C are the initial slots, position C + e holds the slot freed by the e-th eviction, i.e. the slot
+//      of an earlier miss.  Following those links is pointer jumping, ceil(log2 T) + 1 rounds.
+//   7. slots of pairs -> list slots and the per-lookup slot map
+#include <vector>
+
+#include "common.h"
+#include "device_prims.h"
+
+namespace bp {
+namespace {
+
+constexpr int kPlanSortIPT = 16;       // 4096 keys per tile for the big (id, batch) sort
+constexpr int kBlock = 256;
+constexpr uint32_t kGapInf = 0x7fffffffu;
+constexpr int kMaxIters = 8192;
+
+struct PlanScalars {
+    uint32_t error_flags;   // bit 0: id out of range
+    int32_t L_eff;          // 0 = no feasible lookahead
+    int32_t L_sel;          // min(L_eff, Lcap): index into peak[]
+    uint32_t pad;
+    int64_t peak;
+    int64_t min_capacity;
+};
+
+// ---- 1. keys ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void plan_keys_kernel(const int64_t* __restrict__ ids,
+                                                           const int64_t* __restrict__ iter_off, int T, int64_t N,
+                                                           int64_t R, int ib, uint64_t* __restrict__ keys,
+                                                           uint32_t* __restrict__ pos, PlanScalars* sc) {
+    const int64_t p = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (p >= N) return;
+    int64_t g = ids[p];
+    if (g < 0 || g >= R) {
+        atomicOr(&sc->error_flags, 1u);
+        g = 0;
+    }
+    int lo = 0, hi = T;   // iter_off[lo] <= p < iter_off[hi]
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (iter_off[mid] <= p) lo = mid; else hi = mid;
+    }
+    keys[p] = ((uint64_t)g << ib) | (uint64_t)lo;
+    pos[p] = (uint32_t)p;
+}
+
+// ---- 2. unique pairs -------------------------------------------------------------------------
+struct HeadFlagIn {
+    const uint64_t* keys;
+    __device__ __forceinline__ uint32_t operator()(int64_t p) const {
+        return (p == 0 || keys[p] != keys[p - 1]) ? 1u : 0u;
+    }
+};
+struct PairOut {
+    const uint64_t* keys;
+    uint64_t* ukey;
+    uint32_t* uq;
+    __device__ __forceinline__ void operator()(int64_t p, uint32_t exc, uint32_t inc) const {
+        uq[p] = inc - 1u;
+        if (inc != exc) ukey[exc] = keys[p];
+    }
+};
+
+// ---- 3. gaps, histogram, occupancy -----------------------------------------------------------
+__device__ __forceinline__ uint32_t pair_gap(const uint64_t* ukey, uint32_t q, uint32_t M, int ib, uint64_t imask) {
+    if (q + 1 >= M) return kGapInf;
+    const uint64_t a = ukey[q], b = ukey[q + 1];
+    return (a >> ib) == (b >> ib) ? (uint32_t)((b & imask) - (a & imask)) : kGapInf;
+}
+
+__global__ __launch_bounds__(kBlock) void plan_hist_kernel(const uint64_t* __restrict__ ukey, uint32_t M, int ib, int T,
+                                                           int Lcap, uint32_t* __restrict__ H,
+                                                           uint32_t* __restrict__ ucount) {
+    extern __shared__ uint32_t lds_u[];   // [T]
+    for (int i = threadIdx.x; i < T; i += kBlock) lds_u[i] = 0;
+    __syncthreads();
+    const uint64_t imask = (uint64_t(1) << ib) - 1;
+    for (uint32_t q = blockIdx.x * kBlock + threadIdx.x; q < M; q += gridDim.x * kBlock) {
+        const uint32_t i = (uint32_t)(ukey[q] & imask);
+        atomicAdd(&lds_u[i], 1u);
+        const uint32_t gap = pair_gap(ukey, q, M, ib, imask);
+        if (gap >= 2u && gap < (uint32_t)Lcap) atomicAdd(&H[(size_t)gap * T + i], 1u);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < T; i += kBlock)
+        if (lds_u[i]) atomicAdd(&ucount[i], lds_u[i]);
+}
+
+// H[gap][.] -> inclusive prefix over batches, one thread per gap row
+__global__ void plan_occ_prefix_kernel(uint32_t* H, int T, int Lcap) {
+    const int gap = blockIdx.x * blockDim.x + threadIdx.x;
+    if (gap < 2 || gap >= Lcap) return;
+    uint32_t* row = H + (size_t)gap * T;
+    uint32_t run = 0;
+    for (int i = 0; i < T; ++i) {
+        run += row[i];
+        row[i] = run;
+    }
+}
+
+// rows resident but unused at batch j because of pairs with exactly this gap: batches i in (j - gap, j)
+__device__ __forceinline__ uint32_t covering(const uint32_t* Hc, int T, int gap, int j) {
+    if (j < 1) return 0;
+    const uint32_t* row = Hc + (size_t)gap * T;
+    const uint32_t hi = row[j - 1];
+    const uint32_t lo = j - gap >= 0 ? row[j - gap] : 0u;
+    return hi - lo;
+}
+
+// peak[L'] = max_j occupancy(j, L') for L' = 1..Lcap, one thread per batch j
+__global__ void plan_occ_peak_kernel(const uint32_t* __restrict__ Hc, const uint32_t* __restrict__ ucount, int T,
+                                     int Lcap, uint32_t* __restrict__ peak) {
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= T) return;
+    uint32_t run = ucount[j];
+    atomicMax(&peak[1], run);
+    for (int Lp = 2; Lp <= Lcap; ++Lp) {
+        const int gap = Lp - 1;              // pairs with gap <= L'-1 are kept under L'
+        if (gap >= 2) run += covering(Hc, T, gap, j);
+        atomicMax(&peak[Lp], run);
+    }
+}
+
+// one thread: pick L_eff, exclusive scan of the per-batch unique counts
+__global__ void plan_choose_kernel(const uint32_t* __restrict__ peak, const uint32_t* __restrict__ ucount, int T,
+                                   int Lcap, int lookahead, int64_t C, PlanScalars* sc,
+                                   uint32_t* __restrict__ pair_off) {
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    int sel = 0;
+    for (int Lp = Lcap; Lp >= 1; --Lp)
+        if ((int64_t)peak[Lp] <= C) { sel = Lp; break; }
+    sc->L_sel = sel;
+    sc->L_eff = sel == Lcap ? lookahead : sel;   // windows of T or more batches are all alike
+    sc->peak = sel ? peak[sel] : 0;
+    sc->min_capacity = peak[1];
+    uint32_t run = 0;
+    for (int i = 0; i < T; ++i) {
+        pair_off[i] = run;
+        run += ucount[i];
+    }
+    pair_off[T] = run;
+}
+
+__global__ void plan_occ_final_kernel(const uint32_t* __restrict__ Hc, const uint32_t* __restrict__ ucount, int T,
+                                      const PlanScalars* sc, int64_t* __restrict__ occ) {
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= T) return;
+    uint32_t run = ucount[j];
+    for (int gap = 2; gap < sc->L_sel; ++gap) run += covering(Hc, T, gap, j);
+    occ[j] = run;
+}
+
+// ---- 4. per-pair decisions -------------------------------------------------------------------
+constexpr uint8_t kMiss = 1, kEvict = 2;
+
+__global__ __launch_bounds__(kBlock) void plan_flags_kernel(const uint64_t* __restrict__ ukey, uint32_t M, int ib,
+                                                            const PlanScalars* sc, uint8_t* __restrict__ flags,
+                                                            int32_t* __restrict__ ttl, uint32_t* __restrict__ key2,
+                                                            uint32_t* __restrict__ val2) {
+    const uint32_t q = blockIdx.x * kBlock + threadIdx.x;
+    if (q >= M) return;
+    const uint64_t imask = (uint64_t(1) << ib) - 1;
+    const int64_t Leff = sc->L_eff;
+    const uint64_t k = ukey[q];
+    const uint64_t g = k >> ib;
+    const int64_t i = (int64_t)(k & imask);
+    const uint32_t gap = pair_gap(ukey, q, M, ib, imask);
+    const bool keep = (int64_t)gap < Leff;
+    bool miss = true;
+    if (q > 0) {
+        const uint64_t kp = ukey[q - 1];
+        if ((kp >> ib) == g && i - (int64_t)(kp & imask) < Leff) miss = false;
+    }
+    int32_t t = (int32_t)i;
+    if (keep) {
+        // last pair of this id whose batch is <= i + L_eff - 1: it lies within L_eff - 1 pairs of q
+        const int64_t last_iter = i + Leff - 1 < (int64_t)imask ? i + Leff - 1 : (int64_t)imask;
+        const uint64_t bound = (g << ib) | (uint64_t)last_iter;
+        int64_t lo = q, hi = (int64_t)q + Leff - 1;     // ukey[lo] <= bound; answer in [lo, hi]
+        if (hi > (int64_t)M - 1) hi = (int64_t)M - 1;
+        while (lo < hi) {
+            const int64_t mid = (lo + hi + 1) >> 1;
+            if (ukey[mid] <= bound) lo = mid; else hi = mid - 1;
+        }
+        t = (int32_t)(ukey[lo] & imask);
+    }
+    flags[q] = (miss ? kMiss : 0) | (keep ? 0 : kEvict);
+    ttl[q] = t;
+    key2[q] = (uint32_t)i;
+    val2[q] = q;
+}
+
+struct MissIndexIn {
+    const uint8_t* flags;
+    __device__ __forceinline__ uint32_t operator()(int64_t q) const { return (flags[q] & kMiss) ? (uint32_t)q : 0u; }
+};
+struct StoreInclusiveU32 {
+    uint32_t* p;
+    __device__ __forceinline__ void operator()(int64_t i, uint32_t, uint32_t inc) const { p[i] = inc; }
+};
+
+// ---- 5. lists in (batch, id) order -----------------------------------------------------------
+struct ListCountIn {
+    const uint32_t* ord;
+    const uint8_t* flags;
+    __device__ __forceinline__ uint64_t operator()(int64_t k) const {
+        const uint8_t f = flags[ord[k]];
+        return (uint64_t)(f & kMiss) | ((uint64_t)((f & kEvict) >> 1) << 32);
+    }
+};
+struct ListOut {
+    const uint32_t* ord;
+    const uint8_t* flags;
+    const uint64_t* ukey;
+    const int32_t* ttl;
+    const uint32_t* pair_off;
+    int ib;
+    int64_t* keep_ids;
+    int32_t* keep_ttl;
+    int64_t* prefetch_ids;
+    int64_t* evict_ids;
+    uint32_t* missord;
+    uint32_t* evict_pair;
+    int64_t* prefetch_off;   // device copies of the CSR offsets, [T+1], pre-filled with -1
+    int64_t* evict_off;
+    __device__ __forceinline__ void operator()(int64_t k, uint64_t exc, uint64_t) const {
+        const uint32_t q = ord[k];
+        const uint64_t key = ukey[q];
+        const int64_t g = (int64_t)(key >> ib);
+        const uint32_t i = (uint32_t)(key & ((uint64_t(1) << ib) - 1));
+        const uint32_t x = (uint32_t)exc, e = (uint32_t)(exc >> 32);
+        const uint8_t f = flags[q];
+        keep_ids[k] = g;
+        keep_ttl[k] = ttl[q];
+        if (f & kMiss) {
+            prefetch_ids[x] = g;
+            missord[q] = x;
+        }
+        if (f & kEvict) {
+            evict_ids[e] = g;
+            evict_pair[e] = q;
+        }
+        if ((uint32_t)k == pair_off[i]) {
+            prefetch_off[i] = x;
+            evict_off[i] = e;
+        }
+    }
+};
+
+// ---- 6. FIFO ring by pointer jumping ---------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void plan_ring_init_kernel(const uint64_t* __restrict__ totals, int64_t C,
+                                                                const uint32_t* __restrict__ evict_pair,
+                                                                const uint32_t* __restrict__ chain,
+                                                                const uint32_t* __restrict__ missord,
+                                                                uint32_t* __restrict__ par) {
+    const uint32_t n_miss = (uint32_t)*totals, n_evict = (uint32_t)(*totals >> 32);
+    const uint32_t x = blockIdx.x * kBlock + threadIdx.x;
+    if (x >= n_miss) return;
+    if ((int64_t)x < C) {
+        par[x] = x;                                   // initial ring content: slot x at position x
+    } else {
+        const uint32_t e = (uint32_t)((int64_t)x - C);   // ring position C + e was pushed by eviction e
+        par[x] = e < n_evict ? missord[chain[evict_pair[e]]] : 0u;
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void plan_ring_jump_kernel(const uint64_t* __restrict__ totals, uint32_t* par) {
+    const uint32_t n_miss = (uint32_t)*totals;
+    const uint32_t x = blockIdx.x * kBlock + threadIdx.x;
+    if (x >= n_miss) return;
+    const uint32_t p = par[x];
+    const uint32_t pp = p < n_miss ? par[p] : 0u;
+    if (pp != p) par[x] = pp;
+}
+
+// ---- 7. slots --------------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void plan_pair_slots_kernel(uint32_t M, const uint32_t* __restrict__ chain,
+                                                                 const uint32_t* __restrict__ missord,
+                                                                 const uint32_t* __restrict__ par,
+                                                                 int32_t* __restrict__ slot_of_pair) {
+    const uint32_t q = blockIdx.x * kBlock + threadIdx.x;
+    if (q < M) slot_of_pair[q] = (int32_t)par[missord[chain[q]]];
+}
+
+__global__ __launch_bounds__(kBlock) void plan_list_slots_kernel(const uint64_t* __restrict__ totals,
+                                                                 const uint32_t* __restrict__ par,
+                                                                 const uint32_t* __restrict__ evict_pair,
+                                                                 const int32_t* __restrict__ slot_of_pair,
+                                                                 int32_t* __restrict__ prefetch_slots,
+                                                                 int32_t* __restrict__ evict_slots) {
+    const uint32_t n_miss = (uint32_t)*totals, n_evict = (uint32_t)(*totals >> 32);
+    const uint32_t x = blockIdx.x * kBlock + threadIdx.x;
+    if (x < n_miss) prefetch_slots[x] = (int32_t)par[x];
+    if (x < n_evict) evict_slots[x] = slot_of_pair[evict_pair[x]];
+}
+
+__global__ __launch_bounds__(kBlock) void plan_lookup_slots_kernel(int64_t N, const uint32_t* __restrict__ pos,
+                                                                   const uint32_t* __restrict__ uq,
+                                                                   const int32_t* __restrict__ slot_of_pair,
+                                                                   int32_t* __restrict__ lookup_slots) {
+    const int64_t p = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (p < N) lookup_slots[pos[p]] = slot_of_pair[uq[p]];
+}
+
+template <typename T>
+__global__ __launch_bounds__(kBlock) void fill_kernel(T* p, int64_t n, T v) {
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// ---- workspace layout ------------------------------------------------------------------------
+struct PlanWorkspace {
+    uint64_t *keys_a, *keys_b;
+    uint32_t *pos_a, *pos_b;
+    uint32_t* sort_temp;
+    uint32_t* scan_partials32;   // head scan, chain scan
+    uint64_t* scan_partials64;   // list scan
+    uint32_t *H, *ucount, *peak, *pair_off;
+    PlanScalars* scalars;
+    int64_t *occ, *prefetch_off, *evict_off, *iter_off;
+    uint8_t* flags;
+    int32_t* ttl;
+    uint32_t *chain, *key2_a, *key2_b, *val2_a, *val2_b, *missord, *evict_pair, *par;
+    int32_t* slot_of_pair;
+    size_t bytes;
+};
+
+PlanWorkspace carve_plan(void* base, size_t cap, int64_t N, int T, int Lcap) {
+    Carver c(base, cap);
+    PlanWorkspace w{};
+    const size_t n = (size_t)(N > 0 ? N : 1);
+    w.keys_a = c.take<uint64_t>(n);
+    w.keys_b = c.take<uint64_t>(n);
+    w.pos_a = c.take<uint32_t>(n);
+    w.pos_b = c.take<uint32_t>(n);
+    w.sort_temp = c.take<uint32_t>(sort_temp_words<kPlanSortIPT>(N));
+    w.scan_partials32 = c.take<uint32_t>(scan_partials(N));
+    w.scan_partials64 = c.take<uint64_t>(scan_partials(N));
+    w.H = c.take<uint32_t>((size_t)(Lcap + 1) * T);
+    w.ucount = c.take<uint32_t>(T);
+    w.peak = c.take<uint32_t>(Lcap + 2);
+    w.pair_off = c.take<uint32_t>(T + 1);
+    w.scalars = c.take<PlanScalars>(1);
+    w.occ = c.take<int64_t>(T);
+    w.prefetch_off = c.take<int64_t>(T + 1);
+    w.evict_off = c.take<int64_t>(T + 1);
+    w.iter_off = c.take<int64_t>(T + 1);
+    w.flags = c.take<uint8_t>(n);
+    w.ttl = c.take<int32_t>(n);
+    w.chain = c.take<uint32_t>(n);
+    w.key2_a = c.take<uint32_t>(n);
+    w.key2_b = c.take<uint32_t>(n);
+    w.val2_a = c.take<uint32_t>(n);
+    w.val2_b = c.take<uint32_t>(n);
+    w.missord = c.take<uint32_t>(n);
+    w.evict_pair = c.take<uint32_t>(n);
+    w.par = c.take<uint32_t>(n);
+    w.slot_of_pair = c.take<int32_t>(n);
+    w.bytes = c.used();
+    return w;
+}
+
+int check_plan_args(const bp_config* cfg, int64_t N, int32_t T) {
+    BP_TRY(check_config(cfg));
+    if (N < 0 || N >= (int64_t(1) << 31)) return fail(BP_ERR_UNSUPPORTED, "n_lookups %lld outside [0, 2^31)", (long long)N);
+    if (T < 1 || T > kMaxIters) return fail(BP_ERR_UNSUPPORTED, "n_iters %d outside [1, %d]", T, kMaxIters);
+    if (bits_for(cfg->total_rows) + bits_for(T) > 63) return fail(BP_ERR_UNSUPPORTED, "id and batch bits exceed 63");
+    return BP_OK;
+}
+
+inline dim3 grid_for(int64_t n) { return dim3((unsigned)(n > 0 ? ceil_div(n, kBlock) : 1)); }
+
+}  // namespace
+}  // namespace bp
+
+using namespace bp;
+
+BP_EXPORT int bp_oracle_plan_workspace_bytes(const bp_config* cfg, int64_t n_lookups, int32_t n_iters, size_t* bytes) {
+    if (!bytes) return fail(BP_ERR_INVALID_ARG, "bytes is NULL");
+    BP_TRY(check_plan_args(cfg, n_lookups, n_iters));
+    const int Lcap = cfg->lookahead < n_iters ? cfg->lookahead : n_iters;
+    *bytes = carve_plan(nullptr, 0, n_lookups, n_iters, Lcap).bytes;
+    return BP_OK;
+}
+
+BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offsets, int32_t n_iters,
+                              bp_plan* plan, void* workspace, size_t workspace_bytes, void* stream_) {
+    hipStream_t stream = (hipStream_t)stream_;
+    if (!plan || !iter_offsets) return fail(BP_ERR_INVALID_ARG, "plan or iter_offsets is NULL");
+    const int T = n_iters;
+    if (T < 1) return fail(BP_ERR_UNSUPPORTED, "n_iters %d < 1", T);
+    const int64_t N = iter_offsets[T];
+    BP_TRY(check_plan_args(cfg, N, T));
+    if (iter_offsets[0] != 0) return fail(BP_ERR_INVALID_ARG, "iter_offsets[0] != 0");
+    for (int i = 0; i < T; ++i)
+        if (iter_offsets[i + 1] < iter_offsets[i]) return fail(BP_ERR_INVALID_ARG, "iter_offsets decreases at %d", i);
+    if (!plan->prefetch_offsets || !plan->evict_offsets || !plan->keep_offsets || !plan->occupancy)
+        return fail(BP_ERR_INVALID_ARG, "a host output array of the plan is NULL");
+    if (N > 0 && (!ids || !plan->lookup_slots || !plan->prefetch_ids || !plan->prefetch_slots || !plan->evict_ids ||
+                  !plan->evict_slots || !plan->keep_ids || !plan->keep_ttl))
+        return fail(BP_ERR_INVALID_ARG, "a device array of the plan is NULL");
+    if (!workspace || ((uintptr_t)workspace & 255)) return fail(BP_ERR_INVALID_ARG, "workspace NULL or not 256-byte aligned");
+
+    const int Lcap = cfg->lookahead < T ? cfg->lookahead : T;
+    const int64_t C = cfg->capacity;
+    PlanWorkspace w = carve_plan(workspace, workspace_bytes, N, T, Lcap);
+    if (w.bytes > workspace_bytes)
+        return fail(BP_ERR_WORKSPACE_TOO_SMALL, "workspace %zu < required %zu bytes", workspace_bytes, w.bytes);
+
+    plan->L_eff = 0;
+    plan->peak_occupancy = 0;
+    plan->min_capacity = 0;
+    plan->n_unique_pairs = 0;
+    if (N == 0) {   // nothing is ever looked up: empty lists, the full requested lookahead is feasible
+        for (int i = 0; i <= T; ++i) plan->prefetch_offsets[i] = plan->evict_offsets[i] = plan->keep_offsets[i] = 0;
+        for (int i = 0; i < T; ++i) plan->occupancy[i] = 0;
+        plan->L_eff = cfg->lookahead;
+        return BP_OK;
+    }
+
+    const int ib = bits_for(T), gb = bits_for(cfg->total_rows);
+
+    // ---- 1. keys + sort
+    BP_HIP(hipMemcpyAsync(w.iter_off, iter_offsets, sizeof(int64_t) * (T + 1), hipMemcpyHostToDevice, stream));
+    BP_HIP(hipMemsetAsync(w.scalars, 0, sizeof(PlanScalars), stream));
+    BP_LAUNCH(K_PLAN_KEYS, plan_keys_kernel, grid_for(N), dim3(kBlock), 0, stream, ids, (const int64_t*)w.iter_off, T, N,
+              cfg->total_rows, ib, w.keys_a, w.pos_a, w.scalars);
+    bool in_b = false;
+    BP_TRY((radix_sort_pairs<uint64_t, kPlanSortIPT>(w.keys_a, w.keys_b, w.pos_a, w.pos_b, N, 0, ib + gb, w.sort_temp,
+                                                     stream, &in_b)));
+    const uint64_t* skeys = in_b ? w.keys_b : w.keys_a;
+    const uint32_t* spos = in_b ? w.pos_b : w.pos_a;
+    uint64_t* ukey = in_b ? w.keys_a : w.keys_b;   // the other ping-pong buffers are free now
+    uint32_t* uq = in_b ? w.pos_a : w.pos_b;
+
+    // ---- 2. unique pairs
+    BP_TRY((device_scan<uint32_t, AddOp, HeadFlagIn, PairOut>(HeadFlagIn{skeys}, PairOut{skeys, ukey, uq}, N,
+                                                              w.scan_partials32, AddOp(), 0u, stream)));
+    uint32_t M = 0;
+    PlanScalars hs{};
+    BP_HIP(hipMemcpyAsync(&M, w.scan_partials32 + scan_num_tiles(N), sizeof(uint32_t), hipMemcpyDeviceToHost, stream));
+    BP_HIP(hipMemcpyAsync(&hs, w.scalars, sizeof(PlanScalars), hipMemcpyDeviceToHost, stream));
+    BP_HIP(hipStreamSynchronize(stream));
+    if (hs.error_flags & 1u) return fail(BP_ERR_ID_OUT_OF_RANGE, "an id lies outside [0, %lld)", (long long)cfg->total_rows);
+    plan->n_unique_pairs = M;
+    if ((int64_t)M > plan->list_capacity)
+        return fail(BP_ERR_WORKSPACE_TOO_SMALL, "list_capacity %lld < %u unique (id, batch) pairs",
+                    (long long)plan->list_capacity, M);
+
+    // ---- 3. occupancy for every candidate lookahead, L_eff
+    BP_HIP(hipMemsetAsync(w.H, 0, sizeof(uint32_t) * (size_t)(Lcap + 1) * T, stream));
+    BP_HIP(hipMemsetAsync(w.ucount, 0, sizeof(uint32_t) * T, stream));
+    BP_HIP(hipMemsetAsync(w.peak, 0, sizeof(uint32_t) * (Lcap + 2), stream));
+    {
+        int64_t blocks = ceil_div(M, kBlock * 8);
+        if (blocks > 4096) blocks = 4096;
+        BP_LAUNCH(K_PLAN_HIST, plan_hist_kernel, dim3((unsigned)blocks), dim3(kBlock), sizeof(uint32_t) * T, stream,
+                  (const uint64_t*)ukey, M, ib, T, Lcap, w.H, w.ucount);
+    }
+    BP_LAUNCH(K_PLAN_OCC, plan_occ_prefix_kernel, grid_for(Lcap), dim3(kBlock), 0, stream, w.H, T, Lcap);
+    BP_LAUNCH(K_PLAN_OCC, plan_occ_peak_kernel, grid_for(T), dim3(kBlock), 0, stream, (const uint32_t*)w.H,
+              (const uint32_t*)w.ucount, T, Lcap, w.peak);
+    BP_LAUNCH(K_PLAN_OCC, plan_choose_kernel, dim3(1), dim3(64), 0, stream, (const uint32_t*)w.peak,
+              (const uint32_t*)w.ucount, T, Lcap, cfg->lookahead, C, w.scalars, w.pair_off);
+    BP_LAUNCH(K_PLAN_OCC, plan_occ_final_kernel, grid_for(T), dim3(kBlock), 0, stream, (const uint32_t*)w.H,
+              (const uint32_t*)w.ucount, T, (const PlanScalars*)w.scalars, w.occ);
+    BP_HIP(hipMemcpyAsync(&hs, w.scalars, sizeof(PlanScalars), hipMemcpyDeviceToHost, stream));
+    BP_HIP(hipMemcpyAsync(plan->occupancy, w.occ, sizeof(int64_t) * T, hipMemcpyDeviceToHost, stream));
+    BP_HIP(hipStreamSynchronize(stream));
+    plan->min_capacity = hs.min_capacity;
+    if (hs.L_eff < 1)
+        return fail(BP_ERR_CAPACITY, "capacity %lld < %lld unique rows of one batch", (long long)C, (long long)hs.min_capacity);
+    plan->L_eff = hs.L_eff;
+    plan->peak_occupancy = hs.peak;
+
+    // ---- 4. flags, TTL, fetching pair of every pair
+    BP_LAUNCH(K_PLAN_FLAGS, plan_flags_kernel, grid_for(M), dim3(kBlock), 0, stream, (const uint64_t*)ukey, M, ib,
+              (const PlanScalars*)w.scalars, w.flags, w.ttl, w.key2_a, w.val2_a);
+    BP_TRY((device_scan<uint32_t, MaxOp, MissIndexIn, StoreInclusiveU32>(MissIndexIn{w.flags}, StoreInclusiveU32{w.chain},
+                                                                         M, w.scan_partials32, MaxOp(), 0u, stream)));
+
+    // ---- 5. regroup by batch, lists
+    bool ord_in_b = false;
+    BP_TRY((radix_sort_pairs<uint32_t, kPlanSortIPT>(w.key2_a, w.key2_b, w.val2_a, w.val2_b, M, 0, ib, w.sort_temp, stream,
+                                                     &ord_in_b)));
+    const uint32_t* ord = ord_in_b ? w.val2_b : w.val2_a;
+    BP_LAUNCH(K_FILL, fill_kernel<int64_t>, grid_for(T + 1), dim3(kBlock), 0, stream, w.prefetch_off, (int64_t)(T + 1),
+              (int64_t)-1);
+    BP_LAUNCH(K_FILL, fill_kernel<int64_t>, grid_for(T + 1), dim3(kBlock), 0, stream, w.evict_off, (int64_t)(T + 1),
+              (int64_t)-1);
+    BP_TRY((device_scan<uint64_t, AddOp, ListCountIn, ListOut>(
+        ListCountIn{ord, w.flags},
+        ListOut{ord, w.flags, ukey, w.ttl, w.pair_off, ib, plan->keep_ids, plan->keep_ttl, plan->prefetch_ids,
+                plan->evict_ids, w.missord, w.evict_pair, w.prefetch_off, w.evict_off},
+        M, w.scan_partials64, AddOp(), uint64_t(0), stream)));
+    const uint64_t* totals = w.scan_partials64 + scan_num_tiles(M);
+
+    // ---- 6. ring
+    BP_LAUNCH(K_PLAN_JUMP, plan_ring_init_kernel, grid_for(M), dim3(kBlock), 0, stream, totals, C,
+              (const uint32_t*)w.evict_pair, (const uint32_t*)w.chain, (const uint32_t*)w.missord, w.par);
+    const int rounds = bits_for(T) + 1;
+    for (int r = 0; r < rounds; ++r)
+        BP_LAUNCH(K_PLAN_JUMP, plan_ring_jump_kernel, grid_for(M), dim3(kBlock), 0, stream, totals, w.par);
+
+    // ---- 7. slots
+    BP_LAUNCH(K_PLAN_SLOTS, plan_pair_slots_kernel, grid_for(M), dim3(kBlock), 0, stream, M, (const uint32_t*)w.chain,
+              (const uint32_t*)w.missord, (const uint32_t*)w.par, w.slot_of_pair);
+    BP_LAUNCH(K_PLAN_SLOTS, plan_list_slots_kernel, grid_for(M), dim3(kBlock), 0, stream, totals, (const uint32_t*)w.par,
+              (const uint32_t*)w.evict_pair, (const int32_t*)w.slot_of_pair, plan->prefetch_slots, plan->evict_slots);
+    BP_LAUNCH(K_PLAN_SLOTS, plan_lookup_slots_kernel, grid_for(N), dim3(kBlock), 0, stream, N, spos, (const uint32_t*)uq,
+              (const int32_t*)w.slot_of_pair, plan->lookup_slots);
+
+    // ---- CSR offsets to the host
+    uint64_t htot = 0;
+    std::vector<uint32_t> hpair((size_t)T + 1);
+    BP_HIP(hipMemcpyAsync(&htot, totals, sizeof(uint64_t), hipMemcpyDeviceToHost, stream));
+    BP_HIP(hipMemcpyAsync(plan->prefetch_offsets, w.prefetch_off, sizeof(int64_t) * (T + 1), hipMemcpyDeviceToHost, stream));
+    BP_HIP(hipMemcpyAsync(plan->evict_offsets, w.evict_off, sizeof(int64_t) * (T + 1), hipMemcpyDeviceToHost, stream));
+    BP_HIP(hipMemcpyAsync(hpair.data(), w.pair_off, sizeof(uint32_t) * (T + 1), hipMemcpyDeviceToHost, stream));
+    BP_HIP(hipStreamSynchronize(stream));
+    for (int i = 0; i <= T; ++i) plan->keep_offsets[i] = (int64_t)hpair[i];
+    const int64_t n_miss = (int64_t)(uint32_t)htot, n_evict = (int64_t)(htot >> 32);
+    plan->prefetch_offsets[T] = n_miss;
+    plan->evict_offsets[T] = n_evict;
+    for (int i = T - 1; i >= 0; --i) {   // batches without lookups own no pair: their lists are empty
+        if (plan->prefetch_offsets[i] < 0) plan->prefetch_offsets[i] = plan->prefetch_offsets[i + 1];
+        if (plan->evict_offsets[i] < 0) plan->evict_offsets[i] = plan->evict_offsets[i + 1];
+    }
+    if (n_miss != n_evict) return fail(BP_ERR_HIP, "internal: %lld prefetches but %lld evictions", (long long)n_miss, (long long)n_evict);
+    return BP_OK;
+}

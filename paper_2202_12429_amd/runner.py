@@ -1,0 +1,101 @@
+"""Orchestration of the four library calls over a planned trace (no arithmetic here).
+
+    trainer = CachedEmbeddingTrainer(cfg, backing_w, backing_state)      # cache + workspaces in HBM
+    trainer.plan(ids_dev, iter_offsets)                                  # bp_oracle_plan
+    for i in range(T):
+        trainer.maintain(i)                                              # bp_cache_apply(E_{i-1}, P_i)
+        out = trainer.forward(i, bag_offsets_dev)                        # bp_embbag_fwd
+        trainer.backward_update(i, bag_offsets_dev, grad_out)            # bp_embbag_bwd_update
+    trainer.flush()                                                      # bp_cache_apply(E_{T-1}, {})
+
+The order of calls is the synchronous schedule of Section 3.2: the write-backs of batch i-1 are applied before
+the prefetches of batch i, so a row is never fetched while an update to it is still only in the cache.
+"""
+from __future__ import annotations
+
+from typing import Optional
+
+import numpy as np
+
+from . import binding as B
+
+
+def state_shape(rows: int, dim: int, optimizer: int):
+    if optimizer == B.ADAGRAD:
+        return (rows, dim)
+    if optimizer == B.ADAGRAD_ROWWISE:
+        return (rows,)
+    return (0,)
+
+
+class CachedEmbeddingTrainer:
+    def __init__(self, cfg: B.bp_config, backing_w, backing_state=None, device="cuda:0", max_lookups: int = 0,
+                 max_bags: int = 0):
+        import torch
+        self.cfg = cfg
+        self.device = torch.device(device)
+        self.backing_w = backing_w
+        self.backing_state = backing_state
+        wdt = torch.float32 if cfg.weight_dtype == B.F32 else torch.bfloat16
+        C, D = int(cfg.capacity), int(cfg.dim)
+        self.cache_w = torch.zeros((C, D), dtype=wdt, device=self.device)
+        ss = state_shape(C, D, cfg.optimizer)
+        self.cache_state = torch.zeros(ss, dtype=torch.float32, device=self.device) if ss != (0,) else None
+        self.plan_: Optional[B.Plan] = None
+        self.iter_offsets: Optional[np.ndarray] = None
+        self._bwd_ws = None
+        self._out = None
+        if max_lookups:
+            self._reserve(max_lookups, max_bags or max_lookups)
+
+    def _reserve(self, n: int, bags: int):
+        import torch
+        need = B.bp_embbag_bwd_update_workspace_bytes(self.cfg, n, bags)
+        if self._bwd_ws is None or self._bwd_ws.numel() < need:
+            self._bwd_ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        if self._out is None or self._out.shape[0] < bags:
+            self._out = torch.empty((bags, int(self.cfg.dim)), dtype=torch.float32, device=self.device)
+
+    # ---- (1)
+    def plan(self, ids_dev, iter_offsets, list_capacity: Optional[int] = None) -> B.Plan:
+        self.iter_offsets = np.ascontiguousarray(iter_offsets, dtype=np.int64)
+        self.plan_ = B.bp_oracle_plan(self.cfg, ids_dev, self.iter_offsets, list_capacity=list_capacity)
+        return self.plan_
+
+    def _slice(self, which: str, i: int):
+        p = self.plan_
+        off = getattr(p, which + "_offsets")
+        a, b = int(off[i]), int(off[i + 1])
+        return getattr(p, which + "_ids")[a:b], getattr(p, which + "_slots")[a:b]
+
+    def slots(self, i: int):
+        a, b = int(self.iter_offsets[i]), int(self.iter_offsets[i + 1])
+        return self.plan_.lookup_slots[a:b]
+
+    # ---- (2)
+    def maintain(self, i: int, stream=None) -> None:
+        e_ids, e_slots = self._slice("evict", i - 1) if i > 0 else (None, None)
+        p_ids, p_slots = self._slice("prefetch", i)
+        B.bp_cache_apply(self.cfg, self.cache_w, self.cache_state, self.backing_w, self.backing_state, e_ids, e_slots,
+                         p_ids, p_slots, stream=stream)
+
+    def flush(self, stream=None) -> None:
+        T = self.iter_offsets.shape[0] - 1
+        e_ids, e_slots = self._slice("evict", T - 1)
+        B.bp_cache_apply(self.cfg, self.cache_w, self.cache_state, self.backing_w, self.backing_state, e_ids, e_slots,
+                         None, None, stream=stream)
+
+    # ---- (3)
+    def forward(self, i: int, bag_offsets_dev, bags: int, out=None, stream=None):
+        sl = self.slots(i)
+        self._reserve(int(sl.numel()), bags)
+        out = self._out[:bags] if out is None else out
+        B.bp_embbag_fwd(self.cfg, self.cache_w, sl, bag_offsets_dev, bags, out, stream=stream)
+        return out
+
+    # ---- (4)
+    def backward_update(self, i: int, bag_offsets_dev, bags: int, grad_out, stream=None) -> None:
+        sl = self.slots(i)
+        self._reserve(int(sl.numel()), bags)
+        B.bp_embbag_bwd_update(self.cfg, self.cache_w, self.cache_state, sl, bag_offsets_dev, bags, grad_out,
+                               self._bwd_ws, stream=stream)

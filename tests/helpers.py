@@ -1,0 +1,143 @@
+"""Shared test drivers: the oracle's uncached / cached training loops and the GPU loop through the C ABI."""
+import numpy as np
+import torch
+
+import oracle
+import workloads
+
+
+def table_to_numpy(cfg, w_f32: torch.Tensor) -> np.ndarray:
+    """fp32 tensor -> the oracle's storage array (fp32, or bf16 bit patterns as uint16)."""
+    if cfg.weight_dtype == "bf16":
+        return w_f32.to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16).copy()
+    return w_f32.numpy().copy()
+
+
+def oracle_codes(cfg):
+    return oracle.DTYPES[cfg.weight_dtype], oracle.OPTIMIZERS[cfg.optimizer]
+
+
+def oracle_uncached(cfg, trace, T=None, keep_outputs=True):
+    """Oracle part B: synchronous training on the full table.  Returns (W, S, [out_i])."""
+    T = trace.iter_offsets.shape[0] - 1 if T is None else T
+    R, D = cfg.total_rows, cfg.dim
+    dt, op = oracle_codes(cfg)
+    W = table_to_numpy(cfg, workloads.init_weights(cfg, 0, R))
+    S = np.zeros(oracle.state_shape(R, D, op), dtype=np.float32)
+    outs = []
+    bags = trace.bag_offsets.shape[1] - 1
+    for i in range(T):
+        g = workloads.upstream_grad(cfg, i, bags).numpy()
+        o = oracle.train_iter(W, S, D, dt, op, cfg.lr, cfg.eps, trace.iter_ids(i), trace.bag_offsets[i], g)
+        if keep_outputs:
+            outs.append(o)
+    return W, S, outs
+
+
+def oracle_cached(cfg, trace, plan, T=None):
+    """Oracle part C: the same arithmetic through the plan and a cache array with write-backs."""
+    T = trace.iter_offsets.shape[0] - 1 if T is None else T
+    R, D, C = cfg.total_rows, cfg.dim, cfg.capacity
+    dt, op = oracle_codes(cfg)
+    W = table_to_numpy(cfg, workloads.init_weights(cfg, 0, R))
+    S = np.zeros(oracle.state_shape(R, D, op), dtype=np.float32)
+    cw = np.full((C, D), 0x7FC0 if dt == oracle.BF16 else np.nan, dtype=W.dtype)     # poison unfetched slots
+    cs = np.full(oracle.state_shape(C, D, op), np.nan, dtype=np.float32)
+    outs = []
+    e_ids, e_slots = np.zeros(0, np.int64), np.zeros(0, np.int32)
+    bags = trace.bag_offsets.shape[1] - 1
+    for i in range(T):
+        a, b = plan.prefetch_off[i], plan.prefetch_off[i + 1]
+        oracle.cache_apply(cw, cs, W, S, D, dt, op, e_ids, e_slots, plan.prefetch_ids[a:b], plan.prefetch_slots[a:b])
+        g = workloads.upstream_grad(cfg, i, bags).numpy()
+        sl = plan.lookup_slots[trace.iter_offsets[i]:trace.iter_offsets[i + 1]]
+        outs.append(oracle.train_iter(cw, cs, D, dt, op, cfg.lr, cfg.eps, sl, trace.bag_offsets[i], g))
+        a, b = plan.evict_off[i], plan.evict_off[i + 1]
+        e_ids, e_slots = plan.evict_ids[a:b], plan.evict_slots[a:b]
+    oracle.cache_apply(cw, cs, W, S, D, dt, op, e_ids, e_slots, np.zeros(0, np.int64), np.zeros(0, np.int32))
+    return W, S, outs
+
+
+# ---------------------------------------------------------------------------------------------------
+# GPU side (imports the product package lazily so that CPU-only test runs never need it)
+# ---------------------------------------------------------------------------------------------------
+def bp_config_of(cfg, capacity=None):
+    import paper_2202_12429_amd as bp
+    return bp.make_config(cfg.total_rows, cfg.capacity if capacity is None else capacity, cfg.dim, cfg.weight_dtype,
+                          cfg.optimizer, cfg.lookahead, cfg.lr, cfg.eps)
+
+
+def make_backing(cfg, pinned=True, chunk_rows=1 << 20):
+    """Backing table (+ optimizer state) filled with the hash-defined initial weights.  Pinned host memory
+    stands in for the embedding servers; pinned=False keeps it in HBM."""
+    from paper_2202_12429_amd.runner import state_shape
+    import paper_2202_12429_amd as bp
+    R, D = cfg.total_rows, cfg.dim
+    wdt = torch.bfloat16 if cfg.weight_dtype == "bf16" else torch.float32
+    kw = dict(pin_memory=True) if pinned else dict(device="cuda:0")
+    W = torch.empty((R, D), dtype=wdt, **kw)
+    for a in range(0, R, chunk_rows):
+        b = min(R, a + chunk_rows)
+        W[a:b].copy_(workloads.init_weights(cfg, a, b, device="cuda:0").to(wdt))
+    ss = state_shape(R, D, {"sgd": bp.SGD, "adagrad": bp.ADAGRAD, "adagrad_rowwise": bp.ADAGRAD_ROWWISE}[cfg.optimizer])
+    S = torch.zeros(ss, dtype=torch.float32, **kw) if ss != (0,) else None
+    torch.cuda.synchronize()
+    return W, S
+
+
+def gpu_cached_training(cfg, trace, T=None, pinned=True, capacity=None, check_outputs=None):
+    """Runs plan + T iterations of cache_apply / fwd / bwd_update + flush through the C ABI.
+    check_outputs(i, out_tensor) is called after every forward.  Returns (trainer, plan, W, S)."""
+    from paper_2202_12429_amd.runner import CachedEmbeddingTrainer
+    T = trace.iter_offsets.shape[0] - 1 if T is None else T
+    bcfg = bp_config_of(cfg, capacity)
+    W, S = make_backing(cfg, pinned)
+    tr = CachedEmbeddingTrainer(bcfg, W, S)
+    ids_dev = torch.from_numpy(trace.ids[:trace.iter_offsets[T]]).cuda()
+    plan = tr.plan(ids_dev, trace.iter_offsets[:T + 1])
+    bags = trace.bag_offsets.shape[1] - 1
+    for i in range(T):
+        bo = None if cfg.one_hot else torch.from_numpy(np.ascontiguousarray(trace.bag_offsets[i])).cuda()
+        tr.maintain(i)
+        out = tr.forward(i, bo, bags)
+        if check_outputs is not None:
+            check_outputs(i, out)
+        g = workloads.upstream_grad(cfg, i, bags, device="cuda:0")
+        tr.backward_update(i, bo, bags, g)
+    tr.flush()
+    torch.cuda.synchronize()
+    return tr, plan, W, S
+
+
+def table_from_torch(cfg, W: torch.Tensor) -> np.ndarray:
+    W = W.cpu()
+    if cfg.weight_dtype == "bf16":
+        return W.view(torch.int16).numpy().view(np.uint16)
+    return W.numpy()
+
+
+def bf16_bits_to_f32(a: np.ndarray) -> np.ndarray:
+    return (a.astype(np.uint32) << 16).view(np.float32)
+
+
+def assert_outputs_close(got: np.ndarray, want: np.ndarray, max_bag: int, wmax: float = 0.06):
+    """Pooled outputs: relative 1e-5, with an absolute floor for sums that cancel.  The fp32 path adds up to
+    max_bag values of magnitude <= wmax in order; its error is bounded by max_bag * 2^-24 * sum|x|, so
+    against the fp64-accumulated oracle |a-b| <= 1e-5*|b| + 1e-5*wmax*sqrt(max_bag) holds with a wide margin,
+    and one-hot outputs (a row copy) must match bit for bit."""
+    if max_bag == 1:
+        assert np.array_equal(got, want)
+        return
+    tol = 1e-5 * np.abs(want) + 1e-5 * wmax * np.sqrt(max_bag)
+    bad = np.abs(got - want) > tol
+    assert not bad.any(), f"{bad.sum()} outputs off, worst {np.abs(got - want).max()}"
+    assert np.abs(got - want).max() <= 1e-5 * np.abs(want).max()          # norm-wise relative error
+
+
+def assert_weights_close(got: np.ndarray, want: np.ndarray):
+    """Final table: |a-b| <= 1e-4 * max(|b|, 1e-2) element-wise."""
+    tol = 1e-4 * np.maximum(np.abs(want), 1e-2)
+    diff = np.abs(got.astype(np.float64) - want.astype(np.float64))
+    bad = diff > tol
+    assert not bad.any(), f"{bad.sum()} weights off, worst {diff.max()} at {np.unravel_index(diff.argmax(), diff.shape)}"
+    return float((diff / np.maximum(np.abs(want), 1e-2)).max())
