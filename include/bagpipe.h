@@ -147,7 +147,8 @@ int bp_embbag_fwd(const bp_config* cfg, const void* cache_w, const int32_t* look
 /* ------------------------------------------------------------------------------------------------
  * (4) Backward + update, deterministic (bit-identical from run to run): lookups are grouped by slot with
  * a stable radix sort, G[slot, :] = sum of grad_out[bag(k), :] over the slot's lookups is formed in a
- * fixed order in fp32, and each distinct slot is updated once, in place:
+ * fixed order with fp64 accumulators and rounded once to fp32, and each distinct slot is updated once,
+ * in place, in fp32 arithmetic (one rounding per operation, no fused multiply-add):
  *   BP_SGD              w -= lr * G
  *   BP_ADAGRAD          s += G*G;              w -= lr * G / (sqrt(s) + eps)
  *   BP_ADAGRAD_ROWWISE  s_row += mean_d G_d^2; w -= lr * G / (sqrt(s_row) + eps)

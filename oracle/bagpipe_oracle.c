@@ -19,8 +19,10 @@
  *      Section 5, paragraph "Metrics", and Section 5.1 "Convergence Comparison", makes this the definition of the right answer).
  *   C. the same arithmetic routed through the plan and a cache array with write-backs.
  *
- * Floating point: rows are stored in their storage type (fp32, or bf16 with round-to-nearest-even);
- * every sum and every update is carried out in fp64 and rounded once on store.
+ * Floating point: rows are stored in their storage type (fp32, or bf16 with round-to-nearest-even).
+ * Every sum is carried out in fp64.  With fp32 storage the update is carried out in fp64 too and rounded
+ * once on store; with bf16 storage the stored value is a quantised code and the update is carried out in
+ * fp32, the arithmetic type fixed for that workload (see update_row_bf16).
  * Parity pins: tests/test_oracle_*.py (paper's worked example, brute force from the plain
  * definitions, invariants, torch CPU library routines).  Row-wise Adagrad is pinned only by a
  * closed form on one row and by its equality with element-wise Adagrad at D = 1: parity unpinned
@@ -234,6 +236,71 @@ static inline void store_w(void *tab, int dtype, int64_t row, int64_t D, int64_t
     else ((uint16_t *)tab)[row * D + d] = f32_to_bf16((float)v);
 }
 
+/*
+ * Optimizer step on one row, fp32 storage: the plain rules in fp64, each stored value rounded once.
+ * G[d] is the fp64 sum of the row's gradients.
+ */
+static int update_row_f64(float *table, float *state, int64_t row, int64_t D, int optimizer, float lr, float eps,
+                          const double *G) {
+    const double lrd = (double)lr, epsd = (double)eps;
+    float *w = table + row * D;
+    if (optimizer == ORC_SGD) {
+        for (int64_t d = 0; d < D; ++d) w[d] = (float)((double)w[d] - lrd * G[d]);
+    } else if (optimizer == ORC_ADAGRAD) {
+        for (int64_t d = 0; d < D; ++d) {
+            float s = (float)((double)state[row * D + d] + G[d] * G[d]);
+            state[row * D + d] = s;
+            w[d] = (float)((double)w[d] - lrd * G[d] / (sqrt((double)s) + epsd));
+        }
+    } else if (optimizer == ORC_ADAGRAD_ROWWISE) {
+        double ms = 0.0;
+        for (int64_t d = 0; d < D; ++d) ms += G[d] * G[d];
+        float s = (float)((double)state[row] + ms / (double)D);
+        state[row] = s;
+        double den = sqrt((double)s) + epsd;
+        for (int64_t d = 0; d < D; ++d) w[d] = (float)((double)w[d] - lrd * G[d] / den);
+    } else return ORC_ERR_ARG;
+    return ORC_OK;
+}
+
+/*
+ * Optimizer step on one row, bf16 storage.  The stored value is a quantised code, so the value that gets
+ * rounded to bf16 must be formed in the arithmetic type the workload fixes for this case, fp32
+ * ("bf16 storage, fp32 accumulation / optimizer"): sums (the gradient sum, the row-wise mean of squares)
+ * are taken in fp64 and rounded once to fp32, which makes them independent of the order of addition;
+ * every element-wise operation is one correctly rounded fp32 operation, written out one per line.
+ */
+static int update_row_bf16(uint16_t *table, float *state, int64_t row, int64_t D, int optimizer, float lr,
+                           float eps, const double *G) {
+    uint16_t *w = table + row * D;
+    float den_row = 0.0f;
+    if (optimizer == ORC_ADAGRAD_ROWWISE) {
+        double ms = 0.0;
+        for (int64_t d = 0; d < D; ++d) { float g = (float)G[d]; ms += (double)g * (double)g; }
+        float mean = (float)(ms / (double)D);
+        float s = state[row] + mean;
+        state[row] = s;
+        den_row = sqrtf(s) + eps;
+    } else if (optimizer != ORC_SGD && optimizer != ORC_ADAGRAD) return ORC_ERR_ARG;
+    for (int64_t d = 0; d < D; ++d) {
+        float g = (float)G[d];
+        float wv = bf16_to_f32(w[d]);
+        float step = lr * g;
+        if (optimizer == ORC_ADAGRAD) {
+            float gg = g * g;
+            float s = state[row * D + d] + gg;
+            state[row * D + d] = s;
+            float den = sqrtf(s) + eps;
+            step = step / den;
+        } else if (optimizer == ORC_ADAGRAD_ROWWISE) {
+            step = step / den_row;
+        }
+        float wn = wv - step;
+        w[d] = f32_to_bf16(wn);
+    }
+    return ORC_OK;
+}
+
 typedef struct { int64_t row; int64_t pos; } rowpos_t;
 static int cmp_rowpos(const void *a, const void *b) {
     const rowpos_t *x = (const rowpos_t *)a, *y = (const rowpos_t *)b;
@@ -275,7 +342,6 @@ int orc_train_iter(void *table, float *state, int64_t rows, int64_t D, int dtype
         for (int64_t k = bag_off[b]; k < bag_off[b + 1]; ++k) bag_of[k] = b;
     for (int64_t k = 0; k < n; ++k) { rp[k].row = row_idx[k]; rp[k].pos = k; }
     qsort(rp, (size_t)n, sizeof(rowpos_t), cmp_rowpos);
-    const double lrd = (double)lr, epsd = (double)eps;
     for (int64_t a = 0; a < n;) {
         int64_t b = a, row = rp[a].row;
         for (int64_t d = 0; d < D; ++d) G[d] = 0.0;
@@ -283,25 +349,9 @@ int orc_train_iter(void *table, float *state, int64_t rows, int64_t D, int dtype
             const float *g = grad_out + bag_of[rp[b].pos] * D;
             for (int64_t d = 0; d < D; ++d) G[d] += (double)g[d];
         }
-        if (optimizer == ORC_SGD) {
-            for (int64_t d = 0; d < D; ++d)
-                store_w(table, dtype, row, D, d, load_w(table, dtype, row, D, d) - lrd * G[d]);
-        } else if (optimizer == ORC_ADAGRAD) {
-            for (int64_t d = 0; d < D; ++d) {
-                float s = (float)((double)state[row * D + d] + G[d] * G[d]);
-                state[row * D + d] = s;
-                store_w(table, dtype, row, D, d,
-                        load_w(table, dtype, row, D, d) - lrd * G[d] / (sqrt((double)s) + epsd));
-            }
-        } else if (optimizer == ORC_ADAGRAD_ROWWISE) {
-            double ms = 0.0;
-            for (int64_t d = 0; d < D; ++d) ms += G[d] * G[d];
-            float s = (float)((double)state[row] + ms / (double)D);
-            state[row] = s;
-            double den = sqrt((double)s) + epsd;
-            for (int64_t d = 0; d < D; ++d)
-                store_w(table, dtype, row, D, d, load_w(table, dtype, row, D, d) - lrd * G[d] / den);
-        } else { free(rp); free(bag_of); free(G); return ORC_ERR_ARG; }
+        int rc = dtype == ORC_F32 ? update_row_f64((float *)table, state, row, D, optimizer, lr, eps, G)
+                                  : update_row_bf16((uint16_t *)table, state, row, D, optimizer, lr, eps, G);
+        if (rc != ORC_OK) { free(rp); free(bag_of); free(G); return rc; }
         a = b;
     }
     free(rp); free(bag_of); free(G);

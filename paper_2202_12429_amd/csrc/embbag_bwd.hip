@@ -8,12 +8,13 @@
 //   2. the sorted array is cut into work items: a new item starts at every change of slot and at every
 //      multiple of kChunk positions (so a slot hit thousands of times by a skewed batch is shared by
 //      many lane groups); item starts are compacted with a scan.
-//   3. one lane group per item adds its gradient rows in order (fp32).  An item that covers its whole
+//   3. one lane group per item adds its gradient rows in order (fp64 accumulators).  An item that covers its whole
 //      slot applies the update at once; otherwise the sum goes to a partial row addressed by the chunk
 //      boundary it touches.
 //   4. for slots split over several items, the group of the first item adds the partial rows in order
 //      and applies the update.
 // Every order of addition is fixed by the data, never by timing: results are bit-identical run to run.
+// The summed gradient is rounded to fp32 once; the optimizer step itself is fp32 arithmetic.
 #include "common.h"
 #include "device_prims.h"
 #include "row_access.h"
@@ -61,20 +62,64 @@ struct ItemStartOut {
 // ---- 3./4. reduce and update -----------------------------------------------------------------
 struct UpdateParams {
     int optimizer;
-    float lr, eps, inv_dim;
+    float lr, eps;
     int lpr;
     int dim;
 };
 
+// Running sum of one 16-byte piece of gradient rows.  Sums are carried in fp64 and rounded to fp32 once,
+// which makes the result independent of how a slot's lookups were cut into items (fp64 addition of
+// fp32 values is exact until the partial sums outgrow 53 bits); everything after the sum is fp32.
+template <int N>
+struct SumPiece {
+    double v[N];
+    __device__ __forceinline__ void zero() {
+#pragma unroll
+        for (int i = 0; i < N; ++i) v[i] = 0.0;
+    }
+    template <bool BF16>
+    __device__ __forceinline__ void add(const Piece<BF16>& p) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) v[i] += (double)p.v[i];
+    }
+    __device__ __forceinline__ void add(const SumPiece& o) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) v[i] += o.v[i];
+    }
+    // fp64 [.. D] partial rows: the piece of lane c starts at element c * N
+    __device__ __forceinline__ void load(const double* row, int c) {
+        const double2* p = reinterpret_cast<const double2*>(row + (size_t)c * N);
+#pragma unroll
+        for (int i = 0; i < N / 2; ++i) {
+            const double2 t = p[i];
+            v[2 * i] = t.x; v[2 * i + 1] = t.y;
+        }
+    }
+    __device__ __forceinline__ void store(double* row, int c) const {
+        double2* p = reinterpret_cast<double2*>(row + (size_t)c * N);
+#pragma unroll
+        for (int i = 0; i < N / 2; ++i) p[i] = make_double2(v[2 * i], v[2 * i + 1]);
+    }
+    template <bool BF16>
+    __device__ __forceinline__ Piece<BF16> rounded() const {
+        Piece<BF16> p;
+#pragma unroll
+        for (int i = 0; i < N; ++i) p.v[i] = (float)v[i];
+        return p;
+    }
+};
+
 template <int GW>
-__device__ __forceinline__ float group_sum(float x) {
+__device__ __forceinline__ double group_sum(double x) {
 #pragma unroll
     for (int off = GW / 2; off >= 1; off >>= 1) x += __shfl_xor(x, off, GW);
     return x;
 }
 
-// Applies one optimizer step to the piece of lane c of row `slot`.  All lanes of the group call this
-// (the row-wise rule reduces over the group); lanes with c >= lpr carry zeros and touch no memory.
+// Applies one optimizer step to the piece of lane c of row `slot`; g is the row's summed gradient in fp32.
+// All lanes of the group call this (the row-wise rule reduces over the group); lanes with c >= lpr carry
+// zeros and touch no memory.  One fp32 operation per statement: step = lr*g, then for Adagrad
+// s += g*g, den = sqrt(s) + eps, step /= den, and w -= step.
 template <int GW, bool BF16>
 __device__ __forceinline__ void apply_update(const UpdateParams& u, uint4* cache_w, float* cache_s, int64_t slot, int c,
                                              const Piece<BF16>& g) {
@@ -85,27 +130,37 @@ __device__ __forceinline__ void apply_update(const UpdateParams& u, uint4* cache
     if (active) w.decode(cache_w[slot * u.lpr + c]);
     if (u.optimizer == BP_SGD) {
 #pragma unroll
-        for (int i = 0; i < N; ++i) w.v[i] -= u.lr * g.v[i];
+        for (int i = 0; i < N; ++i) {
+            const float step = u.lr * g.v[i];
+            w.v[i] = w.v[i] - step;
+        }
     } else if (u.optimizer == BP_ADAGRAD) {
         if (active) {
             Piece<BF16> s;
             s.load_f32(cache_s + slot * u.dim, c);
 #pragma unroll
             for (int i = 0; i < N; ++i) {
-                s.v[i] += g.v[i] * g.v[i];
-                w.v[i] -= u.lr * g.v[i] / (sqrtf(s.v[i]) + u.eps);
+                const float gg = g.v[i] * g.v[i];
+                s.v[i] = s.v[i] + gg;
+                const float den = sqrtf(s.v[i]) + u.eps;
+                const float step = (u.lr * g.v[i]) / den;
+                w.v[i] = w.v[i] - step;
             }
             s.store_f32(cache_s + slot * u.dim, c);
         }
     } else {
-        float ss = 0.f;
+        double ss = 0.0;                       // mean of squares over the row: an fp64 sum, rounded once
 #pragma unroll
-        for (int i = 0; i < N; ++i) ss += g.v[i] * g.v[i];
+        for (int i = 0; i < N; ++i) ss += (double)g.v[i] * (double)g.v[i];
         ss = group_sum<GW>(ss);
-        const float s = cache_s[slot] + ss * u.inv_dim;
+        const float mean = (float)(ss / (double)u.dim);
+        const float s = cache_s[slot] + mean;
         const float den = sqrtf(s) + u.eps;
 #pragma unroll
-        for (int i = 0; i < N; ++i) w.v[i] -= u.lr * g.v[i] / den;
+        for (int i = 0; i < N; ++i) {
+            const float step = (u.lr * g.v[i]) / den;
+            w.v[i] = w.v[i] - step;
+        }
         if (c == 0) cache_s[slot] = s;
     }
     if (active) cache_w[slot * u.lpr + c] = w.encode();
@@ -117,8 +172,9 @@ __global__ __launch_bounds__(kRowBlock) void bwd_reduce_update_kernel(const uint
                                                                      const uint32_t* __restrict__ item_start,
                                                                      const uint32_t* __restrict__ n_items_ptr, uint32_t n,
                                                                      int64_t C, const float* __restrict__ grad,
-                                                                     uint4* cache_w, float* cache_s, float* partial,
+                                                                     uint4* cache_w, float* cache_s, double* partial,
                                                                      UpdateParams u) {
+    constexpr int N = Piece<BF16>::N;
     const uint32_t W = *n_items_ptr;
     const int c = threadIdx.x % GW;
     const bool active = c < u.lpr;
@@ -130,7 +186,7 @@ __global__ __launch_bounds__(kRowBlock) void bwd_reduce_update_kernel(const uint
         if ((int64_t)slot >= C) continue;            // sentinel of out-of-range slots
         const bool head = start == 0 || keys[start - 1] != slot;
         const bool tail = end == n || keys[end] != slot;
-        Piece<BF16> acc;
+        SumPiece<N> acc;
         acc.zero();
         if (active) {
             uint32_t p = start;
@@ -148,12 +204,12 @@ __global__ __launch_bounds__(kRowBlock) void bwd_reduce_update_kernel(const uint
             }
         }
         if (head && tail) {
-            apply_update<GW, BF16>(u, cache_w, cache_s, (int64_t)slot, c, acc);
+            apply_update<GW, BF16>(u, cache_w, cache_s, (int64_t)slot, c, acc.template rounded<BF16>());
         } else if (active) {
             // head item of a split slot ends on a chunk boundary b*kChunk: row 2b; a later item starts on
             // boundary b*kChunk: row 2b+1
             const size_t row = head ? 2 * (size_t)(end / kChunk) : 2 * (size_t)(start / kChunk) + 1;
-            acc.store_f32(partial + row * u.dim, c);
+            acc.store(partial + row * u.dim, c);
         }
     }
 }
@@ -163,7 +219,8 @@ __global__ __launch_bounds__(kRowBlock) void bwd_combine_update_kernel(const uin
                                                                       const uint32_t* __restrict__ item_start,
                                                                       const uint32_t* __restrict__ n_items_ptr, uint32_t n,
                                                                       int64_t C, uint4* cache_w, float* cache_s,
-                                                                      const float* __restrict__ partial, UpdateParams u) {
+                                                                      const double* __restrict__ partial, UpdateParams u) {
+    constexpr int N = Piece<BF16>::N;
     const uint32_t W = *n_items_ptr;
     const int c = threadIdx.x % GW;
     const bool active = c < u.lpr;
@@ -176,21 +233,21 @@ __global__ __launch_bounds__(kRowBlock) void bwd_combine_update_kernel(const uin
         const bool head = start == 0 || keys[start - 1] != slot;
         const bool tail = end == n || keys[end] != slot;
         if (!head || tail) continue;                  // only the first item of a split slot works here
-        Piece<BF16> acc;
+        SumPiece<N> acc;
         acc.zero();
         uint32_t b = end / kChunk;                    // end is a chunk boundary because the slot goes on
-        if (active) acc.load_f32(partial + 2 * (size_t)b * u.dim, c);
+        if (active) acc.load(partial + 2 * (size_t)b * u.dim, c);
         for (;;) {                                    // items starting at boundaries b, b+1, ... of this slot
             if (active) {
-                Piece<BF16> t;
-                t.load_f32(partial + (2 * (size_t)b + 1) * u.dim, c);
+                SumPiece<N> t;
+                t.load(partial + (2 * (size_t)b + 1) * u.dim, c);
                 acc.add(t);
             }
             const uint64_t next = (uint64_t)(b + 1) * kChunk;
             if (next >= n || keys[next] != slot) break;
             ++b;
         }
-        apply_update<GW, BF16>(u, cache_w, cache_s, (int64_t)slot, c, acc);
+        apply_update<GW, BF16>(u, cache_w, cache_s, (int64_t)slot, c, acc.template rounded<BF16>());
     }
 }
 
@@ -200,7 +257,7 @@ constexpr int64_t kLargeSort = int64_t(1) << 21;
 
 struct BwdWorkspace {
     uint32_t *keys_a, *keys_b, *vals_a, *vals_b, *sort_temp, *item_start, *scan_partials;
-    float* partial;
+    double* partial;
     size_t bytes;
 };
 
@@ -215,7 +272,7 @@ BwdWorkspace carve_bwd(void* base, size_t cap, int64_t n, int dim) {
     w.sort_temp = c.take<uint32_t>(n >= kLargeSort ? sort_temp_words<kLargeIPT>(n) : sort_temp_words<kSmallIPT>(n));
     w.item_start = c.take<uint32_t>(m + 1);
     w.scan_partials = c.take<uint32_t>(scan_partials(n));
-    w.partial = c.take<float>((2 * (m / kChunk + 2)) * (size_t)dim);
+    w.partial = c.take<double>((2 * (m / kChunk + 2)) * (size_t)dim);
     w.bytes = c.used();
     return w;
 }
@@ -232,7 +289,7 @@ struct BwdLaunch {
     hipStream_t stream;
     template <int GW, bool BF16>
     int run() {
-        UpdateParams u{cfg->optimizer, cfg->lr, cfg->eps, 1.0f / (float)cfg->dim, (int)(row_bytes(cfg) / 16), cfg->dim};
+        UpdateParams u{cfg->optimizer, cfg->lr, cfg->eps, (int)(row_bytes(cfg) / 16), cfg->dim};
         const int groups_per_block = kRowBlock / GW;
         int64_t blocks = ceil_div(n, groups_per_block);
         if (blocks > kMaxGridBlocks) blocks = kMaxGridBlocks;
@@ -241,7 +298,7 @@ struct BwdLaunch {
                   (float*)cache_s, w->partial, u);
         BP_LAUNCH(K_BWD_COMBINE_UPDATE, (bwd_combine_update_kernel<GW, BF16>), dim3((unsigned)blocks), dim3(kRowBlock), 0,
                   stream, skeys, (const uint32_t*)w->item_start, n_items, (uint32_t)n, cfg->capacity, (uint4*)cache_w,
-                  (float*)cache_s, (const float*)w->partial, u);
+                  (float*)cache_s, (const double*)w->partial, u);
         return BP_OK;
     }
 };

@@ -120,12 +120,13 @@ def bf16_bits_to_f32(a: np.ndarray) -> np.ndarray:
     return (a.astype(np.uint32) << 16).view(np.float32)
 
 
-def assert_outputs_close(got: np.ndarray, want: np.ndarray, max_bag: int, wmax: float = 0.06):
+def assert_outputs_close(got: np.ndarray, want: np.ndarray, max_bag: int, wmax: float = 0.06, same_table=True):
     """Pooled outputs: relative 1e-5, with an absolute floor for sums that cancel.  The fp32 path adds up to
     max_bag values of magnitude <= wmax in order; its error is bounded by max_bag * 2^-24 * sum|x|, so
     against the fp64-accumulated oracle |a-b| <= 1e-5*|b| + 1e-5*wmax*sqrt(max_bag) holds with a wide margin,
-    and one-hot outputs (a row copy) must match bit for bit."""
-    if max_bag == 1:
+    and one-hot outputs (a row copy) must match bit for bit when both sides read the same table
+    (same_table=False: the tables went through earlier updates and already differ by rounding)."""
+    if max_bag == 1 and same_table:
         assert np.array_equal(got, want)
         return
     tol = 1e-5 * np.abs(want) + 1e-5 * wmax * np.sqrt(max_bag)

@@ -143,19 +143,16 @@ def test_backward_update(bp, D, dtype, optimizer, max_len):
     want_s = None if state is None else state.copy()
     oracle.train_iter(want_w, want_s, D, oracle.DTYPES[dtype], op, 0.01, 1e-8, slots, off, grad, want_out=False)
     if dtype == "bf16":
-        # storage rounding decides a bf16 code: both sides round an fp32 value to nearest-even, and those fp32
-        # values differ by fp32 rounding noise only, so codes may differ by one unit in the last place on the few
-        # elements that sit next to a rounding boundary
-        g = helpers.bf16_bits_to_f32(cache_numpy(got_w))
-        wv = helpers.bf16_bits_to_f32(want_w)
-        ulp = np.maximum(np.abs(wv), 2.0 ** -126) * 2.0 ** -7
-        assert (np.abs(g - wv) <= ulp).all()
-        assert (g != wv).mean() < 2e-3
+        # storage rounding decides a bf16 code, so both sides form the value to be rounded the same way (fp64 sums
+        # rounded once, fp32 element-wise steps): the codes and the fp32 state must agree bit for bit
+        assert np.array_equal(cache_numpy(got_w), want_w)
+        if want_s is not None:
+            assert np.array_equal(got_s, want_s)
     else:
         helpers.assert_weights_close(got_w.numpy(), want_w)
         assert np.abs(got_w.numpy() - w.numpy()).max() > 1e-4
     if want_s is not None:
-        np.testing.assert_allclose(got_s, want_s, rtol=2e-6, atol=1e-12)
+        np.testing.assert_allclose(got_s, want_s, rtol=1e-4, atol=1e-9)     # same bar as the weights
         assert np.array_equal(again_s, got_s)
     # untouched rows keep their bits
     touched = np.zeros(C, bool)
@@ -295,7 +292,7 @@ def test_plan_medium_multi_tile(bp):
     tr = workloads.make_trace(cfg)
     uniq, uoff = oracle.unique_per_iter(tr.ids, tr.iter_offsets, cfg.total_rows)
     umax = int(np.diff(uoff).max())
-    got, want = plan_both(bp, tr.ids, tr.iter_offsets, cfg.total_rows, 40, umax * 4)
+    got, want = plan_both(bp, tr.ids, tr.iter_offsets, cfg.total_rows, 40, umax * 2)
     assert 1 < got.L_eff < 40
     plan_both(bp, tr.ids, tr.iter_offsets, cfg.total_rows, 40, umax)            # barely feasible: L_eff = 1
     plan_both(bp, tr.ids, tr.iter_offsets, cfg.total_rows, 60, 10 ** 6)         # lookahead beyond the trace
@@ -329,7 +326,7 @@ def run_end_to_end(cfg, trace, pinned=True, capacity=None):
     max_bag = cfg.bag_max
 
     def check(i, out):
-        helpers.assert_outputs_close(out.cpu().numpy(), outs[i], max_bag)
+        helpers.assert_outputs_close(out.cpu().numpy(), outs[i], max_bag, same_table=(i == 0))
 
     tr, plan, W, S = helpers.gpu_cached_training(cfg, trace, pinned=pinned, capacity=capacity, check_outputs=check)
     C = cfg.capacity if capacity is None else capacity
@@ -337,12 +334,7 @@ def run_end_to_end(cfg, trace, pinned=True, capacity=None):
     assert_plan_equal(plan, want_plan, trace.n_lookups)
     got = helpers.table_from_torch(cfg, W)
     if cfg.weight_dtype == "bf16":
-        g, w = helpers.bf16_bits_to_f32(got), helpers.bf16_bits_to_f32(Wo)
-        # bf16 codes: at most a few units in the last place after T updates; bound 1e-4 relative does not apply
-        # to an 8-bit mantissa, so compare in units of the last place
-        ulp = np.maximum(np.abs(w), 2.0 ** -126) * 2.0 ** -7
-        assert (np.abs(g - w) <= 4 * ulp).all()
-        assert (g != w).mean() < 0.01
+        assert np.array_equal(got, Wo), "bf16 codes of the final table must match bit for bit"
     else:
         worst = helpers.assert_weights_close(got, Wo)
         say(f"  worst weight error {worst:.3g} of the 1e-4 bound")

@@ -133,9 +133,20 @@ def test_bf16_storage_rounds_to_nearest_even():
     off = np.arange(65, dtype=np.int64)
     out = oracle.train_iter(table, None, 8, oracle.BF16, oracle.SGD, 0.01, 0.0, idx, off, g)
     assert np.array_equal(out, wb.float().numpy())                   # exact up-conversion
-    lr = np.float64(np.float32(0.01))
-    want = torch.from_numpy((wb.double().numpy() - lr * g.astype(np.float64)).astype(np.float32)).to(torch.bfloat16)
+    # bf16 tables: the value that is rounded to bf16 is formed by single fp32 operations (torch CPU float32
+    # ops are IEEE single operations): step = lr * g, w - step
+    want = (wb.float() - torch.tensor(0.01, dtype=torch.float32) * torch.from_numpy(g)).to(torch.bfloat16)
     assert np.array_equal(table, want.view(torch.int16).numpy().view(np.uint16))
+    # Adagrad on a bf16 table, same rule: s += g*g; w -= (lr*g) / (sqrt(s) + eps), every operation in fp32
+    table2 = wb.view(torch.int16).numpy().view(np.uint16).copy()
+    s0 = rng.uniform(0, 2, size=(64, 8)).astype(np.float32)
+    st = s0.copy()
+    oracle.train_iter(table2, st, 8, oracle.BF16, oracle.ADAGRAD, 0.01, 1e-8, idx, off, g, want_out=False)
+    gt, f = torch.from_numpy(g), (lambda x: torch.tensor(x, dtype=torch.float32))
+    s1 = torch.from_numpy(s0) + gt * gt
+    want2 = (wb.float() - (f(0.01) * gt) / (torch.sqrt(s1) + f(1e-8))).to(torch.bfloat16)
+    assert np.array_equal(st, s1.numpy())
+    assert np.array_equal(table2, want2.view(torch.int16).numpy().view(np.uint16))
     # exact ties go to the even mantissa: 1 + 2^-8 is half-way between bf16(1) and the next value
     t2 = torch.tensor([[1.0]], dtype=torch.bfloat16).view(torch.int16).numpy().view(np.uint16).copy()
     oracle.train_iter(t2, None, 1, oracle.BF16, oracle.SGD, 1.0, 0.0, np.array([0]), np.array([0, 1]),
