@@ -1,0 +1,278 @@
+#!/usr/bin/env python3
+"""Benchmark of the embedding-access hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2]
+
+Workload: benchmark configs[2] by default — 26 tables / 33.8 M rows, D=48 fp32, one-hot Zipf ids (top 1 % of
+rows = 92 % of accesses), batch 16,384 (425,984 lookups per step), lookahead 400 over 200 batches, cache = 2 % of
+the rows in HBM, element-wise Adagrad, backing table in pinned host DRAM.  All inputs are seeded and synthetic.
+
+A step is one pass of the hot path over one batch: bp_cache_apply (write back the previous batch's evictions,
+load this batch's prefetches), bp_embbag_fwd, bp_embbag_bwd_update.  The plan (bp_oracle_plan over the whole
+trace) is timed separately; its cost per batch is added to every step, so `value` is whole-job lookups/s with
+ids, upstream gradients and the backing table resident before the timed region starts.
+
+Prints ONE JSON line.  Extra objects: `roofline` (dominant kernel, algorithmic bytes / HIP-event duration against
+the 8 TB/s HBM peak) and `cpu_baseline` (the CPU oracle, single thread, on a bounded sample of the same workload).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published peak
+
+# HBM traffic per launch of the dominant kernel from rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE; KiB per dispatch,
+# scaled by the copy-kernel calibration), keyed by (workload, kernel).  Filled in from profiles/; None = not measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(kernel: str, n: int, bags: int, u: float, row_b: int, state_b: int, D: int, one_hot: bool) -> float:
+    """Bytes the method itself has to move per launch (n lookups, u distinct rows, row_b bytes per weight row,
+    state_b bytes of optimizer state per row)."""
+    if kernel == "embbag_fwd":
+        # slot per lookup + offsets (none for one-hot) + every distinct row once + pooled output
+        return 4 * n + (0 if one_hot else 8 * (bags + 1)) + u * row_b + bags * D * 4
+    if kernel == "bwd_reduce_update":
+        # sorted slot + bag id per lookup, one gradient row per lookup, read-modify-write of every distinct row + state
+        return 8 * n + n * D * 4 + 2 * u * (row_b + state_b)
+    raise KeyError(kernel)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=0, help="timed steps (default: all batches after the warm-up)")
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--cpu-baseline-iters", type=int, default=40)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU by design (no collectives, no sharding); run with --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import workloads
+    import paper_2202_12429_amd as bp
+    from paper_2202_12429_amd.runner import CachedEmbeddingTrainer, state_shape
+
+    bp.load_library()                      # fails loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    cfg = workloads.CONFIGS[args.config]
+    T = cfg.iterations
+    W = max(0, min(args.warmup, T - 1))
+    K = args.steps if args.steps > 0 else T - W
+    if W + K > T:
+        K = T - W
+    bags, D = cfg.bags, cfg.dim
+
+    t0 = time.time()
+    trace = workloads.make_trace(cfg)
+    log(f"trace: {trace.n_lookups} lookups in {T} batches ({time.time() - t0:.1f} s)")
+    n_per_iter = np.diff(trace.iter_offsets)
+
+    # ---- capacity: configs whose single-batch working set exceeds the stated cache get the stated cache on top of it
+    capacity = cfg.capacity
+    ids_dev = torch.from_numpy(trace.ids).to(dev)
+    bcfg = bp.make_config(cfg.total_rows, capacity, D, cfg.weight_dtype, cfg.optimizer, cfg.lookahead, cfg.lr, cfg.eps)
+    capacity_note = None
+    try:
+        plan = bp.bp_oracle_plan(bcfg, ids_dev, trace.iter_offsets)
+    except bp.BagpipeError as e:
+        if e.status != -2:
+            raise
+        need = int(e.info["min_capacity"])
+        capacity = cfg.capacity + ((need + 1023) // 1024) * 1024
+        capacity_note = (f"stated cache {cfg.capacity} < {need} unique rows of one batch; ran with "
+                         f"{capacity} = stated + the batch working set rounded up to 1024")
+        log(capacity_note)
+        bcfg = bp.make_config(cfg.total_rows, capacity, D, cfg.weight_dtype, cfg.optimizer, cfg.lookahead, cfg.lr, cfg.eps)
+        plan = bp.bp_oracle_plan(bcfg, ids_dev, trace.iter_offsets)
+    del plan
+
+    # ---- backing table in pinned host memory (stands in for the embedding servers)
+    t0 = time.time()
+    wdt = torch.bfloat16 if cfg.weight_dtype == "bf16" else torch.float32
+    backing_w = torch.empty((cfg.total_rows, D), dtype=wdt, pin_memory=True)
+    chunk = 1 << 21
+    for a in range(0, cfg.total_rows, chunk):
+        b = min(cfg.total_rows, a + chunk)
+        backing_w[a:b].copy_(workloads.init_weights(cfg, a, b, device=dev).to(wdt))
+    ss = state_shape(cfg.total_rows, D, bcfg.optimizer)
+    backing_s = torch.zeros(ss, dtype=torch.float32, pin_memory=True) if ss != (0,) else None
+    torch.cuda.synchronize()
+    log(f"backing table: {backing_w.numel() * backing_w.element_size() / 2**30:.2f} GiB pinned"
+        f"{'' if backing_s is None else f' + {backing_s.numel() * 4 / 2**30:.2f} GiB state'} ({time.time() - t0:.1f} s)")
+
+    # ---- CPU baseline: the oracle as it stands, one thread, on the first batches of the same workload
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        S_it = min(args.cpu_baseline_iters, T)
+        dt, op = oracle.DTYPES[cfg.weight_dtype], oracle.OPTIMIZERS[cfg.optimizer]
+        Wo = (backing_w.view(torch.int16).numpy().view(np.uint16).copy() if dt == oracle.BF16 else backing_w.numpy().copy())
+        So = np.zeros(oracle.state_shape(cfg.total_rows, D, op), dtype=np.float32)
+        grads = [workloads.upstream_grad(cfg, i, bags, device=dev).cpu().numpy() for i in range(S_it)]
+        t0 = time.time()
+        for i in range(S_it):
+            oracle.train_iter(Wo, So, D, dt, op, cfg.lr, cfg.eps, trace.iter_ids(i), trace.bag_offsets[i], grads[i])
+        t_train = time.time() - t0
+        n_s = int(trace.iter_offsets[S_it])
+        t0 = time.time()
+        sub_off = trace.iter_offsets[:S_it + 1]
+        oracle.plan(trace.ids[:n_s], sub_off, cfg.total_rows, cfg.lookahead, capacity)
+        t_plan = time.time() - t0
+        cpu = {"value": n_s / (t_train + t_plan), "unit": "lookups/s", "cores": 1, "kind": "oracle",
+               "sample": f"first {S_it} of {T} batches ({n_s} lookups): oracle plan {t_plan:.1f} s + uncached "
+                         f"forward/backward/update {t_train:.1f} s, single thread",
+               "plan_ids_per_s": n_s / t_plan, "train_lookups_per_s": n_s / t_train}
+        del Wo, So, grads
+        log(f"cpu oracle: {cpu['value']:.3g} lookups/s on {S_it} batches")
+
+    # ---- GPU: plan (timed), then the trace
+    trainer = CachedEmbeddingTrainer(bcfg, backing_w, backing_s, device=dev, max_lookups=int(n_per_iter.max()),
+                                     max_bags=bags)
+    ws = torch.empty(bp.bp_oracle_plan_workspace_bytes(bcfg, trace.n_lookups, T), dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+    plan_times = []
+    for rep in range(3):
+        t0 = time.perf_counter()
+        trainer.plan_ = bp.bp_oracle_plan(bcfg, ids_dev, trace.iter_offsets, workspace=ws)
+        torch.cuda.synchronize()
+        plan_times.append(time.perf_counter() - t0)
+    trainer.iter_offsets = np.ascontiguousarray(trace.iter_offsets, dtype=np.int64)
+    plan = trainer.plan_
+    t_plan = float(np.median(plan_times))
+    del ws
+    log(f"plan: L_eff={plan.L_eff} peak={plan.peak_occupancy} pairs={plan.n_unique_pairs} "
+        f"prefetches={int(plan.prefetch_offsets[-1])}  {t_plan * 1e3:.1f} ms ({trace.n_lookups / t_plan:.3g} ids/s)")
+
+    bag_off_dev = None if cfg.one_hot else [torch.from_numpy(np.ascontiguousarray(trace.bag_offsets[i])).to(dev)
+                                            for i in range(T)]
+    grads_dev = [workloads.upstream_grad(cfg, i, bags, device=dev) for i in range(W + K)]
+    out = torch.empty((bags, D), dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+
+    def step(i):
+        bo = None if bag_off_dev is None else bag_off_dev[i]
+        trainer.maintain(i)
+        trainer.forward(i, bo, bags, out=out)
+        trainer.backward_update(i, bo, bags, grads_dev[i])
+
+    def run_pass(profile_kernels):
+        """Warm-up W steps, then K timed steps.  profile_kernels: None = no events, [] = all kernels, or a list."""
+        for i in range(W):
+            step(i)
+        torch.cuda.synchronize()
+        if profile_kernels is not None:
+            bp.bp_profile_select(profile_kernels or None)
+            bp.bp_profile_enable(True)
+        t0 = time.perf_counter()
+        for i in range(W, W + K):
+            step(i)
+        torch.cuda.synchronize()
+        dt_ = time.perf_counter() - t0
+        prof = {}
+        if profile_kernels is not None:
+            bp.bp_profile_collect()
+            prof = bp.profile_totals()
+            bp.bp_profile_enable(False)
+            bp.bp_profile_select(None)
+        # finish the trace so the cache drains and the next pass starts from an empty cache
+        for i in range(W + K, T):
+            bo = None if bag_off_dev is None else bag_off_dev[i]
+            trainer.maintain(i)
+        trainer.flush()
+        torch.cuda.synchronize()
+        return dt_, prof
+
+    # pass A: every kernel bracketed by events -> breakdown, picks the dominant kernel
+    _, prof_all = run_pass([])
+    hot = {k: v for k, v in prof_all.items() if k in ("embbag_fwd", "bwd_reduce_update")}
+    dominant = max(hot, key=lambda k: hot[k][1])
+    # pass B: the timed region proper; only the dominant kernel is bracketed (two event records per step)
+    t_loop, prof_dom = run_pass([dominant])
+
+    n_timed = int(n_per_iter[W:W + K].sum())
+    t_total = t_loop + t_plan * K / T                      # the plan's share of these K batches
+    value = n_timed / t_total
+    launches, ms = prof_dom[dominant]
+    dur_s = ms * 1e-3 / launches
+    u_mean = float(np.diff(plan.keep_offsets)[W:W + K].mean())
+    row_b = D * (2 if cfg.weight_dtype == "bf16" else 4)
+    state_b = D * 4 if cfg.optimizer == "adagrad" else 4 if cfg.optimizer == "adagrad_rowwise" else 0
+    n_mean = n_timed / K
+    alg = algorithmic_bytes(dominant, n_mean, bags, u_mean, row_b, state_b if dominant != "embbag_fwd" else 0, D,
+                            cfg.one_hot)
+    achieved = alg / dur_s / 1e9
+    traffic = MEASURED_TRAFFIC_BYTES.get((cfg.name, dominant))
+
+    def per_step(names):
+        return sum(prof_all[k][1] for k in names if k in prof_all) / K
+
+    sort_scan = ["sort_upsweep", "sort_downsweep", "scan_reduce", "scan_spine", "scan_apply"]
+    kernel_ms = {
+        "cache_apply": per_step(["cache_evict", "cache_prefetch"]),
+        "fwd": per_step(["embbag_fwd"]),
+        "bwd_sort_and_items": per_step(["bwd_keys"] + sort_scan),
+        "bwd_reduce_update": per_step(["bwd_reduce_update"]),
+        "bwd_combine_update": per_step(["bwd_combine_update"]),
+    }
+    fbu_ms = kernel_ms["fwd"] + kernel_ms["bwd_sort_and_items"] + kernel_ms["bwd_reduce_update"] + kernel_ms["bwd_combine_update"]
+    moved = int(plan.prefetch_offsets[W + K] - plan.prefetch_offsets[W]) + int(plan.evict_offsets[W + K - 1] - plan.evict_offsets[max(W - 1, 0)])
+
+    result = {
+        "metric": "cached EmbeddingBag fwd+bwd+update lookups/s (whole hot path: plan share + cache apply + fwd + bwd/update)",
+        "value": value,
+        "unit": "lookups/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": t_total / K * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if cfg.weight_dtype == "f32" else "bf16 storage, f32 arithmetic",
+        "data": "synthetic",
+        "config": {"workload": f"configs[{cfg.index}] {cfg.name}: {cfg.num_tables} tables, {cfg.total_rows} rows, D={D} "
+                               f"{cfg.weight_dtype}, batch {cfg.batch} ({int(n_mean)} lookups/step), {T} batches, "
+                               f"lookahead {cfg.lookahead}, cache {capacity} rows, {cfg.optimizer}, backing table in pinned host DRAM",
+                   "L_eff": plan.L_eff, "peak_occupancy": plan.peak_occupancy, "capacity_note": capacity_note,
+                   "unique_rows_per_step": u_mean},
+        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "algorithmic_bytes_per_launch": alg,
+                     "avg_launch_us": dur_s * 1e6, "launches": launches},
+        "cpu_baseline": cpu,
+        "plan": {"ms": t_plan * 1e3, "ids_per_s": trace.n_lookups / t_plan, "n_lookups": trace.n_lookups},
+        "loop_ms_per_step": t_loop / K * 1e3,
+        "kernel_ms_per_step": kernel_ms,
+        "fwd_bwd_update_lookups_per_s_kernel_time": n_mean / (fbu_ms * 1e-3) if fbu_ms > 0 else None,
+        "cache_apply": {"rows_per_step": moved / K, "rows_per_s": moved / (kernel_ms["cache_apply"] * 1e-3 * K)
+                        if kernel_ms["cache_apply"] > 0 else None,
+                        "pcie_GBps": moved * (row_b + state_b) / (kernel_ms["cache_apply"] * 1e-3 * K) / 1e9
+                        if kernel_ms["cache_apply"] > 0 else None},
+    }
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -176,9 +176,12 @@ int bp_version(void);
  * bp_profile_enable(1) starts recording (and clears old records); bp_profile_enable(0) stops.
  * bp_profile_collect() synchronises the recorded events and adds their durations to per-kernel totals;
  * bp_profile_get() reads the totals of kernel `id` in [0, bp_profile_num_kernels()).
+ * bp_profile_select(mask) restricts recording to the kernels whose id bit is set (default: all), so that a
+ * timed loop can bracket one kernel only and pay two event records per launch of that kernel.
  * Recording creates HIP events (no device memory).  Not thread-safe.
  */
 int bp_profile_enable(int on);
+int bp_profile_select(uint64_t kernel_mask);
 int bp_profile_collect(void);
 int bp_profile_num_kernels(void);
 const char* bp_profile_kernel_name(int id);

@@ -72,6 +72,8 @@ def load_library():
     lib.bp_profile_kernel_name.argtypes = [ctypes.c_int]
     lib.bp_profile_kernel_name.restype = ctypes.c_char_p
     lib.bp_profile_get.argtypes = [ctypes.c_int, ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)]
+    lib.bp_profile_select.argtypes = [ctypes.c_uint64]
+    lib.bp_profile_select.restype = ctypes.c_int
     for name in ("bp_oracle_plan_workspace_bytes", "bp_oracle_plan", "bp_cache_apply", "bp_embbag_fwd",
                  "bp_embbag_bwd_update_workspace_bytes", "bp_embbag_bwd_update", "bp_version", "bp_profile_enable",
                  "bp_profile_collect", "bp_profile_num_kernels", "bp_profile_get"):
@@ -245,6 +247,19 @@ def bp_embbag_bwd_update(cfg: bp_config, cache_w, cache_state, lookup_slots, bag
 # ---------------------------------------------------------------------------------------------------
 def bp_profile_enable(on: bool) -> None:
     _check(load_library().bp_profile_enable(int(bool(on))))
+
+
+def bp_profile_select(kernel_names=None) -> None:
+    """Record only the named kernels (None = all)."""
+    lib = load_library()
+    if kernel_names is None:
+        mask = (1 << 64) - 1
+    else:
+        ids = {lib.bp_profile_kernel_name(k).decode(): k for k in range(lib.bp_profile_num_kernels())}
+        mask = 0
+        for n in kernel_names:
+            mask |= 1 << ids[n]
+    _check(lib.bp_profile_select(ctypes.c_uint64(mask)))
 
 
 def bp_profile_collect() -> None:

@@ -42,6 +42,7 @@ int check_config(const bp_config* cfg) {
 
 // ---- profiler --------------------------------------------------------------------------------
 bool g_profile_on = false;
+uint64_t g_profile_mask = ~uint64_t(0);
 
 namespace {
 struct Span {
@@ -117,6 +118,11 @@ BP_EXPORT int bp_profile_enable(int on) {
         std::memset(g_ms, 0, sizeof(g_ms));
     }
     g_profile_on = on != 0;
+    return BP_OK;
+}
+
+BP_EXPORT int bp_profile_select(uint64_t kernel_mask) {
+    g_profile_mask = kernel_mask;
     return BP_OK;
 }
 

@@ -92,15 +92,17 @@ enum KernelId {
 };
 
 extern bool g_profile_on;
+extern uint64_t g_profile_mask;
 void profile_begin(int id, hipStream_t s);
 void profile_end(int id, hipStream_t s);
 
 // Launch `kernel` and, when profiling is on, bracket it with events on the same stream.
 #define BP_LAUNCH(id, kernel, grid, block, shmem, stream, ...)                      \
     do {                                                                             \
-        if (::bp::g_profile_on) ::bp::profile_begin((id), (stream));                \
+        const bool prof_ = ::bp::g_profile_on && ((::bp::g_profile_mask >> (id)) & 1);  \
+        if (prof_) ::bp::profile_begin((id), (stream));                              \
         hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__);        \
-        if (::bp::g_profile_on) ::bp::profile_end((id), (stream));                  \
+        if (prof_) ::bp::profile_end((id), (stream));                                \
         hipError_t le_ = hipGetLastError();                                          \
         if (le_ != hipSuccess)                                                       \
             return ::bp::fail(BP_ERR_HIP, "launch of %s failed: %s", #kernel, hipGetErrorString(le_)); \
