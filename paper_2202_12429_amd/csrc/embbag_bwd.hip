@@ -11,8 +11,8 @@
 //   3. one lane group per item adds its gradient rows in order (fp64 accumulators).  An item that covers its whole
 //      slot applies the update at once; otherwise the sum goes to a partial row addressed by the chunk
 //      boundary it touches.
-//   4. for slots split over several items, the group of the first item adds the partial rows in order
-//      and applies the update.
+//   4. for slots split over several items, one wavefront adds the partial rows (lane groups round-robin,
+//      then a butterfly across the groups) and applies the update.
 // Every order of addition is fixed by the data, never by timing: results are bit-identical run to run.
 // The summed gradient is rounded to fp32 once; the optimizer step itself is fp32 arithmetic.
 #include "common.h"
@@ -122,9 +122,9 @@ __device__ __forceinline__ double group_sum(double x) {
 // s += g*g, den = sqrt(s) + eps, step /= den, and w -= step.
 template <int GW, bool BF16>
 __device__ __forceinline__ void apply_update(const UpdateParams& u, uint4* cache_w, float* cache_s, int64_t slot, int c,
-                                             const Piece<BF16>& g) {
+                                             const Piece<BF16>& g, bool writer = true) {
     constexpr int N = Piece<BF16>::N;
-    const bool active = c < u.lpr;
+    const bool active = c < u.lpr && writer;
     Piece<BF16> w;
     w.zero();
     if (active) w.decode(cache_w[slot * u.lpr + c]);
@@ -161,7 +161,7 @@ __device__ __forceinline__ void apply_update(const UpdateParams& u, uint4* cache
             const float step = (u.lr * g.v[i]) / den;
             w.v[i] = w.v[i] - step;
         }
-        if (c == 0) cache_s[slot] = s;
+        if (c == 0 && writer) cache_s[slot] = s;
     }
     if (active) cache_w[slot * u.lpr + c] = w.encode();
 }
@@ -214,6 +214,11 @@ __global__ __launch_bounds__(kRowBlock) void bwd_reduce_update_kernel(const uint
     }
 }
 
+// Split slots: one wavefront per slot.  Its 64/GW lane groups take the slot's partial rows round-robin
+// (row 2b of the head item goes to group 0, row 2b'+1 of the item starting at boundary b' to group
+// (b' - b) mod groups), each adds its share in order with four loads in flight, and the group sums are added
+// across the wavefront by a butterfly whose order is fixed by the lane numbers.  Every group then holds the
+// slot's gradient; group 0 writes the update.
 template <int GW, bool BF16>
 __global__ __launch_bounds__(kRowBlock) void bwd_combine_update_kernel(const uint32_t* __restrict__ keys,
                                                                       const uint32_t* __restrict__ item_start,
@@ -221,11 +226,13 @@ __global__ __launch_bounds__(kRowBlock) void bwd_combine_update_kernel(const uin
                                                                       int64_t C, uint4* cache_w, float* cache_s,
                                                                       const double* __restrict__ partial, UpdateParams u) {
     constexpr int N = Piece<BF16>::N;
+    constexpr int G = kWave / GW;                     // lane groups per wavefront
     const uint32_t W = *n_items_ptr;
-    const int c = threadIdx.x % GW;
+    const int lane = threadIdx.x % kWave;
+    const int c = lane % GW, j = lane / GW;
     const bool active = c < u.lpr;
-    const uint32_t groups = gridDim.x * (kRowBlock / GW);
-    for (uint32_t w = (blockIdx.x * kRowBlock + threadIdx.x) / GW; w < W; w += groups) {
+    const uint32_t waves = gridDim.x * (kRowBlock / kWave);
+    for (uint32_t w = (blockIdx.x * kRowBlock + threadIdx.x) / kWave; w < W; w += waves) {
         const uint32_t start = item_start[w];
         const uint32_t end = w + 1 < W ? item_start[w + 1] : n;
         const uint32_t slot = keys[start];
@@ -235,19 +242,29 @@ __global__ __launch_bounds__(kRowBlock) void bwd_combine_update_kernel(const uin
         if (!head || tail) continue;                  // only the first item of a split slot works here
         SumPiece<N> acc;
         acc.zero();
-        uint32_t b = end / kChunk;                    // end is a chunk boundary because the slot goes on
-        if (active) acc.load(partial + 2 * (size_t)b * u.dim, c);
-        for (;;) {                                    // items starting at boundaries b, b+1, ... of this slot
-            if (active) {
-                SumPiece<N> t;
-                t.load(partial + (2 * (size_t)b + 1) * u.dim, c);
-                acc.add(t);
+        const uint32_t b0 = end / kChunk;             // end is a chunk boundary because the slot goes on
+        if (active && j == 0) acc.load(partial + 2 * (size_t)b0 * u.dim, c);
+        // the item starting at boundary b belongs to this slot iff b*kChunk < n and keys[b*kChunk] == slot
+        for (uint64_t b = (uint64_t)b0 + j;; b += 4 * G) {
+            bool ok[4];
+            SumPiece<N> t[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint64_t bb = b + (uint64_t)k * G;
+                ok[k] = bb * kChunk < n && keys[bb * kChunk] == slot;
+                t[k].zero();
+                if (ok[k] && active) t[k].load(partial + (2 * bb + 1) * u.dim, c);
             }
-            const uint64_t next = (uint64_t)(b + 1) * kChunk;
-            if (next >= n || keys[next] != slot) break;
-            ++b;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) acc.add(t[k]);
+            if (!ok[3]) break;                        // the slot's boundaries are consecutive
         }
-        apply_update<GW, BF16>(u, cache_w, cache_s, (int64_t)slot, c, acc.template rounded<BF16>());
+#pragma unroll
+        for (int off = GW; off < kWave; off <<= 1) {
+#pragma unroll
+            for (int i = 0; i < N; ++i) acc.v[i] += __shfl_xor(acc.v[i], off, kWave);
+        }
+        apply_update<GW, BF16>(u, cache_w, cache_s, (int64_t)slot, c, acc.template rounded<BF16>(), j == 0);
     }
 }
 
@@ -296,7 +313,9 @@ struct BwdLaunch {
         BP_LAUNCH(K_BWD_REDUCE_UPDATE, (bwd_reduce_update_kernel<GW, BF16>), dim3((unsigned)blocks), dim3(kRowBlock), 0, stream,
                   skeys, sbags, (const uint32_t*)w->item_start, n_items, (uint32_t)n, cfg->capacity, grad, (uint4*)cache_w,
                   (float*)cache_s, w->partial, u);
-        BP_LAUNCH(K_BWD_COMBINE_UPDATE, (bwd_combine_update_kernel<GW, BF16>), dim3((unsigned)blocks), dim3(kRowBlock), 0,
+        int64_t cblocks = ceil_div(n, kRowBlock / kWave);          // one wavefront per item
+        if (cblocks > kMaxGridBlocks) cblocks = kMaxGridBlocks;
+        BP_LAUNCH(K_BWD_COMBINE_UPDATE, (bwd_combine_update_kernel<GW, BF16>), dim3((unsigned)cblocks), dim3(kRowBlock), 0,
                   stream, skeys, (const uint32_t*)w->item_start, n_items, (uint32_t)n, cfg->capacity, (uint4*)cache_w,
                   (float*)cache_s, (const double*)w->partial, u);
         return BP_OK;
