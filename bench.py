@@ -31,7 +31,11 @@ HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published peak
 
 # HBM traffic per launch of the dominant kernel from rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE; KiB per dispatch,
 # scaled by the copy-kernel calibration), keyed by (workload, kernel).  Filled in from profiles/; None = not measured.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # profiles/hbm_traffic_cfg2_pmc.txt: FETCH_SIZE 76402.7 KiB x2 (copy calibration) + WRITE_SIZE 40386.6 KiB x1
+    ("criteo_kaggle_d48", "bwd_reduce_update"): 197.83e6,
+    ("criteo_kaggle_d48", "embbag_fwd"): 128.39e6,
+}
 
 
 def log(msg):
@@ -165,6 +169,19 @@ def main() -> int:
     log(f"plan: L_eff={plan.L_eff} peak={plan.peak_occupancy} pairs={plan.n_unique_pairs} "
         f"prefetches={int(plan.prefetch_offsets[-1])}  {t_plan * 1e3:.1f} ms ({trace.n_lookups / t_plan:.3g} ids/s)")
 
+    # ---- plain copy of known size (1 GiB read + 1 GiB written): counter yardstick and copy ceiling of this GPU
+    ca = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+    cb = torch.empty_like(ca)
+    bp.bp_copy_calibration(cb, ca)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(5):
+        bp.bp_copy_calibration(cb, ca)
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2 * ca.numel() * 4 / (time.perf_counter() - t0) / 1e9
+    del ca, cb
+    log(f"plain copy kernel: {copy_gbs:.0f} GB/s (read + write)")
+
     bag_off_dev = None if cfg.one_hot else [torch.from_numpy(np.ascontiguousarray(trace.bag_offsets[i])).to(dev)
                                             for i in range(T)]
     grads_dev = [workloads.upstream_grad(cfg, i, bags, device=dev) for i in range(W + K)]
@@ -259,7 +276,8 @@ def main() -> int:
                    "unique_rows_per_step": u_mean},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "algorithmic_bytes_per_launch": alg,
-                     "avg_launch_us": dur_s * 1e6, "launches": launches},
+                     "avg_launch_us": dur_s * 1e6, "launches": launches,
+                     "frac_of_measured_copy": achieved / copy_gbs, "measured_copy_GBps": copy_gbs},
         "cpu_baseline": cpu,
         "plan": {"ms": t_plan * 1e3, "ids_per_s": trace.n_lookups / t_plan, "n_lookups": trace.n_lookups},
         "loop_ms_per_step": t_loop / K * 1e3,

@@ -167,6 +167,10 @@ int bp_embbag_bwd_update(const bp_config* cfg, void* cache_w, void* cache_state,
 /* ------------------------------------------------------------------------------------------------
  * Diagnostics.
  * ------------------------------------------------------------------------------------------------ */
+/* Plain device-to-device copy of `bytes` bytes (multiple of 16, 16-byte aligned pointers) by a streaming kernel:
+ * a yardstick of known size for hardware byte counters and for achievable copy bandwidth.  Asynchronous. */
+int bp_copy_calibration(void* dst, const void* src, size_t bytes, void* stream);
+
 const char* bp_error_string(int status);
 const char* bp_last_error_message(void);   /* thread-local, valid until the thread's next failing call */
 int bp_version(void);

@@ -72,6 +72,8 @@ def load_library():
     lib.bp_profile_kernel_name.argtypes = [ctypes.c_int]
     lib.bp_profile_kernel_name.restype = ctypes.c_char_p
     lib.bp_profile_get.argtypes = [ctypes.c_int, ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)]
+    lib.bp_copy_calibration.argtypes = [vp, vp, sz, vp]
+    lib.bp_copy_calibration.restype = ctypes.c_int
     lib.bp_profile_select.argtypes = [ctypes.c_uint64]
     lib.bp_profile_select.restype = ctypes.c_int
     for name in ("bp_oracle_plan_workspace_bytes", "bp_oracle_plan", "bp_cache_apply", "bp_embbag_fwd",
@@ -245,6 +247,13 @@ def bp_embbag_bwd_update(cfg: bp_config, cache_w, cache_state, lookup_slots, bag
 # ---------------------------------------------------------------------------------------------------
 # profiling
 # ---------------------------------------------------------------------------------------------------
+def bp_copy_calibration(dst, src, stream=None) -> None:
+    """dst <- src by the library's plain copy kernel (tensors of equal byte size)."""
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    _check(load_library().bp_copy_calibration(_ptr(dst), _ptr(src), nbytes, _stream(stream)))
+
+
 def bp_profile_enable(on: bool) -> None:
     _check(load_library().bp_profile_enable(int(bool(on))))
 

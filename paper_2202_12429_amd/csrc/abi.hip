@@ -70,7 +70,7 @@ const char* const kKernelNames[K_NUM_KERNELS] = {
     "sort_upsweep", "sort_scan", "sort_downsweep", "scan_reduce", "scan_spine", "scan_apply",
     "plan_keys", "plan_pairs", "plan_hist", "plan_occupancy", "plan_flags", "plan_lists", "plan_ring_jump",
     "plan_slots", "cache_evict", "cache_prefetch", "embbag_fwd", "bwd_keys", "bwd_items", "bwd_reduce_update",
-    "bwd_combine_update", "fill"};
+    "bwd_combine_update", "fill", "copy_calibration"};
 }  // namespace
 
 void profile_begin(int /*id*/, hipStream_t s) {
@@ -84,6 +84,13 @@ void profile_end(int id, hipStream_t s) {
     (void)hipEventRecord(b, s);
     g_spans.push_back(Span{id, g_open, b});
     g_open = nullptr;
+}
+
+// A plain streaming copy of known size: the yardstick for byte counters (what FETCH_SIZE / WRITE_SIZE read for
+// exactly `bytes` read and `bytes` written) and for the copy bandwidth this GPU sustains.
+__global__ __launch_bounds__(256) void copy_calibration_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
+                                                               size_t n16) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
 }
 
 }  // namespace bp
@@ -106,6 +113,18 @@ BP_EXPORT const char* bp_error_string(int status) {
 BP_EXPORT const char* bp_last_error_message(void) { return t_error; }
 
 BP_EXPORT int bp_version(void) { return 100; }
+
+BP_EXPORT int bp_copy_calibration(void* dst, const void* src, size_t bytes, void* stream) {
+    if (!dst || !src || bytes % 16 != 0 || (((uintptr_t)dst | (uintptr_t)src) & 15))
+        return fail(BP_ERR_INVALID_ARG, "copy needs 16-byte aligned pointers and a multiple of 16 bytes");
+    if (bytes == 0) return BP_OK;
+    const size_t n16 = bytes / 16;
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    BP_LAUNCH(K_COPY, copy_calibration_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
+              (const uint4*)src, (uint4*)dst, n16);
+    return BP_OK;
+}
 
 BP_EXPORT int bp_profile_enable(int on) {
     if (on) {

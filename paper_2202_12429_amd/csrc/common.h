@@ -88,6 +88,7 @@ enum KernelId {
     K_BWD_REDUCE_UPDATE,
     K_BWD_COMBINE_UPDATE,
     K_FILL,
+    K_COPY,
     K_NUM_KERNELS
 };
 
