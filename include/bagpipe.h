@@ -47,6 +47,9 @@ typedef enum bp_status {
     BP_ERR_UNSUPPORTED = -6          /* size beyond a documented limit */
 } bp_status;
 
+/* Lookups per work item of the backward pass at most (shared by the planner's grouping and the backward kernels). */
+#define BP_BWD_CHUNK 32
+
 enum { BP_F32 = 0, BP_BF16 = 1 };
 enum { BP_SGD = 0, BP_ADAGRAD = 1, BP_ADAGRAD_ROWWISE = 2 };
 
@@ -92,6 +95,15 @@ typedef struct bp_plan {
     int64_t* evict_offsets;    /* [T+1] */
     int64_t* keep_offsets;     /* [T+1] */
     int64_t* occupancy;        /* [T] rows resident while batch i trains */
+    /* optional (all four NULL, or all four set): every batch's lookups grouped by row, which is a by-product of the
+     * planner's sort and lets bp_embbag_bwd_update_grouped skip its own sort.  Inside a batch the lookups are
+     * ordered by id ascending and, for one id, by lookup position ascending.  A work item is a maximal run of
+     * consecutive grouped lookups of one row that does not cross a multiple of BP_BWD_CHUNK positions (counted
+     * from the batch's first grouped lookup). */
+    int32_t* grouped_slots;    /* device [n_lookups] cache slot of each grouped lookup */
+    int32_t* grouped_lookups;  /* device [n_lookups] its position, relative to the batch's first lookup */
+    uint32_t* item_starts;     /* device [n_lookups] first grouped lookup of each work item, relative to the batch */
+    int64_t* item_offsets;     /* host [T+1] CSR offsets of the batches into item_starts */
     /* scalar results */
     int32_t L_eff;
     int64_t peak_occupancy;
@@ -99,8 +111,10 @@ typedef struct bp_plan {
     int64_t n_unique_pairs;    /* sum_i |U_i| */
 } bp_plan;
 
-/* Bytes of device workspace bp_oracle_plan needs for a trace of n_lookups lookups in n_iters batches. */
-int bp_oracle_plan_workspace_bytes(const bp_config* cfg, int64_t n_lookups, int32_t n_iters, size_t* bytes);
+/* Bytes of device workspace bp_oracle_plan needs for a trace of n_lookups lookups in n_iters batches;
+ * with_grouping != 0 when the plan's optional grouping outputs are requested. */
+int bp_oracle_plan_workspace_bytes(const bp_config* cfg, int64_t n_lookups, int32_t n_iters, int32_t with_grouping,
+                                   size_t* bytes);
 
 /*
  * ids          device, [n_lookups] global row ids in lookup order, batches concatenated
@@ -163,6 +177,24 @@ int bp_embbag_bwd_update_workspace_bytes(const bp_config* cfg, int64_t n_lookups
 int bp_embbag_bwd_update(const bp_config* cfg, void* cache_w, void* cache_state, const int32_t* lookup_slots,
                          const int64_t* bag_offsets, int64_t n_lookups, int64_t bags, const float* grad_out,
                          void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The same backward + update for a batch whose lookups the plan has already grouped by row (bp_plan's
+ * optional outputs): no sort and no scan at run time, two kernel launches.  Results are those of
+ * bp_embbag_bwd_update up to the order in which a row's gradients enter the fp64 sum.
+ *
+ * grouped_slots / grouped_lookups  device, the batch's slices [iter_offsets[i], iter_offsets[i+1]) of the plan arrays
+ * item_starts, n_items             device, the batch's slice [item_offsets[i], item_offsets[i+1]) and its length
+ * workspace                        device, bp_embbag_bwd_update_grouped_workspace_bytes() bytes (multi_hot != 0 when
+ *                                  bag_offsets is not NULL), 256-byte aligned
+ * Other arguments, limits and error behaviour as for bp_embbag_bwd_update.  Asynchronous.
+ */
+int bp_embbag_bwd_update_grouped_workspace_bytes(const bp_config* cfg, int64_t n_lookups, int64_t bags,
+                                                 int32_t multi_hot, size_t* bytes);
+int bp_embbag_bwd_update_grouped(const bp_config* cfg, void* cache_w, void* cache_state, const int32_t* grouped_slots,
+                                 const int32_t* grouped_lookups, const uint32_t* item_starts, int64_t n_items,
+                                 const int64_t* bag_offsets, int64_t n_lookups, int64_t bags, const float* grad_out,
+                                 void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------------
  * Diagnostics.

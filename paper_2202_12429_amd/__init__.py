@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     BagpipeError, Plan, bp_config, library_path, load_library, make_config,
     bp_oracle_plan, bp_oracle_plan_workspace_bytes, bp_cache_apply, bp_embbag_fwd,
     bp_embbag_bwd_update, bp_embbag_bwd_update_workspace_bytes,
+    bp_embbag_bwd_update_grouped, bp_embbag_bwd_update_grouped_workspace_bytes,
     bp_error_string, bp_last_error_message, bp_version,
     bp_copy_calibration, bp_profile_enable, bp_profile_select, bp_profile_collect, bp_profile_get, profile_totals,
 )

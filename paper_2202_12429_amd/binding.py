@@ -35,7 +35,9 @@ class _bp_plan(ctypes.Structure):
                 ("prefetch_slots", ctypes.c_void_p), ("evict_ids", ctypes.c_void_p), ("evict_slots", ctypes.c_void_p),
                 ("keep_ids", ctypes.c_void_p), ("keep_ttl", ctypes.c_void_p), ("list_capacity", ctypes.c_int64),
                 ("prefetch_offsets", ctypes.c_void_p), ("evict_offsets", ctypes.c_void_p),
-                ("keep_offsets", ctypes.c_void_p), ("occupancy", ctypes.c_void_p), ("L_eff", ctypes.c_int32),
+                ("keep_offsets", ctypes.c_void_p), ("occupancy", ctypes.c_void_p),
+                ("grouped_slots", ctypes.c_void_p), ("grouped_lookups", ctypes.c_void_p),
+                ("item_starts", ctypes.c_void_p), ("item_offsets", ctypes.c_void_p), ("L_eff", ctypes.c_int32),
                 ("peak_occupancy", ctypes.c_int64), ("min_capacity", ctypes.c_int64),
                 ("n_unique_pairs", ctypes.c_int64)]
 
@@ -60,12 +62,14 @@ def load_library():
     lib = ctypes.CDLL(_LIB_PATH)
     vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
     cfgp = ctypes.POINTER(bp_config)
-    lib.bp_oracle_plan_workspace_bytes.argtypes = [cfgp, i64, i32, ctypes.POINTER(sz)]
+    lib.bp_oracle_plan_workspace_bytes.argtypes = [cfgp, i64, i32, i32, ctypes.POINTER(sz)]
     lib.bp_oracle_plan.argtypes = [cfgp, vp, vp, i32, ctypes.POINTER(_bp_plan), vp, sz, vp]
     lib.bp_cache_apply.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, i64, vp, vp, i64, vp]
     lib.bp_embbag_fwd.argtypes = [cfgp, vp, vp, vp, i64, i64, vp, vp]
     lib.bp_embbag_bwd_update_workspace_bytes.argtypes = [cfgp, i64, i64, ctypes.POINTER(sz)]
     lib.bp_embbag_bwd_update.argtypes = [cfgp, vp, vp, vp, vp, i64, i64, vp, vp, sz, vp]
+    lib.bp_embbag_bwd_update_grouped_workspace_bytes.argtypes = [cfgp, i64, i64, i32, ctypes.POINTER(sz)]
+    lib.bp_embbag_bwd_update_grouped.argtypes = [cfgp, vp, vp, vp, vp, vp, i64, vp, i64, i64, vp, vp, sz, vp]
     lib.bp_error_string.argtypes = [ctypes.c_int]
     lib.bp_error_string.restype = ctypes.c_char_p
     lib.bp_last_error_message.restype = ctypes.c_char_p
@@ -77,7 +81,8 @@ def load_library():
     lib.bp_profile_select.argtypes = [ctypes.c_uint64]
     lib.bp_profile_select.restype = ctypes.c_int
     for name in ("bp_oracle_plan_workspace_bytes", "bp_oracle_plan", "bp_cache_apply", "bp_embbag_fwd",
-                 "bp_embbag_bwd_update_workspace_bytes", "bp_embbag_bwd_update", "bp_version", "bp_profile_enable",
+                 "bp_embbag_bwd_update_workspace_bytes", "bp_embbag_bwd_update", "bp_version",
+                 "bp_embbag_bwd_update_grouped_workspace_bytes", "bp_embbag_bwd_update_grouped", "bp_profile_enable",
                  "bp_profile_collect", "bp_profile_num_kernels", "bp_profile_get"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -151,17 +156,21 @@ class Plan:
     evict_offsets: np.ndarray
     keep_offsets: np.ndarray
     occupancy: np.ndarray         # int64 [T] host
+    grouped_slots: "object" = None      # int32 [N] device (optional grouping)
+    grouped_lookups: "object" = None    # int32 [N] device
+    item_starts: "object" = None        # uint32 (as int32 tensor) device, trimmed to the item count
+    item_offsets: Optional[np.ndarray] = None   # int64 [T+1] host
 
 
-def bp_oracle_plan_workspace_bytes(cfg: bp_config, n_lookups: int, n_iters: int) -> int:
+def bp_oracle_plan_workspace_bytes(cfg: bp_config, n_lookups: int, n_iters: int, grouping: bool = False) -> int:
     out = ctypes.c_size_t(0)
     _check(load_library().bp_oracle_plan_workspace_bytes(ctypes.byref(cfg), int(n_lookups), int(n_iters),
-                                                         ctypes.byref(out)))
+                                                         int(bool(grouping)), ctypes.byref(out)))
     return int(out.value)
 
 
 def bp_oracle_plan(cfg: bp_config, ids, iter_offsets, list_capacity: Optional[int] = None, workspace=None,
-                   stream=None) -> Plan:
+                   stream=None, grouping: bool = False) -> Plan:
     """ids: int64 device tensor [N]; iter_offsets: int64 host array [T+1].  Output and workspace tensors are
     allocated here with torch (the library itself allocates nothing); list tensors are trimmed views."""
     import torch
@@ -173,7 +182,7 @@ def bp_oracle_plan(cfg: bp_config, ids, iter_offsets, list_capacity: Optional[in
     dev = ids.device
     cap = N if list_capacity is None else int(list_capacity)
     if workspace is None:
-        workspace = torch.empty(bp_oracle_plan_workspace_bytes(cfg, N, T), dtype=torch.uint8, device=dev)
+        workspace = torch.empty(bp_oracle_plan_workspace_bytes(cfg, N, T, grouping), dtype=torch.uint8, device=dev)
     i32 = dict(dtype=torch.int32, device=dev)
     i64 = dict(dtype=torch.int64, device=dev)
     t = dict(lookup_slots=torch.empty(max(N, 1), **i32),
@@ -182,6 +191,10 @@ def bp_oracle_plan(cfg: bp_config, ids, iter_offsets, list_capacity: Optional[in
              keep_ids=torch.empty(max(cap, 1), **i64), keep_ttl=torch.empty(max(cap, 1), **i32))
     h = dict(prefetch_offsets=np.zeros(T + 1, np.int64), evict_offsets=np.zeros(T + 1, np.int64),
              keep_offsets=np.zeros(T + 1, np.int64), occupancy=np.zeros(max(T, 1), np.int64))
+    if grouping:
+        t.update(grouped_slots=torch.empty(max(N, 1), **i32), grouped_lookups=torch.empty(max(N, 1), **i32),
+                 item_starts=torch.empty(max(N, 1), **i32))
+        h.update(item_offsets=np.zeros(T + 1, np.int64))
     p = _bp_plan()
     for k, v in t.items():
         setattr(p, k, v.data_ptr())
@@ -198,7 +211,11 @@ def bp_oracle_plan(cfg: bp_config, ids, iter_offsets, list_capacity: Optional[in
                 evict_ids=t["evict_ids"][:n_pf], evict_slots=t["evict_slots"][:n_pf],
                 keep_ids=t["keep_ids"][:n_k], keep_ttl=t["keep_ttl"][:n_k],
                 prefetch_offsets=h["prefetch_offsets"], evict_offsets=h["evict_offsets"],
-                keep_offsets=h["keep_offsets"], occupancy=h["occupancy"][:T])
+                keep_offsets=h["keep_offsets"], occupancy=h["occupancy"][:T],
+                grouped_slots=t["grouped_slots"][:N] if grouping else None,
+                grouped_lookups=t["grouped_lookups"][:N] if grouping else None,
+                item_starts=t["item_starts"][:int(h["item_offsets"][-1])] if grouping else None,
+                item_offsets=h["item_offsets"] if grouping else None)
 
 
 # ---------------------------------------------------------------------------------------------------
@@ -242,6 +259,23 @@ def bp_embbag_bwd_update(cfg: bp_config, cache_w, cache_state, lookup_slots, bag
     _check(load_library().bp_embbag_bwd_update(ctypes.byref(cfg), _ptr(cache_w), _ptr(cache_state),
                                                _ptr(lookup_slots), _ptr(bag_offsets), n, int(bags), _ptr(grad_out),
                                                _ptr(workspace), int(workspace.numel()), _stream(stream)))
+
+
+def bp_embbag_bwd_update_grouped_workspace_bytes(cfg: bp_config, n_lookups: int, bags: int, multi_hot: bool) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load_library().bp_embbag_bwd_update_grouped_workspace_bytes(ctypes.byref(cfg), int(n_lookups), int(bags),
+                                                                       int(bool(multi_hot)), ctypes.byref(out)))
+    return int(out.value)
+
+
+def bp_embbag_bwd_update_grouped(cfg: bp_config, cache_w, cache_state, grouped_slots, grouped_lookups, item_starts,
+                                 bag_offsets, bags: int, grad_out, workspace, stream=None) -> None:
+    """grouped_slots / grouped_lookups / item_starts: one batch's slices of the plan's grouping arrays."""
+    n = int(grouped_slots.numel())
+    _check(load_library().bp_embbag_bwd_update_grouped(
+        ctypes.byref(cfg), _ptr(cache_w), _ptr(cache_state), _ptr(grouped_slots), _ptr(grouped_lookups),
+        _ptr(item_starts), int(item_starts.numel()), _ptr(bag_offsets), n, int(bags), _ptr(grad_out), _ptr(workspace),
+        int(workspace.numel()), _stream(stream)))
 
 
 # ---------------------------------------------------------------------------------------------------

@@ -18,6 +18,10 @@ namespace bp {
 
 constexpr int kWave = 64;   // gfx950 wavefront
 
+// Lookups per work item of the backward pass at most (BP_BWD_CHUNK of the C header): the planner's optional
+// grouping and the backward kernels must cut the sorted lookups at the same places.
+constexpr int kBwdChunk = BP_BWD_CHUNK;
+
 // ---- error reporting ---------------------------------------------------------------------------
 void set_error(const char* fmt, ...) __attribute__((format(printf, 1, 2)));
 int fail(int status, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
@@ -80,6 +84,7 @@ enum KernelId {
     K_PLAN_LISTS,
     K_PLAN_JUMP,
     K_PLAN_SLOTS,
+    K_PLAN_GROUP,
     K_CACHE_EVICT,
     K_CACHE_PREFETCH,
     K_FWD,

@@ -22,7 +22,7 @@
 namespace bp {
 namespace {
 
-constexpr int kChunk = 32;        // sorted positions per work item at most
+constexpr int kChunk = kBwdChunk;  // sorted positions per work item at most
 constexpr int kMaxGridBlocks = 8192;
 
 // ---- 1. keys ---------------------------------------------------------------------------------
@@ -43,6 +43,21 @@ __global__ __launch_bounds__(256) void bwd_keys_kernel(const int32_t* __restrict
         bag = (uint32_t)lo;
     }
     vals[k] = bag;
+}
+
+// Grouped variant: bag of every lookup position (positions come grouped by row from the plan).
+__global__ __launch_bounds__(256) void bwd_bags_of_positions_kernel(const int32_t* __restrict__ positions,
+                                                                    const int64_t* __restrict__ bag_off, int64_t n,
+                                                                    int64_t bags, uint32_t* __restrict__ bag_of) {
+    const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (p >= n) return;
+    const int64_t k = positions[p];
+    int64_t lo = 0, hi = bags;                       // bag_off[lo] <= k < bag_off[hi]
+    while (hi - lo > 1) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (bag_off[mid] <= k) lo = mid; else hi = mid;
+    }
+    bag_of[p] = (uint32_t)lo;
 }
 
 // ---- 2. work items ---------------------------------------------------------------------------
@@ -170,12 +185,13 @@ template <int GW, bool BF16>
 __global__ __launch_bounds__(kRowBlock) void bwd_reduce_update_kernel(const uint32_t* __restrict__ keys,
                                                                      const uint32_t* __restrict__ bag_of,
                                                                      const uint32_t* __restrict__ item_start,
-                                                                     const uint32_t* __restrict__ n_items_ptr, uint32_t n,
-                                                                     int64_t C, const float* __restrict__ grad,
+                                                                     const uint32_t* __restrict__ n_items_ptr,
+                                                                     uint32_t n_items_host, uint32_t n, int64_t C,
+                                                                     const float* __restrict__ grad,
                                                                      uint4* cache_w, float* cache_s, double* partial,
                                                                      UpdateParams u) {
     constexpr int N = Piece<BF16>::N;
-    const uint32_t W = *n_items_ptr;
+    const uint32_t W = n_items_ptr ? *n_items_ptr : n_items_host;   // counted on the device, or known to the host
     const int c = threadIdx.x % GW;
     const bool active = c < u.lpr;
     const uint32_t groups = gridDim.x * (kRowBlock / GW);
@@ -222,12 +238,13 @@ __global__ __launch_bounds__(kRowBlock) void bwd_reduce_update_kernel(const uint
 template <int GW, bool BF16>
 __global__ __launch_bounds__(kRowBlock) void bwd_combine_update_kernel(const uint32_t* __restrict__ keys,
                                                                       const uint32_t* __restrict__ item_start,
-                                                                      const uint32_t* __restrict__ n_items_ptr, uint32_t n,
-                                                                      int64_t C, uint4* cache_w, float* cache_s,
+                                                                      const uint32_t* __restrict__ n_items_ptr,
+                                                                      uint32_t n_items_host, uint32_t n, int64_t C,
+                                                                      uint4* cache_w, float* cache_s,
                                                                       const double* __restrict__ partial, UpdateParams u) {
     constexpr int N = Piece<BF16>::N;
     constexpr int G = kWave / GW;                     // lane groups per wavefront
-    const uint32_t W = *n_items_ptr;
+    const uint32_t W = n_items_ptr ? *n_items_ptr : n_items_host;   // counted on the device, or known to the host
     const int lane = threadIdx.x % kWave;
     const int c = lane % GW, j = lane / GW;
     const bool active = c < u.lpr;
@@ -296,9 +313,10 @@ BwdWorkspace carve_bwd(void* base, size_t cap, int64_t n, int dim) {
 
 struct BwdLaunch {
     const bp_config* cfg;
-    const BwdWorkspace* w;
-    const uint32_t *skeys, *sbags;
-    const uint32_t* n_items;
+    double* partial;
+    const uint32_t *skeys, *sbags, *item_start;
+    const uint32_t* n_items;       // device count, or NULL when n_items_host is given
+    uint32_t n_items_host;
     int64_t n;
     const float* grad;
     void* cache_w;
@@ -308,16 +326,19 @@ struct BwdLaunch {
     int run() {
         UpdateParams u{cfg->optimizer, cfg->lr, cfg->eps, (int)(row_bytes(cfg) / 16), cfg->dim};
         const int groups_per_block = kRowBlock / GW;
-        int64_t blocks = ceil_div(n, groups_per_block);
+        const int64_t items_bound = n_items ? n : (int64_t)n_items_host;     // at most one item per lookup
+        int64_t blocks = ceil_div(items_bound, groups_per_block);
         if (blocks > kMaxGridBlocks) blocks = kMaxGridBlocks;
+        if (blocks < 1) blocks = 1;
         BP_LAUNCH(K_BWD_REDUCE_UPDATE, (bwd_reduce_update_kernel<GW, BF16>), dim3((unsigned)blocks), dim3(kRowBlock), 0, stream,
-                  skeys, sbags, (const uint32_t*)w->item_start, n_items, (uint32_t)n, cfg->capacity, grad, (uint4*)cache_w,
-                  (float*)cache_s, w->partial, u);
-        int64_t cblocks = ceil_div(n, kRowBlock / kWave);          // one wavefront per item
+                  skeys, sbags, item_start, n_items, n_items_host, (uint32_t)n, cfg->capacity, grad, (uint4*)cache_w,
+                  (float*)cache_s, partial, u);
+        int64_t cblocks = ceil_div(items_bound, kRowBlock / kWave);          // one wavefront per item
+        if (cblocks < 1) cblocks = 1;
         if (cblocks > kMaxGridBlocks) cblocks = kMaxGridBlocks;
         BP_LAUNCH(K_BWD_COMBINE_UPDATE, (bwd_combine_update_kernel<GW, BF16>), dim3((unsigned)cblocks), dim3(kRowBlock), 0,
-                  stream, skeys, (const uint32_t*)w->item_start, n_items, (uint32_t)n, cfg->capacity, (uint4*)cache_w,
-                  (float*)cache_s, (const double*)w->partial, u);
+                  stream, skeys, item_start, n_items, n_items_host, (uint32_t)n, cfg->capacity, (uint4*)cache_w,
+                  (float*)cache_s, (const double*)partial, u);
         return BP_OK;
     }
 };
@@ -376,6 +397,65 @@ BP_EXPORT int bp_embbag_bwd_update(const bp_config* cfg, void* cache_w, void* ca
                                                                     w.scan_partials, AddOp(), 0u, stream)));
     const uint32_t* n_items = w.scan_partials + scan_num_tiles(n);
 
-    BwdLaunch l{cfg, &w, skeys, sbags, n_items, n, grad_out, cache_w, cache_state, stream};
+    BwdLaunch l{cfg, w.partial, skeys, sbags, w.item_start, n_items, 0u, n, grad_out, cache_w, cache_state, stream};
+    return dispatch_row((int)(row_bytes(cfg) / 16), cfg->weight_dtype == BP_BF16, l);
+}
+
+// ---- grouped variant: the plan already lists the batch's lookups grouped by row ---------------------------------
+namespace bp {
+namespace {
+struct GroupedWorkspace {
+    uint32_t* bag_of;
+    double* partial;
+    size_t bytes;
+};
+GroupedWorkspace carve_grouped(void* base, size_t cap, int64_t n, int dim, bool multi_hot) {
+    Carver c(base, cap);
+    GroupedWorkspace w{};
+    const size_t m = (size_t)(n > 0 ? n : 1);
+    w.bag_of = multi_hot ? c.take<uint32_t>(m) : nullptr;
+    w.partial = c.take<double>((2 * (m / kChunk + 2)) * (size_t)dim);
+    w.bytes = c.used();
+    return w;
+}
+}  // namespace
+}  // namespace bp
+
+BP_EXPORT int bp_embbag_bwd_update_grouped_workspace_bytes(const bp_config* cfg, int64_t n_lookups, int64_t bags,
+                                                           int32_t multi_hot, size_t* bytes) {
+    if (!bytes) return fail(BP_ERR_INVALID_ARG, "bytes is NULL");
+    BP_TRY(check_bwd_args(cfg, n_lookups, bags));
+    *bytes = carve_grouped(nullptr, 0, n_lookups, cfg->dim, multi_hot != 0).bytes;
+    return BP_OK;
+}
+
+BP_EXPORT int bp_embbag_bwd_update_grouped(const bp_config* cfg, void* cache_w, void* cache_state,
+                                           const int32_t* grouped_slots, const int32_t* grouped_lookups,
+                                           const uint32_t* item_starts, int64_t n_items, const int64_t* bag_offsets,
+                                           int64_t n_lookups, int64_t bags, const float* grad_out, void* workspace,
+                                           size_t workspace_bytes, void* stream_) {
+    hipStream_t stream = (hipStream_t)stream_;
+    const int64_t n = n_lookups;
+    BP_TRY(check_bwd_args(cfg, n, bags));
+    if (n == 0) return BP_OK;
+    if (n_items < 1 || n_items > n) return fail(BP_ERR_INVALID_ARG, "n_items %lld outside [1, n_lookups]", (long long)n_items);
+    if (!bag_offsets && n != bags)
+        return fail(BP_ERR_INVALID_ARG, "bag_offsets is NULL but n_lookups %lld != bags %lld", (long long)n, (long long)bags);
+    if (!cache_w || !grouped_slots || !grouped_lookups || !item_starts || !grad_out) return fail(BP_ERR_INVALID_ARG, "NULL pointer");
+    if (cfg->optimizer != BP_SGD && !cache_state) return fail(BP_ERR_INVALID_ARG, "cache_state is NULL");
+    if (((uintptr_t)cache_w | (uintptr_t)cache_state | (uintptr_t)grad_out) & 15)
+        return fail(BP_ERR_INVALID_ARG, "cache_w, cache_state and grad_out must be 16-byte aligned");
+    if (!workspace || ((uintptr_t)workspace & 255)) return fail(BP_ERR_INVALID_ARG, "workspace NULL or not 256-byte aligned");
+    GroupedWorkspace w = carve_grouped(workspace, workspace_bytes, n, cfg->dim, bag_offsets != nullptr);
+    if (w.bytes > workspace_bytes)
+        return fail(BP_ERR_WORKSPACE_TOO_SMALL, "workspace %zu < required %zu bytes", workspace_bytes, w.bytes);
+    const uint32_t* bag_of = reinterpret_cast<const uint32_t*>(grouped_lookups);   // one lookup per bag: position == bag
+    if (bag_offsets) {
+        BP_LAUNCH(K_BWD_KEYS, bwd_bags_of_positions_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, stream,
+                  grouped_lookups, bag_offsets, n, bags, w.bag_of);
+        bag_of = w.bag_of;
+    }
+    BwdLaunch l{cfg, w.partial, reinterpret_cast<const uint32_t*>(grouped_slots), bag_of, item_starts, nullptr,
+                (uint32_t)n_items, n, grad_out, cache_w, cache_state, stream};
     return dispatch_row((int)(row_bytes(cfg) / 16), cfg->weight_dtype == BP_BF16, l);
 }

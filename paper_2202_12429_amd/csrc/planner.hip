@@ -18,6 +18,8 @@
 //      C are the initial slots, position C + e holds the slot freed by the e-th eviction, i.e. the slot
 //      of an earlier miss.  Following those links is pointer jumping, ceil(log2 T) + 1 rounds.
 //   7. slots of pairs -> list slots and the per-lookup slot map
+//   8. (optional) one more stable pass on the batch bits lists every batch's lookups grouped by row, with the
+//      work-item cuts the grouped backward pass uses, so that the backward pass need not sort
 #include <vector>
 
 #include "common.h"
@@ -319,6 +321,48 @@ __global__ __launch_bounds__(kBlock) void plan_lookup_slots_kernel(int64_t N, co
     if (p < N) lookup_slots[pos[p]] = slot_of_pair[uq[p]];
 }
 
+// ---- 8. lookups of every batch grouped by row (optional) ---------------------------------------
+// key <- (pair index << iter_bits) | batch: a stable sort on the batch bits then lists every batch's lookups
+// grouped by id (pairs are numbered in id order) and in lookup order inside a group.
+__global__ __launch_bounds__(kBlock) void plan_group_keys_kernel(int64_t N, int ib, const uint32_t* __restrict__ uq,
+                                                                 uint64_t* keys) {
+    const int64_t p = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (p < N) keys[p] = ((uint64_t)uq[p] << ib) | (keys[p] & ((uint64_t(1) << ib) - 1));
+}
+
+// A work item of the grouped backward pass starts where the row changes and at every multiple of kBwdChunk
+// positions counted from the batch's first lookup.
+struct ItemFlagIn {
+    const uint64_t* gkeys;
+    const int64_t* iter_off;
+    int ib;
+    __device__ __forceinline__ uint32_t operator()(int64_t p) const {
+        const uint64_t k = gkeys[p];
+        const int64_t rel = p - iter_off[k & ((uint64_t(1) << ib) - 1)];
+        return (rel % kBwdChunk == 0 || (gkeys[p - 1] >> ib) != (k >> ib)) ? 1u : 0u;   // rel == 0 guards p == 0
+    }
+};
+struct GroupOut {
+    const uint64_t* gkeys;
+    const uint32_t* gpos;
+    const int64_t* iter_off;
+    const int32_t* slot_of_pair;
+    int ib;
+    int32_t* grouped_slots;
+    int32_t* grouped_lookups;
+    uint32_t* item_starts;
+    int64_t* item_off;     // device copy of the CSR offsets, [T+1], pre-filled with -1
+    __device__ __forceinline__ void operator()(int64_t p, uint32_t exc, uint32_t inc) const {
+        const uint64_t k = gkeys[p];
+        const uint32_t i = (uint32_t)(k & ((uint64_t(1) << ib) - 1));
+        const int64_t base = iter_off[i];
+        grouped_slots[p] = slot_of_pair[k >> ib];
+        grouped_lookups[p] = (int32_t)((int64_t)gpos[p] - base);
+        if (inc != exc) item_starts[exc] = (uint32_t)(p - base);
+        if (p == base) item_off[i] = exc;
+    }
+};
+
 template <typename T>
 __global__ __launch_bounds__(kBlock) void fill_kernel(T* p, int64_t n, T v) {
     const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
@@ -339,10 +383,13 @@ struct PlanWorkspace {
     int32_t* ttl;
     uint32_t *chain, *key2_a, *key2_b, *val2_a, *val2_b, *missord, *evict_pair, *par;
     int32_t* slot_of_pair;
+    uint64_t* keys_c;      // grouping only
+    uint32_t* pos_c;
+    int64_t* item_off;
     size_t bytes;
 };
 
-PlanWorkspace carve_plan(void* base, size_t cap, int64_t N, int T, int Lcap) {
+PlanWorkspace carve_plan(void* base, size_t cap, int64_t N, int T, int Lcap, bool grouping) {
     Carver c(base, cap);
     PlanWorkspace w{};
     const size_t n = (size_t)(N > 0 ? N : 1);
@@ -373,6 +420,11 @@ PlanWorkspace carve_plan(void* base, size_t cap, int64_t N, int T, int Lcap) {
     w.evict_pair = c.take<uint32_t>(n);
     w.par = c.take<uint32_t>(n);
     w.slot_of_pair = c.take<int32_t>(n);
+    if (grouping) {
+        w.keys_c = c.take<uint64_t>(n);
+        w.pos_c = c.take<uint32_t>(n);
+        w.item_off = c.take<int64_t>(T + 1);
+    }
     w.bytes = c.used();
     return w;
 }
@@ -392,11 +444,12 @@ inline dim3 grid_for(int64_t n) { return dim3((unsigned)(n > 0 ? ceil_div(n, kBl
 
 using namespace bp;
 
-BP_EXPORT int bp_oracle_plan_workspace_bytes(const bp_config* cfg, int64_t n_lookups, int32_t n_iters, size_t* bytes) {
+BP_EXPORT int bp_oracle_plan_workspace_bytes(const bp_config* cfg, int64_t n_lookups, int32_t n_iters, int32_t with_grouping,
+                                             size_t* bytes) {
     if (!bytes) return fail(BP_ERR_INVALID_ARG, "bytes is NULL");
     BP_TRY(check_plan_args(cfg, n_lookups, n_iters));
     const int Lcap = cfg->lookahead < n_iters ? cfg->lookahead : n_iters;
-    *bytes = carve_plan(nullptr, 0, n_lookups, n_iters, Lcap).bytes;
+    *bytes = carve_plan(nullptr, 0, n_lookups, n_iters, Lcap, with_grouping != 0).bytes;
     return BP_OK;
 }
 
@@ -420,7 +473,10 @@ BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int
 
     const int Lcap = cfg->lookahead < T ? cfg->lookahead : T;
     const int64_t C = cfg->capacity;
-    PlanWorkspace w = carve_plan(workspace, workspace_bytes, N, T, Lcap);
+    const bool grouping = plan->grouped_slots || plan->grouped_lookups || plan->item_starts || plan->item_offsets;
+    if (grouping && !(plan->grouped_slots && plan->grouped_lookups && plan->item_starts && plan->item_offsets))
+        return fail(BP_ERR_INVALID_ARG, "the grouping outputs of the plan must be all set or all NULL");
+    PlanWorkspace w = carve_plan(workspace, workspace_bytes, N, T, Lcap, grouping);
     if (w.bytes > workspace_bytes)
         return fail(BP_ERR_WORKSPACE_TOO_SMALL, "workspace %zu < required %zu bytes", workspace_bytes, w.bytes);
 
@@ -432,6 +488,8 @@ BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int
         for (int i = 0; i <= T; ++i) plan->prefetch_offsets[i] = plan->evict_offsets[i] = plan->keep_offsets[i] = 0;
         for (int i = 0; i < T; ++i) plan->occupancy[i] = 0;
         plan->L_eff = cfg->lookahead;
+        if (grouping)
+            for (int i = 0; i <= T; ++i) plan->item_offsets[i] = 0;
         return BP_OK;
     }
 
@@ -527,6 +585,27 @@ BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int
     BP_LAUNCH(K_PLAN_SLOTS, plan_lookup_slots_kernel, grid_for(N), dim3(kBlock), 0, stream, N, spos, (const uint32_t*)uq,
               (const int32_t*)w.slot_of_pair, plan->lookup_slots);
 
+    // ---- 8. grouping for the backward pass
+    uint32_t n_items = 0;
+    if (grouping) {
+        uint64_t* gk_a = const_cast<uint64_t*>(skeys);
+        uint32_t* gp_a = const_cast<uint32_t*>(spos);
+        BP_LAUNCH(K_PLAN_GROUP, plan_group_keys_kernel, grid_for(N), dim3(kBlock), 0, stream, N, ib, (const uint32_t*)uq, gk_a);
+        bool g_in_b = false;
+        BP_TRY((radix_sort_pairs<uint64_t, kPlanSortIPT>(gk_a, w.keys_c, gp_a, w.pos_c, N, 0, ib, w.sort_temp, stream, &g_in_b)));
+        const uint64_t* gkeys = g_in_b ? w.keys_c : gk_a;
+        const uint32_t* gpos = g_in_b ? w.pos_c : gp_a;
+        BP_LAUNCH(K_FILL, fill_kernel<int64_t>, grid_for(T + 1), dim3(kBlock), 0, stream, w.item_off, (int64_t)(T + 1),
+                  (int64_t)-1);
+        BP_TRY((device_scan<uint32_t, AddOp, ItemFlagIn, GroupOut>(
+            ItemFlagIn{gkeys, w.iter_off, ib},
+            GroupOut{gkeys, gpos, w.iter_off, w.slot_of_pair, ib, plan->grouped_slots, plan->grouped_lookups,
+                     plan->item_starts, w.item_off},
+            N, w.scan_partials32, AddOp(), 0u, stream)));
+        BP_HIP(hipMemcpyAsync(&n_items, w.scan_partials32 + scan_num_tiles(N), sizeof(uint32_t), hipMemcpyDeviceToHost, stream));
+        BP_HIP(hipMemcpyAsync(plan->item_offsets, w.item_off, sizeof(int64_t) * (T + 1), hipMemcpyDeviceToHost, stream));
+    }
+
     // ---- CSR offsets to the host
     uint64_t htot = 0;
     std::vector<uint32_t> hpair((size_t)T + 1);
@@ -542,6 +621,11 @@ BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int
     for (int i = T - 1; i >= 0; --i) {   // batches without lookups own no pair: their lists are empty
         if (plan->prefetch_offsets[i] < 0) plan->prefetch_offsets[i] = plan->prefetch_offsets[i + 1];
         if (plan->evict_offsets[i] < 0) plan->evict_offsets[i] = plan->evict_offsets[i + 1];
+    }
+    if (grouping) {
+        plan->item_offsets[T] = n_items;
+        for (int i = T - 1; i >= 0; --i)
+            if (plan->item_offsets[i] < 0) plan->item_offsets[i] = plan->item_offsets[i + 1];
     }
     if (n_miss != n_evict) return fail(BP_ERR_HIP, "internal: %lld prefetches but %lld evictions", (long long)n_miss, (long long)n_evict);
     return BP_OK;

@@ -1,15 +1,17 @@
-"""Orchestration of the four library calls over a planned trace (no arithmetic here).
+"""Orchestration of the library calls over a planned trace (no arithmetic here).
 
     trainer = CachedEmbeddingTrainer(cfg, backing_w, backing_state)      # cache + workspaces in HBM
     trainer.plan(ids_dev, iter_offsets)                                  # bp_oracle_plan
     for i in range(T):
         trainer.maintain(i)                                              # bp_cache_apply(E_{i-1}, P_i)
-        out = trainer.forward(i, bag_offsets_dev)                        # bp_embbag_fwd
-        trainer.backward_update(i, bag_offsets_dev, grad_out)            # bp_embbag_bwd_update
+        out = trainer.forward(i, bag_offsets_dev, bags)                  # bp_embbag_fwd
+        trainer.backward_update(i, bag_offsets_dev, bags, grad_out)      # bp_embbag_bwd_update[_grouped]
     trainer.flush()                                                      # bp_cache_apply(E_{T-1}, {})
 
 The order of calls is the synchronous schedule of Section 3.2: the write-backs of batch i-1 are applied before
 the prefetches of batch i, so a row is never fetched while an update to it is still only in the cache.
+With grouping=True (default) the plan also lists every batch's lookups grouped by row and the backward pass
+uses bp_embbag_bwd_update_grouped (no sort at run time); with grouping=False it sorts the slots itself.
 """
 from __future__ import annotations
 
@@ -30,12 +32,13 @@ def state_shape(rows: int, dim: int, optimizer: int):
 
 class CachedEmbeddingTrainer:
     def __init__(self, cfg: B.bp_config, backing_w, backing_state=None, device="cuda:0", max_lookups: int = 0,
-                 max_bags: int = 0):
+                 max_bags: int = 0, grouping: bool = True):
         import torch
         self.cfg = cfg
         self.device = torch.device(device)
         self.backing_w = backing_w
         self.backing_state = backing_state
+        self.grouping = grouping
         wdt = torch.float32 if cfg.weight_dtype == B.F32 else torch.bfloat16
         C, D = int(cfg.capacity), int(cfg.dim)
         self.cache_w = torch.zeros((C, D), dtype=wdt, device=self.device)
@@ -50,16 +53,18 @@ class CachedEmbeddingTrainer:
 
     def _reserve(self, n: int, bags: int):
         import torch
-        need = B.bp_embbag_bwd_update_workspace_bytes(self.cfg, n, bags)
+        need = max(B.bp_embbag_bwd_update_workspace_bytes(self.cfg, n, bags),
+                   B.bp_embbag_bwd_update_grouped_workspace_bytes(self.cfg, n, bags, True))
         if self._bwd_ws is None or self._bwd_ws.numel() < need:
             self._bwd_ws = torch.empty(need, dtype=torch.uint8, device=self.device)
         if self._out is None or self._out.shape[0] < bags:
             self._out = torch.empty((bags, int(self.cfg.dim)), dtype=torch.float32, device=self.device)
 
     # ---- (1)
-    def plan(self, ids_dev, iter_offsets, list_capacity: Optional[int] = None) -> B.Plan:
+    def plan(self, ids_dev, iter_offsets, list_capacity: Optional[int] = None, workspace=None) -> B.Plan:
         self.iter_offsets = np.ascontiguousarray(iter_offsets, dtype=np.int64)
-        self.plan_ = B.bp_oracle_plan(self.cfg, ids_dev, self.iter_offsets, list_capacity=list_capacity)
+        self.plan_ = B.bp_oracle_plan(self.cfg, ids_dev, self.iter_offsets, list_capacity=list_capacity,
+                                      workspace=workspace, grouping=self.grouping)
         return self.plan_
 
     def _slice(self, which: str, i: int):
@@ -94,8 +99,18 @@ class CachedEmbeddingTrainer:
         return out
 
     # ---- (4)
-    def backward_update(self, i: int, bag_offsets_dev, bags: int, grad_out, stream=None) -> None:
-        sl = self.slots(i)
-        self._reserve(int(sl.numel()), bags)
-        B.bp_embbag_bwd_update(self.cfg, self.cache_w, self.cache_state, sl, bag_offsets_dev, bags, grad_out,
-                               self._bwd_ws, stream=stream)
+    def backward_update(self, i: int, bag_offsets_dev, bags: int, grad_out, stream=None, grouped: Optional[bool] = None) -> None:
+        p = self.plan_
+        a, b = int(self.iter_offsets[i]), int(self.iter_offsets[i + 1])
+        self._reserve(b - a, bags)
+        use_grouped = (p.grouped_slots is not None) if grouped is None else grouped
+        if use_grouped:
+            if b == a:
+                return
+            ia, ib = int(p.item_offsets[i]), int(p.item_offsets[i + 1])
+            B.bp_embbag_bwd_update_grouped(self.cfg, self.cache_w, self.cache_state, p.grouped_slots[a:b],
+                                           p.grouped_lookups[a:b], p.item_starts[ia:ib], bag_offsets_dev, bags,
+                                           grad_out, self._bwd_ws, stream=stream)
+        else:
+            B.bp_embbag_bwd_update(self.cfg, self.cache_w, self.cache_state, p.lookup_slots[a:b], bag_offsets_dev,
+                                   bags, grad_out, self._bwd_ws, stream=stream)

@@ -116,6 +116,20 @@ def run_bwd(bp, cfg, w, state, slots, off, bags, grad, onehot):
     return wd.cpu(), None if sd is None else sd.cpu().numpy()
 
 
+def run_bwd_grouped(bp, cfg, w, state, slots, off, bags, grad, onehot):
+    valid = (slots >= 0) & (slots < cfg.capacity)
+    assert valid.all()
+    gs, gl, st, ioff = oracle.group_lookups(slots.astype(np.int64), np.array([0, len(slots)]), slots)
+    wd = w.cuda()
+    sd = None if state is None else torch.from_numpy(state).cuda()
+    ws = torch.empty(bp.bp_embbag_bwd_update_grouped_workspace_bytes(cfg, len(slots), bags, not onehot),
+                     dtype=torch.uint8, device="cuda")
+    bp.bp_embbag_bwd_update_grouped(cfg, wd, sd, dev(gs), dev(gl), dev(st.view(np.int32)), None if onehot else dev(off),
+                                    bags, dev(grad), ws)
+    torch.cuda.synchronize()
+    return wd.cpu(), None if sd is None else sd.cpu().numpy()
+
+
 @pytest.mark.parametrize("D,dtype,optimizer", [(16, "f32", "sgd"), (48, "f32", "adagrad"), (64, "f32", "sgd"),
                                                (128, "bf16", "adagrad_rowwise"), (32, "bf16", "adagrad"),
                                                (48, "f32", "adagrad_rowwise"), (8, "bf16", "sgd")])
@@ -137,6 +151,10 @@ def test_backward_update(bp, D, dtype, optimizer, max_len):
     grad = rng.standard_normal((bags, D)).astype(np.float32)
     got_w, got_s = run_bwd(bp, cfg, w, state, slots, off, bags, grad, max_len == 1)
     again_w, again_s = run_bwd(bp, cfg, w, state, slots, off, bags, grad, max_len == 1)
+    # the grouped entry point on the same batch (grouping by slot is a grouping by row) gives the same bits:
+    # the fp64 sums of these gradients are exact, so the cut of a row's lookups into items does not matter
+    grp_w, grp_s = run_bwd_grouped(bp, cfg, w, state, slots, off, bags, grad, max_len == 1)
+    assert np.array_equal(cache_numpy(grp_w), cache_numpy(got_w)) and (got_s is None or np.array_equal(grp_s, got_s))
     assert torch.equal(got_w.view(torch.int16) if dtype == "bf16" else got_w,
                        again_w.view(torch.int16) if dtype == "bf16" else again_w), "backward is not deterministic"
     want_w = cache_numpy(w)
@@ -235,11 +253,24 @@ def assert_plan_equal(got, want, N):
     assert np.array_equal(got.lookup_slots.cpu().numpy(), want.lookup_slots[:N]), "lookup_slots"
 
 
+def assert_grouping_equal(got, want, ids, off):
+    """The plan's optional grouping against the oracle's definition of it (index work: bit-exact)."""
+    gs, gl, st, ioff = oracle.group_lookups(ids, off, want.lookup_slots)
+    assert np.array_equal(got.item_offsets, ioff), "item_offsets"
+    assert np.array_equal(got.grouped_slots.cpu().numpy(), gs), "grouped_slots"
+    assert np.array_equal(got.grouped_lookups.cpu().numpy(), gl), "grouped_lookups"
+    assert np.array_equal(got.item_starts.cpu().numpy().view(np.uint32), st), "item_starts"
+
+
 def plan_both(bp, ids, off, R, L, C):
     cfg = bp.make_config(R, C, 16, lookahead=L)
-    got = bp.bp_oracle_plan(cfg, dev(ids), off)
+    got = bp.bp_oracle_plan(cfg, dev(ids), off, grouping=True)
     want = oracle.plan(ids, off, R, L, C)
     assert_plan_equal(got, want, len(ids))
+    assert_grouping_equal(got, want, ids, off)
+    plain = bp.bp_oracle_plan(cfg, dev(ids), off)                  # without the optional outputs: same plan
+    assert_plan_equal(plain, want, len(ids))
+    assert plain.grouped_slots is None
     return got, want
 
 
@@ -320,7 +351,7 @@ def test_plan_errors(bp):
 # ---------------------------------------------------------------------------------------------------
 # whole path
 # ---------------------------------------------------------------------------------------------------
-def run_end_to_end(cfg, trace, pinned=True, capacity=None):
+def run_end_to_end(cfg, trace, pinned=True, capacity=None, grouping=True):
     T = trace.iter_offsets.shape[0] - 1
     Wo, So, outs = helpers.oracle_uncached(cfg, trace)
     max_bag = cfg.bag_max
@@ -328,7 +359,8 @@ def run_end_to_end(cfg, trace, pinned=True, capacity=None):
     def check(i, out):
         helpers.assert_outputs_close(out.cpu().numpy(), outs[i], max_bag, same_table=(i == 0))
 
-    tr, plan, W, S = helpers.gpu_cached_training(cfg, trace, pinned=pinned, capacity=capacity, check_outputs=check)
+    tr, plan, W, S = helpers.gpu_cached_training(cfg, trace, pinned=pinned, capacity=capacity, check_outputs=check,
+                                                 grouping=grouping)
     C = cfg.capacity if capacity is None else capacity
     want_plan = oracle.plan(trace.ids, trace.iter_offsets, cfg.total_rows, cfg.lookahead, C)
     assert_plan_equal(plan, want_plan, trace.n_lookups)
@@ -351,13 +383,16 @@ def test_end_to_end_tiny_config(bp):
     cfg = workloads.CONFIGS[0]
     plan = run_end_to_end(cfg, workloads.make_trace(cfg))
     assert plan.L_eff == 20
+    plan = run_end_to_end(cfg, workloads.make_trace(cfg), grouping=False)       # backward sorts the slots itself
+    assert plan.L_eff == 20
 
 
+@pytest.mark.parametrize("grouping", [True, False])
 @pytest.mark.parametrize("optimizer,dtype,bag_max,capacity,pinned", [
     ("adagrad", "f32", 1, 1400, True), ("adagrad_rowwise", "bf16", 1, 4096, True), ("sgd", "f32", 6, 3000, False),
     ("adagrad", "bf16", 4, 2600, True)])
-def test_end_to_end_variants(bp, optimizer, dtype, bag_max, capacity, pinned):
-    say(f"end to end: {optimizer} {dtype} bag_max={bag_max} C={capacity}")
+def test_end_to_end_variants(bp, optimizer, dtype, bag_max, capacity, pinned, grouping):
+    say(f"end to end: {optimizer} {dtype} bag_max={bag_max} C={capacity} grouping={grouping}")
     cfg = workloads.get_config(0, optimizer=optimizer, weight_dtype=dtype, bag_max=bag_max, capacity=capacity,
                                batch=128 if bag_max > 1 else 256, iterations=30)
-    run_end_to_end(cfg, workloads.make_trace(cfg), pinned=pinned)
+    run_end_to_end(cfg, workloads.make_trace(cfg), pinned=pinned, grouping=grouping)
