@@ -154,15 +154,15 @@ def main() -> int:
     # ---- GPU: plan (timed), then the trace
     trainer = CachedEmbeddingTrainer(bcfg, backing_w, backing_s, device=dev, max_lookups=int(n_per_iter.max()),
                                      max_bags=bags)
-    ws = torch.empty(bp.bp_oracle_plan_workspace_bytes(bcfg, trace.n_lookups, T), dtype=torch.uint8, device=dev)
+    ws = torch.empty(bp.bp_oracle_plan_workspace_bytes(bcfg, trace.n_lookups, T, grouping=True), dtype=torch.uint8,
+                     device=dev)
     torch.cuda.synchronize()
     plan_times = []
     for rep in range(3):
         t0 = time.perf_counter()
-        trainer.plan_ = bp.bp_oracle_plan(bcfg, ids_dev, trace.iter_offsets, workspace=ws)
+        trainer.plan(ids_dev, trace.iter_offsets, workspace=ws)     # with the grouping the backward pass consumes
         torch.cuda.synchronize()
         plan_times.append(time.perf_counter() - t0)
-    trainer.iter_offsets = np.ascontiguousarray(trace.iter_offsets, dtype=np.int64)
     plan = trainer.plan_
     t_plan = float(np.median(plan_times))
     del ws
@@ -249,7 +249,7 @@ def main() -> int:
     kernel_ms = {
         "cache_apply": per_step(["cache_evict", "cache_prefetch"]),
         "fwd": per_step(["embbag_fwd"]),
-        "bwd_sort_and_items": per_step(["bwd_keys"] + sort_scan),
+        "bwd_sort_and_items": per_step(["bwd_keys"] + sort_scan),      # zero with the plan-provided grouping
         "bwd_reduce_update": per_step(["bwd_reduce_update"]),
         "bwd_combine_update": per_step(["bwd_combine_update"]),
     }

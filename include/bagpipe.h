@@ -95,7 +95,7 @@ typedef struct bp_plan {
     int64_t* evict_offsets;    /* [T+1] */
     int64_t* keep_offsets;     /* [T+1] */
     int64_t* occupancy;        /* [T] rows resident while batch i trains */
-    /* optional (all four NULL, or all four set): every batch's lookups grouped by row, which is a by-product of the
+    /* optional (all six NULL, or all six set): every batch's lookups grouped by row, which is a by-product of the
      * planner's sort and lets bp_embbag_bwd_update_grouped skip its own sort.  Inside a batch the lookups are
      * ordered by id ascending and, for one id, by lookup position ascending.  A work item is a maximal run of
      * consecutive grouped lookups of one row that does not cross a multiple of BP_BWD_CHUNK positions (counted
@@ -104,6 +104,9 @@ typedef struct bp_plan {
     int32_t* grouped_lookups;  /* device [n_lookups] its position, relative to the batch's first lookup */
     uint32_t* item_starts;     /* device [n_lookups] first grouped lookup of each work item, relative to the batch */
     int64_t* item_offsets;     /* host [T+1] CSR offsets of the batches into item_starts */
+    uint32_t* split_starts;    /* device [n_lookups / BP_BWD_CHUNK + 1] first grouped lookup (relative to the batch) of
+                                  every row whose lookups span several work items */
+    int64_t* split_offsets;    /* host [T+1] CSR offsets of the batches into split_starts */
     /* scalar results */
     int32_t L_eff;
     int64_t peak_occupancy;
@@ -185,6 +188,8 @@ int bp_embbag_bwd_update(const bp_config* cfg, void* cache_w, void* cache_state,
  *
  * grouped_slots / grouped_lookups  device, the batch's slices [iter_offsets[i], iter_offsets[i+1]) of the plan arrays
  * item_starts, n_items             device, the batch's slice [item_offsets[i], item_offsets[i+1]) and its length
+ * split_starts, n_split            device, the batch's slice [split_offsets[i], split_offsets[i+1]) and its length
+ *                                  (n_split may be 0)
  * workspace                        device, bp_embbag_bwd_update_grouped_workspace_bytes() bytes (multi_hot != 0 when
  *                                  bag_offsets is not NULL), 256-byte aligned
  * Other arguments, limits and error behaviour as for bp_embbag_bwd_update.  Asynchronous.
@@ -193,7 +198,7 @@ int bp_embbag_bwd_update_grouped_workspace_bytes(const bp_config* cfg, int64_t n
                                                  int32_t multi_hot, size_t* bytes);
 int bp_embbag_bwd_update_grouped(const bp_config* cfg, void* cache_w, void* cache_state, const int32_t* grouped_slots,
                                  const int32_t* grouped_lookups, const uint32_t* item_starts, int64_t n_items,
-                                 const int64_t* bag_offsets, int64_t n_lookups, int64_t bags, const float* grad_out,
+                                 const uint32_t* split_starts, int64_t n_split, const int64_t* bag_offsets, int64_t n_lookups, int64_t bags, const float* grad_out,
                                  void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------------

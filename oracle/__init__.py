@@ -59,7 +59,7 @@ def _load():
         _lib.orc_train_iter.restype = i32
         _lib.orc_train_iter.argtypes = [p, p, i64, i64, i32, i32, ctypes.c_float, ctypes.c_float, p, i64, p, i64, p, p]
         _lib.orc_group_lookups.restype = i64
-        _lib.orc_group_lookups.argtypes = [p, p, i64, p, i64, p, p, p, p]
+        _lib.orc_group_lookups.argtypes = [p, p, i64, p, i64, p, p, p, p, p, p]
         _lib.orc_cache_apply.restype = i32
         _lib.orc_cache_apply.argtypes = [p, p, p, p, i64, i64, i64, i32, i32, p, p, i64, p, p, i64]
     return _lib
@@ -193,7 +193,7 @@ def cache_apply(cache_w, cache_state, host_w, host_state, D, dtype, optimizer, e
 
 def group_lookups(ids, iter_off, lookup_slots, chunk=32):
     """Every batch's lookups grouped by row + work-item cuts (see orc_group_lookups).
-    Returns (grouped_slots, grouped_lookups, item_starts, item_off)."""
+    Returns (grouped_slots, grouped_lookups, item_starts, item_off, split_starts, split_off)."""
     lib = _load()
     ids, iter_off = _c(ids, np.int64), _c(iter_off, np.int64)
     slots = _c(lookup_slots, np.int32)
@@ -201,7 +201,10 @@ def group_lookups(ids, iter_off, lookup_slots, chunk=32):
     gs, gl = np.empty(max(N, 1), np.int32), np.empty(max(N, 1), np.int32)
     st = np.empty(max(N, 1), np.uint32)
     off = np.zeros(T + 1, np.int64)
-    r = lib.orc_group_lookups(_ptr(ids), _ptr(iter_off), T, _ptr(slots), int(chunk), _ptr(gs), _ptr(gl), _ptr(st), _ptr(off))
+    sp = np.empty(max(N, 1), np.uint32)
+    soff = np.zeros(T + 1, np.int64)
+    r = lib.orc_group_lookups(_ptr(ids), _ptr(iter_off), T, _ptr(slots), int(chunk), _ptr(gs), _ptr(gl), _ptr(st), _ptr(off),
+                              _ptr(sp), _ptr(soff))
     if r < 0:
         raise OracleError(r, "group_lookups")
-    return gs[:N], gl[:N], st[:r].copy(), off
+    return gs[:N], gl[:N], st[:r].copy(), off, sp[:int(soff[-1])].copy(), soff

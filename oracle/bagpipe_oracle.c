@@ -390,14 +390,17 @@ int orc_cache_apply(void *cache_w, float *cache_state, void *host_w, float *host
  * Optional by-product of the plan: the lookups of every batch grouped by row (ids ascending, and for one
  * id the lookup positions ascending), the cache slot of each grouped lookup, and the cuts of the grouped
  * list into work items: a new item starts where the id changes and at every multiple of `chunk` positions
- * counted from the batch's first grouped lookup.  This is bookkeeping for the backward pass, not part of
- * Algorithm 1; the definition is this build's.  Returns the number of items or <0.
+ * counted from the batch's first grouped lookup.  split_starts lists the first grouped lookup of every id
+ * whose lookups span several items (they reach past the next multiple of `chunk`).  This is bookkeeping for
+ * the backward pass, not part of Algorithm 1; the definition is this build's.  Returns the number of items
+ * or <0.
  */
 int64_t orc_group_lookups(const int64_t *ids, const int64_t *iter_off, int64_t T, const int32_t *lookup_slots,
                           int64_t chunk, int32_t *grouped_slots, int32_t *grouped_lookups, uint32_t *item_starts,
-                          int64_t *item_off) {
-    int64_t nitems = 0;
+                          int64_t *item_off, uint32_t *split_starts, int64_t *split_off) {
+    int64_t nitems = 0, nsplit = 0;
     item_off[0] = 0;
+    split_off[0] = 0;
     for (int64_t i = 0; i < T; ++i) {
         int64_t a = iter_off[i], n = iter_off[i + 1] - a;
         rowpos_t *rp = (rowpos_t *)malloc((size_t)(n > 0 ? n : 1) * sizeof(rowpos_t));
@@ -408,9 +411,14 @@ int64_t orc_group_lookups(const int64_t *ids, const int64_t *iter_off, int64_t T
             grouped_lookups[a + p] = (int32_t)rp[p].pos;
             grouped_slots[a + p] = lookup_slots[a + rp[p].pos];
             if (p % chunk == 0 || rp[p].row != rp[p - 1].row) item_starts[nitems++] = (uint32_t)p;
+            if (p == 0 || rp[p].row != rp[p - 1].row) {            /* first lookup of an id */
+                int64_t next_cut = (p / chunk + 1) * chunk;
+                if (next_cut < n && rp[next_cut].row == rp[p].row) split_starts[nsplit++] = (uint32_t)p;
+            }
         }
         free(rp);
         item_off[i + 1] = nitems;
+        split_off[i + 1] = nsplit;
     }
     return nitems;
 }

@@ -37,7 +37,8 @@ class _bp_plan(ctypes.Structure):
                 ("prefetch_offsets", ctypes.c_void_p), ("evict_offsets", ctypes.c_void_p),
                 ("keep_offsets", ctypes.c_void_p), ("occupancy", ctypes.c_void_p),
                 ("grouped_slots", ctypes.c_void_p), ("grouped_lookups", ctypes.c_void_p),
-                ("item_starts", ctypes.c_void_p), ("item_offsets", ctypes.c_void_p), ("L_eff", ctypes.c_int32),
+                ("item_starts", ctypes.c_void_p), ("item_offsets", ctypes.c_void_p),
+                ("split_starts", ctypes.c_void_p), ("split_offsets", ctypes.c_void_p), ("L_eff", ctypes.c_int32),
                 ("peak_occupancy", ctypes.c_int64), ("min_capacity", ctypes.c_int64),
                 ("n_unique_pairs", ctypes.c_int64)]
 
@@ -69,7 +70,7 @@ def load_library():
     lib.bp_embbag_bwd_update_workspace_bytes.argtypes = [cfgp, i64, i64, ctypes.POINTER(sz)]
     lib.bp_embbag_bwd_update.argtypes = [cfgp, vp, vp, vp, vp, i64, i64, vp, vp, sz, vp]
     lib.bp_embbag_bwd_update_grouped_workspace_bytes.argtypes = [cfgp, i64, i64, i32, ctypes.POINTER(sz)]
-    lib.bp_embbag_bwd_update_grouped.argtypes = [cfgp, vp, vp, vp, vp, vp, i64, vp, i64, i64, vp, vp, sz, vp]
+    lib.bp_embbag_bwd_update_grouped.argtypes = [cfgp, vp, vp, vp, vp, vp, i64, vp, i64, vp, i64, i64, vp, vp, sz, vp]
     lib.bp_error_string.argtypes = [ctypes.c_int]
     lib.bp_error_string.restype = ctypes.c_char_p
     lib.bp_last_error_message.restype = ctypes.c_char_p
@@ -160,6 +161,8 @@ class Plan:
     grouped_lookups: "object" = None    # int32 [N] device
     item_starts: "object" = None        # uint32 (as int32 tensor) device, trimmed to the item count
     item_offsets: Optional[np.ndarray] = None   # int64 [T+1] host
+    split_starts: "object" = None       # uint32 (as int32 tensor) device, trimmed
+    split_offsets: Optional[np.ndarray] = None  # int64 [T+1] host
 
 
 def bp_oracle_plan_workspace_bytes(cfg: bp_config, n_lookups: int, n_iters: int, grouping: bool = False) -> int:
@@ -193,8 +196,8 @@ def bp_oracle_plan(cfg: bp_config, ids, iter_offsets, list_capacity: Optional[in
              keep_offsets=np.zeros(T + 1, np.int64), occupancy=np.zeros(max(T, 1), np.int64))
     if grouping:
         t.update(grouped_slots=torch.empty(max(N, 1), **i32), grouped_lookups=torch.empty(max(N, 1), **i32),
-                 item_starts=torch.empty(max(N, 1), **i32))
-        h.update(item_offsets=np.zeros(T + 1, np.int64))
+                 item_starts=torch.empty(max(N, 1), **i32), split_starts=torch.empty(N // 32 + 2, **i32))
+        h.update(item_offsets=np.zeros(T + 1, np.int64), split_offsets=np.zeros(T + 1, np.int64))
     p = _bp_plan()
     for k, v in t.items():
         setattr(p, k, v.data_ptr())
@@ -215,7 +218,9 @@ def bp_oracle_plan(cfg: bp_config, ids, iter_offsets, list_capacity: Optional[in
                 grouped_slots=t["grouped_slots"][:N] if grouping else None,
                 grouped_lookups=t["grouped_lookups"][:N] if grouping else None,
                 item_starts=t["item_starts"][:int(h["item_offsets"][-1])] if grouping else None,
-                item_offsets=h["item_offsets"] if grouping else None)
+                item_offsets=h["item_offsets"] if grouping else None,
+                split_starts=t["split_starts"][:int(h["split_offsets"][-1])] if grouping else None,
+                split_offsets=h["split_offsets"] if grouping else None)
 
 
 # ---------------------------------------------------------------------------------------------------
@@ -269,13 +274,15 @@ def bp_embbag_bwd_update_grouped_workspace_bytes(cfg: bp_config, n_lookups: int,
 
 
 def bp_embbag_bwd_update_grouped(cfg: bp_config, cache_w, cache_state, grouped_slots, grouped_lookups, item_starts,
-                                 bag_offsets, bags: int, grad_out, workspace, stream=None) -> None:
-    """grouped_slots / grouped_lookups / item_starts: one batch's slices of the plan's grouping arrays."""
+                                 split_starts, bag_offsets, bags: int, grad_out, workspace, stream=None) -> None:
+    """grouped_slots / grouped_lookups / item_starts / split_starts: one batch's slices of the plan's grouping
+    arrays (split_starts may be None or empty)."""
     n = int(grouped_slots.numel())
+    n_split = 0 if split_starts is None else int(split_starts.numel())
     _check(load_library().bp_embbag_bwd_update_grouped(
         ctypes.byref(cfg), _ptr(cache_w), _ptr(cache_state), _ptr(grouped_slots), _ptr(grouped_lookups),
-        _ptr(item_starts), int(item_starts.numel()), _ptr(bag_offsets), n, int(bags), _ptr(grad_out), _ptr(workspace),
-        int(workspace.numel()), _stream(stream)))
+        _ptr(item_starts), int(item_starts.numel()), _ptr(split_starts) if n_split else None, n_split,
+        _ptr(bag_offsets), n, int(bags), _ptr(grad_out), _ptr(workspace), int(workspace.numel()), _stream(stream)))
 
 
 # ---------------------------------------------------------------------------------------------------

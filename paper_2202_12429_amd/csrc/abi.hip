@@ -90,7 +90,8 @@ void profile_end(int id, hipStream_t s) {
 // exactly `bytes` read and `bytes` written) and for the copy bandwidth this GPU sustains.
 __global__ __launch_bounds__(256) void copy_calibration_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
                                                                size_t n16) {
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;      // one 16-byte piece per lane, exact grid
+    if (i < n16) dst[i] = src[i];
 }
 
 }  // namespace bp
@@ -119,8 +120,8 @@ BP_EXPORT int bp_copy_calibration(void* dst, const void* src, size_t bytes, void
         return fail(BP_ERR_INVALID_ARG, "copy needs 16-byte aligned pointers and a multiple of 16 bytes");
     if (bytes == 0) return BP_OK;
     const size_t n16 = bytes / 16;
-    size_t blocks = (n16 + 255) / 256;
-    if (blocks > 65536) blocks = 65536;
+    const size_t blocks = (n16 + 255) / 256;
+    if (blocks >= (size_t(1) << 31)) return fail(BP_ERR_UNSUPPORTED, "copy of %zu bytes is too large for one launch", bytes);
     BP_LAUNCH(K_COPY, copy_calibration_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
               (const uint4*)src, (uint4*)dst, n16);
     return BP_OK;

@@ -268,12 +268,17 @@ __global__ __launch_bounds__(kRowBlock) void bwd_combine_update_kernel(const uin
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const uint64_t bb = b + (uint64_t)k * G;
-                ok[k] = bb * kChunk < n && keys[bb * kChunk] == slot;
+                // the key test and the partial row are loaded side by side (row 2bb+1 exists whenever
+                // bb*kChunk < n; a row that turns out not to belong to the slot is dropped): one latency per round
+                const bool inb = bb * kChunk < n;
+                const uint32_t key = inb ? keys[bb * kChunk] : ~0u;
                 t[k].zero();
-                if (ok[k] && active) t[k].load(partial + (2 * bb + 1) * u.dim, c);
+                if (inb && active) t[k].load(partial + (2 * bb + 1) * u.dim, c);
+                ok[k] = inb && key == slot;
             }
 #pragma unroll
-            for (int k = 0; k < 4; ++k) acc.add(t[k]);
+            for (int k = 0; k < 4; ++k)
+                if (ok[k]) acc.add(t[k]);
             if (!ok[3]) break;                        // the slot's boundaries are consecutive
         }
 #pragma unroll
@@ -283,6 +288,57 @@ __global__ __launch_bounds__(kRowBlock) void bwd_combine_update_kernel(const uin
         }
         apply_update<GW, BF16>(u, cache_w, cache_s, (int64_t)slot, c, acc.template rounded<BF16>(), j == 0);
     }
+}
+
+// Split rows when the plan lists them: one workgroup per split row.  Its 256/GW lane groups take the row's partial
+// sums round-robin as above; the group sums meet in LDS and every group adds them in group order, so all hold the
+// row's gradient and group 0 writes the update.  No idle wavefronts: the grid is the list.
+template <int GW, bool BF16>
+__global__ __launch_bounds__(kRowBlock) void bwd_combine_split_kernel(const uint32_t* __restrict__ keys,
+                                                                     const uint32_t* __restrict__ split_starts, uint32_t n,
+                                                                     int64_t C, uint4* cache_w, float* cache_s,
+                                                                     const double* __restrict__ partial, UpdateParams u) {
+    constexpr int N = Piece<BF16>::N;
+    constexpr int G = kRowBlock / GW;                 // lane groups per workgroup
+    __shared__ double red[G][N][GW];
+    const int c = threadIdx.x % GW, j = threadIdx.x / GW;
+    const bool active = c < u.lpr;
+    const uint32_t start = split_starts[blockIdx.x];
+    if (start >= n) return;
+    const uint32_t slot = keys[start];
+    if ((int64_t)slot >= C) return;
+    const uint32_t b0 = start / kChunk + 1;           // the row's first item ends at the next cut after `start`
+    SumPiece<N> acc;
+    acc.zero();
+    if (active && j == 0) acc.load(partial + 2 * (size_t)b0 * u.dim, c);
+    for (uint64_t b = (uint64_t)b0 + j;; b += 4 * G) {
+        bool ok[4];
+        SumPiece<N> t[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint64_t bb = b + (uint64_t)k * G;
+            // the key test and the partial row are loaded side by side (row 2bb+1 exists whenever
+            // bb*kChunk < n; a row that turns out not to belong to the slot is dropped): one latency per round
+            const bool inb = bb * kChunk < n;
+            const uint32_t key = inb ? keys[bb * kChunk] : ~0u;
+            t[k].zero();
+            if (inb && active) t[k].load(partial + (2 * bb + 1) * u.dim, c);
+            ok[k] = inb && key == slot;
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (ok[k]) acc.add(t[k]);
+        if (!ok[3]) break;
+    }
+#pragma unroll
+    for (int i = 0; i < N; ++i) red[j][i][c] = acc.v[i];
+    __syncthreads();
+    acc.zero();
+    for (int g = 0; g < G; ++g) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) acc.v[i] += red[g][i][c];
+    }
+    apply_update<GW, BF16>(u, cache_w, cache_s, (int64_t)slot, c, acc.template rounded<BF16>(), j == 0);
 }
 
 // ---- workspace -------------------------------------------------------------------------------
@@ -317,6 +373,8 @@ struct BwdLaunch {
     const uint32_t *skeys, *sbags, *item_start;
     const uint32_t* n_items;       // device count, or NULL when n_items_host is given
     uint32_t n_items_host;
+    const uint32_t* split_starts;  // list of split rows (grouped path), or NULL: find them item by item
+    uint32_t n_split;
     int64_t n;
     const float* grad;
     void* cache_w;
@@ -333,6 +391,13 @@ struct BwdLaunch {
         BP_LAUNCH(K_BWD_REDUCE_UPDATE, (bwd_reduce_update_kernel<GW, BF16>), dim3((unsigned)blocks), dim3(kRowBlock), 0, stream,
                   skeys, sbags, item_start, n_items, n_items_host, (uint32_t)n, cfg->capacity, grad, (uint4*)cache_w,
                   (float*)cache_s, partial, u);
+        if (n_items == nullptr) {                                            // grouped path: the plan lists the split rows
+            if (n_split)
+                BP_LAUNCH(K_BWD_COMBINE_UPDATE, (bwd_combine_split_kernel<GW, BF16>), dim3(n_split), dim3(kRowBlock), 0,
+                          stream, skeys, split_starts, (uint32_t)n, cfg->capacity, (uint4*)cache_w, (float*)cache_s,
+                          (const double*)partial, u);
+            return BP_OK;
+        }
         int64_t cblocks = ceil_div(items_bound, kRowBlock / kWave);          // one wavefront per item
         if (cblocks < 1) cblocks = 1;
         if (cblocks > kMaxGridBlocks) cblocks = kMaxGridBlocks;
@@ -397,7 +462,7 @@ BP_EXPORT int bp_embbag_bwd_update(const bp_config* cfg, void* cache_w, void* ca
                                                                     w.scan_partials, AddOp(), 0u, stream)));
     const uint32_t* n_items = w.scan_partials + scan_num_tiles(n);
 
-    BwdLaunch l{cfg, w.partial, skeys, sbags, w.item_start, n_items, 0u, n, grad_out, cache_w, cache_state, stream};
+    BwdLaunch l{cfg, w.partial, skeys, sbags, w.item_start, n_items, 0u, nullptr, 0u, n, grad_out, cache_w, cache_state, stream};
     return dispatch_row((int)(row_bytes(cfg) / 16), cfg->weight_dtype == BP_BF16, l);
 }
 
@@ -431,7 +496,8 @@ BP_EXPORT int bp_embbag_bwd_update_grouped_workspace_bytes(const bp_config* cfg,
 
 BP_EXPORT int bp_embbag_bwd_update_grouped(const bp_config* cfg, void* cache_w, void* cache_state,
                                            const int32_t* grouped_slots, const int32_t* grouped_lookups,
-                                           const uint32_t* item_starts, int64_t n_items, const int64_t* bag_offsets,
+                                           const uint32_t* item_starts, int64_t n_items, const uint32_t* split_starts,
+                                           int64_t n_split, const int64_t* bag_offsets,
                                            int64_t n_lookups, int64_t bags, const float* grad_out, void* workspace,
                                            size_t workspace_bytes, void* stream_) {
     hipStream_t stream = (hipStream_t)stream_;
@@ -439,6 +505,8 @@ BP_EXPORT int bp_embbag_bwd_update_grouped(const bp_config* cfg, void* cache_w, 
     BP_TRY(check_bwd_args(cfg, n, bags));
     if (n == 0) return BP_OK;
     if (n_items < 1 || n_items > n) return fail(BP_ERR_INVALID_ARG, "n_items %lld outside [1, n_lookups]", (long long)n_items);
+    if (n_split < 0 || n_split > n_items || (n_split && !split_starts))
+        return fail(BP_ERR_INVALID_ARG, "n_split %lld outside [0, n_items] or split_starts is NULL", (long long)n_split);
     if (!bag_offsets && n != bags)
         return fail(BP_ERR_INVALID_ARG, "bag_offsets is NULL but n_lookups %lld != bags %lld", (long long)n, (long long)bags);
     if (!cache_w || !grouped_slots || !grouped_lookups || !item_starts || !grad_out) return fail(BP_ERR_INVALID_ARG, "NULL pointer");
@@ -456,6 +524,6 @@ BP_EXPORT int bp_embbag_bwd_update_grouped(const bp_config* cfg, void* cache_w, 
         bag_of = w.bag_of;
     }
     BwdLaunch l{cfg, w.partial, reinterpret_cast<const uint32_t*>(grouped_slots), bag_of, item_starts, nullptr,
-                (uint32_t)n_items, n, grad_out, cache_w, cache_state, stream};
+                (uint32_t)n_items, split_starts, (uint32_t)n_split, n, grad_out, cache_w, cache_state, stream};
     return dispatch_row((int)(row_bytes(cfg) / 16), cfg->weight_dtype == BP_BF16, l);
 }

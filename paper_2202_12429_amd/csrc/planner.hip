@@ -331,15 +331,25 @@ __global__ __launch_bounds__(kBlock) void plan_group_keys_kernel(int64_t N, int 
 }
 
 // A work item of the grouped backward pass starts where the row changes and at every multiple of kBwdChunk
-// positions counted from the batch's first lookup.
+// positions counted from the batch's first lookup.  A row is "split" when its lookups go past the next such
+// multiple, i.e. they span several items.  Low word: item start flag; high word: first lookup of a split row.
 struct ItemFlagIn {
     const uint64_t* gkeys;
     const int64_t* iter_off;
     int ib;
-    __device__ __forceinline__ uint32_t operator()(int64_t p) const {
+    __device__ __forceinline__ uint64_t operator()(int64_t p) const {
         const uint64_t k = gkeys[p];
-        const int64_t rel = p - iter_off[k & ((uint64_t(1) << ib) - 1)];
-        return (rel % kBwdChunk == 0 || (gkeys[p - 1] >> ib) != (k >> ib)) ? 1u : 0u;   // rel == 0 guards p == 0
+        const uint32_t i = (uint32_t)(k & ((uint64_t(1) << ib) - 1));
+        const int64_t base = iter_off[i];
+        const int64_t rel = p - base;
+        const bool first_of_row = rel == 0 || (gkeys[p - 1] >> ib) != (k >> ib);      // rel == 0 guards p == 0
+        const bool item = first_of_row || rel % kBwdChunk == 0;
+        bool split = false;
+        if (first_of_row) {
+            const int64_t nb = base + (rel / kBwdChunk + 1) * kBwdChunk;               // next cut after p
+            split = nb < iter_off[i + 1] && (gkeys[nb] >> ib) == (k >> ib);
+        }
+        return (uint64_t)item | ((uint64_t)split << 32);
     }
 };
 struct GroupOut {
@@ -351,15 +361,21 @@ struct GroupOut {
     int32_t* grouped_slots;
     int32_t* grouped_lookups;
     uint32_t* item_starts;
-    int64_t* item_off;     // device copy of the CSR offsets, [T+1], pre-filled with -1
-    __device__ __forceinline__ void operator()(int64_t p, uint32_t exc, uint32_t inc) const {
+    uint32_t* split_starts;
+    int64_t* item_off;     // device copies of the CSR offsets, [T+1] each, pre-filled with -1
+    int64_t* split_off;
+    __device__ __forceinline__ void operator()(int64_t p, uint64_t exc, uint64_t inc) const {
         const uint64_t k = gkeys[p];
         const uint32_t i = (uint32_t)(k & ((uint64_t(1) << ib) - 1));
         const int64_t base = iter_off[i];
         grouped_slots[p] = slot_of_pair[k >> ib];
         grouped_lookups[p] = (int32_t)((int64_t)gpos[p] - base);
-        if (inc != exc) item_starts[exc] = (uint32_t)(p - base);
-        if (p == base) item_off[i] = exc;
+        if ((uint32_t)inc != (uint32_t)exc) item_starts[(uint32_t)exc] = (uint32_t)(p - base);
+        if ((inc >> 32) != (exc >> 32)) split_starts[exc >> 32] = (uint32_t)(p - base);
+        if (p == base) {
+            item_off[i] = (uint32_t)exc;
+            split_off[i] = (int64_t)(exc >> 32);
+        }
     }
 };
 
@@ -386,6 +402,7 @@ struct PlanWorkspace {
     uint64_t* keys_c;      // grouping only
     uint32_t* pos_c;
     int64_t* item_off;
+    int64_t* split_off;
     size_t bytes;
 };
 
@@ -424,6 +441,7 @@ PlanWorkspace carve_plan(void* base, size_t cap, int64_t N, int T, int Lcap, boo
         w.keys_c = c.take<uint64_t>(n);
         w.pos_c = c.take<uint32_t>(n);
         w.item_off = c.take<int64_t>(T + 1);
+        w.split_off = c.take<int64_t>(T + 1);
     }
     w.bytes = c.used();
     return w;
@@ -473,8 +491,10 @@ BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int
 
     const int Lcap = cfg->lookahead < T ? cfg->lookahead : T;
     const int64_t C = cfg->capacity;
-    const bool grouping = plan->grouped_slots || plan->grouped_lookups || plan->item_starts || plan->item_offsets;
-    if (grouping && !(plan->grouped_slots && plan->grouped_lookups && plan->item_starts && plan->item_offsets))
+    const bool grouping = plan->grouped_slots || plan->grouped_lookups || plan->item_starts || plan->item_offsets ||
+                          plan->split_starts || plan->split_offsets;
+    if (grouping && !(plan->grouped_slots && plan->grouped_lookups && plan->item_starts && plan->item_offsets &&
+                      plan->split_starts && plan->split_offsets))
         return fail(BP_ERR_INVALID_ARG, "the grouping outputs of the plan must be all set or all NULL");
     PlanWorkspace w = carve_plan(workspace, workspace_bytes, N, T, Lcap, grouping);
     if (w.bytes > workspace_bytes)
@@ -489,7 +509,7 @@ BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int
         for (int i = 0; i < T; ++i) plan->occupancy[i] = 0;
         plan->L_eff = cfg->lookahead;
         if (grouping)
-            for (int i = 0; i <= T; ++i) plan->item_offsets[i] = 0;
+            for (int i = 0; i <= T; ++i) plan->item_offsets[i] = plan->split_offsets[i] = 0;
         return BP_OK;
     }
 
@@ -585,8 +605,11 @@ BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int
     BP_LAUNCH(K_PLAN_SLOTS, plan_lookup_slots_kernel, grid_for(N), dim3(kBlock), 0, stream, N, spos, (const uint32_t*)uq,
               (const int32_t*)w.slot_of_pair, plan->lookup_slots);
 
+    uint64_t htot = 0;     // miss / evict totals: fetched now, the grouping scan below reuses the partials buffer
+    BP_HIP(hipMemcpyAsync(&htot, totals, sizeof(uint64_t), hipMemcpyDeviceToHost, stream));
+
     // ---- 8. grouping for the backward pass
-    uint32_t n_items = 0;
+    uint64_t n_items_split = 0;
     if (grouping) {
         uint64_t* gk_a = const_cast<uint64_t*>(skeys);
         uint32_t* gp_a = const_cast<uint32_t*>(spos);
@@ -597,19 +620,21 @@ BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int
         const uint32_t* gpos = g_in_b ? w.pos_c : gp_a;
         BP_LAUNCH(K_FILL, fill_kernel<int64_t>, grid_for(T + 1), dim3(kBlock), 0, stream, w.item_off, (int64_t)(T + 1),
                   (int64_t)-1);
-        BP_TRY((device_scan<uint32_t, AddOp, ItemFlagIn, GroupOut>(
+        BP_LAUNCH(K_FILL, fill_kernel<int64_t>, grid_for(T + 1), dim3(kBlock), 0, stream, w.split_off, (int64_t)(T + 1),
+                  (int64_t)-1);
+        BP_TRY((device_scan<uint64_t, AddOp, ItemFlagIn, GroupOut>(
             ItemFlagIn{gkeys, w.iter_off, ib},
             GroupOut{gkeys, gpos, w.iter_off, w.slot_of_pair, ib, plan->grouped_slots, plan->grouped_lookups,
-                     plan->item_starts, w.item_off},
-            N, w.scan_partials32, AddOp(), 0u, stream)));
-        BP_HIP(hipMemcpyAsync(&n_items, w.scan_partials32 + scan_num_tiles(N), sizeof(uint32_t), hipMemcpyDeviceToHost, stream));
+                     plan->item_starts, plan->split_starts, w.item_off, w.split_off},
+            N, w.scan_partials64, AddOp(), uint64_t(0), stream)));
+        BP_HIP(hipMemcpyAsync(&n_items_split, w.scan_partials64 + scan_num_tiles(N), sizeof(uint64_t), hipMemcpyDeviceToHost,
+                              stream));
         BP_HIP(hipMemcpyAsync(plan->item_offsets, w.item_off, sizeof(int64_t) * (T + 1), hipMemcpyDeviceToHost, stream));
+        BP_HIP(hipMemcpyAsync(plan->split_offsets, w.split_off, sizeof(int64_t) * (T + 1), hipMemcpyDeviceToHost, stream));
     }
 
     // ---- CSR offsets to the host
-    uint64_t htot = 0;
     std::vector<uint32_t> hpair((size_t)T + 1);
-    BP_HIP(hipMemcpyAsync(&htot, totals, sizeof(uint64_t), hipMemcpyDeviceToHost, stream));
     BP_HIP(hipMemcpyAsync(plan->prefetch_offsets, w.prefetch_off, sizeof(int64_t) * (T + 1), hipMemcpyDeviceToHost, stream));
     BP_HIP(hipMemcpyAsync(plan->evict_offsets, w.evict_off, sizeof(int64_t) * (T + 1), hipMemcpyDeviceToHost, stream));
     BP_HIP(hipMemcpyAsync(hpair.data(), w.pair_off, sizeof(uint32_t) * (T + 1), hipMemcpyDeviceToHost, stream));
@@ -623,9 +648,12 @@ BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int
         if (plan->evict_offsets[i] < 0) plan->evict_offsets[i] = plan->evict_offsets[i + 1];
     }
     if (grouping) {
-        plan->item_offsets[T] = n_items;
-        for (int i = T - 1; i >= 0; --i)
+        plan->item_offsets[T] = (int64_t)(uint32_t)n_items_split;
+        plan->split_offsets[T] = (int64_t)(n_items_split >> 32);
+        for (int i = T - 1; i >= 0; --i) {
             if (plan->item_offsets[i] < 0) plan->item_offsets[i] = plan->item_offsets[i + 1];
+            if (plan->split_offsets[i] < 0) plan->split_offsets[i] = plan->split_offsets[i + 1];
+        }
     }
     if (n_miss != n_evict) return fail(BP_ERR_HIP, "internal: %lld prefetches but %lld evictions", (long long)n_miss, (long long)n_evict);
     return BP_OK;

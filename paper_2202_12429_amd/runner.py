@@ -108,9 +108,10 @@ class CachedEmbeddingTrainer:
             if b == a:
                 return
             ia, ib = int(p.item_offsets[i]), int(p.item_offsets[i + 1])
+            sa, sb = int(p.split_offsets[i]), int(p.split_offsets[i + 1])
             B.bp_embbag_bwd_update_grouped(self.cfg, self.cache_w, self.cache_state, p.grouped_slots[a:b],
-                                           p.grouped_lookups[a:b], p.item_starts[ia:ib], bag_offsets_dev, bags,
-                                           grad_out, self._bwd_ws, stream=stream)
+                                           p.grouped_lookups[a:b], p.item_starts[ia:ib], p.split_starts[sa:sb],
+                                           bag_offsets_dev, bags, grad_out, self._bwd_ws, stream=stream)
         else:
             B.bp_embbag_bwd_update(self.cfg, self.cache_w, self.cache_state, p.lookup_slots[a:b], bag_offsets_dev,
                                    bags, grad_out, self._bwd_ws, stream=stream)

@@ -119,13 +119,13 @@ def run_bwd(bp, cfg, w, state, slots, off, bags, grad, onehot):
 def run_bwd_grouped(bp, cfg, w, state, slots, off, bags, grad, onehot):
     valid = (slots >= 0) & (slots < cfg.capacity)
     assert valid.all()
-    gs, gl, st, ioff = oracle.group_lookups(slots.astype(np.int64), np.array([0, len(slots)]), slots)
+    gs, gl, st, ioff, sp, soff = oracle.group_lookups(slots.astype(np.int64), np.array([0, len(slots)]), slots)
     wd = w.cuda()
     sd = None if state is None else torch.from_numpy(state).cuda()
     ws = torch.empty(bp.bp_embbag_bwd_update_grouped_workspace_bytes(cfg, len(slots), bags, not onehot),
                      dtype=torch.uint8, device="cuda")
-    bp.bp_embbag_bwd_update_grouped(cfg, wd, sd, dev(gs), dev(gl), dev(st.view(np.int32)), None if onehot else dev(off),
-                                    bags, dev(grad), ws)
+    bp.bp_embbag_bwd_update_grouped(cfg, wd, sd, dev(gs), dev(gl), dev(st.view(np.int32)), dev(sp.view(np.int32)),
+                                    None if onehot else dev(off), bags, dev(grad), ws)
     torch.cuda.synchronize()
     return wd.cpu(), None if sd is None else sd.cpu().numpy()
 
@@ -151,8 +151,8 @@ def test_backward_update(bp, D, dtype, optimizer, max_len):
     grad = rng.standard_normal((bags, D)).astype(np.float32)
     got_w, got_s = run_bwd(bp, cfg, w, state, slots, off, bags, grad, max_len == 1)
     again_w, again_s = run_bwd(bp, cfg, w, state, slots, off, bags, grad, max_len == 1)
-    # the grouped entry point on the same batch (grouping by slot is a grouping by row) gives the same bits:
-    # the fp64 sums of these gradients are exact, so the cut of a row's lookups into items does not matter
+    # the grouped entry point on the same batch (grouping by slot is a grouping by row) gives the same bits: the
+    # fp64 partial sums of a few thousand fp32 values of similar size are exact, so the cuts do not matter
     grp_w, grp_s = run_bwd_grouped(bp, cfg, w, state, slots, off, bags, grad, max_len == 1)
     assert np.array_equal(cache_numpy(grp_w), cache_numpy(got_w)) and (got_s is None or np.array_equal(grp_s, got_s))
     assert torch.equal(got_w.view(torch.int16) if dtype == "bf16" else got_w,
@@ -255,8 +255,10 @@ def assert_plan_equal(got, want, N):
 
 def assert_grouping_equal(got, want, ids, off):
     """The plan's optional grouping against the oracle's definition of it (index work: bit-exact)."""
-    gs, gl, st, ioff = oracle.group_lookups(ids, off, want.lookup_slots)
+    gs, gl, st, ioff, sp, soff = oracle.group_lookups(ids, off, want.lookup_slots)
     assert np.array_equal(got.item_offsets, ioff), "item_offsets"
+    assert np.array_equal(got.split_offsets, soff), "split_offsets"
+    assert np.array_equal(got.split_starts.cpu().numpy().view(np.uint32), sp), "split_starts"
     assert np.array_equal(got.grouped_slots.cpu().numpy(), gs), "grouped_slots"
     assert np.array_equal(got.grouped_lookups.cpu().numpy(), gl), "grouped_lookups"
     assert np.array_equal(got.item_starts.cpu().numpy().view(np.uint32), st), "item_starts"
