@@ -148,6 +148,23 @@ int bp_cache_apply(const bp_config* cfg, void* cache_w, void* cache_state, void*
                    const int64_t* evict_ids, const int32_t* evict_slots, int64_t n_evict,
                    const int64_t* prefetch_ids, const int32_t* prefetch_slots, int64_t n_prefetch, void* stream);
 
+/*
+ * The same maintenance with both directions of the host link busy at once.  Evicted rows are first copied to a
+ * staging area in HBM (which frees their slots), then ONE launch writes the staged rows to the backing table while
+ * it reads the prefetched rows from it.  Precondition: no id is in both lists — true for every plan with
+ * L_eff >= 2 (a row evicted after batch i-1 is not used by batch i); with L_eff == 1 use bp_cache_apply.
+ * The result is then identical to bp_cache_apply.
+ *
+ * workspace  device (HBM), bp_cache_apply_duplex_workspace_bytes(cfg, n_evict) bytes, 256-byte aligned; unused when
+ *            n_evict == 0
+ * Other arguments and error behaviour as for bp_cache_apply.  Asynchronous on `stream`.
+ */
+int bp_cache_apply_duplex_workspace_bytes(const bp_config* cfg, int64_t n_evict, size_t* bytes);
+int bp_cache_apply_duplex(const bp_config* cfg, void* cache_w, void* cache_state, void* backing_w, void* backing_state,
+                          const int64_t* evict_ids, const int32_t* evict_slots, int64_t n_evict,
+                          const int64_t* prefetch_ids, const int32_t* prefetch_slots, int64_t n_prefetch,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
 /* ------------------------------------------------------------------------------------------------
  * (3) Forward: out[b, :] = sum over lookups k in [bag_offsets[b], bag_offsets[b+1]) of cache_w[slot[k], :],
  * accumulated in fp32 in lookup order; an empty bag gives a zero row.

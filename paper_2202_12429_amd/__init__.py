@@ -9,7 +9,8 @@ raises if libbagpipe_hip.so has not been built (python -m paper_2202_12429_amd.b
 from .binding import (  # noqa: F401
     BF16, F32, SGD, ADAGRAD, ADAGRAD_ROWWISE,
     BagpipeError, Plan, bp_config, library_path, load_library, make_config,
-    bp_oracle_plan, bp_oracle_plan_workspace_bytes, bp_cache_apply, bp_embbag_fwd,
+    bp_oracle_plan, bp_oracle_plan_workspace_bytes, bp_cache_apply, bp_cache_apply_duplex, bp_cache_apply_duplex_workspace_bytes,
+    bp_embbag_fwd,
     bp_embbag_bwd_update, bp_embbag_bwd_update_workspace_bytes,
     bp_embbag_bwd_update_grouped, bp_embbag_bwd_update_grouped_workspace_bytes,
     bp_error_string, bp_last_error_message, bp_version,

@@ -66,6 +66,8 @@ def load_library():
     lib.bp_oracle_plan_workspace_bytes.argtypes = [cfgp, i64, i32, i32, ctypes.POINTER(sz)]
     lib.bp_oracle_plan.argtypes = [cfgp, vp, vp, i32, ctypes.POINTER(_bp_plan), vp, sz, vp]
     lib.bp_cache_apply.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, i64, vp, vp, i64, vp]
+    lib.bp_cache_apply_duplex_workspace_bytes.argtypes = [cfgp, i64, ctypes.POINTER(sz)]
+    lib.bp_cache_apply_duplex.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, i64, vp, vp, i64, vp, sz, vp]
     lib.bp_embbag_fwd.argtypes = [cfgp, vp, vp, vp, i64, i64, vp, vp]
     lib.bp_embbag_bwd_update_workspace_bytes.argtypes = [cfgp, i64, i64, ctypes.POINTER(sz)]
     lib.bp_embbag_bwd_update.argtypes = [cfgp, vp, vp, vp, vp, i64, i64, vp, vp, sz, vp]
@@ -83,7 +85,8 @@ def load_library():
     lib.bp_profile_select.restype = ctypes.c_int
     for name in ("bp_oracle_plan_workspace_bytes", "bp_oracle_plan", "bp_cache_apply", "bp_embbag_fwd",
                  "bp_embbag_bwd_update_workspace_bytes", "bp_embbag_bwd_update", "bp_version",
-                 "bp_embbag_bwd_update_grouped_workspace_bytes", "bp_embbag_bwd_update_grouped", "bp_profile_enable",
+                 "bp_embbag_bwd_update_grouped_workspace_bytes", "bp_embbag_bwd_update_grouped",
+                 "bp_cache_apply_duplex_workspace_bytes", "bp_cache_apply_duplex", "bp_profile_enable",
                  "bp_profile_collect", "bp_profile_num_kernels", "bp_profile_get"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -236,6 +239,24 @@ def bp_cache_apply(cfg: bp_config, cache_w, cache_state, backing_w, backing_stat
         ctypes.byref(cfg), _ptr(cache_w), _ptr(cache_state), _ptr(backing_w), _ptr(backing_state),
         _ptr(evict_ids) if n_e else None, _ptr(evict_slots) if n_e else None, n_e,
         _ptr(prefetch_ids) if n_p else None, _ptr(prefetch_slots) if n_p else None, n_p, _stream(stream)))
+
+
+def bp_cache_apply_duplex_workspace_bytes(cfg: bp_config, n_evict: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load_library().bp_cache_apply_duplex_workspace_bytes(ctypes.byref(cfg), int(n_evict), ctypes.byref(out)))
+    return int(out.value)
+
+
+def bp_cache_apply_duplex(cfg: bp_config, cache_w, cache_state, backing_w, backing_state, evict_ids, evict_slots,
+                          prefetch_ids, prefetch_slots, workspace, stream=None) -> None:
+    """bp_cache_apply with both link directions busy at once; needs id-disjoint lists (any plan with L_eff >= 2)."""
+    n_e = 0 if evict_ids is None else int(evict_ids.numel())
+    n_p = 0 if prefetch_ids is None else int(prefetch_ids.numel())
+    _check(load_library().bp_cache_apply_duplex(
+        ctypes.byref(cfg), _ptr(cache_w), _ptr(cache_state), _ptr(backing_w), _ptr(backing_state),
+        _ptr(evict_ids) if n_e else None, _ptr(evict_slots) if n_e else None, n_e,
+        _ptr(prefetch_ids) if n_p else None, _ptr(prefetch_slots) if n_p else None, n_p,
+        _ptr(workspace), 0 if workspace is None else int(workspace.numel()), _stream(stream)))
 
 
 # ---------------------------------------------------------------------------------------------------

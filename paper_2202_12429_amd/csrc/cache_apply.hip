@@ -37,6 +37,101 @@ __global__ __launch_bounds__(kRowBlock) void cache_copy_rows_kernel(uint4* __res
     }
 }
 
+// Duplex variant, step 1: evicted rows leave the cache for a staging area in HBM (entry e -> staging row e), which
+// frees their slots at HBM speed.
+template <int GW>
+__global__ __launch_bounds__(kRowBlock) void cache_stage_rows_kernel(const uint4* __restrict__ cache_w,
+                                                                     const uint4* __restrict__ cache_s,
+                                                                     uint4* __restrict__ stage_w, uint4* __restrict__ stage_s,
+                                                                     const int32_t* __restrict__ slots, int64_t n, int64_t C,
+                                                                     int lpr, int slpr, int rowwise) {
+    const int64_t e = ((int64_t)blockIdx.x * kRowBlock + threadIdx.x) / GW;
+    const int c = threadIdx.x % GW;
+    if (e >= n) return;
+    const int64_t s = slots[e];
+    if (s < 0 || s >= C) return;
+    if (c < lpr) stage_w[e * lpr + c] = cache_w[s * lpr + c];
+    for (int k = c; k < slpr; k += GW) stage_s[e * slpr + k] = cache_s[s * slpr + k];
+    if (rowwise && c == 0) reinterpret_cast<float*>(stage_s)[e] = reinterpret_cast<const float*>(cache_s)[s];
+}
+
+// Duplex variant, step 2: one launch moves rows in both directions at once, so writes to the backing table
+// (staging -> backing) and reads from it (backing -> cache) share the link's two directions instead of taking
+// turns.  Lane groups alternate between the two lists while both last.
+template <int GW>
+__global__ __launch_bounds__(kRowBlock) void cache_duplex_kernel(uint4* __restrict__ cache_w, uint4* __restrict__ cache_s,
+                                                                 uint4* __restrict__ back_w, uint4* __restrict__ back_s,
+                                                                 const uint4* __restrict__ stage_w,
+                                                                 const uint4* __restrict__ stage_s,
+                                                                 const int64_t* __restrict__ e_ids,
+                                                                 const int32_t* __restrict__ e_slots, int64_t n_e,
+                                                                 const int64_t* __restrict__ p_ids,
+                                                                 const int32_t* __restrict__ p_slots, int64_t n_p, int64_t R,
+                                                                 int64_t C, int lpr, int slpr, int rowwise) {
+    const int64_t x = ((int64_t)blockIdx.x * kRowBlock + threadIdx.x) / GW;
+    const int c = threadIdx.x % GW;
+    if (x >= n_e + n_p) return;
+    const int64_t both = 2 * (n_e < n_p ? n_e : n_p);
+    bool evict;
+    int64_t k;
+    if (x < both) {
+        evict = (x & 1) == 0;
+        k = x >> 1;
+    } else {
+        evict = n_e > n_p;
+        k = x - both / 2;
+    }
+    if (evict) {
+        const int64_t g = e_ids[k];
+        const int64_t s = e_slots[k];
+        if (g < 0 || g >= R || s < 0 || s >= C) return;          // same entries the staging step skipped
+        if (c < lpr) back_w[g * lpr + c] = stage_w[k * lpr + c];
+        for (int q = c; q < slpr; q += GW) back_s[g * slpr + q] = stage_s[k * slpr + q];
+        if (rowwise && c == 0) reinterpret_cast<float*>(back_s)[g] = reinterpret_cast<const float*>(stage_s)[k];
+    } else {
+        const int64_t g = p_ids[k];
+        const int64_t s = p_slots[k];
+        if (g < 0 || g >= R || s < 0 || s >= C) return;
+        if (c < lpr) cache_w[s * lpr + c] = back_w[g * lpr + c];
+        for (int q = c; q < slpr; q += GW) cache_s[s * slpr + q] = back_s[g * slpr + q];
+        if (rowwise && c == 0) reinterpret_cast<float*>(cache_s)[s] = reinterpret_cast<const float*>(back_s)[g];
+    }
+}
+
+struct DuplexLaunch {
+    const bp_config* cfg;
+    void *cache_w, *cache_s, *back_w, *back_s, *stage_w, *stage_s;
+    const int64_t* e_ids;
+    const int32_t* e_slots;
+    int64_t n_e;
+    const int64_t* p_ids;
+    const int32_t* p_slots;
+    int64_t n_p;
+    hipStream_t stream;
+    template <int GW, bool BF16>
+    int run() {
+        const int lpr = (int)(row_bytes(cfg) / 16);
+        const int slpr = cfg->optimizer == BP_ADAGRAD ? cfg->dim / 4 : 0;
+        const int rowwise = cfg->optimizer == BP_ADAGRAD_ROWWISE;
+        if (n_e)
+            BP_LAUNCH(K_CACHE_STAGE, (cache_stage_rows_kernel<GW>), dim3((unsigned)ceil_div(n_e * GW, kRowBlock)),
+                      dim3(kRowBlock), 0, stream, (const uint4*)cache_w, (const uint4*)cache_s, (uint4*)stage_w,
+                      (uint4*)stage_s, e_slots, n_e, cfg->capacity, lpr, slpr, rowwise);
+        BP_LAUNCH(K_CACHE_DUPLEX, (cache_duplex_kernel<GW>), dim3((unsigned)ceil_div((n_e + n_p) * GW, kRowBlock)),
+                  dim3(kRowBlock), 0, stream, (uint4*)cache_w, (uint4*)cache_s, (uint4*)back_w, (uint4*)back_s,
+                  (const uint4*)stage_w, (const uint4*)stage_s, e_ids, e_slots, n_e, p_ids, p_slots, n_p, cfg->total_rows,
+                  cfg->capacity, lpr, slpr, rowwise);
+        return BP_OK;
+    }
+};
+
+size_t stage_w_bytes(const bp_config* cfg, int64_t n_evict) {
+    return (((size_t)(n_evict > 0 ? n_evict : 1) * row_bytes(cfg)) + 255) & ~size_t(255);
+}
+size_t stage_s_bytes(const bp_config* cfg, int64_t n_evict) {
+    return (((size_t)(n_evict > 0 ? n_evict : 1) * state_row_bytes(cfg)) + 255) & ~size_t(255);
+}
+
 struct CopyLaunch {
     const bp_config* cfg;
     void *cache_w, *cache_s, *back_w, *back_s;
@@ -94,4 +189,37 @@ BP_EXPORT int bp_cache_apply(const bp_config* cfg, void* cache_w, void* cache_st
         BP_TRY(dispatch_row(lpr, false, l));
     }
     return BP_OK;
+}
+
+BP_EXPORT int bp_cache_apply_duplex_workspace_bytes(const bp_config* cfg, int64_t n_evict, size_t* bytes) {
+    if (!bytes) return fail(BP_ERR_INVALID_ARG, "bytes is NULL");
+    BP_TRY(check_config(cfg));
+    if (n_evict < 0) return fail(BP_ERR_INVALID_ARG, "negative list length");
+    *bytes = stage_w_bytes(cfg, n_evict) + stage_s_bytes(cfg, n_evict);
+    return BP_OK;
+}
+
+BP_EXPORT int bp_cache_apply_duplex(const bp_config* cfg, void* cache_w, void* cache_state, void* backing_w,
+                                    void* backing_state, const int64_t* evict_ids, const int32_t* evict_slots,
+                                    int64_t n_evict, const int64_t* prefetch_ids, const int32_t* prefetch_slots,
+                                    int64_t n_prefetch, void* workspace, size_t workspace_bytes, void* stream) {
+    BP_TRY(check_config(cfg));
+    if (n_evict < 0 || n_prefetch < 0) return fail(BP_ERR_INVALID_ARG, "negative list length");
+    if (n_evict + n_prefetch == 0) return BP_OK;
+    if (!cache_w || !backing_w) return fail(BP_ERR_INVALID_ARG, "cache_w or backing_w is NULL");
+    if (cfg->optimizer != BP_SGD && (!cache_state || !backing_state))
+        return fail(BP_ERR_INVALID_ARG, "optimizer state pointers are NULL");
+    if (((uintptr_t)cache_w | (uintptr_t)backing_w | (uintptr_t)cache_state | (uintptr_t)backing_state) & 15)
+        return fail(BP_ERR_INVALID_ARG, "row pointers must be 16-byte aligned");
+    if ((n_evict && (!evict_ids || !evict_slots)) || (n_prefetch && (!prefetch_ids || !prefetch_slots)))
+        return fail(BP_ERR_INVALID_ARG, "a list pointer is NULL");
+    const size_t need = stage_w_bytes(cfg, n_evict) + stage_s_bytes(cfg, n_evict);
+    if (n_evict && (!workspace || ((uintptr_t)workspace & 255)))
+        return fail(BP_ERR_INVALID_ARG, "workspace NULL or not 256-byte aligned");
+    if (n_evict && workspace_bytes < need)
+        return fail(BP_ERR_WORKSPACE_TOO_SMALL, "workspace %zu < required %zu bytes", workspace_bytes, need);
+    DuplexLaunch l{cfg, cache_w, cache_state, backing_w, backing_state, workspace,
+                   workspace ? (char*)workspace + stage_w_bytes(cfg, n_evict) : nullptr, evict_ids, evict_slots, n_evict,
+                   prefetch_ids, prefetch_slots, n_prefetch, (hipStream_t)stream};
+    return dispatch_row((int)(row_bytes(cfg) / 16), false, l);
 }

@@ -87,6 +87,8 @@ enum KernelId {
     K_PLAN_GROUP,
     K_CACHE_EVICT,
     K_CACHE_PREFETCH,
+    K_CACHE_STAGE,
+    K_CACHE_DUPLEX,
     K_FWD,
     K_BWD_KEYS,
     K_BWD_ITEMS,

@@ -10,7 +10,8 @@
 
 The order of calls is the synchronous schedule of Section 3.2: the write-backs of batch i-1 are applied before
 the prefetches of batch i, so a row is never fetched while an update to it is still only in the cache.
-With grouping=True (default) the plan also lists every batch's lookups grouped by row and the backward pass
+With duplex=True (default) and a plan whose L_eff >= 2, maintain() uses bp_cache_apply_duplex (writes to and reads
+from the backing table in one launch).  With grouping=True (default) the plan also lists every batch's lookups grouped by row and the backward pass
 uses bp_embbag_bwd_update_grouped (no sort at run time); with grouping=False it sorts the slots itself.
 """
 from __future__ import annotations
@@ -32,13 +33,15 @@ def state_shape(rows: int, dim: int, optimizer: int):
 
 class CachedEmbeddingTrainer:
     def __init__(self, cfg: B.bp_config, backing_w, backing_state=None, device="cuda:0", max_lookups: int = 0,
-                 max_bags: int = 0, grouping: bool = True):
+                 max_bags: int = 0, grouping: bool = True, duplex: bool = True):
         import torch
         self.cfg = cfg
         self.device = torch.device(device)
         self.backing_w = backing_w
         self.backing_state = backing_state
         self.grouping = grouping
+        self.duplex = duplex           # both link directions at once in maintain(); needs a plan with L_eff >= 2
+        self._stage = None
         wdt = torch.float32 if cfg.weight_dtype == B.F32 else torch.bfloat16
         C, D = int(cfg.capacity), int(cfg.dim)
         self.cache_w = torch.zeros((C, D), dtype=wdt, device=self.device)
@@ -65,6 +68,12 @@ class CachedEmbeddingTrainer:
         self.iter_offsets = np.ascontiguousarray(iter_offsets, dtype=np.int64)
         self.plan_ = B.bp_oracle_plan(self.cfg, ids_dev, self.iter_offsets, list_capacity=list_capacity,
                                       workspace=workspace, grouping=self.grouping)
+        if self.duplex and self.plan_.L_eff >= 2:
+            import torch
+            most = int(np.diff(self.plan_.evict_offsets).max()) if len(self.plan_.evict_offsets) > 1 else 0
+            need = B.bp_cache_apply_duplex_workspace_bytes(self.cfg, most)
+            if self._stage is None or self._stage.numel() < need:
+                self._stage = torch.empty(need, dtype=torch.uint8, device=self.device)
         return self.plan_
 
     def _slice(self, which: str, i: int):
@@ -81,8 +90,12 @@ class CachedEmbeddingTrainer:
     def maintain(self, i: int, stream=None) -> None:
         e_ids, e_slots = self._slice("evict", i - 1) if i > 0 else (None, None)
         p_ids, p_slots = self._slice("prefetch", i)
-        B.bp_cache_apply(self.cfg, self.cache_w, self.cache_state, self.backing_w, self.backing_state, e_ids, e_slots,
-                         p_ids, p_slots, stream=stream)
+        if self.duplex and self.plan_.L_eff >= 2:
+            B.bp_cache_apply_duplex(self.cfg, self.cache_w, self.cache_state, self.backing_w, self.backing_state, e_ids,
+                                    e_slots, p_ids, p_slots, self._stage, stream=stream)
+        else:
+            B.bp_cache_apply(self.cfg, self.cache_w, self.cache_state, self.backing_w, self.backing_state, e_ids,
+                             e_slots, p_ids, p_slots, stream=stream)
 
     def flush(self, stream=None) -> None:
         T = self.iter_offsets.shape[0] - 1

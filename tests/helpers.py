@@ -94,14 +94,15 @@ def make_backing(cfg, pinned=True, chunk_rows=1 << 20):
     return W, S
 
 
-def gpu_cached_training(cfg, trace, T=None, pinned=True, capacity=None, check_outputs=None, grouping=True):
+def gpu_cached_training(cfg, trace, T=None, pinned=True, capacity=None, check_outputs=None, grouping=True,
+                        duplex=None):
     """Runs plan + T iterations of cache_apply / fwd / bwd_update + flush through the C ABI.
     check_outputs(i, out_tensor) is called after every forward.  Returns (trainer, plan, W, S)."""
     from paper_2202_12429_amd.runner import CachedEmbeddingTrainer
     T = trace.iter_offsets.shape[0] - 1 if T is None else T
     bcfg = bp_config_of(cfg, capacity)
     W, S = make_backing(cfg, pinned)
-    tr = CachedEmbeddingTrainer(bcfg, W, S, grouping=grouping)
+    tr = CachedEmbeddingTrainer(bcfg, W, S, grouping=grouping, duplex=grouping if duplex is None else duplex)
     ids_dev = torch.from_numpy(trace.ids[:trace.iter_offsets[T]]).cuda()
     plan = tr.plan(ids_dev, trace.iter_offsets[:T + 1])
     bags = trace.bag_offsets.shape[1] - 1

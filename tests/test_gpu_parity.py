@@ -238,6 +238,27 @@ def test_cache_apply(bp, D, dtype, optimizer, pinned):
         assert np.array_equal(hs_d.cpu().numpy(), hs_o) and np.array_equal(cs_d.cpu().numpy(), cs_o)
     # empty lists are no-ops
     bp.bp_cache_apply(cfg, cw_d, cs_d, hw_d, hs_d, None, None, None, None)
+    # the duplex variant on id-disjoint lists gives the same bytes
+    p_ids2 = np.setdiff1d(np.arange(R), e_ids)[:900].astype(np.int64)
+    hw_o, cw_o, hs_o, cs_o = cache_numpy(hw), cache_numpy(cw), hs.copy(), cs.copy()
+    oracle.cache_apply(cw_o, cs_o, hw_o, hs_o, D, oracle.DTYPES[dtype], op, e_ids, e_slots, p_ids2, p_slots)
+    hw_d, cw_d = mk(hw.clone()), cw.cuda()
+    hs_d = mk(torch.from_numpy(hs.copy())) if op != oracle.SGD else None
+    cs_d = torch.from_numpy(cs.copy()).cuda() if op != oracle.SGD else None
+    ws = torch.empty(bp.bp_cache_apply_duplex_workspace_bytes(cfg, len(e_ids)), dtype=torch.uint8, device="cuda")
+    bp.bp_cache_apply_duplex(cfg, cw_d, cs_d, hw_d, hs_d, dev(e_ids), dev(e_slots), dev(p_ids2), dev(p_slots), ws)
+    bp.bp_cache_apply_duplex(cfg, cw_d, cs_d, hw_d, hs_d, None, None, None, None, None)          # no-op
+    torch.cuda.synchronize()
+    assert np.array_equal(cache_numpy(hw_d.cpu()), hw_o) and np.array_equal(cache_numpy(cw_d.cpu()), cw_o)
+    if op != oracle.SGD:
+        assert np.array_equal(hs_d.cpu().numpy(), hs_o) and np.array_equal(cs_d.cpu().numpy(), cs_o)
+    # only evictions, only prefetches
+    bp.bp_cache_apply_duplex(cfg, cw_d, cs_d, hw_d, hs_d, dev(e_ids), dev(e_slots), None, None, ws)
+    bp.bp_cache_apply_duplex(cfg, cw_d, cs_d, hw_d, hs_d, None, None, dev(p_ids2), dev(p_slots), None)
+    oracle.cache_apply(cw_o, cs_o, hw_o, hs_o, D, oracle.DTYPES[dtype], op, e_ids, e_slots, np.zeros(0, np.int64), np.zeros(0, np.int32))
+    oracle.cache_apply(cw_o, cs_o, hw_o, hs_o, D, oracle.DTYPES[dtype], op, np.zeros(0, np.int64), np.zeros(0, np.int32), p_ids2, p_slots)
+    torch.cuda.synchronize()
+    assert np.array_equal(cache_numpy(hw_d.cpu()), hw_o) and np.array_equal(cache_numpy(cw_d.cpu()), cw_o)
 
 
 # ---------------------------------------------------------------------------------------------------
