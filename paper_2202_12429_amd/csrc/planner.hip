@@ -87,22 +87,35 @@ __device__ __forceinline__ uint32_t pair_gap(const uint64_t* ukey, uint32_t q, u
     return (a >> ib) == (b >> ib) ? (uint32_t)((b & imask) - (a & imask)) : kGapInf;
 }
 
+// Each workgroup walks a contiguous stretch of pairs and keeps its counts in LDS: the per-batch unique counts and
+// the histogram rows of the small gaps [2, 2 + lds_gaps), which take nearly all the hits; larger gaps go to global
+// atomics.  Integer atomics only: the sums do not depend on the order.
 __global__ __launch_bounds__(kBlock) void plan_hist_kernel(const uint64_t* __restrict__ ukey, uint32_t M, int ib, int T,
-                                                           int Lcap, uint32_t* __restrict__ H,
-                                                           uint32_t* __restrict__ ucount) {
-    extern __shared__ uint32_t lds_u[];   // [T]
-    for (int i = threadIdx.x; i < T; i += kBlock) lds_u[i] = 0;
+                                                           int Lcap, int lds_gaps, uint32_t per_block,
+                                                           uint32_t* __restrict__ H, uint32_t* __restrict__ ucount) {
+    extern __shared__ uint32_t lds[];   // [T] unique counts, then [lds_gaps][T] histogram rows
+    uint32_t* lds_u = lds;
+    uint32_t* lds_h = lds + T;
+    const int cells = (1 + lds_gaps) * T;
+    for (int i = threadIdx.x; i < cells; i += kBlock) lds[i] = 0;
     __syncthreads();
     const uint64_t imask = (uint64_t(1) << ib) - 1;
-    for (uint32_t q = blockIdx.x * kBlock + threadIdx.x; q < M; q += gridDim.x * kBlock) {
+    const uint64_t begin = (uint64_t)blockIdx.x * per_block;
+    const uint64_t end = begin + per_block < M ? begin + per_block : M;
+    for (uint64_t q = begin + threadIdx.x; q < end; q += kBlock) {
         const uint32_t i = (uint32_t)(ukey[q] & imask);
         atomicAdd(&lds_u[i], 1u);
-        const uint32_t gap = pair_gap(ukey, q, M, ib, imask);
-        if (gap >= 2u && gap < (uint32_t)Lcap) atomicAdd(&H[(size_t)gap * T + i], 1u);
+        const uint32_t gap = pair_gap(ukey, (uint32_t)q, M, ib, imask);
+        if (gap >= 2u && gap < (uint32_t)Lcap) {
+            if (gap < 2u + (uint32_t)lds_gaps) atomicAdd(&lds_h[(gap - 2u) * T + i], 1u);
+            else atomicAdd(&H[(size_t)gap * T + i], 1u);
+        }
     }
     __syncthreads();
     for (int i = threadIdx.x; i < T; i += kBlock)
         if (lds_u[i]) atomicAdd(&ucount[i], lds_u[i]);
+    for (int x = threadIdx.x; x < lds_gaps * T; x += kBlock)
+        if (lds_h[x]) atomicAdd(&H[(size_t)2 * T + x], lds_h[x]);      // row (2 + x / T), column x % T
 }
 
 // H[gap][.] -> inclusive prefix over batches, one thread per gap row
@@ -126,17 +139,25 @@ __device__ __forceinline__ uint32_t covering(const uint32_t* Hc, int T, int gap,
     return hi - lo;
 }
 
-// peak[L'] = max_j occupancy(j, L') for L' = 1..Lcap, one thread per batch j
-__global__ void plan_occ_peak_kernel(const uint32_t* __restrict__ Hc, const uint32_t* __restrict__ ucount, int T,
-                                     int Lcap, uint32_t* __restrict__ peak) {
-    const int j = blockIdx.x * blockDim.x + threadIdx.x;
-    if (j >= T) return;
-    uint32_t run = ucount[j];
-    atomicMax(&peak[1], run);
-    for (int Lp = 2; Lp <= Lcap; ++Lp) {
-        const int gap = Lp - 1;              // pairs with gap <= L'-1 are kept under L'
-        if (gap >= 2) run += covering(Hc, T, gap, j);
-        atomicMax(&peak[Lp], run);
+// peak[L'] = max_j occupancy(j, L') for L' = 1..Lcap.  One workgroup per batch j: occupancy(j, L') is the unique
+// count of j plus the prefix sum over gap < L' of covering(gap, j), taken with a workgroup scan over the gaps.
+__global__ __launch_bounds__(kBlock) void plan_occ_peak_kernel(const uint32_t* __restrict__ Hc,
+                                                               const uint32_t* __restrict__ ucount, int T, int Lcap,
+                                                               uint32_t* __restrict__ peak) {
+    __shared__ uint32_t wave_tot[kBlock / kWave];
+    const int j = blockIdx.x;
+    uint32_t carry = ucount[j];
+    if (threadIdx.x == 0) {
+        atomicMax(&peak[1], carry);
+        if (Lcap >= 2) atomicMax(&peak[2], carry);       // L' = 2 keeps gap 1 only: nothing is resident unused
+    }
+    for (int base = 2; base < Lcap; base += kBlock) {     // gap = L' - 1 for L' = 3..Lcap
+        const int gap = base + threadIdx.x;
+        const uint32_t v = gap < Lcap ? covering(Hc, T, gap, j) : 0u;
+        uint32_t exc, inc, total;
+        block_scan<kBlock>(v, AddOp(), 0u, wave_tot, &exc, &inc, &total);
+        if (gap < Lcap) atomicMax(&peak[gap + 1], carry + inc);
+        carry += total;
     }
 }
 
@@ -170,11 +191,23 @@ __global__ void plan_occ_final_kernel(const uint32_t* __restrict__ Hc, const uin
 }
 
 // ---- 4. per-pair decisions -------------------------------------------------------------------
-constexpr uint8_t kMiss = 1, kEvict = 2;
+// Everything the lists need about a pair travels in one 64-bit record, which is also the key of the regroup sort
+// (sorted on its lowest iter_bits only):  id | ttl | evict | miss | batch.
+constexpr uint64_t kMiss = 1, kEvict = 2;
+
+struct PairRecord {
+    int ib;
+    __device__ __forceinline__ uint64_t pack(uint64_t g, uint32_t ttl, uint64_t flags, uint32_t i) const {
+        return (g << (2 * ib + 2)) | ((uint64_t)ttl << (ib + 2)) | (flags << ib) | i;
+    }
+    __device__ __forceinline__ uint32_t batch(uint64_t r) const { return (uint32_t)(r & ((uint64_t(1) << ib) - 1)); }
+    __device__ __forceinline__ uint64_t flags(uint64_t r) const { return (r >> ib) & 3; }
+    __device__ __forceinline__ uint32_t ttl(uint64_t r) const { return (uint32_t)((r >> (ib + 2)) & ((uint64_t(1) << ib) - 1)); }
+    __device__ __forceinline__ int64_t id(uint64_t r) const { return (int64_t)(r >> (2 * ib + 2)); }
+};
 
 __global__ __launch_bounds__(kBlock) void plan_flags_kernel(const uint64_t* __restrict__ ukey, uint32_t M, int ib,
-                                                            const PlanScalars* sc, uint8_t* __restrict__ flags,
-                                                            int32_t* __restrict__ ttl, uint32_t* __restrict__ key2,
+                                                            const PlanScalars* sc, uint64_t* __restrict__ rec,
                                                             uint32_t* __restrict__ val2) {
     const uint32_t q = blockIdx.x * kBlock + threadIdx.x;
     if (q >= M) return;
@@ -190,7 +223,7 @@ __global__ __launch_bounds__(kBlock) void plan_flags_kernel(const uint64_t* __re
         const uint64_t kp = ukey[q - 1];
         if ((kp >> ib) == g && i - (int64_t)(kp & imask) < Leff) miss = false;
     }
-    int32_t t = (int32_t)i;
+    uint32_t t = (uint32_t)i;
     if (keep) {
         // last pair of this id whose batch is <= i + L_eff - 1: it lies within L_eff - 1 pairs of q
         const int64_t last_iter = i + Leff - 1 < (int64_t)imask ? i + Leff - 1 : (int64_t)imask;
@@ -201,17 +234,18 @@ __global__ __launch_bounds__(kBlock) void plan_flags_kernel(const uint64_t* __re
             const int64_t mid = (lo + hi + 1) >> 1;
             if (ukey[mid] <= bound) lo = mid; else hi = mid - 1;
         }
-        t = (int32_t)(ukey[lo] & imask);
+        t = (uint32_t)(ukey[lo] & imask);
     }
-    flags[q] = (miss ? kMiss : 0) | (keep ? 0 : kEvict);
-    ttl[q] = t;
-    key2[q] = (uint32_t)i;
+    rec[q] = PairRecord{ib}.pack(g, t, (miss ? kMiss : 0) | (keep ? 0 : kEvict), (uint32_t)i);
     val2[q] = q;
 }
 
 struct MissIndexIn {
-    const uint8_t* flags;
-    __device__ __forceinline__ uint32_t operator()(int64_t q) const { return (flags[q] & kMiss) ? (uint32_t)q : 0u; }
+    const uint64_t* rec;
+    int ib;
+    __device__ __forceinline__ uint32_t operator()(int64_t q) const {
+        return (PairRecord{ib}.flags(rec[q]) & kMiss) ? (uint32_t)q : 0u;
+    }
 };
 struct StoreInclusiveU32 {
     uint32_t* p;
@@ -220,18 +254,16 @@ struct StoreInclusiveU32 {
 
 // ---- 5. lists in (batch, id) order -----------------------------------------------------------
 struct ListCountIn {
-    const uint32_t* ord;
-    const uint8_t* flags;
+    const uint64_t* srec;     // records sorted by batch (stable: id order inside a batch)
+    int ib;
     __device__ __forceinline__ uint64_t operator()(int64_t k) const {
-        const uint8_t f = flags[ord[k]];
-        return (uint64_t)(f & kMiss) | ((uint64_t)((f & kEvict) >> 1) << 32);
+        const uint64_t f = PairRecord{ib}.flags(srec[k]);
+        return (f & kMiss) | (((f & kEvict) >> 1) << 32);
     }
 };
 struct ListOut {
-    const uint32_t* ord;
-    const uint8_t* flags;
-    const uint64_t* ukey;
-    const int32_t* ttl;
+    const uint64_t* srec;
+    const uint32_t* ord;      // pair index of the k-th sorted record
     const uint32_t* pair_off;
     int ib;
     int64_t* keep_ids;
@@ -243,14 +275,15 @@ struct ListOut {
     int64_t* prefetch_off;   // device copies of the CSR offsets, [T+1], pre-filled with -1
     int64_t* evict_off;
     __device__ __forceinline__ void operator()(int64_t k, uint64_t exc, uint64_t) const {
+        const PairRecord pr{ib};
+        const uint64_t r = srec[k];
         const uint32_t q = ord[k];
-        const uint64_t key = ukey[q];
-        const int64_t g = (int64_t)(key >> ib);
-        const uint32_t i = (uint32_t)(key & ((uint64_t(1) << ib) - 1));
+        const int64_t g = pr.id(r);
+        const uint32_t i = pr.batch(r);
         const uint32_t x = (uint32_t)exc, e = (uint32_t)(exc >> 32);
-        const uint8_t f = flags[q];
+        const uint64_t f = pr.flags(r);
         keep_ids[k] = g;
-        keep_ttl[k] = ttl[q];
+        keep_ttl[k] = (int32_t)pr.ttl(r);
         if (f & kMiss) {
             prefetch_ids[x] = g;
             missord[q] = x;
@@ -360,6 +393,7 @@ struct GroupOut {
     int ib;
     int32_t* grouped_slots;
     int32_t* grouped_lookups;
+    int32_t* lookup_slots;  // the per-lookup slot map is scattered from here: a batch's targets share a small window
     uint32_t* item_starts;
     uint32_t* split_starts;
     int64_t* item_off;     // device copies of the CSR offsets, [T+1] each, pre-filled with -1
@@ -368,8 +402,11 @@ struct GroupOut {
         const uint64_t k = gkeys[p];
         const uint32_t i = (uint32_t)(k & ((uint64_t(1) << ib) - 1));
         const int64_t base = iter_off[i];
-        grouped_slots[p] = slot_of_pair[k >> ib];
-        grouped_lookups[p] = (int32_t)((int64_t)gpos[p] - base);
+        const int32_t slot = slot_of_pair[k >> ib];
+        const uint32_t pos = gpos[p];
+        grouped_slots[p] = slot;
+        grouped_lookups[p] = (int32_t)((int64_t)pos - base);
+        lookup_slots[pos] = slot;
         if ((uint32_t)inc != (uint32_t)exc) item_starts[(uint32_t)exc] = (uint32_t)(p - base);
         if ((inc >> 32) != (exc >> 32)) split_starts[exc >> 32] = (uint32_t)(p - base);
         if (p == base) {
@@ -395,9 +432,8 @@ struct PlanWorkspace {
     uint32_t *H, *ucount, *peak, *pair_off;
     PlanScalars* scalars;
     int64_t *occ, *prefetch_off, *evict_off, *iter_off;
-    uint8_t* flags;
-    int32_t* ttl;
-    uint32_t *chain, *key2_a, *key2_b, *val2_a, *val2_b, *missord, *evict_pair, *par;
+    uint64_t *rec_a, *rec_b;
+    uint32_t *chain, *val2_a, *val2_b, *missord, *evict_pair, *par;
     int32_t* slot_of_pair;
     uint64_t* keys_c;      // grouping only
     uint32_t* pos_c;
@@ -426,11 +462,9 @@ PlanWorkspace carve_plan(void* base, size_t cap, int64_t N, int T, int Lcap, boo
     w.prefetch_off = c.take<int64_t>(T + 1);
     w.evict_off = c.take<int64_t>(T + 1);
     w.iter_off = c.take<int64_t>(T + 1);
-    w.flags = c.take<uint8_t>(n);
-    w.ttl = c.take<int32_t>(n);
+    w.rec_a = c.take<uint64_t>(n);
+    w.rec_b = c.take<uint64_t>(n);
     w.chain = c.take<uint32_t>(n);
-    w.key2_a = c.take<uint32_t>(n);
-    w.key2_b = c.take<uint32_t>(n);
     w.val2_a = c.take<uint32_t>(n);
     w.val2_b = c.take<uint32_t>(n);
     w.missord = c.take<uint32_t>(n);
@@ -451,7 +485,8 @@ int check_plan_args(const bp_config* cfg, int64_t N, int32_t T) {
     BP_TRY(check_config(cfg));
     if (N < 0 || N >= (int64_t(1) << 31)) return fail(BP_ERR_UNSUPPORTED, "n_lookups %lld outside [0, 2^31)", (long long)N);
     if (T < 1 || T > kMaxIters) return fail(BP_ERR_UNSUPPORTED, "n_iters %d outside [1, %d]", T, kMaxIters);
-    if (bits_for(cfg->total_rows) + bits_for(T) > 63) return fail(BP_ERR_UNSUPPORTED, "id and batch bits exceed 63");
+    if (bits_for(cfg->total_rows) + 2 * bits_for(T) + 2 > 64)
+        return fail(BP_ERR_UNSUPPORTED, "id bits + 2 * batch bits + 2 exceed 64");
     return BP_OK;
 }
 
@@ -547,13 +582,18 @@ BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int
     BP_HIP(hipMemsetAsync(w.ucount, 0, sizeof(uint32_t) * T, stream));
     BP_HIP(hipMemsetAsync(w.peak, 0, sizeof(uint32_t) * (Lcap + 2), stream));
     {
-        int64_t blocks = ceil_div(M, kBlock * 8);
-        if (blocks > 4096) blocks = 4096;
-        BP_LAUNCH(K_PLAN_HIST, plan_hist_kernel, dim3((unsigned)blocks), dim3(kBlock), sizeof(uint32_t) * T, stream,
-                  (const uint64_t*)ukey, M, ib, T, Lcap, w.H, w.ucount);
+        int lds_gaps = (int)((48 * 1024 / 4 - T) / T);                  // histogram rows that fit in 48 KiB next to [T]
+        if (lds_gaps > Lcap - 2) lds_gaps = Lcap - 2;
+        if (lds_gaps < 0) lds_gaps = 0;
+        int64_t blocks = ceil_div(M, 32 * 1024);                         // >= 32 Ki pairs per workgroup amortise the flush
+        if (blocks > 1024) blocks = 1024;
+        const uint32_t per_block = (uint32_t)ceil_div(M, blocks);
+        BP_LAUNCH(K_PLAN_HIST, plan_hist_kernel, dim3((unsigned)blocks), dim3(kBlock),
+                  sizeof(uint32_t) * (size_t)(1 + lds_gaps) * T, stream, (const uint64_t*)ukey, M, ib, T, Lcap, lds_gaps,
+                  per_block, w.H, w.ucount);
     }
     BP_LAUNCH(K_PLAN_OCC, plan_occ_prefix_kernel, grid_for(Lcap), dim3(kBlock), 0, stream, w.H, T, Lcap);
-    BP_LAUNCH(K_PLAN_OCC, plan_occ_peak_kernel, grid_for(T), dim3(kBlock), 0, stream, (const uint32_t*)w.H,
+    BP_LAUNCH(K_PLAN_OCC, plan_occ_peak_kernel, dim3(T), dim3(kBlock), 0, stream, (const uint32_t*)w.H,
               (const uint32_t*)w.ucount, T, Lcap, w.peak);
     BP_LAUNCH(K_PLAN_OCC, plan_choose_kernel, dim3(1), dim3(64), 0, stream, (const uint32_t*)w.peak,
               (const uint32_t*)w.ucount, T, Lcap, cfg->lookahead, C, w.scalars, w.pair_off);
@@ -570,23 +610,24 @@ BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int
 
     // ---- 4. flags, TTL, fetching pair of every pair
     BP_LAUNCH(K_PLAN_FLAGS, plan_flags_kernel, grid_for(M), dim3(kBlock), 0, stream, (const uint64_t*)ukey, M, ib,
-              (const PlanScalars*)w.scalars, w.flags, w.ttl, w.key2_a, w.val2_a);
-    BP_TRY((device_scan<uint32_t, MaxOp, MissIndexIn, StoreInclusiveU32>(MissIndexIn{w.flags}, StoreInclusiveU32{w.chain},
+              (const PlanScalars*)w.scalars, w.rec_a, w.val2_a);
+    BP_TRY((device_scan<uint32_t, MaxOp, MissIndexIn, StoreInclusiveU32>(MissIndexIn{w.rec_a, ib}, StoreInclusiveU32{w.chain},
                                                                          M, w.scan_partials32, MaxOp(), 0u, stream)));
 
-    // ---- 5. regroup by batch, lists
+    // ---- 5. regroup by batch (the records travel as keys), lists
     bool ord_in_b = false;
-    BP_TRY((radix_sort_pairs<uint32_t, kPlanSortIPT>(w.key2_a, w.key2_b, w.val2_a, w.val2_b, M, 0, ib, w.sort_temp, stream,
+    BP_TRY((radix_sort_pairs<uint64_t, kPlanSortIPT>(w.rec_a, w.rec_b, w.val2_a, w.val2_b, M, 0, ib, w.sort_temp, stream,
                                                      &ord_in_b)));
+    const uint64_t* srec = ord_in_b ? w.rec_b : w.rec_a;
     const uint32_t* ord = ord_in_b ? w.val2_b : w.val2_a;
     BP_LAUNCH(K_FILL, fill_kernel<int64_t>, grid_for(T + 1), dim3(kBlock), 0, stream, w.prefetch_off, (int64_t)(T + 1),
               (int64_t)-1);
     BP_LAUNCH(K_FILL, fill_kernel<int64_t>, grid_for(T + 1), dim3(kBlock), 0, stream, w.evict_off, (int64_t)(T + 1),
               (int64_t)-1);
     BP_TRY((device_scan<uint64_t, AddOp, ListCountIn, ListOut>(
-        ListCountIn{ord, w.flags},
-        ListOut{ord, w.flags, ukey, w.ttl, w.pair_off, ib, plan->keep_ids, plan->keep_ttl, plan->prefetch_ids,
-                plan->evict_ids, w.missord, w.evict_pair, w.prefetch_off, w.evict_off},
+        ListCountIn{srec, ib},
+        ListOut{srec, ord, w.pair_off, ib, plan->keep_ids, plan->keep_ttl, plan->prefetch_ids, plan->evict_ids, w.missord,
+                w.evict_pair, w.prefetch_off, w.evict_off},
         M, w.scan_partials64, AddOp(), uint64_t(0), stream)));
     const uint64_t* totals = w.scan_partials64 + scan_num_tiles(M);
 
@@ -602,8 +643,9 @@ BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int
               (const uint32_t*)w.missord, (const uint32_t*)w.par, w.slot_of_pair);
     BP_LAUNCH(K_PLAN_SLOTS, plan_list_slots_kernel, grid_for(M), dim3(kBlock), 0, stream, totals, (const uint32_t*)w.par,
               (const uint32_t*)w.evict_pair, (const int32_t*)w.slot_of_pair, plan->prefetch_slots, plan->evict_slots);
-    BP_LAUNCH(K_PLAN_SLOTS, plan_lookup_slots_kernel, grid_for(N), dim3(kBlock), 0, stream, N, spos, (const uint32_t*)uq,
-              (const int32_t*)w.slot_of_pair, plan->lookup_slots);
+    if (!grouping)      // with grouping the slot map is written from the batch-grouped order (step 8)
+        BP_LAUNCH(K_PLAN_SLOTS, plan_lookup_slots_kernel, grid_for(N), dim3(kBlock), 0, stream, N, spos,
+                  (const uint32_t*)uq, (const int32_t*)w.slot_of_pair, plan->lookup_slots);
 
     uint64_t htot = 0;     // miss / evict totals: fetched now, the grouping scan below reuses the partials buffer
     BP_HIP(hipMemcpyAsync(&htot, totals, sizeof(uint64_t), hipMemcpyDeviceToHost, stream));
@@ -625,7 +667,7 @@ BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int
         BP_TRY((device_scan<uint64_t, AddOp, ItemFlagIn, GroupOut>(
             ItemFlagIn{gkeys, w.iter_off, ib},
             GroupOut{gkeys, gpos, w.iter_off, w.slot_of_pair, ib, plan->grouped_slots, plan->grouped_lookups,
-                     plan->item_starts, plan->split_starts, w.item_off, w.split_off},
+                     plan->lookup_slots, plan->item_starts, plan->split_starts, w.item_off, w.split_off},
             N, w.scan_partials64, AddOp(), uint64_t(0), stream)));
         BP_HIP(hipMemcpyAsync(&n_items_split, w.scan_partials64 + scan_num_tiles(N), sizeof(uint64_t), hipMemcpyDeviceToHost,
                               stream));
