@@ -139,24 +139,26 @@ int device_scan(In in, Out out, int64_t n, T* partials, Op op, T identity, hipSt
 }
 
 // ---------------------------------------------------------------------------------------------
-// stable LSD radix sort of (key, 32-bit value) pairs, 8 bits per pass
+// stable LSD radix sort of (key, 32-bit value) pairs, RB = 8 or 9 bits per pass
 //   upsweep    per-tile digit histogram              -> counts[digit][tile]
 //   scan       exclusive scan of counts (digit-major) -> global base of every (digit, tile)
 //   downsweep  per-tile stable ranking in LDS, coalesced scatter
 // Ranking inside a tile: each wavefront owns a contiguous 64*IPT stretch, lane l holds elements
 // j*64+l; for every j the lanes that share a digit find each other with ballots (one per digit bit),
 // rank = running per-wave digit count + number of lower lanes among the peers.
+// The bits to sort are spread evenly over the fewest passes of at most 9 bits (34 bits: 9+9+8+8).
 // ---------------------------------------------------------------------------------------------
 constexpr int kSortBlock = 256;
-constexpr int kRadixBits = 8;
-constexpr int kRadix = 1 << kRadixBits;
+constexpr int kMaxRadixBits = 9;
+constexpr int kMaxRadix = 1 << kMaxRadixBits;
 
-template <typename K, int IPT>
+template <typename K, int IPT, int RB>
 __global__ __launch_bounds__(kSortBlock) void sort_upsweep_kernel(const K* __restrict__ keys, uint32_t n, int shift,
                                                                   uint32_t mask, uint32_t* __restrict__ counts,
                                                                   uint32_t ntiles) {
-    __shared__ uint32_t hist[kRadix];
-    hist[threadIdx.x] = 0;
+    constexpr int RADIX = 1 << RB;
+    __shared__ uint32_t hist[RADIX];
+    for (int d = threadIdx.x; d < RADIX; d += kSortBlock) hist[d] = 0;
     __syncthreads();
     const uint32_t base = blockIdx.x * (kSortBlock * IPT);
 #pragma unroll
@@ -165,28 +167,30 @@ __global__ __launch_bounds__(kSortBlock) void sort_upsweep_kernel(const K* __res
         if (i < n) atomicAdd(&hist[(uint32_t)(keys[i] >> shift) & mask], 1u);
     }
     __syncthreads();
-    counts[(size_t)threadIdx.x * ntiles + blockIdx.x] = hist[threadIdx.x];
+    for (int d = threadIdx.x; d < RADIX; d += kSortBlock) counts[(size_t)d * ntiles + blockIdx.x] = hist[d];
 }
 
-template <typename K, int IPT>
+template <typename K, int IPT, int RB>
 __global__ __launch_bounds__(kSortBlock) void sort_downsweep_kernel(const K* __restrict__ kin, K* __restrict__ kout,
                                                                     const uint32_t* __restrict__ vin,
                                                                     uint32_t* __restrict__ vout, uint32_t n, int shift,
                                                                     uint32_t mask, const uint32_t* __restrict__ bases,
                                                                     uint32_t ntiles) {
+    constexpr int RADIX = 1 << RB;
+    constexpr int DPT = RADIX / kSortBlock;    // consecutive digits owned by a thread in the digit scan (1 or 2)
     constexpr int WAVES = kSortBlock / kWave;
     constexpr int TILE = kSortBlock * IPT;
     constexpr int WTILE = kWave * IPT;
-    __shared__ uint32_t wcnt[WAVES][kRadix];   // per-wave digit counts, then per-wave exclusive offsets
-    __shared__ uint32_t dstart[kRadix];        // tile-local start of each digit
-    __shared__ uint32_t gbase[kRadix];         // global base of the digit for this tile, minus dstart
+    static_assert(RADIX % kSortBlock == 0, "radix must be a multiple of the workgroup size");
+    __shared__ uint32_t wcnt[WAVES][RADIX];    // per-wave digit counts, then per-wave exclusive offsets
+    __shared__ uint32_t dstart[RADIX];         // tile-local start of each digit
+    __shared__ uint32_t gbase[RADIX];          // global base of the digit for this tile, minus dstart
     __shared__ uint32_t wave_tot[WAVES];
     __shared__ K skeys[TILE];
     __shared__ uint32_t svals[TILE];
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
-#pragma unroll
-    for (int i = 0; i < WAVES; ++i) wcnt[i][tid] = 0;
+    for (int d = tid; d < WAVES * RADIX; d += kSortBlock) (&wcnt[0][0])[d] = 0;
     __syncthreads();
 
     const uint32_t tile_base = blockIdx.x * TILE;
@@ -208,7 +212,7 @@ __global__ __launch_bounds__(kSortBlock) void sort_downsweep_kernel(const K* __r
         const uint32_t d = (uint32_t)(key[j] >> shift) & mask;
         uint64_t peers = __ballot(valid);
 #pragma unroll
-        for (int b = 0; b < kRadixBits; ++b) {
+        for (int b = 0; b < RB; ++b) {
             const bool bit = (d >> b) & 1u;
             const uint64_t m = __ballot(bit);
             peers &= bit ? m : ~m;
@@ -221,18 +225,31 @@ __global__ __launch_bounds__(kSortBlock) void sort_downsweep_kernel(const K* __r
     }
     __syncthreads();
 
-    {   // thread tid owns digit tid: offsets of the waves inside the digit, then digit starts inside the tile
-        uint32_t run = 0;
+    {   // thread tid owns digits tid*DPT .. tid*DPT+DPT-1: offsets of the waves inside each digit, then digit starts
+        uint32_t tot[DPT];
+        uint32_t sum = 0;
 #pragma unroll
-        for (int i = 0; i < WAVES; ++i) {
-            uint32_t c = wcnt[i][tid];
-            wcnt[i][tid] = run;
-            run += c;
+        for (int k = 0; k < DPT; ++k) {
+            const int d = tid * DPT + k;
+            uint32_t run = 0;
+#pragma unroll
+            for (int i = 0; i < WAVES; ++i) {
+                uint32_t c = wcnt[i][d];
+                wcnt[i][d] = run;
+                run += c;
+            }
+            tot[k] = run;
+            sum += run;
         }
         uint32_t exc, inc, total;
-        block_scan<kSortBlock>(run, AddOp(), 0u, wave_tot, &exc, &inc, &total);
-        dstart[tid] = exc;
-        gbase[tid] = bases[(size_t)tid * ntiles + blockIdx.x] - exc;
+        block_scan<kSortBlock>(sum, AddOp(), 0u, wave_tot, &exc, &inc, &total);
+#pragma unroll
+        for (int k = 0; k < DPT; ++k) {
+            const int d = tid * DPT + k;
+            dstart[d] = exc;
+            gbase[d] = bases[(size_t)d * ntiles + blockIdx.x] - exc;
+            exc += tot[k];
+        }
     }
     __syncthreads();
 
@@ -275,8 +292,22 @@ inline uint32_t sort_num_tiles(int64_t n) { return (uint32_t)(n > 0 ? ceil_div(n
 // uint32 words of temporary storage for radix_sort_pairs<.., IPT> of n elements
 template <int IPT>
 inline size_t sort_temp_words(int64_t n) {
-    size_t counts = (size_t)kRadix * sort_num_tiles<IPT>(n);
+    size_t counts = (size_t)kMaxRadix * sort_num_tiles<IPT>(n);
     return counts + 64 + scan_partials((int64_t)counts) + 64;
+}
+
+template <typename K, int IPT, int RB>
+int radix_sort_pass(const K* kin, K* kout, const uint32_t* vin, uint32_t* vout, int64_t n, int bit, int nb,
+                    uint32_t* counts, uint32_t* partials, uint32_t ntiles, hipStream_t stream) {
+    const int64_t ncounts = (int64_t)(1 << RB) * ntiles;
+    const uint32_t mask = (1u << nb) - 1u;
+    BP_LAUNCH(K_SORT_UPSWEEP, (sort_upsweep_kernel<K, IPT, RB>), dim3(ntiles), dim3(kSortBlock), 0, stream, kin,
+              (uint32_t)n, bit, mask, counts, ntiles);
+    BP_TRY((device_scan<uint32_t, AddOp, LoadU32, StoreExclusiveU32>(LoadU32{counts}, StoreExclusiveU32{counts}, ncounts,
+                                                                     partials, AddOp(), 0u, stream)));
+    BP_LAUNCH(K_SORT_DOWNSWEEP, (sort_downsweep_kernel<K, IPT, RB>), dim3(ntiles), dim3(kSortBlock), 0, stream, kin, kout,
+              vin, vout, (uint32_t)n, bit, mask, (const uint32_t*)counts, ntiles);
+    return BP_OK;
 }
 
 // Sorts n (key, value) pairs by key bits [begin_bit, end_bit), stable.  The data ping-pongs between
@@ -286,25 +317,25 @@ template <typename K, int IPT>
 int radix_sort_pairs(K* keys_a, K* keys_b, uint32_t* vals_a, uint32_t* vals_b, int64_t n, int begin_bit, int end_bit,
                      uint32_t* temp, hipStream_t stream, bool* result_in_b) {
     *result_in_b = false;
-    if (n <= 0) return BP_OK;
+    if (n <= 0 || end_bit <= begin_bit) return BP_OK;
     const uint32_t ntiles = sort_num_tiles<IPT>(n);
-    const int64_t ncounts = (int64_t)kRadix * ntiles;
     uint32_t* counts = temp;
-    uint32_t* partials = temp + ((ncounts + 63) & ~int64_t(63));
+    uint32_t* partials = temp + (((size_t)kMaxRadix * ntiles + 63) & ~size_t(63));
     K* kin = keys_a;
     K* kout = keys_b;
     uint32_t* vin = vals_a;
     uint32_t* vout = vals_b;
-    for (int bit = begin_bit; bit < end_bit; bit += kRadixBits) {
-        const int nb = end_bit - bit < kRadixBits ? end_bit - bit : kRadixBits;
-        const uint32_t mask = (1u << nb) - 1u;
-        BP_LAUNCH(K_SORT_UPSWEEP, (sort_upsweep_kernel<K, IPT>), dim3(ntiles), dim3(kSortBlock), 0, stream,
-                  (const K*)kin, (uint32_t)n, bit, mask, counts, ntiles);
-        BP_TRY((device_scan<uint32_t, AddOp, LoadU32, StoreExclusiveU32>(LoadU32{counts}, StoreExclusiveU32{counts},
-                                                                         ncounts, partials, AddOp(), 0u, stream)));
-        BP_LAUNCH(K_SORT_DOWNSWEEP, (sort_downsweep_kernel<K, IPT>), dim3(ntiles), dim3(kSortBlock), 0, stream,
-                  (const K*)kin, kout, (const uint32_t*)vin, vout, (uint32_t)n, bit, mask, (const uint32_t*)counts,
-                  ntiles);
+    const int total = end_bit - begin_bit;
+    int passes = (total + kMaxRadixBits - 1) / kMaxRadixBits;
+    int bit = begin_bit;
+    for (int p = 0; p < passes; ++p) {
+        const int left = end_bit - bit;
+        const int nb = (left + (passes - p) - 1) / (passes - p);      // spread the remaining bits evenly
+        if (nb > 8)
+            BP_TRY((radix_sort_pass<K, IPT, 9>(kin, kout, vin, vout, n, bit, nb, counts, partials, ntiles, stream)));
+        else
+            BP_TRY((radix_sort_pass<K, IPT, 8>(kin, kout, vin, vout, n, bit, nb, counts, partials, ntiles, stream)));
+        bit += nb;
         K* tk = kin; kin = kout; kout = tk;
         uint32_t* tv = vin; vin = vout; vout = tv;
         *result_in_b = !*result_in_b;

@@ -393,7 +393,6 @@ struct GroupOut {
     int ib;
     int32_t* grouped_slots;
     int32_t* grouped_lookups;
-    int32_t* lookup_slots;  // the per-lookup slot map is scattered from here: a batch's targets share a small window
     uint32_t* item_starts;
     uint32_t* split_starts;
     int64_t* item_off;     // device copies of the CSR offsets, [T+1] each, pre-filled with -1
@@ -402,11 +401,8 @@ struct GroupOut {
         const uint64_t k = gkeys[p];
         const uint32_t i = (uint32_t)(k & ((uint64_t(1) << ib) - 1));
         const int64_t base = iter_off[i];
-        const int32_t slot = slot_of_pair[k >> ib];
-        const uint32_t pos = gpos[p];
-        grouped_slots[p] = slot;
-        grouped_lookups[p] = (int32_t)((int64_t)pos - base);
-        lookup_slots[pos] = slot;
+        grouped_slots[p] = slot_of_pair[k >> ib];
+        grouped_lookups[p] = (int32_t)((int64_t)gpos[p] - base);
         if ((uint32_t)inc != (uint32_t)exc) item_starts[(uint32_t)exc] = (uint32_t)(p - base);
         if ((inc >> 32) != (exc >> 32)) split_starts[exc >> 32] = (uint32_t)(p - base);
         if (p == base) {
@@ -415,6 +411,16 @@ struct GroupOut {
         }
     }
 };
+
+// The per-lookup slot map written from the batch-grouped order: the targets of neighbouring grouped lookups lie in
+// their batch's stretch of the map (a few MB at most), so the 4-byte stores combine in L2 instead of each costing a
+// partial line in HBM, as they do when scattered from the id-major order.
+__global__ __launch_bounds__(kBlock) void plan_lookup_slots_grouped_kernel(int64_t N, const uint32_t* __restrict__ gpos,
+                                                                           const int32_t* __restrict__ grouped_slots,
+                                                                           int32_t* __restrict__ lookup_slots) {
+    const int64_t p = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (p < N) lookup_slots[gpos[p]] = grouped_slots[p];
+}
 
 template <typename T>
 __global__ __launch_bounds__(kBlock) void fill_kernel(T* p, int64_t n, T v) {
@@ -667,8 +673,10 @@ BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int
         BP_TRY((device_scan<uint64_t, AddOp, ItemFlagIn, GroupOut>(
             ItemFlagIn{gkeys, w.iter_off, ib},
             GroupOut{gkeys, gpos, w.iter_off, w.slot_of_pair, ib, plan->grouped_slots, plan->grouped_lookups,
-                     plan->lookup_slots, plan->item_starts, plan->split_starts, w.item_off, w.split_off},
+                     plan->item_starts, plan->split_starts, w.item_off, w.split_off},
             N, w.scan_partials64, AddOp(), uint64_t(0), stream)));
+        BP_LAUNCH(K_PLAN_SLOTS, plan_lookup_slots_grouped_kernel, grid_for(N), dim3(kBlock), 0, stream, N, gpos,
+                  (const int32_t*)plan->grouped_slots, plan->lookup_slots);
         BP_HIP(hipMemcpyAsync(&n_items_split, w.scan_partials64 + scan_num_tiles(N), sizeof(uint64_t), hipMemcpyDeviceToHost,
                               stream));
         BP_HIP(hipMemcpyAsync(plan->item_offsets, w.item_off, sizeof(int64_t) * (T + 1), hipMemcpyDeviceToHost, stream));
