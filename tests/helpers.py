@@ -24,12 +24,48 @@ def _grad_host(cfg, i, bags):
     return workloads.upstream_grad(cfg, i, bags, device=dev).cpu().numpy()
 
 
+def init_table_host(cfg, chunk_rows=1 << 21):
+    """The oracle's full table with the hash-defined initial weights, filled chunk by chunk (on the GPU when there
+    is one: the generator is integer-exact, so the bits are the same) so that 100 GB tables never need a second
+    copy or 64-bit temporaries of their full size."""
+    R, D = cfg.total_rows, cfg.dim
+    dev = "cuda:0" if torch.cuda.is_available() else "cpu"
+    bf16 = cfg.weight_dtype == "bf16"
+    W = np.empty((R, D), dtype=np.uint16 if bf16 else np.float32)
+    for a in range(0, R, chunk_rows):
+        b = min(R, a + chunk_rows)
+        w = workloads.init_weights(cfg, a, b, device=dev)
+        if bf16:
+            W[a:b] = w.to(torch.bfloat16).view(torch.int16).cpu().numpy().view(np.uint16)
+        else:
+            W[a:b] = w.cpu().numpy()
+    return W
+
+
+class OracleStepper:
+    """Oracle part B one batch at a time, for lockstep comparison with the GPU at sizes where keeping every
+    pooled output would not fit in memory."""
+
+    def __init__(self, cfg, trace):
+        self.cfg, self.trace = cfg, trace
+        self.dt, self.op = oracle_codes(cfg)
+        self.W = init_table_host(cfg)
+        self.S = np.zeros(oracle.state_shape(cfg.total_rows, cfg.dim, self.op), dtype=np.float32)
+        self.bags = trace.bag_offsets.shape[1] - 1
+
+    def step(self, i):
+        c = self.cfg
+        g = _grad_host(c, i, self.bags)
+        return oracle.train_iter(self.W, self.S, c.dim, self.dt, self.op, c.lr, c.eps, self.trace.iter_ids(i),
+                                 self.trace.bag_offsets[i], g)
+
+
 def oracle_uncached(cfg, trace, T=None, keep_outputs=True, progress=None):
     """Oracle part B: synchronous training on the full table.  Returns (W, S, [out_i])."""
     T = trace.iter_offsets.shape[0] - 1 if T is None else T
     R, D = cfg.total_rows, cfg.dim
     dt, op = oracle_codes(cfg)
-    W = table_to_numpy(cfg, workloads.init_weights(cfg, 0, R))
+    W = init_table_host(cfg)
     S = np.zeros(oracle.state_shape(R, D, op), dtype=np.float32)
     outs = []
     bags = trace.bag_offsets.shape[1] - 1

@@ -91,3 +91,119 @@ def test_config2_full():
     say("config 2 full")
     plan = run_full(cfg, cfg.capacity)
     assert 1 < plan.L_eff < cfg.lookahead and plan.peak_occupancy <= cfg.capacity
+
+
+# ---------------------------------------------------------------------------------------------------
+# configs[3] and configs[4]: full tables, full batches; the number of batches is reduced for the training
+# comparison (the oracle needs ~1-3 s per batch at these sizes), the planner is compared on the whole trace.
+# ---------------------------------------------------------------------------------------------------
+def compare_plans(plan, want_plan):
+    assert plan.L_eff == want_plan.L_eff and plan.peak_occupancy == want_plan.peak
+    assert np.array_equal(plan.occupancy, want_plan.occ)
+    for a, b in (("prefetch_offsets", "prefetch_off"), ("evict_offsets", "evict_off"), ("keep_offsets", "keep_off")):
+        assert np.array_equal(getattr(plan, a), getattr(want_plan, b)), a
+    for name in ("lookup_slots", "prefetch_ids", "prefetch_slots", "evict_ids", "evict_slots", "keep_ids", "keep_ttl"):
+        assert np.array_equal(getattr(plan, name).cpu().numpy(), getattr(want_plan, name)), name
+
+
+def run_lockstep(cfg, T, pinned):
+    """Plan + T batches, the oracle stepping one batch ahead of every GPU forward so that no output is stored."""
+    t0 = time.time()
+    trace = workloads.make_trace(cfg, iterations=T)
+    say(f"  trace {trace.n_lookups} lookups in {T} batches ({time.time() - t0:.1f} s)")
+    t0 = time.time()
+    want_plan = oracle.plan(trace.ids, trace.iter_offsets, cfg.total_rows, cfg.lookahead, cfg.capacity)
+    say(f"  oracle plan L_eff={want_plan.L_eff} peak={want_plan.peak} ({time.time() - t0:.1f} s)")
+    t0 = time.time()
+    stepper = helpers.OracleStepper(cfg, trace)
+    say(f"  oracle table ready ({time.time() - t0:.1f} s)")
+    worst = [0.0]
+    t_or = [0.0]
+
+    def check(i, out):
+        t1 = time.time()
+        want = stepper.step(i)
+        t_or[0] += time.time() - t1
+        got = out.cpu().numpy()
+        helpers.assert_outputs_close(got, want, cfg.bag_max, same_table=(i == 0 and cfg.bag_max == 1))
+        worst[0] = max(worst[0], float(np.abs(got - want).max()))
+        if (i + 1) % 10 == 0:
+            say(f"  batch {i + 1}/{T}: outputs match (oracle {t_or[0]:.0f} s so far)")
+
+    t0 = time.time()
+    tr, plan, W, S = helpers.gpu_cached_training(cfg, trace, T=T, pinned=pinned, check_outputs=check)
+    say(f"  gpu plan + training + lockstep oracle ({time.time() - t0:.1f} s), worst |out - oracle| {worst[0]:.3g}")
+    compare_plans(plan, want_plan)
+    gs, gl, st, ioff, sp, soff = oracle.group_lookups(trace.ids, trace.iter_offsets, want_plan.lookup_slots)
+    assert np.array_equal(plan.grouped_slots.cpu().numpy(), gs) and np.array_equal(plan.grouped_lookups.cpu().numpy(), gl)
+    assert np.array_equal(plan.item_offsets, ioff) and np.array_equal(plan.split_offsets, soff)
+    del gs, gl, st, sp
+    # final table: compare in row blocks to bound the memory of the comparison itself
+    R = cfg.total_rows
+    worst_w = 0.0
+    for a in range(0, R, 1 << 22):
+        b = min(R, a + (1 << 22))
+        got = W[a:b].cpu()
+        if cfg.weight_dtype == "bf16":
+            assert np.array_equal(got.view(torch.int16).numpy().view(np.uint16), stepper.W[a:b]), f"bf16 rows {a}..{b}"
+        else:
+            worst_w = max(worst_w, helpers.assert_weights_close(got.numpy(), stepper.W[a:b]))
+    if cfg.weight_dtype != "bf16":
+        say(f"  worst weight error / bound(1e-4): {worst_w / 1e-4:.3g}")
+    if stepper.S.size:
+        got_s = S.cpu().numpy()
+        if cfg.weight_dtype == "bf16":
+            assert np.array_equal(got_s, stepper.S)
+        else:
+            np.testing.assert_allclose(got_s, stepper.S, rtol=1e-4, atol=1e-9)
+    return plan
+
+
+@pytest.mark.timeout(1500)
+def test_config3_full_tables():
+    """configs[3]: 20 tables x 5 M rows, D=64, bags of 1..50 ids (~4.2 M lookups per batch), batch 8,192, L=300,
+    cache 4 M rows, SGD; 25.6 GB backing table in pinned host memory.  30 of the 100 batches."""
+    cfg = workloads.CONFIGS[3]
+    say("config 3, full tables, 30 batches")
+    plan = run_lockstep(cfg, 30, pinned=True)
+    assert plan.peak_occupancy <= cfg.capacity
+
+
+@pytest.mark.timeout(1500)
+def test_config4_full_tables():
+    """configs[4]: 40 tables x 10 M rows, D=128 bf16 rows with fp32 arithmetic, row-wise Adagrad, batch 32,768
+    (1.31 M lookups per batch), L=500, cache 16 M rows, hot set re-drawn every 50 batches.  60 of the 300 batches
+    (one re-draw inside); the 102 GB backing table lives in HBM here so that the oracle's copy fits in host RAM."""
+    cfg = workloads.CONFIGS[4]
+    say("config 4, full tables, 60 batches")
+    plan = run_lockstep(cfg, 60, pinned=False)
+    assert plan.peak_occupancy <= cfg.capacity
+
+
+@pytest.mark.timeout(1500)
+@pytest.mark.parametrize("index", [3, 4])
+def test_plan_whole_trace_configs_3_and_4(index):
+    """The planner alone on the complete traces of configs[3] (≈418 M lookups) and configs[4] (393 M lookups, hot set
+    re-drawn every 50 batches): every list, the slot map and the grouping, bit for bit."""
+    import paper_2202_12429_amd as bp
+    cfg = workloads.CONFIGS[index]
+    say(f"config {index}: whole-trace plan")
+    t0 = time.time()
+    trace = workloads.make_trace(cfg)
+    say(f"  trace {trace.n_lookups} lookups ({time.time() - t0:.1f} s)")
+    t0 = time.time()
+    plan = bp.bp_oracle_plan(helpers.bp_config_of(cfg), torch.from_numpy(trace.ids).cuda(), trace.iter_offsets, grouping=True)
+    torch.cuda.synchronize()
+    say(f"  gpu plan L_eff={plan.L_eff} peak={plan.peak_occupancy} pairs={plan.n_unique_pairs} ({time.time() - t0:.1f} s incl. allocation)")
+    t0 = time.time()
+    want = oracle.plan(trace.ids, trace.iter_offsets, cfg.total_rows, cfg.lookahead, cfg.capacity)
+    say(f"  oracle plan ({time.time() - t0:.1f} s)")
+    compare_plans(plan, want)
+    t0 = time.time()
+    gs, gl, st, ioff, sp, soff = oracle.group_lookups(trace.ids, trace.iter_offsets, want.lookup_slots)
+    say(f"  oracle grouping ({time.time() - t0:.1f} s)")
+    assert np.array_equal(plan.item_offsets, ioff) and np.array_equal(plan.split_offsets, soff)
+    assert np.array_equal(plan.grouped_slots.cpu().numpy(), gs)
+    assert np.array_equal(plan.grouped_lookups.cpu().numpy(), gl)
+    assert np.array_equal(plan.item_starts.cpu().numpy().view(np.uint32), st)
+    assert np.array_equal(plan.split_starts.cpu().numpy().view(np.uint32), sp)
