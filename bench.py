@@ -199,7 +199,9 @@ def main() -> int:
 
     bag_off_dev = None if cfg.one_hot else [torch.from_numpy(np.ascontiguousarray(trace.bag_offsets[i])).to(dev)
                                             for i in range(T)]
-    grads_dev = [workloads.upstream_grad(cfg, i, bags, device=dev) for i in range(W + K)]
+    # upstream gradients resident before the timed region; beyond 16 GB the buffers are reused round-robin
+    n_grad = min(W + K, max(2, int(16e9 // (bags * D * 4))))
+    grads_dev = [workloads.upstream_grad(cfg, i, bags, device=dev) for i in range(n_grad)]
     out = torch.empty((bags, D), dtype=torch.float32, device=dev)
     torch.cuda.synchronize()
     n_timed = int(n_per_iter[W:W + K].sum())
@@ -214,7 +216,7 @@ def main() -> int:
             bo = None if bag_off_dev is None else bag_off_dev[i]
             trainer.maintain(i)
             trainer.forward(i, bo, bags, out=out)
-            trainer.backward_update(i, bo, bags, grads_dev[i])
+            trainer.backward_update(i, bo, bags, grads_dev[i % n_grad])
 
         def run_pass(profile_kernels):
             """Warm-up W steps, then K timed steps.  profile_kernels: [] = every kernel bracketed, or a list."""

@@ -6,6 +6,22 @@ import oracle
 import workloads
 
 
+def say(msg):
+    """Progress line of a long test: printed, and appended to gpurun_out/gpu_test_progress.log so that a run whose
+    stdout is captured still shows signs of life."""
+    import os
+    import sys
+    print(msg, flush=True)
+    try:
+        root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+        os.makedirs(os.path.join(root, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(root, "gpurun_out", "gpu_test_progress.log"), "a") as f:
+            f.write(msg + "\n")
+    except OSError:
+        pass
+    sys.stdout.flush()
+
+
 def table_to_numpy(cfg, w_f32: torch.Tensor) -> np.ndarray:
     """fp32 tensor -> the oracle's storage array (fp32, or bf16 bit patterns as uint16)."""
     if cfg.weight_dtype == "bf16":

@@ -15,9 +15,7 @@ import workloads
 pytestmark = pytest.mark.gpu
 
 
-def say(msg):
-    print(msg, flush=True)
-    sys.stdout.flush()
+say = helpers.say
 
 
 @pytest.fixture(scope="module")
