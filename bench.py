@@ -49,8 +49,9 @@ def algorithmic_bytes(kernel: str, n: int, bags: int, u: float, row_b: int, stat
         # slot per lookup + offsets (none for one-hot) + every distinct row once + pooled output
         return 4 * n + (0 if one_hot else 8 * (bags + 1)) + u * row_b + bags * D * 4
     if kernel == "bwd_reduce_update":
-        # sorted slot + bag id per lookup, one gradient row per lookup, read-modify-write of every distinct row + state
-        return 8 * n + n * D * 4 + 2 * u * (row_b + state_b)
+        # sorted slot + bag id per lookup, every distinct gradient row once (a bag's row serves all its lookups),
+        # read-modify-write of every distinct row + state
+        return 8 * n + min(n, bags) * D * 4 + 2 * u * (row_b + state_b)
     raise KeyError(kernel)
 
 

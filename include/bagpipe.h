@@ -105,7 +105,8 @@ typedef struct bp_plan {
     uint32_t* item_starts;     /* device [n_lookups] first grouped lookup of each work item, relative to the batch */
     int64_t* item_offsets;     /* host [T+1] CSR offsets of the batches into item_starts */
     uint32_t* split_starts;    /* device [n_lookups / BP_BWD_CHUNK + 1] first grouped lookup (relative to the batch) of
-                                  every row whose lookups span several work items */
+                                  every row whose lookups span three work items or more (they reach the second
+                                  multiple of BP_BWD_CHUNK after the row's first lookup) */
     int64_t* split_offsets;    /* host [T+1] CSR offsets of the batches into split_starts */
     /* scalar results */
     int32_t L_eff;

@@ -391,7 +391,7 @@ int orc_cache_apply(void *cache_w, float *cache_state, void *host_w, float *host
  * id the lookup positions ascending), the cache slot of each grouped lookup, and the cuts of the grouped
  * list into work items: a new item starts where the id changes and at every multiple of `chunk` positions
  * counted from the batch's first grouped lookup.  split_starts lists the first grouped lookup of every id
- * whose lookups span several items (they reach past the next multiple of `chunk`).  This is bookkeeping for
+ * whose lookups span three items or more (they reach the second multiple of `chunk` after the first lookup).  This is bookkeeping for
  * the backward pass, not part of Algorithm 1; the definition is this build's.  Returns the number of items
  * or <0.
  */
@@ -412,8 +412,8 @@ int64_t orc_group_lookups(const int64_t *ids, const int64_t *iter_off, int64_t T
             grouped_slots[a + p] = lookup_slots[a + rp[p].pos];
             if (p % chunk == 0 || rp[p].row != rp[p - 1].row) item_starts[nitems++] = (uint32_t)p;
             if (p == 0 || rp[p].row != rp[p - 1].row) {            /* first lookup of an id */
-                int64_t next_cut = (p / chunk + 1) * chunk;
-                if (next_cut < n && rp[next_cut].row == rp[p].row) split_starts[nsplit++] = (uint32_t)p;
+                int64_t second_cut = (p / chunk + 2) * chunk;
+                if (second_cut < n && rp[second_cut].row == rp[p].row) split_starts[nsplit++] = (uint32_t)p;
             }
         }
         free(rp);

@@ -9,8 +9,9 @@
 //      multiple of kChunk positions (so a slot hit thousands of times by a skewed batch is shared by
 //      many lane groups); item starts are compacted with a scan.
 //   3. one lane group per item adds its gradient rows in order (fp64 accumulators).  An item that covers its whole
-//      slot applies the update at once; otherwise the sum goes to a partial row addressed by the chunk
-//      boundary it touches.
+//      slot applies the update at once; so does the first item of a slot that crosses a single cut (it carries on
+//      to the slot's end and the second item steps aside); otherwise the sum goes to a partial row addressed by
+//      the chunk boundary it touches.
 //   4. for slots split over several items, one wavefront adds the partial rows (lane groups round-robin,
 //      then a butterfly across the groups) and applies the update.
 // Every order of addition is fixed by the data, never by timing: results are bit-identical run to run.
@@ -202,24 +203,39 @@ __global__ __launch_bounds__(kRowBlock) void bwd_reduce_update_kernel(const uint
         if ((int64_t)slot >= C) continue;            // sentinel of out-of-range slots
         const bool head = start == 0 || keys[start - 1] != slot;
         const bool tail = end == n || keys[end] != slot;
+        // A row that crosses exactly one cut (it starts in one chunk and ends in the next) is finished by its first
+        // item alone: that item carries on to the row's end, the second item steps aside.  Only rows that cross two
+        // cuts or more go through partial sums.
+        uint32_t last = end;
+        bool whole = head && tail;
+        if (head && !tail) {
+            const uint64_t cut2 = (uint64_t)end + kChunk;              // `end` is a cut; the next one
+            if (cut2 >= n || keys[cut2] != slot) {
+                last = w + 2 < W ? item_start[w + 2] : n;               // end of the row's second (and last) item
+                whole = true;
+            }
+        } else if (!head && tail) {
+            const uint32_t prev_cut = start - kChunk;                   // `start` is a cut >= kChunk
+            if (prev_cut == 0 || keys[prev_cut - 1] != slot) continue;  // the row began in the previous chunk
+        }
         SumPiece<N> acc;
         acc.zero();
         if (active) {
             uint32_t p = start;
-            for (; p + 4 <= end; p += 4) {           // four gradient rows in flight, added in order
+            for (; p + 4 <= last; p += 4) {          // four gradient rows in flight, added in order
                 Piece<BF16> t[4];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) t[j].load_f32(grad + (size_t)bag_of[p + j] * u.dim, c);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) acc.add(t[j]);
             }
-            for (; p < end; ++p) {
+            for (; p < last; ++p) {
                 Piece<BF16> t;
                 t.load_f32(grad + (size_t)bag_of[p] * u.dim, c);
                 acc.add(t);
             }
         }
-        if (head && tail) {
+        if (whole) {
             apply_update<GW, BF16>(u, cache_w, cache_s, (int64_t)slot, c, acc.template rounded<BF16>());
         } else if (active) {
             // head item of a split slot ends on a chunk boundary b*kChunk: row 2b; a later item starts on
@@ -257,6 +273,10 @@ __global__ __launch_bounds__(kRowBlock) void bwd_combine_update_kernel(const uin
         const bool head = start == 0 || keys[start - 1] != slot;
         const bool tail = end == n || keys[end] != slot;
         if (!head || tail) continue;                  // only the first item of a split slot works here
+        {
+            const uint64_t cut2 = (uint64_t)end + kChunk;
+            if (cut2 >= n || keys[cut2] != slot) continue;   // crosses one cut only: done by the reduce kernel
+        }
         SumPiece<N> acc;
         acc.zero();
         const uint32_t b0 = end / kChunk;             // end is a chunk boundary because the slot goes on
@@ -300,6 +320,7 @@ __global__ __launch_bounds__(kRowBlock) void bwd_combine_split_kernel(const uint
                                                                      const double* __restrict__ partial, UpdateParams u) {
     constexpr int N = Piece<BF16>::N;
     constexpr int G = kRowBlock / GW;                 // lane groups per workgroup
+    constexpr int U = G >= 64 ? 1 : (G >= 32 ? 2 : 4);  // partial rows in flight per group: about 64 per round
     __shared__ double red[G][N][GW];
     const int c = threadIdx.x % GW, j = threadIdx.x / GW;
     const bool active = c < u.lpr;
@@ -311,11 +332,11 @@ __global__ __launch_bounds__(kRowBlock) void bwd_combine_split_kernel(const uint
     SumPiece<N> acc;
     acc.zero();
     if (active && j == 0) acc.load(partial + 2 * (size_t)b0 * u.dim, c);
-    for (uint64_t b = (uint64_t)b0 + j;; b += 4 * G) {
-        bool ok[4];
-        SumPiece<N> t[4];
+    for (uint64_t b = (uint64_t)b0 + j;; b += U * G) {
+        bool ok[U];
+        SumPiece<N> t[U];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
+        for (int k = 0; k < U; ++k) {
             const uint64_t bb = b + (uint64_t)k * G;
             // the key test and the partial row are loaded side by side (row 2bb+1 exists whenever
             // bb*kChunk < n; a row that turns out not to belong to the slot is dropped): one latency per round
@@ -326,9 +347,9 @@ __global__ __launch_bounds__(kRowBlock) void bwd_combine_split_kernel(const uint
             ok[k] = inb && key == slot;
         }
 #pragma unroll
-        for (int k = 0; k < 4; ++k)
+        for (int k = 0; k < U; ++k)
             if (ok[k]) acc.add(t[k]);
-        if (!ok[3]) break;
+        if (!ok[U - 1]) break;
     }
 #pragma unroll
     for (int i = 0; i < N; ++i) red[j][i][c] = acc.v[i];

@@ -364,8 +364,9 @@ __global__ __launch_bounds__(kBlock) void plan_group_keys_kernel(int64_t N, int 
 }
 
 // A work item of the grouped backward pass starts where the row changes and at every multiple of kBwdChunk
-// positions counted from the batch's first lookup.  A row is "split" when its lookups go past the next such
-// multiple, i.e. they span several items.  Low word: item start flag; high word: first lookup of a split row.
+// positions counted from the batch's first lookup.  A row is "split" when its lookups go past the next two such
+// multiples, i.e. they span three items or more (a row spanning two items is finished by its first item).
+// Low word: item start flag; high word: first lookup of a split row.
 struct ItemFlagIn {
     const uint64_t* gkeys;
     const int64_t* iter_off;
@@ -379,8 +380,8 @@ struct ItemFlagIn {
         const bool item = first_of_row || rel % kBwdChunk == 0;
         bool split = false;
         if (first_of_row) {
-            const int64_t nb = base + (rel / kBwdChunk + 1) * kBwdChunk;               // next cut after p
-            split = nb < iter_off[i + 1] && (gkeys[nb] >> ib) == (k >> ib);
+            const int64_t nb2 = base + (rel / kBwdChunk + 2) * kBwdChunk;              // second cut after p
+            split = nb2 < iter_off[i + 1] && (gkeys[nb2] >> ib) == (k >> ib);
         }
         return (uint64_t)item | ((uint64_t)split << 32);
     }
