@@ -102,7 +102,8 @@ typedef struct bp_plan {
      * from the batch's first grouped lookup). */
     int32_t* grouped_slots;    /* device [n_lookups] cache slot of each grouped lookup */
     int32_t* grouped_lookups;  /* device [n_lookups] its position, relative to the batch's first lookup */
-    uint32_t* item_starts;     /* device [n_lookups] first grouped lookup of each work item, relative to the batch */
+    uint32_t* item_starts;     /* device [n_lookups] first grouped lookup of each work item, relative to the batch,
+                                  with bit 31 set when that lookup is the first of its row */
     int64_t* item_offsets;     /* host [T+1] CSR offsets of the batches into item_starts */
     uint32_t* split_starts;    /* device [n_lookups / BP_BWD_CHUNK + 1] first grouped lookup (relative to the batch) of
                                   every row whose lookups span three work items or more (they reach the second

@@ -390,7 +390,7 @@ int orc_cache_apply(void *cache_w, float *cache_state, void *host_w, float *host
  * Optional by-product of the plan: the lookups of every batch grouped by row (ids ascending, and for one
  * id the lookup positions ascending), the cache slot of each grouped lookup, and the cuts of the grouped
  * list into work items: a new item starts where the id changes and at every multiple of `chunk` positions
- * counted from the batch's first grouped lookup.  split_starts lists the first grouped lookup of every id
+ * counted from the batch's first grouped lookup (bit 31 of an item's start marks the first kind).  split_starts lists the first grouped lookup of every id
  * whose lookups span three items or more (they reach the second multiple of `chunk` after the first lookup).  This is bookkeeping for
  * the backward pass, not part of Algorithm 1; the definition is this build's.  Returns the number of items
  * or <0.
@@ -410,7 +410,9 @@ int64_t orc_group_lookups(const int64_t *ids, const int64_t *iter_off, int64_t T
         for (int64_t p = 0; p < n; ++p) {
             grouped_lookups[a + p] = (int32_t)rp[p].pos;
             grouped_slots[a + p] = lookup_slots[a + rp[p].pos];
-            if (p % chunk == 0 || rp[p].row != rp[p - 1].row) item_starts[nitems++] = (uint32_t)p;
+            int first_of_id = p == 0 || rp[p].row != rp[p - 1].row;
+            if (p % chunk == 0 || first_of_id)                     /* bit 31 marks an item that starts an id */
+                item_starts[nitems++] = (uint32_t)p | (first_of_id ? 0x80000000u : 0u);
             if (p == 0 || rp[p].row != rp[p - 1].row) {            /* first lookup of an id */
                 int64_t second_cut = (p / chunk + 2) * chunk;
                 if (second_cut < n && rp[second_cut].row == rp[p].row) split_starts[nsplit++] = (uint32_t)p;

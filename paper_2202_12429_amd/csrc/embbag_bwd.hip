@@ -68,10 +68,16 @@ struct ItemStartIn {
         return (p == 0 || (p % kChunk) == 0 || keys[p] != keys[p - 1]) ? 1u : 0u;
     }
 };
+// An item record is the position of the item's first sorted lookup, with bit 31 set when that lookup is the first
+// of its slot.  Everything else a kernel needs to know about an item follows from its neighbours' records: the item
+// ends where the next one starts, and it is the last of its slot iff the next item is a first.
+constexpr uint32_t kItemHead = 0x80000000u, kItemPos = 0x7fffffffu;
+
 struct ItemStartOut {
+    const uint32_t* keys;
     uint32_t* item_start;
     __device__ __forceinline__ void operator()(int64_t p, uint32_t exc, uint32_t inc) const {
-        if (inc != exc) item_start[exc] = (uint32_t)p;
+        if (inc != exc) item_start[exc] = (uint32_t)p | ((p == 0 || keys[p] != keys[p - 1]) ? kItemHead : 0u);
     }
 };
 
@@ -132,18 +138,41 @@ __device__ __forceinline__ double group_sum(double x) {
     return x;
 }
 
-// Applies one optimizer step to the piece of lane c of row `slot`; g is the row's summed gradient in fp32.
-// All lanes of the group call this (the row-wise rule reduces over the group); lanes with c >= lpr carry
-// zeros and touch no memory.  One fp32 operation per statement: step = lr*g, then for Adagrad
-// s += g*g, den = sqrt(s) + eps, step /= den, and w -= step.
+// The piece of lane c of row `slot` and of its optimizer state, loaded ahead of the gradient sum so that the row's
+// latency hides behind the gradient loads.
+template <bool BF16>
+struct RowPiece {
+    uint4 w_raw;
+    Piece<BF16> s;       // element-wise Adagrad state
+    float s_row;         // row-wise Adagrad state
+};
+
+template <bool BF16>
+__device__ __forceinline__ RowPiece<BF16> load_row(const UpdateParams& u, const uint4* cache_w, const float* cache_s,
+                                                   int64_t slot, int c, bool active) {
+    RowPiece<BF16> r;
+    r.w_raw = make_uint4(0, 0, 0, 0);
+    r.s.zero();
+    r.s_row = 0.f;
+    if (active) {
+        r.w_raw = cache_w[slot * u.lpr + c];
+        if (u.optimizer == BP_ADAGRAD) r.s.load_f32(cache_s + slot * u.dim, c);
+    }
+    if (u.optimizer == BP_ADAGRAD_ROWWISE) r.s_row = cache_s[slot];
+    return r;
+}
+
+// Applies one optimizer step to the piece of lane c of row `slot`; g is the row's summed gradient in fp32, r the
+// piece as loaded by load_row.  All lanes of the group call this (the row-wise rule reduces over the group); lanes
+// with c >= lpr carry zeros and touch no memory, and neither do the lanes of a group that is not the writer.
+// One fp32 operation per statement: step = lr*g, then for Adagrad s += g*g, den = sqrt(s) + eps, step /= den,
+// and w -= step.
 template <int GW, bool BF16>
-__device__ __forceinline__ void apply_update(const UpdateParams& u, uint4* cache_w, float* cache_s, int64_t slot, int c,
-                                             const Piece<BF16>& g, bool writer = true) {
+__device__ __forceinline__ void finish_update(const UpdateParams& u, uint4* cache_w, float* cache_s, int64_t slot, int c,
+                                              const RowPiece<BF16>& r, const Piece<BF16>& g, bool active) {
     constexpr int N = Piece<BF16>::N;
-    const bool active = c < u.lpr && writer;
     Piece<BF16> w;
-    w.zero();
-    if (active) w.decode(cache_w[slot * u.lpr + c]);
+    w.decode(r.w_raw);
     if (u.optimizer == BP_SGD) {
 #pragma unroll
         for (int i = 0; i < N; ++i) {
@@ -151,35 +180,40 @@ __device__ __forceinline__ void apply_update(const UpdateParams& u, uint4* cache
             w.v[i] = w.v[i] - step;
         }
     } else if (u.optimizer == BP_ADAGRAD) {
-        if (active) {
-            Piece<BF16> s;
-            s.load_f32(cache_s + slot * u.dim, c);
+        Piece<BF16> s = r.s;
 #pragma unroll
-            for (int i = 0; i < N; ++i) {
-                const float gg = g.v[i] * g.v[i];
-                s.v[i] = s.v[i] + gg;
-                const float den = sqrtf(s.v[i]) + u.eps;
-                const float step = (u.lr * g.v[i]) / den;
-                w.v[i] = w.v[i] - step;
-            }
-            s.store_f32(cache_s + slot * u.dim, c);
+        for (int i = 0; i < N; ++i) {
+            const float gg = g.v[i] * g.v[i];
+            s.v[i] = s.v[i] + gg;
+            const float den = sqrtf(s.v[i]) + u.eps;
+            const float step = (u.lr * g.v[i]) / den;
+            w.v[i] = w.v[i] - step;
         }
+        if (active) s.store_f32(cache_s + slot * u.dim, c);
     } else {
         double ss = 0.0;                       // mean of squares over the row: an fp64 sum, rounded once
 #pragma unroll
         for (int i = 0; i < N; ++i) ss += (double)g.v[i] * (double)g.v[i];
         ss = group_sum<GW>(ss);
         const float mean = (float)(ss / (double)u.dim);
-        const float s = cache_s[slot] + mean;
+        const float s = r.s_row + mean;
         const float den = sqrtf(s) + u.eps;
 #pragma unroll
         for (int i = 0; i < N; ++i) {
             const float step = (u.lr * g.v[i]) / den;
             w.v[i] = w.v[i] - step;
         }
-        if (c == 0 && writer) cache_s[slot] = s;
+        if (c == 0 && active) cache_s[slot] = s;
     }
     if (active) cache_w[slot * u.lpr + c] = w.encode();
+}
+
+template <int GW, bool BF16>
+__device__ __forceinline__ void apply_update(const UpdateParams& u, uint4* cache_w, float* cache_s, int64_t slot, int c,
+                                             const Piece<BF16>& g, bool writer = true) {
+    const bool active = c < u.lpr && writer;
+    const RowPiece<BF16> r = load_row<BF16>(u, cache_w, cache_s, slot, c, active);
+    finish_update<GW, BF16>(u, cache_w, cache_s, slot, c, r, g, active);
 }
 
 template <int GW, bool BF16>
@@ -197,27 +231,28 @@ __global__ __launch_bounds__(kRowBlock) void bwd_reduce_update_kernel(const uint
     const bool active = c < u.lpr;
     const uint32_t groups = gridDim.x * (kRowBlock / GW);
     for (uint32_t w = (blockIdx.x * kRowBlock + threadIdx.x) / GW; w < W; w += groups) {
-        const uint32_t start = item_start[w];
-        const uint32_t end = w + 1 < W ? item_start[w + 1] : n;
-        const uint32_t slot = keys[start];
-        if ((int64_t)slot >= C) continue;            // sentinel of out-of-range slots
-        const bool head = start == 0 || keys[start - 1] != slot;
-        const bool tail = end == n || keys[end] != slot;
+        const uint32_t r0 = item_start[w];
+        const uint32_t r1 = w + 1 < W ? item_start[w + 1] : (n | kItemHead);
+        const uint32_t start = r0 & kItemPos, end = r1 & kItemPos;
+        const bool head = (r0 & kItemHead) != 0, tail = (r1 & kItemHead) != 0;
         // A row that crosses exactly one cut (it starts in one chunk and ends in the next) is finished by its first
         // item alone: that item carries on to the row's end, the second item steps aside.  Only rows that cross two
         // cuts or more go through partial sums.
         uint32_t last = end;
         bool whole = head && tail;
         if (head && !tail) {
-            const uint64_t cut2 = (uint64_t)end + kChunk;              // `end` is a cut; the next one
-            if (cut2 >= n || keys[cut2] != slot) {
-                last = w + 2 < W ? item_start[w + 2] : n;               // end of the row's second (and last) item
+            const uint32_t r2 = w + 2 < W ? item_start[w + 2] : (n | kItemHead);
+            if (r2 & kItemHead) {                                       // the row's second item is its last
+                last = r2 & kItemPos;
                 whole = true;
             }
         } else if (!head && tail) {
-            const uint32_t prev_cut = start - kChunk;                   // `start` is a cut >= kChunk
-            if (prev_cut == 0 || keys[prev_cut - 1] != slot) continue;  // the row began in the previous chunk
+            if (item_start[w - 1] & kItemHead) continue;                // second of two: the first item does it all
         }
+        const uint32_t slot = keys[start];
+        if ((int64_t)slot >= C) continue;            // sentinel of out-of-range slots
+        RowPiece<BF16> row;
+        if (whole) row = load_row<BF16>(u, cache_w, cache_s, (int64_t)slot, c, active);
         SumPiece<N> acc;
         acc.zero();
         if (active) {
@@ -236,12 +271,12 @@ __global__ __launch_bounds__(kRowBlock) void bwd_reduce_update_kernel(const uint
             }
         }
         if (whole) {
-            apply_update<GW, BF16>(u, cache_w, cache_s, (int64_t)slot, c, acc.template rounded<BF16>());
+            finish_update<GW, BF16>(u, cache_w, cache_s, (int64_t)slot, c, row, acc.template rounded<BF16>(), active);
         } else if (active) {
             // head item of a split slot ends on a chunk boundary b*kChunk: row 2b; a later item starts on
             // boundary b*kChunk: row 2b+1
-            const size_t row = head ? 2 * (size_t)(end / kChunk) : 2 * (size_t)(start / kChunk) + 1;
-            acc.store(partial + row * u.dim, c);
+            const size_t prow = head ? 2 * (size_t)(end / kChunk) : 2 * (size_t)(start / kChunk) + 1;
+            acc.store(partial + prow * u.dim, c);
         }
     }
 }
@@ -266,17 +301,14 @@ __global__ __launch_bounds__(kRowBlock) void bwd_combine_update_kernel(const uin
     const bool active = c < u.lpr;
     const uint32_t waves = gridDim.x * (kRowBlock / kWave);
     for (uint32_t w = (blockIdx.x * kRowBlock + threadIdx.x) / kWave; w < W; w += waves) {
-        const uint32_t start = item_start[w];
-        const uint32_t end = w + 1 < W ? item_start[w + 1] : n;
+        const uint32_t r0 = item_start[w];
+        const uint32_t r1 = w + 1 < W ? item_start[w + 1] : (n | kItemHead);
+        if (!(r0 & kItemHead) || (r1 & kItemHead)) continue;   // only the first item of a split slot works here
+        const uint32_t r2 = w + 2 < W ? item_start[w + 2] : (n | kItemHead);
+        if (r2 & kItemHead) continue;                           // crosses one cut only: done by the reduce kernel
+        const uint32_t start = r0 & kItemPos, end = r1 & kItemPos;
         const uint32_t slot = keys[start];
         if ((int64_t)slot >= C) continue;
-        const bool head = start == 0 || keys[start - 1] != slot;
-        const bool tail = end == n || keys[end] != slot;
-        if (!head || tail) continue;                  // only the first item of a split slot works here
-        {
-            const uint64_t cut2 = (uint64_t)end + kChunk;
-            if (cut2 >= n || keys[cut2] != slot) continue;   // crosses one cut only: done by the reduce kernel
-        }
         SumPiece<N> acc;
         acc.zero();
         const uint32_t b0 = end / kChunk;             // end is a chunk boundary because the slot goes on
@@ -479,7 +511,7 @@ BP_EXPORT int bp_embbag_bwd_update(const bp_config* cfg, void* cache_w, void* ca
     const uint32_t* skeys = in_b ? w.keys_b : w.keys_a;
     const uint32_t* sbags = in_b ? w.vals_b : w.vals_a;
 
-    BP_TRY((device_scan<uint32_t, AddOp, ItemStartIn, ItemStartOut>(ItemStartIn{skeys}, ItemStartOut{w.item_start}, n,
+    BP_TRY((device_scan<uint32_t, AddOp, ItemStartIn, ItemStartOut>(ItemStartIn{skeys}, ItemStartOut{skeys, w.item_start}, n,
                                                                     w.scan_partials, AddOp(), 0u, stream)));
     const uint32_t* n_items = w.scan_partials + scan_num_tiles(n);
 

@@ -404,7 +404,10 @@ struct GroupOut {
         const int64_t base = iter_off[i];
         grouped_slots[p] = slot_of_pair[k >> ib];
         grouped_lookups[p] = (int32_t)((int64_t)gpos[p] - base);
-        if ((uint32_t)inc != (uint32_t)exc) item_starts[(uint32_t)exc] = (uint32_t)(p - base);
+        if ((uint32_t)inc != (uint32_t)exc) {
+            const bool first_of_row = p == base || (gkeys[p - 1] >> ib) != (k >> ib);
+            item_starts[(uint32_t)exc] = (uint32_t)(p - base) | (first_of_row ? 0x80000000u : 0u);
+        }
         if ((inc >> 32) != (exc >> 32)) split_starts[exc >> 32] = (uint32_t)(p - base);
         if (p == base) {
             item_off[i] = (uint32_t)exc;
