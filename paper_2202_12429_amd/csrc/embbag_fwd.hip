@@ -47,7 +47,7 @@ __global__ __launch_bounds__(kRowBlock) void embbag_fwd_kernel(const uint4* __re
             }
         }
     }
-    acc.store_f32(out + bag * dim, c);
+    acc.store_f32_stream(out + bag * dim, c);
 }
 
 struct FwdLaunch {

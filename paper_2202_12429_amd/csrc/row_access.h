@@ -81,6 +81,27 @@ struct Piece {
 #pragma unroll
         for (int i = 0; i < N / 4; ++i) p[i] = make_float4(v[4 * i], v[4 * i + 1], v[4 * i + 2], v[4 * i + 3]);
     }
+    // Streaming variants for data touched once (pooled output, upstream gradient of one-hot bags): non-temporal
+    // accesses leave the cache lines to the table rows that are reused.
+    __device__ __forceinline__ void load_f32_stream(const float* row, int c) {
+        typedef float vec4 __attribute__((ext_vector_type(4)));
+        const vec4* p = reinterpret_cast<const vec4*>(row + (size_t)c * N);
+#pragma unroll
+        for (int i = 0; i < N / 4; ++i) {
+            const vec4 t = __builtin_nontemporal_load(p + i);
+            v[4 * i] = t.x; v[4 * i + 1] = t.y; v[4 * i + 2] = t.z; v[4 * i + 3] = t.w;
+        }
+    }
+    __device__ __forceinline__ void store_f32_stream(float* row, int c) const {
+        typedef float vec4 __attribute__((ext_vector_type(4)));
+        vec4* p = reinterpret_cast<vec4*>(row + (size_t)c * N);
+#pragma unroll
+        for (int i = 0; i < N / 4; ++i) {
+            vec4 t;
+            t.x = v[4 * i]; t.y = v[4 * i + 1]; t.z = v[4 * i + 2]; t.w = v[4 * i + 3];
+            __builtin_nontemporal_store(t, p + i);
+        }
+    }
     __device__ __forceinline__ void add(const Piece& o) {
 #pragma unroll
         for (int i = 0; i < N; ++i) v[i] += o.v[i];
