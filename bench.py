@@ -32,9 +32,9 @@ HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published peak
 # HBM traffic per launch of the dominant kernel from rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE; KiB per dispatch,
 # scaled by the copy-kernel calibration), keyed by (workload, kernel).  Filled in from profiles/; None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/hbm_traffic_cfg2_pmc.txt: FETCH_SIZE 76402.7 KiB x2 (copy calibration) + WRITE_SIZE 40386.6 KiB x1
-    ("criteo_kaggle_d48", "bwd_reduce_update"): 197.83e6,
-    ("criteo_kaggle_d48", "embbag_fwd"): 128.39e6,
+    # profiles/hbm_traffic_cfg2_pmc.txt: FETCH_SIZE 76907.5 KiB x2 (copy calibration) + WRITE_SIZE 39449.9 KiB x1
+    ("criteo_kaggle_d48", "bwd_reduce_update"): 197.90e6,
+    ("criteo_kaggle_d48", "embbag_fwd"): 123.74e6,
 }
 
 
