@@ -216,6 +216,8 @@ __device__ __forceinline__ void apply_update(const UpdateParams& u, uint4* cache
     finish_update<GW, BF16>(u, cache_w, cache_s, slot, c, r, g, active);
 }
 
+// One lane group per work item.  Loads are issued as early as their addresses are known: the item's records
+// together, then its slot and the first gradient indices together, then the cache row and the gradient rows.
 template <int GW, bool BF16>
 __global__ __launch_bounds__(kRowBlock) void bwd_reduce_update_kernel(const uint32_t* __restrict__ keys,
                                                                      const uint32_t* __restrict__ bag_of,
@@ -231,43 +233,40 @@ __global__ __launch_bounds__(kRowBlock) void bwd_reduce_update_kernel(const uint
     const bool active = c < u.lpr;
     const uint32_t groups = gridDim.x * (kRowBlock / GW);
     for (uint32_t w = (blockIdx.x * kRowBlock + threadIdx.x) / GW; w < W; w += groups) {
+        const uint32_t rp = item_start[w > 0 ? w - 1 : 0];
         const uint32_t r0 = item_start[w];
         const uint32_t r1 = w + 1 < W ? item_start[w + 1] : (n | kItemHead);
+        const uint32_t r2 = w + 2 < W ? item_start[w + 2] : (n | kItemHead);
         const uint32_t start = r0 & kItemPos, end = r1 & kItemPos;
         const bool head = (r0 & kItemHead) != 0, tail = (r1 & kItemHead) != 0;
         // A row that crosses exactly one cut (it starts in one chunk and ends in the next) is finished by its first
         // item alone: that item carries on to the row's end, the second item steps aside.  Only rows that cross two
         // cuts or more go through partial sums.
-        uint32_t last = end;
-        bool whole = head && tail;
-        if (head && !tail) {
-            const uint32_t r2 = w + 2 < W ? item_start[w + 2] : (n | kItemHead);
-            if (r2 & kItemHead) {                                       // the row's second item is its last
-                last = r2 & kItemPos;
-                whole = true;
-            }
-        } else if (!head && tail) {
-            if (item_start[w - 1] & kItemHead) continue;                // second of two: the first item does it all
-        }
+        const bool takes_next = head && !tail && (r2 & kItemHead);     // the row's second item is its last
+        const bool steps_aside = !head && tail && (rp & kItemHead);    // second of two: the first item does it all
+        const uint32_t last = takes_next ? (r2 & kItemPos) : end;
+        const bool whole = (head && tail) || takes_next;
         const uint32_t slot = keys[start];
-        if ((int64_t)slot >= C) continue;            // sentinel of out-of-range slots
+        uint32_t idx[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) idx[j] = start + j < last ? bag_of[start + j] : 0u;
+        if (steps_aside || (int64_t)slot >= C) continue;               // slot C: sentinel of out-of-range slots
         RowPiece<BF16> row;
         if (whole) row = load_row<BF16>(u, cache_w, cache_s, (int64_t)slot, c, active);
         SumPiece<N> acc;
         acc.zero();
         if (active) {
-            uint32_t p = start;
-            for (; p + 4 <= last; p += 4) {          // four gradient rows in flight, added in order
+            // bursts of four rows; the indices of the next burst are loaded while the rows of this one arrive
+            for (uint32_t p = start; p < last; p += 4) {
                 Piece<BF16> t[4];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) t[j].load_f32(grad + (size_t)bag_of[p + j] * u.dim, c);
+                for (int j = 0; j < 4; ++j)
+                    if (p + j < last) t[j].load_f32(grad + (size_t)idx[j] * u.dim, c);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) acc.add(t[j]);
-            }
-            for (; p < last; ++p) {
-                Piece<BF16> t;
-                t.load_f32(grad + (size_t)bag_of[p] * u.dim, c);
-                acc.add(t);
+                for (int j = 0; j < 4; ++j) idx[j] = p + 4 + j < last ? bag_of[p + 4 + j] : 0u;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (p + j < last) acc.add(t[j]);
             }
         }
         if (whole) {

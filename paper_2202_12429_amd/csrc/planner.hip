@@ -7,7 +7,8 @@
 //   TTL                   =   last use inside [i, i + L_eff - 1]
 // so the planner sorts (id, batch) keys, dedupes them into unique pairs, reads gaps off neighbouring
 // pairs, and derives everything else with scans:
-//   1. keys (id << iter_bits | batch), stable LSD radix sort with the lookup position as payload
+//   1. keys (id << iter_bits | batch), stable LSD radix sort on the id bits with the lookup position as payload
+//      (the input is batch-major, so equal ids stay in batch order)
 //   2. head flags + scan  -> unique pairs (sorted by id, then batch), pair index of every lookup
 //   3. histogram H[gap][batch] and per-batch unique counts -> occupancy for every candidate lookahead
 //      -> L_eff = largest lookahead whose peak occupancy fits the capacity
@@ -18,8 +19,8 @@
 //      C are the initial slots, position C + e holds the slot freed by the e-th eviction, i.e. the slot
 //      of an earlier miss.  Following those links is pointer jumping, ceil(log2 T) + 1 rounds.
 //   7. slots of pairs -> list slots and the per-lookup slot map
-//   8. (optional) one more stable pass on the batch bits lists every batch's lookups grouped by row, with the
-//      work-item cuts the grouped backward pass uses, so that the backward pass need not sort
+//   8. (optional) one more stable pass on the batch bits, with (slot, batch) keys, lists every batch's lookups grouped
+//      by row, with the work-item cuts the grouped backward pass uses, so that the backward pass need not sort
 #include <vector>
 
 #include "common.h"
@@ -54,10 +55,20 @@ __global__ __launch_bounds__(kBlock) void plan_keys_kernel(const int64_t* __rest
         atomicOr(&sc->error_flags, 1u);
         g = 0;
     }
-    int lo = 0, hi = T;   // iter_off[lo] <= p < iter_off[hi]
+    // batch of position p: iter_off[lo] <= p < iter_off[lo + 1].  The search starts from the batch of the workgroup's
+    // first position (same for all its lanes), and nearly always ends there.
+    const int64_t p_first = (int64_t)blockIdx.x * kBlock;
+    int lo = 0, hi = T;
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
-        if (iter_off[mid] <= p) lo = mid; else hi = mid;
+        if (iter_off[mid] <= p_first) lo = mid; else hi = mid;
+    }
+    if (iter_off[lo + 1] <= p) {
+        hi = T;
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (iter_off[mid] <= p) lo = mid; else hi = mid;
+        }
     }
     keys[p] = ((uint64_t)g << ib) | (uint64_t)lo;
     pos[p] = (uint32_t)p;
@@ -346,34 +357,49 @@ __global__ __launch_bounds__(kBlock) void plan_list_slots_kernel(const uint64_t*
     if (x < n_evict) evict_slots[x] = slot_of_pair[evict_pair[x]];
 }
 
-__global__ __launch_bounds__(kBlock) void plan_lookup_slots_kernel(int64_t N, const uint32_t* __restrict__ pos,
+// Workgroups are handed to the eight XCDs round-robin, and each XCD has an L2 of its own.  The kernels below write
+// 4-byte values to scattered places of a stretch of memory; when the workgroups that share a stretch run on one XCD
+// the stores meet in its L2 and leave as full lines.  This maps blockIdx so that XCD x walks the x-th eighth of the
+// virtual blocks in order.
+constexpr uint32_t kXcds = 8;
+__device__ __forceinline__ int64_t xcd_contiguous_block(uint32_t per_xcd) {
+    return (int64_t)(blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+}
+inline uint32_t blocks_per_xcd(int64_t n) { return (uint32_t)ceil_div(n > 0 ? ceil_div(n, kBlock) : 1, (int64_t)kXcds); }
+
+__global__ __launch_bounds__(kBlock) void plan_lookup_slots_kernel(int64_t N, uint32_t per_xcd,
+                                                                   const uint32_t* __restrict__ pos,
                                                                    const uint32_t* __restrict__ uq,
                                                                    const int32_t* __restrict__ slot_of_pair,
                                                                    int32_t* __restrict__ lookup_slots) {
-    const int64_t p = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int64_t p = xcd_contiguous_block(per_xcd) * kBlock + threadIdx.x;
     if (p < N) lookup_slots[pos[p]] = slot_of_pair[uq[p]];
 }
 
 // ---- 8. lookups of every batch grouped by row (optional) ---------------------------------------
-// key <- (pair index << iter_bits) | batch: a stable sort on the batch bits then lists every batch's lookups
-// grouped by id (pairs are numbered in id order) and in lookup order inside a group.
-__global__ __launch_bounds__(kBlock) void plan_group_keys_kernel(int64_t N, int ib, const uint32_t* __restrict__ uq,
-                                                                 uint64_t* keys) {
+// key <- (slot << iter_bits) | batch, written in the id-major order (where the pair indices, and so the reads of the
+// pairs' slots, ascend): a stable sort on the batch bits then lists every batch's lookups grouped by id and in lookup
+// order inside a group.  Inside one batch a change of slot is a change of row.  K is uint32_t when the key fits.
+template <typename K>
+__global__ __launch_bounds__(kBlock) void plan_group_keys_kernel(int64_t N, int ib, const uint64_t* skeys,
+                                                                 const uint32_t* __restrict__ uq,
+                                                                 const int32_t* __restrict__ slot_of_pair, K* gkeys) {
     const int64_t p = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (p < N) keys[p] = ((uint64_t)uq[p] << ib) | (keys[p] & ((uint64_t(1) << ib) - 1));
+    if (p < N) gkeys[p] = ((K)(uint32_t)slot_of_pair[uq[p]] << ib) | (K)(skeys[p] & ((uint64_t(1) << ib) - 1));
 }
 
 // A work item of the grouped backward pass starts where the row changes and at every multiple of kBwdChunk
 // positions counted from the batch's first lookup.  A row is "split" when its lookups go past the next two such
 // multiples, i.e. they span three items or more (a row spanning two items is finished by its first item).
 // Low word: item start flag; high word: first lookup of a split row.
+template <typename K>
 struct ItemFlagIn {
-    const uint64_t* gkeys;
+    const K* gkeys;
     const int64_t* iter_off;
     int ib;
     __device__ __forceinline__ uint64_t operator()(int64_t p) const {
-        const uint64_t k = gkeys[p];
-        const uint32_t i = (uint32_t)(k & ((uint64_t(1) << ib) - 1));
+        const K k = gkeys[p];
+        const uint32_t i = (uint32_t)(k & ((K(1) << ib) - 1));
         const int64_t base = iter_off[i];
         const int64_t rel = p - base;
         const bool first_of_row = rel == 0 || (gkeys[p - 1] >> ib) != (k >> ib);      // rel == 0 guards p == 0
@@ -386,11 +412,11 @@ struct ItemFlagIn {
         return (uint64_t)item | ((uint64_t)split << 32);
     }
 };
+template <typename K>
 struct GroupOut {
-    const uint64_t* gkeys;
+    const K* gkeys;
     const uint32_t* gpos;
     const int64_t* iter_off;
-    const int32_t* slot_of_pair;
     int ib;
     int32_t* grouped_slots;
     int32_t* grouped_lookups;
@@ -399,10 +425,10 @@ struct GroupOut {
     int64_t* item_off;     // device copies of the CSR offsets, [T+1] each, pre-filled with -1
     int64_t* split_off;
     __device__ __forceinline__ void operator()(int64_t p, uint64_t exc, uint64_t inc) const {
-        const uint64_t k = gkeys[p];
-        const uint32_t i = (uint32_t)(k & ((uint64_t(1) << ib) - 1));
+        const K k = gkeys[p];
+        const uint32_t i = (uint32_t)(k & ((K(1) << ib) - 1));
         const int64_t base = iter_off[i];
-        grouped_slots[p] = slot_of_pair[k >> ib];
+        grouped_slots[p] = (int32_t)(k >> ib);
         grouped_lookups[p] = (int32_t)((int64_t)gpos[p] - base);
         if ((uint32_t)inc != (uint32_t)exc) {
             const bool first_of_row = p == base || (gkeys[p - 1] >> ib) != (k >> ib);
@@ -417,13 +443,14 @@ struct GroupOut {
 };
 
 // The per-lookup slot map written from the batch-grouped order: the targets of neighbouring grouped lookups lie in
-// their batch's stretch of the map (a few MB at most), so the 4-byte stores combine in L2 instead of each costing a
-// partial line in HBM, as they do when scattered from the id-major order.
-__global__ __launch_bounds__(kBlock) void plan_lookup_slots_grouped_kernel(int64_t N, const uint32_t* __restrict__ gpos,
-                                                                           const int32_t* __restrict__ grouped_slots,
+// their batch's stretch of the map (a few MB at most).
+template <typename K>
+__global__ __launch_bounds__(kBlock) void plan_lookup_slots_grouped_kernel(int64_t N, uint32_t per_xcd, int ib,
+                                                                           const uint32_t* __restrict__ gpos,
+                                                                           const K* __restrict__ gkeys,
                                                                            int32_t* __restrict__ lookup_slots) {
-    const int64_t p = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (p < N) lookup_slots[gpos[p]] = grouped_slots[p];
+    const int64_t p = xcd_contiguous_block(per_xcd) * kBlock + threadIdx.x;
+    if (p < N) lookup_slots[gpos[p]] = (int32_t)(gkeys[p] >> ib);
 }
 
 template <typename T>
@@ -502,6 +529,37 @@ int check_plan_args(const bp_config* cfg, int64_t N, int32_t T) {
 
 inline dim3 grid_for(int64_t n) { return dim3((unsigned)(n > 0 ? ceil_div(n, kBlock) : 1)); }
 
+// Step 8 for one key width.  ka receives the keys (for 64-bit keys it may be the sorted (id, batch) keys' own
+// buffer: every element is read and written by the same lane), kb is the other half of the ping-pong.
+struct GroupingPass {
+    int64_t N;
+    int T, ib;
+    const uint64_t* skeys;
+    uint32_t* spos;
+    const uint32_t* uq;
+    PlanWorkspace* w;
+    bp_plan* plan;
+    hipStream_t stream;
+    template <typename K>
+    int run(K* ka, K* kb) {
+        BP_LAUNCH(K_PLAN_GROUP, plan_group_keys_kernel<K>, grid_for(N), dim3(kBlock), 0, stream, N, ib, skeys, uq,
+                  (const int32_t*)w->slot_of_pair, ka);
+        bool in_b = false;
+        BP_TRY((radix_sort_pairs<K, kPlanSortIPT>(ka, kb, spos, w->pos_c, N, 0, ib, w->sort_temp, stream, &in_b)));
+        const K* gkeys = in_b ? kb : ka;
+        const uint32_t* gpos = in_b ? w->pos_c : spos;
+        BP_TRY((device_scan<uint64_t, AddOp, ItemFlagIn<K>, GroupOut<K>>(
+            ItemFlagIn<K>{gkeys, w->iter_off, ib},
+            GroupOut<K>{gkeys, gpos, w->iter_off, ib, plan->grouped_slots, plan->grouped_lookups, plan->item_starts,
+                        plan->split_starts, w->item_off, w->split_off},
+            N, w->scan_partials64, AddOp(), uint64_t(0), stream)));
+        const uint32_t per_xcd = blocks_per_xcd(N);
+        BP_LAUNCH(K_PLAN_SLOTS, plan_lookup_slots_grouped_kernel<K>, dim3(per_xcd * kXcds), dim3(kBlock), 0, stream, N,
+                  per_xcd, ib, gpos, gkeys, plan->lookup_slots);
+        return BP_OK;
+    }
+};
+
 }  // namespace
 }  // namespace bp
 
@@ -566,7 +624,8 @@ BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int
     BP_LAUNCH(K_PLAN_KEYS, plan_keys_kernel, grid_for(N), dim3(kBlock), 0, stream, ids, (const int64_t*)w.iter_off, T, N,
               cfg->total_rows, ib, w.keys_a, w.pos_a, w.scalars);
     bool in_b = false;
-    BP_TRY((radix_sort_pairs<uint64_t, kPlanSortIPT>(w.keys_a, w.keys_b, w.pos_a, w.pos_b, N, 0, ib + gb, w.sort_temp,
+    // the lookups arrive batch by batch, so a stable sort on the id bits alone leaves every id's keys in batch order
+    BP_TRY((radix_sort_pairs<uint64_t, kPlanSortIPT>(w.keys_a, w.keys_b, w.pos_a, w.pos_b, N, ib, ib + gb, w.sort_temp,
                                                      stream, &in_b)));
     const uint64_t* skeys = in_b ? w.keys_b : w.keys_a;
     const uint32_t* spos = in_b ? w.pos_b : w.pos_a;
@@ -653,9 +712,11 @@ BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int
               (const uint32_t*)w.missord, (const uint32_t*)w.par, w.slot_of_pair);
     BP_LAUNCH(K_PLAN_SLOTS, plan_list_slots_kernel, grid_for(M), dim3(kBlock), 0, stream, totals, (const uint32_t*)w.par,
               (const uint32_t*)w.evict_pair, (const int32_t*)w.slot_of_pair, plan->prefetch_slots, plan->evict_slots);
-    if (!grouping)      // with grouping the slot map is written from the batch-grouped order (step 8)
-        BP_LAUNCH(K_PLAN_SLOTS, plan_lookup_slots_kernel, grid_for(N), dim3(kBlock), 0, stream, N, spos,
+    if (!grouping) {    // with grouping the slot map is written from the batch-grouped order (step 8)
+        const uint32_t per_xcd = blocks_per_xcd(N);
+        BP_LAUNCH(K_PLAN_SLOTS, plan_lookup_slots_kernel, dim3(per_xcd * kXcds), dim3(kBlock), 0, stream, N, per_xcd, spos,
                   (const uint32_t*)uq, (const int32_t*)w.slot_of_pair, plan->lookup_slots);
+    }
 
     uint64_t htot = 0;     // miss / evict totals: fetched now, the grouping scan below reuses the partials buffer
     BP_HIP(hipMemcpyAsync(&htot, totals, sizeof(uint64_t), hipMemcpyDeviceToHost, stream));
@@ -663,24 +724,15 @@ BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int
     // ---- 8. grouping for the backward pass
     uint64_t n_items_split = 0;
     if (grouping) {
-        uint64_t* gk_a = const_cast<uint64_t*>(skeys);
-        uint32_t* gp_a = const_cast<uint32_t*>(spos);
-        BP_LAUNCH(K_PLAN_GROUP, plan_group_keys_kernel, grid_for(N), dim3(kBlock), 0, stream, N, ib, (const uint32_t*)uq, gk_a);
-        bool g_in_b = false;
-        BP_TRY((radix_sort_pairs<uint64_t, kPlanSortIPT>(gk_a, w.keys_c, gp_a, w.pos_c, N, 0, ib, w.sort_temp, stream, &g_in_b)));
-        const uint64_t* gkeys = g_in_b ? w.keys_c : gk_a;
-        const uint32_t* gpos = g_in_b ? w.pos_c : gp_a;
         BP_LAUNCH(K_FILL, fill_kernel<int64_t>, grid_for(T + 1), dim3(kBlock), 0, stream, w.item_off, (int64_t)(T + 1),
                   (int64_t)-1);
         BP_LAUNCH(K_FILL, fill_kernel<int64_t>, grid_for(T + 1), dim3(kBlock), 0, stream, w.split_off, (int64_t)(T + 1),
                   (int64_t)-1);
-        BP_TRY((device_scan<uint64_t, AddOp, ItemFlagIn, GroupOut>(
-            ItemFlagIn{gkeys, w.iter_off, ib},
-            GroupOut{gkeys, gpos, w.iter_off, w.slot_of_pair, ib, plan->grouped_slots, plan->grouped_lookups,
-                     plan->item_starts, plan->split_starts, w.item_off, w.split_off},
-            N, w.scan_partials64, AddOp(), uint64_t(0), stream)));
-        BP_LAUNCH(K_PLAN_SLOTS, plan_lookup_slots_grouped_kernel, grid_for(N), dim3(kBlock), 0, stream, N, gpos,
-                  (const int32_t*)plan->grouped_slots, plan->lookup_slots);
+        GroupingPass g{N, T, ib, skeys, const_cast<uint32_t*>(spos), uq, &w, plan, stream};
+        if (bits_for(C) + ib <= 32)
+            BP_TRY(g.run<uint32_t>(reinterpret_cast<uint32_t*>(w.keys_c), reinterpret_cast<uint32_t*>(w.keys_c) + N));
+        else
+            BP_TRY(g.run<uint64_t>(const_cast<uint64_t*>(skeys), w.keys_c));
         BP_HIP(hipMemcpyAsync(&n_items_split, w.scan_partials64 + scan_num_tiles(N), sizeof(uint64_t), hipMemcpyDeviceToHost,
                               stream));
         BP_HIP(hipMemcpyAsync(plan->item_offsets, w.item_off, sizeof(int64_t) * (T + 1), hipMemcpyDeviceToHost, stream));

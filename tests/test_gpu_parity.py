@@ -350,6 +350,20 @@ def test_plan_medium_multi_tile(bp):
     plan_both(bp, tr.ids, tr.iter_offsets, cfg.total_rows, 60, 10 ** 6)         # lookahead beyond the trace
 
 
+def test_plan_many_batches_wide_group_keys(bp):
+    """4,100 short batches (13 batch bits) with a capacity of 2^20: slot and batch bits together exceed 32, so the
+    grouping runs on 64-bit keys; the other plan tests take the 32-bit path."""
+    say("plan with many batches and wide grouping keys")
+    rng = np.random.default_rng(77)
+    T, R = 4100, 300
+    lens = rng.integers(0, 9, size=T)
+    off = np.zeros(T + 1, dtype=np.int64)
+    off[1:] = np.cumsum(lens)
+    ids = np.minimum(rng.zipf(1.3, size=int(off[-1])) - 1, R - 1).astype(np.int64)
+    plan_both(bp, ids, off, R, 50, 1 << 20)
+    plan_both(bp, ids, off, R, 7, 9)                       # same trace, narrow keys, capacity binds
+
+
 def test_plan_errors(bp):
     say("plan errors")
     ids = np.array([0, 1, 2, 3, 0, 1], dtype=np.int64)
