@@ -68,26 +68,43 @@ __device__ __forceinline__ void block_scan(T x, Op op, T identity, T* wave_tot, 
 //   pass 1  per-tile reduction                   -> partials[tile]
 //   pass 2  one workgroup scans the partials in place (exclusive) and appends the grand total
 //   pass 3  per-tile scan seeded with its partial
-// A tile is kScanRounds consecutive rounds of 256 consecutive elements, so loads coalesce.
+// A tile is kScanTile consecutive elements; each wavefront owns a contiguous stretch of it and takes it in
+// kScanRounds rounds of 64 consecutive elements (lane l holds element r*64 + l of the stretch), so loads coalesce
+// and a round is scanned with lane shuffles alone; the workgroup meets at one barrier per tile.
 // Op must be associative and commutative (add, max).
 // ---------------------------------------------------------------------------------------------
 constexpr int kScanBlock = 256;
 constexpr int kScanRounds = 8;
 constexpr int kScanTile = kScanBlock * kScanRounds;
+constexpr int kScanWaveStretch = kWave * kScanRounds;
+
+template <typename T, typename Op>
+__device__ __forceinline__ T wave_reduce(T x, Op op) {
+#pragma unroll
+    for (int off = kWave / 2; off >= 1; off >>= 1) x = op(x, __shfl_xor(x, off, kWave));
+    return x;
+}
 
 template <typename T, typename Op, typename In>
 __global__ __launch_bounds__(kScanBlock) void scan_reduce_kernel(In in, int64_t n, T* partials, Op op, T identity) {
     __shared__ T wave_tot[kScanBlock / kWave];
-    const int64_t base = (int64_t)blockIdx.x * kScanTile;
+    const int w = threadIdx.x / kWave, lane = lane_id();
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + w * kScanWaveStretch + lane;
     T acc = identity;
 #pragma unroll
     for (int r = 0; r < kScanRounds; ++r) {
-        int64_t i = base + r * kScanBlock + threadIdx.x;
+        const int64_t i = base + r * kWave;
         if (i < n) acc = op(acc, in(i));
     }
-    T exc, inc, total;
-    block_scan<kScanBlock>(acc, op, identity, wave_tot, &exc, &inc, &total);
-    if (threadIdx.x == 0) partials[blockIdx.x] = total;
+    acc = wave_reduce(acc, op);
+    if (lane == 0) wave_tot[w] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        T total = identity;
+#pragma unroll
+        for (int k = 0; k < kScanBlock / kWave; ++k) total = op(total, wave_tot[k]);
+        partials[blockIdx.x] = total;
+    }
 }
 
 template <typename T, typename Op>
@@ -109,16 +126,29 @@ template <typename T, typename Op, typename In, typename Out>
 __global__ __launch_bounds__(kScanBlock) void scan_apply_kernel(In in, Out out, int64_t n, const T* partials, Op op,
                                                                 T identity) {
     __shared__ T wave_tot[kScanBlock / kWave];
-    const int64_t base = (int64_t)blockIdx.x * kScanTile;
-    T carry = partials[blockIdx.x];
-#pragma unroll 1
+    const int w = threadIdx.x / kWave, lane = lane_id();
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + w * kScanWaveStretch + lane;
+    T v[kScanRounds];
+    T mine = identity;
+#pragma unroll
     for (int r = 0; r < kScanRounds; ++r) {
-        int64_t i = base + r * kScanBlock + threadIdx.x;
-        T v = i < n ? in(i) : identity;
-        T exc, inc, total;
-        block_scan<kScanBlock>(v, op, identity, wave_tot, &exc, &inc, &total);
+        const int64_t i = base + r * kWave;
+        v[r] = i < n ? in(i) : identity;
+        mine = op(mine, v[r]);
+    }
+    mine = wave_reduce(mine, op);
+    if (lane == 0) wave_tot[w] = mine;
+    __syncthreads();
+    T carry = partials[blockIdx.x];                       // everything before this wavefront's stretch
+    for (int k = 0; k < w; ++k) carry = op(carry, wave_tot[k]);
+#pragma unroll
+    for (int r = 0; r < kScanRounds; ++r) {
+        const int64_t i = base + r * kWave;
+        const T inc = wave_inclusive_scan(v[r], op);
+        T exc = __shfl_up(inc, 1, kWave);
+        if (lane == 0) exc = identity;
         if (i < n) out(i, op(carry, exc), op(carry, inc));
-        carry = op(carry, total);
+        carry = op(carry, __shfl(inc, kWave - 1, kWave));
     }
 }
 
@@ -149,6 +179,26 @@ int device_scan(In in, Out out, int64_t n, T* partials, Op op, T identity, hipSt
 // The bits to sort are spread evenly over the fewest passes of at most 9 bits (34 bits: 9+9+8+8).
 // ---------------------------------------------------------------------------------------------
 constexpr int kSortBlock = 256;
+#ifndef BP_SORT_XCD
+#define BP_SORT_XCD 1
+#endif
+// Tile of this workgroup.  Workgroups go to the eight XCDs round-robin; with the mapping below XCD x takes the x-th
+// eighth of the tiles in order, so the tiles whose scattered runs are neighbours in memory meet in one L2.
+__device__ __forceinline__ uint32_t sort_tile_of_block(uint32_t ntiles) {
+#if BP_SORT_XCD
+    const uint32_t per = (ntiles + 7u) / 8u;
+    return (blockIdx.x % 8u) * per + blockIdx.x / 8u;
+#else
+    return blockIdx.x;
+#endif
+}
+inline uint32_t sort_grid(uint32_t ntiles) {
+#if BP_SORT_XCD
+    return (ntiles + 7u) / 8u * 8u;
+#else
+    return ntiles;
+#endif
+}
 constexpr int kMaxRadixBits = 9;
 constexpr int kMaxRadix = 1 << kMaxRadixBits;
 
@@ -158,16 +208,18 @@ __global__ __launch_bounds__(kSortBlock) void sort_upsweep_kernel(const K* __res
                                                                   uint32_t ntiles) {
     constexpr int RADIX = 1 << RB;
     __shared__ uint32_t hist[RADIX];
+    const uint32_t tile = sort_tile_of_block(ntiles);
+    if (tile >= ntiles) return;
     for (int d = threadIdx.x; d < RADIX; d += kSortBlock) hist[d] = 0;
     __syncthreads();
-    const uint32_t base = blockIdx.x * (kSortBlock * IPT);
+    const uint32_t base = tile * (kSortBlock * IPT);
 #pragma unroll
     for (int j = 0; j < IPT; ++j) {
         uint32_t i = base + j * kSortBlock + threadIdx.x;
         if (i < n) atomicAdd(&hist[(uint32_t)(keys[i] >> shift) & mask], 1u);
     }
     __syncthreads();
-    for (int d = threadIdx.x; d < RADIX; d += kSortBlock) counts[(size_t)d * ntiles + blockIdx.x] = hist[d];
+    for (int d = threadIdx.x; d < RADIX; d += kSortBlock) counts[(size_t)d * ntiles + tile] = hist[d];
 }
 
 template <typename K, int IPT, int RB>
@@ -190,10 +242,12 @@ __global__ __launch_bounds__(kSortBlock) void sort_downsweep_kernel(const K* __r
     __shared__ uint32_t svals[TILE];
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
+    const uint32_t tile = sort_tile_of_block(ntiles);
+    if (tile >= ntiles) return;
     for (int d = tid; d < WAVES * RADIX; d += kSortBlock) (&wcnt[0][0])[d] = 0;
     __syncthreads();
 
-    const uint32_t tile_base = blockIdx.x * TILE;
+    const uint32_t tile_base = tile * TILE;
     const uint32_t wbase = tile_base + w * WTILE;
     K key[IPT];
     uint32_t val[IPT];
@@ -247,7 +301,7 @@ __global__ __launch_bounds__(kSortBlock) void sort_downsweep_kernel(const K* __r
         for (int k = 0; k < DPT; ++k) {
             const int d = tid * DPT + k;
             dstart[d] = exc;
-            gbase[d] = bases[(size_t)d * ntiles + blockIdx.x] - exc;
+            gbase[d] = bases[(size_t)d * ntiles + tile] - exc;
             exc += tot[k];
         }
     }
@@ -301,11 +355,11 @@ int radix_sort_pass(const K* kin, K* kout, const uint32_t* vin, uint32_t* vout, 
                     uint32_t* counts, uint32_t* partials, uint32_t ntiles, hipStream_t stream) {
     const int64_t ncounts = (int64_t)(1 << RB) * ntiles;
     const uint32_t mask = (1u << nb) - 1u;
-    BP_LAUNCH(K_SORT_UPSWEEP, (sort_upsweep_kernel<K, IPT, RB>), dim3(ntiles), dim3(kSortBlock), 0, stream, kin,
+    BP_LAUNCH(K_SORT_UPSWEEP, (sort_upsweep_kernel<K, IPT, RB>), dim3(sort_grid(ntiles)), dim3(kSortBlock), 0, stream, kin,
               (uint32_t)n, bit, mask, counts, ntiles);
     BP_TRY((device_scan<uint32_t, AddOp, LoadU32, StoreExclusiveU32>(LoadU32{counts}, StoreExclusiveU32{counts}, ncounts,
                                                                      partials, AddOp(), 0u, stream)));
-    BP_LAUNCH(K_SORT_DOWNSWEEP, (sort_downsweep_kernel<K, IPT, RB>), dim3(ntiles), dim3(kSortBlock), 0, stream, kin, kout,
+    BP_LAUNCH(K_SORT_DOWNSWEEP, (sort_downsweep_kernel<K, IPT, RB>), dim3(sort_grid(ntiles)), dim3(kSortBlock), 0, stream, kin, kout,
               vin, vout, (uint32_t)n, bit, mask, (const uint32_t*)counts, ntiles);
     return BP_OK;
 }

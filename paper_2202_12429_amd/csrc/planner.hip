@@ -367,12 +367,11 @@ __device__ __forceinline__ int64_t xcd_contiguous_block(uint32_t per_xcd) {
 }
 inline uint32_t blocks_per_xcd(int64_t n) { return (uint32_t)ceil_div(n > 0 ? ceil_div(n, kBlock) : 1, (int64_t)kXcds); }
 
-__global__ __launch_bounds__(kBlock) void plan_lookup_slots_kernel(int64_t N, uint32_t per_xcd,
-                                                                   const uint32_t* __restrict__ pos,
+__global__ __launch_bounds__(kBlock) void plan_lookup_slots_kernel(int64_t N, const uint32_t* __restrict__ pos,
                                                                    const uint32_t* __restrict__ uq,
                                                                    const int32_t* __restrict__ slot_of_pair,
                                                                    int32_t* __restrict__ lookup_slots) {
-    const int64_t p = xcd_contiguous_block(per_xcd) * kBlock + threadIdx.x;
+    const int64_t p = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (p < N) lookup_slots[pos[p]] = slot_of_pair[uq[p]];
 }
 
@@ -712,11 +711,9 @@ BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int
               (const uint32_t*)w.missord, (const uint32_t*)w.par, w.slot_of_pair);
     BP_LAUNCH(K_PLAN_SLOTS, plan_list_slots_kernel, grid_for(M), dim3(kBlock), 0, stream, totals, (const uint32_t*)w.par,
               (const uint32_t*)w.evict_pair, (const int32_t*)w.slot_of_pair, plan->prefetch_slots, plan->evict_slots);
-    if (!grouping) {    // with grouping the slot map is written from the batch-grouped order (step 8)
-        const uint32_t per_xcd = blocks_per_xcd(N);
-        BP_LAUNCH(K_PLAN_SLOTS, plan_lookup_slots_kernel, dim3(per_xcd * kXcds), dim3(kBlock), 0, stream, N, per_xcd, spos,
+    if (!grouping)      // with grouping the slot map is written from the batch-grouped order (step 8)
+        BP_LAUNCH(K_PLAN_SLOTS, plan_lookup_slots_kernel, grid_for(N), dim3(kBlock), 0, stream, N, spos,
                   (const uint32_t*)uq, (const int32_t*)w.slot_of_pair, plan->lookup_slots);
-    }
 
     uint64_t htot = 0;     // miss / evict totals: fetched now, the grouping scan below reuses the partials buffer
     BP_HIP(hipMemcpyAsync(&htot, totals, sizeof(uint64_t), hipMemcpyDeviceToHost, stream));
