@@ -64,12 +64,17 @@ typedef struct bp_config {
                              one (Algorithm 1's LookAheadValue), >= 1 */
     float lr;             /* learning rate */
     float eps;            /* Adagrad epsilon */
+    int64_t reserve;      /* slots the planner's capacity policy leaves free, 0 <= reserve < capacity: L_eff is the
+                             largest lookahead whose peak occupancy is <= capacity - reserve, while slots still come
+                             from all `capacity` slots.  With reserve >= the misses of any one batch, every slot a
+                             batch's prefetches land in was already free before the previous batch trained, so they
+                             can be fetched while that batch trains (Section 3.2: prefetching overlaps training). */
 } bp_config;
 
 /* ------------------------------------------------------------------------------------------------
  * (1) Planner.  Algorithm 1 over a whole trace of T batches, plus the two choices the paper leaves
  * open: the effective lookahead L_eff is the largest L' <= lookahead whose peak cache occupancy is
- * <= capacity (Section 4, "Automatically Calculating Lookahead"), and cache slots come from a FIFO
+ * <= capacity - reserve (Section 4, "Automatically Calculating Lookahead"), and cache slots come from a FIFO
  * ring of free slots (initially 0..C-1; misses of a batch pop in ascending id order, evictions push
  * in ascending id order after all pops of that batch).
  *
@@ -112,7 +117,7 @@ typedef struct bp_plan {
     /* scalar results */
     int32_t L_eff;
     int64_t peak_occupancy;
-    int64_t min_capacity;      /* max_i |U_i|: the smallest capacity for which a plan exists */
+    int64_t min_capacity;      /* max_i |U_i|: the smallest capacity - reserve for which a plan exists */
     int64_t n_unique_pairs;    /* sum_i |U_i| */
 } bp_plan;
 
@@ -167,6 +172,67 @@ int bp_cache_apply_duplex(const bp_config* cfg, void* cache_w, void* cache_state
                           const int64_t* evict_ids, const int32_t* evict_slots, int64_t n_evict,
                           const int64_t* prefetch_ids, const int32_t* prefetch_slots, int64_t n_prefetch,
                           void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The two halves of bp_cache_apply_duplex as calls of their own, for a schedule that overlaps cache maintenance with
+ * training (Section 3.2 and 3.4: prefetches and write-backs run beside the trainer, touching slots the running batch
+ * does not use):
+ *   bp_cache_stage         copies the evicted rows (weights, state) from their slots to the staging area, entry e to
+ *                          staging row e; afterwards the slots may be refilled.
+ *   bp_cache_apply_staged  ONE launch writes the staged rows to the backing table (entry e to row evict_ids[e]) and
+ *                          copies the prefetched rows from the backing table into their slots.  Precondition: no id
+ *                          is in both lists.  Either list may be empty.
+ * Both calls of a pair take the same evict list and n_evict (the staging layout depends on n_evict) and the same
+ * staging area: device (HBM), bp_cache_apply_duplex_workspace_bytes(cfg, n_evict) bytes, 256-byte aligned, unused
+ * when n_evict == 0.  Entries with id or slot out of range are skipped by both.  Asynchronous on `stream`.
+ */
+int bp_cache_stage(const bp_config* cfg, const void* cache_w, const void* cache_state, const int32_t* evict_slots,
+                   int64_t n_evict, void* staging, size_t staging_bytes, void* stream);
+int bp_cache_apply_staged(const bp_config* cfg, void* cache_w, void* cache_state, void* backing_w, void* backing_state,
+                          const int64_t* evict_ids, const int32_t* evict_slots, int64_t n_evict, const void* staging,
+                          size_t staging_bytes, const int64_t* prefetch_ids, const int32_t* prefetch_slots,
+                          int64_t n_prefetch, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * (2b) Cache maintenance overlapped with training (Section 3.2: the lookahead lets rows be fetched before the
+ * batch that needs them; Section 3.4: the trainer's cache is maintained beside the training step, on slots the
+ * running batch does not touch).  A bp_pipeline owns a maintenance stream and enqueues, for a plan of T batches,
+ *     after batch i:  A_i  stage the rows evicted after batch i; fetch the late prefetches of batch i+1
+ *                     B_i  write the staged rows back; fetch the early prefetches of batch i+2
+ * where the EARLY prefetches of batch j are the leading entries of its prefetch list whose slot was already free
+ * before batch j-1 (their count follows from the FIFO ring: capacity + evictions of batches <= j-2 - misses of
+ * batches < j, clamped to [0, misses of j]; zero when L_eff < 2 and for batch 0).  B_i runs while batch i+1
+ * trains.  The result (cache, backing table) is the one of the synchronous order of (2).
+ *
+ * Use:  create; begin(compute_stream); for every batch i in order: acquire(i, cs), the caller's forward and
+ * backward/update of batch i on cs, release(i, cs); end(cs); destroy.
+ *   create   copies the host offsets; the device lists (slices of a bp_plan), the cache, the backing table and the
+ *            staging area (device, bp_cache_apply_duplex_workspace_bytes(cfg, largest evict list) bytes, 256-byte
+ *            aligned) must stay valid until destroy.  Creates one stream (default priority) and five events.
+ *   begin    orders the maintenance stream behind everything enqueued on compute_stream so far, then enqueues the
+ *            fetches for batch 0 and the early ones for batch 1.
+ *   acquire  makes compute_stream wait until batch i's rows are in the cache.
+ *   release  makes the maintenance stream wait for what compute_stream has enqueued so far (batch i's update),
+ *            then enqueues A_i and B_i.
+ *   end      makes compute_stream wait for all maintenance work (the last write-backs).
+ *   destroy  waits for the maintenance stream and frees the object; NULL is allowed.
+ * All calls are host-side and asynchronous except destroy.  One pipeline serves one pass over its plan; begin may
+ * be called again after end.  bp_pipeline_early_counts is the host-only computation of the early counts
+ * (early[n_iters], no GPU call); bp_pipeline_early reads one of them back.
+ * ------------------------------------------------------------------------------------------------ */
+typedef struct bp_pipeline bp_pipeline;
+int bp_pipeline_early_counts(const int64_t* prefetch_offsets, const int64_t* evict_offsets, int32_t n_iters,
+                             int64_t capacity, int32_t L_eff, int64_t* early);
+int bp_pipeline_create(const bp_config* cfg, void* cache_w, void* cache_state, void* backing_w, void* backing_state,
+                       const int64_t* prefetch_ids, const int32_t* prefetch_slots, const int64_t* prefetch_offsets,
+                       const int64_t* evict_ids, const int32_t* evict_slots, const int64_t* evict_offsets,
+                       int32_t n_iters, int32_t L_eff, void* staging, size_t staging_bytes, bp_pipeline** out);
+int bp_pipeline_destroy(bp_pipeline* p);
+int bp_pipeline_early(const bp_pipeline* p, int32_t batch, int64_t* early);
+int bp_pipeline_begin(bp_pipeline* p, void* compute_stream);
+int bp_pipeline_acquire(bp_pipeline* p, int32_t batch, void* compute_stream);
+int bp_pipeline_release(bp_pipeline* p, int32_t batch, void* compute_stream);
+int bp_pipeline_end(bp_pipeline* p, void* compute_stream);
 
 /* ------------------------------------------------------------------------------------------------
  * (3) Forward: out[b, :] = sum over lookups k in [bag_offsets[b], bag_offsets[b+1]) of cache_w[slot[k], :],

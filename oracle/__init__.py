@@ -124,15 +124,17 @@ def choose_lookahead(uniq, uoff, total_rows, L, C, exhaustive=False):
     return int(r)
 
 
-def plan(ids, iter_off, total_rows, L, C, exhaustive=False, L_eff=None) -> Plan:
-    """Whole-trace lookahead plan (part A).  L_eff=None applies the capacity policy."""
+def plan(ids, iter_off, total_rows, L, C, exhaustive=False, L_eff=None, reserve=0) -> Plan:
+    """Whole-trace lookahead plan (part A).  L_eff=None applies the capacity policy: the largest lookahead whose
+    peak occupancy fits C - reserve slots (reserve > 0 keeps that many slots free, so that a batch's prefetches can
+    land while the previous batch trains, Section 3.2); slots always come from the ring over all C slots."""
     lib = _load()
     ids, iter_off = _c(ids, np.int64), _c(iter_off, np.int64)
     T = iter_off.shape[0] - 1
     N = ids.shape[0]
     uniq, uoff = unique_per_iter(ids, iter_off, total_rows)
     if L_eff is None:
-        L_eff = choose_lookahead(uniq, uoff, total_rows, L, C, exhaustive)
+        L_eff = choose_lookahead(uniq, uoff, total_rows, L, C - reserve, exhaustive)
     M = max(1, uniq.shape[0])
     occ = np.zeros(T, dtype=np.int64)
     slots = np.empty(max(1, N), dtype=np.int32)

@@ -27,7 +27,7 @@ class BagpipeError(RuntimeError):
 class bp_config(ctypes.Structure):
     _fields_ = [("total_rows", ctypes.c_int64), ("capacity", ctypes.c_int64), ("dim", ctypes.c_int32),
                 ("weight_dtype", ctypes.c_int32), ("optimizer", ctypes.c_int32), ("lookahead", ctypes.c_int32),
-                ("lr", ctypes.c_float), ("eps", ctypes.c_float)]
+                ("lr", ctypes.c_float), ("eps", ctypes.c_float), ("reserve", ctypes.c_int64)]
 
 
 class _bp_plan(ctypes.Structure):
@@ -68,6 +68,17 @@ def load_library():
     lib.bp_cache_apply.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, i64, vp, vp, i64, vp]
     lib.bp_cache_apply_duplex_workspace_bytes.argtypes = [cfgp, i64, ctypes.POINTER(sz)]
     lib.bp_cache_apply_duplex.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, i64, vp, vp, i64, vp, sz, vp]
+    lib.bp_cache_stage.argtypes = [cfgp, vp, vp, vp, i64, vp, sz, vp]
+    lib.bp_cache_apply_staged.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, i64, vp, sz, vp, vp, i64, vp]
+    lib.bp_pipeline_early_counts.argtypes = [vp, vp, i32, i64, i32, vp]
+    lib.bp_pipeline_create.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, sz,
+                                       ctypes.POINTER(vp)]
+    lib.bp_pipeline_destroy.argtypes = [vp]
+    lib.bp_pipeline_early.argtypes = [vp, i32, ctypes.POINTER(i64)]
+    lib.bp_pipeline_begin.argtypes = [vp, vp]
+    lib.bp_pipeline_acquire.argtypes = [vp, i32, vp]
+    lib.bp_pipeline_release.argtypes = [vp, i32, vp]
+    lib.bp_pipeline_end.argtypes = [vp, vp]
     lib.bp_embbag_fwd.argtypes = [cfgp, vp, vp, vp, i64, i64, vp, vp]
     lib.bp_embbag_bwd_update_workspace_bytes.argtypes = [cfgp, i64, i64, ctypes.POINTER(sz)]
     lib.bp_embbag_bwd_update.argtypes = [cfgp, vp, vp, vp, vp, i64, i64, vp, vp, sz, vp]
@@ -86,7 +97,10 @@ def load_library():
     for name in ("bp_oracle_plan_workspace_bytes", "bp_oracle_plan", "bp_cache_apply", "bp_embbag_fwd",
                  "bp_embbag_bwd_update_workspace_bytes", "bp_embbag_bwd_update", "bp_version",
                  "bp_embbag_bwd_update_grouped_workspace_bytes", "bp_embbag_bwd_update_grouped",
-                 "bp_cache_apply_duplex_workspace_bytes", "bp_cache_apply_duplex", "bp_profile_enable",
+                 "bp_cache_apply_duplex_workspace_bytes", "bp_cache_apply_duplex", "bp_cache_stage",
+                 "bp_cache_apply_staged", "bp_profile_enable", "bp_pipeline_early_counts", "bp_pipeline_create",
+                 "bp_pipeline_destroy", "bp_pipeline_early", "bp_pipeline_begin", "bp_pipeline_acquire",
+                 "bp_pipeline_release", "bp_pipeline_end",
                  "bp_profile_collect", "bp_profile_num_kernels", "bp_profile_get"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -101,10 +115,10 @@ def _check(status: int, **info):
 
 
 def make_config(total_rows: int, capacity: int, dim: int, weight_dtype="f32", optimizer="sgd", lookahead: int = 1,
-                lr: float = 0.01, eps: float = 1e-8) -> bp_config:
+                lr: float = 0.01, eps: float = 1e-8, reserve: int = 0) -> bp_config:
     wd = _DTYPES[weight_dtype] if isinstance(weight_dtype, str) else int(weight_dtype)
     op = _OPTIMIZERS[optimizer] if isinstance(optimizer, str) else int(optimizer)
-    return bp_config(int(total_rows), int(capacity), int(dim), wd, op, int(lookahead), float(lr), float(eps))
+    return bp_config(int(total_rows), int(capacity), int(dim), wd, op, int(lookahead), float(lr), float(eps), int(reserve))
 
 
 def _ptr(t) -> Optional[int]:
@@ -257,6 +271,79 @@ def bp_cache_apply_duplex(cfg: bp_config, cache_w, cache_state, backing_w, backi
         _ptr(evict_ids) if n_e else None, _ptr(evict_slots) if n_e else None, n_e,
         _ptr(prefetch_ids) if n_p else None, _ptr(prefetch_slots) if n_p else None, n_p,
         _ptr(workspace), 0 if workspace is None else int(workspace.numel()), _stream(stream)))
+
+
+def bp_cache_stage(cfg: bp_config, cache_w, cache_state, evict_slots, staging, stream=None) -> None:
+    """First half of bp_cache_apply_duplex: evicted rows -> staging area (their slots may then be refilled)."""
+    n_e = 0 if evict_slots is None else int(evict_slots.numel())
+    _check(load_library().bp_cache_stage(ctypes.byref(cfg), _ptr(cache_w), _ptr(cache_state),
+                                         _ptr(evict_slots) if n_e else None, n_e, _ptr(staging),
+                                         0 if staging is None else int(staging.numel()), _stream(stream)))
+
+
+def bp_cache_apply_staged(cfg: bp_config, cache_w, cache_state, backing_w, backing_state, evict_ids, evict_slots,
+                          staging, prefetch_ids, prefetch_slots, stream=None) -> None:
+    """Second half: staged rows -> backing table and prefetched rows -> cache in one launch (id-disjoint lists)."""
+    n_e = 0 if evict_ids is None else int(evict_ids.numel())
+    n_p = 0 if prefetch_ids is None else int(prefetch_ids.numel())
+    _check(load_library().bp_cache_apply_staged(
+        ctypes.byref(cfg), _ptr(cache_w), _ptr(cache_state), _ptr(backing_w), _ptr(backing_state),
+        _ptr(evict_ids) if n_e else None, _ptr(evict_slots) if n_e else None, n_e, _ptr(staging),
+        0 if staging is None else int(staging.numel()), _ptr(prefetch_ids) if n_p else None,
+        _ptr(prefetch_slots) if n_p else None, n_p, _stream(stream)))
+
+
+# ---------------------------------------------------------------------------------------------------
+# (2b) maintenance overlapped with training
+# ---------------------------------------------------------------------------------------------------
+def bp_pipeline_early_counts(prefetch_offsets, evict_offsets, capacity: int, L_eff: int) -> np.ndarray:
+    """Per batch, how many leading prefetch entries may be fetched while the previous batch trains (host only)."""
+    po = np.ascontiguousarray(prefetch_offsets, dtype=np.int64)
+    eo = np.ascontiguousarray(evict_offsets, dtype=np.int64)
+    T = po.shape[0] - 1
+    early = np.zeros(T, dtype=np.int64)
+    _check(load_library().bp_pipeline_early_counts(po.ctypes.data, eo.ctypes.data, T, int(capacity), int(L_eff),
+                                                   early.ctypes.data))
+    return early
+
+
+def bp_pipeline_create(cfg: bp_config, cache_w, cache_state, backing_w, backing_state, plan: "Plan", staging) -> int:
+    """Returns the handle of a bp_pipeline over the plan's lists (which, like the tensors, must outlive it)."""
+    out = ctypes.c_void_p(0)
+    po = np.ascontiguousarray(plan.prefetch_offsets, dtype=np.int64)
+    eo = np.ascontiguousarray(plan.evict_offsets, dtype=np.int64)
+    _check(load_library().bp_pipeline_create(
+        ctypes.byref(cfg), _ptr(cache_w), _ptr(cache_state), _ptr(backing_w), _ptr(backing_state),
+        _ptr(plan.prefetch_ids), _ptr(plan.prefetch_slots), po.ctypes.data, _ptr(plan.evict_ids),
+        _ptr(plan.evict_slots), eo.ctypes.data, po.shape[0] - 1, int(plan.L_eff), _ptr(staging),
+        0 if staging is None else int(staging.numel()), ctypes.byref(out)))
+    return int(out.value)
+
+
+def bp_pipeline_destroy(handle: int) -> None:
+    _check(load_library().bp_pipeline_destroy(handle))
+
+
+def bp_pipeline_early(handle: int, batch: int) -> int:
+    out = ctypes.c_int64(0)
+    _check(load_library().bp_pipeline_early(handle, int(batch), ctypes.byref(out)))
+    return int(out.value)
+
+
+def bp_pipeline_begin(handle: int, stream=None) -> None:
+    _check(load_library().bp_pipeline_begin(handle, _stream(stream)))
+
+
+def bp_pipeline_acquire(handle: int, batch: int, stream=None) -> None:
+    _check(load_library().bp_pipeline_acquire(handle, int(batch), _stream(stream)))
+
+
+def bp_pipeline_release(handle: int, batch: int, stream=None) -> None:
+    _check(load_library().bp_pipeline_release(handle, int(batch), _stream(stream)))
+
+
+def bp_pipeline_end(handle: int, stream=None) -> None:
+    _check(load_library().bp_pipeline_end(handle, _stream(stream)))
 
 
 # ---------------------------------------------------------------------------------------------------

@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libbagpipe_hip.so")
-SOURCES = ["abi.hip", "planner.hip", "cache_apply.hip", "embbag_fwd.hip", "embbag_bwd.hip"]
+SOURCES = ["abi.hip", "planner.hip", "cache_apply.hip", "pipeline.hip", "embbag_fwd.hip", "embbag_bwd.hip"]
 
 # -ffp-contract=off: every fp32 operation rounds once (no fused multiply-add), which keeps the update
 #   arithmetic reproducible and close to the fp64 reference.

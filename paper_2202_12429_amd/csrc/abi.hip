@@ -32,6 +32,8 @@ int check_config(const bp_config* cfg) {
         return fail(BP_ERR_INVALID_ARG, "unknown weight_dtype %d", cfg->weight_dtype);
     if (cfg->optimizer != BP_SGD && cfg->optimizer != BP_ADAGRAD && cfg->optimizer != BP_ADAGRAD_ROWWISE)
         return fail(BP_ERR_INVALID_ARG, "unknown optimizer %d", cfg->optimizer);
+    if (cfg->reserve < 0 || cfg->reserve >= cfg->capacity)
+        return fail(BP_ERR_INVALID_ARG, "reserve %lld outside [0, capacity)", (long long)cfg->reserve);
     if (cfg->lookahead < 1) return fail(BP_ERR_INVALID_ARG, "lookahead %d < 1", cfg->lookahead);
     if (cfg->dim < 1) return fail(BP_ERR_INVALID_ARG, "dim %d < 1", cfg->dim);
     const size_t rb = row_bytes(cfg);

@@ -108,19 +108,21 @@ struct DuplexLaunch {
     const int32_t* p_slots;
     int64_t n_p;
     hipStream_t stream;
+    bool stage, apply;     // which of the two steps to launch
     template <int GW, bool BF16>
     int run() {
         const int lpr = (int)(row_bytes(cfg) / 16);
         const int slpr = cfg->optimizer == BP_ADAGRAD ? cfg->dim / 4 : 0;
         const int rowwise = cfg->optimizer == BP_ADAGRAD_ROWWISE;
-        if (n_e)
+        if (stage && n_e)
             BP_LAUNCH(K_CACHE_STAGE, (cache_stage_rows_kernel<GW>), dim3((unsigned)ceil_div(n_e * GW, kRowBlock)),
                       dim3(kRowBlock), 0, stream, (const uint4*)cache_w, (const uint4*)cache_s, (uint4*)stage_w,
                       (uint4*)stage_s, e_slots, n_e, cfg->capacity, lpr, slpr, rowwise);
-        BP_LAUNCH(K_CACHE_DUPLEX, (cache_duplex_kernel<GW>), dim3((unsigned)ceil_div((n_e + n_p) * GW, kRowBlock)),
-                  dim3(kRowBlock), 0, stream, (uint4*)cache_w, (uint4*)cache_s, (uint4*)back_w, (uint4*)back_s,
-                  (const uint4*)stage_w, (const uint4*)stage_s, e_ids, e_slots, n_e, p_ids, p_slots, n_p, cfg->total_rows,
-                  cfg->capacity, lpr, slpr, rowwise);
+        if (apply && n_e + n_p)
+            BP_LAUNCH(K_CACHE_DUPLEX, (cache_duplex_kernel<GW>), dim3((unsigned)ceil_div((n_e + n_p) * GW, kRowBlock)),
+                      dim3(kRowBlock), 0, stream, (uint4*)cache_w, (uint4*)cache_s, (uint4*)back_w, (uint4*)back_s,
+                      (const uint4*)stage_w, (const uint4*)stage_s, e_ids, e_slots, n_e, p_ids, p_slots, n_p,
+                      cfg->total_rows, cfg->capacity, lpr, slpr, rowwise);
         return BP_OK;
     }
 };
@@ -220,6 +222,56 @@ BP_EXPORT int bp_cache_apply_duplex(const bp_config* cfg, void* cache_w, void* c
         return fail(BP_ERR_WORKSPACE_TOO_SMALL, "workspace %zu < required %zu bytes", workspace_bytes, need);
     DuplexLaunch l{cfg, cache_w, cache_state, backing_w, backing_state, workspace,
                    workspace ? (char*)workspace + stage_w_bytes(cfg, n_evict) : nullptr, evict_ids, evict_slots, n_evict,
-                   prefetch_ids, prefetch_slots, n_prefetch, (hipStream_t)stream};
+                   prefetch_ids, prefetch_slots, n_prefetch, (hipStream_t)stream, true, true};
+    return dispatch_row((int)(row_bytes(cfg) / 16), false, l);
+}
+
+namespace bp {
+namespace {
+int check_staging(const bp_config* cfg, int64_t n_evict, const void* staging, size_t staging_bytes) {
+    if (n_evict == 0) return BP_OK;
+    const size_t need = stage_w_bytes(cfg, n_evict) + stage_s_bytes(cfg, n_evict);
+    if (!staging || ((uintptr_t)staging & 255)) return fail(BP_ERR_INVALID_ARG, "staging NULL or not 256-byte aligned");
+    if (staging_bytes < need)
+        return fail(BP_ERR_WORKSPACE_TOO_SMALL, "staging %zu < required %zu bytes", staging_bytes, need);
+    return BP_OK;
+}
+}  // namespace
+}  // namespace bp
+
+BP_EXPORT int bp_cache_stage(const bp_config* cfg, const void* cache_w, const void* cache_state, const int32_t* evict_slots,
+                             int64_t n_evict, void* staging, size_t staging_bytes, void* stream) {
+    BP_TRY(check_config(cfg));
+    if (n_evict < 0) return fail(BP_ERR_INVALID_ARG, "negative list length");
+    if (n_evict == 0) return BP_OK;
+    if (!cache_w || !evict_slots) return fail(BP_ERR_INVALID_ARG, "cache_w or evict_slots is NULL");
+    if (cfg->optimizer != BP_SGD && !cache_state) return fail(BP_ERR_INVALID_ARG, "cache_state is NULL");
+    if (((uintptr_t)cache_w | (uintptr_t)cache_state) & 15) return fail(BP_ERR_INVALID_ARG, "row pointers must be 16-byte aligned");
+    BP_TRY(check_staging(cfg, n_evict, staging, staging_bytes));
+    DuplexLaunch l{cfg, const_cast<void*>(cache_w), const_cast<void*>(cache_state), nullptr, nullptr, staging,
+                   (char*)staging + stage_w_bytes(cfg, n_evict), nullptr, evict_slots, n_evict, nullptr, nullptr, 0,
+                   (hipStream_t)stream, true, false};
+    return dispatch_row((int)(row_bytes(cfg) / 16), false, l);
+}
+
+BP_EXPORT int bp_cache_apply_staged(const bp_config* cfg, void* cache_w, void* cache_state, void* backing_w,
+                                    void* backing_state, const int64_t* evict_ids, const int32_t* evict_slots,
+                                    int64_t n_evict, const void* staging, size_t staging_bytes, const int64_t* prefetch_ids,
+                                    const int32_t* prefetch_slots, int64_t n_prefetch, void* stream) {
+    BP_TRY(check_config(cfg));
+    if (n_evict < 0 || n_prefetch < 0) return fail(BP_ERR_INVALID_ARG, "negative list length");
+    if (n_evict + n_prefetch == 0) return BP_OK;
+    if (!backing_w || (n_prefetch && !cache_w)) return fail(BP_ERR_INVALID_ARG, "cache_w or backing_w is NULL");
+    if (cfg->optimizer != BP_SGD && (!backing_state || (n_prefetch && !cache_state)))
+        return fail(BP_ERR_INVALID_ARG, "optimizer state pointers are NULL");
+    if (((uintptr_t)cache_w | (uintptr_t)backing_w | (uintptr_t)cache_state | (uintptr_t)backing_state) & 15)
+        return fail(BP_ERR_INVALID_ARG, "row pointers must be 16-byte aligned");
+    if ((n_evict && (!evict_ids || !evict_slots)) || (n_prefetch && (!prefetch_ids || !prefetch_slots)))
+        return fail(BP_ERR_INVALID_ARG, "a list pointer is NULL");
+    BP_TRY(check_staging(cfg, n_evict, staging, staging_bytes));
+    void* st = const_cast<void*>(staging);
+    DuplexLaunch l{cfg, cache_w, cache_state, backing_w, backing_state, st,
+                   st ? (char*)st + stage_w_bytes(cfg, n_evict) : nullptr, evict_ids, evict_slots, n_evict, prefetch_ids,
+                   prefetch_slots, n_prefetch, (hipStream_t)stream, false, true};
     return dispatch_row((int)(row_bytes(cfg) / 16), false, l);
 }

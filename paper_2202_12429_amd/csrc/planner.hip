@@ -664,7 +664,7 @@ BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int
     BP_LAUNCH(K_PLAN_OCC, plan_occ_peak_kernel, dim3(T), dim3(kBlock), 0, stream, (const uint32_t*)w.H,
               (const uint32_t*)w.ucount, T, Lcap, w.peak);
     BP_LAUNCH(K_PLAN_OCC, plan_choose_kernel, dim3(1), dim3(64), 0, stream, (const uint32_t*)w.peak,
-              (const uint32_t*)w.ucount, T, Lcap, cfg->lookahead, C, w.scalars, w.pair_off);
+              (const uint32_t*)w.ucount, T, Lcap, cfg->lookahead, C - cfg->reserve, w.scalars, w.pair_off);
     BP_LAUNCH(K_PLAN_OCC, plan_occ_final_kernel, grid_for(T), dim3(kBlock), 0, stream, (const uint32_t*)w.H,
               (const uint32_t*)w.ucount, T, (const PlanScalars*)w.scalars, w.occ);
     BP_HIP(hipMemcpyAsync(&hs, w.scalars, sizeof(PlanScalars), hipMemcpyDeviceToHost, stream));
@@ -672,7 +672,8 @@ BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int
     BP_HIP(hipStreamSynchronize(stream));
     plan->min_capacity = hs.min_capacity;
     if (hs.L_eff < 1)
-        return fail(BP_ERR_CAPACITY, "capacity %lld < %lld unique rows of one batch", (long long)C, (long long)hs.min_capacity);
+        return fail(BP_ERR_CAPACITY, "capacity %lld - reserve %lld < %lld unique rows of one batch", (long long)C,
+                    (long long)cfg->reserve, (long long)hs.min_capacity);
     plan->L_eff = hs.L_eff;
     plan->peak_occupancy = hs.peak;
 

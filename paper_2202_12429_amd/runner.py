@@ -8,7 +8,14 @@
         trainer.backward_update(i, bag_offsets_dev, bags, grad_out)      # bp_embbag_bwd_update[_grouped]
     trainer.flush()                                                      # bp_cache_apply(E_{T-1}, {})
 
-The order of calls is the synchronous schedule of Section 3.2: the write-backs of batch i-1 are applied before
+Overlapped schedule (cache maintenance on a stream of its own, beside the training step):
+    trainer.begin()                                                      # bp_pipeline_create + begin
+    for i in range(T):
+        trainer.acquire(i); forward(i); backward_update(i); trainer.release(i)
+    trainer.end()                                                        # last write-backs ordered before the caller
+It needs free slots to fetch into while a batch trains: plan with cfg.reserve >= the misses of one batch.
+
+The order of calls in the first loop is the synchronous schedule of Section 3.2: the write-backs of batch i-1 are applied before
 the prefetches of batch i, so a row is never fetched while an update to it is still only in the cache.
 With duplex=True (default) and a plan whose L_eff >= 2, maintain() uses bp_cache_apply_duplex (writes to and reads
 from the backing table in one launch).  With grouping=True (default) the plan also lists every batch's lookups grouped by row and the backward pass
@@ -51,6 +58,7 @@ class CachedEmbeddingTrainer:
         self.iter_offsets: Optional[np.ndarray] = None
         self._bwd_ws = None
         self._out = None
+        self._pipeline = None
         if max_lookups:
             self._reserve(max_lookups, max_bags or max_lookups)
 
@@ -68,7 +76,8 @@ class CachedEmbeddingTrainer:
         self.iter_offsets = np.ascontiguousarray(iter_offsets, dtype=np.int64)
         self.plan_ = B.bp_oracle_plan(self.cfg, ids_dev, self.iter_offsets, list_capacity=list_capacity,
                                       workspace=workspace, grouping=self.grouping)
-        if self.duplex and self.plan_.L_eff >= 2:
+        self.close()
+        if self.plan_.L_eff >= 2:
             import torch
             most = int(np.diff(self.plan_.evict_offsets).max()) if len(self.plan_.evict_offsets) > 1 else 0
             need = B.bp_cache_apply_duplex_workspace_bytes(self.cfg, most)
@@ -96,6 +105,33 @@ class CachedEmbeddingTrainer:
         else:
             B.bp_cache_apply(self.cfg, self.cache_w, self.cache_state, self.backing_w, self.backing_state, e_ids,
                              e_slots, p_ids, p_slots, stream=stream)
+
+    # ---- (2b) the same maintenance, overlapped with training
+    def begin(self, stream=None) -> None:
+        if self._pipeline is None:
+            self._pipeline = B.bp_pipeline_create(self.cfg, self.cache_w, self.cache_state, self.backing_w,
+                                                  self.backing_state, self.plan_, self._stage)
+        B.bp_pipeline_begin(self._pipeline, stream)
+
+    def acquire(self, i: int, stream=None) -> None:
+        B.bp_pipeline_acquire(self._pipeline, i, stream)
+
+    def release(self, i: int, stream=None) -> None:
+        B.bp_pipeline_release(self._pipeline, i, stream)
+
+    def end(self, stream=None) -> None:
+        B.bp_pipeline_end(self._pipeline, stream)
+
+    def close(self) -> None:
+        if self._pipeline is not None:
+            B.bp_pipeline_destroy(self._pipeline)
+            self._pipeline = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
     def flush(self, stream=None) -> None:
         T = self.iter_offsets.shape[0] - 1

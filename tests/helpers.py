@@ -122,10 +122,10 @@ def oracle_cached(cfg, trace, plan, T=None):
 # ---------------------------------------------------------------------------------------------------
 # GPU side (imports the product package lazily so that CPU-only test runs never need it)
 # ---------------------------------------------------------------------------------------------------
-def bp_config_of(cfg, capacity=None):
+def bp_config_of(cfg, capacity=None, reserve=0):
     import paper_2202_12429_amd as bp
     return bp.make_config(cfg.total_rows, cfg.capacity if capacity is None else capacity, cfg.dim, cfg.weight_dtype,
-                          cfg.optimizer, cfg.lookahead, cfg.lr, cfg.eps)
+                          cfg.optimizer, cfg.lookahead, cfg.lr, cfg.eps, reserve=reserve)
 
 
 def make_backing(cfg, pinned=True, chunk_rows=1 << 20):
@@ -147,26 +147,39 @@ def make_backing(cfg, pinned=True, chunk_rows=1 << 20):
 
 
 def gpu_cached_training(cfg, trace, T=None, pinned=True, capacity=None, check_outputs=None, grouping=True,
-                        duplex=None):
+                        duplex=None, overlapped=False, reserve=0):
     """Runs plan + T iterations of cache_apply / fwd / bwd_update + flush through the C ABI.
-    check_outputs(i, out_tensor) is called after every forward.  Returns (trainer, plan, W, S)."""
+    check_outputs(i, out_tensor) is called after every forward.  Returns (trainer, plan, W, S).
+    overlapped=True: cache maintenance runs on the library's maintenance stream (bp_pipeline_*)."""
     from paper_2202_12429_amd.runner import CachedEmbeddingTrainer
     T = trace.iter_offsets.shape[0] - 1 if T is None else T
-    bcfg = bp_config_of(cfg, capacity)
+    bcfg = bp_config_of(cfg, capacity, reserve)
     W, S = make_backing(cfg, pinned)
     tr = CachedEmbeddingTrainer(bcfg, W, S, grouping=grouping, duplex=grouping if duplex is None else duplex)
     ids_dev = torch.from_numpy(trace.ids[:trace.iter_offsets[T]]).cuda()
     plan = tr.plan(ids_dev, trace.iter_offsets[:T + 1])
     bags = trace.bag_offsets.shape[1] - 1
+    if overlapped:
+        tr.begin()
     for i in range(T):
         bo = None if cfg.one_hot else torch.from_numpy(np.ascontiguousarray(trace.bag_offsets[i])).cuda()
-        tr.maintain(i)
-        out = tr.forward(i, bo, bags)
-        if check_outputs is not None:
-            check_outputs(i, out)
         g = workloads.upstream_grad(cfg, i, bags, device="cuda:0")
+        if overlapped:
+            tr.acquire(i)
+        else:
+            tr.maintain(i)
+        out = tr.forward(i, bo, bags)
+        if check_outputs is not None and not overlapped:
+            check_outputs(i, out)
         tr.backward_update(i, bo, bags, g)
-    tr.flush()
+        if overlapped:
+            tr.release(i)
+            if check_outputs is not None:       # after release: the host waits here while maintenance runs on
+                check_outputs(i, out)
+    if overlapped:
+        tr.end()
+    else:
+        tr.flush()
     torch.cuda.synchronize()
     return tr, plan, W, S
 

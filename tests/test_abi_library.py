@@ -44,8 +44,8 @@ def test_binding_has_the_same_names():
 
 def test_config_struct_layout_matches_header():
     import paper_2202_12429_amd as bp
-    assert ctypes.sizeof(bp.bp_config) == 40
-    assert bp.bp_config.lookahead.offset == 28 and bp.bp_config.lr.offset == 32
+    assert ctypes.sizeof(bp.bp_config) == 48
+    assert bp.bp_config.lookahead.offset == 28 and bp.bp_config.lr.offset == 32 and bp.bp_config.reserve.offset == 40
 
 
 def test_argument_errors_without_gpu(lib):
@@ -58,7 +58,9 @@ def test_argument_errors_without_gpu(lib):
     for bad in (bp.make_config(1000, 64, 6),              # 24-byte rows: not a multiple of 16 bytes
                 bp.make_config(1000, 0, 16),               # no capacity
                 bp.make_config(0, 64, 16),                 # no rows
-                bp.make_config(1000, 64, 16, lookahead=0)):
+                bp.make_config(1000, 64, 16, lookahead=0),
+                bp.make_config(1000, 64, 16, reserve=64),  # nothing left to plan with
+                bp.make_config(1000, 64, 16, reserve=-1)):
         with pytest.raises(bp.BagpipeError) as e:
             bp.bp_embbag_bwd_update_workspace_bytes(bad, 128, 128)
         assert e.value.status == -1

@@ -386,7 +386,7 @@ def test_plan_errors(bp):
 # ---------------------------------------------------------------------------------------------------
 # whole path
 # ---------------------------------------------------------------------------------------------------
-def run_end_to_end(cfg, trace, pinned=True, capacity=None, grouping=True):
+def run_end_to_end(cfg, trace, pinned=True, capacity=None, grouping=True, overlapped=False, reserve=0):
     T = trace.iter_offsets.shape[0] - 1
     Wo, So, outs = helpers.oracle_uncached(cfg, trace)
     max_bag = cfg.bag_max
@@ -395,9 +395,9 @@ def run_end_to_end(cfg, trace, pinned=True, capacity=None, grouping=True):
         helpers.assert_outputs_close(out.cpu().numpy(), outs[i], max_bag, same_table=(i == 0))
 
     tr, plan, W, S = helpers.gpu_cached_training(cfg, trace, pinned=pinned, capacity=capacity, check_outputs=check,
-                                                 grouping=grouping)
+                                                 grouping=grouping, overlapped=overlapped, reserve=reserve)
     C = cfg.capacity if capacity is None else capacity
-    want_plan = oracle.plan(trace.ids, trace.iter_offsets, cfg.total_rows, cfg.lookahead, C)
+    want_plan = oracle.plan(trace.ids, trace.iter_offsets, cfg.total_rows, cfg.lookahead, C, reserve=reserve)
     assert_plan_equal(plan, want_plan, trace.n_lookups)
     got = helpers.table_from_torch(cfg, W)
     if cfg.weight_dtype == "bf16":
@@ -409,6 +409,7 @@ def run_end_to_end(cfg, trace, pinned=True, capacity=None, grouping=True):
         np.testing.assert_allclose(S.cpu().numpy(), So, rtol=1e-4, atol=1e-9)
     # the cache drains: every resident row was written back
     assert plan.prefetch_offsets[-1] == plan.evict_offsets[-1]
+    tr.close()
     return plan
 
 
@@ -431,3 +432,48 @@ def test_end_to_end_variants(bp, optimizer, dtype, bag_max, capacity, pinned, gr
     cfg = workloads.get_config(0, optimizer=optimizer, weight_dtype=dtype, bag_max=bag_max, capacity=capacity,
                                batch=128 if bag_max > 1 else 256, iterations=30)
     run_end_to_end(cfg, workloads.make_trace(cfg), pinned=pinned, grouping=grouping)
+
+
+# ---------------------------------------------------------------------------------------------------
+# cache maintenance overlapped with training (bp_pipeline_*)
+# ---------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("optimizer,dtype,bag_max,capacity,reserve,lookahead,pinned", [
+    ("adagrad", "f32", 1, 4096, 1200, 20, True),          # roomy: every prefetch is early
+    ("adagrad", "f32", 1, 1400, 0, 20, True),             # capacity binds, no reserve: most prefetches are late
+    ("adagrad_rowwise", "bf16", 1, 2400, 700, 20, True),
+    ("sgd", "f32", 6, 3000, 600, 20, False),
+    ("adagrad", "bf16", 4, 2600, 0, 2, True),             # L_eff == 2: write-back and early fetch take turns
+    ("sgd", "f32", 1, 1400, 0, 1, True)])                 # L_eff == 1: the synchronous order on the other stream
+def test_end_to_end_overlapped(bp, optimizer, dtype, bag_max, capacity, reserve, lookahead, pinned):
+    """Same trace, same oracle, maintenance on the library's own stream: outputs and final table as before."""
+    say(f"overlapped: {optimizer} {dtype} bag_max={bag_max} C={capacity} reserve={reserve} L={lookahead}")
+    cfg = workloads.get_config(0, optimizer=optimizer, weight_dtype=dtype, bag_max=bag_max, capacity=capacity,
+                               batch=128 if bag_max > 1 else 256, iterations=30, lookahead=lookahead)
+    plan = run_end_to_end(cfg, workloads.make_trace(cfg), pinned=pinned, overlapped=True, reserve=reserve)
+    early = bp.bp_pipeline_early_counts(plan.prefetch_offsets, plan.evict_offsets, capacity, plan.L_eff)
+    misses = np.diff(plan.prefetch_offsets)
+    say(f"  L_eff={plan.L_eff} early {int(early[1:].sum())} of {int(misses[1:].sum())} prefetches after batch 0")
+    if plan.L_eff == 1:
+        assert early.sum() == 0
+    if reserve >= misses.max():
+        assert np.array_equal(early[1:], misses[1:])
+
+
+def test_plan_with_reserve(bp):
+    """The capacity policy with reserved slots: L_eff as for a cache of capacity - reserve, slots from all of it."""
+    say("plan with reserve")
+    cfg = workloads.get_config(0, iterations=40)
+    tr = workloads.make_trace(cfg)
+    for C, reserve in ((4096, 0), (4096, 1500), (2500, 800), (2500, 2499 - 1400)):
+        bc = bp.make_config(cfg.total_rows, C, 16, lookahead=cfg.lookahead, reserve=reserve)
+        try:
+            want = oracle.plan(tr.ids, tr.iter_offsets, cfg.total_rows, cfg.lookahead, C, reserve=reserve)
+        except oracle.OracleError:
+            with pytest.raises(bp.BagpipeError) as e:
+                bp.bp_oracle_plan(bc, dev(tr.ids), tr.iter_offsets)
+            assert e.value.status == -2
+            continue
+        got = bp.bp_oracle_plan(bc, dev(tr.ids), tr.iter_offsets, grouping=True)
+        assert_plan_equal(got, want, len(tr.ids))
+        assert_grouping_equal(got, want, tr.ids, tr.iter_offsets)
+        assert got.peak_occupancy <= C - reserve
