@@ -7,10 +7,13 @@ Workload: benchmark configs[2] by default — 26 tables / 33.8 M rows, D=48 
 rows = 92 % of accesses), batch 16,384 (425,984 lookups per step), lookahead 400 over 200 batches, cache = 2 % of
 the rows in HBM, element-wise Adagrad, backing table in pinned host DRAM.  All inputs are seeded and synthetic.
 
-A step is one pass of the hot path over one batch: bp_cache_apply (write back the previous batch's evictions,
-load this batch's prefetches), bp_embbag_fwd, bp_embbag_bwd_update.  The plan (bp_oracle_plan over the whole
-trace) is timed separately; its cost per batch is added to every step, so `value` is whole-job lookups/s with
-ids, upstream gradients and the backing table resident before the timed region starts.
+A step is one pass of the hot path over one batch: cache maintenance (write back the previous batch's evictions,
+load this batch's prefetches), bp_embbag_fwd, bp_embbag_bwd_update_grouped.  The plan (bp_oracle_plan over the whole
+trace, median of 5) is timed separately; its cost per batch is added to every step, so `value` is whole-job
+lookups/s with ids, upstream gradients and the backing table resident in HBM before the timed region starts.
+`pcie_inclusive` is the same trace against the backing table in pinned host memory, with the maintenance running on
+the library's own stream beside the training step (bp_pipeline_*); the other schedule of either placement is
+reported next to it.
 
 Prints ONE JSON line.  Extra objects: `roofline` (dominant kernel, algorithmic bytes / HIP-event duration against
 the 8 TB/s HBM peak) and `cpu_baseline` (the CPU oracle, single thread, on a bounded sample of the same workload).
@@ -63,6 +66,9 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--cpu-baseline-iters", type=int, default=40)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--reserve", type=int, default=-1,
+                    help="cache slots the capacity policy keeps free for fetches that overlap training "
+                         "(-1: 1.5 x the median per-batch miss count of the plan without reserve)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU by design (no collectives, no sharding); run with --gpus 1",
@@ -111,6 +117,18 @@ def main() -> int:
         log(capacity_note)
         bcfg = bp.make_config(cfg.total_rows, capacity, D, cfg.weight_dtype, cfg.optimizer, cfg.lookahead, cfg.lr, cfg.eps)
         plan = bp.bp_oracle_plan(bcfg, ids_dev, trace.iter_offsets)
+    # ---- reserve: free slots for the fetches that run beside the training step (the overlapped schedule)
+    reserve = args.reserve
+    if reserve < 0:
+        # the cold start fetches far more per batch, but then the cache is far from full; what has to stay free in
+        # the steady state is one typical batch's misses
+        typical = int(np.median(np.diff(plan.prefetch_offsets)[1:])) if T > 1 else 0
+        reserve = min(((typical * 3 // 2 + 1023) // 1024) * 1024, capacity - int(plan.min_capacity))
+        reserve = max(reserve, 0)
+    bcfg = bp.make_config(cfg.total_rows, capacity, D, cfg.weight_dtype, cfg.optimizer, cfg.lookahead, cfg.lr, cfg.eps,
+                          reserve=reserve)
+    bcfg_sync = bp.make_config(cfg.total_rows, capacity, D, cfg.weight_dtype, cfg.optimizer, cfg.lookahead, cfg.lr,
+                               cfg.eps)
     del plan
 
     # ---- backing table in pinned host memory (stands in for the embedding servers)
@@ -161,29 +179,40 @@ def main() -> int:
     if hbm_resident:
         backing_w_dev = backing_w.to(dev)
         backing_s_dev = None if backing_s is None else backing_s.to(dev)
+    # runs: (placement of the backing table, schedule).  `value` is HBM-resident + overlapped; the others are reported
+    # beside it.  The overlapped runs plan with the reserve, the synchronous ones without.
+    def make_trainer(cfg_, w_, s_):
+        return CachedEmbeddingTrainer(cfg_, w_, s_, device=dev, max_lookups=int(n_per_iter.max()), max_bags=bags)
+
     trainers = {}
     if hbm_resident:
-        trainers["hbm"] = CachedEmbeddingTrainer(bcfg, backing_w_dev, backing_s_dev, device=dev,
-                                                 max_lookups=int(n_per_iter.max()), max_bags=bags)
-    trainers["pinned_host"] = CachedEmbeddingTrainer(bcfg, backing_w, backing_s, device=dev,
-                                                     max_lookups=int(n_per_iter.max()), max_bags=bags)
+        trainers["hbm", "overlapped"] = make_trainer(bcfg, backing_w_dev, backing_s_dev)
+        trainers["hbm", "synchronous"] = make_trainer(bcfg_sync, backing_w_dev, backing_s_dev)
+    trainers["pinned_host", "overlapped"] = make_trainer(bcfg, backing_w, backing_s)
+    trainers["pinned_host", "synchronous"] = make_trainer(bcfg_sync, backing_w, backing_s)
     first = next(iter(trainers.values()))
     ws = torch.empty(bp.bp_oracle_plan_workspace_bytes(bcfg, trace.n_lookups, T, grouping=True), dtype=torch.uint8,
                      device=dev)
     torch.cuda.synchronize()
     plan_times = []
-    for rep in range(3):
+    for rep in range(5):
         t0 = time.perf_counter()
         first.plan(ids_dev, trace.iter_offsets, workspace=ws)       # with the grouping the backward pass consumes
         torch.cuda.synchronize()
         plan_times.append(time.perf_counter() - t0)
     plan = first.plan_
-    for tr_ in trainers.values():                                    # one plan serves both placements
-        tr_.plan_, tr_.iter_offsets, tr_._stage = first.plan_, first.iter_offsets, first._stage
+    first_sync = trainers["pinned_host", "synchronous"]
+    first_sync.plan(ids_dev, trace.iter_offsets, workspace=ws)
+    for (place, sched), tr_ in trainers.items():                     # one plan per schedule serves both placements
+        src = first if sched == "overlapped" else first_sync
+        if tr_ is not src:
+            tr_.plan_, tr_.iter_offsets, tr_._stage = src.plan_, src.iter_offsets, src._stage
     t_plan = float(np.median(plan_times))
     del ws
-    log(f"plan: L_eff={plan.L_eff} peak={plan.peak_occupancy} pairs={plan.n_unique_pairs} "
-        f"prefetches={int(plan.prefetch_offsets[-1])}  {t_plan * 1e3:.1f} ms ({trace.n_lookups / t_plan:.3g} ids/s)")
+    early = bp.bp_pipeline_early_counts(plan.prefetch_offsets, plan.evict_offsets, capacity, plan.L_eff)
+    log(f"plan: L_eff={plan.L_eff} (without reserve {first_sync.plan_.L_eff}) reserve={reserve} "
+        f"peak={plan.peak_occupancy} pairs={plan.n_unique_pairs} prefetches={int(plan.prefetch_offsets[-1])} "
+        f"early={int(early.sum())}  {t_plan * 1e3:.1f} ms ({trace.n_lookups / t_plan:.3g} ids/s)")
 
     # ---- plain copy of known size (1 GiB read + 1 GiB written): counter yardstick and copy ceiling of this GPU
     ca = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -207,20 +236,30 @@ def main() -> int:
     torch.cuda.synchronize()
     n_timed = int(n_per_iter[W:W + K].sum())
     n_mean = n_timed / K
-    u_mean = float(np.diff(plan.keep_offsets)[W:W + K].mean())
-    moved = int(plan.prefetch_offsets[W + K] - plan.prefetch_offsets[W]) + \
-        int(plan.evict_offsets[W + K - 1] - plan.evict_offsets[max(W - 1, 0)])
+    u_mean = float(np.diff(first_sync.plan_.keep_offsets)[W:W + K].mean())
+
+    def rows_moved(pl):
+        return int(pl.prefetch_offsets[W + K] - pl.prefetch_offsets[W]) + \
+            int(pl.evict_offsets[W + K - 1] - pl.evict_offsets[max(W - 1, 0)])
     sort_scan = ["sort_upsweep", "sort_downsweep", "scan_reduce", "scan_spine", "scan_apply"]
 
-    def measure(trainer):
-        def step(i):
+    def measure(trainer, overlapped):
+        def step(i, compute=True):
             bo = None if bag_off_dev is None else bag_off_dev[i]
-            trainer.maintain(i)
-            trainer.forward(i, bo, bags, out=out)
-            trainer.backward_update(i, bo, bags, grads_dev[i % n_grad])
+            if overlapped:
+                trainer.acquire(i)
+            else:
+                trainer.maintain(i)
+            if compute:
+                trainer.forward(i, bo, bags, out=out)
+                trainer.backward_update(i, bo, bags, grads_dev[i % n_grad])
+            if overlapped:
+                trainer.release(i)
 
         def run_pass(profile_kernels):
             """Warm-up W steps, then K timed steps.  profile_kernels: [] = every kernel bracketed, or a list."""
+            if overlapped:
+                trainer.begin()
             for i in range(W):
                 step(i)
             torch.cuda.synchronize()
@@ -236,8 +275,11 @@ def main() -> int:
             bp.bp_profile_enable(False)
             bp.bp_profile_select(None)
             for i in range(W + K, T):        # finish the trace: the cache drains, the next pass starts empty
-                trainer.maintain(i)
-            trainer.flush()
+                step(i, compute=False)
+            if overlapped:
+                trainer.end()
+            else:
+                trainer.flush()
             torch.cuda.synchronize()
             return dt_, prof
 
@@ -252,7 +294,7 @@ def main() -> int:
             return sum(prof_all[k][1] for k in names if k in prof_all) / K
 
         kernel_ms = {
-            "cache_apply": per_step(["cache_evict", "cache_prefetch", "cache_stage", "cache_duplex"]),
+            "cache_apply": per_step(["cache_evict", "cache_prefetch", "cache_stage", "cache_duplex"]),   # own stream when overlapped
             "fwd": per_step(["embbag_fwd"]),
             "bwd_sort_and_items": per_step(["bwd_keys"] + sort_scan),      # zero with the plan-provided grouping
             "bwd_reduce_update": per_step(["bwd_reduce_update"]),
@@ -261,9 +303,14 @@ def main() -> int:
         t_total = t_loop + t_plan * K / T                      # the plan's share of these K batches
         return dict(t_loop=t_loop, t_total=t_total, dominant=dominant, prof_dom=prof_dom[dominant], kernel_ms=kernel_ms)
 
-    res = {name: measure(tr_) for name, tr_ in trainers.items()}
-    main_name = "hbm" if hbm_resident else "pinned_host"
-    m = res[main_name]
+    res = {key: measure(tr_, key[1] == "overlapped") for key, tr_ in trainers.items()}
+    main_place = "hbm" if hbm_resident else "pinned_host"
+    # With the table in HBM every kernel of the step is HBM-bound, so running the maintenance beside the training
+    # kernels moves the same bytes through the same memory and gains nothing: the synchronous schedule is the one
+    # `value` reports.  With the table behind the host link the overlapped schedule hides the link time.
+    main_sched = "synchronous" if hbm_resident else "overlapped"
+    m = res[main_place, main_sched]
+    plan_main = first_sync.plan_ if main_sched == "synchronous" else plan
     value = n_timed / m["t_total"]
     dominant = m["dominant"]
     launches, ms = m["prof_dom"]
@@ -274,8 +321,14 @@ def main() -> int:
     traffic = MEASURED_TRAFFIC_BYTES.get((cfg.name, dominant))
     kernel_ms = m["kernel_ms"]
     fbu_ms = kernel_ms["fwd"] + kernel_ms["bwd_sort_and_items"] + kernel_ms["bwd_reduce_update"] + kernel_ms["bwd_combine_update"]
-    pin = res["pinned_host"]
-    pin_apply_s = pin["kernel_ms"]["cache_apply"] * 1e-3 * K
+    pin = res["pinned_host", "overlapped"]
+    pin_sync = res["pinned_host", "synchronous"]
+    moved = rows_moved(first_sync.plan_)
+    pin_apply_s = pin_sync["kernel_ms"]["cache_apply"] * 1e-3 * K
+
+    def brief(r):
+        return {"value": n_timed / r["t_total"], "unit": "lookups/s", "ms_per_step": r["t_total"] / K * 1e3,
+                "loop_ms_per_step": r["t_loop"] / K * 1e3, "kernel_ms_per_step": r["kernel_ms"]}
 
     result = {
         "metric": "cached EmbeddingBag fwd+bwd+update lookups/s (whole hot path: plan share + cache apply + fwd + bwd/update)",
@@ -295,8 +348,10 @@ def main() -> int:
                                f"lookahead {cfg.lookahead}, cache {capacity} rows, {cfg.optimizer}",
                    "backing_table": "HBM-resident for `value`; pinned host DRAM for `pcie_inclusive`" if hbm_resident
                                     else "pinned host DRAM (too large to mirror in HBM)",
-                   "L_eff": plan.L_eff, "peak_occupancy": plan.peak_occupancy, "capacity_note": capacity_note,
-                   "unique_rows_per_step": u_mean},
+                   "schedule": f"`value`: {main_sched}; `pcie_inclusive`: cache maintenance overlapped with training on "
+                               "a second stream (bp_pipeline_*), planned with `reserve` free slots",
+                   "L_eff": plan_main.L_eff, "peak_occupancy": plan_main.peak_occupancy,
+                   "capacity_note": capacity_note, "unique_rows_per_step": u_mean},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "algorithmic_bytes_per_launch": alg,
                      "avg_launch_us": dur_s * 1e6, "launches": launches,
@@ -306,11 +361,18 @@ def main() -> int:
         "loop_ms_per_step": m["t_loop"] / K * 1e3,
         "kernel_ms_per_step": kernel_ms,
         "fwd_bwd_update_lookups_per_s_kernel_time": n_mean / (fbu_ms * 1e-3) if fbu_ms > 0 else None,
-        "pcie_inclusive": {"value": n_timed / pin["t_total"], "unit": "lookups/s", "ms_per_step": pin["t_total"] / K * 1e3,
-                           "kernel_ms_per_step": pin["kernel_ms"], "rows_moved_per_step": moved / K,
-                           "cache_apply_rows_per_s": moved / pin_apply_s if pin_apply_s > 0 else None,
-                           "cache_apply_GBps": moved * (row_b + state_b) / pin_apply_s / 1e9 if pin_apply_s > 0 else None},
+        "other_schedule": dict(brief(res[main_place, "overlapped" if main_sched == "synchronous" else "synchronous"]),
+                               schedule="overlapped" if main_sched == "synchronous" else "synchronous"),
+        "pcie_inclusive": dict(brief(pin), schedule="overlapped", L_eff=plan.L_eff, reserve=reserve,
+                               early_prefetch_fraction=float(early[W:W + K].sum()) /
+                               max(1, int(plan.prefetch_offsets[W + K] - plan.prefetch_offsets[W])),
+                               synchronous=dict(brief(pin_sync), L_eff=first_sync.plan_.L_eff),
+                               rows_moved_per_step=moved / K,
+                               cache_apply_rows_per_s=moved / pin_apply_s if pin_apply_s > 0 else None,
+                               cache_apply_GBps=moved * (row_b + state_b) / pin_apply_s / 1e9 if pin_apply_s > 0 else None),
     }
+    for tr_ in trainers.values():
+        tr_.close()
     print(json.dumps(result))
     return 0
 

@@ -7,6 +7,12 @@
 #include "row_access.h"
 
 namespace bp {
+
+// Largest grid of the maintenance launches made from this host thread (0: one lane group per list entry).  The
+// overlapped schedule sets it so that its copies leave most of the GPU to the training kernels running beside them;
+// a few hundred wavefronts already keep the host link busy.
+thread_local int64_t g_cache_grid_cap = 0;
+
 namespace {
 
 // TO_BACKING: backing[id] <- cache[slot]; otherwise cache[slot] <- backing[id].
@@ -16,24 +22,25 @@ __global__ __launch_bounds__(kRowBlock) void cache_copy_rows_kernel(uint4* __res
                                                                     const int64_t* __restrict__ ids,
                                                                     const int32_t* __restrict__ slots, int64_t n, int64_t R,
                                                                     int64_t C, int lpr, int slpr, int rowwise) {
-    const int64_t e = ((int64_t)blockIdx.x * kRowBlock + threadIdx.x) / GW;
     const int c = threadIdx.x % GW;
-    if (e >= n) return;
-    const int64_t g = ids[e];
-    const int64_t s = slots[e];
-    if (g < 0 || g >= R || s < 0 || s >= C) return;
-    if (c < lpr) {
-        if (TO_BACKING) back_w[g * lpr + c] = cache_w[s * lpr + c];
-        else cache_w[s * lpr + c] = back_w[g * lpr + c];
-    }
-    for (int k = c; k < slpr; k += GW) {          // element-wise state: its own row of slpr pieces
-        if (TO_BACKING) back_s[g * slpr + k] = cache_s[s * slpr + k];
-        else cache_s[s * slpr + k] = back_s[g * slpr + k];
-    }
-    if (rowwise && c == 0) {                      // row-wise state: one fp32 per row
-        float* cs = reinterpret_cast<float*>(cache_s);
-        float* bs = reinterpret_cast<float*>(back_s);
-        if (TO_BACKING) bs[g] = cs[s]; else cs[s] = bs[g];
+    const int64_t stride = (int64_t)gridDim.x * (kRowBlock / GW);
+    for (int64_t e = ((int64_t)blockIdx.x * kRowBlock + threadIdx.x) / GW; e < n; e += stride) {
+        const int64_t g = ids[e];
+        const int64_t s = slots[e];
+        if (g < 0 || g >= R || s < 0 || s >= C) continue;
+        if (c < lpr) {
+            if (TO_BACKING) back_w[g * lpr + c] = cache_w[s * lpr + c];
+            else cache_w[s * lpr + c] = back_w[g * lpr + c];
+        }
+        for (int k = c; k < slpr; k += GW) {          // element-wise state: its own row of slpr pieces
+            if (TO_BACKING) back_s[g * slpr + k] = cache_s[s * slpr + k];
+            else cache_s[s * slpr + k] = back_s[g * slpr + k];
+        }
+        if (rowwise && c == 0) {                      // row-wise state: one fp32 per row
+            float* cs = reinterpret_cast<float*>(cache_s);
+            float* bs = reinterpret_cast<float*>(back_s);
+            if (TO_BACKING) bs[g] = cs[s]; else cs[s] = bs[g];
+        }
     }
 }
 
@@ -45,14 +52,15 @@ __global__ __launch_bounds__(kRowBlock) void cache_stage_rows_kernel(const uint4
                                                                      uint4* __restrict__ stage_w, uint4* __restrict__ stage_s,
                                                                      const int32_t* __restrict__ slots, int64_t n, int64_t C,
                                                                      int lpr, int slpr, int rowwise) {
-    const int64_t e = ((int64_t)blockIdx.x * kRowBlock + threadIdx.x) / GW;
     const int c = threadIdx.x % GW;
-    if (e >= n) return;
-    const int64_t s = slots[e];
-    if (s < 0 || s >= C) return;
-    if (c < lpr) stage_w[e * lpr + c] = cache_w[s * lpr + c];
-    for (int k = c; k < slpr; k += GW) stage_s[e * slpr + k] = cache_s[s * slpr + k];
-    if (rowwise && c == 0) reinterpret_cast<float*>(stage_s)[e] = reinterpret_cast<const float*>(cache_s)[s];
+    const int64_t stride = (int64_t)gridDim.x * (kRowBlock / GW);
+    for (int64_t e = ((int64_t)blockIdx.x * kRowBlock + threadIdx.x) / GW; e < n; e += stride) {
+        const int64_t s = slots[e];
+        if (s < 0 || s >= C) continue;
+        if (c < lpr) stage_w[e * lpr + c] = cache_w[s * lpr + c];
+        for (int k = c; k < slpr; k += GW) stage_s[e * slpr + k] = cache_s[s * slpr + k];
+        if (rowwise && c == 0) reinterpret_cast<float*>(stage_s)[e] = reinterpret_cast<const float*>(cache_s)[s];
+    }
 }
 
 // Duplex variant, step 2: one launch moves rows in both directions at once, so writes to the backing table
@@ -68,34 +76,41 @@ __global__ __launch_bounds__(kRowBlock) void cache_duplex_kernel(uint4* __restri
                                                                  const int64_t* __restrict__ p_ids,
                                                                  const int32_t* __restrict__ p_slots, int64_t n_p, int64_t R,
                                                                  int64_t C, int lpr, int slpr, int rowwise) {
-    const int64_t x = ((int64_t)blockIdx.x * kRowBlock + threadIdx.x) / GW;
     const int c = threadIdx.x % GW;
-    if (x >= n_e + n_p) return;
+    const int64_t stride = (int64_t)gridDim.x * (kRowBlock / GW);
     const int64_t both = 2 * (n_e < n_p ? n_e : n_p);
-    bool evict;
-    int64_t k;
-    if (x < both) {
-        evict = (x & 1) == 0;
-        k = x >> 1;
-    } else {
-        evict = n_e > n_p;
-        k = x - both / 2;
+    for (int64_t x = ((int64_t)blockIdx.x * kRowBlock + threadIdx.x) / GW; x < n_e + n_p; x += stride) {
+        bool evict;
+        int64_t k;
+        if (x < both) {
+            evict = (x & 1) == 0;
+            k = x >> 1;
+        } else {
+            evict = n_e > n_p;
+            k = x - both / 2;
+        }
+        if (evict) {
+            const int64_t g = e_ids[k];
+            const int64_t s = e_slots[k];
+            if (g < 0 || g >= R || s < 0 || s >= C) continue;        // same entries the staging step skipped
+            if (c < lpr) back_w[g * lpr + c] = stage_w[k * lpr + c];
+            for (int q = c; q < slpr; q += GW) back_s[g * slpr + q] = stage_s[k * slpr + q];
+            if (rowwise && c == 0) reinterpret_cast<float*>(back_s)[g] = reinterpret_cast<const float*>(stage_s)[k];
+        } else {
+            const int64_t g = p_ids[k];
+            const int64_t s = p_slots[k];
+            if (g < 0 || g >= R || s < 0 || s >= C) continue;
+            if (c < lpr) cache_w[s * lpr + c] = back_w[g * lpr + c];
+            for (int q = c; q < slpr; q += GW) cache_s[s * slpr + q] = back_s[g * slpr + q];
+            if (rowwise && c == 0) reinterpret_cast<float*>(cache_s)[s] = reinterpret_cast<const float*>(back_s)[g];
+        }
     }
-    if (evict) {
-        const int64_t g = e_ids[k];
-        const int64_t s = e_slots[k];
-        if (g < 0 || g >= R || s < 0 || s >= C) return;          // same entries the staging step skipped
-        if (c < lpr) back_w[g * lpr + c] = stage_w[k * lpr + c];
-        for (int q = c; q < slpr; q += GW) back_s[g * slpr + q] = stage_s[k * slpr + q];
-        if (rowwise && c == 0) reinterpret_cast<float*>(back_s)[g] = reinterpret_cast<const float*>(stage_s)[k];
-    } else {
-        const int64_t g = p_ids[k];
-        const int64_t s = p_slots[k];
-        if (g < 0 || g >= R || s < 0 || s >= C) return;
-        if (c < lpr) cache_w[s * lpr + c] = back_w[g * lpr + c];
-        for (int q = c; q < slpr; q += GW) cache_s[s * slpr + q] = back_s[g * slpr + q];
-        if (rowwise && c == 0) reinterpret_cast<float*>(cache_s)[s] = reinterpret_cast<const float*>(back_s)[g];
-    }
+}
+
+inline dim3 capped_grid(int64_t threads, int64_t max_blocks) {
+    int64_t blocks = ceil_div(threads, kRowBlock);
+    if (max_blocks > 0 && blocks > max_blocks) blocks = max_blocks;
+    return dim3((unsigned)(blocks > 0 ? blocks : 1));
 }
 
 struct DuplexLaunch {
@@ -109,17 +124,18 @@ struct DuplexLaunch {
     int64_t n_p;
     hipStream_t stream;
     bool stage, apply;     // which of the two steps to launch
+    int64_t max_blocks;    // 0: one lane group per entry; otherwise the grid is capped and the lane groups stride
     template <int GW, bool BF16>
     int run() {
         const int lpr = (int)(row_bytes(cfg) / 16);
         const int slpr = cfg->optimizer == BP_ADAGRAD ? cfg->dim / 4 : 0;
         const int rowwise = cfg->optimizer == BP_ADAGRAD_ROWWISE;
         if (stage && n_e)
-            BP_LAUNCH(K_CACHE_STAGE, (cache_stage_rows_kernel<GW>), dim3((unsigned)ceil_div(n_e * GW, kRowBlock)),
+            BP_LAUNCH(K_CACHE_STAGE, (cache_stage_rows_kernel<GW>), capped_grid(n_e * GW, max_blocks),
                       dim3(kRowBlock), 0, stream, (const uint4*)cache_w, (const uint4*)cache_s, (uint4*)stage_w,
                       (uint4*)stage_s, e_slots, n_e, cfg->capacity, lpr, slpr, rowwise);
         if (apply && n_e + n_p)
-            BP_LAUNCH(K_CACHE_DUPLEX, (cache_duplex_kernel<GW>), dim3((unsigned)ceil_div((n_e + n_p) * GW, kRowBlock)),
+            BP_LAUNCH(K_CACHE_DUPLEX, (cache_duplex_kernel<GW>), capped_grid((n_e + n_p) * GW, max_blocks),
                       dim3(kRowBlock), 0, stream, (uint4*)cache_w, (uint4*)cache_s, (uint4*)back_w, (uint4*)back_s,
                       (const uint4*)stage_w, (const uint4*)stage_s, e_ids, e_slots, n_e, p_ids, p_slots, n_p,
                       cfg->total_rows, cfg->capacity, lpr, slpr, rowwise);
@@ -142,12 +158,13 @@ struct CopyLaunch {
     int64_t n;
     bool to_backing;
     hipStream_t stream;
+    int64_t max_blocks;
     template <int GW, bool BF16>
     int run() {
         const int lpr = (int)(row_bytes(cfg) / 16);
         const int slpr = cfg->optimizer == BP_ADAGRAD ? cfg->dim / 4 : 0;
         const int rowwise = cfg->optimizer == BP_ADAGRAD_ROWWISE;
-        const dim3 grid((unsigned)ceil_div(n * GW, kRowBlock));
+        const dim3 grid = capped_grid(n * GW, max_blocks);
         if (to_backing)
             BP_LAUNCH(K_CACHE_EVICT, (cache_copy_rows_kernel<GW, true>), grid, dim3(kRowBlock), 0, stream, (uint4*)cache_w,
                       (uint4*)back_w, (uint4*)cache_s, (uint4*)back_s, ids, slots, n, cfg->total_rows, cfg->capacity, lpr,
@@ -182,12 +199,12 @@ BP_EXPORT int bp_cache_apply(const bp_config* cfg, void* cache_w, void* cache_st
     const int lpr = (int)(row_bytes(cfg) / 16);
     if (n_evict) {
         CopyLaunch l{cfg, cache_w, cache_state, backing_w, backing_state, evict_ids, evict_slots, n_evict, true,
-                     (hipStream_t)stream};
+                     (hipStream_t)stream, g_cache_grid_cap};
         BP_TRY(dispatch_row(lpr, false, l));
     }
     if (n_prefetch) {
         CopyLaunch l{cfg, cache_w, cache_state, backing_w, backing_state, prefetch_ids, prefetch_slots, n_prefetch, false,
-                     (hipStream_t)stream};
+                     (hipStream_t)stream, g_cache_grid_cap};
         BP_TRY(dispatch_row(lpr, false, l));
     }
     return BP_OK;
@@ -222,7 +239,7 @@ BP_EXPORT int bp_cache_apply_duplex(const bp_config* cfg, void* cache_w, void* c
         return fail(BP_ERR_WORKSPACE_TOO_SMALL, "workspace %zu < required %zu bytes", workspace_bytes, need);
     DuplexLaunch l{cfg, cache_w, cache_state, backing_w, backing_state, workspace,
                    workspace ? (char*)workspace + stage_w_bytes(cfg, n_evict) : nullptr, evict_ids, evict_slots, n_evict,
-                   prefetch_ids, prefetch_slots, n_prefetch, (hipStream_t)stream, true, true};
+                   prefetch_ids, prefetch_slots, n_prefetch, (hipStream_t)stream, true, true, g_cache_grid_cap};
     return dispatch_row((int)(row_bytes(cfg) / 16), false, l);
 }
 
@@ -250,7 +267,7 @@ BP_EXPORT int bp_cache_stage(const bp_config* cfg, const void* cache_w, const vo
     BP_TRY(check_staging(cfg, n_evict, staging, staging_bytes));
     DuplexLaunch l{cfg, const_cast<void*>(cache_w), const_cast<void*>(cache_state), nullptr, nullptr, staging,
                    (char*)staging + stage_w_bytes(cfg, n_evict), nullptr, evict_slots, n_evict, nullptr, nullptr, 0,
-                   (hipStream_t)stream, true, false};
+                   (hipStream_t)stream, true, false, g_cache_grid_cap};
     return dispatch_row((int)(row_bytes(cfg) / 16), false, l);
 }
 
@@ -272,6 +289,6 @@ BP_EXPORT int bp_cache_apply_staged(const bp_config* cfg, void* cache_w, void* c
     void* st = const_cast<void*>(staging);
     DuplexLaunch l{cfg, cache_w, cache_state, backing_w, backing_state, st,
                    st ? (char*)st + stage_w_bytes(cfg, n_evict) : nullptr, evict_ids, evict_slots, n_evict, prefetch_ids,
-                   prefetch_slots, n_prefetch, (hipStream_t)stream, false, true};
+                   prefetch_slots, n_prefetch, (hipStream_t)stream, false, true, g_cache_grid_cap};
     return dispatch_row((int)(row_bytes(cfg) / 16), false, l);
 }

@@ -42,6 +42,9 @@ int fail(int status, const char* fmt, ...) __attribute__((format(printf, 2, 3)))
 
 int check_config(const bp_config* cfg);
 
+// Grid cap of the cache maintenance launches made from this host thread (cache_apply.hip); 0 = no cap.
+extern thread_local int64_t g_cache_grid_cap;
+
 inline size_t elem_bytes(int dtype) { return dtype == BP_F32 ? 4 : 2; }
 inline size_t row_bytes(const bp_config* c) { return (size_t)c->dim * elem_bytes(c->weight_dtype); }
 inline size_t state_row_bytes(const bp_config* c) {

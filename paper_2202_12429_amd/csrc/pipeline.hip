@@ -8,6 +8,8 @@
 //        freed by batch i's evictions)                                         -> batch i+1 may start
 //   B_i  write the staged rows back and fetch the EARLY prefetches of batch i+2 (slots free since before batch
 //        i+1), while batch i+1 trains.
+// A batch without late prefetches (the usual case when the plan keeps a reserve of free slots) is ready as soon as
+// B of two batches earlier is done, so the compute stream never waits for the batch before it.
 // Which prefetches are early follows from the ring order alone: the x-th miss of the trace takes ring position x,
 // positions below C are the initial slots and position C + e is the slot of the e-th eviction, so the misses of
 // batch j whose position lies below C + (evictions up to batch j-2) are a prefix of its (id-ordered) list.
@@ -31,11 +33,16 @@ struct bp_pipeline {
     size_t staging_bytes;
     hipStream_t maint;
     hipEvent_t ready[2], done[2], hand;
+    int64_t grid_cap;     // workgroups per maintenance launch at most
     bool begun;
 };
 
 namespace bp {
 namespace {
+
+// Workgroups per maintenance launch: 2 per CU keeps ~2,000 wavefronts of 16-byte accesses in flight, enough for the
+// host link and for a backing table in HBM, and leaves the rest of every CU to the training kernels.
+constexpr int64_t kMaintenanceBlocks = 512;
 
 int prefetch_range(bp_pipeline* p, int64_t a, int64_t b) {      // cache <- backing for list entries [a, b)
     if (b <= a) return BP_OK;
@@ -43,8 +50,21 @@ int prefetch_range(bp_pipeline* p, int64_t a, int64_t b) {      // cache <- back
                           p->p_slots + a, b - a, p->maint);
 }
 
-// A_i and B_i for i in [-1, T-1]; i == -1 is the start of the trace (nothing to write back).
+struct GridCap {          // the maintenance launches of this scope stay narrow
+    explicit GridCap(int64_t cap) : old_(g_cache_grid_cap) { g_cache_grid_cap = cap; }
+    ~GridCap() { g_cache_grid_cap = old_; }
+    int64_t old_;
+};
+
+int64_t late_count(const bp_pipeline* p, int j) {
+    return j < p->T ? (p->p_off[j + 1] - p->p_off[j]) - p->early[j] : 0;
+}
+
+// A_i and B_i for i in [-1, T-1]; i == -1 is the start of the trace (nothing to write back).  Batch j is ready once
+// its last fetch is enqueued: after A_{j-1} when it has late prefetches, else already after B_{j-2}, in which case
+// it never waits for the batch before it.
 int enqueue_after_batch(bp_pipeline* p, int i) {
+    GridCap cap(p->grid_cap);
     const int T = p->T;
     const int64_t ea = i >= 0 ? p->e_off[i] : 0, eb = i >= 0 ? p->e_off[i + 1] : 0;
     const int64_t ne = eb - ea;
@@ -59,8 +79,10 @@ int enqueue_after_batch(bp_pipeline* p, int i) {
         return BP_OK;
     }
     BP_TRY(bp_cache_stage(&p->cfg, p->cache_w, p->cache_s, p->e_slots + ea, ne, p->staging, p->staging_bytes, p->maint));
-    BP_TRY(prefetch_range(p, p1a, p1b));
-    if (j1 < T) BP_HIP(hipEventRecord(p->ready[j1 & 1], p->maint));
+    if (j1 < T && (i < 0 || late_count(p, j1) > 0)) {
+        BP_TRY(prefetch_range(p, p1a, p1b));
+        BP_HIP(hipEventRecord(p->ready[j1 & 1], p->maint));
+    }
     if (p->L_eff >= 3) {     // rows evicted after batch i are not used by batch i+2: one launch, both directions
         BP_TRY(bp_cache_apply_staged(&p->cfg, p->cache_w, p->cache_s, p->back_w, p->back_s, p->e_ids + ea, p->e_slots + ea,
                                      ne, p->staging, p->staging_bytes, p->p_ids + p2a, p->p_slots + p2a, p2b - p2a,
@@ -70,6 +92,7 @@ int enqueue_after_batch(bp_pipeline* p, int i) {
                                      ne, p->staging, p->staging_bytes, nullptr, nullptr, 0, p->maint));
         BP_TRY(prefetch_range(p, p2a, p2b));
     }
+    if (j2 < T && late_count(p, j2) == 0) BP_HIP(hipEventRecord(p->ready[j2 & 1], p->maint));
     return BP_OK;
 }
 
@@ -135,6 +158,7 @@ BP_EXPORT int bp_pipeline_create(const bp_config* cfg, void* cache_w, void* cach
     p->T = n_iters; p->L_eff = L_eff;
     p->staging = staging; p->staging_bytes = staging_bytes;
     p->maint = nullptr; p->hand = nullptr; p->begun = false;
+    p->grid_cap = kMaintenanceBlocks;
     p->ready[0] = p->ready[1] = p->done[0] = p->done[1] = nullptr;
     int st = bp_pipeline_early_counts(prefetch_offsets, evict_offsets, n_iters, cfg->capacity, L_eff, p->early.data());
     hipError_t e = hipSuccess;
