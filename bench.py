@@ -66,6 +66,9 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--cpu-baseline-iters", type=int, default=40)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--skew", type=float, default=None,
+                    help="draw the ids from the skew-sensitivity law instead of Zipf: the hottest 1 %% of every "
+                         "table's rows take this share of the accesses (0.01 .. 0.9)")
     ap.add_argument("--reserve", type=int, default=-1,
                     help="cache slots the capacity policy keeps free for fetches that overlap training "
                          "(-1: 1.5 x the median per-batch miss count of the plan without reserve)")
@@ -87,7 +90,7 @@ def main() -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
-    cfg = workloads.CONFIGS[args.config]
+    cfg = workloads.CONFIGS[args.config] if args.skew is None else workloads.skew_config(args.config, args.skew)
     T = cfg.iterations
     W = max(0, min(args.warmup, T - 1))
     K = args.steps if args.steps > 0 else T - W

@@ -46,19 +46,27 @@ __global__ __launch_bounds__(256) void bwd_keys_kernel(const int32_t* __restrict
     vals[k] = bag;
 }
 
-// Grouped variant: bag of every lookup position (positions come grouped by row from the plan).
+// Grouped variant: the plan lists lookup positions grouped by row; the gradient row of a position is its bag.
+// First every bag writes its number over its own stretch of positions (neighbouring lanes write neighbouring
+// stretches), then the grouped positions pick their bag up from that map, which stays in L2.
+__global__ __launch_bounds__(256) void bwd_bag_of_lookup_kernel(const int64_t* __restrict__ bag_off, int64_t bags, int64_t n,
+                                                                uint32_t* __restrict__ bag_of_lookup) {
+    const int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (b >= bags) return;
+    int64_t k = bag_off[b], end = bag_off[b + 1];
+    if (k < 0) k = 0;
+    if (end > n) end = n;
+    for (; k < end; ++k) bag_of_lookup[k] = (uint32_t)b;
+}
+
 __global__ __launch_bounds__(256) void bwd_bags_of_positions_kernel(const int32_t* __restrict__ positions,
-                                                                    const int64_t* __restrict__ bag_off, int64_t n,
+                                                                    const uint32_t* __restrict__ bag_of_lookup, int64_t n,
                                                                     int64_t bags, uint32_t* __restrict__ bag_of) {
     const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (p >= n) return;
-    const int64_t k = positions[p];
-    int64_t lo = 0, hi = bags;                       // bag_off[lo] <= k < bag_off[hi]
-    while (hi - lo > 1) {
-        const int64_t mid = (lo + hi) >> 1;
-        if (bag_off[mid] <= k) lo = mid; else hi = mid;
-    }
-    bag_of[p] = (uint32_t)lo;
+    const uint32_t k = (uint32_t)positions[p];
+    const uint32_t b = k < (uint64_t)n ? bag_of_lookup[k] : 0u;
+    bag_of[p] = b < (uint64_t)bags ? b : 0u;      // offsets that do not cover every lookup leave holes in the map
 }
 
 // ---- 2. work items ---------------------------------------------------------------------------
@@ -522,7 +530,8 @@ BP_EXPORT int bp_embbag_bwd_update(const bp_config* cfg, void* cache_w, void* ca
 namespace bp {
 namespace {
 struct GroupedWorkspace {
-    uint32_t* bag_of;
+    uint32_t* bag_of;          // bag of every grouped position
+    uint32_t* bag_of_lookup;   // bag of every lookup, in lookup order
     double* partial;
     size_t bytes;
 };
@@ -531,6 +540,7 @@ GroupedWorkspace carve_grouped(void* base, size_t cap, int64_t n, int dim, bool 
     GroupedWorkspace w{};
     const size_t m = (size_t)(n > 0 ? n : 1);
     w.bag_of = multi_hot ? c.take<uint32_t>(m) : nullptr;
+    w.bag_of_lookup = multi_hot ? c.take<uint32_t>(m) : nullptr;
     w.partial = c.take<double>((2 * (m / kChunk + 2)) * (size_t)dim);
     w.bytes = c.used();
     return w;
@@ -571,8 +581,10 @@ BP_EXPORT int bp_embbag_bwd_update_grouped(const bp_config* cfg, void* cache_w, 
         return fail(BP_ERR_WORKSPACE_TOO_SMALL, "workspace %zu < required %zu bytes", workspace_bytes, w.bytes);
     const uint32_t* bag_of = reinterpret_cast<const uint32_t*>(grouped_lookups);   // one lookup per bag: position == bag
     if (bag_offsets) {
+        BP_LAUNCH(K_BWD_KEYS, bwd_bag_of_lookup_kernel, dim3((unsigned)ceil_div(bags > 0 ? bags : 1, 256)), dim3(256), 0,
+                  stream, bag_offsets, bags, n, w.bag_of_lookup);
         BP_LAUNCH(K_BWD_KEYS, bwd_bags_of_positions_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, stream,
-                  grouped_lookups, bag_offsets, n, bags, w.bag_of);
+                  grouped_lookups, (const uint32_t*)w.bag_of_lookup, n, bags, w.bag_of);
         bag_of = w.bag_of;
     }
     BwdLaunch l{cfg, w.partial, reinterpret_cast<const uint32_t*>(grouped_slots), bag_of, item_starts, nullptr,

@@ -477,3 +477,12 @@ def test_plan_with_reserve(bp):
         assert_plan_equal(got, want, len(tr.ids))
         assert_grouping_equal(got, want, tr.ids, tr.iter_offsets)
         assert got.peak_occupancy <= C - reserve
+
+
+@pytest.mark.parametrize("skew", [0.01, 0.4, 0.9])
+def test_end_to_end_skew_workload(bp, skew):
+    """The skew-sensitivity workload of Section 5.3 (hot 1 % with an exponential law, uniform tail), small."""
+    say(f"end to end: skew workload {skew}")
+    cfg = workloads.skew_config(0, skew, optimizer="adagrad", capacity=6000, iterations=30)
+    run_end_to_end(cfg, workloads.make_trace(cfg))
+    run_end_to_end(cfg, workloads.make_trace(cfg), overlapped=True, reserve=1500)

@@ -71,3 +71,38 @@ def test_hash_weights_and_grads():
     assert torch.equal(g, workloads.upstream_grad(cfg, 7, 2048))
     # every value is a multiple of 2^-16 (exact in fp32 on any device)
     assert torch.equal((g.double() * 65536).round(), g.double() * 65536)
+
+
+def test_hot_exp_law_has_the_chosen_skew():
+    """Section 5.3's artificial workload: the hottest 1 % of a table's rows carry the chosen share of the accesses
+    through a decaying law, the rest is uniform."""
+    for n, skew in ((10_000, 0.4), (1_000, 0.9), (50, 0.01), (3, 0.4)):
+        cdf = workloads.hot_exp_cdf(n, skew)
+        p = np.diff(np.concatenate([[0.0], cdf]))
+        h = max(1, int(np.ceil(0.01 * n)))
+        assert abs(cdf[-1] - 1.0) < 1e-12 and (p > 0).all()
+        assert abs(p[:h].sum() - skew) < 1e-12
+        assert np.all(np.diff(p[:h]) < 0)                              # decays over the hot ranks
+        if h > 1:
+            assert abs(p[0] / p[h - 1] - np.exp(workloads.HOT_EXP_DECAY * (h - 1) / h)) < 1e-6 * p[0] / p[h - 1]
+        assert np.allclose(p[h:], (1 - skew) / (n - h), rtol=1e-9)     # uniform tail
+    assert abs(workloads.hot_exp_cdf(1, 0.4)[0] - 1.0) < 1e-15       # a one-row table: all of it
+
+
+def test_skew_config_trace_matches_its_law():
+    cfg = workloads.skew_config(0, 0.4, iterations=40, batch=512)
+    assert cfg.id_law == "hot_exp" and cfg.name.endswith("skew40")
+    tr = workloads.make_trace(cfg)
+    tr2 = workloads.make_trace(cfg)
+    assert np.array_equal(tr.ids, tr2.ids)
+    toff = workloads.table_offsets(cfg)
+    # per table: the 1 % most frequent rows of the sample take about 40 % of its draws (20,480 draws per table)
+    for t in range(cfg.num_tables):
+        col = tr.ids.reshape(-1, cfg.num_tables)[:, t]
+        assert col.min() >= toff[t] and col.max() < toff[t + 1]
+        counts = np.sort(np.bincount(col - toff[t], minlength=cfg.table_rows[t]))[::-1]
+        share = counts[:cfg.table_rows[t] // 100].sum() / counts.sum()
+        assert 0.38 < share < 0.44, share                              # top-k of a sample overshoots a little
+    # a different skew gives a different trace, and Zipf configs are untouched by the new field
+    assert not np.array_equal(tr.ids, workloads.make_trace(workloads.skew_config(0, 0.9, iterations=40, batch=512)).ids)
+    assert workloads.CONFIGS[0].id_law == "zipf"

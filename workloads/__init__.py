@@ -9,7 +9,8 @@ The five workloads take the shapes of the paper's recommendation datasets
 (Table "Dataset and their embedding tables": 26 categorical features, tens of
 millions of rows, D=16 or 48; Section 2.3 "Embedding Access Patterns": ~1 % of
 rows serve > 92 % of accesses, batch 16,384) and of its own skew-sensitivity
-generator (Section 5.3, "Effect of Access Pattern Skew": Zipf-distributed ids).
+generators (Section 5.3, "Effect of Access Pattern Skew": Zipf-distributed ids, and a hot 1 % with an exponential
+law over a uniform tail).
 No dataset record is reproduced; every value below comes from a seeded
 generator.
 """
@@ -23,7 +24,7 @@ import numpy as np
 
 __all__ = [
     "Config", "Trace", "CONFIGS", "get_config", "make_trace", "table_offsets",
-    "zipf_cdf", "top_fraction_mass", "tune_zipf_exponent",
+    "zipf_cdf", "hot_exp_cdf", "rank_cdf", "skew_config", "top_fraction_mass", "tune_zipf_exponent",
     "init_weights", "upstream_grad", "hash_u32",
 ]
 
@@ -50,6 +51,8 @@ class Config:
     bag_min: int = 1             # bag length ~ U{bag_min..bag_max}; 1,1 = one-hot
     bag_max: int = 1
     drift_every: int = 0         # re-draw the rank->row permutation every this many iterations (0 = never)
+    id_law: str = "zipf"         # "zipf": P(rank r) ~ r**-zipf_s;  "hot_exp": the skew-sensitivity law (hot_exp_cdf)
+    hot_skew: float = 0.0        # "hot_exp": access probability carried by the hottest 1 % of every table's rows
 
     @property
     def num_tables(self) -> int:
@@ -150,6 +153,46 @@ def zipf_cdf(n_rows: int, s: float) -> np.ndarray:
     return p
 
 
+# Decay of the exponential law over the hot ranks: the hottest row is e**HOT_EXP_DECAY times as likely as the
+# coldest hot row.  The paper gives the shape ("an exponential function") but no rate; this value is this build's.
+HOT_EXP_DECAY = 5.0
+HOT_FRACTION = 0.01
+
+
+def hot_exp_cdf(n_rows: int, skew: float) -> np.ndarray:
+    """float64 CDF over ranks 0..n_rows-1 of the paper's skew-sensitivity workload (Section 5.3, "Effect of Access
+    Pattern Skew"): the hottest 1 % of the rows (at least one) share the probability `skew` through an
+    exponentially decaying law over their rank, the other rows share 1 - skew uniformly."""
+    h = max(1, int(math.ceil(HOT_FRACTION * n_rows)))
+    p = np.empty(n_rows, dtype=np.float64)
+    hot = np.exp(-HOT_EXP_DECAY * np.arange(h, dtype=np.float64) / h)
+    if h == n_rows:
+        p[:] = hot / hot.sum()
+    else:
+        p[:h] = hot * (skew / hot.sum())
+        p[h:] = (1.0 - skew) / (n_rows - h)
+    np.cumsum(p, out=p)
+    p /= p[-1]
+    return p
+
+
+def rank_cdf(cfg: "Config", n_rows: int) -> np.ndarray:
+    """CDF over the popularity ranks of a table of n_rows rows under the workload's id law."""
+    if cfg.id_law == "zipf":
+        return zipf_cdf(n_rows, cfg.zipf_s)
+    if cfg.id_law == "hot_exp":
+        return hot_exp_cdf(n_rows, cfg.hot_skew)
+    raise ValueError(f"unknown id_law {cfg.id_law!r}")
+
+
+def skew_config(index: int, skew: float, **overrides) -> "Config":
+    """configs[index] with its ids drawn from the skew-sensitivity law instead of Zipf: the hottest 1 % of every
+    table's rows take `skew` of the accesses (the paper sweeps 0.01 .. 0.90)."""
+    base = CONFIGS[index]
+    return dataclasses.replace(base, id_law="hot_exp", hot_skew=float(skew),
+                               name=f"{base.name}_skew{int(round(skew * 100))}", **overrides)
+
+
 def top_fraction_mass(table_rows, s: float, fraction: float = 0.01) -> float:
     """Access probability carried by the globally hottest `fraction` of rows when every table is sampled once per
     example with the same exponent s."""
@@ -200,7 +243,8 @@ class Trace:
 def make_trace(cfg: Config, iterations: Optional[int] = None) -> Trace:
     """Draw the lookup ids of `iterations` (default cfg.iterations) batches.
 
-    Each (sample, table) bag holds U{bag_min..bag_max} ids; an id is rank r ~ Zipf(s) over the table's rows,
+    Each (sample, table) bag holds U{bag_min..bag_max} ids; an id is a rank drawn from the workload's id law
+    (Zipf(s), or the hot-1 % law of skew_config) over the table's rows,
     mapped to a row through a seeded per-table permutation (re-drawn every `drift_every` iterations to move the
     hot set).  Streams are independent per (seed, purpose, table, epoch)."""
     T = cfg.iterations if iterations is None else int(iterations)
@@ -229,7 +273,7 @@ def make_trace(cfg: Config, iterations: Optional[int] = None) -> Trace:
     for t in range(nt):
         n_rows = cfg.table_rows[t]
         if n_rows not in cdf_cache:
-            cdf_cache = {n_rows: zipf_cdf(n_rows, cfg.zipf_s)}   # keep one CDF alive (10 M rows = 80 MB)
+            cdf_cache = {n_rows: rank_cdf(cfg, n_rows)}   # keep one CDF alive (10 M rows = 80 MB)
         cdf = cdf_cache[n_rows]
         for e, (a, b) in enumerate(epochs):
             rng = np.random.default_rng([cfg.seed, 303, t, e])
