@@ -35,9 +35,9 @@ HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published peak
 # HBM traffic per launch of the dominant kernel from rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE; KiB per dispatch,
 # scaled by the copy-kernel calibration), keyed by (workload, kernel).  Filled in from profiles/; None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/hbm_traffic_cfg2_pmc.txt: FETCH_SIZE 76907.5 KiB x2 (copy calibration) + WRITE_SIZE 39449.9 KiB x1
-    ("criteo_kaggle_d48", "bwd_reduce_update"): 197.90e6,
-    ("criteo_kaggle_d48", "embbag_fwd"): 123.74e6,
+    # profiles/hbm_traffic_cfg2_pmc.txt: FETCH_SIZE 76915.4 KiB x2 (copy calibration) + WRITE_SIZE 39384.8 KiB x1
+    ("criteo_kaggle_d48", "bwd_reduce_update"): 197.85e6,
+    ("criteo_kaggle_d48", "embbag_fwd"): 122.54e6,
 }
 
 
@@ -66,6 +66,9 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--cpu-baseline-iters", type=int, default=40)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--value-only", action="store_true",
+                    help="run only the placement and schedule `value` is quoted on (for kernel profiles: the other "
+                         "runs launch the same kernels under different conditions and would blur per-kernel averages)")
     ap.add_argument("--skew", type=float, default=None,
                     help="draw the ids from the skew-sensitivity law instead of Zipf: the hottest 1 %% of every "
                          "table's rows take this share of the accesses (0.01 .. 0.9)")
@@ -193,6 +196,8 @@ def main() -> int:
         trainers["hbm", "synchronous"] = make_trainer(bcfg_sync, backing_w_dev, backing_s_dev)
     trainers["pinned_host", "overlapped"] = make_trainer(bcfg, backing_w, backing_s)
     trainers["pinned_host", "synchronous"] = make_trainer(bcfg_sync, backing_w, backing_s)
+    main_place = "hbm" if hbm_resident else "pinned_host"
+    main_sched = "synchronous" if hbm_resident else "overlapped"
     first = next(iter(trainers.values()))
     ws = torch.empty(bp.bp_oracle_plan_workspace_bytes(bcfg, trace.n_lookups, T, grouping=True), dtype=torch.uint8,
                      device=dev)
@@ -229,6 +234,8 @@ def main() -> int:
     copy_gbs = 5 * 2 * ca.numel() * 4 / (time.perf_counter() - t0) / 1e9
     del ca, cb
     log(f"plain copy kernel: {copy_gbs:.0f} GB/s (read + write)")
+    bracket_us = bp.bp_profile_bracket_overhead(400)
+    log(f"event bracket around an empty kernel: {bracket_us:.2f} us")
 
     bag_off_dev = None if cfg.one_hot else [torch.from_numpy(np.ascontiguousarray(trace.bag_offsets[i])).to(dev)
                                             for i in range(T)]
@@ -306,12 +313,11 @@ def main() -> int:
         t_total = t_loop + t_plan * K / T                      # the plan's share of these K batches
         return dict(t_loop=t_loop, t_total=t_total, dominant=dominant, prof_dom=prof_dom[dominant], kernel_ms=kernel_ms)
 
-    res = {key: measure(tr_, key[1] == "overlapped") for key, tr_ in trainers.items()}
-    main_place = "hbm" if hbm_resident else "pinned_host"
+    res = {key: measure(tr_, key[1] == "overlapped") for key, tr_ in trainers.items()
+           if not args.value_only or key == (main_place, main_sched)}
     # With the table in HBM every kernel of the step is HBM-bound, so running the maintenance beside the training
     # kernels moves the same bytes through the same memory and gains nothing: the synchronous schedule is the one
     # `value` reports.  With the table behind the host link the overlapped schedule hides the link time.
-    main_sched = "synchronous" if hbm_resident else "overlapped"
     m = res[main_place, main_sched]
     plan_main = first_sync.plan_ if main_sched == "synchronous" else plan
     value = n_timed / m["t_total"]
@@ -324,10 +330,10 @@ def main() -> int:
     traffic = MEASURED_TRAFFIC_BYTES.get((cfg.name, dominant))
     kernel_ms = m["kernel_ms"]
     fbu_ms = kernel_ms["fwd"] + kernel_ms["bwd_sort_and_items"] + kernel_ms["bwd_reduce_update"] + kernel_ms["bwd_combine_update"]
-    pin = res["pinned_host", "overlapped"]
-    pin_sync = res["pinned_host", "synchronous"]
+    pin = res.get(("pinned_host", "overlapped"))
+    pin_sync = res.get(("pinned_host", "synchronous"))
     moved = rows_moved(first_sync.plan_)
-    pin_apply_s = pin_sync["kernel_ms"]["cache_apply"] * 1e-3 * K
+    pin_apply_s = pin_sync["kernel_ms"]["cache_apply"] * 1e-3 * K if pin_sync else 0.0
 
     def brief(r):
         return {"value": n_timed / r["t_total"], "unit": "lookups/s", "ms_per_step": r["t_total"] / K * 1e3,
@@ -357,16 +363,18 @@ def main() -> int:
                    "capacity_note": capacity_note, "unique_rows_per_step": u_mean},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "algorithmic_bytes_per_launch": alg,
-                     "avg_launch_us": dur_s * 1e6, "launches": launches,
+                     "avg_launch_us": dur_s * 1e6, "launches": launches, "empty_kernel_bracket_us": bracket_us,
                      "frac_of_measured_copy": achieved / copy_gbs, "measured_copy_GBps": copy_gbs},
         "cpu_baseline": cpu,
         "plan": {"ms": t_plan * 1e3, "ids_per_s": trace.n_lookups / t_plan, "n_lookups": trace.n_lookups},
         "loop_ms_per_step": m["t_loop"] / K * 1e3,
         "kernel_ms_per_step": kernel_ms,
         "fwd_bwd_update_lookups_per_s_kernel_time": n_mean / (fbu_ms * 1e-3) if fbu_ms > 0 else None,
-        "other_schedule": dict(brief(res[main_place, "overlapped" if main_sched == "synchronous" else "synchronous"]),
-                               schedule="overlapped" if main_sched == "synchronous" else "synchronous"),
-        "pcie_inclusive": dict(brief(pin), schedule="overlapped", L_eff=plan.L_eff, reserve=reserve,
+        "other_schedule": None if args.value_only else dict(
+            brief(res[main_place, "overlapped" if main_sched == "synchronous" else "synchronous"]),
+            schedule="overlapped" if main_sched == "synchronous" else "synchronous"),
+        "pcie_inclusive": None if args.value_only else dict(
+                               brief(pin), schedule="overlapped", L_eff=plan.L_eff, reserve=reserve,
                                early_prefetch_fraction=float(early[W:W + K].sum()) /
                                max(1, int(plan.prefetch_offsets[W + K] - plan.prefetch_offsets[W])),
                                synchronous=dict(brief(pin_sync), L_eff=first_sync.plan_.L_eff),

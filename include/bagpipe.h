@@ -309,6 +309,9 @@ int bp_version(void);
  */
 int bp_profile_enable(int on);
 int bp_profile_select(uint64_t kernel_mask);
+/* Median reading, in microseconds, of the same pair of events around a kernel that does nothing (`reps` launches on
+ * `stream`, synchronises it): the share of every profiled duration that is the bracket, not the kernel. */
+int bp_profile_bracket_overhead(void* stream, int32_t reps, double* median_us);
 int bp_profile_collect(void);
 int bp_profile_num_kernels(void);
 const char* bp_profile_kernel_name(int id);

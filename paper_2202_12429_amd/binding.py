@@ -92,6 +92,8 @@ def load_library():
     lib.bp_profile_get.argtypes = [ctypes.c_int, ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)]
     lib.bp_copy_calibration.argtypes = [vp, vp, sz, vp]
     lib.bp_copy_calibration.restype = ctypes.c_int
+    lib.bp_profile_bracket_overhead.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double)]
+    lib.bp_profile_bracket_overhead.restype = ctypes.c_int
     lib.bp_profile_select.argtypes = [ctypes.c_uint64]
     lib.bp_profile_select.restype = ctypes.c_int
     for name in ("bp_oracle_plan_workspace_bytes", "bp_oracle_plan", "bp_cache_apply", "bp_embbag_fwd",
@@ -405,6 +407,13 @@ def bp_copy_calibration(dst, src, stream=None) -> None:
 
 def bp_profile_enable(on: bool) -> None:
     _check(load_library().bp_profile_enable(int(bool(on))))
+
+
+def bp_profile_bracket_overhead(reps: int = 200, stream=None) -> float:
+    """Microseconds the profiler's event bracket reads around an empty kernel (median of `reps`)."""
+    out = ctypes.c_double(0.0)
+    _check(load_library().bp_profile_bracket_overhead(_stream(stream), int(reps), ctypes.byref(out)))
+    return float(out.value)
 
 
 def bp_profile_select(kernel_names=None) -> None:

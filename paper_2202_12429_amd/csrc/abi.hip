@@ -1,5 +1,6 @@
 // Status text, argument checks shared by all entry points, and the event-based kernel profiler.
 #include <cstring>
+#include <algorithm>
 #include <vector>
 
 #include "common.h"
@@ -96,6 +97,9 @@ __global__ __launch_bounds__(256) void copy_calibration_kernel(const uint4* __re
     if (i < n16) dst[i] = src[i];
 }
 
+// Does nothing: what a pair of bracketing events reads around it is the cost of the bracket itself.
+__global__ __launch_bounds__(64) void bracket_probe_kernel() {}
+
 }  // namespace bp
 
 using namespace bp;
@@ -116,6 +120,32 @@ BP_EXPORT const char* bp_error_string(int status) {
 BP_EXPORT const char* bp_last_error_message(void) { return t_error; }
 
 BP_EXPORT int bp_version(void) { return 100; }
+
+BP_EXPORT int bp_profile_bracket_overhead(void* stream_, int32_t reps, double* median_us) {
+    hipStream_t stream = (hipStream_t)stream_;
+    if (!median_us || reps < 1 || reps > 4096) return fail(BP_ERR_INVALID_ARG, "median_us is NULL or reps outside [1, 4096]");
+    std::vector<hipEvent_t> ev(2 * (size_t)reps, nullptr);
+    int st = BP_OK;
+    for (auto& e : ev)
+        if (hipEventCreate(&e) != hipSuccess) st = fail(BP_ERR_HIP, "hipEventCreate failed");
+    if (st == BP_OK) {
+        for (int r = 0; r < reps; ++r) {
+            (void)hipEventRecord(ev[2 * r], stream);
+            hipLaunchKernelGGL(bracket_probe_kernel, dim3(1), dim3(64), 0, stream);
+            (void)hipEventRecord(ev[2 * r + 1], stream);
+        }
+        if (hipStreamSynchronize(stream) != hipSuccess) st = fail(BP_ERR_HIP, "hipStreamSynchronize failed");
+    }
+    if (st == BP_OK) {
+        std::vector<float> ms((size_t)reps, 0.f);
+        for (int r = 0; r < reps; ++r) (void)hipEventElapsedTime(&ms[r], ev[2 * r], ev[2 * r + 1]);
+        std::nth_element(ms.begin(), ms.begin() + reps / 2, ms.end());
+        *median_us = (double)ms[reps / 2] * 1e3;
+    }
+    for (auto e : ev)
+        if (e) (void)hipEventDestroy(e);
+    return st;
+}
 
 BP_EXPORT int bp_copy_calibration(void* dst, const void* src, size_t bytes, void* stream) {
     if (!dst || !src || bytes % 16 != 0 || (((uintptr_t)dst | (uintptr_t)src) & 15))
