@@ -130,7 +130,10 @@ def run_bwd_grouped(bp, cfg, w, state, slots, off, bags, grad, onehot):
 
 @pytest.mark.parametrize("D,dtype,optimizer", [(16, "f32", "sgd"), (48, "f32", "adagrad"), (64, "f32", "sgd"),
                                                (128, "bf16", "adagrad_rowwise"), (32, "bf16", "adagrad"),
-                                               (48, "f32", "adagrad_rowwise"), (8, "bf16", "sgd")])
+                                               (48, "f32", "adagrad_rowwise"), (8, "bf16", "sgd"),
+                                               # one lane, 32 and 64 lanes per row (1,024-byte rows are the limit)
+                                               (4, "f32", "adagrad"), (128, "f32", "sgd"), (256, "f32", "adagrad"),
+                                               (512, "bf16", "adagrad_rowwise"), (160, "f32", "adagrad_rowwise")])
 @pytest.mark.parametrize("max_len", [1, 20])
 def test_backward_update(bp, D, dtype, optimizer, max_len):
     say(f"backward D={D} {dtype} {optimizer} max_len={max_len}")
@@ -206,7 +209,8 @@ def test_backward_degenerate(bp):
 # ---------------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("D,dtype,optimizer,pinned", [(16, "f32", "sgd", True), (48, "f32", "adagrad", True),
                                                       (128, "bf16", "adagrad_rowwise", True),
-                                                      (64, "bf16", "adagrad", False)])
+                                                      (64, "bf16", "adagrad", False),
+                                                      (256, "f32", "adagrad", True), (4, "f32", "sgd", False)])
 def test_cache_apply(bp, D, dtype, optimizer, pinned):
     say(f"cache_apply D={D} {dtype} {optimizer} pinned={pinned}")
     R, C = 20011, 1500
