@@ -52,6 +52,8 @@ def _load():
         _lib.orc_unique_per_iter.argtypes = [p, p, i64, i64, p, p]
         _lib.orc_peak_occupancy.restype = i64
         _lib.orc_peak_occupancy.argtypes = [p, p, i64, i64, i64, p]
+        _lib.orc_auto_lookahead.restype = i64
+        _lib.orc_auto_lookahead.argtypes = [p, p, i64, i64, i64]
         _lib.orc_choose_lookahead.restype = i64
         _lib.orc_choose_lookahead.argtypes = [p, p, i64, i64, i64, i64, i32, p]
         _lib.orc_plan.restype = i64
@@ -124,6 +126,15 @@ def choose_lookahead(uniq, uoff, total_rows, L, C, exhaustive=False):
     return int(r)
 
 
+def auto_lookahead(uniq, uoff, total_rows, C) -> int:
+    """Lookahead when none is configured: batches prefetched at start-up until the cache of C slots is full."""
+    lib = _load()
+    r = lib.orc_auto_lookahead(_ptr(uniq), _ptr(uoff), uoff.shape[0] - 1, total_rows, int(C))
+    if r < 0:
+        raise OracleError(r, "auto_lookahead")
+    return int(r)
+
+
 def plan(ids, iter_off, total_rows, L, C, exhaustive=False, L_eff=None, reserve=0) -> Plan:
     """Whole-trace lookahead plan (part A).  L_eff=None applies the capacity policy: the largest lookahead whose
     peak occupancy fits C - reserve slots (reserve > 0 keeps that many slots free, so that a batch's prefetches can
@@ -134,6 +145,10 @@ def plan(ids, iter_off, total_rows, L, C, exhaustive=False, L_eff=None, reserve=
     N = ids.shape[0]
     uniq, uoff = unique_per_iter(ids, iter_off, total_rows)
     if L_eff is None:
+        if L == 0:      # no lookahead configured: the start-up rule gives it, then the capacity policy applies
+            L = auto_lookahead(uniq, uoff, total_rows, C - reserve)
+            if L == 0:
+                raise OracleError(-2, "auto_lookahead", min_capacity=int(np.diff(uoff).max()))
         L_eff = choose_lookahead(uniq, uoff, total_rows, L, C - reserve, exhaustive)
     M = max(1, uniq.shape[0])
     occ = np.zeros(T, dtype=np.int64)

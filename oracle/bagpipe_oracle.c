@@ -151,6 +151,30 @@ int64_t orc_choose_lookahead(const int64_t *uniq, const int64_t *uniq_off, int64
 }
 
 /*
+ * Lookahead when none is configured (Section 4, "Automatically Calculating Lookahead"): at start-up the batches are
+ * prefetched one after the other until the cache is full; the number of batches prefetched by then is the lookahead.
+ * Written out: the largest k such that the distinct ids of batches 0 .. k-1 together fit into C slots (k <= T).
+ * Returns k (0 when even the first batch does not fit).
+ */
+int64_t orc_auto_lookahead(const int64_t *uniq, const int64_t *uniq_off, int64_t T, int64_t total_rows, int64_t C) {
+    if (C < 1 || T < 0) return ORC_ERR_ARG;
+    uint8_t *seen = (uint8_t *)calloc((size_t)(total_rows > 0 ? total_rows : 1), 1);
+    if (!seen) return ORC_ERR_NOMEM;
+    int64_t held = 0, k = 0;
+    for (int64_t i = 0; i < T; ++i) {
+        for (int64_t q = uniq_off[i]; q < uniq_off[i + 1]; ++q) {
+            int64_t g = uniq[q];
+            if (g < 0 || g >= total_rows) { free(seen); return ORC_ERR_ID_RANGE; }
+            if (!seen[g]) { seen[g] = 1; ++held; }
+        }
+        if (held > C) break;
+        k = i + 1;
+    }
+    free(seen);
+    return k;
+}
+
+/*
  * The plan: Algorithm 1 with lookahead Leff, cache slots from a FIFO ring of C free slots.
  *
  * Per iteration i (two phases, so that a slot freed by one id of batch i is never handed to another

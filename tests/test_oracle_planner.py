@@ -368,3 +368,63 @@ def test_tiny_config_plan_invariants():
     # capacity binding: L_eff shrinks, occupancy still fits
     p2 = check_invariants(tr.ids, tr.iter_offsets, cfg.total_rows, cfg.lookahead, 1500)
     assert 1 <= p2.L_eff < cfg.lookahead and p2.peak <= 1500
+
+
+# ---------------------------------------------------------------------------------------------------
+# lookahead when none is configured (Section 4, "Automatically Calculating Lookahead")
+# ---------------------------------------------------------------------------------------------------
+def _auto_by_sets(ids, off, C):
+    """Batches prefetched at start-up until the cache is full, with Python sets."""
+    held, k = set(), 0
+    for i in range(len(off) - 1):
+        held |= set(ids[off[i]:off[i + 1]].tolist())
+        if len(held) > C:
+            break
+        k = i + 1
+    return k
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_auto_lookahead_against_sets(seed):
+    rng = np.random.default_rng(900 + seed)
+    R, T = int(rng.integers(10, 200)), int(rng.integers(1, 25))
+    lens = rng.integers(0, 40, size=T)
+    off = np.zeros(T + 1, dtype=np.int64)
+    off[1:] = np.cumsum(lens)
+    ids = rng.integers(0, R, size=int(off[-1])).astype(np.int64)
+    uniq, uoff = oracle.unique_per_iter(ids, off, R)
+    for C in (1, 3, 10, 40, R, 10 * R):
+        assert oracle.auto_lookahead(uniq, uoff, R, C) == _auto_by_sets(ids, off, C), (seed, C)
+
+
+def test_auto_lookahead_closed_forms():
+    # all ids distinct, m per batch: floor(C / m) batches fit
+    m, T = 7, 12
+    ids = np.arange(m * T, dtype=np.int64)
+    off = np.arange(0, m * T + 1, m, dtype=np.int64)
+    uniq, uoff = oracle.unique_per_iter(ids, off, m * T)
+    for C in (6, 7, 13, 14, 50, 1000):
+        assert oracle.auto_lookahead(uniq, uoff, m * T, C) == min(C // m, T)
+    # the same batch again and again: everything fits as soon as one batch does
+    ids = np.tile(np.arange(5, dtype=np.int64), 9)
+    off = np.arange(0, 46, 5, dtype=np.int64)
+    uniq, uoff = oracle.unique_per_iter(ids, off, 5)
+    assert oracle.auto_lookahead(uniq, uoff, 5, 5) == 9 and oracle.auto_lookahead(uniq, uoff, 5, 4) == 0
+
+
+def test_plan_without_configured_lookahead():
+    """L = 0: the start-up rule picks the lookahead, then the capacity policy may still lower it."""
+    rng = np.random.default_rng(5)
+    R, T = 120, 30
+    off = np.arange(0, 20 * T + 1, 20, dtype=np.int64)
+    ids = np.minimum(rng.zipf(1.3, size=20 * T) - 1, R - 1).astype(np.int64)
+    uniq, uoff = oracle.unique_per_iter(ids, off, R)
+    for C in (25, 40, 80, 400):
+        La = oracle.auto_lookahead(uniq, uoff, R, C)
+        assert La >= 1
+        p = oracle.plan(ids, off, R, 0, C)
+        q = oracle.plan(ids, off, R, La, C)
+        assert p.L_eff == q.L_eff <= La and np.array_equal(p.lookup_slots, q.lookup_slots)
+        assert p.peak <= C
+    with pytest.raises(oracle.OracleError):
+        oracle.plan(ids, off, R, 0, 3)                   # the first batch alone does not fit
