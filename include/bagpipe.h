@@ -61,7 +61,9 @@ typedef struct bp_config {
     int32_t weight_dtype; /* BP_F32 | BP_BF16 */
     int32_t optimizer;    /* BP_SGD | BP_ADAGRAD | BP_ADAGRAD_ROWWISE */
     int32_t lookahead;    /* requested lookahead value: window of this many batches including the current
-                             one (Algorithm 1's LookAheadValue), >= 1 */
+                             one (Algorithm 1's LookAheadValue), >= 1.  0 = not configured: the planner takes the
+                             number of leading batches whose distinct rows together fit capacity - reserve slots
+                             ("prefetch until the cache is full", Section 4) and applies the capacity policy to it */
     float lr;             /* learning rate */
     float eps;            /* Adagrad epsilon */
     int64_t reserve;      /* slots the planner's capacity policy leaves free, 0 <= reserve < capacity: L_eff is the
@@ -116,6 +118,8 @@ typedef struct bp_plan {
     int64_t* split_offsets;    /* host [T+1] CSR offsets of the batches into split_starts */
     /* scalar results */
     int32_t L_eff;
+    int32_t L_requested;       /* the lookahead the capacity policy started from: cfg->lookahead, or, when that is 0,
+                                  the start-up rule's value (see bp_config.lookahead) */
     int64_t peak_occupancy;
     int64_t min_capacity;      /* max_i |U_i|: the smallest capacity - reserve for which a plan exists */
     int64_t n_unique_pairs;    /* sum_i |U_i| */

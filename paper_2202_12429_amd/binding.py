@@ -39,7 +39,7 @@ class _bp_plan(ctypes.Structure):
                 ("grouped_slots", ctypes.c_void_p), ("grouped_lookups", ctypes.c_void_p),
                 ("item_starts", ctypes.c_void_p), ("item_offsets", ctypes.c_void_p),
                 ("split_starts", ctypes.c_void_p), ("split_offsets", ctypes.c_void_p), ("L_eff", ctypes.c_int32),
-                ("peak_occupancy", ctypes.c_int64), ("min_capacity", ctypes.c_int64),
+                ("L_requested", ctypes.c_int32), ("peak_occupancy", ctypes.c_int64), ("min_capacity", ctypes.c_int64),
                 ("n_unique_pairs", ctypes.c_int64)]
 
 
@@ -180,6 +180,7 @@ class Plan:
     grouped_lookups: "object" = None    # int32 [N] device
     item_starts: "object" = None        # uint32 (as int32 tensor) device, trimmed to the item count
     item_offsets: Optional[np.ndarray] = None   # int64 [T+1] host
+    L_requested: int = 0                # configured lookahead, or the start-up rule's value when none was configured
     split_starts: "object" = None       # uint32 (as int32 tensor) device, trimmed
     split_offsets: Optional[np.ndarray] = None  # int64 [T+1] host
 
@@ -227,7 +228,7 @@ def bp_oracle_plan(cfg: bp_config, ids, iter_offsets, list_capacity: Optional[in
                             _ptr(workspace), workspace.numel(), _stream(stream))
     _check(st, min_capacity=int(p.min_capacity), n_unique_pairs=int(p.n_unique_pairs))
     n_pf, n_k = int(h["prefetch_offsets"][-1]), int(h["keep_offsets"][-1])
-    return Plan(L_eff=int(p.L_eff), peak_occupancy=int(p.peak_occupancy), min_capacity=int(p.min_capacity),
+    return Plan(L_eff=int(p.L_eff), L_requested=int(p.L_requested), peak_occupancy=int(p.peak_occupancy), min_capacity=int(p.min_capacity),
                 n_unique_pairs=int(p.n_unique_pairs), lookup_slots=t["lookup_slots"][:N],
                 prefetch_ids=t["prefetch_ids"][:n_pf], prefetch_slots=t["prefetch_slots"][:n_pf],
                 evict_ids=t["evict_ids"][:n_pf], evict_slots=t["evict_slots"][:n_pf],

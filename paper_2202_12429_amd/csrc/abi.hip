@@ -35,7 +35,7 @@ int check_config(const bp_config* cfg) {
         return fail(BP_ERR_INVALID_ARG, "unknown optimizer %d", cfg->optimizer);
     if (cfg->reserve < 0 || cfg->reserve >= cfg->capacity)
         return fail(BP_ERR_INVALID_ARG, "reserve %lld outside [0, capacity)", (long long)cfg->reserve);
-    if (cfg->lookahead < 1) return fail(BP_ERR_INVALID_ARG, "lookahead %d < 1", cfg->lookahead);
+    if (cfg->lookahead < 0) return fail(BP_ERR_INVALID_ARG, "lookahead %d < 0", cfg->lookahead);
     if (cfg->dim < 1) return fail(BP_ERR_INVALID_ARG, "dim %d < 1", cfg->dim);
     const size_t rb = row_bytes(cfg);
     if (rb % 16 != 0) return fail(BP_ERR_INVALID_ARG, "row of %zu bytes is not a multiple of 16 bytes", rb);

@@ -38,7 +38,7 @@ struct PlanScalars {
     uint32_t error_flags;   // bit 0: id out of range
     int32_t L_eff;          // 0 = no feasible lookahead
     int32_t L_sel;          // min(L_eff, Lcap): index into peak[]
-    uint32_t pad;
+    int32_t L_requested;    // configured lookahead, or the start-up rule's value when none is configured
     int64_t peak;
     int64_t min_capacity;
 };
@@ -103,11 +103,13 @@ __device__ __forceinline__ uint32_t pair_gap(const uint64_t* ukey, uint32_t q, u
 // atomics.  Integer atomics only: the sums do not depend on the order.
 __global__ __launch_bounds__(kBlock) void plan_hist_kernel(const uint64_t* __restrict__ ukey, uint32_t M, int ib, int T,
                                                            int Lcap, int lds_gaps, uint32_t per_block,
-                                                           uint32_t* __restrict__ H, uint32_t* __restrict__ ucount) {
-    extern __shared__ uint32_t lds[];   // [T] unique counts, then [lds_gaps][T] histogram rows
+                                                           uint32_t* __restrict__ H, uint32_t* __restrict__ ucount,
+                                                           uint32_t* __restrict__ first_use) {
+    extern __shared__ uint32_t lds[];   // [T] unique counts, [T] first uses, then [lds_gaps][T] histogram rows
     uint32_t* lds_u = lds;
-    uint32_t* lds_h = lds + T;
-    const int cells = (1 + lds_gaps) * T;
+    uint32_t* lds_f = lds + T;
+    uint32_t* lds_h = lds + 2 * T;
+    const int cells = (2 + lds_gaps) * T;
     for (int i = threadIdx.x; i < cells; i += kBlock) lds[i] = 0;
     __syncthreads();
     const uint64_t imask = (uint64_t(1) << ib) - 1;
@@ -116,6 +118,7 @@ __global__ __launch_bounds__(kBlock) void plan_hist_kernel(const uint64_t* __res
     for (uint64_t q = begin + threadIdx.x; q < end; q += kBlock) {
         const uint32_t i = (uint32_t)(ukey[q] & imask);
         atomicAdd(&lds_u[i], 1u);
+        if (q == 0 || (ukey[q - 1] >> ib) != (ukey[q] >> ib)) atomicAdd(&lds_f[i], 1u);   // the id's first batch
         const uint32_t gap = pair_gap(ukey, (uint32_t)q, M, ib, imask);
         if (gap >= 2u && gap < (uint32_t)Lcap) {
             if (gap < 2u + (uint32_t)lds_gaps) atomicAdd(&lds_h[(gap - 2u) * T + i], 1u);
@@ -123,8 +126,10 @@ __global__ __launch_bounds__(kBlock) void plan_hist_kernel(const uint64_t* __res
         }
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < T; i += kBlock)
+    for (int i = threadIdx.x; i < T; i += kBlock) {
         if (lds_u[i]) atomicAdd(&ucount[i], lds_u[i]);
+        if (lds_f[i]) atomicAdd(&first_use[i], lds_f[i]);
+    }
     for (int x = threadIdx.x; x < lds_gaps * T; x += kBlock)
         if (lds_h[x]) atomicAdd(&H[(size_t)2 * T + x], lds_h[x]);      // row (2 + x / T), column x % T
 }
@@ -173,15 +178,30 @@ __global__ __launch_bounds__(kBlock) void plan_occ_peak_kernel(const uint32_t* _
 }
 
 // one thread: pick L_eff, exclusive scan of the per-batch unique counts
-__global__ void plan_choose_kernel(const uint32_t* __restrict__ peak, const uint32_t* __restrict__ ucount, int T,
-                                   int Lcap, int lookahead, int64_t C, PlanScalars* sc,
-                                   uint32_t* __restrict__ pair_off) {
+__global__ void plan_choose_kernel(const uint32_t* __restrict__ peak, const uint32_t* __restrict__ ucount,
+                                   const uint32_t* __restrict__ first_use, int T, int Lcap, int lookahead, int64_t budget,
+                                   PlanScalars* sc, uint32_t* __restrict__ pair_off) {
     if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    int requested = lookahead, top = Lcap;
+    if (lookahead == 0) {
+        // no lookahead configured (Section 4): batches are prefetched at start-up until the cache is full; the
+        // distinct rows of batches 0..k-1 are the ids whose first use lies in those batches
+        int64_t held = 0;
+        int k = 0;
+        for (int i = 0; i < T; ++i) {
+            held += first_use[i];
+            if (held > budget) break;
+            k = i + 1;
+        }
+        requested = k;
+        top = k < Lcap ? k : Lcap;
+    }
     int sel = 0;
-    for (int Lp = Lcap; Lp >= 1; --Lp)
-        if ((int64_t)peak[Lp] <= C) { sel = Lp; break; }
+    for (int Lp = top; Lp >= 1; --Lp)
+        if ((int64_t)peak[Lp] <= budget) { sel = Lp; break; }
     sc->L_sel = sel;
-    sc->L_eff = sel == Lcap ? lookahead : sel;   // windows of T or more batches are all alike
+    sc->L_eff = (sel == top && sel > 0) ? requested : sel;   // windows of T or more batches are all alike
+    sc->L_requested = requested;
     sc->peak = sel ? peak[sel] : 0;
     sc->min_capacity = peak[1];
     uint32_t run = 0;
@@ -465,7 +485,7 @@ struct PlanWorkspace {
     uint32_t* sort_temp;
     uint32_t* scan_partials32;   // head scan, chain scan
     uint64_t* scan_partials64;   // list scan
-    uint32_t *H, *ucount, *peak, *pair_off;
+    uint32_t *H, *ucount, *first_use, *peak, *pair_off;
     PlanScalars* scalars;
     int64_t *occ, *prefetch_off, *evict_off, *iter_off;
     uint64_t *rec_a, *rec_b;
@@ -491,6 +511,7 @@ PlanWorkspace carve_plan(void* base, size_t cap, int64_t N, int T, int Lcap, boo
     w.scan_partials64 = c.take<uint64_t>(scan_partials(N));
     w.H = c.take<uint32_t>((size_t)(Lcap + 1) * T);
     w.ucount = c.take<uint32_t>(T);
+    w.first_use = c.take<uint32_t>(T);
     w.peak = c.take<uint32_t>(Lcap + 2);
     w.pair_off = c.take<uint32_t>(T + 1);
     w.scalars = c.take<PlanScalars>(1);
@@ -568,7 +589,7 @@ BP_EXPORT int bp_oracle_plan_workspace_bytes(const bp_config* cfg, int64_t n_loo
                                              size_t* bytes) {
     if (!bytes) return fail(BP_ERR_INVALID_ARG, "bytes is NULL");
     BP_TRY(check_plan_args(cfg, n_lookups, n_iters));
-    const int Lcap = cfg->lookahead < n_iters ? cfg->lookahead : n_iters;
+    const int Lcap = cfg->lookahead > 0 && cfg->lookahead < n_iters ? cfg->lookahead : n_iters;
     *bytes = carve_plan(nullptr, 0, n_lookups, n_iters, Lcap, with_grouping != 0).bytes;
     return BP_OK;
 }
@@ -591,7 +612,7 @@ BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int
         return fail(BP_ERR_INVALID_ARG, "a device array of the plan is NULL");
     if (!workspace || ((uintptr_t)workspace & 255)) return fail(BP_ERR_INVALID_ARG, "workspace NULL or not 256-byte aligned");
 
-    const int Lcap = cfg->lookahead < T ? cfg->lookahead : T;
+    const int Lcap = cfg->lookahead > 0 && cfg->lookahead < T ? cfg->lookahead : T;   // 0: not configured, any window
     const int64_t C = cfg->capacity;
     const bool grouping = plan->grouped_slots || plan->grouped_lookups || plan->item_starts || plan->item_offsets ||
                           plan->split_starts || plan->split_offsets;
@@ -603,13 +624,14 @@ BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int
         return fail(BP_ERR_WORKSPACE_TOO_SMALL, "workspace %zu < required %zu bytes", workspace_bytes, w.bytes);
 
     plan->L_eff = 0;
+    plan->L_requested = cfg->lookahead;
     plan->peak_occupancy = 0;
     plan->min_capacity = 0;
     plan->n_unique_pairs = 0;
     if (N == 0) {   // nothing is ever looked up: empty lists, the full requested lookahead is feasible
         for (int i = 0; i <= T; ++i) plan->prefetch_offsets[i] = plan->evict_offsets[i] = plan->keep_offsets[i] = 0;
         for (int i = 0; i < T; ++i) plan->occupancy[i] = 0;
-        plan->L_eff = cfg->lookahead;
+        plan->L_eff = plan->L_requested = cfg->lookahead ? cfg->lookahead : T;
         if (grouping)
             for (int i = 0; i <= T; ++i) plan->item_offsets[i] = plan->split_offsets[i] = 0;
         return BP_OK;
@@ -648,29 +670,32 @@ BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int
     // ---- 3. occupancy for every candidate lookahead, L_eff
     BP_HIP(hipMemsetAsync(w.H, 0, sizeof(uint32_t) * (size_t)(Lcap + 1) * T, stream));
     BP_HIP(hipMemsetAsync(w.ucount, 0, sizeof(uint32_t) * T, stream));
+    BP_HIP(hipMemsetAsync(w.first_use, 0, sizeof(uint32_t) * T, stream));
     BP_HIP(hipMemsetAsync(w.peak, 0, sizeof(uint32_t) * (Lcap + 2), stream));
     {
-        int lds_gaps = (int)((48 * 1024 / 4 - T) / T);                  // histogram rows that fit in 48 KiB next to [T]
+        int lds_gaps = (int)((48 * 1024 / 4 - 2 * T) / T);              // histogram rows that fit in 48 KiB next to 2 x [T]
         if (lds_gaps > Lcap - 2) lds_gaps = Lcap - 2;
         if (lds_gaps < 0) lds_gaps = 0;
         int64_t blocks = ceil_div(M, 32 * 1024);                         // >= 32 Ki pairs per workgroup amortise the flush
         if (blocks > 1024) blocks = 1024;
         const uint32_t per_block = (uint32_t)ceil_div(M, blocks);
         BP_LAUNCH(K_PLAN_HIST, plan_hist_kernel, dim3((unsigned)blocks), dim3(kBlock),
-                  sizeof(uint32_t) * (size_t)(1 + lds_gaps) * T, stream, (const uint64_t*)ukey, M, ib, T, Lcap, lds_gaps,
-                  per_block, w.H, w.ucount);
+                  sizeof(uint32_t) * (size_t)(2 + lds_gaps) * T, stream, (const uint64_t*)ukey, M, ib, T, Lcap, lds_gaps,
+                  per_block, w.H, w.ucount, w.first_use);
     }
     BP_LAUNCH(K_PLAN_OCC, plan_occ_prefix_kernel, grid_for(Lcap), dim3(kBlock), 0, stream, w.H, T, Lcap);
     BP_LAUNCH(K_PLAN_OCC, plan_occ_peak_kernel, dim3(T), dim3(kBlock), 0, stream, (const uint32_t*)w.H,
               (const uint32_t*)w.ucount, T, Lcap, w.peak);
     BP_LAUNCH(K_PLAN_OCC, plan_choose_kernel, dim3(1), dim3(64), 0, stream, (const uint32_t*)w.peak,
-              (const uint32_t*)w.ucount, T, Lcap, cfg->lookahead, C - cfg->reserve, w.scalars, w.pair_off);
+              (const uint32_t*)w.ucount, (const uint32_t*)w.first_use, T, Lcap, cfg->lookahead, C - cfg->reserve,
+              w.scalars, w.pair_off);
     BP_LAUNCH(K_PLAN_OCC, plan_occ_final_kernel, grid_for(T), dim3(kBlock), 0, stream, (const uint32_t*)w.H,
               (const uint32_t*)w.ucount, T, (const PlanScalars*)w.scalars, w.occ);
     BP_HIP(hipMemcpyAsync(&hs, w.scalars, sizeof(PlanScalars), hipMemcpyDeviceToHost, stream));
     BP_HIP(hipMemcpyAsync(plan->occupancy, w.occ, sizeof(int64_t) * T, hipMemcpyDeviceToHost, stream));
     BP_HIP(hipStreamSynchronize(stream));
     plan->min_capacity = hs.min_capacity;
+    plan->L_requested = hs.L_requested;
     if (hs.L_eff < 1)
         return fail(BP_ERR_CAPACITY, "capacity %lld - reserve %lld < %lld unique rows of one batch", (long long)C,
                     (long long)cfg->reserve, (long long)hs.min_capacity);

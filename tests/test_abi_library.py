@@ -58,7 +58,7 @@ def test_argument_errors_without_gpu(lib):
     for bad in (bp.make_config(1000, 64, 6),              # 24-byte rows: not a multiple of 16 bytes
                 bp.make_config(1000, 0, 16),               # no capacity
                 bp.make_config(0, 64, 16),                 # no rows
-                bp.make_config(1000, 64, 16, lookahead=0),
+                bp.make_config(1000, 64, 16, lookahead=-1),
                 bp.make_config(1000, 64, 16, reserve=64),  # nothing left to plan with
                 bp.make_config(1000, 64, 16, reserve=-1)):
         with pytest.raises(bp.BagpipeError) as e:

@@ -325,8 +325,8 @@ def test_plan_random_small(bp, seed):
     if len(ids) == 0:
         return
     umax = max(len(np.unique(ids[off[i]:off[i + 1]])) for i in range(T))
-    for L, C in ((1, umax), (3, umax), (T + 7, umax + 5), (T, 4 * R), (2, umax + 1)):
-        plan_both(bp, ids, off, R, max(1, L), max(1, C))
+    for L, C in ((1, umax), (3, umax), (T + 7, umax + 5), (T, 4 * R), (2, umax + 1), (0, umax + 5), (0, 2 * umax)):
+        plan_both(bp, ids, off, R, L, max(1, C))          # L = 0: lookahead from the start-up rule
 
 
 def test_plan_tiny_config(bp):
@@ -461,6 +461,27 @@ def test_end_to_end_overlapped(bp, optimizer, dtype, bag_max, capacity, reserve,
         assert early.sum() == 0
     if reserve >= misses.max():
         assert np.array_equal(early[1:], misses[1:])
+
+
+def test_plan_without_configured_lookahead(bp):
+    """lookahead = 0: the start-up rule of Section 4 (batches prefetched until the cache is full) gives the lookahead,
+    the capacity policy may lower it; same plan as the oracle's."""
+    say("plan without a configured lookahead")
+    cfg = workloads.get_config(0, iterations=40)
+    tr = workloads.make_trace(cfg)
+    uniq, uoff = oracle.unique_per_iter(tr.ids, tr.iter_offsets, cfg.total_rows)
+    for C, reserve in ((1400, 0), (2500, 300), (4096, 0), (200_000, 0)):
+        want_L = oracle.auto_lookahead(uniq, uoff, cfg.total_rows, C - reserve)
+        want = oracle.plan(tr.ids, tr.iter_offsets, cfg.total_rows, 0, C, reserve=reserve)
+        got = bp.bp_oracle_plan(bp.make_config(cfg.total_rows, C, 16, lookahead=0, reserve=reserve), dev(tr.ids),
+                                tr.iter_offsets, grouping=True)
+        assert got.L_requested == want_L
+        assert_plan_equal(got, want, len(tr.ids))
+        assert_grouping_equal(got, want, tr.ids, tr.iter_offsets)
+        say(f"  C={C} reserve={reserve}: start-up rule {want_L}, L_eff {got.L_eff}")
+    with pytest.raises(bp.BagpipeError) as e:            # the first batch alone does not fit
+        bp.bp_oracle_plan(bp.make_config(cfg.total_rows, 900, 16, lookahead=0), dev(tr.ids), tr.iter_offsets)
+    assert e.value.status == -2
 
 
 def test_plan_with_reserve(bp):
