@@ -144,6 +144,40 @@ int bp_oracle_plan_workspace_bytes(const bp_config* cfg, int64_t n_lookups, int3
 int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offsets, int32_t n_iters,
                    bp_plan* plan, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Chunked planning for a stream of batches (the paper's Oracle Cacher sees the batches as they arrive, a lookahead
+ * ahead of the trainers, Sections 3.1 and 3.3): bp_oracle_plan_chunk plans the first n_emit of the n_iters batches
+ * it is given and carries the state of the cache to the next call.  The batches after the n_emit-th are the window
+ * the decisions look into: pass min(lookahead - 1, what the stream still holds) of them.  With the same effective
+ * lookahead in every chunk the concatenated plans equal bp_oracle_plan's over the whole stream, slot for slot.
+ * The capacity policy is applied per chunk (peak occupancy of the emitted batches, carried rows included), so the
+ * effective lookahead may change from chunk to chunk; a row kept under an earlier, larger lookahead stays until
+ * its next use.
+ *
+ * bp_plan_state   n_resident rows are in the cache at the boundary: resident_ids (device [capacity], ascending)
+ *                 and ring (device [capacity]): the residents' slots in the same order, then the free slots in
+ *                 the order they will be handed out.  state_in == NULL: empty cache, slots 0..capacity-1 in order.
+ *                 state_in and state_out must be different buffers; the caller owns both.
+ * plan            as for bp_oracle_plan, with these differences: host arrays have n_emit + 1 (offsets) or n_emit
+ *                 (occupancy) entries; offsets are positions in the device lists and need not start at 0 (the carried
+ *                 rows' own entries come first); keep_ttl counts batches from the chunk's first batch; lookup_slots
+ *                 and the grouping cover all n_iters batches given (those past n_emit are provisional);
+ *                 list_capacity >= n_unique_pairs, which counts the carried rows too; peak_occupancy and
+ *                 min_capacity are taken over the emitted batches.
+ * workspace       bp_oracle_plan_chunk_workspace_bytes(cfg, n_lookups, n_iters, with_grouping) bytes.
+ * Errors as for bp_oracle_plan.  Synchronises `stream`.
+ */
+typedef struct bp_plan_state {
+    int64_t n_resident;
+    int64_t* resident_ids;
+    int32_t* ring;
+} bp_plan_state;
+int bp_oracle_plan_chunk_workspace_bytes(const bp_config* cfg, int64_t n_lookups, int32_t n_iters, int32_t with_grouping,
+                                         size_t* bytes);
+int bp_oracle_plan_chunk(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offsets, int32_t n_iters,
+                         int32_t n_emit, const bp_plan_state* state_in, bp_plan_state* state_out, bp_plan* plan,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
 /* ------------------------------------------------------------------------------------------------
  * (2) Cache maintenance between two batches: first every evicted row (weights and optimizer state) is
  * copied from its cache slot back to the backing table, then every prefetched row is copied from the

@@ -52,6 +52,8 @@ def _load():
         _lib.orc_unique_per_iter.argtypes = [p, p, i64, i64, p, p]
         _lib.orc_peak_occupancy.restype = i64
         _lib.orc_peak_occupancy.argtypes = [p, p, i64, i64, i64, p]
+        _lib.orc_plan_stream.restype = i64
+        _lib.orc_plan_stream.argtypes = [p] * 4 + [i64, i64, p, i64] + [p] * 11
         _lib.orc_auto_lookahead.restype = i64
         _lib.orc_auto_lookahead.argtypes = [p, p, i64, i64, i64]
         _lib.orc_choose_lookahead.restype = i64
@@ -166,6 +168,57 @@ def plan(ids, iter_off, total_rows, L, C, exhaustive=False, L_eff=None, reserve=
                 prefetch_off=poff, prefetch_ids=pid[:r].copy(), prefetch_slots=ps[:r].copy(),
                 evict_off=eoff, evict_ids=eid[:r].copy(), evict_slots=es[:r].copy(),
                 keep_off=koff, keep_ids=kid[:nk].copy(), keep_ttl=kt[:nk].copy())
+
+
+def plan_varying(ids, iter_off, total_rows, L_of, C) -> Plan:
+    """Algorithm 1 with a lookahead per batch: the window of batch i is [i, i + L_of[i] - 1].  Slow, small inputs."""
+    lib = _load()
+    ids, iter_off = _c(ids, np.int64), _c(iter_off, np.int64)
+    L_of = _c(L_of, np.int32)
+    T = iter_off.shape[0] - 1
+    N = ids.shape[0]
+    assert L_of.shape[0] == T
+    uniq, uoff = unique_per_iter(ids, iter_off, total_rows)
+    M = max(1, uniq.shape[0])
+    occ = np.zeros(T, dtype=np.int64)
+    slots = np.empty(max(1, N), dtype=np.int32)
+    poff, eoff, koff = (np.zeros(T + 1, dtype=np.int64) for _ in range(3))
+    pid, eid, kid = (np.empty(M, dtype=np.int64) for _ in range(3))
+    ps, es, kt = (np.empty(M, dtype=np.int32) for _ in range(3))
+    r = lib.orc_plan_stream(_ptr(ids), _ptr(iter_off), _ptr(uniq), _ptr(uoff), T, total_rows, _ptr(L_of), int(C),
+                            _ptr(occ), _ptr(slots), _ptr(poff), _ptr(pid), _ptr(ps), _ptr(eoff), _ptr(eid), _ptr(es),
+                            _ptr(koff), _ptr(kid), _ptr(kt))
+    if r < 0:
+        raise OracleError(r, "plan_varying")
+    nk = int(koff[-1])
+    return Plan(L_eff=int(L_of.max()) if T else 0, peak=int(occ.max()) if T else 0, occ=occ, lookup_slots=slots[:N],
+                prefetch_off=poff, prefetch_ids=pid[:r].copy(), prefetch_slots=ps[:r].copy(),
+                evict_off=eoff, evict_ids=eid[:r].copy(), evict_slots=es[:r].copy(),
+                keep_off=koff, keep_ids=kid[:nk].copy(), keep_ttl=kt[:nk].copy())
+
+
+def plan_chunked(ids, iter_off, total_rows, L, C, n_emit, reserve=0):
+    """The stream planned chunk by chunk (n_emit batches at a time), each chunk with the largest lookahead <= L whose
+    peak occupancy over the chunk's batches fits C - reserve, earlier chunks keeping theirs.  Returns (plan, L_of).
+    Exhaustive and slow: every candidate is planned from the start of the stream."""
+    iter_off = _c(iter_off, np.int64)
+    T = iter_off.shape[0] - 1
+    L_of = np.full(T, L, dtype=np.int32)
+    for a in range(0, T, n_emit):
+        b = min(T, a + n_emit)
+        chosen = None
+        for cand in range(L, 0, -1):
+            L_of[a:] = cand
+            # occupancy does not depend on how many slots there are: count it with a ring that cannot run dry
+            p = plan_varying(ids, iter_off, total_rows, L_of, total_rows + 1)
+            if p.occ[a:b].max(initial=0) <= C - reserve:
+                chosen = cand
+                break
+        if chosen is None:
+            raise OracleError(-2, "plan_chunked", chunk_start=a)
+        L_of[a:b] = chosen
+        L_of[b:] = L
+    return plan_varying(ids, iter_off, total_rows, L_of, C), L_of
 
 
 def state_shape(rows, D, optimizer):

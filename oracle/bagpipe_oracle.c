@@ -238,6 +238,72 @@ int64_t orc_plan(const int64_t *ids, const int64_t *iter_off, const int64_t *uni
     return rc == ORC_OK ? np : rc;
 }
 
+/*
+ * The plan when the lookahead may change from batch to batch (Section 4: the Oracle Cacher "can reduce" the
+ * lookahead when the cache is about to fill): Algorithm 1 with the window of batch i taken as
+ * [i, i + Leff_of[i] - 1].  TTL of an id of batch i = its last use inside that window, found by looking into the
+ * batches of the window one by one; everything else as in orc_plan (two phases per batch, FIFO ring of free slots).
+ * Same outputs as orc_plan.  Slow on purpose: O(window) per (id, batch).
+ */
+static int batch_has_id(const int64_t *uniq, const int64_t *uniq_off, int64_t b, int64_t g) {
+    int64_t lo = uniq_off[b], hi = uniq_off[b + 1];        /* ids of a batch are sorted */
+    while (lo < hi) {
+        int64_t mid = lo + (hi - lo) / 2;
+        if (uniq[mid] < g) lo = mid + 1; else hi = mid;
+    }
+    return lo < uniq_off[b + 1] && uniq[lo] == g;
+}
+
+int64_t orc_plan_stream(const int64_t *ids, const int64_t *iter_off, const int64_t *uniq, const int64_t *uniq_off,
+                        int64_t T, int64_t total_rows, const int32_t *Leff_of, int64_t C,
+                        int64_t *occ, int32_t *lookup_slots,
+                        int64_t *prefetch_off, int64_t *prefetch_ids, int32_t *prefetch_slots,
+                        int64_t *evict_off, int64_t *evict_ids, int32_t *evict_slots,
+                        int64_t *keep_off, int64_t *keep_ids, int32_t *keep_ttl) {
+    if (C < 1 || C > INT32_MAX) return ORC_ERR_ARG;
+    int32_t *slot_of = (int32_t *)malloc((size_t)total_rows * sizeof(int32_t));   /* -1: not in cache */
+    int32_t *ring = (int32_t *)malloc((size_t)C * sizeof(int32_t));
+    if (!slot_of || !ring) { free(slot_of); free(ring); return ORC_ERR_NOMEM; }
+    for (int64_t g = 0; g < total_rows; ++g) slot_of[g] = -1;
+    for (int64_t s = 0; s < C; ++s) ring[s] = (int32_t)s;
+    int64_t head = 0, nfree = C, resident = 0, np = 0, ne = 0, nk = 0, rc = ORC_OK;
+    prefetch_off[0] = evict_off[0] = keep_off[0] = 0;
+    for (int64_t i = 0; i < T && rc == ORC_OK; ++i) {
+        if (Leff_of[i] < 1) { rc = ORC_ERR_ARG; break; }
+        int64_t last_batch = i + Leff_of[i] - 1 < T - 1 ? i + Leff_of[i] - 1 : T - 1;
+        int64_t first_keep = nk;
+        for (int64_t k = uniq_off[i]; k < uniq_off[i + 1]; ++k) {
+            int64_t g = uniq[k];
+            int64_t ttl = i;
+            for (int64_t b = i + 1; b <= last_batch; ++b)
+                if (batch_has_id(uniq, uniq_off, b, g)) ttl = b;
+            keep_ids[nk] = g; keep_ttl[nk] = (int32_t)ttl; ++nk;
+            if (slot_of[g] < 0) {
+                if (nfree == 0) { rc = ORC_ERR_CAPACITY; break; }
+                int32_t s = ring[head]; head = (head + 1) % C; --nfree;
+                slot_of[g] = s; ++resident;
+                prefetch_ids[np] = g; prefetch_slots[np] = s; ++np;
+            }
+        }
+        if (rc != ORC_OK) break;
+        if (occ) occ[i] = resident;
+        for (int64_t k = iter_off[i]; k < iter_off[i + 1]; ++k) lookup_slots[k] = slot_of[ids[k]];
+        for (int64_t k = first_keep; k < nk; ++k) {
+            if (keep_ttl[k] == i) {
+                int64_t g = keep_ids[k];
+                int32_t s = slot_of[g];
+                evict_ids[ne] = g; evict_slots[ne] = s; ++ne;
+                ring[(head + nfree) % C] = s; ++nfree;
+                slot_of[g] = -1; --resident;
+            }
+        }
+        prefetch_off[i + 1] = np; evict_off[i + 1] = ne; keep_off[i + 1] = nk;
+    }
+    if (rc == ORC_OK && (resident != 0 || np != ne || nfree != C)) rc = ORC_ERR_INTERNAL;  /* cache drains */
+    free(slot_of); free(ring);
+    return rc == ORC_OK ? np : rc;
+}
+
 /* ------------------------------------------------------------------ parts B and C: training */
 
 static inline float bf16_to_f32(uint16_t h) {

@@ -30,6 +30,10 @@ class bp_config(ctypes.Structure):
                 ("lr", ctypes.c_float), ("eps", ctypes.c_float), ("reserve", ctypes.c_int64)]
 
 
+class _bp_plan_state(ctypes.Structure):
+    _fields_ = [("n_resident", ctypes.c_int64), ("resident_ids", ctypes.c_void_p), ("ring", ctypes.c_void_p)]
+
+
 class _bp_plan(ctypes.Structure):
     _fields_ = [("lookup_slots", ctypes.c_void_p), ("prefetch_ids", ctypes.c_void_p),
                 ("prefetch_slots", ctypes.c_void_p), ("evict_ids", ctypes.c_void_p), ("evict_slots", ctypes.c_void_p),
@@ -65,6 +69,9 @@ def load_library():
     cfgp = ctypes.POINTER(bp_config)
     lib.bp_oracle_plan_workspace_bytes.argtypes = [cfgp, i64, i32, i32, ctypes.POINTER(sz)]
     lib.bp_oracle_plan.argtypes = [cfgp, vp, vp, i32, ctypes.POINTER(_bp_plan), vp, sz, vp]
+    lib.bp_oracle_plan_chunk_workspace_bytes.argtypes = [cfgp, i64, i32, i32, ctypes.POINTER(sz)]
+    lib.bp_oracle_plan_chunk.argtypes = [cfgp, vp, vp, i32, i32, ctypes.POINTER(_bp_plan_state),
+                                         ctypes.POINTER(_bp_plan_state), ctypes.POINTER(_bp_plan), vp, sz, vp]
     lib.bp_cache_apply.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, i64, vp, vp, i64, vp]
     lib.bp_cache_apply_duplex_workspace_bytes.argtypes = [cfgp, i64, ctypes.POINTER(sz)]
     lib.bp_cache_apply_duplex.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, i64, vp, vp, i64, vp, sz, vp]
@@ -100,7 +107,8 @@ def load_library():
                  "bp_embbag_bwd_update_workspace_bytes", "bp_embbag_bwd_update", "bp_version",
                  "bp_embbag_bwd_update_grouped_workspace_bytes", "bp_embbag_bwd_update_grouped",
                  "bp_cache_apply_duplex_workspace_bytes", "bp_cache_apply_duplex", "bp_cache_stage",
-                 "bp_cache_apply_staged", "bp_profile_enable", "bp_pipeline_early_counts", "bp_pipeline_create",
+                 "bp_cache_apply_staged", "bp_profile_enable", "bp_oracle_plan_chunk_workspace_bytes",
+                 "bp_oracle_plan_chunk", "bp_pipeline_early_counts", "bp_pipeline_create",
                  "bp_pipeline_destroy", "bp_pipeline_early", "bp_pipeline_begin", "bp_pipeline_acquire",
                  "bp_pipeline_release", "bp_pipeline_end",
                  "bp_profile_collect", "bp_profile_num_kernels", "bp_profile_get"):
@@ -241,6 +249,79 @@ def bp_oracle_plan(cfg: bp_config, ids, iter_offsets, list_capacity: Optional[in
                 item_offsets=h["item_offsets"] if grouping else None,
                 split_starts=t["split_starts"][:int(h["split_offsets"][-1])] if grouping else None,
                 split_offsets=h["split_offsets"] if grouping else None)
+
+
+@dataclasses.dataclass
+class PlanState:
+    """State of the cache at a chunk boundary (bp_plan_state): device tensors of `capacity` entries."""
+    n_resident: int
+    resident_ids: "object"       # int64 [C] device, the first n_resident valid, ascending
+    ring: "object"               # int32 [C] device: the residents' slots, then the free slots in hand-out order
+
+
+def bp_oracle_plan_chunk_workspace_bytes(cfg: bp_config, n_lookups: int, n_iters: int, grouping: bool = False) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load_library().bp_oracle_plan_chunk_workspace_bytes(ctypes.byref(cfg), int(n_lookups), int(n_iters),
+                                                               int(bool(grouping)), ctypes.byref(out)))
+    return int(out.value)
+
+
+def bp_oracle_plan_chunk(cfg: bp_config, ids, iter_offsets, n_emit: int, state: Optional[PlanState] = None,
+                         stream=None, grouping: bool = False):
+    """Plans the first n_emit of the batches given (the rest is the lookahead window) from the carried `state`
+    (None: empty cache).  Returns (Plan, PlanState after the last emitted batch).  The Plan's offsets have
+    n_emit + 1 entries and index the list tensors, which are left untrimmed at the front."""
+    import torch
+    lib = load_library()
+    iter_offsets = np.ascontiguousarray(iter_offsets, dtype=np.int64)
+    T = iter_offsets.shape[0] - 1
+    N = int(iter_offsets[-1])
+    C = int(cfg.capacity)
+    assert ids.dtype == torch.int64 and ids.numel() == N
+    dev = ids.device
+    cap = N + C
+    workspace = torch.empty(bp_oracle_plan_chunk_workspace_bytes(cfg, N, T, grouping), dtype=torch.uint8, device=dev)
+    i32 = dict(dtype=torch.int32, device=dev)
+    i64 = dict(dtype=torch.int64, device=dev)
+    t = dict(lookup_slots=torch.empty(max(N, 1), **i32),
+             prefetch_ids=torch.empty(cap, **i64), prefetch_slots=torch.empty(cap, **i32),
+             evict_ids=torch.empty(cap, **i64), evict_slots=torch.empty(cap, **i32),
+             keep_ids=torch.empty(cap, **i64), keep_ttl=torch.empty(cap, **i32))
+    h = dict(prefetch_offsets=np.zeros(n_emit + 1, np.int64), evict_offsets=np.zeros(n_emit + 1, np.int64),
+             keep_offsets=np.zeros(n_emit + 1, np.int64), occupancy=np.zeros(max(n_emit, 1), np.int64))
+    if grouping:
+        t.update(grouped_slots=torch.empty(max(N, 1), **i32), grouped_lookups=torch.empty(max(N, 1), **i32),
+                 item_starts=torch.empty(max(N, 1), **i32), split_starts=torch.empty(N // 32 + 2, **i32))
+        h.update(item_offsets=np.zeros(n_emit + 1, np.int64), split_offsets=np.zeros(n_emit + 1, np.int64))
+    p = _bp_plan()
+    for k, v in t.items():
+        setattr(p, k, v.data_ptr())
+    for k, v in h.items():
+        setattr(p, k, v.ctypes.data)
+    p.list_capacity = cap
+    out = PlanState(0, torch.empty(C, **i64), torch.empty(C, **i32))
+    s_out = _bp_plan_state(0, out.resident_ids.data_ptr(), out.ring.data_ptr())
+    s_in = None
+    if state is not None:
+        s_in = ctypes.byref(_bp_plan_state(int(state.n_resident), state.resident_ids.data_ptr(), state.ring.data_ptr()))
+    st = lib.bp_oracle_plan_chunk(ctypes.byref(cfg), _ptr(ids) if N else None, iter_offsets.ctypes.data, T, int(n_emit),
+                                  s_in, ctypes.byref(s_out), ctypes.byref(p), _ptr(workspace), workspace.numel(),
+                                  _stream(stream))
+    _check(st, min_capacity=int(p.min_capacity), n_unique_pairs=int(p.n_unique_pairs))
+    out.n_resident = int(s_out.n_resident)
+    plan = Plan(L_eff=int(p.L_eff), L_requested=int(p.L_requested), peak_occupancy=int(p.peak_occupancy),
+                min_capacity=int(p.min_capacity), n_unique_pairs=int(p.n_unique_pairs), lookup_slots=t["lookup_slots"][:N],
+                prefetch_ids=t["prefetch_ids"], prefetch_slots=t["prefetch_slots"], evict_ids=t["evict_ids"],
+                evict_slots=t["evict_slots"], keep_ids=t["keep_ids"], keep_ttl=t["keep_ttl"],
+                prefetch_offsets=h["prefetch_offsets"], evict_offsets=h["evict_offsets"],
+                keep_offsets=h["keep_offsets"], occupancy=h["occupancy"][:n_emit],
+                grouped_slots=t["grouped_slots"][:N] if grouping else None,
+                grouped_lookups=t["grouped_lookups"][:N] if grouping else None,
+                item_starts=t["item_starts"] if grouping else None,
+                item_offsets=h["item_offsets"] if grouping else None,
+                split_starts=t["split_starts"] if grouping else None,
+                split_offsets=h["split_offsets"] if grouping else None)
+    return plan, out
 
 
 # ---------------------------------------------------------------------------------------------------

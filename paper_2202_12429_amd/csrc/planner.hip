@@ -45,19 +45,20 @@ struct PlanScalars {
 
 // ---- 1. keys ---------------------------------------------------------------------------------
 __global__ __launch_bounds__(kBlock) void plan_keys_kernel(const int64_t* __restrict__ ids,
-                                                           const int64_t* __restrict__ iter_off, int T, int64_t N,
-                                                           int64_t R, int ib, uint64_t* __restrict__ keys,
+                                                           const int64_t* __restrict__ iter_off, int T, int64_t first,
+                                                           int64_t N, int64_t R, int ib, uint64_t* __restrict__ keys,
                                                            uint32_t* __restrict__ pos, PlanScalars* sc) {
-    const int64_t p = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    // positions [first, N) hold the lookups (first > 0 when a chunk's carried residents sit in front of them)
+    const int64_t p = first + (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (p >= N) return;
-    int64_t g = ids[p];
+    int64_t g = ids[p - first];
     if (g < 0 || g >= R) {
         atomicOr(&sc->error_flags, 1u);
         g = 0;
     }
     // batch of position p: iter_off[lo] <= p < iter_off[lo + 1].  The search starts from the batch of the workgroup's
     // first position (same for all its lanes), and nearly always ends there.
-    const int64_t p_first = (int64_t)blockIdx.x * kBlock;
+    const int64_t p_first = first + (int64_t)blockIdx.x * kBlock;
     int lo = 0, hi = T;
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
@@ -72,6 +73,22 @@ __global__ __launch_bounds__(kBlock) void plan_keys_kernel(const int64_t* __rest
     }
     keys[p] = ((uint64_t)g << ib) | (uint64_t)lo;
     pos[p] = (uint32_t)p;
+}
+
+// Chunked planning: the rows resident at the chunk boundary form a batch 0 of their own in front of the chunk's
+// batches (which then count from 1), so that everything downstream sees them as rows fetched before the chunk.
+__global__ __launch_bounds__(kBlock) void plan_resident_keys_kernel(const int64_t* __restrict__ resident_ids, int64_t R0,
+                                                                    int64_t R, int ib, uint64_t* __restrict__ keys,
+                                                                    uint32_t* __restrict__ pos, PlanScalars* sc) {
+    const int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (r >= R0) return;
+    int64_t g = resident_ids[r];
+    if (g < 0 || g >= R) {
+        atomicOr(&sc->error_flags, 1u);
+        g = 0;
+    }
+    keys[r] = (uint64_t)g << ib;
+    pos[r] = (uint32_t)r;
 }
 
 // ---- 2. unique pairs -------------------------------------------------------------------------
@@ -104,7 +121,8 @@ __device__ __forceinline__ uint32_t pair_gap(const uint64_t* ukey, uint32_t q, u
 __global__ __launch_bounds__(kBlock) void plan_hist_kernel(const uint64_t* __restrict__ ukey, uint32_t M, int ib, int T,
                                                            int Lcap, int lds_gaps, uint32_t per_block,
                                                            uint32_t* __restrict__ H, uint32_t* __restrict__ ucount,
-                                                           uint32_t* __restrict__ first_use) {
+                                                           uint32_t* __restrict__ first_use, int chunk,
+                                                           uint32_t* __restrict__ V) {
     extern __shared__ uint32_t lds[];   // [T] unique counts, [T] first uses, then [lds_gaps][T] histogram rows
     uint32_t* lds_u = lds;
     uint32_t* lds_f = lds + T;
@@ -120,6 +138,10 @@ __global__ __launch_bounds__(kBlock) void plan_hist_kernel(const uint64_t* __res
         atomicAdd(&lds_u[i], 1u);
         if (q == 0 || (ukey[q - 1] >> ib) != (ukey[q] >> ib)) atomicAdd(&lds_f[i], 1u);   // the id's first batch
         const uint32_t gap = pair_gap(ukey, (uint32_t)q, M, ib, imask);
+        if (chunk && i == 0) {      // a carried resident stays until its next use, whatever the lookahead
+            atomicAdd(&V[gap == kGapInf ? (uint32_t)T : gap], 1u);
+            continue;
+        }
         if (gap >= 2u && gap < (uint32_t)Lcap) {
             if (gap < 2u + (uint32_t)lds_gaps) atomicAdd(&lds_h[(gap - 2u) * T + i], 1u);
             else atomicAdd(&H[(size_t)gap * T + i], 1u);
@@ -146,6 +168,18 @@ __global__ void plan_occ_prefix_kernel(uint32_t* H, int T, int Lcap) {
     }
 }
 
+// Carried residents not yet used again at batch j: vcover[j] = residents - (those whose next use is batch <= j);
+// batch 0 holds them as its own rows.  One thread.
+__global__ void plan_vcover_kernel(const uint32_t* __restrict__ V, uint32_t R0, int T, uint32_t* __restrict__ vcover) {
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    uint32_t run = R0;
+    vcover[0] = 0;
+    for (int j = 1; j < T; ++j) {
+        run -= V[j];
+        vcover[j] = run;
+    }
+}
+
 // rows resident but unused at batch j because of pairs with exactly this gap: batches i in (j - gap, j)
 __device__ __forceinline__ uint32_t covering(const uint32_t* Hc, int T, int gap, int j) {
     if (j < 1) return 0;
@@ -158,11 +192,13 @@ __device__ __forceinline__ uint32_t covering(const uint32_t* Hc, int T, int gap,
 // peak[L'] = max_j occupancy(j, L') for L' = 1..Lcap.  One workgroup per batch j: occupancy(j, L') is the unique
 // count of j plus the prefix sum over gap < L' of covering(gap, j), taken with a workgroup scan over the gaps.
 __global__ __launch_bounds__(kBlock) void plan_occ_peak_kernel(const uint32_t* __restrict__ Hc,
-                                                               const uint32_t* __restrict__ ucount, int T, int Lcap,
-                                                               uint32_t* __restrict__ peak) {
+                                                               const uint32_t* __restrict__ ucount,
+                                                               const uint32_t* __restrict__ vcover, int j_first,
+                                                               int j_last, int T, int Lcap, uint32_t* __restrict__ peak) {
     __shared__ uint32_t wave_tot[kBlock / kWave];
     const int j = blockIdx.x;
-    uint32_t carry = ucount[j];
+    if (j < j_first || j > j_last) return;             // a chunk's peak is taken over the batches it emits
+    uint32_t carry = ucount[j] + (vcover ? vcover[j] : 0u);
     if (threadIdx.x == 0) {
         atomicMax(&peak[1], carry);
         if (Lcap >= 2) atomicMax(&peak[2], carry);       // L' = 2 keeps gap 1 only: nothing is resident unused
@@ -180,7 +216,7 @@ __global__ __launch_bounds__(kBlock) void plan_occ_peak_kernel(const uint32_t* _
 // one thread: pick L_eff, exclusive scan of the per-batch unique counts
 __global__ void plan_choose_kernel(const uint32_t* __restrict__ peak, const uint32_t* __restrict__ ucount,
                                    const uint32_t* __restrict__ first_use, int T, int Lcap, int lookahead, int64_t budget,
-                                   PlanScalars* sc, uint32_t* __restrict__ pair_off) {
+                                   int carried_batches, PlanScalars* sc, uint32_t* __restrict__ pair_off) {
     if (blockIdx.x != 0 || threadIdx.x != 0) return;
     int requested = lookahead, top = Lcap;
     if (lookahead == 0) {
@@ -193,8 +229,9 @@ __global__ void plan_choose_kernel(const uint32_t* __restrict__ peak, const uint
             if (held > budget) break;
             k = i + 1;
         }
-        requested = k;
-        top = k < Lcap ? k : Lcap;
+        requested = k - carried_batches;             // a chunk's batch 0 holds the carried residents, not lookups
+        if (requested < 0) requested = 0;
+        top = requested < Lcap ? requested : Lcap;
     }
     int sel = 0;
     for (int Lp = top; Lp >= 1; --Lp)
@@ -212,11 +249,12 @@ __global__ void plan_choose_kernel(const uint32_t* __restrict__ peak, const uint
     pair_off[T] = run;
 }
 
-__global__ void plan_occ_final_kernel(const uint32_t* __restrict__ Hc, const uint32_t* __restrict__ ucount, int T,
-                                      const PlanScalars* sc, int64_t* __restrict__ occ) {
+__global__ void plan_occ_final_kernel(const uint32_t* __restrict__ Hc, const uint32_t* __restrict__ ucount,
+                                      const uint32_t* __restrict__ vcover, int T, const PlanScalars* sc,
+                                      int64_t* __restrict__ occ) {
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
     if (j >= T) return;
-    uint32_t run = ucount[j];
+    uint32_t run = ucount[j] + (vcover ? vcover[j] : 0u);
     for (int gap = 2; gap < sc->L_sel; ++gap) run += covering(Hc, T, gap, j);
     occ[j] = run;
 }
@@ -238,7 +276,7 @@ struct PairRecord {
 };
 
 __global__ __launch_bounds__(kBlock) void plan_flags_kernel(const uint64_t* __restrict__ ukey, uint32_t M, int ib,
-                                                            const PlanScalars* sc, uint64_t* __restrict__ rec,
+                                                            const PlanScalars* sc, int chunk, uint64_t* __restrict__ rec,
                                                             uint32_t* __restrict__ val2) {
     const uint32_t q = blockIdx.x * kBlock + threadIdx.x;
     if (q >= M) return;
@@ -248,14 +286,15 @@ __global__ __launch_bounds__(kBlock) void plan_flags_kernel(const uint64_t* __re
     const uint64_t g = k >> ib;
     const int64_t i = (int64_t)(k & imask);
     const uint32_t gap = pair_gap(ukey, q, M, ib, imask);
-    const bool keep = (int64_t)gap < Leff;
+    const bool carried = chunk && i == 0;              // resident since before the chunk: stays until its next use
+    const bool keep = carried || (int64_t)gap < Leff;
     bool miss = true;
     if (q > 0) {
         const uint64_t kp = ukey[q - 1];
-        if ((kp >> ib) == g && i - (int64_t)(kp & imask) < Leff) miss = false;
+        if ((kp >> ib) == g && ((chunk && (kp & imask) == 0) || i - (int64_t)(kp & imask) < Leff)) miss = false;
     }
     uint32_t t = (uint32_t)i;
-    if (keep) {
+    if (keep && !carried) {
         // last pair of this id whose batch is <= i + L_eff - 1: it lies within L_eff - 1 pairs of q
         const int64_t last_iter = i + Leff - 1 < (int64_t)imask ? i + Leff - 1 : (int64_t)imask;
         const uint64_t bound = (g << ib) | (uint64_t)last_iter;
@@ -305,6 +344,7 @@ struct ListOut {
     uint32_t* evict_pair;
     int64_t* prefetch_off;   // device copies of the CSR offsets, [T+1], pre-filled with -1
     int64_t* evict_off;
+    int32_t ttl_shift;       // 1 in chunk mode: the chunk's batches count from 1 inside the planner
     __device__ __forceinline__ void operator()(int64_t k, uint64_t exc, uint64_t) const {
         const PairRecord pr{ib};
         const uint64_t r = srec[k];
@@ -314,7 +354,7 @@ struct ListOut {
         const uint32_t x = (uint32_t)exc, e = (uint32_t)(exc >> 32);
         const uint64_t f = pr.flags(r);
         keep_ids[k] = g;
-        keep_ttl[k] = (int32_t)pr.ttl(r);
+        keep_ttl[k] = (int32_t)pr.ttl(r) - ttl_shift;
         if (f & kMiss) {
             prefetch_ids[x] = g;
             missord[q] = x;
@@ -360,20 +400,26 @@ __global__ __launch_bounds__(kBlock) void plan_ring_jump_kernel(const uint64_t* 
 __global__ __launch_bounds__(kBlock) void plan_pair_slots_kernel(uint32_t M, const uint32_t* __restrict__ chain,
                                                                  const uint32_t* __restrict__ missord,
                                                                  const uint32_t* __restrict__ par,
+                                                                 const int32_t* __restrict__ ring0,
                                                                  int32_t* __restrict__ slot_of_pair) {
+    // par resolves every miss to a ring position below C; ring0 (NULL: the identity) is what that position held
+    // when planning started
     const uint32_t q = blockIdx.x * kBlock + threadIdx.x;
-    if (q < M) slot_of_pair[q] = (int32_t)par[missord[chain[q]]];
+    if (q >= M) return;
+    const uint32_t p0 = par[missord[chain[q]]];
+    slot_of_pair[q] = ring0 ? ring0[p0] : (int32_t)p0;
 }
 
 __global__ __launch_bounds__(kBlock) void plan_list_slots_kernel(const uint64_t* __restrict__ totals,
                                                                  const uint32_t* __restrict__ par,
                                                                  const uint32_t* __restrict__ evict_pair,
                                                                  const int32_t* __restrict__ slot_of_pair,
+                                                                 const int32_t* __restrict__ ring0,
                                                                  int32_t* __restrict__ prefetch_slots,
                                                                  int32_t* __restrict__ evict_slots) {
     const uint32_t n_miss = (uint32_t)*totals, n_evict = (uint32_t)(*totals >> 32);
     const uint32_t x = blockIdx.x * kBlock + threadIdx.x;
-    if (x < n_miss) prefetch_slots[x] = (int32_t)par[x];
+    if (x < n_miss) prefetch_slots[x] = ring0 ? ring0[par[x]] : (int32_t)par[x];
     if (x < n_evict) evict_slots[x] = slot_of_pair[evict_pair[x]];
 }
 
@@ -387,12 +433,13 @@ __device__ __forceinline__ int64_t xcd_contiguous_block(uint32_t per_xcd) {
 }
 inline uint32_t blocks_per_xcd(int64_t n) { return (uint32_t)ceil_div(n > 0 ? ceil_div(n, kBlock) : 1, (int64_t)kXcds); }
 
-__global__ __launch_bounds__(kBlock) void plan_lookup_slots_kernel(int64_t N, const uint32_t* __restrict__ pos,
+__global__ __launch_bounds__(kBlock) void plan_lookup_slots_kernel(int64_t N, uint32_t first,
+                                                                   const uint32_t* __restrict__ pos,
                                                                    const uint32_t* __restrict__ uq,
                                                                    const int32_t* __restrict__ slot_of_pair,
                                                                    int32_t* __restrict__ lookup_slots) {
     const int64_t p = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (p < N) lookup_slots[pos[p]] = slot_of_pair[uq[p]];
+    if (p < N && pos[p] >= first) lookup_slots[pos[p] - first] = slot_of_pair[uq[p]];   // below first: carried rows
 }
 
 // ---- 8. lookups of every batch grouped by row (optional) ---------------------------------------
@@ -416,7 +463,9 @@ struct ItemFlagIn {
     const K* gkeys;
     const int64_t* iter_off;
     int ib;
+    int64_t first;          // entries below `first` are a chunk's carried residents, not lookups
     __device__ __forceinline__ uint64_t operator()(int64_t p) const {
+        if (p < first) return 0;
         const K k = gkeys[p];
         const uint32_t i = (uint32_t)(k & ((K(1) << ib) - 1));
         const int64_t base = iter_off[i];
@@ -443,12 +492,14 @@ struct GroupOut {
     uint32_t* split_starts;
     int64_t* item_off;     // device copies of the CSR offsets, [T+1] each, pre-filled with -1
     int64_t* split_off;
+    int64_t first;         // entries below `first` are a chunk's carried residents: skipped, outputs start at `first`
     __device__ __forceinline__ void operator()(int64_t p, uint64_t exc, uint64_t inc) const {
+        if (p < first) return;
         const K k = gkeys[p];
         const uint32_t i = (uint32_t)(k & ((K(1) << ib) - 1));
         const int64_t base = iter_off[i];
-        grouped_slots[p] = (int32_t)(k >> ib);
-        grouped_lookups[p] = (int32_t)((int64_t)gpos[p] - base);
+        grouped_slots[p - first] = (int32_t)(k >> ib);
+        grouped_lookups[p - first] = (int32_t)((int64_t)gpos[p] - base);
         if ((uint32_t)inc != (uint32_t)exc) {
             const bool first_of_row = p == base || (gkeys[p - 1] >> ib) != (k >> ib);
             item_starts[(uint32_t)exc] = (uint32_t)(p - base) | (first_of_row ? 0x80000000u : 0u);
@@ -465,17 +516,65 @@ struct GroupOut {
 // their batch's stretch of the map (a few MB at most).
 template <typename K>
 __global__ __launch_bounds__(kBlock) void plan_lookup_slots_grouped_kernel(int64_t N, uint32_t per_xcd, int ib,
+                                                                           int64_t first,
                                                                            const uint32_t* __restrict__ gpos,
                                                                            const K* __restrict__ gkeys,
                                                                            int32_t* __restrict__ lookup_slots) {
     const int64_t p = xcd_contiguous_block(per_xcd) * kBlock + threadIdx.x;
-    if (p < N) lookup_slots[gpos[p]] = (int32_t)(gkeys[p] >> ib);
+    if (p >= first && p < N) lookup_slots[gpos[p] - first] = (int32_t)(gkeys[p] >> ib);
 }
 
 template <typename T>
 __global__ __launch_bounds__(kBlock) void fill_kernel(T* p, int64_t n, T v) {
     const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (i < n) p[i] = v;
+}
+
+// ---- 9. carried state of chunked planning ------------------------------------------------------
+// Rows resident after batch e: for every id, its last pair with batch <= e, if that pair keeps the row (a carried
+// resident not used up to e, or a gap to the next use below L_eff).  Pairs are in (id, batch) order, so the output is
+// ascending in id.
+struct ResidentFlagIn {
+    const uint64_t* ukey;
+    uint32_t M;
+    int ib;
+    uint32_t e;
+    const PlanScalars* sc;
+    __device__ __forceinline__ uint32_t operator()(int64_t q) const {
+        const uint64_t imask = (uint64_t(1) << ib) - 1;
+        const uint64_t k = ukey[q];
+        const uint32_t i = (uint32_t)(k & imask);
+        if (i > e) return 0u;
+        const uint32_t gap = pair_gap(ukey, (uint32_t)q, M, ib, imask);
+        const bool last_seen = gap == kGapInf || i + gap > e;            // no later use at or before batch e
+        const bool kept = i == 0 || (int64_t)gap < (int64_t)sc->L_eff;
+        return last_seen && kept ? 1u : 0u;
+    }
+};
+struct ResidentOut {
+    const uint64_t* ukey;
+    const int32_t* slot_of_pair;
+    int ib;
+    int64_t* resident_ids;
+    int32_t* ring;
+    __device__ __forceinline__ void operator()(int64_t q, uint32_t exc, uint32_t inc) const {
+        if (inc != exc) {
+            resident_ids[exc] = (int64_t)(ukey[q] >> ib);
+            ring[exc] = slot_of_pair[q];
+        }
+    }
+};
+
+// The free slots in FIFO order behind the residents: ring positions [n_miss, C + n_evict) as of batch e.
+__global__ __launch_bounds__(kBlock) void plan_state_queue_kernel(int64_t n_miss, int64_t n_evict, int64_t C,
+                                                                  const int32_t* __restrict__ ring0,
+                                                                  const int32_t* __restrict__ evict_slots,
+                                                                  int64_t n_resident, int32_t* __restrict__ ring_out) {
+    const int64_t x = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int64_t pos = n_miss + x;
+    if (pos >= C + n_evict) return;
+    const int32_t slot = pos < C ? (ring0 ? ring0[pos] : (int32_t)pos) : evict_slots[pos - C];
+    ring_out[n_resident + x] = slot;
 }
 
 // ---- workspace layout ------------------------------------------------------------------------
@@ -485,7 +584,7 @@ struct PlanWorkspace {
     uint32_t* sort_temp;
     uint32_t* scan_partials32;   // head scan, chain scan
     uint64_t* scan_partials64;   // list scan
-    uint32_t *H, *ucount, *first_use, *peak, *pair_off;
+    uint32_t *H, *ucount, *first_use, *peak, *pair_off, *V, *vcover;
     PlanScalars* scalars;
     int64_t *occ, *prefetch_off, *evict_off, *iter_off;
     uint64_t *rec_a, *rec_b;
@@ -512,6 +611,8 @@ PlanWorkspace carve_plan(void* base, size_t cap, int64_t N, int T, int Lcap, boo
     w.H = c.take<uint32_t>((size_t)(Lcap + 1) * T);
     w.ucount = c.take<uint32_t>(T);
     w.first_use = c.take<uint32_t>(T);
+    w.V = c.take<uint32_t>(T + 1);
+    w.vcover = c.take<uint32_t>(T + 1);
     w.peak = c.take<uint32_t>(Lcap + 2);
     w.pair_off = c.take<uint32_t>(T + 1);
     w.scalars = c.take<PlanScalars>(1);
@@ -553,6 +654,7 @@ inline dim3 grid_for(int64_t n) { return dim3((unsigned)(n > 0 ? ceil_div(n, kBl
 // buffer: every element is read and written by the same lane), kb is the other half of the ping-pong.
 struct GroupingPass {
     int64_t N;
+    int64_t first;        // carried residents in front of the lookups (0 outside chunk mode)
     int T, ib;
     const uint64_t* skeys;
     uint32_t* spos;
@@ -569,13 +671,13 @@ struct GroupingPass {
         const K* gkeys = in_b ? kb : ka;
         const uint32_t* gpos = in_b ? w->pos_c : spos;
         BP_TRY((device_scan<uint64_t, AddOp, ItemFlagIn<K>, GroupOut<K>>(
-            ItemFlagIn<K>{gkeys, w->iter_off, ib},
+            ItemFlagIn<K>{gkeys, w->iter_off, ib, first},
             GroupOut<K>{gkeys, gpos, w->iter_off, ib, plan->grouped_slots, plan->grouped_lookups, plan->item_starts,
-                        plan->split_starts, w->item_off, w->split_off},
+                        plan->split_starts, w->item_off, w->split_off, first},
             N, w->scan_partials64, AddOp(), uint64_t(0), stream)));
         const uint32_t per_xcd = blocks_per_xcd(N);
         BP_LAUNCH(K_PLAN_SLOTS, plan_lookup_slots_grouped_kernel<K>, dim3(per_xcd * kXcds), dim3(kBlock), 0, stream, N,
-                  per_xcd, ib, gpos, gkeys, plan->lookup_slots);
+                  per_xcd, ib, first, gpos, gkeys, plan->lookup_slots);
         return BP_OK;
     }
 };
@@ -594,26 +696,56 @@ BP_EXPORT int bp_oracle_plan_workspace_bytes(const bp_config* cfg, int64_t n_loo
     return BP_OK;
 }
 
-BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offsets, int32_t n_iters,
-                              bp_plan* plan, void* workspace, size_t workspace_bytes, void* stream_) {
-    hipStream_t stream = (hipStream_t)stream_;
+namespace bp {
+namespace {
+
+struct ChunkArgs {              // chunked planning: emit the first n_emit batches, carry the cache state across
+    int n_emit;
+    const bp_plan_state* in;    // NULL: the cache is empty and the ring holds slots 0..C-1 in order
+    bp_plan_state* out;
+};
+
+__global__ __launch_bounds__(kBlock) void iota_slots_kernel(int32_t* p, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i < n) p[i] = (int32_t)i;
+}
+
+// The planner proper.  T_in batches of lookups; in chunk mode (ch != NULL) the rows resident at the chunk boundary
+// are put in front of them as a batch 0 of their own, the lists of the first n_emit real batches are reported, and
+// the state after the last of them is written out.
+int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offsets, int32_t T_in, bp_plan* plan,
+              void* workspace, size_t workspace_bytes, hipStream_t stream, const ChunkArgs* ch) {
     if (!plan || !iter_offsets) return fail(BP_ERR_INVALID_ARG, "plan or iter_offsets is NULL");
-    const int T = n_iters;
-    if (T < 1) return fail(BP_ERR_UNSUPPORTED, "n_iters %d < 1", T);
-    const int64_t N = iter_offsets[T];
+    if (T_in < 1) return fail(BP_ERR_UNSUPPORTED, "n_iters %d < 1", T_in);
+    BP_TRY(check_config(cfg));
+    const bool chunk = ch != nullptr;
+    const int shift = chunk ? 1 : 0;
+    const int T = T_in + shift;                         // batches as the planner counts them
+    const int n_emit = chunk ? ch->n_emit : T_in;
+    const int64_t C = cfg->capacity;
+    const int64_t R0 = chunk && ch->in ? ch->in->n_resident : 0;
+    if (chunk) {
+        if (n_emit < 1 || n_emit > T_in) return fail(BP_ERR_INVALID_ARG, "n_emit %d outside [1, n_iters]", n_emit);
+        if (!ch->out || !ch->out->resident_ids || !ch->out->ring) return fail(BP_ERR_INVALID_ARG, "the output state is NULL");
+        if (R0 < 0 || R0 > C) return fail(BP_ERR_INVALID_ARG, "n_resident %lld outside [0, capacity]", (long long)R0);
+        if (ch->in && (!ch->in->ring || (R0 && !ch->in->resident_ids))) return fail(BP_ERR_INVALID_ARG, "the input state is NULL");
+        if (ch->in && (ch->in->ring == ch->out->ring || (R0 && ch->in->resident_ids == ch->out->resident_ids)))
+            return fail(BP_ERR_INVALID_ARG, "input and output state must be different buffers");
+    }
+    const int64_t N_real = iter_offsets[T_in];
+    const int64_t N = N_real + R0;                      // carried residents come first, then the lookups
     BP_TRY(check_plan_args(cfg, N, T));
     if (iter_offsets[0] != 0) return fail(BP_ERR_INVALID_ARG, "iter_offsets[0] != 0");
-    for (int i = 0; i < T; ++i)
+    for (int i = 0; i < T_in; ++i)
         if (iter_offsets[i + 1] < iter_offsets[i]) return fail(BP_ERR_INVALID_ARG, "iter_offsets decreases at %d", i);
     if (!plan->prefetch_offsets || !plan->evict_offsets || !plan->keep_offsets || !plan->occupancy)
         return fail(BP_ERR_INVALID_ARG, "a host output array of the plan is NULL");
-    if (N > 0 && (!ids || !plan->lookup_slots || !plan->prefetch_ids || !plan->prefetch_slots || !plan->evict_ids ||
-                  !plan->evict_slots || !plan->keep_ids || !plan->keep_ttl))
+    if (N > 0 && ((N_real > 0 && (!ids || !plan->lookup_slots)) || !plan->prefetch_ids || !plan->prefetch_slots ||
+                  !plan->evict_ids || !plan->evict_slots || !plan->keep_ids || !plan->keep_ttl))
         return fail(BP_ERR_INVALID_ARG, "a device array of the plan is NULL");
     if (!workspace || ((uintptr_t)workspace & 255)) return fail(BP_ERR_INVALID_ARG, "workspace NULL or not 256-byte aligned");
 
     const int Lcap = cfg->lookahead > 0 && cfg->lookahead < T ? cfg->lookahead : T;   // 0: not configured, any window
-    const int64_t C = cfg->capacity;
     const bool grouping = plan->grouped_slots || plan->grouped_lookups || plan->item_starts || plan->item_offsets ||
                           plan->split_starts || plan->split_offsets;
     if (grouping && !(plan->grouped_slots && plan->grouped_lookups && plan->item_starts && plan->item_offsets &&
@@ -622,6 +754,7 @@ BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int
     PlanWorkspace w = carve_plan(workspace, workspace_bytes, N, T, Lcap, grouping);
     if (w.bytes > workspace_bytes)
         return fail(BP_ERR_WORKSPACE_TOO_SMALL, "workspace %zu < required %zu bytes", workspace_bytes, w.bytes);
+    const int32_t* ring0 = chunk && ch->in ? ch->in->ring : nullptr;
 
     plan->L_eff = 0;
     plan->L_requested = cfg->lookahead;
@@ -629,21 +762,34 @@ BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int
     plan->min_capacity = 0;
     plan->n_unique_pairs = 0;
     if (N == 0) {   // nothing is ever looked up: empty lists, the full requested lookahead is feasible
-        for (int i = 0; i <= T; ++i) plan->prefetch_offsets[i] = plan->evict_offsets[i] = plan->keep_offsets[i] = 0;
-        for (int i = 0; i < T; ++i) plan->occupancy[i] = 0;
-        plan->L_eff = plan->L_requested = cfg->lookahead ? cfg->lookahead : T;
+        for (int i = 0; i <= n_emit; ++i) plan->prefetch_offsets[i] = plan->evict_offsets[i] = plan->keep_offsets[i] = 0;
+        for (int i = 0; i < n_emit; ++i) plan->occupancy[i] = 0;
+        plan->L_eff = plan->L_requested = cfg->lookahead ? cfg->lookahead : T_in;
         if (grouping)
-            for (int i = 0; i <= T; ++i) plan->item_offsets[i] = plan->split_offsets[i] = 0;
+            for (int i = 0; i <= n_emit; ++i) plan->item_offsets[i] = plan->split_offsets[i] = 0;
+        if (chunk) {                                      // the ring passes through unchanged
+            ch->out->n_resident = 0;
+            if (ring0) BP_HIP(hipMemcpyAsync(ch->out->ring, ring0, sizeof(int32_t) * C, hipMemcpyDeviceToDevice, stream));
+            else BP_LAUNCH(K_FILL, iota_slots_kernel, grid_for(C), dim3(kBlock), 0, stream, ch->out->ring, C);
+            BP_HIP(hipStreamSynchronize(stream));
+        }
         return BP_OK;
     }
 
     const int ib = bits_for(T), gb = bits_for(cfg->total_rows);
+    std::vector<int64_t> voff((size_t)T + 1);            // batch offsets as the planner counts them
+    voff[0] = 0;
+    for (int i = 0; i <= T_in; ++i) voff[(size_t)i + shift] = R0 + iter_offsets[i];
 
     // ---- 1. keys + sort
-    BP_HIP(hipMemcpyAsync(w.iter_off, iter_offsets, sizeof(int64_t) * (T + 1), hipMemcpyHostToDevice, stream));
+    BP_HIP(hipMemcpyAsync(w.iter_off, voff.data(), sizeof(int64_t) * (T + 1), hipMemcpyHostToDevice, stream));
     BP_HIP(hipMemsetAsync(w.scalars, 0, sizeof(PlanScalars), stream));
-    BP_LAUNCH(K_PLAN_KEYS, plan_keys_kernel, grid_for(N), dim3(kBlock), 0, stream, ids, (const int64_t*)w.iter_off, T, N,
-              cfg->total_rows, ib, w.keys_a, w.pos_a, w.scalars);
+    if (R0)
+        BP_LAUNCH(K_PLAN_KEYS, plan_resident_keys_kernel, grid_for(R0), dim3(kBlock), 0, stream,
+                  (const int64_t*)ch->in->resident_ids, R0, cfg->total_rows, ib, w.keys_a, w.pos_a, w.scalars);
+    if (N_real)
+        BP_LAUNCH(K_PLAN_KEYS, plan_keys_kernel, grid_for(N_real), dim3(kBlock), 0, stream, ids, (const int64_t*)w.iter_off, T,
+                  R0, N, cfg->total_rows, ib, w.keys_a, w.pos_a, w.scalars);
     bool in_b = false;
     // the lookups arrive batch by batch, so a stable sort on the id bits alone leaves every id's keys in batch order
     BP_TRY((radix_sort_pairs<uint64_t, kPlanSortIPT>(w.keys_a, w.keys_b, w.pos_a, w.pos_b, N, ib, ib + gb, w.sort_temp,
@@ -672,6 +818,7 @@ BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int
     BP_HIP(hipMemsetAsync(w.ucount, 0, sizeof(uint32_t) * T, stream));
     BP_HIP(hipMemsetAsync(w.first_use, 0, sizeof(uint32_t) * T, stream));
     BP_HIP(hipMemsetAsync(w.peak, 0, sizeof(uint32_t) * (Lcap + 2), stream));
+    if (chunk) BP_HIP(hipMemsetAsync(w.V, 0, sizeof(uint32_t) * (T + 1), stream));
     {
         int lds_gaps = (int)((48 * 1024 / 4 - 2 * T) / T);              // histogram rows that fit in 48 KiB next to 2 x [T]
         if (lds_gaps > Lcap - 2) lds_gaps = Lcap - 2;
@@ -681,30 +828,38 @@ BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int
         const uint32_t per_block = (uint32_t)ceil_div(M, blocks);
         BP_LAUNCH(K_PLAN_HIST, plan_hist_kernel, dim3((unsigned)blocks), dim3(kBlock),
                   sizeof(uint32_t) * (size_t)(2 + lds_gaps) * T, stream, (const uint64_t*)ukey, M, ib, T, Lcap, lds_gaps,
-                  per_block, w.H, w.ucount, w.first_use);
+                  per_block, w.H, w.ucount, w.first_use, (int)chunk, w.V);
     }
+    const uint32_t* vcover = nullptr;
+    if (chunk) {
+        BP_LAUNCH(K_PLAN_OCC, plan_vcover_kernel, dim3(1), dim3(64), 0, stream, (const uint32_t*)w.V, (uint32_t)R0, T, w.vcover);
+        vcover = w.vcover;
+    }
+    const int j_first = shift, j_last = shift + n_emit - 1;      // the batches whose occupancy counts
     BP_LAUNCH(K_PLAN_OCC, plan_occ_prefix_kernel, grid_for(Lcap), dim3(kBlock), 0, stream, w.H, T, Lcap);
     BP_LAUNCH(K_PLAN_OCC, plan_occ_peak_kernel, dim3(T), dim3(kBlock), 0, stream, (const uint32_t*)w.H,
-              (const uint32_t*)w.ucount, T, Lcap, w.peak);
+              (const uint32_t*)w.ucount, vcover, j_first, j_last, T, Lcap, w.peak);
     BP_LAUNCH(K_PLAN_OCC, plan_choose_kernel, dim3(1), dim3(64), 0, stream, (const uint32_t*)w.peak,
-              (const uint32_t*)w.ucount, (const uint32_t*)w.first_use, T, Lcap, cfg->lookahead, C - cfg->reserve,
+              (const uint32_t*)w.ucount, (const uint32_t*)w.first_use, T, Lcap, cfg->lookahead, C - cfg->reserve, shift,
               w.scalars, w.pair_off);
     BP_LAUNCH(K_PLAN_OCC, plan_occ_final_kernel, grid_for(T), dim3(kBlock), 0, stream, (const uint32_t*)w.H,
-              (const uint32_t*)w.ucount, T, (const PlanScalars*)w.scalars, w.occ);
+              (const uint32_t*)w.ucount, vcover, T, (const PlanScalars*)w.scalars, w.occ);
+    std::vector<int64_t> hocc((size_t)T);
     BP_HIP(hipMemcpyAsync(&hs, w.scalars, sizeof(PlanScalars), hipMemcpyDeviceToHost, stream));
-    BP_HIP(hipMemcpyAsync(plan->occupancy, w.occ, sizeof(int64_t) * T, hipMemcpyDeviceToHost, stream));
+    BP_HIP(hipMemcpyAsync(hocc.data(), w.occ, sizeof(int64_t) * T, hipMemcpyDeviceToHost, stream));
     BP_HIP(hipStreamSynchronize(stream));
+    for (int i = 0; i < n_emit; ++i) plan->occupancy[i] = hocc[(size_t)i + shift];
     plan->min_capacity = hs.min_capacity;
     plan->L_requested = hs.L_requested;
     if (hs.L_eff < 1)
-        return fail(BP_ERR_CAPACITY, "capacity %lld - reserve %lld < %lld unique rows of one batch", (long long)C,
+        return fail(BP_ERR_CAPACITY, "capacity %lld - reserve %lld < %lld rows one batch needs in the cache", (long long)C,
                     (long long)cfg->reserve, (long long)hs.min_capacity);
     plan->L_eff = hs.L_eff;
     plan->peak_occupancy = hs.peak;
 
     // ---- 4. flags, TTL, fetching pair of every pair
     BP_LAUNCH(K_PLAN_FLAGS, plan_flags_kernel, grid_for(M), dim3(kBlock), 0, stream, (const uint64_t*)ukey, M, ib,
-              (const PlanScalars*)w.scalars, w.rec_a, w.val2_a);
+              (const PlanScalars*)w.scalars, (int)chunk, w.rec_a, w.val2_a);
     BP_TRY((device_scan<uint32_t, MaxOp, MissIndexIn, StoreInclusiveU32>(MissIndexIn{w.rec_a, ib}, StoreInclusiveU32{w.chain},
                                                                          M, w.scan_partials32, MaxOp(), 0u, stream)));
 
@@ -721,7 +876,7 @@ BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int
     BP_TRY((device_scan<uint64_t, AddOp, ListCountIn, ListOut>(
         ListCountIn{srec, ib},
         ListOut{srec, ord, w.pair_off, ib, plan->keep_ids, plan->keep_ttl, plan->prefetch_ids, plan->evict_ids, w.missord,
-                w.evict_pair, w.prefetch_off, w.evict_off},
+                w.evict_pair, w.prefetch_off, w.evict_off, shift},
         M, w.scan_partials64, AddOp(), uint64_t(0), stream)));
     const uint64_t* totals = w.scan_partials64 + scan_num_tiles(M);
 
@@ -734,11 +889,12 @@ BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int
 
     // ---- 7. slots
     BP_LAUNCH(K_PLAN_SLOTS, plan_pair_slots_kernel, grid_for(M), dim3(kBlock), 0, stream, M, (const uint32_t*)w.chain,
-              (const uint32_t*)w.missord, (const uint32_t*)w.par, w.slot_of_pair);
+              (const uint32_t*)w.missord, (const uint32_t*)w.par, ring0, w.slot_of_pair);
     BP_LAUNCH(K_PLAN_SLOTS, plan_list_slots_kernel, grid_for(M), dim3(kBlock), 0, stream, totals, (const uint32_t*)w.par,
-              (const uint32_t*)w.evict_pair, (const int32_t*)w.slot_of_pair, plan->prefetch_slots, plan->evict_slots);
-    if (!grouping)      // with grouping the slot map is written from the batch-grouped order (step 8)
-        BP_LAUNCH(K_PLAN_SLOTS, plan_lookup_slots_kernel, grid_for(N), dim3(kBlock), 0, stream, N, spos,
+              (const uint32_t*)w.evict_pair, (const int32_t*)w.slot_of_pair, ring0, plan->prefetch_slots,
+              plan->evict_slots);
+    if (!grouping && N_real)      // with grouping the slot map is written from the batch-grouped order (step 8)
+        BP_LAUNCH(K_PLAN_SLOTS, plan_lookup_slots_kernel, grid_for(N), dim3(kBlock), 0, stream, N, (uint32_t)R0, spos,
                   (const uint32_t*)uq, (const int32_t*)w.slot_of_pair, plan->lookup_slots);
 
     uint64_t htot = 0;     // miss / evict totals: fetched now, the grouping scan below reuses the partials buffer
@@ -746,44 +902,107 @@ BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int
 
     // ---- 8. grouping for the backward pass
     uint64_t n_items_split = 0;
+    std::vector<int64_t> hitem, hsplit;
     if (grouping) {
         BP_LAUNCH(K_FILL, fill_kernel<int64_t>, grid_for(T + 1), dim3(kBlock), 0, stream, w.item_off, (int64_t)(T + 1),
                   (int64_t)-1);
         BP_LAUNCH(K_FILL, fill_kernel<int64_t>, grid_for(T + 1), dim3(kBlock), 0, stream, w.split_off, (int64_t)(T + 1),
                   (int64_t)-1);
-        GroupingPass g{N, T, ib, skeys, const_cast<uint32_t*>(spos), uq, &w, plan, stream};
+        GroupingPass g{N, R0, T, ib, skeys, const_cast<uint32_t*>(spos), uq, &w, plan, stream};
         if (bits_for(C) + ib <= 32)
             BP_TRY(g.run<uint32_t>(reinterpret_cast<uint32_t*>(w.keys_c), reinterpret_cast<uint32_t*>(w.keys_c) + N));
         else
             BP_TRY(g.run<uint64_t>(const_cast<uint64_t*>(skeys), w.keys_c));
+        hitem.resize((size_t)T + 1);
+        hsplit.resize((size_t)T + 1);
         BP_HIP(hipMemcpyAsync(&n_items_split, w.scan_partials64 + scan_num_tiles(N), sizeof(uint64_t), hipMemcpyDeviceToHost,
                               stream));
-        BP_HIP(hipMemcpyAsync(plan->item_offsets, w.item_off, sizeof(int64_t) * (T + 1), hipMemcpyDeviceToHost, stream));
-        BP_HIP(hipMemcpyAsync(plan->split_offsets, w.split_off, sizeof(int64_t) * (T + 1), hipMemcpyDeviceToHost, stream));
+        BP_HIP(hipMemcpyAsync(hitem.data(), w.item_off, sizeof(int64_t) * (T + 1), hipMemcpyDeviceToHost, stream));
+        BP_HIP(hipMemcpyAsync(hsplit.data(), w.split_off, sizeof(int64_t) * (T + 1), hipMemcpyDeviceToHost, stream));
     }
 
-    // ---- CSR offsets to the host
+    // ---- CSR offsets to the host (in chunk mode: of the emitted batches; positions in the device lists, so the
+    // first offset is where the carried residents' own entries end)
     std::vector<uint32_t> hpair((size_t)T + 1);
-    BP_HIP(hipMemcpyAsync(plan->prefetch_offsets, w.prefetch_off, sizeof(int64_t) * (T + 1), hipMemcpyDeviceToHost, stream));
-    BP_HIP(hipMemcpyAsync(plan->evict_offsets, w.evict_off, sizeof(int64_t) * (T + 1), hipMemcpyDeviceToHost, stream));
+    std::vector<int64_t> hpre((size_t)T + 1), hev((size_t)T + 1);
+    BP_HIP(hipMemcpyAsync(hpre.data(), w.prefetch_off, sizeof(int64_t) * (T + 1), hipMemcpyDeviceToHost, stream));
+    BP_HIP(hipMemcpyAsync(hev.data(), w.evict_off, sizeof(int64_t) * (T + 1), hipMemcpyDeviceToHost, stream));
     BP_HIP(hipMemcpyAsync(hpair.data(), w.pair_off, sizeof(uint32_t) * (T + 1), hipMemcpyDeviceToHost, stream));
     BP_HIP(hipStreamSynchronize(stream));
-    for (int i = 0; i <= T; ++i) plan->keep_offsets[i] = (int64_t)hpair[i];
     const int64_t n_miss = (int64_t)(uint32_t)htot, n_evict = (int64_t)(htot >> 32);
-    plan->prefetch_offsets[T] = n_miss;
-    plan->evict_offsets[T] = n_evict;
+    hpre[T] = n_miss;
+    hev[T] = n_evict;
     for (int i = T - 1; i >= 0; --i) {   // batches without lookups own no pair: their lists are empty
-        if (plan->prefetch_offsets[i] < 0) plan->prefetch_offsets[i] = plan->prefetch_offsets[i + 1];
-        if (plan->evict_offsets[i] < 0) plan->evict_offsets[i] = plan->evict_offsets[i + 1];
+        if (hpre[i] < 0) hpre[i] = hpre[i + 1];
+        if (hev[i] < 0) hev[i] = hev[i + 1];
+    }
+    for (int i = 0; i <= n_emit; ++i) {
+        plan->prefetch_offsets[i] = hpre[(size_t)i + shift];
+        plan->evict_offsets[i] = hev[(size_t)i + shift];
+        plan->keep_offsets[i] = (int64_t)hpair[(size_t)i + shift];
     }
     if (grouping) {
-        plan->item_offsets[T] = (int64_t)(uint32_t)n_items_split;
-        plan->split_offsets[T] = (int64_t)(n_items_split >> 32);
+        hitem[T] = (int64_t)(uint32_t)n_items_split;
+        hsplit[T] = (int64_t)(n_items_split >> 32);
         for (int i = T - 1; i >= 0; --i) {
-            if (plan->item_offsets[i] < 0) plan->item_offsets[i] = plan->item_offsets[i + 1];
-            if (plan->split_offsets[i] < 0) plan->split_offsets[i] = plan->split_offsets[i + 1];
+            if (hitem[i] < 0) hitem[i] = hitem[i + 1];
+            if (hsplit[i] < 0) hsplit[i] = hsplit[i + 1];
+        }
+        for (int i = 0; i <= n_emit; ++i) {
+            plan->item_offsets[i] = hitem[(size_t)i + shift];
+            plan->split_offsets[i] = hsplit[(size_t)i + shift];
         }
     }
-    if (n_miss != n_evict) return fail(BP_ERR_HIP, "internal: %lld prefetches but %lld evictions", (long long)n_miss, (long long)n_evict);
+    if (!chunk) {
+        if (n_miss != n_evict) return fail(BP_ERR_HIP, "internal: %lld prefetches but %lld evictions", (long long)n_miss, (long long)n_evict);
+        return BP_OK;
+    }
+
+    // ---- 9. the state after the last emitted batch
+    const uint32_t e = (uint32_t)j_last;
+    const int64_t miss_e = hpre[(size_t)e + 1], evict_e = hev[(size_t)e + 1];       // misses / evictions through batch e
+    BP_TRY((device_scan<uint32_t, AddOp, ResidentFlagIn, ResidentOut>(
+        ResidentFlagIn{ukey, M, ib, e, w.scalars},
+        ResidentOut{ukey, (const int32_t*)w.slot_of_pair, ib, ch->out->resident_ids, ch->out->ring}, M, w.scan_partials32,
+        AddOp(), 0u, stream)));
+    uint32_t n_res = 0;
+    BP_HIP(hipMemcpyAsync(&n_res, w.scan_partials32 + scan_num_tiles(M), sizeof(uint32_t), hipMemcpyDeviceToHost, stream));
+    BP_HIP(hipStreamSynchronize(stream));
+    if ((int64_t)n_res != miss_e - evict_e)
+        return fail(BP_ERR_HIP, "internal: %u resident rows but %lld misses - %lld evictions", n_res, (long long)miss_e,
+                    (long long)evict_e);
+    const int64_t n_free = C + evict_e - miss_e;
+    if (n_free > 0)
+        BP_LAUNCH(K_PLAN_SLOTS, plan_state_queue_kernel, grid_for(n_free), dim3(kBlock), 0, stream, miss_e, evict_e, C, ring0,
+                  (const int32_t*)plan->evict_slots, (int64_t)n_res, ch->out->ring);
+    BP_HIP(hipStreamSynchronize(stream));
+    ch->out->n_resident = n_res;
     return BP_OK;
+}
+
+}  // namespace
+}  // namespace bp
+
+BP_EXPORT int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offsets, int32_t n_iters,
+                              bp_plan* plan, void* workspace, size_t workspace_bytes, void* stream) {
+    return plan_impl(cfg, ids, iter_offsets, n_iters, plan, workspace, workspace_bytes, (hipStream_t)stream, nullptr);
+}
+
+BP_EXPORT int bp_oracle_plan_chunk_workspace_bytes(const bp_config* cfg, int64_t n_lookups, int32_t n_iters,
+                                                   int32_t with_grouping, size_t* bytes) {
+    if (!bytes) return fail(BP_ERR_INVALID_ARG, "bytes is NULL");
+    BP_TRY(check_config(cfg));
+    if (n_lookups < 0 || n_iters < 1) return fail(BP_ERR_INVALID_ARG, "n_lookups < 0 or n_iters < 1");
+    BP_TRY(check_plan_args(cfg, n_lookups + cfg->capacity, n_iters + 1));
+    const int T = n_iters + 1;
+    const int Lcap = cfg->lookahead > 0 && cfg->lookahead < T ? cfg->lookahead : T;
+    *bytes = carve_plan(nullptr, 0, n_lookups + cfg->capacity, T, Lcap, with_grouping != 0).bytes;
+    return BP_OK;
+}
+
+BP_EXPORT int bp_oracle_plan_chunk(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offsets, int32_t n_iters,
+                                    int32_t n_emit, const bp_plan_state* state_in, bp_plan_state* state_out, bp_plan* plan,
+                                    void* workspace, size_t workspace_bytes, void* stream) {
+    const ChunkArgs ch{n_emit, state_in, state_out};
+    return plan_impl(cfg, ids, iter_offsets, n_iters, plan, workspace, workspace_bytes, (hipStream_t)stream, &ch);
 }

@@ -428,3 +428,87 @@ def test_plan_without_configured_lookahead():
         assert p.peak <= C
     with pytest.raises(oracle.OracleError):
         oracle.plan(ids, off, R, 0, 3)                   # the first batch alone does not fit
+
+
+# ---------------------------------------------------------------------------------------------------
+# a lookahead that changes from batch to batch; planning a stream chunk by chunk
+# ---------------------------------------------------------------------------------------------------
+def _plan_varying_by_sets(ids, off, L_of, C):
+    """Algorithm 1 with the window of batch i = [i, i + L_of[i] - 1], with Python sets and a deque."""
+    from collections import deque
+    T = len(off) - 1
+    batches = [sorted(set(ids[off[i]:off[i + 1]].tolist())) for i in range(T)]
+    free, slot = deque(range(C)), {}
+    pre, ev, keep, occ = [], [], [], []
+    for i in range(T):
+        window = range(i + 1, min(T, i + L_of[i]))
+        ttl = {g: max([b for b in window if g in set(batches[b])], default=i) for g in batches[i]}
+        keep.append([(g, ttl[g]) for g in batches[i]])
+        pre.append([])
+        for g in batches[i]:
+            if g not in slot:
+                slot[g] = free.popleft()
+                pre[-1].append((g, slot[g]))
+        occ.append(len(slot))
+        ev.append([])
+        for g in batches[i]:
+            if ttl[g] == i:
+                ev[-1].append((g, slot[g]))
+                free.append(slot.pop(g))
+    return pre, ev, keep, occ
+
+
+def _lists(plan, which, second):
+    off = getattr(plan, which + "_off")
+    a, b = getattr(plan, which + "_ids"), getattr(plan, second)
+    return [list(zip(a[off[i]:off[i + 1]].tolist(), b[off[i]:off[i + 1]].tolist())) for i in range(len(off) - 1)]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_plan_varying_against_sets(seed):
+    rng = np.random.default_rng(300 + seed)
+    R, T = int(rng.integers(8, 60)), int(rng.integers(2, 16))
+    lens = rng.integers(0, 25, size=T)
+    off = np.zeros(T + 1, dtype=np.int64)
+    off[1:] = np.cumsum(lens)
+    ids = np.minimum(rng.zipf(1.4, size=int(off[-1])) - 1, R - 1).astype(np.int64)
+    L_of = rng.integers(1, 7, size=T).astype(np.int32)
+    C = R                                                    # never dry
+    p = oracle.plan_varying(ids, off, R, L_of, C)
+    pre, ev, keep, occ = _plan_varying_by_sets(ids, off, L_of, C)
+    assert _lists(p, "prefetch", "prefetch_slots") == pre
+    assert _lists(p, "evict", "evict_slots") == ev
+    assert _lists(p, "keep", "keep_ttl") == keep
+    assert p.occ.tolist() == occ
+    # a constant lookahead is the plan of part A
+    q = oracle.plan(ids, off, R, 4, C, L_eff=4)
+    r = oracle.plan_varying(ids, off, R, np.full(T, 4, np.int32), C)
+    for name in ("lookup_slots", "prefetch_ids", "prefetch_slots", "evict_ids", "evict_slots", "keep_ids", "keep_ttl", "occ"):
+        assert np.array_equal(getattr(q, name), getattr(r, name)), name
+
+
+def test_plan_chunked_policy_small():
+    """Chunks of 3 batches, capacity tight: every chunk gets the largest lookahead whose occupancy over its own
+    batches fits, and no smaller one would be needed."""
+    rng = np.random.default_rng(11)
+    R, T = 80, 12
+    off = np.arange(0, 15 * T + 1, 15, dtype=np.int64)
+    ids = np.minimum(rng.zipf(1.3, size=15 * T) - 1, R - 1).astype(np.int64)
+    umax = max(len(np.unique(ids[off[i]:off[i + 1]])) for i in range(T))
+    C = umax + 1
+    p, L_of = oracle.plan_chunked(ids, off, R, 5, C, 3)
+    assert p.occ.max() <= C and L_of.min() >= 1 and L_of.max() <= 5
+    assert len(set(L_of.tolist())) > 1 or L_of[0] < 5            # the capacity binds somewhere
+    for a in range(0, T, 3):
+        assert len(set(L_of[a:a + 3].tolist())) == 1            # one lookahead per chunk
+        if L_of[a] < 5:                                          # one more would overflow this chunk
+            bigger = L_of.copy()
+            bigger[a:] = L_of[a] + 1
+            q = oracle.plan_varying(ids, off, R, bigger, R + 1)
+            assert q.occ[a:a + 3].max() > C
+    # rows kept under an earlier, larger lookahead stay: with one slot less the second chunk cannot be planned at all
+    with pytest.raises(oracle.OracleError):
+        oracle.plan_chunked(ids, off, R, 5, umax, 3)
+    # ample capacity: the configured lookahead everywhere, i.e. the plan of part A
+    p2, L2 = oracle.plan_chunked(ids, off, R, 5, R, 3)
+    assert (L2 == 5).all() and np.array_equal(p2.lookup_slots, oracle.plan(ids, off, R, 5, R, L_eff=5).lookup_slots)
