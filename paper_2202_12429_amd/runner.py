@@ -59,6 +59,9 @@ class CachedEmbeddingTrainer:
         self._bwd_ws = None
         self._out = None
         self._pipeline = None
+        self._plan_state = None        # chunked planning: state of the cache at the last chunk boundary
+        self._carried_evict = None     # evictions of the previous chunk's last batch, applied before this chunk's first
+        self._n_emit = None
         if max_lookups:
             self._reserve(max_lookups, max_bags or max_lookups)
 
@@ -85,6 +88,27 @@ class CachedEmbeddingTrainer:
                 self._stage = torch.empty(need, dtype=torch.uint8, device=self.device)
         return self.plan_
 
+    def plan_chunk(self, ids_dev, iter_offsets, n_emit: int) -> B.Plan:
+        """Plans the next n_emit batches of a stream (bp_oracle_plan_chunk); the batches after them in `ids_dev` are
+        the lookahead window.  Batches are then addressed 0 .. n_emit-1 until the next call.  Synchronous schedule."""
+        import torch
+        if self.plan_ is not None and self._n_emit:
+            e_ids, e_slots = self._slice("evict", self._n_emit - 1)
+            self._carried_evict = (e_ids.clone(), e_slots.clone(), int(self.plan_.L_eff))
+        self.close()
+        self.iter_offsets = np.ascontiguousarray(iter_offsets, dtype=np.int64)
+        self.plan_, self._plan_state = B.bp_oracle_plan_chunk(self.cfg, ids_dev, self.iter_offsets, n_emit,
+                                                              self._plan_state, grouping=self.grouping)
+        self._n_emit = n_emit
+        if self.plan_.L_eff >= 2:
+            most = int(np.diff(self.plan_.evict_offsets).max()) if n_emit > 0 else 0
+            if self._carried_evict is not None:
+                most = max(most, int(self._carried_evict[0].numel()))
+            need = B.bp_cache_apply_duplex_workspace_bytes(self.cfg, most)
+            if self._stage is None or self._stage.numel() < need:
+                self._stage = torch.empty(need, dtype=torch.uint8, device=self.device)
+        return self.plan_
+
     def _slice(self, which: str, i: int):
         p = self.plan_
         off = getattr(p, which + "_offsets")
@@ -98,8 +122,13 @@ class CachedEmbeddingTrainer:
     # ---- (2)
     def maintain(self, i: int, stream=None) -> None:
         e_ids, e_slots = self._slice("evict", i - 1) if i > 0 else (None, None)
+        disjoint = self.plan_.L_eff >= 2          # a row evicted after batch i-1 is then not fetched for batch i
+        if i == 0 and self._carried_evict is not None:
+            e_ids, e_slots, l_prev = self._carried_evict
+            disjoint = disjoint and l_prev >= 2    # ... under the lookahead the eviction was decided with
+            self._carried_evict = None
         p_ids, p_slots = self._slice("prefetch", i)
-        if self.duplex and self.plan_.L_eff >= 2:
+        if self.duplex and disjoint:
             B.bp_cache_apply_duplex(self.cfg, self.cache_w, self.cache_state, self.backing_w, self.backing_state, e_ids,
                                     e_slots, p_ids, p_slots, self._stage, stream=stream)
         else:
@@ -134,7 +163,7 @@ class CachedEmbeddingTrainer:
             pass
 
     def flush(self, stream=None) -> None:
-        T = self.iter_offsets.shape[0] - 1
+        T = self._n_emit if self._n_emit else self.iter_offsets.shape[0] - 1
         e_ids, e_slots = self._slice("evict", T - 1)
         B.bp_cache_apply(self.cfg, self.cache_w, self.cache_state, self.backing_w, self.backing_state, e_ids, e_slots,
                          None, None, stream=stream)

@@ -511,3 +511,153 @@ def test_end_to_end_skew_workload(bp, skew):
     cfg = workloads.skew_config(0, skew, optimizer="adagrad", capacity=6000, iterations=30)
     run_end_to_end(cfg, workloads.make_trace(cfg))
     run_end_to_end(cfg, workloads.make_trace(cfg), overlapped=True, reserve=1500)
+
+
+# ---------------------------------------------------------------------------------------------------
+# planning a stream chunk by chunk (bp_oracle_plan_chunk)
+# ---------------------------------------------------------------------------------------------------
+def run_chunked(bp, ids, off, R, L, C, n_emit, reserve=0):
+    """Plans the stream n_emit batches at a time through the C ABI, each call seeing L - 1 batches beyond its chunk,
+    and compares every emitted batch and every carried state with the oracle's chunk-by-chunk plan."""
+    want, L_of = oracle.plan_chunked(ids, off, R, L, C, n_emit, reserve)
+    T = len(off) - 1
+    cfg = bp.make_config(R, C, 16, lookahead=L, reserve=reserve)
+    state = None
+    for a in range(0, T, n_emit):
+        b = min(T, a + n_emit)
+        hi = min(T, b + L - 1)
+        sub_off = (off[a:hi + 1] - off[a]).astype(np.int64)
+        sub_ids = ids[off[a]:off[hi]]
+        got, state = bp.bp_oracle_plan_chunk(cfg, dev(sub_ids), sub_off, b - a, state, grouping=True)
+        assert got.L_eff == L_of[a], (a, got.L_eff, L_of[a])
+        assert np.array_equal(got.occupancy, want.occ[a:b])
+        for k in range(b - a):
+            i = a + k
+            for name, oname in (("prefetch", "prefetch"), ("evict", "evict")):
+                g0, g1 = getattr(got, name + "_offsets")[k], getattr(got, name + "_offsets")[k + 1]
+                w0, w1 = getattr(want, oname + "_off")[i], getattr(want, oname + "_off")[i + 1]
+                assert np.array_equal(getattr(got, name + "_ids")[g0:g1].cpu().numpy(), getattr(want, oname + "_ids")[w0:w1]), (name, i)
+                assert np.array_equal(getattr(got, name + "_slots")[g0:g1].cpu().numpy(), getattr(want, oname + "_slots")[w0:w1]), (name, i)
+            g0, g1 = got.keep_offsets[k], got.keep_offsets[k + 1]
+            w0, w1 = want.keep_off[i], want.keep_off[i + 1]
+            assert np.array_equal(got.keep_ids[g0:g1].cpu().numpy(), want.keep_ids[w0:w1])
+            assert np.array_equal(got.keep_ttl[g0:g1].cpu().numpy() + a, want.keep_ttl[w0:w1])
+        n_em = int(off[b] - off[a])
+        assert np.array_equal(got.lookup_slots[:n_em].cpu().numpy(), want.lookup_slots[off[a]:off[b]])
+        if n_em:
+            gs, gl, st, ioff, sp, soff = oracle.group_lookups(sub_ids[:n_em], sub_off[:b - a + 1],
+                                                              want.lookup_slots[off[a]:off[b]])
+            assert np.array_equal(got.grouped_slots[:n_em].cpu().numpy(), gs)
+            assert np.array_equal(got.grouped_lookups[:n_em].cpu().numpy(), gl)
+            assert np.array_equal(got.item_offsets - got.item_offsets[0], ioff)
+            assert np.array_equal(got.split_offsets - got.split_offsets[0], soff)
+            i0, i1 = int(got.item_offsets[0]), int(got.item_offsets[-1])
+            assert np.array_equal(got.item_starts[i0:i1].cpu().numpy().view(np.uint32), st)
+            s0, s1 = int(got.split_offsets[0]), int(got.split_offsets[-1])
+            assert np.array_equal(got.split_starts[s0:s1].cpu().numpy().view(np.uint32), sp)
+        # carried state: replay the oracle's lists up to batch b - 1
+        held = {}
+        free = list(range(C))
+        for i in range(b):
+            for g, s in zip(want.prefetch_ids[want.prefetch_off[i]:want.prefetch_off[i + 1]].tolist(),
+                            want.prefetch_slots[want.prefetch_off[i]:want.prefetch_off[i + 1]].tolist()):
+                assert free.pop(0) == s
+                held[g] = s
+            for g, s in zip(want.evict_ids[want.evict_off[i]:want.evict_off[i + 1]].tolist(),
+                            want.evict_slots[want.evict_off[i]:want.evict_off[i + 1]].tolist()):
+                assert held.pop(g) == s
+                free.append(s)
+        n = state.n_resident
+        assert n == len(held)
+        assert state.resident_ids[:n].cpu().tolist() == sorted(held)
+        assert state.ring[:n].cpu().tolist() == [held[g] for g in sorted(held)]
+        assert state.ring[n:].cpu().tolist() == free
+    return want, L_of
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_plan_chunked_random(bp, seed):
+    say(f"plan chunked random seed={seed}")
+    rng = np.random.default_rng(500 + seed)
+    R = int(rng.integers(20, 300))
+    T = int(rng.integers(4, 30))
+    lens = rng.integers(0, 200, size=T)
+    lens[rng.integers(0, T)] = 0
+    off = np.zeros(T + 1, dtype=np.int64)
+    off[1:] = np.cumsum(lens)
+    ids = np.minimum(rng.zipf(1.25, size=int(off[-1])) - 1, R - 1).astype(np.int64)
+    umax = max(len(np.unique(ids[off[i]:off[i + 1]])) for i in range(T))
+    for L, C, n_emit in ((4, 4 * R, 3), (4, 4 * R, 1), (1, 4 * R, 5), (2, 4 * R, 2), (T + 3, 4 * R, 4), (6, 4 * R, T)):
+        want, L_of = run_chunked(bp, ids, off, R, L, C, n_emit)
+        assert (L_of == L).all()
+        # same lookahead everywhere: the chunks together are the whole-trace plan
+        whole = oracle.plan(ids, off, R, L, C, L_eff=L)
+        assert np.array_equal(want.lookup_slots, whole.lookup_slots) and np.array_equal(want.evict_slots, whole.evict_slots)
+    # capacity binds: chunks may get different lookaheads (or the stream cannot be planned: then both sides say so)
+    for L, C, n_emit in ((5, umax + 6, 3), (5, umax + 12, 1), (8, 2 * umax, 4)):
+        try:
+            want, L_of = run_chunked(bp, ids, off, R, L, C, n_emit)
+            say(f"  L={L} C={C} chunks of {n_emit}: lookaheads {sorted(set(L_of.tolist()))}")
+        except oracle.OracleError:
+            say(f"  L={L} C={C} chunks of {n_emit}: not plannable (oracle)")
+
+
+def test_plan_chunked_medium(bp):
+    """~0.6 M lookups, 50 batches in chunks of 10 with a lookahead of 8: multi-tile sorts and scans in chunk mode."""
+    say("plan chunked medium")
+    cfg = workloads.get_config(1, batch=500, iterations=50, lookahead=8)
+    tr = workloads.make_trace(cfg)
+    R = cfg.total_rows
+    whole = oracle.plan(tr.ids, tr.iter_offsets, R, 8, 10 ** 6, L_eff=8)
+    c = bp.make_config(R, 10 ** 6, 16, lookahead=8)
+    state, off = None, tr.iter_offsets
+    for a in range(0, 50, 10):
+        b, hi = a + 10, min(50, a + 10 + 7)
+        got, state = bp.bp_oracle_plan_chunk(c, dev(tr.ids[off[a]:off[hi]]), off[a:hi + 1] - off[a], 10, state, grouping=True)
+        assert got.L_eff == 8
+        n_em = int(off[b] - off[a])
+        assert np.array_equal(got.lookup_slots[:n_em].cpu().numpy(), whole.lookup_slots[off[a]:off[b]])
+        g0, g1 = got.prefetch_offsets[0], got.prefetch_offsets[-1]
+        assert np.array_equal(got.prefetch_ids[g0:g1].cpu().numpy(), whole.prefetch_ids[whole.prefetch_off[a]:whole.prefetch_off[b]])
+        assert np.array_equal(got.prefetch_slots[g0:g1].cpu().numpy(), whole.prefetch_slots[whole.prefetch_off[a]:whole.prefetch_off[b]])
+        g0, g1 = got.evict_offsets[0], got.evict_offsets[-1]
+        assert np.array_equal(got.evict_slots[g0:g1].cpu().numpy(), whole.evict_slots[whole.evict_off[a]:whole.evict_off[b]])
+        assert state.n_resident == whole.prefetch_off[b] - whole.evict_off[b]
+
+
+@pytest.mark.parametrize("optimizer,dtype,bag_max,capacity,lookahead,n_emit", [
+    ("adagrad", "f32", 1, 4096, 6, 7), ("sgd", "f32", 5, 2200, 8, 4), ("adagrad_rowwise", "bf16", 1, 1300, 5, 1),
+    ("adagrad", "bf16", 3, 3000, 1, 6)])
+def test_end_to_end_streaming(bp, optimizer, dtype, bag_max, capacity, lookahead, n_emit):
+    """The trace planned chunk by chunk while it is trained on: same outputs and final table as the uncached oracle."""
+    say(f"streaming: {optimizer} {dtype} bag_max={bag_max} C={capacity} L={lookahead} chunks of {n_emit}")
+    from paper_2202_12429_amd.runner import CachedEmbeddingTrainer
+    cfg = workloads.get_config(0, optimizer=optimizer, weight_dtype=dtype, bag_max=bag_max, capacity=capacity,
+                               batch=128 if bag_max > 1 else 256, iterations=30, lookahead=lookahead)
+    trace = workloads.make_trace(cfg)
+    Wo, So, outs = helpers.oracle_uncached(cfg, trace)
+    W, S = helpers.make_backing(cfg, True)
+    tr = CachedEmbeddingTrainer(helpers.bp_config_of(cfg), W, S)
+    T, off, bags = cfg.iterations, trace.iter_offsets, cfg.bags
+    seen = []
+    for a in range(0, T, n_emit):
+        b, hi = min(T, a + n_emit), min(T, a + n_emit + lookahead - 1)
+        plan = tr.plan_chunk(dev(trace.ids[off[a]:off[hi]]), off[a:hi + 1] - off[a], b - a)
+        seen.append(plan.L_eff)
+        for k in range(b - a):
+            i = a + k
+            bo = None if cfg.one_hot else dev(np.ascontiguousarray(trace.bag_offsets[i]))
+            tr.maintain(k)
+            out = tr.forward(k, bo, bags)
+            helpers.assert_outputs_close(out.cpu().numpy(), outs[i], cfg.bag_max, same_table=(i == 0))
+            tr.backward_update(k, bo, bags, workloads.upstream_grad(cfg, i, bags, device="cuda:0"))
+    tr.flush()
+    torch.cuda.synchronize()
+    say(f"  lookaheads of the chunks: {sorted(set(seen))}")
+    got = helpers.table_from_torch(cfg, W)
+    if dtype == "bf16":
+        assert np.array_equal(got, Wo)
+    else:
+        helpers.assert_weights_close(got, Wo)
+    if So.size:
+        np.testing.assert_allclose(S.cpu().numpy(), So, rtol=1e-4, atol=1e-9)
