@@ -198,26 +198,29 @@ def plan_varying(ids, iter_off, total_rows, L_of, C) -> Plan:
 
 
 def plan_chunked(ids, iter_off, total_rows, L, C, n_emit, reserve=0):
-    """The stream planned chunk by chunk (n_emit batches at a time), each chunk with the largest lookahead <= L whose
-    peak occupancy over the chunk's batches fits C - reserve, earlier chunks keeping theirs.  Returns (plan, L_of).
+    """The stream planned chunk by chunk (n_emit batches at a time).  Each chunk takes the largest lookahead <= L
+    such that, with the earlier chunks keeping theirs and every later batch planned with a lookahead of one, no
+    batch from the chunk's first to the last one its decisions can reach (L - 1 batches past the chunk) holds more
+    than C - reserve rows.  So a chunk never leaves the next one a cache it cannot plan.  Returns (plan, L_of).
     Exhaustive and slow: every candidate is planned from the start of the stream."""
     iter_off = _c(iter_off, np.int64)
     T = iter_off.shape[0] - 1
     L_of = np.full(T, L, dtype=np.int32)
     for a in range(0, T, n_emit):
         b = min(T, a + n_emit)
+        reach = min(T, b + L - 1)
         chosen = None
         for cand in range(L, 0, -1):
-            L_of[a:] = cand
+            L_of[a:b] = cand
+            L_of[b:] = 1
             # occupancy does not depend on how many slots there are: count it with a ring that cannot run dry
             p = plan_varying(ids, iter_off, total_rows, L_of, total_rows + 1)
-            if p.occ[a:b].max(initial=0) <= C - reserve:
+            if p.occ[a:reach].max(initial=0) <= C - reserve:
                 chosen = cand
                 break
         if chosen is None:
             raise OracleError(-2, "plan_chunked", chunk_start=a)
         L_of[a:b] = chosen
-        L_of[b:] = L
     return plan_varying(ids, iter_off, total_rows, L_of, C), L_of
 
 

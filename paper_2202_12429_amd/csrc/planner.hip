@@ -180,11 +180,14 @@ __global__ void plan_vcover_kernel(const uint32_t* __restrict__ V, uint32_t R0, 
     }
 }
 
-// rows resident but unused at batch j because of pairs with exactly this gap: batches i in (j - gap, j)
-__device__ __forceinline__ uint32_t covering(const uint32_t* Hc, int T, int gap, int j) {
+// rows resident but unused at batch j because of pairs with exactly this gap: batches i in (j - gap, j), and only
+// pairs of batches <= last_deciding (a chunk asks what its own decisions leave in the cache of the batches after it)
+__device__ __forceinline__ uint32_t covering(const uint32_t* Hc, int T, int gap, int j, int last_deciding) {
     if (j < 1) return 0;
+    const int top = j - 1 < last_deciding ? j - 1 : last_deciding;
+    if (j - gap >= top) return 0;
     const uint32_t* row = Hc + (size_t)gap * T;
-    const uint32_t hi = row[j - 1];
+    const uint32_t hi = row[top];
     const uint32_t lo = j - gap >= 0 ? row[j - gap] : 0u;
     return hi - lo;
 }
@@ -196,8 +199,11 @@ __global__ __launch_bounds__(kBlock) void plan_occ_peak_kernel(const uint32_t* _
                                                                const uint32_t* __restrict__ vcover, int j_first,
                                                                int j_last, int T, int Lcap, uint32_t* __restrict__ peak) {
     __shared__ uint32_t wave_tot[kBlock / kWave];
+    // A chunk's peak is taken over the batches it emits and, for the batches after them, over what its decisions
+    // alone leave there (their own rows, the carried rows, the rows this chunk keeps): if that fits, the following
+    // chunk can be planned at least with a lookahead of one.
     const int j = blockIdx.x;
-    if (j < j_first || j > j_last) return;             // a chunk's peak is taken over the batches it emits
+    if (j < j_first) return;
     uint32_t carry = ucount[j] + (vcover ? vcover[j] : 0u);
     if (threadIdx.x == 0) {
         atomicMax(&peak[1], carry);
@@ -205,7 +211,7 @@ __global__ __launch_bounds__(kBlock) void plan_occ_peak_kernel(const uint32_t* _
     }
     for (int base = 2; base < Lcap; base += kBlock) {     // gap = L' - 1 for L' = 3..Lcap
         const int gap = base + threadIdx.x;
-        const uint32_t v = gap < Lcap ? covering(Hc, T, gap, j) : 0u;
+        const uint32_t v = gap < Lcap ? covering(Hc, T, gap, j, j_last) : 0u;
         uint32_t exc, inc, total;
         block_scan<kBlock>(v, AddOp(), 0u, wave_tot, &exc, &inc, &total);
         if (gap < Lcap) atomicMax(&peak[gap + 1], carry + inc);
@@ -255,7 +261,7 @@ __global__ void plan_occ_final_kernel(const uint32_t* __restrict__ Hc, const uin
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
     if (j >= T) return;
     uint32_t run = ucount[j] + (vcover ? vcover[j] : 0u);
-    for (int gap = 2; gap < sc->L_sel; ++gap) run += covering(Hc, T, gap, j);
+    for (int gap = 2; gap < sc->L_sel; ++gap) run += covering(Hc, T, gap, j, T);
     occ[j] = run;
 }
 

@@ -593,13 +593,13 @@ def test_plan_chunked_random(bp, seed):
         # same lookahead everywhere: the chunks together are the whole-trace plan
         whole = oracle.plan(ids, off, R, L, C, L_eff=L)
         assert np.array_equal(want.lookup_slots, whole.lookup_slots) and np.array_equal(want.evict_slots, whole.evict_slots)
-    # capacity binds: chunks may get different lookaheads (or the stream cannot be planned: then both sides say so)
-    for L, C, n_emit in ((5, umax + 6, 3), (5, umax + 12, 1), (8, 2 * umax, 4)):
-        try:
-            want, L_of = run_chunked(bp, ids, off, R, L, C, n_emit)
-            say(f"  L={L} C={C} chunks of {n_emit}: lookaheads {sorted(set(L_of.tolist()))}")
-        except oracle.OracleError:
-            say(f"  L={L} C={C} chunks of {n_emit}: not plannable (oracle)")
+    # capacity binds: chunks get different lookaheads; a stream whose batches fit one by one can always be planned
+    for L, C, n_emit in ((5, umax, 3), (6, umax + 2, 1), (8, umax + 10, 4), (5, umax + 6, 3)):
+        want, L_of = run_chunked(bp, ids, off, R, L, C, n_emit)
+        say(f"  L={L} C={C} chunks of {n_emit}: lookaheads {sorted(set(L_of.tolist()))}")
+    with pytest.raises(bp.BagpipeError) as e:
+        bp.bp_oracle_plan_chunk(bp.make_config(R, umax - 1, 16, lookahead=3), dev(ids), off, T)
+    assert e.value.status == -2
 
 
 def test_plan_chunked_medium(bp):
@@ -627,7 +627,8 @@ def test_plan_chunked_medium(bp):
 
 @pytest.mark.parametrize("optimizer,dtype,bag_max,capacity,lookahead,n_emit", [
     ("adagrad", "f32", 1, 4096, 6, 7), ("sgd", "f32", 5, 2200, 8, 4), ("adagrad_rowwise", "bf16", 1, 1300, 5, 1),
-    ("adagrad", "bf16", 3, 3000, 1, 6)])
+    ("adagrad", "bf16", 3, 3000, 1, 6),
+    ("adagrad", "f32", 1, 1500, 20, 3), ("sgd", "f32", 1, 1450, 20, 1)])      # the capacity binds: lookaheads differ
 def test_end_to_end_streaming(bp, optimizer, dtype, bag_max, capacity, lookahead, n_emit):
     """The trace planned chunk by chunk while it is trained on: same outputs and final table as the uncached oracle."""
     say(f"streaming: {optimizer} {dtype} bag_max={bag_max} C={capacity} L={lookahead} chunks of {n_emit}")

@@ -488,27 +488,27 @@ def test_plan_varying_against_sets(seed):
 
 
 def test_plan_chunked_policy_small():
-    """Chunks of 3 batches, capacity tight: every chunk gets the largest lookahead whose occupancy over its own
-    batches fits, and no smaller one would be needed."""
+    """Chunks of 3 batches, capacity tight: every chunk gets the largest lookahead that fits its own batches and
+    leaves the batches its decisions reach plannable; any stream whose batches fit one by one can be planned."""
     rng = np.random.default_rng(11)
-    R, T = 80, 12
+    R, T, L = 80, 12, 5
     off = np.arange(0, 15 * T + 1, 15, dtype=np.int64)
     ids = np.minimum(rng.zipf(1.3, size=15 * T) - 1, R - 1).astype(np.int64)
     umax = max(len(np.unique(ids[off[i]:off[i + 1]])) for i in range(T))
-    C = umax + 1
-    p, L_of = oracle.plan_chunked(ids, off, R, 5, C, 3)
-    assert p.occ.max() <= C and L_of.min() >= 1 and L_of.max() <= 5
-    assert len(set(L_of.tolist())) > 1 or L_of[0] < 5            # the capacity binds somewhere
-    for a in range(0, T, 3):
-        assert len(set(L_of[a:a + 3].tolist())) == 1            # one lookahead per chunk
-        if L_of[a] < 5:                                          # one more would overflow this chunk
-            bigger = L_of.copy()
-            bigger[a:] = L_of[a] + 1
-            q = oracle.plan_varying(ids, off, R, bigger, R + 1)
-            assert q.occ[a:a + 3].max() > C
-    # rows kept under an earlier, larger lookahead stay: with one slot less the second chunk cannot be planned at all
-    with pytest.raises(oracle.OracleError):
-        oracle.plan_chunked(ids, off, R, 5, umax, 3)
+    for C in (umax + 1, umax):
+        p, L_of = oracle.plan_chunked(ids, off, R, L, C, 3)
+        assert p.occ.max() <= C and L_of.min() >= 1 and L_of.max() <= L
+        assert len(set(L_of.tolist())) > 1                         # the capacity binds somewhere
+        for a in range(0, T, 3):
+            assert len(set(L_of[a:a + 3].tolist())) == 1            # one lookahead per chunk
+            if L_of[a] < L:                                          # one more would overflow a batch it reaches
+                bigger = L_of.copy()
+                bigger[a:a + 3] = L_of[a] + 1
+                bigger[a + 3:] = 1
+                q = oracle.plan_varying(ids, off, R, bigger, R + 1)
+                assert q.occ[a:min(T, a + 3 + L - 1)].max() > C
+    with pytest.raises(oracle.OracleError):                         # a batch that does not fit by itself
+        oracle.plan_chunked(ids, off, R, L, umax - 1, 3)
     # ample capacity: the configured lookahead everywhere, i.e. the plan of part A
-    p2, L2 = oracle.plan_chunked(ids, off, R, 5, R, 3)
-    assert (L2 == 5).all() and np.array_equal(p2.lookup_slots, oracle.plan(ids, off, R, 5, R, L_eff=5).lookup_slots)
+    p2, L2 = oracle.plan_chunked(ids, off, R, L, R, 3)
+    assert (L2 == L).all() and np.array_equal(p2.lookup_slots, oracle.plan(ids, off, R, L, R, L_eff=L).lookup_slots)
