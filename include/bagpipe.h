@@ -337,7 +337,8 @@ const char* bp_last_error_message(void);   /* thread-local, valid until the thre
 int bp_version(void);
 
 /*
- * Per-kernel timing with HIP events recorded on the launch stream around every kernel launch.
+ * Per-kernel timing with HIP events: every profiled launch carries a start and a stop event of its own, stamped by
+ * the runtime with the kernel's begin and end on the launch stream.
  * bp_profile_enable(1) starts recording (and clears old records); bp_profile_enable(0) stops.
  * bp_profile_collect() synchronises the recorded events and adds their durations to per-kernel totals;
  * bp_profile_get() reads the totals of kernel `id` in [0, bp_profile_num_kernels()).

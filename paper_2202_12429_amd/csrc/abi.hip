@@ -56,7 +56,6 @@ std::vector<Span> g_spans;          // recorded, not yet collected
 std::vector<hipEvent_t> g_free;     // recycled events
 int64_t g_count[K_NUM_KERNELS];
 double g_ms[K_NUM_KERNELS];
-hipEvent_t g_open = nullptr;
 
 hipEvent_t get_event() {
     if (!g_free.empty()) {
@@ -76,17 +75,17 @@ const char* const kKernelNames[K_NUM_KERNELS] = {
     "bwd_combine_update", "fill", "copy_calibration"};
 }  // namespace
 
-void profile_begin(int /*id*/, hipStream_t s) {
-    g_open = get_event();
-    if (g_open) (void)hipEventRecord(g_open, s);
-}
-
-void profile_end(int id, hipStream_t s) {
-    hipEvent_t b = get_event();
-    if (!g_open || !b) return;
-    (void)hipEventRecord(b, s);
-    g_spans.push_back(Span{id, g_open, b});
-    g_open = nullptr;
+bool profile_events(int id, hipEvent_t* start, hipEvent_t* stop) {
+    hipEvent_t a = get_event(), b = get_event();
+    if (!a || !b) {
+        if (a) g_free.push_back(a);
+        if (b) g_free.push_back(b);
+        return false;
+    }
+    g_spans.push_back(Span{id, a, b});
+    *start = a;
+    *stop = b;
+    return true;
 }
 
 // A plain streaming copy of known size: the yardstick for byte counters (what FETCH_SIZE / WRITE_SIZE read for
@@ -130,9 +129,7 @@ BP_EXPORT int bp_profile_bracket_overhead(void* stream_, int32_t reps, double* m
         if (hipEventCreate(&e) != hipSuccess) st = fail(BP_ERR_HIP, "hipEventCreate failed");
     if (st == BP_OK) {
         for (int r = 0; r < reps; ++r) {
-            (void)hipEventRecord(ev[2 * r], stream);
-            hipLaunchKernelGGL(bracket_probe_kernel, dim3(1), dim3(64), 0, stream);
-            (void)hipEventRecord(ev[2 * r + 1], stream);
+            hipExtLaunchKernelGGL(bracket_probe_kernel, dim3(1), dim3(64), 0, stream, ev[2 * r], ev[2 * r + 1], 0);
         }
         if (hipStreamSynchronize(stream) != hipSuccess) st = fail(BP_ERR_HIP, "hipStreamSynchronize failed");
     }

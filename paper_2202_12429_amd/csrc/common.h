@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <cstdarg>
 #include <cstddef>
@@ -104,16 +105,17 @@ enum KernelId {
 
 extern bool g_profile_on;
 extern uint64_t g_profile_mask;
-void profile_begin(int id, hipStream_t s);
-void profile_end(int id, hipStream_t s);
+bool profile_events(int id, hipEvent_t* start, hipEvent_t* stop);
 
-// Launch `kernel` and, when profiling is on, bracket it with events on the same stream.
+// Launch `kernel`; when profiling is on, the launch carries a start and a stop event of its own (the runtime stamps
+// them with the kernel's begin and end, so the reading holds no launch gap and no neighbouring work).
 #define BP_LAUNCH(id, kernel, grid, block, shmem, stream, ...)                      \
     do {                                                                             \
-        const bool prof_ = ::bp::g_profile_on && ((::bp::g_profile_mask >> (id)) & 1);  \
-        if (prof_) ::bp::profile_begin((id), (stream));                              \
-        hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__);        \
-        if (prof_) ::bp::profile_end((id), (stream));                                \
+        hipEvent_t ea_ = nullptr, eb_ = nullptr;                                     \
+        if (::bp::g_profile_on && ((::bp::g_profile_mask >> (id)) & 1) && ::bp::profile_events((id), &ea_, &eb_))  \
+            hipExtLaunchKernelGGL(kernel, grid, block, shmem, stream, ea_, eb_, 0, __VA_ARGS__);  \
+        else                                                                         \
+            hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__);    \
         hipError_t le_ = hipGetLastError();                                          \
         if (le_ != hipSuccess)                                                       \
             return ::bp::fail(BP_ERR_HIP, "launch of %s failed: %s", #kernel, hipGetErrorString(le_)); \
