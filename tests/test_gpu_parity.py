@@ -662,3 +662,64 @@ def test_end_to_end_streaming(bp, optimizer, dtype, bag_max, capacity, lookahead
         helpers.assert_weights_close(got, Wo)
     if So.size:
         np.testing.assert_allclose(S.cpu().numpy(), So, rtol=1e-4, atol=1e-9)
+
+
+# ---------------------------------------------------------------------------------------------------
+# HIP graph capture of a step
+# ---------------------------------------------------------------------------------------------------
+def test_step_captured_in_a_graph(bp):
+    """cache maintenance + forward + grouped backward of one batch recorded into a HIP graph (the entry points only
+    launch kernels on the given stream: no allocation, no memset, no synchronisation) and replayed three times with
+    eager work and synchronisations in between: bit for bit what three eager runs of the same step give."""
+    say("one step captured in a HIP graph")
+    from paper_2202_12429_amd.runner import CachedEmbeddingTrainer
+    cfg = workloads.get_config(0, optimizer="adagrad", iterations=6, capacity=3000)
+    trace = workloads.make_trace(cfg)
+    bags, k = cfg.bags, 3
+
+    def fresh():
+        W, S = helpers.make_backing(cfg, pinned=False)
+        tr = CachedEmbeddingTrainer(helpers.bp_config_of(cfg), W, S, max_lookups=bags, max_bags=bags)
+        tr.plan(dev(trace.ids), trace.iter_offsets)
+        for i in range(k):                                   # bring the cache to the state before batch k
+            tr.maintain(i)
+            tr.forward(i, None, bags)
+            tr.backward_update(i, None, bags, workloads.upstream_grad(cfg, i, bags, device="cuda:0"))
+        torch.cuda.synchronize()
+        return tr, W, S
+
+    grad = workloads.upstream_grad(cfg, k, bags, device="cuda:0")
+    out = torch.empty((bags, cfg.dim), dtype=torch.float32, device="cuda")
+
+    def step(tr):
+        tr.maintain(k)
+        tr.forward(k, None, bags, out=out)
+        tr.backward_update(k, None, bags, grad)
+
+    tr, W, S = fresh()
+    outs_eager = []
+    for _ in range(3):
+        step(tr)
+        outs_eager.append(out.clone())
+    torch.cuda.synchronize()
+    want_w, want_s = tr.cache_w.clone(), tr.cache_state.clone()
+
+    tr, W, S = fresh()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                            # warm-up on the capture stream, then undo it
+        pass
+    graph = torch.cuda.CUDAGraph()
+    w0, s0 = tr.cache_w.clone(), tr.cache_state.clone()
+    with torch.cuda.graph(graph):
+        step(tr)
+    tr.cache_w.copy_(w0)
+    tr.cache_state.copy_(s0)
+    scratch = torch.zeros(1 << 20, device="cuda")
+    for r in range(3):
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, outs_eager[r]), f"replay {r}: pooled output differs from the eager run"
+        scratch.add_(1.0)                                    # eager work between the replays
+        assert float(scratch.sum()) == (r + 1) * scratch.numel()
+    assert torch.equal(tr.cache_w, want_w) and torch.equal(tr.cache_state, want_s)
