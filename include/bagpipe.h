@@ -116,6 +116,16 @@ typedef struct bp_plan {
                                   every row whose lookups span three work items or more (they reach the second
                                   multiple of BP_BWD_CHUNK after the row's first lookup) */
     int64_t* split_offsets;    /* host [T+1] CSR offsets of the batches into split_starts */
+    /* optional: which logical trainer uses a row (Section 3.3: rows used by a single trainer need no synchronisation;
+     * of the shared rows only those the next batch needs are synchronised on the critical path).  All three set or
+     * none.  The lookups of batch i are dealt to n_trainers trainers by position: trainer t owns the positions
+     * [trainer_cuts[i*(n_trainers+1) + t], trainer_cuts[i*(n_trainers+1) + t + 1]) counted from the batch's first
+     * lookup (non-decreasing, from 0 to the batch's size). */
+    const int64_t* trainer_cuts;   /* input, host [T][n_trainers + 1] */
+    int32_t n_trainers;            /* input, 1 .. 64 */
+    int32_t* keep_owner;           /* output, device [list_capacity], parallel to keep_ids: t when only trainer t looks
+                                      the id up in that batch; -1 several trainers and the next batch does not use
+                                      it; -2 several trainers and the next batch uses it too */
     /* scalar results */
     int32_t L_eff;
     int32_t L_requested;       /* the lookahead the capacity policy started from: cfg->lookahead, or, when that is 0,

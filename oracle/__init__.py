@@ -54,6 +54,8 @@ def _load():
         _lib.orc_peak_occupancy.argtypes = [p, p, i64, i64, i64, p]
         _lib.orc_plan_stream.restype = i64
         _lib.orc_plan_stream.argtypes = [p] * 4 + [i64, i64, p, i64] + [p] * 11
+        _lib.orc_keep_owners.restype = i64
+        _lib.orc_keep_owners.argtypes = [p, p, p, p, i64, i64, p, p]
         _lib.orc_auto_lookahead.restype = i64
         _lib.orc_auto_lookahead.argtypes = [p, p, i64, i64, i64]
         _lib.orc_choose_lookahead.restype = i64
@@ -168,6 +170,23 @@ def plan(ids, iter_off, total_rows, L, C, exhaustive=False, L_eff=None, reserve=
                 prefetch_off=poff, prefetch_ids=pid[:r].copy(), prefetch_slots=ps[:r].copy(),
                 evict_off=eoff, evict_ids=eid[:r].copy(), evict_slots=es[:r].copy(),
                 keep_off=koff, keep_ids=kid[:nk].copy(), keep_ttl=kt[:nk].copy())
+
+
+def keep_owners(ids, iter_off, total_rows, cuts) -> np.ndarray:
+    """Per keep-list entry: the one logical trainer that uses the row in that batch, -1 (several, not needed by the
+    next batch) or -2 (several, and the next batch uses it).  cuts: int64 [T, P+1] lookup positions inside a batch."""
+    lib = _load()
+    ids, iter_off = _c(ids, np.int64), _c(iter_off, np.int64)
+    cuts = _c(cuts, np.int64)
+    T = iter_off.shape[0] - 1
+    assert cuts.shape[0] == T
+    uniq, uoff = unique_per_iter(ids, iter_off, total_rows)
+    owner = np.empty(max(1, uniq.shape[0]), dtype=np.int32)
+    r = lib.orc_keep_owners(_ptr(ids), _ptr(iter_off), _ptr(uniq), _ptr(uoff), T, cuts.shape[1] - 1, _ptr(cuts),
+                            _ptr(owner))
+    if r < 0:
+        raise OracleError(r, "keep_owners")
+    return owner[:uniq.shape[0]]
 
 
 def plan_varying(ids, iter_off, total_rows, L_of, C) -> Plan:

@@ -304,6 +304,40 @@ int64_t orc_plan_stream(const int64_t *ids, const int64_t *iter_off, const int64
     return rc == ORC_OK ? np : rc;
 }
 
+/*
+ * Who uses a row (Section 3.3, logically replicated / physically partitioned caches: the Oracle Cacher marks the ids
+ * that a single trainer uses, which then need no synchronisation; Section 3.3 "delayed synchronisation": of the
+ * shared rows only those needed by the very next batch are synchronised on the critical path).
+ * The lookups of batch i are dealt to P logical trainers by position: trainer t owns the positions
+ * [cuts[i*(P+1) + t], cuts[i*(P+1) + t + 1]) counted from the batch's first lookup.
+ * For every (id, batch) entry of the keep list, in its order:  owner = t when every lookup of the id in that batch is
+ * trainer t's;  -1 when several trainers use it and the next batch does not;  -2 when several trainers use it and
+ * the next batch uses it too.
+ */
+int64_t orc_keep_owners(const int64_t *ids, const int64_t *iter_off, const int64_t *uniq, const int64_t *uniq_off,
+                        int64_t T, int64_t P, const int64_t *cuts, int32_t *owner) {
+    if (P < 1) return ORC_ERR_ARG;
+    for (int64_t i = 0; i < T; ++i) {
+        const int64_t *c = cuts + i * (P + 1);
+        for (int64_t q = uniq_off[i]; q < uniq_off[i + 1]; ++q) {
+            int64_t g = uniq[q];
+            int64_t first = -1;
+            int shared = 0;
+            for (int64_t k = iter_off[i]; k < iter_off[i + 1]; ++k) {
+                if (ids[k] != g) continue;
+                int64_t rel = k - iter_off[i], t = -1;
+                for (int64_t x = 0; x < P; ++x)
+                    if (rel >= c[x] && rel < c[x + 1]) t = x;
+                if (t < 0) return ORC_ERR_ARG;              /* the cuts do not cover the batch */
+                if (first < 0) first = t; else if (t != first) shared = 1;
+            }
+            int next = i + 1 < T && batch_has_id(uniq, uniq_off, i + 1, g);
+            owner[q] = shared ? (next ? -2 : -1) : (int32_t)first;
+        }
+    }
+    return ORC_OK;
+}
+
 /* ------------------------------------------------------------------ parts B and C: training */
 
 static inline float bf16_to_f32(uint16_t h) {

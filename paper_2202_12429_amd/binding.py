@@ -42,7 +42,9 @@ class _bp_plan(ctypes.Structure):
                 ("keep_offsets", ctypes.c_void_p), ("occupancy", ctypes.c_void_p),
                 ("grouped_slots", ctypes.c_void_p), ("grouped_lookups", ctypes.c_void_p),
                 ("item_starts", ctypes.c_void_p), ("item_offsets", ctypes.c_void_p),
-                ("split_starts", ctypes.c_void_p), ("split_offsets", ctypes.c_void_p), ("L_eff", ctypes.c_int32),
+                ("split_starts", ctypes.c_void_p), ("split_offsets", ctypes.c_void_p),
+                ("trainer_cuts", ctypes.c_void_p), ("n_trainers", ctypes.c_int32), ("keep_owner", ctypes.c_void_p),
+                ("L_eff", ctypes.c_int32),
                 ("L_requested", ctypes.c_int32), ("peak_occupancy", ctypes.c_int64), ("min_capacity", ctypes.c_int64),
                 ("n_unique_pairs", ctypes.c_int64)]
 
@@ -191,6 +193,7 @@ class Plan:
     L_requested: int = 0                # configured lookahead, or the start-up rule's value when none was configured
     split_starts: "object" = None       # uint32 (as int32 tensor) device, trimmed
     split_offsets: Optional[np.ndarray] = None  # int64 [T+1] host
+    keep_owner: "object" = None         # int32 device, parallel to keep_ids (optional trainer marking)
 
 
 def bp_oracle_plan_workspace_bytes(cfg: bp_config, n_lookups: int, n_iters: int, grouping: bool = False) -> int:
@@ -201,7 +204,7 @@ def bp_oracle_plan_workspace_bytes(cfg: bp_config, n_lookups: int, n_iters: int,
 
 
 def bp_oracle_plan(cfg: bp_config, ids, iter_offsets, list_capacity: Optional[int] = None, workspace=None,
-                   stream=None, grouping: bool = False) -> Plan:
+                   stream=None, grouping: bool = False, trainer_cuts=None) -> Plan:
     """ids: int64 device tensor [N]; iter_offsets: int64 host array [T+1].  Output and workspace tensors are
     allocated here with torch (the library itself allocates nothing); list tensors are trimmed views."""
     import torch
@@ -226,12 +229,19 @@ def bp_oracle_plan(cfg: bp_config, ids, iter_offsets, list_capacity: Optional[in
         t.update(grouped_slots=torch.empty(max(N, 1), **i32), grouped_lookups=torch.empty(max(N, 1), **i32),
                  item_starts=torch.empty(max(N, 1), **i32), split_starts=torch.empty(N // 32 + 2, **i32))
         h.update(item_offsets=np.zeros(T + 1, np.int64), split_offsets=np.zeros(T + 1, np.int64))
+    if trainer_cuts is not None:          # int64 [T, P+1]: which logical trainer owns which lookups of a batch
+        trainer_cuts = np.ascontiguousarray(trainer_cuts, dtype=np.int64)
+        assert trainer_cuts.shape[0] == T
+        t.update(keep_owner=torch.empty(max(cap, 1), **i32))
     p = _bp_plan()
     for k, v in t.items():
         setattr(p, k, v.data_ptr())
     for k, v in h.items():
         setattr(p, k, v.ctypes.data)
     p.list_capacity = cap
+    if trainer_cuts is not None:
+        p.trainer_cuts = trainer_cuts.ctypes.data
+        p.n_trainers = trainer_cuts.shape[1] - 1
     st = lib.bp_oracle_plan(ctypes.byref(cfg), _ptr(ids), iter_offsets.ctypes.data, T, ctypes.byref(p),
                             _ptr(workspace), workspace.numel(), _stream(stream))
     _check(st, min_capacity=int(p.min_capacity), n_unique_pairs=int(p.n_unique_pairs))
@@ -248,7 +258,8 @@ def bp_oracle_plan(cfg: bp_config, ids, iter_offsets, list_capacity: Optional[in
                 item_starts=t["item_starts"][:int(h["item_offsets"][-1])] if grouping else None,
                 item_offsets=h["item_offsets"] if grouping else None,
                 split_starts=t["split_starts"][:int(h["split_offsets"][-1])] if grouping else None,
-                split_offsets=h["split_offsets"] if grouping else None)
+                split_offsets=h["split_offsets"] if grouping else None,
+                keep_owner=t["keep_owner"][:n_k] if trainer_cuts is not None else None)
 
 
 @dataclasses.dataclass

@@ -33,6 +33,7 @@ constexpr int kPlanSortIPT = 16;       // 4096 keys per tile for the big (id, ba
 constexpr int kBlock = 256;
 constexpr uint32_t kGapInf = 0x7fffffffu;
 constexpr int kMaxIters = 8192;
+constexpr int kMaxTrainers = 64;
 
 struct PlanScalars {
     uint32_t error_flags;   // bit 0: id out of range
@@ -102,9 +103,13 @@ struct PairOut {
     const uint64_t* keys;
     uint64_t* ukey;
     uint32_t* uq;
+    uint32_t* pair_start;     // where the pair's lookups begin in the sorted order
     __device__ __forceinline__ void operator()(int64_t p, uint32_t exc, uint32_t inc) const {
         uq[p] = inc - 1u;
-        if (inc != exc) ukey[exc] = keys[p];
+        if (inc != exc) {
+            ukey[exc] = keys[p];
+            pair_start[exc] = (uint32_t)p;
+        }
     }
 };
 
@@ -351,6 +356,36 @@ struct ListOut {
     int64_t* prefetch_off;   // device copies of the CSR offsets, [T+1], pre-filled with -1
     int64_t* evict_off;
     int32_t ttl_shift;       // 1 in chunk mode: the chunk's batches count from 1 inside the planner
+    // optional marking of the trainers that use a row (keep_owner == NULL: off)
+    int32_t* keep_owner;
+    const uint64_t* ukey;     // pairs in (id, batch) order
+    uint32_t M;
+    const uint32_t* pair_start;
+    uint32_t n_sorted;        // lookups in the sorted order (carried rows included)
+    const uint32_t* spos;     // position of every sorted lookup
+    const int64_t* iter_off;  // batch offsets as the planner counts them
+    const int64_t* cuts;      // device [real batches][P + 1]
+    int P;
+    __device__ __forceinline__ int trainer_of(const int64_t* c, int64_t rel) const {
+        int lo = 0, hi = P;                               // largest t < P with c[t] <= rel
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (c[mid] <= rel) lo = mid; else hi = mid;
+        }
+        return lo;
+    }
+    __device__ __forceinline__ int32_t owner_of(uint32_t q, uint32_t i) const {
+        if (ttl_shift && i == 0) return -1;               // a chunk's carried rows: no lookups
+        const uint32_t a = pair_start[q], b = q + 1 < M ? pair_start[q + 1] : n_sorted;
+        const int64_t base = iter_off[i];
+        const int64_t* c = cuts + (size_t)(i - ttl_shift) * (P + 1);
+        // the pair's lookups are in position order and a trainer owns a stretch of positions: first and last decide
+        const int t0 = trainer_of(c, (int64_t)spos[a] - base), t1 = trainer_of(c, (int64_t)spos[b - 1] - base);
+        if (t0 == t1) return t0;
+        const uint64_t imask = (uint64_t(1) << ib) - 1;
+        const bool next = q + 1 < M && (ukey[q + 1] >> ib) == (ukey[q] >> ib) && (ukey[q + 1] & imask) == (uint64_t)i + 1;
+        return next ? -2 : -1;
+    }
     __device__ __forceinline__ void operator()(int64_t k, uint64_t exc, uint64_t) const {
         const PairRecord pr{ib};
         const uint64_t r = srec[k];
@@ -361,6 +396,7 @@ struct ListOut {
         const uint64_t f = pr.flags(r);
         keep_ids[k] = g;
         keep_ttl[k] = (int32_t)pr.ttl(r) - ttl_shift;
+        if (keep_owner) keep_owner[k] = owner_of(q, i);
         if (f & kMiss) {
             prefetch_ids[x] = g;
             missord[q] = x;
@@ -594,7 +630,8 @@ struct PlanWorkspace {
     PlanScalars* scalars;
     int64_t *occ, *prefetch_off, *evict_off, *iter_off;
     uint64_t *rec_a, *rec_b;
-    uint32_t *chain, *val2_a, *val2_b, *missord, *evict_pair, *par;
+    uint32_t *chain, *val2_a, *val2_b, *missord, *evict_pair, *par, *pair_start;
+    int64_t* cuts;           // trainer cuts of every batch, [T][kMaxTrainers + 1] at most
     int32_t* slot_of_pair;
     uint64_t* keys_c;      // grouping only
     uint32_t* pos_c;
@@ -634,6 +671,8 @@ PlanWorkspace carve_plan(void* base, size_t cap, int64_t N, int T, int Lcap, boo
     w.missord = c.take<uint32_t>(n);
     w.evict_pair = c.take<uint32_t>(n);
     w.par = c.take<uint32_t>(n);
+    w.pair_start = c.take<uint32_t>(n + 1);
+    w.cuts = c.take<int64_t>((size_t)T * (kMaxTrainers + 1));
     w.slot_of_pair = c.take<int32_t>(n);
     if (grouping) {
         w.keys_c = c.take<uint64_t>(n);
@@ -761,6 +800,18 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
     if (w.bytes > workspace_bytes)
         return fail(BP_ERR_WORKSPACE_TOO_SMALL, "workspace %zu < required %zu bytes", workspace_bytes, w.bytes);
     const int32_t* ring0 = chunk && ch->in ? ch->in->ring : nullptr;
+    const bool owners = plan->keep_owner || plan->trainer_cuts;
+    const int P = plan->n_trainers;
+    if (owners) {
+        if (!plan->keep_owner || !plan->trainer_cuts || P < 1 || P > kMaxTrainers)
+            return fail(BP_ERR_INVALID_ARG, "keep_owner, trainer_cuts and n_trainers in [1, %d] go together", kMaxTrainers);
+        for (int i = 0; i < T_in; ++i) {
+            const int64_t* c = plan->trainer_cuts + (size_t)i * (P + 1);
+            bool ok = c[0] == 0 && c[P] == iter_offsets[i + 1] - iter_offsets[i];
+            for (int t = 0; t < P && ok; ++t) ok = c[t] <= c[t + 1];
+            if (!ok) return fail(BP_ERR_INVALID_ARG, "trainer_cuts of batch %d do not run from 0 to the batch's size", i);
+        }
+    }
 
     plan->L_eff = 0;
     plan->L_requested = cfg->lookahead;
@@ -790,6 +841,9 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
     // ---- 1. keys + sort
     BP_HIP(hipMemcpyAsync(w.iter_off, voff.data(), sizeof(int64_t) * (T + 1), hipMemcpyHostToDevice, stream));
     BP_HIP(hipMemsetAsync(w.scalars, 0, sizeof(PlanScalars), stream));
+    if (owners)
+        BP_HIP(hipMemcpyAsync(w.cuts, plan->trainer_cuts, sizeof(int64_t) * (size_t)T_in * (P + 1), hipMemcpyHostToDevice,
+                              stream));
     if (R0)
         BP_LAUNCH(K_PLAN_KEYS, plan_resident_keys_kernel, grid_for(R0), dim3(kBlock), 0, stream,
                   (const int64_t*)ch->in->resident_ids, R0, cfg->total_rows, ib, w.keys_a, w.pos_a, w.scalars);
@@ -806,7 +860,7 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
     uint32_t* uq = in_b ? w.pos_a : w.pos_b;
 
     // ---- 2. unique pairs
-    BP_TRY((device_scan<uint32_t, AddOp, HeadFlagIn, PairOut>(HeadFlagIn{skeys}, PairOut{skeys, ukey, uq}, N,
+    BP_TRY((device_scan<uint32_t, AddOp, HeadFlagIn, PairOut>(HeadFlagIn{skeys}, PairOut{skeys, ukey, uq, w.pair_start}, N,
                                                               w.scan_partials32, AddOp(), 0u, stream)));
     uint32_t M = 0;
     PlanScalars hs{};
@@ -882,7 +936,8 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
     BP_TRY((device_scan<uint64_t, AddOp, ListCountIn, ListOut>(
         ListCountIn{srec, ib},
         ListOut{srec, ord, w.pair_off, ib, plan->keep_ids, plan->keep_ttl, plan->prefetch_ids, plan->evict_ids, w.missord,
-                w.evict_pair, w.prefetch_off, w.evict_off, shift},
+                w.evict_pair, w.prefetch_off, w.evict_off, shift, owners ? plan->keep_owner : nullptr, ukey, M,
+                w.pair_start, (uint32_t)N, spos, w.iter_off, w.cuts, P},
         M, w.scan_partials64, AddOp(), uint64_t(0), stream)));
     const uint64_t* totals = w.scan_partials64 + scan_num_tiles(M);
 

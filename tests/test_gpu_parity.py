@@ -723,3 +723,32 @@ def test_step_captured_in_a_graph(bp):
         scratch.add_(1.0)                                    # eager work between the replays
         assert float(scratch.sum()) == (r + 1) * scratch.numel()
     assert torch.equal(tr.cache_w, want_w) and torch.equal(tr.cache_state, want_s)
+
+
+# ---------------------------------------------------------------------------------------------------
+# which logical trainer uses a row
+# ---------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("seed", range(3))
+def test_plan_trainer_marking(bp, seed):
+    """keep_owner of every (id, batch): the single trainer that looks the id up, or -1 / -2 for rows several trainers
+    share (deferred / needed by the next batch), for lookups dealt to P trainers by position."""
+    say(f"plan trainer marking seed={seed}")
+    rng = np.random.default_rng(700 + seed)
+    R, T = int(rng.integers(30, 500)), int(rng.integers(2, 25))
+    lens = rng.integers(0, 400, size=T)
+    off = np.zeros(T + 1, dtype=np.int64)
+    off[1:] = np.cumsum(lens)
+    ids = np.minimum(rng.zipf(1.2, size=int(off[-1])) - 1, R - 1).astype(np.int64)
+    for P in (1, 2, 8, 64):
+        even = np.stack([np.floor(np.arange(P + 1) * n / P) for n in lens]).astype(np.int64)        # equal shares
+        ragged = np.stack([np.concatenate([[0], np.sort(rng.integers(0, n + 1, size=P - 1)), [n]]) for n in lens]).astype(np.int64)
+        for cuts in (even, ragged):
+            got = bp.bp_oracle_plan(bp.make_config(R, 4 * R, 16, lookahead=5), dev(ids), off, trainer_cuts=cuts)
+            want = oracle.keep_owners(ids, off, R, cuts)
+            assert np.array_equal(got.keep_owner.cpu().numpy(), want)
+            if P == 1:
+                assert (want == 0).all()
+    with pytest.raises(bp.BagpipeError):                                # cuts that do not end at the batch's size
+        bad = even.copy()
+        bad[0, -1] += 1
+        bp.bp_oracle_plan(bp.make_config(R, 4 * R, 16, lookahead=5), dev(ids), off, trainer_cuts=bad)

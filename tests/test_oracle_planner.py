@@ -512,3 +512,34 @@ def test_plan_chunked_policy_small():
     # ample capacity: the configured lookahead everywhere, i.e. the plan of part A
     p2, L2 = oracle.plan_chunked(ids, off, R, L, R, 3)
     assert (L2 == L).all() and np.array_equal(p2.lookup_slots, oracle.plan(ids, off, R, L, R, L_eff=L).lookup_slots)
+
+
+# ---------------------------------------------------------------------------------------------------
+# which logical trainer uses a row (single-trainer marking, critical / deferred shared rows)
+# ---------------------------------------------------------------------------------------------------
+def test_keep_owners_by_hand_and_against_sets():
+    # batch 0: positions 0..5 hold ids 7 7 3 7 9 3, trainers own [0,2) [2,4) [4,6); batch 1: ids 3 3 5 5, cuts 0 2 2 4
+    ids = np.array([7, 7, 3, 7, 9, 3, 3, 3, 5, 5], dtype=np.int64)
+    off = np.array([0, 6, 10], dtype=np.int64)
+    cuts = np.array([[0, 2, 4, 6], [0, 2, 2, 4]], dtype=np.int64)
+    # keep list order: batch 0 ids 3, 7, 9; batch 1 ids 3, 5
+    # id 3 in batch 0: trainers 1 and 2, used again by batch 1 -> -2; id 7: trainers 0 and 1, not in batch 1 -> -1;
+    # id 9: trainer 2 alone; batch 1: id 3 trainer 0 alone, id 5 trainer 2 alone (trainer 1 owns nothing)
+    assert oracle.keep_owners(ids, off, 10, cuts).tolist() == [-2, -1, 2, 0, 2]
+    rng = np.random.default_rng(3)
+    for _ in range(5):
+        R, T, P = int(rng.integers(5, 40)), int(rng.integers(1, 8)), int(rng.integers(1, 6))
+        lens = rng.integers(0, 30, size=T)
+        off = np.zeros(T + 1, dtype=np.int64)
+        off[1:] = np.cumsum(lens)
+        ids = rng.integers(0, R, size=int(off[-1])).astype(np.int64)
+        cuts = np.stack([np.concatenate([[0], np.sort(rng.integers(0, n + 1, size=P - 1)), [n]]) for n in lens]).astype(np.int64)
+        got = oracle.keep_owners(ids, off, R, cuts).tolist()
+        want = []
+        for i in range(T):
+            b = ids[off[i]:off[i + 1]]
+            nxt = set(ids[off[i + 1]:off[i + 2]].tolist()) if i + 1 < T else set()
+            for g in sorted(set(b.tolist())):
+                ts = {int(np.searchsorted(cuts[i], p, side="right") - 1) for p in np.nonzero(b == g)[0]}
+                want.append(ts.pop() if len(ts) == 1 else (-2 if g in nxt else -1))
+        assert got == want
