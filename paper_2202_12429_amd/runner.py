@@ -15,6 +15,11 @@ Overlapped schedule (cache maintenance on a stream of its own, beside the traini
     trainer.end()                                                        # last write-backs ordered before the caller
 It needs free slots to fetch into while a batch trains: plan with cfg.reserve >= the misses of one batch.
 
+Streaming (the trace arrives chunk by chunk; synchronous schedule):
+    for every chunk: trainer.plan_chunk(ids_of_chunk_and_window_dev, offsets, n_emit)   # bp_oracle_plan_chunk
+                     for k in range(n_emit): maintain(k); forward(k); backward_update(k)
+    trainer.flush()
+
 The order of calls in the first loop is the synchronous schedule of Section 3.2: the write-backs of batch i-1 are applied before
 the prefetches of batch i, so a row is never fetched while an update to it is still only in the cache.
 With duplex=True (default) and a plan whose L_eff >= 2, maintain() uses bp_cache_apply_duplex (writes to and reads
@@ -77,6 +82,7 @@ class CachedEmbeddingTrainer:
     # ---- (1)
     def plan(self, ids_dev, iter_offsets, list_capacity: Optional[int] = None, workspace=None) -> B.Plan:
         self.iter_offsets = np.ascontiguousarray(iter_offsets, dtype=np.int64)
+        self._n_emit, self._plan_state, self._carried_evict = None, None, None
         self.plan_ = B.bp_oracle_plan(self.cfg, ids_dev, self.iter_offsets, list_capacity=list_capacity,
                                       workspace=workspace, grouping=self.grouping)
         self.close()
@@ -137,6 +143,8 @@ class CachedEmbeddingTrainer:
 
     # ---- (2b) the same maintenance, overlapped with training
     def begin(self, stream=None) -> None:
+        if self._n_emit:
+            raise RuntimeError("the overlapped schedule takes whole-trace plans (plan()), not chunks (plan_chunk())")
         if self._pipeline is None:
             self._pipeline = B.bp_pipeline_create(self.cfg, self.cache_w, self.cache_state, self.backing_w,
                                                   self.backing_state, self.plan_, self._stage)
