@@ -171,7 +171,8 @@ int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int64_t* iter
  * plan            as for bp_oracle_plan, with these differences: host arrays have n_emit + 1 (offsets) or n_emit
  *                 (occupancy) entries; offsets are positions in the device lists and need not start at 0 (the carried
  *                 rows' own entries come first); keep_ttl counts batches from the chunk's first batch; lookup_slots
- *                 and the grouping cover all n_iters batches given (those past n_emit are provisional);
+ *                 and the grouping cover all n_iters batches given, but past the n_emit-th batch their contents are
+ *                 unspecified (slots may be -1 there: the window is planned without a bound on its occupancy);
  *                 list_capacity >= n_unique_pairs, which counts the carried rows too; peak_occupancy and
  *                 min_capacity are taken over the emitted batches.
  * workspace       bp_oracle_plan_chunk_workspace_bytes(cfg, n_lookups, n_iters, with_grouping) bytes.

@@ -439,29 +439,36 @@ __global__ __launch_bounds__(kBlock) void plan_ring_jump_kernel(const uint64_t* 
 }
 
 // ---- 7. slots --------------------------------------------------------------------------------
+// par resolves a miss to a ring position below C, and ring0 (NULL: the identity) is what that position held when
+// planning started.  Only while the occupancy stays within C, though: in chunk mode the batches past the emitted ones
+// are planned with the chunk's lookahead without any bound on their occupancy, so their misses may ask for slots
+// that are freed only later; such a miss resolves to nothing below C and gets no slot (-1).  Those batches are never
+// reported.
+__device__ __forceinline__ int32_t resolved_slot(uint32_t p0, const int32_t* __restrict__ ring0, int64_t C) {
+    if ((int64_t)p0 >= C) return -1;
+    return ring0 ? ring0[p0] : (int32_t)p0;
+}
+
 __global__ __launch_bounds__(kBlock) void plan_pair_slots_kernel(uint32_t M, const uint32_t* __restrict__ chain,
                                                                  const uint32_t* __restrict__ missord,
                                                                  const uint32_t* __restrict__ par,
-                                                                 const int32_t* __restrict__ ring0,
+                                                                 const int32_t* __restrict__ ring0, int64_t C,
                                                                  int32_t* __restrict__ slot_of_pair) {
-    // par resolves every miss to a ring position below C; ring0 (NULL: the identity) is what that position held
-    // when planning started
     const uint32_t q = blockIdx.x * kBlock + threadIdx.x;
     if (q >= M) return;
-    const uint32_t p0 = par[missord[chain[q]]];
-    slot_of_pair[q] = ring0 ? ring0[p0] : (int32_t)p0;
+    slot_of_pair[q] = resolved_slot(par[missord[chain[q]]], ring0, C);
 }
 
 __global__ __launch_bounds__(kBlock) void plan_list_slots_kernel(const uint64_t* __restrict__ totals,
                                                                  const uint32_t* __restrict__ par,
                                                                  const uint32_t* __restrict__ evict_pair,
                                                                  const int32_t* __restrict__ slot_of_pair,
-                                                                 const int32_t* __restrict__ ring0,
+                                                                 const int32_t* __restrict__ ring0, int64_t C,
                                                                  int32_t* __restrict__ prefetch_slots,
                                                                  int32_t* __restrict__ evict_slots) {
     const uint32_t n_miss = (uint32_t)*totals, n_evict = (uint32_t)(*totals >> 32);
     const uint32_t x = blockIdx.x * kBlock + threadIdx.x;
-    if (x < n_miss) prefetch_slots[x] = ring0 ? ring0[par[x]] : (int32_t)par[x];
+    if (x < n_miss) prefetch_slots[x] = resolved_slot(par[x], ring0, C);
     if (x < n_evict) evict_slots[x] = slot_of_pair[evict_pair[x]];
 }
 
@@ -950,9 +957,9 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
 
     // ---- 7. slots
     BP_LAUNCH(K_PLAN_SLOTS, plan_pair_slots_kernel, grid_for(M), dim3(kBlock), 0, stream, M, (const uint32_t*)w.chain,
-              (const uint32_t*)w.missord, (const uint32_t*)w.par, ring0, w.slot_of_pair);
+              (const uint32_t*)w.missord, (const uint32_t*)w.par, ring0, C, w.slot_of_pair);
     BP_LAUNCH(K_PLAN_SLOTS, plan_list_slots_kernel, grid_for(M), dim3(kBlock), 0, stream, totals, (const uint32_t*)w.par,
-              (const uint32_t*)w.evict_pair, (const int32_t*)w.slot_of_pair, ring0, plan->prefetch_slots,
+              (const uint32_t*)w.evict_pair, (const int32_t*)w.slot_of_pair, ring0, C, plan->prefetch_slots,
               plan->evict_slots);
     if (!grouping && N_real)      // with grouping the slot map is written from the batch-grouped order (step 8)
         BP_LAUNCH(K_PLAN_SLOTS, plan_lookup_slots_kernel, grid_for(N), dim3(kBlock), 0, stream, N, (uint32_t)R0, spos,
