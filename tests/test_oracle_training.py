@@ -123,6 +123,30 @@ def test_rowwise_adagrad_closed_form_and_d1_equivalence():
     assert np.array_equal(Wa, Wb) and np.array_equal(Sa[:, 0], Sb)
 
 
+def test_rowwise_adagrad_equals_torch_adagrad_on_constant_rows():
+    """When every upstream gradient row is constant along the embedding dimension, so is every summed row gradient:
+    the mean of its squares is the square of each element, the row's one state value equals every element's state,
+    and row-wise Adagrad is torch.optim.Adagrad.  Several iterations, duplicates inside and across bags, multi-hot."""
+    D, rows = 8, 40
+    W, _, _, rng = rand_problem(7, rows=rows, D=D)
+    lr, eps = 0.02, 1e-8
+    emb = torch_bag(W.astype(np.float64), None, None)
+    opt = torch.optim.Adagrad(emb.parameters(), lr=lr, eps=eps, initial_accumulator_value=0.0, lr_decay=0.0)
+    Wo, S = W.copy(), np.zeros(rows, dtype=np.float32)
+    for it in range(6):
+        _, idx, off, r2 = rand_problem(200 + it, rows=rows, D=D)
+        g = np.repeat(r2.standard_normal((len(off) - 1, 1)).astype(np.float32), D, axis=1)
+        oracle.train_iter(Wo, S, D, oracle.F32, oracle.ADAGRAD_ROWWISE, lr, eps, idx, off, g)
+        opt.zero_grad()
+        emb(torch.from_numpy(idx), torch.from_numpy(off)).backward(torch.from_numpy(g).double())
+        opt.step()
+    np.testing.assert_allclose(Wo, emb.weight.detach().numpy(), rtol=1e-5, atol=1e-7)
+    st = opt.state[emb.weight]["sum"].numpy()
+    np.testing.assert_allclose(S, st[:, 0], rtol=1e-5, atol=1e-9)
+    assert np.allclose(st, st[:, :1])                       # torch's state is indeed constant along a row
+    assert np.abs(Wo - W).max() > 1e-3
+
+
 def test_bf16_storage_rounds_to_nearest_even():
     rng = np.random.default_rng(3)
     w32 = rng.uniform(-0.05, 0.05, size=(64, 8)).astype(np.float32)
