@@ -24,9 +24,13 @@
  * once on store; with bf16 storage the stored value is a quantised code and the update is carried out in
  * fp32, the arithmetic type fixed for that workload (see update_row_bf16).
  * Parity pins: tests/test_oracle_*.py (paper's worked example, brute force from the plain
- * definitions, invariants, torch CPU library routines).  Row-wise Adagrad is pinned only by a
- * closed form on one row and by its equality with element-wise Adagrad at D = 1: parity unpinned
- * beyond that.
+ * definitions, invariants, torch CPU library routines).  Row-wise Adagrad is pinned by a closed form
+ * on one row, by its equality with element-wise Adagrad at D = 1 and against torch's Adagrad on
+ * gradients that are constant along a row: parity unpinned for gradients that vary along a row
+ * beyond the one-row closed form.
+ * Further parts, each with its own pins: the lookahead when none is configured (orc_auto_lookahead),
+ * a lookahead that changes from batch to batch (orc_plan_stream), the grouping of a batch's lookups for
+ * the backward pass (orc_group_lookups), the trainers that use a row (orc_keep_owners).
  */
 #include <math.h>
 #include <stdint.h>
