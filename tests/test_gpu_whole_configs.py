@@ -205,3 +205,38 @@ def test_plan_whole_trace_configs_3_and_4(index):
     assert np.array_equal(plan.grouped_lookups.cpu().numpy(), gl)
     assert np.array_equal(plan.item_starts.cpu().numpy().view(np.uint32), st)
     assert np.array_equal(plan.split_starts.cpu().numpy().view(np.uint32), sp)
+
+
+@pytest.mark.timeout(900)
+def test_plan_chunked_config2():
+    """configs[2] planned as a stream: chunks of 50 batches with a lookahead of 63 (each call sees 62 batches past its
+    chunk, carries ~0.6 M resident rows) against the oracle's whole-trace plan with that lookahead: slot map, lists
+    and carried row counts bit for bit, at the benchmark's size."""
+    import paper_2202_12429_amd as bp
+    cfg = workloads.CONFIGS[2]
+    say("config 2 planned in chunks of 50 batches")
+    trace = workloads.make_trace(cfg)
+    L, n_emit, T, off = 63, 50, cfg.iterations, trace.iter_offsets
+    t0 = time.time()
+    want = oracle.plan(trace.ids, off, cfg.total_rows, L, cfg.capacity, L_eff=L)
+    say(f"  oracle plan with lookahead {L}: peak {want.peak} ({time.time() - t0:.1f} s)")
+    assert want.peak <= cfg.capacity
+    c = bp.make_config(cfg.total_rows, cfg.capacity, cfg.dim, cfg.weight_dtype, cfg.optimizer, L, cfg.lr, cfg.eps)
+    ids_dev = torch.from_numpy(trace.ids).cuda()
+    state = None
+    for a in range(0, T, n_emit):
+        b, hi = min(T, a + n_emit), min(T, a + n_emit + L - 1)
+        got, state = bp.bp_oracle_plan_chunk(c, ids_dev[off[a]:off[hi]], off[a:hi + 1] - off[a], b - a, state, grouping=True)
+        assert got.L_eff == L
+        assert np.array_equal(got.occupancy, want.occ[a:b])
+        n_em = int(off[b] - off[a])
+        assert np.array_equal(got.lookup_slots[:n_em].cpu().numpy(), want.lookup_slots[off[a]:off[b]])
+        for name in ("prefetch", "evict"):
+            g0, g1 = int(getattr(got, name + "_offsets")[0]), int(getattr(got, name + "_offsets")[-1])
+            w0, w1 = int(getattr(want, name + "_off")[a]), int(getattr(want, name + "_off")[b])
+            assert np.array_equal(np.diff(getattr(got, name + "_offsets")), np.diff(getattr(want, name + "_off")[a:b + 1]))
+            assert np.array_equal(getattr(got, name + "_ids")[g0:g1].cpu().numpy(), getattr(want, name + "_ids")[w0:w1]), name
+            assert np.array_equal(getattr(got, name + "_slots")[g0:g1].cpu().numpy(), getattr(want, name + "_slots")[w0:w1]), name
+        assert state.n_resident == want.prefetch_off[b] - want.evict_off[b]
+        say(f"  batches {a}..{b - 1}: lists, slot map and {state.n_resident} carried rows match")
+    assert state.n_resident == 0
