@@ -15,6 +15,10 @@ lookups/s with ids, upstream gradients and the backing table resident in HBM bef
 the library's own stream beside the training step (bp_pipeline_*); the other schedule of either placement is
 reported next to it.
 
+Every run executes the same K timed steps three times: with events on every kernel (breakdown), with events on the
+dominant kernel only (`roofline`: its duration inside the running loop) and with no events (`value`: a launch that
+carries events costs a few microseconds on the host and on the stream); both loop times are reported.
+
 Prints ONE JSON line.  Extra objects: `roofline` (dominant kernel, algorithmic bytes / HIP-event duration against
 the 8 TB/s HBM peak) and `cpu_baseline` (the CPU oracle, single thread, on a bounded sample of the same workload).
 """
@@ -287,14 +291,15 @@ def main() -> int:
                 trainer.release(i)
 
         def run_pass(profile_kernels):
-            """Warm-up W steps, then K timed steps.  profile_kernels: [] = every kernel bracketed, or a list."""
+            """Warm-up W steps, then K timed steps.  profile_kernels: [] = every kernel carries events, a list = only
+            those kernels, None = no events at all."""
             if overlapped:
                 trainer.begin()
             for i in range(W):
                 step(i)
             torch.cuda.synchronize()
             bp.bp_profile_select(profile_kernels or None)
-            bp.bp_profile_enable(True)
+            bp.bp_profile_enable(profile_kernels is not None)
             t0 = time.perf_counter()
             for i in range(W, W + K):
                 step(i)
@@ -317,8 +322,11 @@ def main() -> int:
         _, prof_all = run_pass([])
         hot = {k: v for k, v in prof_all.items() if k in ("embbag_fwd", "bwd_reduce_update")}
         dominant = max(hot, key=lambda k: hot[k][1])
-        # pass B: the timed region proper; only the dominant kernel is bracketed (two event records per step)
-        t_loop, prof_dom = run_pass([dominant])
+        # pass B: the same K steps with events on the dominant kernel only -> its duration inside the running loop
+        t_loop_events, prof_dom = run_pass([dominant])
+        # pass C: the same K steps with no events at all -> throughput.  A launch that carries events costs ~10 us more
+        # on the host and ~4 us on the stream: 5 % of a configs[2] step, a quarter of a step of the small configs.
+        t_loop, _ = run_pass(None)
 
         def per_step(names):
             return sum(prof_all[k][1] for k in names if k in prof_all) / K
@@ -331,7 +339,8 @@ def main() -> int:
             "bwd_combine_update": per_step(["bwd_combine_update"]),
         }
         t_total = t_loop + t_plan * K / T                      # the plan's share of these K batches
-        return dict(t_loop=t_loop, t_total=t_total, dominant=dominant, prof_dom=prof_dom[dominant], kernel_ms=kernel_ms)
+        return dict(t_loop=t_loop, t_loop_events=t_loop_events, t_total=t_total, dominant=dominant,
+                    prof_dom=prof_dom[dominant], kernel_ms=kernel_ms)
 
     res = {key: measure(tr_, key[1] == "overlapped") for key, tr_ in trainers.items()
            if not args.value_only or key == (main_place, main_sched)}
@@ -400,6 +409,7 @@ def main() -> int:
         "cpu_baseline": cpu,
         "plan": {"ms": t_plan * 1e3, "ids_per_s": trace.n_lookups / t_plan, "n_lookups": trace.n_lookups},
         "loop_ms_per_step": m["t_loop"] / K * 1e3,
+        "loop_ms_per_step_with_events_on_dominant_kernel": m["t_loop_events"] / K * 1e3,
         "kernel_ms_per_step": kernel_ms,
         "fwd_bwd_update_lookups_per_s_kernel_time": n_mean / (fbu_ms * 1e-3) if fbu_ms > 0 else None,
         "other_schedule": None if args.value_only else dict(
