@@ -95,6 +95,7 @@ struct UpdateParams {
     float lr, eps;
     int lpr;
     int dim;
+    uint32_t bags;      // rows of the upstream gradient: a bag number beyond them reads row 0 instead
 };
 
 // Running sum of one 16-byte piece of gradient rows.  Sums are carried in fp64 and rounded to fp32 once,
@@ -254,6 +255,7 @@ __global__ __launch_bounds__(kRowBlock) void bwd_reduce_update_kernel(const uint
         const bool steps_aside = !head && tail && (rp & kItemHead);    // second of two: the first item does it all
         const uint32_t last = takes_next ? (r2 & kItemPos) : end;
         const bool whole = (head && tail) || takes_next;
+        if (start >= n || last > n || last < start) continue;           // a malformed record reads nothing
         const uint32_t slot = keys[start];
         uint32_t idx[4];
 #pragma unroll
@@ -269,7 +271,7 @@ __global__ __launch_bounds__(kRowBlock) void bwd_reduce_update_kernel(const uint
                 Piece<BF16> t[4];
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    if (p + j < last) t[j].load_f32(grad + (size_t)idx[j] * u.dim, c);
+                    if (p + j < last) t[j].load_f32(grad + (size_t)min(idx[j], u.bags - 1u) * u.dim, c);   // clamped where it is used: the index load stays in flight until then
 #pragma unroll
                 for (int j = 0; j < 4; ++j) idx[j] = p + 4 + j < last ? bag_of[p + 4 + j] : 0u;
 #pragma unroll
@@ -440,9 +442,11 @@ struct BwdLaunch {
     void* cache_w;
     void* cache_s;
     hipStream_t stream;
+    int64_t bags;
     template <int GW, bool BF16>
     int run() {
-        UpdateParams u{cfg->optimizer, cfg->lr, cfg->eps, (int)(row_bytes(cfg) / 16), cfg->dim};
+        UpdateParams u{cfg->optimizer, cfg->lr, cfg->eps, (int)(row_bytes(cfg) / 16), cfg->dim,
+                       (uint32_t)(bags > 0 ? bags : 1)};
         const int groups_per_block = kRowBlock / GW;
         const int64_t items_bound = n_items ? n : (int64_t)n_items_host;     // at most one item per lookup
         int64_t blocks = ceil_div(items_bound, groups_per_block);
@@ -522,7 +526,7 @@ BP_EXPORT int bp_embbag_bwd_update(const bp_config* cfg, void* cache_w, void* ca
                                                                     w.scan_partials, AddOp(), 0u, stream)));
     const uint32_t* n_items = w.scan_partials + scan_num_tiles(n);
 
-    BwdLaunch l{cfg, w.partial, skeys, sbags, w.item_start, n_items, 0u, nullptr, 0u, n, grad_out, cache_w, cache_state, stream};
+    BwdLaunch l{cfg, w.partial, skeys, sbags, w.item_start, n_items, 0u, nullptr, 0u, n, grad_out, cache_w, cache_state, stream, bags};
     return dispatch_row((int)(row_bytes(cfg) / 16), cfg->weight_dtype == BP_BF16, l);
 }
 
@@ -588,6 +592,6 @@ BP_EXPORT int bp_embbag_bwd_update_grouped(const bp_config* cfg, void* cache_w, 
         bag_of = w.bag_of;
     }
     BwdLaunch l{cfg, w.partial, reinterpret_cast<const uint32_t*>(grouped_slots), bag_of, item_starts, nullptr,
-                (uint32_t)n_items, split_starts, (uint32_t)n_split, n, grad_out, cache_w, cache_state, stream};
+                (uint32_t)n_items, split_starts, (uint32_t)n_split, n, grad_out, cache_w, cache_state, stream, bags};
     return dispatch_row((int)(row_bytes(cfg) / 16), cfg->weight_dtype == BP_BF16, l);
 }

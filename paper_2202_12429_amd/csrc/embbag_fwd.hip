@@ -13,8 +13,9 @@ namespace {
 template <int GW, bool BF16>
 __global__ __launch_bounds__(kRowBlock) void embbag_fwd_kernel(const uint4* __restrict__ cache_w,
                                                                const int32_t* __restrict__ slots,
-                                                               const int64_t* __restrict__ bag_off, int64_t bags, int64_t C,
-                                                               int lpr, int dim, float* __restrict__ out) {
+                                                               const int64_t* __restrict__ bag_off, int64_t bags,
+                                                               int64_t n, int64_t C, int lpr, int dim,
+                                                               float* __restrict__ out) {
     const int64_t bag = ((int64_t)blockIdx.x * kRowBlock + threadIdx.x) / GW;
     const int c = threadIdx.x % GW;
     if (bag >= bags || c >= lpr) return;
@@ -22,7 +23,9 @@ __global__ __launch_bounds__(kRowBlock) void embbag_fwd_kernel(const uint4* __re
     acc.zero();
     {
         int64_t k = bag_off[bag];
-        const int64_t end = bag_off[bag + 1];
+        int64_t end = bag_off[bag + 1];
+        if (k < 0) k = 0;                           // offsets that point outside the lookups read nothing there
+        if (end > n) end = n;
         for (; k + 4 <= end; k += 4) {              // four independent row loads in flight, added in order
             uint32_t s[4];
             uint4 raw[4];
@@ -89,7 +92,7 @@ struct FwdLaunch {
     const void* cache_w;
     const int32_t* slots;
     const int64_t* bag_off;
-    int64_t bags;
+    int64_t bags, n_lookups;
     float* out;
     hipStream_t stream;
     template <int GW, bool BF16>
@@ -104,7 +107,7 @@ struct FwdLaunch {
         }
         const dim3 grid((unsigned)ceil_div(bags * GW, kRowBlock));
         BP_LAUNCH(K_FWD, (embbag_fwd_kernel<GW, BF16>), grid, dim3(kRowBlock), 0, stream, (const uint4*)cache_w, slots,
-                  bag_off, bags, cfg->capacity, lpr, cfg->dim, out);
+                  bag_off, bags, n_lookups, cfg->capacity, lpr, cfg->dim, out);
         return BP_OK;
     }
 };
@@ -124,6 +127,6 @@ BP_EXPORT int bp_embbag_fwd(const bp_config* cfg, const void* cache_w, const int
         return fail(BP_ERR_INVALID_ARG, "bag_offsets is NULL but n_lookups %lld != bags %lld", (long long)n_lookups, (long long)bags);
     if (!cache_w || !out || (n_lookups && !lookup_slots)) return fail(BP_ERR_INVALID_ARG, "NULL pointer");
     if (((uintptr_t)cache_w | (uintptr_t)out) & 15) return fail(BP_ERR_INVALID_ARG, "cache_w and out must be 16-byte aligned");
-    FwdLaunch l{cfg, cache_w, lookup_slots, bag_offsets, bags, out, (hipStream_t)stream};
+    FwdLaunch l{cfg, cache_w, lookup_slots, bag_offsets, bags, n_lookups, out, (hipStream_t)stream};
     return dispatch_row((int)(row_bytes(cfg) / 16), cfg->weight_dtype == BP_BF16, l);
 }
