@@ -263,6 +263,40 @@ def test_cache_apply(bp, D, dtype, optimizer, pinned):
     assert np.array_equal(cache_numpy(hw_d.cpu()), hw_o) and np.array_equal(cache_numpy(cw_d.cpu()), cw_o)
 
 
+def test_cache_stage_then_apply_staged(bp):
+    """The two halves of the duplex maintenance called on their own, with unrelated work on the cache between them
+    (the staged rows' slots are overwritten before the write-back): backing table and cache as the oracle's."""
+    say("cache_stage + cache_apply_staged")
+    R, C, D = 9001, 800, 48
+    rng = np.random.default_rng(21)
+    hw, cw = random_cache(R, D, "f32", 31), random_cache(C, D, "f32", 32)
+    hs = rng.uniform(0, 1, size=(R, D)).astype(np.float32)
+    cs = rng.uniform(1, 2, size=(C, D)).astype(np.float32)
+    e_slots = rng.permutation(C)[:300].astype(np.int32)
+    e_ids = rng.permutation(R)[:300].astype(np.int64)
+    p_slots = np.concatenate([e_slots[:200], np.setdiff1d(np.arange(C), e_slots)[:100]]).astype(np.int32)
+    p_ids = np.setdiff1d(np.arange(R), e_ids)[:300].astype(np.int64)
+    cfg = bp.make_config(R, C, D, "f32", "adagrad")
+    hw_d, cw_d = hw.clone().pin_memory(), cw.cuda()
+    hs_d, cs_d = torch.from_numpy(hs.copy()).pin_memory(), torch.from_numpy(cs.copy()).cuda()
+    ws = torch.empty(bp.bp_cache_apply_duplex_workspace_bytes(cfg, 300), dtype=torch.uint8, device="cuda")
+    bp.bp_cache_stage(cfg, cw_d, cs_d, dev(e_slots), ws)
+    cw_d[torch.from_numpy(e_slots[:200].astype(np.int64)).cuda()] = 7.0        # the freed slots are reused at once
+    bp.bp_cache_apply_staged(cfg, cw_d, cs_d, hw_d, hs_d, dev(e_ids), dev(e_slots), ws, dev(p_ids), dev(p_slots))
+    torch.cuda.synchronize()
+    hw_o, cw_o, hs_o, cs_o = hw.numpy().copy(), cw.numpy().copy(), hs.copy(), cs.copy()
+    oracle.cache_apply(cw_o, cs_o, hw_o, hs_o, D, oracle.F32, oracle.ADAGRAD, e_ids, e_slots, p_ids, p_slots)
+    assert np.array_equal(hw_d.numpy(), hw_o) and np.array_equal(hs_d.numpy(), hs_o)
+    assert np.array_equal(cw_d.cpu().numpy(), cw_o) and np.array_equal(cs_d.cpu().numpy(), cs_o)
+    # argument errors: staging too small, misaligned
+    with pytest.raises(bp.BagpipeError) as e:
+        bp.bp_cache_stage(cfg, cw_d, cs_d, dev(e_slots), ws[:256])
+    assert e.value.status == -3
+    with pytest.raises(bp.BagpipeError) as e:
+        bp.bp_cache_apply_staged(cfg, cw_d, cs_d, hw_d, hs_d, dev(e_ids), dev(e_slots), ws[16:], dev(p_ids), dev(p_slots))
+    assert e.value.status == -1
+
+
 # ---------------------------------------------------------------------------------------------------
 # planner
 # ---------------------------------------------------------------------------------------------------
