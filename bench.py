@@ -238,7 +238,7 @@ def main() -> int:
     for (place, sched), tr_ in trainers.items():                     # one plan per schedule serves both placements
         src = first if sched == "overlapped" else first_sync
         if tr_ is not src:
-            tr_.plan_, tr_.iter_offsets, tr_._stage = src.plan_, src.iter_offsets, src._stage
+            tr_.plan_, tr_.iter_offsets, tr_._stage, tr_._early = src.plan_, src.iter_offsets, src._stage, src._early
     t_plan = float(np.median(plan_times))
     del ws
     early = bp.bp_pipeline_early_counts(plan.prefetch_offsets, plan.evict_offsets, capacity, plan.L_eff)

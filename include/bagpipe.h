@@ -242,6 +242,24 @@ int bp_cache_apply_staged(const bp_config* cfg, void* cache_w, void* cache_state
                           size_t staging_bytes, const int64_t* prefetch_ids, const int32_t* prefetch_slots,
                           int64_t n_prefetch, void* stream);
 
+/*
+ * The same maintenance in ONE launch and without a staging area, for lists that come from the planner's FIFO ring:
+ * there the prefetches of a batch that land in slots freed by the previous batch's evictions are the last
+ * n_prefetch - n_early entries of the prefetch list and take those slots in the evictions' own order (prefetch entry
+ * n_early + k gets the slot of evict entry k), so one lane group moves the evicted row out of a slot and the fetched
+ * row into it, one after the other.  n_early = the leading prefetch entries whose slots were free before: for batch
+ * i of a whole-trace plan, clamp(capacity + evict_offsets[i-1] - prefetch_offsets[i], 0, misses of i) (the evictions
+ * are those of batch i-1; evict_offsets[i-1] counts the evictions of the batches before it).
+ * Preconditions: no id in both lists (L_eff >= 2), and the pairing above.  A pair whose slots differ is left alone
+ * (its slot keeps the evicted row, which is still written back) and *mismatch_flag (device, may be NULL; the caller
+ * clears it) is set to 1: a set flag means the cache is not what the plan says.
+ * Other arguments and error behaviour as for bp_cache_apply.  Asynchronous on `stream`.
+ */
+int bp_cache_apply_handoff(const bp_config* cfg, void* cache_w, void* cache_state, void* backing_w, void* backing_state,
+                           const int64_t* evict_ids, const int32_t* evict_slots, int64_t n_evict,
+                           const int64_t* prefetch_ids, const int32_t* prefetch_slots, int64_t n_prefetch,
+                           int64_t n_early, uint32_t* mismatch_flag, void* stream);
+
 /* ------------------------------------------------------------------------------------------------
  * (2b) Cache maintenance overlapped with training (Section 3.2: the lookahead lets rows be fetched before the
  * batch that needs them; Section 3.4: the trainer's cache is maintained beside the training step, on slots the

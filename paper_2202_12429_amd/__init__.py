@@ -9,7 +9,7 @@ raises if libbagpipe_hip.so has not been built (python -m paper_2202_12429_amd.b
 from .binding import (  # noqa: F401
     BF16, F32, SGD, ADAGRAD, ADAGRAD_ROWWISE,
     BagpipeError, Plan, bp_config, library_path, load_library, make_config,
-    bp_oracle_plan, bp_oracle_plan_workspace_bytes, bp_oracle_plan_chunk, bp_oracle_plan_chunk_workspace_bytes, PlanState, bp_cache_apply, bp_cache_apply_duplex, bp_cache_apply_duplex_workspace_bytes, bp_cache_stage, bp_cache_apply_staged,
+    bp_oracle_plan, bp_oracle_plan_workspace_bytes, bp_oracle_plan_chunk, bp_oracle_plan_chunk_workspace_bytes, PlanState, bp_cache_apply, bp_cache_apply_duplex, bp_cache_apply_duplex_workspace_bytes, bp_cache_stage, bp_cache_apply_staged, bp_cache_apply_handoff,
     bp_pipeline_early_counts, bp_pipeline_create, bp_pipeline_destroy, bp_pipeline_early, bp_pipeline_begin,
     bp_pipeline_acquire, bp_pipeline_release, bp_pipeline_end,
     bp_embbag_fwd,

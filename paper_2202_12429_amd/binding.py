@@ -77,6 +77,7 @@ def load_library():
     lib.bp_cache_apply.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, i64, vp, vp, i64, vp]
     lib.bp_cache_apply_duplex_workspace_bytes.argtypes = [cfgp, i64, ctypes.POINTER(sz)]
     lib.bp_cache_apply_duplex.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, i64, vp, vp, i64, vp, sz, vp]
+    lib.bp_cache_apply_handoff.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, i64, vp, vp, i64, i64, vp, vp]
     lib.bp_cache_stage.argtypes = [cfgp, vp, vp, vp, i64, vp, sz, vp]
     lib.bp_cache_apply_staged.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, i64, vp, sz, vp, vp, i64, vp]
     lib.bp_pipeline_early_counts.argtypes = [vp, vp, i32, i64, i32, vp]
@@ -109,6 +110,7 @@ def load_library():
                  "bp_embbag_bwd_update_workspace_bytes", "bp_embbag_bwd_update", "bp_version",
                  "bp_embbag_bwd_update_grouped_workspace_bytes", "bp_embbag_bwd_update_grouped",
                  "bp_cache_apply_duplex_workspace_bytes", "bp_cache_apply_duplex", "bp_cache_stage",
+                 "bp_cache_apply_handoff",
                  "bp_cache_apply_staged", "bp_profile_enable", "bp_oracle_plan_chunk_workspace_bytes",
                  "bp_oracle_plan_chunk", "bp_pipeline_early_counts", "bp_pipeline_create",
                  "bp_pipeline_destroy", "bp_pipeline_early", "bp_pipeline_begin", "bp_pipeline_acquire",
@@ -366,6 +368,19 @@ def bp_cache_apply_duplex(cfg: bp_config, cache_w, cache_state, backing_w, backi
         _ptr(evict_ids) if n_e else None, _ptr(evict_slots) if n_e else None, n_e,
         _ptr(prefetch_ids) if n_p else None, _ptr(prefetch_slots) if n_p else None, n_p,
         _ptr(workspace), 0 if workspace is None else int(workspace.numel()), _stream(stream)))
+
+
+def bp_cache_apply_handoff(cfg: bp_config, cache_w, cache_state, backing_w, backing_state, evict_ids, evict_slots,
+                           prefetch_ids, prefetch_slots, n_early: int, mismatch_flag=None, stream=None) -> None:
+    """Maintenance in one launch for lists of a FIFO plan: the last n_prefetch - n_early prefetches take the slots of
+    the first evictions, in order.  mismatch_flag: uint32/int32 device tensor of one element, set to 1 on a bad pair."""
+    n_e = 0 if evict_ids is None else int(evict_ids.numel())
+    n_p = 0 if prefetch_ids is None else int(prefetch_ids.numel())
+    _check(load_library().bp_cache_apply_handoff(
+        ctypes.byref(cfg), _ptr(cache_w), _ptr(cache_state), _ptr(backing_w), _ptr(backing_state),
+        _ptr(evict_ids) if n_e else None, _ptr(evict_slots) if n_e else None, n_e,
+        _ptr(prefetch_ids) if n_p else None, _ptr(prefetch_slots) if n_p else None, n_p, int(n_early),
+        _ptr(mismatch_flag), _stream(stream)))
 
 
 def bp_cache_stage(cfg: bp_config, cache_w, cache_state, evict_slots, staging, stream=None) -> None:

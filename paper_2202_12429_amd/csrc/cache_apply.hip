@@ -107,6 +107,58 @@ __global__ __launch_bounds__(kRowBlock) void cache_duplex_kernel(uint4* __restri
     }
 }
 
+// Maintenance in one launch without a staging area.  With the FIFO ring the prefetches of a step that land in slots
+// freed by the same step's evictions are the tail of the prefetch list, and they take those slots in the evictions'
+// own order: prefetch entry n_early + k gets the slot of evict entry k.  Lane group k therefore moves the evicted row
+// out and the fetched row in, one after the other, through its registers; nobody else touches that slot in this
+// step.  The other evictions (k >= n_late) and the early prefetches (slots that were free before) are plain copies.
+template <int GW>
+__global__ __launch_bounds__(kRowBlock) void cache_handoff_kernel(uint4* __restrict__ cache_w, uint4* __restrict__ cache_s,
+                                                                  uint4* __restrict__ back_w, uint4* __restrict__ back_s,
+                                                                  const int64_t* __restrict__ e_ids,
+                                                                  const int32_t* __restrict__ e_slots, int64_t n_e,
+                                                                  const int64_t* __restrict__ p_ids,
+                                                                  const int32_t* __restrict__ p_slots, int64_t n_p,
+                                                                  int64_t n_early, int64_t R, int64_t C, int lpr, int slpr,
+                                                                  int rowwise, uint32_t* __restrict__ mismatch) {
+    const int c = threadIdx.x % GW;
+    const int64_t stride = (int64_t)gridDim.x * (kRowBlock / GW);
+    const int64_t n_late = n_p - n_early;
+    // units: [0, n_e) the evictions (the first n_late of them followed by their paired fetch), then the early fetches
+    for (int64_t x = ((int64_t)blockIdx.x * kRowBlock + threadIdx.x) / GW; x < n_e + n_early; x += stride) {
+        if (x < n_e) {
+            const int64_t g = e_ids[x];
+            const int64_t s = e_slots[x];
+            const bool ok = g >= 0 && g < R && s >= 0 && s < C;
+            if (ok) {
+                if (c < lpr) back_w[g * lpr + c] = cache_w[s * lpr + c];
+                for (int q = c; q < slpr; q += GW) back_s[g * slpr + q] = cache_s[s * slpr + q];
+                if (rowwise && c == 0) reinterpret_cast<float*>(back_s)[g] = reinterpret_cast<const float*>(cache_s)[s];
+            }
+            if (x >= n_late) continue;
+            const int64_t g2 = p_ids[n_early + x];
+            const int64_t s2 = p_slots[n_early + x];
+            if (s2 != s) {                       // not the pairing of a FIFO plan: leave the slot alone and say so
+                if (c == 0 && mismatch) atomicOr(mismatch, 1u);
+                continue;
+            }
+            if (g2 < 0 || g2 >= R || !ok) continue;
+            // the reads of the evicted row above have returned before these writes are issued: same lanes, same addresses
+            if (c < lpr) cache_w[s * lpr + c] = back_w[g2 * lpr + c];
+            for (int q = c; q < slpr; q += GW) cache_s[s * slpr + q] = back_s[g2 * slpr + q];
+            if (rowwise && c == 0) reinterpret_cast<float*>(cache_s)[s] = reinterpret_cast<const float*>(back_s)[g2];
+        } else {
+            const int64_t m = x - n_e;
+            const int64_t g = p_ids[m];
+            const int64_t s = p_slots[m];
+            if (g < 0 || g >= R || s < 0 || s >= C) continue;
+            if (c < lpr) cache_w[s * lpr + c] = back_w[g * lpr + c];
+            for (int q = c; q < slpr; q += GW) cache_s[s * slpr + q] = back_s[g * slpr + q];
+            if (rowwise && c == 0) reinterpret_cast<float*>(cache_s)[s] = reinterpret_cast<const float*>(back_s)[g];
+        }
+    }
+}
+
 inline dim3 capped_grid(int64_t threads, int64_t max_blocks) {
     int64_t blocks = ceil_div(threads, kRowBlock);
     if (max_blocks > 0 && blocks > max_blocks) blocks = max_blocks;
@@ -290,5 +342,55 @@ BP_EXPORT int bp_cache_apply_staged(const bp_config* cfg, void* cache_w, void* c
     DuplexLaunch l{cfg, cache_w, cache_state, backing_w, backing_state, st,
                    st ? (char*)st + stage_w_bytes(cfg, n_evict) : nullptr, evict_ids, evict_slots, n_evict, prefetch_ids,
                    prefetch_slots, n_prefetch, (hipStream_t)stream, false, true, g_cache_grid_cap};
+    return dispatch_row((int)(row_bytes(cfg) / 16), false, l);
+}
+
+namespace bp {
+namespace {
+struct HandoffLaunch {
+    const bp_config* cfg;
+    void *cache_w, *cache_s, *back_w, *back_s;
+    const int64_t* e_ids;
+    const int32_t* e_slots;
+    int64_t n_e;
+    const int64_t* p_ids;
+    const int32_t* p_slots;
+    int64_t n_p, n_early;
+    uint32_t* mismatch;
+    hipStream_t stream;
+    template <int GW, bool BF16>
+    int run() {
+        const int lpr = (int)(row_bytes(cfg) / 16);
+        const int slpr = cfg->optimizer == BP_ADAGRAD ? cfg->dim / 4 : 0;
+        const int rowwise = cfg->optimizer == BP_ADAGRAD_ROWWISE;
+        BP_LAUNCH(K_CACHE_DUPLEX, (cache_handoff_kernel<GW>), capped_grid((n_e + n_early) * GW, g_cache_grid_cap),
+                  dim3(kRowBlock), 0, stream, (uint4*)cache_w, (uint4*)cache_s, (uint4*)back_w, (uint4*)back_s, e_ids,
+                  e_slots, n_e, p_ids, p_slots, n_p, n_early, cfg->total_rows, cfg->capacity, lpr, slpr, rowwise,
+                  mismatch);
+        return BP_OK;
+    }
+};
+}  // namespace
+}  // namespace bp
+
+BP_EXPORT int bp_cache_apply_handoff(const bp_config* cfg, void* cache_w, void* cache_state, void* backing_w,
+                                     void* backing_state, const int64_t* evict_ids, const int32_t* evict_slots,
+                                     int64_t n_evict, const int64_t* prefetch_ids, const int32_t* prefetch_slots,
+                                     int64_t n_prefetch, int64_t n_early, uint32_t* mismatch_flag, void* stream) {
+    BP_TRY(check_config(cfg));
+    if (n_evict < 0 || n_prefetch < 0) return fail(BP_ERR_INVALID_ARG, "negative list length");
+    if (n_early < 0 || n_early > n_prefetch || n_prefetch - n_early > n_evict)
+        return fail(BP_ERR_INVALID_ARG, "n_early %lld: need 0 <= n_early <= n_prefetch and n_prefetch - n_early <= n_evict",
+                    (long long)n_early);
+    if (n_evict + n_prefetch == 0) return BP_OK;
+    if (!cache_w || !backing_w) return fail(BP_ERR_INVALID_ARG, "cache_w or backing_w is NULL");
+    if (cfg->optimizer != BP_SGD && (!cache_state || !backing_state))
+        return fail(BP_ERR_INVALID_ARG, "optimizer state pointers are NULL");
+    if (((uintptr_t)cache_w | (uintptr_t)backing_w | (uintptr_t)cache_state | (uintptr_t)backing_state) & 15)
+        return fail(BP_ERR_INVALID_ARG, "row pointers must be 16-byte aligned");
+    if ((n_evict && (!evict_ids || !evict_slots)) || (n_prefetch && (!prefetch_ids || !prefetch_slots)))
+        return fail(BP_ERR_INVALID_ARG, "a list pointer is NULL");
+    HandoffLaunch l{cfg, cache_w, cache_state, backing_w, backing_state, evict_ids, evict_slots, n_evict, prefetch_ids,
+                    prefetch_slots, n_prefetch, n_early, mismatch_flag, (hipStream_t)stream};
     return dispatch_row((int)(row_bytes(cfg) / 16), false, l);
 }

@@ -22,8 +22,10 @@ Streaming (the trace arrives chunk by chunk; synchronous schedule):
 
 The order of calls in the first loop is the synchronous schedule of Section 3.2: the write-backs of batch i-1 are applied before
 the prefetches of batch i, so a row is never fetched while an update to it is still only in the cache.
-With duplex=True (default) and a plan whose L_eff >= 2, maintain() uses bp_cache_apply_duplex (writes to and reads
-from the backing table in one launch).  With grouping=True (default) the plan also lists every batch's lookups grouped by row and the backward pass
+With a whole-trace plan whose L_eff >= 2, maintain() uses bp_cache_apply_handoff (one launch, no staging: the rows
+that leave and the rows that enter a slot go through the same lane group; handoff=True, default); otherwise, with
+duplex=True (default) and L_eff >= 2, bp_cache_apply_duplex (staging area, then writes to and reads from the backing
+table in one launch); otherwise bp_cache_apply.  With grouping=True (default) the plan also lists every batch's lookups grouped by row and the backward pass
 uses bp_embbag_bwd_update_grouped (no sort at run time); with grouping=False it sorts the slots itself.
 """
 from __future__ import annotations
@@ -45,7 +47,7 @@ def state_shape(rows: int, dim: int, optimizer: int):
 
 class CachedEmbeddingTrainer:
     def __init__(self, cfg: B.bp_config, backing_w, backing_state=None, device="cuda:0", max_lookups: int = 0,
-                 max_bags: int = 0, grouping: bool = True, duplex: bool = True):
+                 max_bags: int = 0, grouping: bool = True, duplex: bool = True, handoff: bool = True):
         import torch
         self.cfg = cfg
         self.device = torch.device(device)
@@ -53,6 +55,9 @@ class CachedEmbeddingTrainer:
         self.backing_state = backing_state
         self.grouping = grouping
         self.duplex = duplex           # both link directions at once in maintain(); needs a plan with L_eff >= 2
+        self.handoff = handoff         # maintenance in one launch; needs a whole-trace plan with L_eff >= 2
+        self._early = None
+        self._mismatch = torch.zeros(1, dtype=torch.int32, device=self.device)
         self._stage = None
         wdt = torch.float32 if cfg.weight_dtype == B.F32 else torch.bfloat16
         C, D = int(cfg.capacity), int(cfg.dim)
@@ -86,6 +91,10 @@ class CachedEmbeddingTrainer:
         self.plan_ = B.bp_oracle_plan(self.cfg, ids_dev, self.iter_offsets, list_capacity=list_capacity,
                                       workspace=workspace, grouping=self.grouping)
         self.close()
+        self._early = None
+        if self.handoff and self.plan_.L_eff >= 2:
+            self._early = B.bp_pipeline_early_counts(self.plan_.prefetch_offsets, self.plan_.evict_offsets,
+                                                     int(self.cfg.capacity), self.plan_.L_eff)
         if self.plan_.L_eff >= 2:
             import torch
             most = int(np.diff(self.plan_.evict_offsets).max()) if len(self.plan_.evict_offsets) > 1 else 0
@@ -106,6 +115,7 @@ class CachedEmbeddingTrainer:
         self.plan_, self._plan_state = B.bp_oracle_plan_chunk(self.cfg, ids_dev, self.iter_offsets, n_emit,
                                                               self._plan_state, grouping=self.grouping)
         self._n_emit = n_emit
+        self._early = None
         if self.plan_.L_eff >= 2:
             most = int(np.diff(self.plan_.evict_offsets).max()) if n_emit > 0 else 0
             if self._carried_evict is not None:
@@ -134,7 +144,11 @@ class CachedEmbeddingTrainer:
             disjoint = disjoint and l_prev >= 2    # ... under the lookahead the eviction was decided with
             self._carried_evict = None
         p_ids, p_slots = self._slice("prefetch", i)
-        if self.duplex and disjoint:
+        if self._early is not None and disjoint and not self._n_emit:
+            n_early = int(self._early[i]) if i > 0 else int(p_ids.numel())
+            B.bp_cache_apply_handoff(self.cfg, self.cache_w, self.cache_state, self.backing_w, self.backing_state, e_ids,
+                                     e_slots, p_ids, p_slots, n_early, self._mismatch, stream=stream)
+        elif self.duplex and disjoint:
             B.bp_cache_apply_duplex(self.cfg, self.cache_w, self.cache_state, self.backing_w, self.backing_state, e_ids,
                                     e_slots, p_ids, p_slots, self._stage, stream=stream)
         else:
@@ -175,6 +189,8 @@ class CachedEmbeddingTrainer:
         e_ids, e_slots = self._slice("evict", T - 1)
         B.bp_cache_apply(self.cfg, self.cache_w, self.cache_state, self.backing_w, self.backing_state, e_ids, e_slots,
                          None, None, stream=stream)
+        if self._early is not None and int(self._mismatch.item()) != 0:       # synchronises
+            raise RuntimeError("bp_cache_apply_handoff met a slot pairing that is not the plan's: the cache is corrupt")
 
     # ---- (3)
     def forward(self, i: int, bag_offsets_dev, bags: int, out=None, stream=None):

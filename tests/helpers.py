@@ -147,7 +147,7 @@ def make_backing(cfg, pinned=True, chunk_rows=1 << 20):
 
 
 def gpu_cached_training(cfg, trace, T=None, pinned=True, capacity=None, check_outputs=None, grouping=True,
-                        duplex=None, overlapped=False, reserve=0):
+                        duplex=None, overlapped=False, reserve=0, handoff=None):
     """Runs plan + T iterations of cache_apply / fwd / bwd_update + flush through the C ABI.
     check_outputs(i, out_tensor) is called after every forward.  Returns (trainer, plan, W, S).
     overlapped=True: cache maintenance runs on the library's maintenance stream (bp_pipeline_*)."""
@@ -155,7 +155,9 @@ def gpu_cached_training(cfg, trace, T=None, pinned=True, capacity=None, check_ou
     T = trace.iter_offsets.shape[0] - 1 if T is None else T
     bcfg = bp_config_of(cfg, capacity, reserve)
     W, S = make_backing(cfg, pinned)
-    tr = CachedEmbeddingTrainer(bcfg, W, S, grouping=grouping, duplex=grouping if duplex is None else duplex)
+    # by default the sorting backward (grouping=False) also takes the older maintenance paths, so both stay covered
+    tr = CachedEmbeddingTrainer(bcfg, W, S, grouping=grouping, duplex=True if duplex is None else duplex,
+                                handoff=grouping if handoff is None else handoff)
     ids_dev = torch.from_numpy(trace.ids[:trace.iter_offsets[T]]).cuda()
     plan = tr.plan(ids_dev, trace.iter_offsets[:T + 1])
     bags = trace.bag_offsets.shape[1] - 1

@@ -263,6 +263,58 @@ def test_cache_apply(bp, D, dtype, optimizer, pinned):
     assert np.array_equal(cache_numpy(hw_d.cpu()), hw_o) and np.array_equal(cache_numpy(cw_d.cpu()), cw_o)
 
 
+@pytest.mark.parametrize("D,dtype,optimizer,pinned", [(48, "f32", "adagrad", True), (128, "bf16", "adagrad_rowwise", False),
+                                                      (16, "f32", "sgd", True)])
+def test_cache_apply_handoff(bp, D, dtype, optimizer, pinned):
+    """Maintenance in one launch: 700 evictions, 900 prefetches of which the last 400 take the first 400 evicted
+    slots in order (the pairing of a FIFO plan) and 500 go to free slots.  Same bytes as the oracle's two-step rule."""
+    say(f"cache_apply_handoff D={D} {dtype} {optimizer} pinned={pinned}")
+    R, C = 20011, 1500
+    rng = np.random.default_rng(D + 5)
+    op = oracle.OPTIMIZERS[optimizer]
+    hw, cw = random_cache(R, D, dtype, 41), random_cache(C, D, dtype, 42)
+    hs = rng.uniform(0, 1, size=oracle.state_shape(R, D, op)).astype(np.float32)
+    cs = rng.uniform(1, 2, size=oracle.state_shape(C, D, op)).astype(np.float32)
+    e_slots = rng.permutation(C)[:700].astype(np.int32)
+    e_ids = rng.permutation(R)[:700].astype(np.int64)
+    free = np.setdiff1d(np.arange(C), e_slots)[:500]
+    p_slots = np.concatenate([free, e_slots[:400]]).astype(np.int32)              # early ones first, then the paired ones
+    p_ids = rng.permutation(np.setdiff1d(np.arange(R), e_ids))[:900].astype(np.int64)
+    cfg = bp.make_config(R, C, D, dtype, optimizer)
+    mk = (lambda t: t.pin_memory()) if pinned else (lambda t: t.cuda())
+
+    def run(n_early, ps):
+        hw_d, cw_d = mk(hw.clone()), cw.cuda()
+        hs_d = mk(torch.from_numpy(hs.copy())) if op != oracle.SGD else None
+        cs_d = torch.from_numpy(cs.copy()).cuda() if op != oracle.SGD else None
+        flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+        bp.bp_cache_apply_handoff(cfg, cw_d, cs_d, hw_d, hs_d, dev(e_ids), dev(e_slots), dev(p_ids), dev(ps), n_early, flag)
+        torch.cuda.synchronize()
+        return hw_d, cw_d, hs_d, cs_d, int(flag.item())
+
+    hw_d, cw_d, hs_d, cs_d, flag = run(500, p_slots)
+    hw_o, cw_o, hs_o, cs_o = cache_numpy(hw), cache_numpy(cw), hs.copy(), cs.copy()
+    oracle.cache_apply(cw_o, cs_o, hw_o, hs_o, D, oracle.DTYPES[dtype], op, e_ids, e_slots, p_ids, p_slots)
+    assert flag == 0
+    assert np.array_equal(cache_numpy(hw_d.cpu()), hw_o) and np.array_equal(cache_numpy(cw_d.cpu()), cw_o)
+    if op != oracle.SGD:
+        assert np.array_equal(hs_d.cpu().numpy(), hs_o) and np.array_equal(cs_d.cpu().numpy(), cs_o)
+    # a pair whose slots differ is reported, its slot is left alone, everything is still written back
+    bad = p_slots.copy()
+    bad[500 + 7], bad[500 + 8] = bad[500 + 8], bad[500 + 7]
+    hw_d, cw_d, hs_d, cs_d, flag = run(500, bad)
+    assert flag == 1
+    assert np.array_equal(cache_numpy(hw_d.cpu()), hw_o)
+    assert np.array_equal(cache_numpy(cw_d.cpu())[e_slots[7]], cache_numpy(cw)[e_slots[7]])
+    # argument errors: more late prefetches than evictions
+    with pytest.raises(bp.BagpipeError) as e:
+        bp.bp_cache_apply_handoff(cfg, cw_d, cs_d, hw_d, hs_d, dev(e_ids[:10]), dev(e_slots[:10]), dev(p_ids),
+                                  dev(p_slots), 100, None)
+    assert e.value.status == -1
+    # no lists: nothing to do
+    bp.bp_cache_apply_handoff(cfg, cw_d, cs_d, hw_d, hs_d, None, None, None, None, 0, None)
+
+
 def test_cache_stage_then_apply_staged(bp):
     """The two halves of the duplex maintenance called on their own, with unrelated work on the cache between them
     (the staged rows' slots are overwritten before the write-back): backing table and cache as the oracle's."""

@@ -107,3 +107,26 @@ def test_reserve_is_the_policy_of_a_smaller_cache_on_the_full_ring(seed):
     assert np.array_equal(with_reserve.lookup_slots, full.lookup_slots)
     with pytest.raises(oracle.OracleError):
         oracle.plan(ids, off, R, L, umax + 3, reserve=4)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_late_prefetches_take_the_evicted_slots_in_order(seed):
+    """What bp_cache_apply_handoff relies on: of the prefetch list of batch i, the entries after the early ones take
+    the slots of batch i-1's evictions, entry by entry in the evictions' order."""
+    import paper_2202_12429_amd as bp
+    ids, off, R, T = random_trace(200 + seed)
+    if len(ids) == 0:
+        return
+    umax = max(len(np.unique(ids[off[i]:off[i + 1]])) for i in range(T))
+    for L, C in ((4, umax + 2), (6, 2 * umax), (3, umax), (T, 4 * umax)):
+        plan = oracle.plan(ids, off, R, L, C)
+        if plan.L_eff < 2:
+            continue
+        early = bp.bp_pipeline_early_counts(plan.prefetch_off, plan.evict_off, C, plan.L_eff)
+        for i in range(1, T):
+            p = plan.prefetch_slots[plan.prefetch_off[i]:plan.prefetch_off[i + 1]]
+            e = plan.evict_slots[plan.evict_off[i - 1]:plan.evict_off[i]]
+            n_late = len(p) - int(early[i])
+            assert 0 <= n_late <= len(e)
+            assert np.array_equal(p[int(early[i]):], e[:n_late]), (seed, L, C, i)
+            assert not set(p[:int(early[i])].tolist()) & set(e.tolist())
