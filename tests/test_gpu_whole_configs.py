@@ -160,21 +160,21 @@ def run_lockstep(cfg, T, pinned):
 @pytest.mark.timeout(1500)
 def test_config3_full_tables():
     """configs[3]: 20 tables x 5 M rows, D=64, bags of 1..50 ids (~4.2 M lookups per batch), batch 8,192, L=300,
-    cache 4 M rows, SGD; 25.6 GB backing table in pinned host memory.  30 of the 100 batches."""
+    cache 4 M rows, SGD; 25.6 GB backing table in pinned host memory.  20 of the 100 batches."""
     cfg = workloads.CONFIGS[3]
-    say("config 3, full tables, 30 batches")
-    plan = run_lockstep(cfg, 30, pinned=True)
+    say("config 3, full tables, 20 batches")
+    plan = run_lockstep(cfg, 20, pinned=True)
     assert plan.peak_occupancy <= cfg.capacity
 
 
 @pytest.mark.timeout(1500)
 def test_config4_full_tables():
     """configs[4]: 40 tables x 10 M rows, D=128 bf16 rows with fp32 arithmetic, row-wise Adagrad, batch 32,768
-    (1.31 M lookups per batch), L=500, cache 16 M rows, hot set re-drawn every 50 batches.  60 of the 300 batches
+    (1.31 M lookups per batch), L=500, cache 16 M rows, hot set re-drawn every 50 batches.  54 of the 300 batches
     (one re-draw inside); the 102 GB backing table lives in HBM here so that the oracle's copy fits in host RAM."""
     cfg = workloads.CONFIGS[4]
-    say("config 4, full tables, 60 batches")
-    plan = run_lockstep(cfg, 60, pinned=False)
+    say("config 4, full tables, 54 batches")
+    plan = run_lockstep(cfg, 54, pinned=False)
     assert plan.peak_occupancy <= cfg.capacity
 
 

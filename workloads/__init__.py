@@ -18,6 +18,8 @@ from __future__ import annotations
 
 import dataclasses
 import math
+import os
+from concurrent.futures import ThreadPoolExecutor
 from typing import List, Optional
 
 import numpy as np
@@ -269,35 +271,47 @@ def make_trace(cfg: Config, iterations: Optional[int] = None) -> Trace:
 
     epochs = [(0, T)] if cfg.drift_every <= 0 else [
         (a, min(a + cfg.drift_every, T)) for a in range(0, T, cfg.drift_every)]
-    cdf_cache = {}
-    for t in range(nt):
+    cdfs = {}                               # one CDF per table size (10 M rows = 80 MB), shared by the workers
+    for n_rows in sorted(set(cfg.table_rows)):
+        cdfs[n_rows] = rank_cdf(cfg, n_rows)
+
+    def fill(job):
+        # one (table, epoch): its stream depends on (seed, table, epoch) alone and it writes places no other job does,
+        # so the trace does not depend on how the jobs are spread over threads
+        t, e, a, b = job
         n_rows = cfg.table_rows[t]
-        if n_rows not in cdf_cache:
-            cdf_cache = {n_rows: rank_cdf(cfg, n_rows)}   # keep one CDF alive (10 M rows = 80 MB)
-        cdf = cdf_cache[n_rows]
-        for e, (a, b) in enumerate(epochs):
-            rng = np.random.default_rng([cfg.seed, 303, t, e])
-            perm = rng.permutation(n_rows).astype(np.int64)
-            if cfg.one_hot:
-                cnt = (b - a) * B
-                ranks = np.searchsorted(cdf, rng.random(cnt), side="right")
-                np.minimum(ranks, n_rows - 1, out=ranks)
-                g = toff[t] + perm[ranks]
-                # lookup position inside iteration i: sample * nt + t
-                view = ids[iter_off[a]:iter_off[b]].reshape(b - a, B, nt)
-                view[:, :, t] = g.reshape(b - a, B)
-            else:
-                l_t = lens[a:b, :, t]                                   # [b-a, B]
-                cnt = int(l_t.sum())
-                ranks = np.searchsorted(cdf, rng.random(cnt), side="right")
-                np.minimum(ranks, n_rows - 1, out=ranks)
-                g = toff[t] + perm[ranks]
-                # destination of each drawn id: start of its bag (global) + position inside the bag
-                starts = (iter_off[a:b, None] + bag_off[a:b, :-1].reshape(b - a, B, nt)[:, :, t]).ravel()
-                flat_l = l_t.ravel()
-                first = np.cumsum(flat_l) - flat_l
-                dst = np.repeat(starts - first, flat_l) + np.arange(cnt, dtype=np.int64)
-                ids[dst] = g
+        cdf = cdfs[n_rows]
+        rng = np.random.default_rng([cfg.seed, 303, t, e])
+        perm = rng.permutation(n_rows).astype(np.int64)
+        if cfg.one_hot:
+            cnt = (b - a) * B
+            ranks = np.searchsorted(cdf, rng.random(cnt), side="right")
+            np.minimum(ranks, n_rows - 1, out=ranks)
+            g = toff[t] + perm[ranks]
+            # lookup position inside iteration i: sample * nt + t
+            view = ids[iter_off[a]:iter_off[b]].reshape(b - a, B, nt)
+            view[:, :, t] = g.reshape(b - a, B)
+        else:
+            l_t = lens[a:b, :, t]                                   # [b-a, B]
+            cnt = int(l_t.sum())
+            ranks = np.searchsorted(cdf, rng.random(cnt), side="right")
+            np.minimum(ranks, n_rows - 1, out=ranks)
+            g = toff[t] + perm[ranks]
+            # destination of each drawn id: start of its bag (global) + position inside the bag
+            starts = (iter_off[a:b, None] + bag_off[a:b, :-1].reshape(b - a, B, nt)[:, :, t]).ravel()
+            flat_l = l_t.ravel()
+            first = np.cumsum(flat_l) - flat_l
+            dst = np.repeat(starts - first, flat_l) + np.arange(cnt, dtype=np.int64)
+            ids[dst] = g
+
+    jobs = [(t, e, a, b) for t in range(nt) for e, (a, b) in enumerate(epochs)]
+    workers = max(1, min(8, os.cpu_count() or 1, len(jobs)))
+    if workers == 1 or ids.size < (1 << 22):
+        for job in jobs:
+            fill(job)
+    else:
+        with ThreadPoolExecutor(max_workers=workers) as pool:
+            list(pool.map(fill, jobs))
     return Trace(cfg=cfg, ids=ids, iter_offsets=iter_off, bag_offsets=bag_off)
 
 
