@@ -268,6 +268,22 @@ def main() -> int:
     grads_dev = [workloads.upstream_grad(cfg, i, bags, device=dev) for i in range(n_grad)]
     out = torch.empty((bags, D), dtype=torch.float32, device=dev)
     torch.cuda.synchronize()
+    # ---- randomly placed rows fetched with nothing else going on: every row of a gradient buffer once, in a random
+    # order, four per lane group at a time (a different buffer per launch, so nothing is left in the caches)
+    g_rows = torch.randperm(bags, device=dev, generator=torch.Generator(device=dev).manual_seed(7)).to(torch.int32)
+    reps = min(40, len(grads_dev))
+    bp.bp_gather_calibration(grads_dev[0], g_rows)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for r in range(reps):
+        bp.bp_gather_calibration(grads_dev[r], g_rows)
+    torch.cuda.synchronize()
+    gather_s = (time.perf_counter() - t0) / reps
+    gather = {"rows": bags, "row_bytes": D * 4, "us_per_launch_wall": gather_s * 1e6, "rows_per_s": bags / gather_s,
+              "GBps": bags * D * 4 / gather_s / 1e9,
+              "note": "bp_gather_calibration: every row of one upstream-gradient buffer read once in random order, "
+                      "wall clock over back-to-back launches on different buffers"}
+    log(f"random row gather: {bags} rows of {D * 4} B in {gather_s * 1e6:.1f} us ({gather['GBps']:.0f} GB/s)")
     n_timed = int(n_per_iter[W:W + K].sum())
     n_mean = n_timed / K
     u_mean = float(np.diff(first_sync.plan_.keep_offsets)[W:W + K].mean())
@@ -405,7 +421,8 @@ def main() -> int:
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "algorithmic_bytes_per_launch": alg,
                      "avg_launch_us": dur_s * 1e6, "launches": launches, "empty_kernel_bracket_us": bracket_us,
-                     "frac_of_measured_copy": achieved / copy_gbs, "measured_copy_GBps": copy_gbs},
+                     "frac_of_measured_copy": achieved / copy_gbs, "measured_copy_GBps": copy_gbs,
+                     "frac_of_random_row_gather": achieved / gather["GBps"], "random_row_gather": gather},
         "cpu_baseline": cpu,
         "plan": {"ms": t_plan * 1e3, "ids_per_s": trace.n_lookups / t_plan, "n_lookups": trace.n_lookups},
         "loop_ms_per_step": m["t_loop"] / K * 1e3,

@@ -102,6 +102,8 @@ def load_library():
     lib.bp_profile_get.argtypes = [ctypes.c_int, ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)]
     lib.bp_copy_calibration.argtypes = [vp, vp, sz, vp]
     lib.bp_copy_calibration.restype = ctypes.c_int
+    lib.bp_gather_calibration.argtypes = [vp, vp, i64, i32, vp, i64, vp]
+    lib.bp_gather_calibration.restype = ctypes.c_int
     lib.bp_profile_bracket_overhead.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double)]
     lib.bp_profile_bracket_overhead.restype = ctypes.c_int
     lib.bp_profile_select.argtypes = [ctypes.c_uint64]
@@ -511,6 +513,18 @@ def bp_copy_calibration(dst, src, stream=None) -> None:
     nbytes = src.numel() * src.element_size()
     assert dst.numel() * dst.element_size() == nbytes
     _check(load_library().bp_copy_calibration(_ptr(dst), _ptr(src), nbytes, _stream(stream)))
+
+
+def bp_gather_calibration(table, rows, stream=None):
+    """Reads table[rows[k]] for every k (table: 2-D device tensor with rows of a multiple of 16 bytes, rows: int32
+    device tensor holding uint32 row numbers) four rows per lane group at a time; returns the sink tensor."""
+    import torch
+    row_bytes = table.shape[1] * table.element_size()
+    n = int(rows.numel())
+    sink = torch.empty((-(-n // 4) + 256) * 4, dtype=torch.int32, device=table.device)
+    _check(load_library().bp_gather_calibration(_ptr(sink), _ptr(table), int(table.shape[0]), int(row_bytes), _ptr(rows), n,
+                                                _stream(stream)))
+    return sink
 
 
 def bp_profile_enable(on: bool) -> None:

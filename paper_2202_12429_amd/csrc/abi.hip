@@ -4,6 +4,7 @@
 #include <vector>
 
 #include "common.h"
+#include "row_access.h"
 
 namespace bp {
 
@@ -96,6 +97,56 @@ __global__ __launch_bounds__(256) void copy_calibration_kernel(const uint4* __re
     if (i < n16) dst[i] = src[i];
 }
 
+// Randomly placed rows fetched four at a time per lane group, as the backward pass reads gradient rows, and folded
+// into one word per lane so that the loads cannot be dropped.
+template <int GW>
+__global__ __launch_bounds__(256) void gather_calibration_kernel(const uint4* __restrict__ table, uint32_t table_rows,
+                                                                 int lpr, const uint32_t* __restrict__ rows, uint32_t n,
+                                                                 uint4* __restrict__ sink) {
+    const uint32_t t = blockIdx.x * 256u + threadIdx.x;
+    const uint32_t group = t / GW;
+    const int c = (int)(t % GW);
+    uint4 acc = make_uint4(0, 0, 0, 0);
+    const uint64_t first = (uint64_t)group * 4;
+    if (c < lpr && first < n) {
+        uint32_t r[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) r[j] = first + j < n ? min(rows[first + j], table_rows - 1u) : 0u;
+        uint4 v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = first + j < n ? table[(size_t)r[j] * lpr + c] : make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            acc.x ^= v[j].x; acc.y ^= v[j].y; acc.z ^= v[j].z; acc.w ^= v[j].w;
+        }
+    }
+#pragma unroll
+    for (int off = GW / 2; off >= 1; off >>= 1) {     // one word per lane group leaves: the writes stay negligible
+        acc.x ^= __shfl_xor(acc.x, off, GW); acc.y ^= __shfl_xor(acc.y, off, GW);
+        acc.z ^= __shfl_xor(acc.z, off, GW); acc.w ^= __shfl_xor(acc.w, off, GW);
+    }
+    if (c == 0) sink[group] = acc;
+}
+
+struct GatherLaunch {
+    const void* table;
+    int64_t table_rows;
+    int lpr;
+    const uint32_t* rows;
+    int64_t n;
+    void* sink;
+    hipStream_t stream;
+    template <int GW, bool BF16>
+    int run() {
+        const int64_t threads = ceil_div(n, 4) * GW;
+        const int64_t blocks = ceil_div(threads, 256);
+        if (blocks >= (int64_t(1) << 24)) return fail(BP_ERR_UNSUPPORTED, "gather of %lld rows is too large for one launch", (long long)n);
+        BP_LAUNCH(K_COPY, (gather_calibration_kernel<GW>), dim3((unsigned)blocks), dim3(256), 0, stream, (const uint4*)table,
+                  (uint32_t)table_rows, lpr, rows, (uint32_t)n, (uint4*)sink);
+        return BP_OK;
+    }
+};
+
 // Does nothing: what a pair of bracketing events reads around it is the cost of the bracket itself.
 __global__ __launch_bounds__(64) void bracket_probe_kernel() {}
 
@@ -154,6 +205,19 @@ BP_EXPORT int bp_copy_calibration(void* dst, const void* src, size_t bytes, void
     BP_LAUNCH(K_COPY, copy_calibration_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
               (const uint4*)src, (uint4*)dst, n16);
     return BP_OK;
+}
+
+BP_EXPORT int bp_gather_calibration(void* sink, const void* table, int64_t table_rows, int32_t row_bytes,
+                                    const uint32_t* rows, int64_t n, void* stream) {
+    if (!sink || !table || !rows || (((uintptr_t)sink | (uintptr_t)table) & 15))
+        return fail(BP_ERR_INVALID_ARG, "gather needs 16-byte aligned table and sink and a row list");
+    if (row_bytes < 16 || row_bytes > 1024 || row_bytes % 16 != 0)
+        return fail(BP_ERR_INVALID_ARG, "row_bytes %d: a multiple of 16 in [16, 1024]", row_bytes);
+    if (table_rows < 1 || table_rows >= (int64_t(1) << 32) || n < 0 || n >= (int64_t(1) << 31))
+        return fail(BP_ERR_INVALID_ARG, "table_rows or n out of range");
+    if (n == 0) return BP_OK;
+    GatherLaunch l{table, table_rows, row_bytes / 16, rows, n, sink, (hipStream_t)stream};
+    return dispatch_row(row_bytes / 16, false, l);
 }
 
 BP_EXPORT int bp_profile_enable(int on) {

@@ -838,3 +838,18 @@ def test_plan_trainer_marking(bp, seed):
         bad = even.copy()
         bad[0, -1] += 1
         bp.bp_oracle_plan(bp.make_config(R, 4 * R, 16, lookahead=5), dev(ids), off, trainer_cuts=bad)
+
+
+@pytest.mark.parametrize("row_ints,n", [(48, 1000), (16, 4097), (4, 3), (256, 77)])
+def test_gather_calibration(bp, row_ints, n):
+    """The row-gather yardstick folds exactly the rows it is given (so it reads them)."""
+    rng = np.random.default_rng(row_ints + n)
+    table = rng.integers(-2**31, 2**31, size=(500, row_ints), dtype=np.int64).astype(np.int32)
+    rows = rng.integers(0, 500, size=n).astype(np.int32)
+    rows[0] = 499
+    sink = bp.bp_gather_calibration(torch.from_numpy(table).cuda(), torch.from_numpy(rows).cuda())
+    torch.cuda.synchronize()
+    got = sink.cpu().numpy().reshape(-1, 4)
+    for k in range(-(-n // 4)):
+        sel = table[rows[4 * k:4 * k + 4]].reshape(-1, 4)
+        assert np.array_equal(got[k], np.bitwise_xor.reduce(sel, axis=0)), k
