@@ -145,8 +145,10 @@ int bp_oracle_plan_workspace_bytes(const bp_config* cfg, int64_t n_lookups, int3
  * iter_offsets host, [n_iters+1], non-decreasing, iter_offsets[0] == 0, last == n_lookups
  * plan         host struct; its pointers as documented above; scalars are written on return
  * workspace    device, at least bp_oracle_plan_workspace_bytes() bytes, 256-byte aligned
- * Limits: n_lookups < 2^31, 1 <= n_iters <= 8192, bits(total_rows) + 2 * bits(n_iters) + 2 <= 64 (bits(x) = bits
- * needed for values below x).
+ * Limits: n_lookups < 2^31, 1 <= n_iters <= 8192, bits(total_rows) + 2 * bits(n_iters) + 2 <= 64 and
+ * max(bits(total_rows), 32) + bits(n_iters) + bits(lookups of the largest batch) <= 64 (bits(x) = bits needed for
+ * values below x; a lookup travels as one 64-bit word of id or slot, batch and place in the batch), else
+ * BP_ERR_UNSUPPORTED.
  * Errors: BP_ERR_ID_OUT_OF_RANGE; BP_ERR_CAPACITY (plan->min_capacity is set); BP_ERR_WORKSPACE_TOO_SMALL
  * (also when list_capacity < n_unique_pairs; plan->n_unique_pairs is set).  On error the device outputs
  * are unspecified.  Synchronises `stream`.

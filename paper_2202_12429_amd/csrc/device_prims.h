@@ -202,10 +202,26 @@ inline uint32_t sort_grid(uint32_t ntiles) {
 constexpr int kMaxRadixBits = 9;
 constexpr int kMaxRadix = 1 << kMaxRadixBits;
 
-template <typename K, int IPT, int RB>
-__global__ __launch_bounds__(kSortBlock) void sort_upsweep_kernel(const K* __restrict__ keys, uint32_t n, int shift,
-                                                                  uint32_t mask, uint32_t* __restrict__ counts,
-                                                                  uint32_t ntiles) {
+// Where a pass reads its elements.  Plain arrays are the common case; a pass may also make its keys on the fly from
+// something else (and so save writing them out first).  A source loads what it needs for element i with load(i),
+// which depends on nothing but i, so a thread's loads all go out together; a cursor per thread then turns what was
+// loaded into the key, for element numbers in ascending order.
+template <typename K>
+struct SortArrays {
+    const K* keys;
+    const uint32_t* vals;     // NULL for a sort of keys alone
+    typedef K Raw;
+    __device__ __forceinline__ K load(uint32_t i) const { return keys[i]; }
+    __device__ __forceinline__ uint32_t val(uint32_t i) const { return vals[i]; }
+    struct Cursor {
+        __device__ __forceinline__ Cursor(const SortArrays&, uint32_t) {}
+        __device__ __forceinline__ K key(uint32_t, K raw) { return raw; }
+    };
+};
+
+template <typename K, int IPT, int RB, typename Src>
+__global__ __launch_bounds__(kSortBlock) void sort_upsweep_kernel(Src src, uint32_t n, int shift, uint32_t mask,
+                                                                  uint32_t* __restrict__ counts, uint32_t ntiles) {
     constexpr int RADIX = 1 << RB;
     __shared__ uint32_t hist[RADIX];
     const uint32_t tile = sort_tile_of_block(ntiles);
@@ -213,18 +229,26 @@ __global__ __launch_bounds__(kSortBlock) void sort_upsweep_kernel(const K* __res
     for (int d = threadIdx.x; d < RADIX; d += kSortBlock) hist[d] = 0;
     __syncthreads();
     const uint32_t base = tile * (kSortBlock * IPT);
+    if (base + threadIdx.x < n) {
+        typename Src::Raw raw[IPT];
 #pragma unroll
-    for (int j = 0; j < IPT; ++j) {
-        uint32_t i = base + j * kSortBlock + threadIdx.x;
-        if (i < n) atomicAdd(&hist[(uint32_t)(keys[i] >> shift) & mask], 1u);
+        for (int j = 0; j < IPT; ++j) {
+            uint32_t i = base + j * kSortBlock + threadIdx.x;
+            raw[j] = src.load(i < n ? i : n - 1u);
+        }
+        typename Src::Cursor cur(src, base + threadIdx.x);
+#pragma unroll
+        for (int j = 0; j < IPT; ++j) {
+            uint32_t i = base + j * kSortBlock + threadIdx.x;
+            if (i < n) atomicAdd(&hist[(uint32_t)(cur.key(i, raw[j]) >> shift) & mask], 1u);
+        }
     }
     __syncthreads();
     for (int d = threadIdx.x; d < RADIX; d += kSortBlock) counts[(size_t)d * ntiles + tile] = hist[d];
 }
 
-template <typename K, int IPT, int RB>
-__global__ __launch_bounds__(kSortBlock) void sort_downsweep_kernel(const K* __restrict__ kin, K* __restrict__ kout,
-                                                                    const uint32_t* __restrict__ vin,
+template <typename K, int IPT, int RB, typename Src, bool VALS>
+__global__ __launch_bounds__(kSortBlock) void sort_downsweep_kernel(Src src, K* __restrict__ kout,
                                                                     uint32_t* __restrict__ vout, uint32_t n, int shift,
                                                                     uint32_t mask, const uint32_t* __restrict__ bases,
                                                                     uint32_t ntiles) {
@@ -239,7 +263,7 @@ __global__ __launch_bounds__(kSortBlock) void sort_downsweep_kernel(const K* __r
     __shared__ uint32_t gbase[RADIX];          // global base of the digit for this tile, minus dstart
     __shared__ uint32_t wave_tot[WAVES];
     __shared__ K skeys[TILE];
-    __shared__ uint32_t svals[TILE];
+    __shared__ uint32_t svals[VALS ? TILE : 1];
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid / kWave;
     const uint32_t tile = sort_tile_of_block(ntiles);
@@ -250,14 +274,22 @@ __global__ __launch_bounds__(kSortBlock) void sort_downsweep_kernel(const K* __r
     const uint32_t tile_base = tile * TILE;
     const uint32_t wbase = tile_base + w * WTILE;
     K key[IPT];
-    uint32_t val[IPT];
+    uint32_t val[VALS ? IPT : 1];
     uint32_t rank[IPT];
+    {
+        typename Src::Raw raw[IPT];
 #pragma unroll
-    for (int j = 0; j < IPT; ++j) {
-        uint32_t i = wbase + j * kWave + lane;
-        bool valid = i < n;
-        key[j] = valid ? kin[i] : K(~K(0));
-        val[j] = valid ? vin[i] : 0u;
+        for (int j = 0; j < IPT; ++j) {
+            uint32_t i = wbase + j * kWave + lane;
+            raw[j] = src.load(i < n ? i : n - 1u);
+            if constexpr (VALS) val[j] = i < n ? src.val(i) : 0u;
+        }
+        typename Src::Cursor cur(src, wbase + lane < n ? wbase + lane : 0u);
+#pragma unroll
+        for (int j = 0; j < IPT; ++j) {
+            uint32_t i = wbase + j * kWave + lane;
+            key[j] = i < n ? cur.key(i, raw[j]) : K(~K(0));
+        }
     }
     const uint64_t lt = lanemask_lt();
 #pragma unroll
@@ -313,7 +345,7 @@ __global__ __launch_bounds__(kSortBlock) void sort_downsweep_kernel(const K* __r
             const uint32_t d = (uint32_t)(key[j] >> shift) & mask;
             const uint32_t pos = dstart[d] + wcnt[w][d] + rank[j];
             skeys[pos] = key[j];
-            svals[pos] = val[j];
+            if constexpr (VALS) svals[pos] = val[j];
         }
     }
     __syncthreads();
@@ -326,7 +358,7 @@ __global__ __launch_bounds__(kSortBlock) void sort_downsweep_kernel(const K* __r
             const K k = skeys[pos];
             const uint32_t dst = gbase[(uint32_t)(k >> shift) & mask] + pos;
             kout[dst] = k;
-            vout[dst] = svals[pos];
+            if constexpr (VALS) vout[dst] = svals[pos];
         }
     }
 }
@@ -350,17 +382,57 @@ inline size_t sort_temp_words(int64_t n) {
     return counts + 64 + scan_partials((int64_t)counts) + 64;
 }
 
-template <typename K, int IPT, int RB>
-int radix_sort_pass(const K* kin, K* kout, const uint32_t* vin, uint32_t* vout, int64_t n, int bit, int nb,
-                    uint32_t* counts, uint32_t* partials, uint32_t ntiles, hipStream_t stream) {
+template <typename K, int IPT, int RB, typename Src, bool VALS>
+int radix_sort_pass(const Src& src, K* kout, uint32_t* vout, int64_t n, int bit, int nb, uint32_t* counts,
+                    uint32_t* partials, uint32_t ntiles, hipStream_t stream) {
     const int64_t ncounts = (int64_t)(1 << RB) * ntiles;
     const uint32_t mask = (1u << nb) - 1u;
-    BP_LAUNCH(K_SORT_UPSWEEP, (sort_upsweep_kernel<K, IPT, RB>), dim3(sort_grid(ntiles)), dim3(kSortBlock), 0, stream, kin,
-              (uint32_t)n, bit, mask, counts, ntiles);
+    BP_LAUNCH(K_SORT_UPSWEEP, (sort_upsweep_kernel<K, IPT, RB, Src>), dim3(sort_grid(ntiles)), dim3(kSortBlock), 0, stream,
+              src, (uint32_t)n, bit, mask, counts, ntiles);
     BP_TRY((device_scan<uint32_t, AddOp, LoadU32, StoreExclusiveU32>(LoadU32{counts}, StoreExclusiveU32{counts}, ncounts,
                                                                      partials, AddOp(), 0u, stream)));
-    BP_LAUNCH(K_SORT_DOWNSWEEP, (sort_downsweep_kernel<K, IPT, RB>), dim3(sort_grid(ntiles)), dim3(kSortBlock), 0, stream, kin, kout,
-              vin, vout, (uint32_t)n, bit, mask, (const uint32_t*)counts, ntiles);
+    BP_LAUNCH(K_SORT_DOWNSWEEP, (sort_downsweep_kernel<K, IPT, RB, Src, VALS>), dim3(sort_grid(ntiles)), dim3(kSortBlock), 0,
+              stream, src, kout, vout, (uint32_t)n, bit, mask, (const uint32_t*)counts, ntiles);
+    return BP_OK;
+}
+
+template <typename K, int IPT, typename Src, bool VALS>
+int radix_sort_one_pass(const Src& src, K* kout, uint32_t* vout, int64_t n, int bit, int nb, uint32_t* counts,
+                        uint32_t* partials, uint32_t ntiles, hipStream_t stream) {
+    if (nb > 8) return radix_sort_pass<K, IPT, 9, Src, VALS>(src, kout, vout, n, bit, nb, counts, partials, ntiles, stream);
+    return radix_sort_pass<K, IPT, 8, Src, VALS>(src, kout, vout, n, bit, nb, counts, partials, ntiles, stream);
+}
+
+// Stable sort of n elements by key bits [begin_bit, end_bit).  The first pass reads `first` (any source) and writes
+// buffer 0, every later pass reads the buffer the one before wrote and writes the other one; *result says which
+// buffer holds the sorted output (-1: no pass ran, nothing was written).  VALS: 32-bit values travel with the keys.
+// n < 2^32 - kSortBlock*IPT.
+template <typename K, int IPT, typename Src, bool VALS>
+int radix_sort_from(const Src& first, K* const kbuf[2], uint32_t* const vbuf[2], int64_t n, int begin_bit, int end_bit,
+                    uint32_t* temp, hipStream_t stream, int* result) {
+    *result = -1;
+    if (n <= 0 || end_bit <= begin_bit) return BP_OK;
+    const uint32_t ntiles = sort_num_tiles<IPT>(n);
+    uint32_t* counts = temp;
+    uint32_t* partials = temp + (((size_t)kMaxRadix * ntiles + 63) & ~size_t(63));
+    const int total = end_bit - begin_bit;
+    const int passes = (total + kMaxRadixBits - 1) / kMaxRadixBits;
+    int bit = begin_bit;
+    for (int p = 0; p < passes; ++p) {
+        const int left = end_bit - bit;
+        const int nb = (left + (passes - p) - 1) / (passes - p);      // spread the remaining bits evenly
+        const int out = p & 1;
+        if (p == 0) {
+            BP_TRY((radix_sort_one_pass<K, IPT, Src, VALS>(first, kbuf[out], VALS ? vbuf[out] : nullptr, n, bit, nb, counts,
+                                                           partials, ntiles, stream)));
+        } else {
+            const SortArrays<K> in{kbuf[out ^ 1], VALS ? vbuf[out ^ 1] : nullptr};
+            BP_TRY((radix_sort_one_pass<K, IPT, SortArrays<K>, VALS>(in, kbuf[out], VALS ? vbuf[out] : nullptr, n, bit, nb,
+                                                                     counts, partials, ntiles, stream)));
+        }
+        bit += nb;
+        *result = out;
+    }
     return BP_OK;
 }
 
@@ -370,30 +442,25 @@ int radix_sort_pass(const K* kin, K* kout, const uint32_t* vin, uint32_t* vout, 
 template <typename K, int IPT>
 int radix_sort_pairs(K* keys_a, K* keys_b, uint32_t* vals_a, uint32_t* vals_b, int64_t n, int begin_bit, int end_bit,
                      uint32_t* temp, hipStream_t stream, bool* result_in_b) {
-    *result_in_b = false;
-    if (n <= 0 || end_bit <= begin_bit) return BP_OK;
-    const uint32_t ntiles = sort_num_tiles<IPT>(n);
-    uint32_t* counts = temp;
-    uint32_t* partials = temp + (((size_t)kMaxRadix * ntiles + 63) & ~size_t(63));
-    K* kin = keys_a;
-    K* kout = keys_b;
-    uint32_t* vin = vals_a;
-    uint32_t* vout = vals_b;
-    const int total = end_bit - begin_bit;
-    int passes = (total + kMaxRadixBits - 1) / kMaxRadixBits;
-    int bit = begin_bit;
-    for (int p = 0; p < passes; ++p) {
-        const int left = end_bit - bit;
-        const int nb = (left + (passes - p) - 1) / (passes - p);      // spread the remaining bits evenly
-        if (nb > 8)
-            BP_TRY((radix_sort_pass<K, IPT, 9>(kin, kout, vin, vout, n, bit, nb, counts, partials, ntiles, stream)));
-        else
-            BP_TRY((radix_sort_pass<K, IPT, 8>(kin, kout, vin, vout, n, bit, nb, counts, partials, ntiles, stream)));
-        bit += nb;
-        K* tk = kin; kin = kout; kout = tk;
-        uint32_t* tv = vin; vin = vout; vout = tv;
-        *result_in_b = !*result_in_b;
-    }
+    K* const kbuf[2] = {keys_b, keys_a};
+    uint32_t* const vbuf[2] = {vals_b, vals_a};
+    int result = -1;
+    BP_TRY((radix_sort_from<K, IPT, SortArrays<K>, true>(SortArrays<K>{keys_a, vals_a}, kbuf, vbuf, n, begin_bit, end_bit, temp,
+                                                         stream, &result)));
+    *result_in_b = result == 0;
+    return BP_OK;
+}
+
+// The same for keys alone.
+template <typename K, int IPT>
+int radix_sort_keys(K* keys_a, K* keys_b, int64_t n, int begin_bit, int end_bit, uint32_t* temp, hipStream_t stream,
+                    bool* result_in_b) {
+    K* const kbuf[2] = {keys_b, keys_a};
+    uint32_t* const vbuf[2] = {nullptr, nullptr};
+    int result = -1;
+    BP_TRY((radix_sort_from<K, IPT, SortArrays<K>, false>(SortArrays<K>{keys_a, nullptr}, kbuf, vbuf, n, begin_bit, end_bit,
+                                                          temp, stream, &result)));
+    *result_in_b = result == 0;
     return BP_OK;
 }
 

@@ -45,69 +45,93 @@ struct PlanScalars {
 };
 
 // ---- 1. keys ---------------------------------------------------------------------------------
-__global__ __launch_bounds__(kBlock) void plan_keys_kernel(const int64_t* __restrict__ ids,
-                                                           const int64_t* __restrict__ iter_off, int T, int64_t first,
-                                                           int64_t N, int64_t R, int ib, uint64_t* __restrict__ keys,
-                                                           uint32_t* __restrict__ pos, PlanScalars* sc) {
-    // positions [first, N) hold the lookups (first > 0 when a chunk's carried residents sit in front of them)
-    const int64_t p = first + (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (p >= N) return;
-    int64_t g = ids[p - first];
-    if (g < 0 || g >= R) {
-        atomicOr(&sc->error_flags, 1u);
-        g = 0;
-    }
-    // batch of position p: iter_off[lo] <= p < iter_off[lo + 1].  The search starts from the batch of the workgroup's
-    // first position (same for all its lanes), and nearly always ends there.
-    const int64_t p_first = first + (int64_t)blockIdx.x * kBlock;
-    int lo = 0, hi = T;
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (iter_off[mid] <= p_first) lo = mid; else hi = mid;
-    }
-    if (iter_off[lo + 1] <= p) {
-        hi = T;
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (iter_off[mid] <= p) lo = mid; else hi = mid;
-        }
-    }
-    keys[p] = ((uint64_t)g << ib) | (uint64_t)lo;
-    pos[p] = (uint32_t)p;
-}
-
+// A lookup travels through the sort as one 64-bit word: (id << (ib + pb)) | (batch << pb) | place, `place` being the
+// lookup's position inside its batch (pb bits).  The word is made where the first sort pass reads its input, from the
+// caller's ids, so no array of keys and positions is written beforehand and none of positions is carried along.
 // Chunked planning: the rows resident at the chunk boundary form a batch 0 of their own in front of the chunk's
 // batches (which then count from 1), so that everything downstream sees them as rows fetched before the chunk.
-__global__ __launch_bounds__(kBlock) void plan_resident_keys_kernel(const int64_t* __restrict__ resident_ids, int64_t R0,
-                                                                    int64_t R, int ib, uint64_t* __restrict__ keys,
-                                                                    uint32_t* __restrict__ pos, PlanScalars* sc) {
-    const int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (r >= R0) return;
-    int64_t g = resident_ids[r];
-    if (g < 0 || g >= R) {
-        atomicOr(&sc->error_flags, 1u);
-        g = 0;
+// Batch of a position (in the lookups' own order, and equally in the batch-grouped order, which has the same batch
+// stretches).  The host lists the batch of every kPosTile-th position; from there a lane walks on, which it hardly
+// ever has to.  Nothing here depends on a loaded key, so these reads run beside the key's own.
+constexpr int kPosTileShift = 12;
+struct BatchOfPos {
+    const int32_t* tile_batch;     // batch of position t << kPosTileShift
+    const int64_t* iter_off;       // batch offsets as the planner counts them, [T + 1]
+    int T;
+    __device__ __forceinline__ int find(int64_t p) const {
+        int b = tile_batch[p >> kPosTileShift];
+        while (b + 1 < T && iter_off[b + 1] <= p) ++b;
+        return b;
     }
-    keys[r] = (uint64_t)g << ib;
-    pos[r] = (uint32_t)r;
+};
+
+__global__ __launch_bounds__(kBlock) void plan_tile_batch_kernel(const int64_t* __restrict__ iter_off, int T, int64_t tiles,
+                                                                 int32_t* __restrict__ tile_batch) {
+    const int64_t t = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (t >= tiles) return;
+    const int64_t p = t << kPosTileShift;
+    int lo = 0, hi = T;                                   // the last batch that starts at or before p
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (iter_off[mid] <= p) lo = mid; else hi = mid;
+    }
+    tile_batch[t] = lo;
 }
+
+struct PlanKeySource {
+    const int64_t* ids;            // the lookups, batch after batch
+    const int64_t* resident_ids;   // the carried rows (elements [0, first)), or NULL
+    int64_t first;
+    BatchOfPos where;
+    int ib, pb;
+    int64_t R;
+    PlanScalars* sc;
+    typedef int64_t Raw;
+    __device__ __forceinline__ int64_t load(uint32_t i) const {
+        return *((int64_t)i < first ? resident_ids + i : ids + ((int64_t)i - first));
+    }
+    struct Cursor {
+        const PlanKeySource& s;
+        int b;                     // batch of the last element asked for
+        int64_t lo, hi;            // its stretch
+        __device__ __forceinline__ Cursor(const PlanKeySource& src, uint32_t i) : s(src) {
+            b = s.where.find((int64_t)i);
+            lo = s.where.iter_off[b];
+            hi = s.where.iter_off[b + 1];
+        }
+        __device__ __forceinline__ uint64_t key(uint32_t i, int64_t g) {
+            while ((int64_t)i >= hi && b + 1 < s.where.T) {      // elements are asked for in ascending order
+                ++b;
+                lo = hi;
+                hi = s.where.iter_off[b + 1];
+            }
+            if (g < 0 || g >= s.R) {
+                atomicOr(&s.sc->error_flags, 1u);
+                g = 0;
+            }
+            return ((uint64_t)g << (s.ib + s.pb)) | ((uint64_t)b << s.pb) | (uint64_t)((int64_t)i - lo);
+        }
+    };
+};
 
 // ---- 2. unique pairs -------------------------------------------------------------------------
 struct HeadFlagIn {
     const uint64_t* keys;
+    int pb;
     __device__ __forceinline__ uint32_t operator()(int64_t p) const {
-        return (p == 0 || keys[p] != keys[p - 1]) ? 1u : 0u;
+        return (p == 0 || (keys[p] >> pb) != (keys[p - 1] >> pb)) ? 1u : 0u;
     }
 };
 struct PairOut {
     const uint64_t* keys;
-    uint64_t* ukey;
+    int pb;
+    uint64_t* ukey;           // (id << ib) | batch of every pair
     uint32_t* uq;
     uint32_t* pair_start;     // where the pair's lookups begin in the sorted order
     __device__ __forceinline__ void operator()(int64_t p, uint32_t exc, uint32_t inc) const {
         uq[p] = inc - 1u;
         if (inc != exc) {
-            ukey[exc] = keys[p];
+            ukey[exc] = keys[p] >> pb;
             pair_start[exc] = (uint32_t)p;
         }
     }
@@ -362,8 +386,8 @@ struct ListOut {
     uint32_t M;
     const uint32_t* pair_start;
     uint32_t n_sorted;        // lookups in the sorted order (carried rows included)
-    const uint32_t* spos;     // position of every sorted lookup
-    const int64_t* iter_off;  // batch offsets as the planner counts them
+    const uint64_t* skeys;    // the sorted lookups' words: the low pb bits are the place inside the batch
+    int pb;
     const int64_t* cuts;      // device [real batches][P + 1]
     int P;
     __device__ __forceinline__ int trainer_of(const int64_t* c, int64_t rel) const {
@@ -377,10 +401,10 @@ struct ListOut {
     __device__ __forceinline__ int32_t owner_of(uint32_t q, uint32_t i) const {
         if (ttl_shift && i == 0) return -1;               // a chunk's carried rows: no lookups
         const uint32_t a = pair_start[q], b = q + 1 < M ? pair_start[q + 1] : n_sorted;
-        const int64_t base = iter_off[i];
+        const uint64_t pmask = (uint64_t(1) << pb) - 1;
         const int64_t* c = cuts + (size_t)(i - ttl_shift) * (P + 1);
         // the pair's lookups are in position order and a trainer owns a stretch of positions: first and last decide
-        const int t0 = trainer_of(c, (int64_t)spos[a] - base), t1 = trainer_of(c, (int64_t)spos[b - 1] - base);
+        const int t0 = trainer_of(c, (int64_t)(skeys[a] & pmask)), t1 = trainer_of(c, (int64_t)(skeys[b - 1] & pmask));
         if (t0 == t1) return t0;
         const uint64_t imask = (uint64_t(1) << ib) - 1;
         const bool next = q + 1 < M && (ukey[q + 1] >> ib) == (ukey[q] >> ib) && (ukey[q + 1] & imask) == (uint64_t)i + 1;
@@ -482,59 +506,68 @@ __device__ __forceinline__ int64_t xcd_contiguous_block(uint32_t per_xcd) {
 }
 inline uint32_t blocks_per_xcd(int64_t n) { return (uint32_t)ceil_div(n > 0 ? ceil_div(n, kBlock) : 1, (int64_t)kXcds); }
 
-__global__ __launch_bounds__(kBlock) void plan_lookup_slots_kernel(int64_t N, uint32_t first,
-                                                                   const uint32_t* __restrict__ pos,
+__global__ __launch_bounds__(kBlock) void plan_lookup_slots_kernel(int64_t N, int64_t first, int ib, int pb,
+                                                                   const uint64_t* __restrict__ skeys,
+                                                                   const int64_t* __restrict__ iter_off,
                                                                    const uint32_t* __restrict__ uq,
                                                                    const int32_t* __restrict__ slot_of_pair,
                                                                    int32_t* __restrict__ lookup_slots) {
     const int64_t p = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (p < N && pos[p] >= first) lookup_slots[pos[p] - first] = slot_of_pair[uq[p]];   // below first: carried rows
+    if (p >= N) return;
+    const uint64_t k = skeys[p];
+    const int64_t pos = iter_off[(k >> pb) & ((uint64_t(1) << ib) - 1)] + (int64_t)(k & ((uint64_t(1) << pb) - 1));
+    if (pos >= first) lookup_slots[pos - first] = slot_of_pair[uq[p]];   // below first: carried rows
 }
 
 // ---- 8. lookups of every batch grouped by row (optional) ---------------------------------------
-// key <- (slot << iter_bits) | batch, written in the id-major order (where the pair indices, and so the reads of the
-// pairs' slots, ascend): a stable sort on the batch bits then lists every batch's lookups grouped by id and in lookup
-// order inside a group.  Inside one batch a change of slot is a change of row.  K is uint32_t when the key fits.
-template <typename K>
-__global__ __launch_bounds__(kBlock) void plan_group_keys_kernel(int64_t N, int ib, const uint64_t* skeys,
+// The id bits of every sorted word are replaced by the slot of its pair, in the id-major order (where the pair
+// indices, and so the reads of the pairs' slots, ascend): word = (slot << (ib + pb)) | (batch << pb) | place.  A
+// stable sort on the batch bits then lists every batch's lookups grouped by id and in lookup order inside a group.
+// Inside one batch a change of slot is a change of row.
+struct GroupWord {
+    int ib, pb;
+    __device__ __forceinline__ uint32_t slot(uint64_t k) const { return (uint32_t)(k >> (ib + pb)); }
+    __device__ __forceinline__ uint32_t batch(uint64_t k) const { return (uint32_t)(k >> pb) & ((1u << ib) - 1u); }
+    __device__ __forceinline__ uint32_t place(uint64_t k) const { return (uint32_t)(k & ((uint64_t(1) << pb) - 1)); }
+};
+__global__ __launch_bounds__(kBlock) void plan_group_keys_kernel(int64_t N, int ib, int pb, uint64_t* keys,
                                                                  const uint32_t* __restrict__ uq,
-                                                                 const int32_t* __restrict__ slot_of_pair, K* gkeys) {
+                                                                 const int32_t* __restrict__ slot_of_pair) {
     const int64_t p = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (p < N) gkeys[p] = ((K)(uint32_t)slot_of_pair[uq[p]] << ib) | (K)(skeys[p] & ((uint64_t(1) << ib) - 1));
+    if (p < N)
+        keys[p] = ((uint64_t)(uint32_t)slot_of_pair[uq[p]] << (ib + pb)) | (keys[p] & ((uint64_t(1) << (ib + pb)) - 1));
 }
 
 // A work item of the grouped backward pass starts where the row changes and at every multiple of kBwdChunk
 // positions counted from the batch's first lookup.  A row is "split" when its lookups go past the next two such
 // multiples, i.e. they span three items or more (a row spanning two items is finished by its first item).
 // Low word: item start flag; high word: first lookup of a split row.
-template <typename K>
 struct ItemFlagIn {
-    const K* gkeys;
-    const int64_t* iter_off;
-    int ib;
+    const uint64_t* gkeys;
+    BatchOfPos where;
+    GroupWord gw;
     int64_t first;          // entries below `first` are a chunk's carried residents, not lookups
     __device__ __forceinline__ uint64_t operator()(int64_t p) const {
         if (p < first) return 0;
-        const K k = gkeys[p];
-        const uint32_t i = (uint32_t)(k & ((K(1) << ib) - 1));
+        const uint64_t k = gkeys[p];
+        const int64_t* iter_off = where.iter_off;
+        const uint32_t i = gw.batch(k);
         const int64_t base = iter_off[i];
         const int64_t rel = p - base;
-        const bool first_of_row = rel == 0 || (gkeys[p - 1] >> ib) != (k >> ib);      // rel == 0 guards p == 0
+        const bool first_of_row = rel == 0 || gw.slot(gkeys[p - 1]) != gw.slot(k);      // rel == 0 guards p == 0
         const bool item = first_of_row || rel % kBwdChunk == 0;
         bool split = false;
         if (first_of_row) {
             const int64_t nb2 = base + (rel / kBwdChunk + 2) * kBwdChunk;              // second cut after p
-            split = nb2 < iter_off[i + 1] && (gkeys[nb2] >> ib) == (k >> ib);
+            split = nb2 < iter_off[i + 1] && gw.slot(gkeys[nb2]) == gw.slot(k);
         }
         return (uint64_t)item | ((uint64_t)split << 32);
     }
 };
-template <typename K>
 struct GroupOut {
-    const K* gkeys;
-    const uint32_t* gpos;
-    const int64_t* iter_off;
-    int ib;
+    const uint64_t* gkeys;
+    BatchOfPos where;
+    GroupWord gw;
     int32_t* grouped_slots;
     int32_t* grouped_lookups;
     uint32_t* item_starts;
@@ -544,13 +577,13 @@ struct GroupOut {
     int64_t first;         // entries below `first` are a chunk's carried residents: skipped, outputs start at `first`
     __device__ __forceinline__ void operator()(int64_t p, uint64_t exc, uint64_t inc) const {
         if (p < first) return;
-        const K k = gkeys[p];
-        const uint32_t i = (uint32_t)(k & ((K(1) << ib) - 1));
-        const int64_t base = iter_off[i];
-        grouped_slots[p - first] = (int32_t)(k >> ib);
-        grouped_lookups[p - first] = (int32_t)((int64_t)gpos[p] - base);
+        const uint64_t k = gkeys[p];
+        const uint32_t i = gw.batch(k);
+        const int64_t base = where.iter_off[i];
+        grouped_slots[p - first] = (int32_t)gw.slot(k);
+        grouped_lookups[p - first] = (int32_t)gw.place(k);
         if ((uint32_t)inc != (uint32_t)exc) {
-            const bool first_of_row = p == base || (gkeys[p - 1] >> ib) != (k >> ib);
+            const bool first_of_row = p == base || gw.slot(gkeys[p - 1]) != gw.slot(k);
             item_starts[(uint32_t)exc] = (uint32_t)(p - base) | (first_of_row ? 0x80000000u : 0u);
         }
         if ((inc >> 32) != (exc >> 32)) split_starts[exc >> 32] = (uint32_t)(p - base);
@@ -563,14 +596,15 @@ struct GroupOut {
 
 // The per-lookup slot map written from the batch-grouped order: the targets of neighbouring grouped lookups lie in
 // their batch's stretch of the map (a few MB at most).
-template <typename K>
-__global__ __launch_bounds__(kBlock) void plan_lookup_slots_grouped_kernel(int64_t N, uint32_t per_xcd, int ib,
+__global__ __launch_bounds__(kBlock) void plan_lookup_slots_grouped_kernel(int64_t N, uint32_t per_xcd, GroupWord gw,
                                                                            int64_t first,
-                                                                           const uint32_t* __restrict__ gpos,
-                                                                           const K* __restrict__ gkeys,
+                                                                           const uint64_t* __restrict__ gkeys,
+                                                                           BatchOfPos where,
                                                                            int32_t* __restrict__ lookup_slots) {
     const int64_t p = xcd_contiguous_block(per_xcd) * kBlock + threadIdx.x;
-    if (p >= first && p < N) lookup_slots[gpos[p] - first] = (int32_t)(gkeys[p] >> ib);
+    if (p < first || p >= N) return;
+    const uint64_t k = gkeys[p];
+    lookup_slots[where.iter_off[gw.batch(k)] + gw.place(k) - first] = (int32_t)gw.slot(k);
 }
 
 template <typename T>
@@ -629,7 +663,8 @@ __global__ __launch_bounds__(kBlock) void plan_state_queue_kernel(int64_t n_miss
 // ---- workspace layout ------------------------------------------------------------------------
 struct PlanWorkspace {
     uint64_t *keys_a, *keys_b;
-    uint32_t *pos_a, *pos_b;
+    uint32_t* uq;            // pair of every sorted lookup
+    int32_t* tile_batch;     // batch of every 4096-th position
     uint32_t* sort_temp;
     uint32_t* scan_partials32;   // head scan, chain scan
     uint64_t* scan_partials64;   // list scan
@@ -640,8 +675,7 @@ struct PlanWorkspace {
     uint32_t *chain, *val2_a, *val2_b, *missord, *evict_pair, *par, *pair_start;
     int64_t* cuts;           // trainer cuts of every batch, [T][kMaxTrainers + 1] at most
     int32_t* slot_of_pair;
-    uint64_t* keys_c;      // grouping only
-    uint32_t* pos_c;
+    uint64_t* keys_c;      // grouping only: the other half of the regrouping sort's ping-pong
     int64_t* item_off;
     int64_t* split_off;
     size_t bytes;
@@ -653,8 +687,8 @@ PlanWorkspace carve_plan(void* base, size_t cap, int64_t N, int T, int Lcap, boo
     const size_t n = (size_t)(N > 0 ? N : 1);
     w.keys_a = c.take<uint64_t>(n);
     w.keys_b = c.take<uint64_t>(n);
-    w.pos_a = c.take<uint32_t>(n);
-    w.pos_b = c.take<uint32_t>(n);
+    w.uq = c.take<uint32_t>(n);
+    w.tile_batch = c.take<int32_t>((n >> kPosTileShift) + 2);
     w.sort_temp = c.take<uint32_t>(sort_temp_words<kPlanSortIPT>(N));
     w.scan_partials32 = c.take<uint32_t>(scan_partials(N));
     w.scan_partials64 = c.take<uint64_t>(scan_partials(N));
@@ -683,7 +717,6 @@ PlanWorkspace carve_plan(void* base, size_t cap, int64_t N, int T, int Lcap, boo
     w.slot_of_pair = c.take<int32_t>(n);
     if (grouping) {
         w.keys_c = c.take<uint64_t>(n);
-        w.pos_c = c.take<uint32_t>(n);
         w.item_off = c.take<int64_t>(T + 1);
         w.split_off = c.take<int64_t>(T + 1);
     }
@@ -701,38 +734,6 @@ int check_plan_args(const bp_config* cfg, int64_t N, int32_t T) {
 }
 
 inline dim3 grid_for(int64_t n) { return dim3((unsigned)(n > 0 ? ceil_div(n, kBlock) : 1)); }
-
-// Step 8 for one key width.  ka receives the keys (for 64-bit keys it may be the sorted (id, batch) keys' own
-// buffer: every element is read and written by the same lane), kb is the other half of the ping-pong.
-struct GroupingPass {
-    int64_t N;
-    int64_t first;        // carried residents in front of the lookups (0 outside chunk mode)
-    int T, ib;
-    const uint64_t* skeys;
-    uint32_t* spos;
-    const uint32_t* uq;
-    PlanWorkspace* w;
-    bp_plan* plan;
-    hipStream_t stream;
-    template <typename K>
-    int run(K* ka, K* kb) {
-        BP_LAUNCH(K_PLAN_GROUP, plan_group_keys_kernel<K>, grid_for(N), dim3(kBlock), 0, stream, N, ib, skeys, uq,
-                  (const int32_t*)w->slot_of_pair, ka);
-        bool in_b = false;
-        BP_TRY((radix_sort_pairs<K, kPlanSortIPT>(ka, kb, spos, w->pos_c, N, 0, ib, w->sort_temp, stream, &in_b)));
-        const K* gkeys = in_b ? kb : ka;
-        const uint32_t* gpos = in_b ? w->pos_c : spos;
-        BP_TRY((device_scan<uint64_t, AddOp, ItemFlagIn<K>, GroupOut<K>>(
-            ItemFlagIn<K>{gkeys, w->iter_off, ib, first},
-            GroupOut<K>{gkeys, gpos, w->iter_off, ib, plan->grouped_slots, plan->grouped_lookups, plan->item_starts,
-                        plan->split_starts, w->item_off, w->split_off, first},
-            N, w->scan_partials64, AddOp(), uint64_t(0), stream)));
-        const uint32_t per_xcd = blocks_per_xcd(N);
-        BP_LAUNCH(K_PLAN_SLOTS, plan_lookup_slots_grouped_kernel<K>, dim3(per_xcd * kXcds), dim3(kBlock), 0, stream, N,
-                  per_xcd, ib, first, gpos, gkeys, plan->lookup_slots);
-        return BP_OK;
-    }
-};
 
 }  // namespace
 }  // namespace bp
@@ -844,30 +845,37 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
     std::vector<int64_t> voff((size_t)T + 1);            // batch offsets as the planner counts them
     voff[0] = 0;
     for (int i = 0; i <= T_in; ++i) voff[(size_t)i + shift] = R0 + iter_offsets[i];
+    int64_t largest = 1;
+    for (int i = 0; i < T; ++i) largest = std::max(largest, voff[(size_t)i + 1] - voff[(size_t)i]);
+    const int pb = bits_for(largest);                    // bits of a lookup's place inside its batch
+    if (gb + ib + pb > 64 || 32 + ib + pb > 64)
+        return fail(BP_ERR_UNSUPPORTED, "id or slot bits (%d / 32) + batch bits (%d) + bits of the largest batch (%d) exceed 64",
+                    gb, ib, pb);
 
     // ---- 1. keys + sort
     BP_HIP(hipMemcpyAsync(w.iter_off, voff.data(), sizeof(int64_t) * (T + 1), hipMemcpyHostToDevice, stream));
+    BP_LAUNCH(K_PLAN_KEYS, plan_tile_batch_kernel, grid_for((N >> kPosTileShift) + 1), dim3(kBlock), 0, stream,
+              (const int64_t*)w.iter_off, T, (N >> kPosTileShift) + 1, w.tile_batch);
     BP_HIP(hipMemsetAsync(w.scalars, 0, sizeof(PlanScalars), stream));
     if (owners)
         BP_HIP(hipMemcpyAsync(w.cuts, plan->trainer_cuts, sizeof(int64_t) * (size_t)T_in * (P + 1), hipMemcpyHostToDevice,
                               stream));
-    if (R0)
-        BP_LAUNCH(K_PLAN_KEYS, plan_resident_keys_kernel, grid_for(R0), dim3(kBlock), 0, stream,
-                  (const int64_t*)ch->in->resident_ids, R0, cfg->total_rows, ib, w.keys_a, w.pos_a, w.scalars);
-    if (N_real)
-        BP_LAUNCH(K_PLAN_KEYS, plan_keys_kernel, grid_for(N_real), dim3(kBlock), 0, stream, ids, (const int64_t*)w.iter_off, T,
-                  R0, N, cfg->total_rows, ib, w.keys_a, w.pos_a, w.scalars);
-    bool in_b = false;
-    // the lookups arrive batch by batch, so a stable sort on the id bits alone leaves every id's keys in batch order
-    BP_TRY((radix_sort_pairs<uint64_t, kPlanSortIPT>(w.keys_a, w.keys_b, w.pos_a, w.pos_b, N, ib, ib + gb, w.sort_temp,
-                                                     stream, &in_b)));
-    const uint64_t* skeys = in_b ? w.keys_b : w.keys_a;
-    const uint32_t* spos = in_b ? w.pos_b : w.pos_a;
-    uint64_t* ukey = in_b ? w.keys_a : w.keys_b;   // the other ping-pong buffers are free now
-    uint32_t* uq = in_b ? w.pos_a : w.pos_b;
+    // the lookups arrive batch by batch, so a stable sort on the id bits alone leaves every id's words in batch order
+    // and, inside a batch, in lookup order
+    const BatchOfPos where{w.tile_batch, w.iter_off, T};
+    const PlanKeySource source{ids, chunk && ch->in ? ch->in->resident_ids : nullptr, R0, where, ib, pb, cfg->total_rows,
+                               w.scalars};
+    uint64_t* const kbuf[2] = {w.keys_a, w.keys_b};
+    uint32_t* const no_vals[2] = {nullptr, nullptr};
+    int sorted_in = -1;
+    BP_TRY((radix_sort_from<uint64_t, kPlanSortIPT, PlanKeySource, false>(source, kbuf, no_vals, N, ib + pb, ib + pb + gb,
+                                                                          w.sort_temp, stream, &sorted_in)));
+    const uint64_t* skeys = kbuf[sorted_in];
+    uint64_t* ukey = kbuf[sorted_in ^ 1];          // the other ping-pong buffer is free now
+    uint32_t* uq = w.uq;
 
     // ---- 2. unique pairs
-    BP_TRY((device_scan<uint32_t, AddOp, HeadFlagIn, PairOut>(HeadFlagIn{skeys}, PairOut{skeys, ukey, uq, w.pair_start}, N,
+    BP_TRY((device_scan<uint32_t, AddOp, HeadFlagIn, PairOut>(HeadFlagIn{skeys, pb}, PairOut{skeys, pb, ukey, uq, w.pair_start}, N,
                                                               w.scan_partials32, AddOp(), 0u, stream)));
     uint32_t M = 0;
     PlanScalars hs{};
@@ -944,7 +952,7 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
         ListCountIn{srec, ib},
         ListOut{srec, ord, w.pair_off, ib, plan->keep_ids, plan->keep_ttl, plan->prefetch_ids, plan->evict_ids, w.missord,
                 w.evict_pair, w.prefetch_off, w.evict_off, shift, owners ? plan->keep_owner : nullptr, ukey, M,
-                w.pair_start, (uint32_t)N, spos, w.iter_off, w.cuts, P},
+                w.pair_start, (uint32_t)N, skeys, pb, w.cuts, P},
         M, w.scan_partials64, AddOp(), uint64_t(0), stream)));
     const uint64_t* totals = w.scan_partials64 + scan_num_tiles(M);
 
@@ -962,8 +970,8 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
               (const uint32_t*)w.evict_pair, (const int32_t*)w.slot_of_pair, ring0, C, plan->prefetch_slots,
               plan->evict_slots);
     if (!grouping && N_real)      // with grouping the slot map is written from the batch-grouped order (step 8)
-        BP_LAUNCH(K_PLAN_SLOTS, plan_lookup_slots_kernel, grid_for(N), dim3(kBlock), 0, stream, N, (uint32_t)R0, spos,
-                  (const uint32_t*)uq, (const int32_t*)w.slot_of_pair, plan->lookup_slots);
+        BP_LAUNCH(K_PLAN_SLOTS, plan_lookup_slots_kernel, grid_for(N), dim3(kBlock), 0, stream, N, R0, ib, pb, skeys,
+                  (const int64_t*)w.iter_off, (const uint32_t*)uq, (const int32_t*)w.slot_of_pair, plan->lookup_slots);
 
     uint64_t htot = 0;     // miss / evict totals: fetched now, the grouping scan below reuses the partials buffer
     BP_HIP(hipMemcpyAsync(&htot, totals, sizeof(uint64_t), hipMemcpyDeviceToHost, stream));
@@ -976,11 +984,21 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
                   (int64_t)-1);
         BP_LAUNCH(K_FILL, fill_kernel<int64_t>, grid_for(T + 1), dim3(kBlock), 0, stream, w.split_off, (int64_t)(T + 1),
                   (int64_t)-1);
-        GroupingPass g{N, R0, T, ib, skeys, const_cast<uint32_t*>(spos), uq, &w, plan, stream};
-        if (bits_for(C) + ib <= 32)
-            BP_TRY(g.run<uint32_t>(reinterpret_cast<uint32_t*>(w.keys_c), reinterpret_cast<uint32_t*>(w.keys_c) + N));
-        else
-            BP_TRY(g.run<uint64_t>(const_cast<uint64_t*>(skeys), w.keys_c));
+        uint64_t* ka = const_cast<uint64_t*>(skeys);      // the sorted words are not needed any more: regrouped in place
+        BP_LAUNCH(K_PLAN_GROUP, plan_group_keys_kernel, grid_for(N), dim3(kBlock), 0, stream, N, ib, pb, ka,
+                  (const uint32_t*)uq, (const int32_t*)w.slot_of_pair);
+        bool g_in_b = false;
+        BP_TRY((radix_sort_keys<uint64_t, kPlanSortIPT>(ka, w.keys_c, N, pb, pb + ib, w.sort_temp, stream, &g_in_b)));
+        const uint64_t* gkeys = g_in_b ? w.keys_c : ka;
+        const GroupWord gw{ib, pb};
+        BP_TRY((device_scan<uint64_t, AddOp, ItemFlagIn, GroupOut>(
+            ItemFlagIn{gkeys, where, gw, R0},
+            GroupOut{gkeys, where, gw, plan->grouped_slots, plan->grouped_lookups, plan->item_starts,
+                     plan->split_starts, w.item_off, w.split_off, R0},
+            N, w.scan_partials64, AddOp(), uint64_t(0), stream)));
+        const uint32_t per_xcd = blocks_per_xcd(N);
+        BP_LAUNCH(K_PLAN_SLOTS, plan_lookup_slots_grouped_kernel, dim3(per_xcd * kXcds), dim3(kBlock), 0, stream, N, per_xcd,
+                  gw, R0, gkeys, where, plan->lookup_slots);
         hitem.resize((size_t)T + 1);
         hsplit.resize((size_t)T + 1);
         BP_HIP(hipMemcpyAsync(&n_items_split, w.scan_partials64 + scan_num_tiles(N), sizeof(uint64_t), hipMemcpyDeviceToHost,
