@@ -382,13 +382,15 @@ inline size_t sort_temp_words(int64_t n) {
     return counts + 64 + scan_partials((int64_t)counts) + 64;
 }
 
-template <typename K, int IPT, int RB, typename Src, bool VALS>
-int radix_sort_pass(const Src& src, K* kout, uint32_t* vout, int64_t n, int bit, int nb, uint32_t* counts,
+// One pass.  The histogram reads `up`, the scatter reads `src`: the same elements, but a source that has to fetch
+// more than the digit needs may leave that to the scatter alone.
+template <typename K, int IPT, int RB, typename Up, typename Src, bool VALS>
+int radix_sort_pass(const Up& up, const Src& src, K* kout, uint32_t* vout, int64_t n, int bit, int nb, uint32_t* counts,
                     uint32_t* partials, uint32_t ntiles, hipStream_t stream) {
     const int64_t ncounts = (int64_t)(1 << RB) * ntiles;
     const uint32_t mask = (1u << nb) - 1u;
-    BP_LAUNCH(K_SORT_UPSWEEP, (sort_upsweep_kernel<K, IPT, RB, Src>), dim3(sort_grid(ntiles)), dim3(kSortBlock), 0, stream,
-              src, (uint32_t)n, bit, mask, counts, ntiles);
+    BP_LAUNCH(K_SORT_UPSWEEP, (sort_upsweep_kernel<K, IPT, RB, Up>), dim3(sort_grid(ntiles)), dim3(kSortBlock), 0, stream,
+              up, (uint32_t)n, bit, mask, counts, ntiles);
     BP_TRY((device_scan<uint32_t, AddOp, LoadU32, StoreExclusiveU32>(LoadU32{counts}, StoreExclusiveU32{counts}, ncounts,
                                                                      partials, AddOp(), 0u, stream)));
     BP_LAUNCH(K_SORT_DOWNSWEEP, (sort_downsweep_kernel<K, IPT, RB, Src, VALS>), dim3(sort_grid(ntiles)), dim3(kSortBlock), 0,
@@ -396,20 +398,21 @@ int radix_sort_pass(const Src& src, K* kout, uint32_t* vout, int64_t n, int bit,
     return BP_OK;
 }
 
-template <typename K, int IPT, typename Src, bool VALS>
-int radix_sort_one_pass(const Src& src, K* kout, uint32_t* vout, int64_t n, int bit, int nb, uint32_t* counts,
-                        uint32_t* partials, uint32_t ntiles, hipStream_t stream) {
-    if (nb > 8) return radix_sort_pass<K, IPT, 9, Src, VALS>(src, kout, vout, n, bit, nb, counts, partials, ntiles, stream);
-    return radix_sort_pass<K, IPT, 8, Src, VALS>(src, kout, vout, n, bit, nb, counts, partials, ntiles, stream);
+template <typename K, int IPT, typename Up, typename Src, bool VALS>
+int radix_sort_one_pass(const Up& up, const Src& src, K* kout, uint32_t* vout, int64_t n, int bit, int nb,
+                        uint32_t* counts, uint32_t* partials, uint32_t ntiles, hipStream_t stream) {
+    if (nb > 8)
+        return radix_sort_pass<K, IPT, 9, Up, Src, VALS>(up, src, kout, vout, n, bit, nb, counts, partials, ntiles, stream);
+    return radix_sort_pass<K, IPT, 8, Up, Src, VALS>(up, src, kout, vout, n, bit, nb, counts, partials, ntiles, stream);
 }
 
-// Stable sort of n elements by key bits [begin_bit, end_bit).  The first pass reads `first` (any source) and writes
-// buffer 0, every later pass reads the buffer the one before wrote and writes the other one; *result says which
-// buffer holds the sorted output (-1: no pass ran, nothing was written).  VALS: 32-bit values travel with the keys.
-// n < 2^32 - kSortBlock*IPT.
-template <typename K, int IPT, typename Src, bool VALS>
-int radix_sort_from(const Src& first, K* const kbuf[2], uint32_t* const vbuf[2], int64_t n, int begin_bit, int end_bit,
-                    uint32_t* temp, hipStream_t stream, int* result) {
+// Stable sort of n elements by key bits [begin_bit, end_bit).  The first pass reads `first` (any source; its
+// histogram reads `first_up`, which must give the same sorted bits) and writes buffer 0, every later pass reads the
+// buffer the one before wrote and writes the other one; *result says which buffer holds the sorted output (-1: no
+// pass ran, nothing was written).  VALS: 32-bit values travel with the keys.  n < 2^32 - kSortBlock*IPT.
+template <typename K, int IPT, typename Up, typename Src, bool VALS>
+int radix_sort_from(const Up& first_up, const Src& first, K* const kbuf[2], uint32_t* const vbuf[2], int64_t n,
+                    int begin_bit, int end_bit, uint32_t* temp, hipStream_t stream, int* result) {
     *result = -1;
     if (n <= 0 || end_bit <= begin_bit) return BP_OK;
     const uint32_t ntiles = sort_num_tiles<IPT>(n);
@@ -423,12 +426,13 @@ int radix_sort_from(const Src& first, K* const kbuf[2], uint32_t* const vbuf[2],
         const int nb = (left + (passes - p) - 1) / (passes - p);      // spread the remaining bits evenly
         const int out = p & 1;
         if (p == 0) {
-            BP_TRY((radix_sort_one_pass<K, IPT, Src, VALS>(first, kbuf[out], VALS ? vbuf[out] : nullptr, n, bit, nb, counts,
-                                                           partials, ntiles, stream)));
+            BP_TRY((radix_sort_one_pass<K, IPT, Up, Src, VALS>(first_up, first, kbuf[out], VALS ? vbuf[out] : nullptr, n, bit,
+                                                               nb, counts, partials, ntiles, stream)));
         } else {
             const SortArrays<K> in{kbuf[out ^ 1], VALS ? vbuf[out ^ 1] : nullptr};
-            BP_TRY((radix_sort_one_pass<K, IPT, SortArrays<K>, VALS>(in, kbuf[out], VALS ? vbuf[out] : nullptr, n, bit, nb,
-                                                                     counts, partials, ntiles, stream)));
+            BP_TRY((radix_sort_one_pass<K, IPT, SortArrays<K>, SortArrays<K>, VALS>(in, in, kbuf[out],
+                                                                                    VALS ? vbuf[out] : nullptr, n, bit, nb,
+                                                                                    counts, partials, ntiles, stream)));
         }
         bit += nb;
         *result = out;
@@ -445,8 +449,9 @@ int radix_sort_pairs(K* keys_a, K* keys_b, uint32_t* vals_a, uint32_t* vals_b, i
     K* const kbuf[2] = {keys_b, keys_a};
     uint32_t* const vbuf[2] = {vals_b, vals_a};
     int result = -1;
-    BP_TRY((radix_sort_from<K, IPT, SortArrays<K>, true>(SortArrays<K>{keys_a, vals_a}, kbuf, vbuf, n, begin_bit, end_bit, temp,
-                                                         stream, &result)));
+    const SortArrays<K> in{keys_a, vals_a};
+    BP_TRY((radix_sort_from<K, IPT, SortArrays<K>, SortArrays<K>, true>(in, in, kbuf, vbuf, n, begin_bit, end_bit, temp, stream,
+                                                                        &result)));
     *result_in_b = result == 0;
     return BP_OK;
 }
@@ -458,8 +463,9 @@ int radix_sort_keys(K* keys_a, K* keys_b, int64_t n, int begin_bit, int end_bit,
     K* const kbuf[2] = {keys_b, keys_a};
     uint32_t* const vbuf[2] = {nullptr, nullptr};
     int result = -1;
-    BP_TRY((radix_sort_from<K, IPT, SortArrays<K>, false>(SortArrays<K>{keys_a, nullptr}, kbuf, vbuf, n, begin_bit, end_bit,
-                                                          temp, stream, &result)));
+    const SortArrays<K> in{keys_a, nullptr};
+    BP_TRY((radix_sort_from<K, IPT, SortArrays<K>, SortArrays<K>, false>(in, in, kbuf, vbuf, n, begin_bit, end_bit, temp, stream,
+                                                                         &result)));
     *result_in_b = result == 0;
     return BP_OK;
 }

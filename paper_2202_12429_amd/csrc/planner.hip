@@ -530,13 +530,26 @@ struct GroupWord {
     __device__ __forceinline__ uint32_t batch(uint64_t k) const { return (uint32_t)(k >> pb) & ((1u << ib) - 1u); }
     __device__ __forceinline__ uint32_t place(uint64_t k) const { return (uint32_t)(k & ((uint64_t(1) << pb) - 1)); }
 };
-__global__ __launch_bounds__(kBlock) void plan_group_keys_kernel(int64_t N, int ib, int pb, uint64_t* keys,
-                                                                 const uint32_t* __restrict__ uq,
-                                                                 const int32_t* __restrict__ slot_of_pair) {
-    const int64_t p = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (p < N)
-        keys[p] = ((uint64_t)(uint32_t)slot_of_pair[uq[p]] << (ib + pb)) | (keys[p] & ((uint64_t(1) << (ib + pb)) - 1));
-}
+// The regrouping sort's scatter makes these words as it reads its input (its histogram only needs the batch bits,
+// which the sorted words already hold).
+struct GroupWordSource {
+    const uint64_t* skeys;
+    const uint32_t* uq;
+    const int32_t* slot_of_pair;
+    int low;                                  // ib + pb: the bits kept from the sorted word
+    struct Raw {
+        uint64_t k;
+        uint32_t q;
+    };
+    __device__ __forceinline__ Raw load(uint32_t i) const { return Raw{skeys[i], uq[i]}; }
+    struct Cursor {
+        const GroupWordSource& s;
+        __device__ __forceinline__ Cursor(const GroupWordSource& src, uint32_t) : s(src) {}
+        __device__ __forceinline__ uint64_t key(uint32_t, Raw raw) {
+            return ((uint64_t)(uint32_t)s.slot_of_pair[raw.q] << s.low) | (raw.k & ((uint64_t(1) << s.low) - 1));
+        }
+    };
+};
 
 // A work item of the grouped backward pass starts where the row changes and at every multiple of kBwdChunk
 // positions counted from the batch's first lookup.  A row is "split" when its lookups go past the next two such
@@ -868,8 +881,8 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
     uint64_t* const kbuf[2] = {w.keys_a, w.keys_b};
     uint32_t* const no_vals[2] = {nullptr, nullptr};
     int sorted_in = -1;
-    BP_TRY((radix_sort_from<uint64_t, kPlanSortIPT, PlanKeySource, false>(source, kbuf, no_vals, N, ib + pb, ib + pb + gb,
-                                                                          w.sort_temp, stream, &sorted_in)));
+    BP_TRY((radix_sort_from<uint64_t, kPlanSortIPT, PlanKeySource, PlanKeySource, false>(
+        source, source, kbuf, no_vals, N, ib + pb, ib + pb + gb, w.sort_temp, stream, &sorted_in)));
     const uint64_t* skeys = kbuf[sorted_in];
     uint64_t* ukey = kbuf[sorted_in ^ 1];          // the other ping-pong buffer is free now
     uint32_t* uq = w.uq;
@@ -984,12 +997,15 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
                   (int64_t)-1);
         BP_LAUNCH(K_FILL, fill_kernel<int64_t>, grid_for(T + 1), dim3(kBlock), 0, stream, w.split_off, (int64_t)(T + 1),
                   (int64_t)-1);
-        uint64_t* ka = const_cast<uint64_t*>(skeys);      // the sorted words are not needed any more: regrouped in place
-        BP_LAUNCH(K_PLAN_GROUP, plan_group_keys_kernel, grid_for(N), dim3(kBlock), 0, stream, N, ib, pb, ka,
-                  (const uint32_t*)uq, (const int32_t*)w.slot_of_pair);
-        bool g_in_b = false;
-        BP_TRY((radix_sort_keys<uint64_t, kPlanSortIPT>(ka, w.keys_c, N, pb, pb + ib, w.sort_temp, stream, &g_in_b)));
-        const uint64_t* gkeys = g_in_b ? w.keys_c : ka;
+        // one pass as a rule (batch bits <= 9): out of the sorted words into the spare buffer; a second pass would
+        // come back into the sorted words' own buffer, which nobody reads any more by then
+        const GroupWordSource gsrc{skeys, uq, w.slot_of_pair, ib + pb};
+        const SortArrays<uint64_t> gup{skeys, nullptr};
+        uint64_t* const gbuf[2] = {w.keys_c, const_cast<uint64_t*>(skeys)};
+        int g_in = -1;
+        BP_TRY((radix_sort_from<uint64_t, kPlanSortIPT, SortArrays<uint64_t>, GroupWordSource, false>(
+            gup, gsrc, gbuf, no_vals, N, pb, pb + ib, w.sort_temp, stream, &g_in)));
+        const uint64_t* gkeys = gbuf[g_in];
         const GroupWord gw{ib, pb};
         BP_TRY((device_scan<uint64_t, AddOp, ItemFlagIn, GroupOut>(
             ItemFlagIn{gkeys, where, gw, R0},

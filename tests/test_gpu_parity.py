@@ -467,6 +467,12 @@ def test_plan_errors(bp):
     with pytest.raises(bp.BagpipeError) as e:
         bp.bp_oracle_plan(bp.make_config(10, 8, 16, lookahead=2), dev(ids), off, list_capacity=3)
     assert e.value.status == -3 and e.value.info["n_unique_pairs"] == 6
+    # id bits + batch bits + bits of the largest batch beyond one 64-bit word: refused, nothing is launched
+    big = np.arange(1 << 17, dtype=np.int64)
+    with pytest.raises(bp.BagpipeError) as e:
+        bp.bp_oracle_plan(bp.make_config(1 << 44, 1 << 18, 16, lookahead=2), dev(big),
+                          np.concatenate([np.zeros(30, np.int64), [1 << 17]]))
+    assert e.value.status == -6
     # an all-empty trace plans to nothing
     p = bp.bp_oracle_plan(bp.make_config(10, 8, 16, lookahead=2), torch.zeros(0, dtype=torch.int64, device="cuda"),
                           np.zeros(4, np.int64))
