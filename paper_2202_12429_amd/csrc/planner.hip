@@ -17,7 +17,7 @@
 //      miss / evict ordinals by one packed scan
 //   6. FIFO free ring without a walk over batches: the x-th miss takes ring position x; positions below
 //      C are the initial slots, position C + e holds the slot freed by the e-th eviction, i.e. the slot
-//      of an earlier miss.  Following those links is pointer jumping, ceil(log2 T) + 1 rounds.
+//      of an earlier miss.  Every miss follows those links to the end of its chain (plan_ring_resolve_kernel).
 //   7. slots of pairs -> list slots and the per-lookup slot map
 //   8. (optional) one more stable pass on the batch bits, with (slot, batch) keys, lists every batch's lookups grouped
 //      by row, with the work-item cuts the grouped backward pass uses, so that the backward pass need not sort
@@ -436,7 +436,7 @@ struct ListOut {
     }
 };
 
-// ---- 6. FIFO ring by pointer jumping ---------------------------------------------------------
+// ---- 6. FIFO ring: chains of links ------------------------------------------------------------
 __global__ __launch_bounds__(kBlock) void plan_ring_init_kernel(const uint64_t* __restrict__ totals, int64_t C,
                                                                 const uint32_t* __restrict__ evict_pair,
                                                                 const uint32_t* __restrict__ chain,
@@ -453,13 +453,24 @@ __global__ __launch_bounds__(kBlock) void plan_ring_init_kernel(const uint64_t* 
     }
 }
 
-__global__ __launch_bounds__(kBlock) void plan_ring_jump_kernel(const uint64_t* __restrict__ totals, uint32_t* par) {
+// Every miss walks its own chain towards the ring position below C it ends at, kRingHops hops per launch at most,
+// and leaves with a link to where it got.  A hop goes back at least one batch, so a chain has at most T hops and
+// ceil(log_kRingHops(T + 1)) launches resolve everything whatever the trace (in practice a slot changes hands a few
+// times over a trace and the first launch does it all).  Lanes read entries that other lanes may have advanced
+// already: either value lies on the same chain, the newer one nearer to its end.
+constexpr int kRingHops = 64;
+__global__ __launch_bounds__(kBlock) void plan_ring_resolve_kernel(const uint64_t* __restrict__ totals, int max_hops,
+                                                                   uint32_t* par) {
     const uint32_t n_miss = (uint32_t)*totals;
     const uint32_t x = blockIdx.x * kBlock + threadIdx.x;
     if (x >= n_miss) return;
-    const uint32_t p = par[x];
-    const uint32_t pp = p < n_miss ? par[p] : 0u;
-    if (pp != p) par[x] = pp;
+    uint32_t p = par[x];
+    for (int hop = 0; hop < max_hops; ++hop) {
+        const uint32_t pp = p < n_miss ? par[p] : 0u;
+        if (pp == p) break;
+        p = pp;
+    }
+    par[x] = p;
 }
 
 // ---- 7. slots --------------------------------------------------------------------------------
@@ -972,9 +983,8 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
     // ---- 6. ring
     BP_LAUNCH(K_PLAN_JUMP, plan_ring_init_kernel, grid_for(M), dim3(kBlock), 0, stream, totals, C,
               (const uint32_t*)w.evict_pair, (const uint32_t*)w.chain, (const uint32_t*)w.missord, w.par);
-    const int rounds = bits_for(T) + 1;
-    for (int r = 0; r < rounds; ++r)
-        BP_LAUNCH(K_PLAN_JUMP, plan_ring_jump_kernel, grid_for(M), dim3(kBlock), 0, stream, totals, w.par);
+    for (int64_t reach = 1; reach < (int64_t)T + 1; reach *= kRingHops)
+        BP_LAUNCH(K_PLAN_JUMP, plan_ring_resolve_kernel, grid_for(M), dim3(kBlock), 0, stream, totals, kRingHops, w.par);
 
     // ---- 7. slots
     BP_LAUNCH(K_PLAN_SLOTS, plan_pair_slots_kernel, grid_for(M), dim3(kBlock), 0, stream, M, (const uint32_t*)w.chain,

@@ -441,9 +441,10 @@ def test_plan_medium_multi_tile(bp):
 
 
 def test_plan_many_batches_wide_group_keys(bp):
-    """4,100 short batches (13 batch bits) with a capacity of 2^20: slot and batch bits together exceed 32, so the
-    grouping runs on 64-bit keys; the other plan tests take the 32-bit path."""
-    say("plan with many batches and wide grouping keys")
+    """4,100 short batches (13 batch bits) with a capacity of 2^20 (wide slot and batch fields in the lookups' words),
+    then with 9 slots: every slot changes hands hundreds of times, so the chains of the free ring are far longer than
+    one launch of the chain walk follows."""
+    say("plan with many batches: wide words, long slot chains")
     rng = np.random.default_rng(77)
     T, R = 4100, 300
     lens = rng.integers(0, 9, size=T)
