@@ -694,7 +694,7 @@ struct PlanWorkspace {
     uint64_t* scan_partials64;   // list scan
     uint32_t *H, *ucount, *first_use, *peak, *pair_off, *V, *vcover;
     PlanScalars* scalars;
-    int64_t *occ, *prefetch_off, *evict_off, *iter_off;
+    int64_t *occ, *offsets, *prefetch_off, *evict_off, *iter_off;
     uint64_t *rec_a, *rec_b;
     uint32_t *chain, *val2_a, *val2_b, *missord, *evict_pair, *par, *pair_start;
     int64_t* cuts;           // trainer cuts of every batch, [T][kMaxTrainers + 1] at most
@@ -722,11 +722,15 @@ PlanWorkspace carve_plan(void* base, size_t cap, int64_t N, int T, int Lcap, boo
     w.V = c.take<uint32_t>(T + 1);
     w.vcover = c.take<uint32_t>(T + 1);
     w.peak = c.take<uint32_t>(Lcap + 2);
-    w.pair_off = c.take<uint32_t>(T + 1);
     w.scalars = c.take<PlanScalars>(1);
     w.occ = c.take<int64_t>(T);
-    w.prefetch_off = c.take<int64_t>(T + 1);
-    w.evict_off = c.take<int64_t>(T + 1);
+    // the per-batch offsets the host reads at the end, side by side so that one copy fetches them all
+    w.offsets = c.take<int64_t>(5 * (size_t)(T + 1));
+    w.prefetch_off = w.offsets;
+    w.evict_off = w.offsets + (T + 1);
+    w.item_off = w.offsets + 2 * (size_t)(T + 1);
+    w.split_off = w.offsets + 3 * (size_t)(T + 1);
+    w.pair_off = reinterpret_cast<uint32_t*>(w.offsets + 4 * (size_t)(T + 1));
     w.iter_off = c.take<int64_t>(T + 1);
     w.rec_a = c.take<uint64_t>(n);
     w.rec_b = c.take<uint64_t>(n);
@@ -741,8 +745,6 @@ PlanWorkspace carve_plan(void* base, size_t cap, int64_t N, int T, int Lcap, boo
     w.slot_of_pair = c.take<int32_t>(n);
     if (grouping) {
         w.keys_c = c.take<uint64_t>(n);
-        w.item_off = c.take<int64_t>(T + 1);
-        w.split_off = c.take<int64_t>(T + 1);
     }
     w.bytes = c.used();
     return w;
@@ -968,9 +970,8 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
                                                      &ord_in_b)));
     const uint64_t* srec = ord_in_b ? w.rec_b : w.rec_a;
     const uint32_t* ord = ord_in_b ? w.val2_b : w.val2_a;
-    BP_LAUNCH(K_FILL, fill_kernel<int64_t>, grid_for(T + 1), dim3(kBlock), 0, stream, w.prefetch_off, (int64_t)(T + 1),
-              (int64_t)-1);
-    BP_LAUNCH(K_FILL, fill_kernel<int64_t>, grid_for(T + 1), dim3(kBlock), 0, stream, w.evict_off, (int64_t)(T + 1),
+    // prefetch, evict, item and split offsets start at -1 ("this batch owns no entry")
+    BP_LAUNCH(K_FILL, fill_kernel<int64_t>, grid_for(4 * (T + 1)), dim3(kBlock), 0, stream, w.offsets, (int64_t)(4 * (T + 1)),
               (int64_t)-1);
     BP_TRY((device_scan<uint64_t, AddOp, ListCountIn, ListOut>(
         ListCountIn{srec, ib},
@@ -1001,12 +1002,7 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
 
     // ---- 8. grouping for the backward pass
     uint64_t n_items_split = 0;
-    std::vector<int64_t> hitem, hsplit;
     if (grouping) {
-        BP_LAUNCH(K_FILL, fill_kernel<int64_t>, grid_for(T + 1), dim3(kBlock), 0, stream, w.item_off, (int64_t)(T + 1),
-                  (int64_t)-1);
-        BP_LAUNCH(K_FILL, fill_kernel<int64_t>, grid_for(T + 1), dim3(kBlock), 0, stream, w.split_off, (int64_t)(T + 1),
-                  (int64_t)-1);
         // one pass as a rule (batch bits <= 9): out of the sorted words into the spare buffer; a second pass would
         // come back into the sorted words' own buffer, which nobody reads any more by then
         const GroupWordSource gsrc{skeys, uq, w.slot_of_pair, ib + pb};
@@ -1025,22 +1021,20 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
         const uint32_t per_xcd = blocks_per_xcd(N);
         BP_LAUNCH(K_PLAN_SLOTS, plan_lookup_slots_grouped_kernel, dim3(per_xcd * kXcds), dim3(kBlock), 0, stream, N, per_xcd,
                   gw, R0, gkeys, where, plan->lookup_slots);
-        hitem.resize((size_t)T + 1);
-        hsplit.resize((size_t)T + 1);
         BP_HIP(hipMemcpyAsync(&n_items_split, w.scan_partials64 + scan_num_tiles(N), sizeof(uint64_t), hipMemcpyDeviceToHost,
                               stream));
-        BP_HIP(hipMemcpyAsync(hitem.data(), w.item_off, sizeof(int64_t) * (T + 1), hipMemcpyDeviceToHost, stream));
-        BP_HIP(hipMemcpyAsync(hsplit.data(), w.split_off, sizeof(int64_t) * (T + 1), hipMemcpyDeviceToHost, stream));
     }
 
     // ---- CSR offsets to the host (in chunk mode: of the emitted batches; positions in the device lists, so the
     // first offset is where the carried residents' own entries end)
-    std::vector<uint32_t> hpair((size_t)T + 1);
-    std::vector<int64_t> hpre((size_t)T + 1), hev((size_t)T + 1);
-    BP_HIP(hipMemcpyAsync(hpre.data(), w.prefetch_off, sizeof(int64_t) * (T + 1), hipMemcpyDeviceToHost, stream));
-    BP_HIP(hipMemcpyAsync(hev.data(), w.evict_off, sizeof(int64_t) * (T + 1), hipMemcpyDeviceToHost, stream));
-    BP_HIP(hipMemcpyAsync(hpair.data(), w.pair_off, sizeof(uint32_t) * (T + 1), hipMemcpyDeviceToHost, stream));
+    std::vector<int64_t> hoffsets(5 * (size_t)(T + 1));     // one copy: the five arrays lie side by side
+    BP_HIP(hipMemcpyAsync(hoffsets.data(), w.offsets, sizeof(int64_t) * hoffsets.size(), hipMemcpyDeviceToHost, stream));
     BP_HIP(hipStreamSynchronize(stream));
+    int64_t* const hpre = hoffsets.data();
+    int64_t* const hev = hpre + (T + 1);
+    int64_t* const hitem = hpre + 2 * (size_t)(T + 1);
+    int64_t* const hsplit = hpre + 3 * (size_t)(T + 1);
+    const uint32_t* const hpair = reinterpret_cast<const uint32_t*>(hpre + 4 * (size_t)(T + 1));
     const int64_t n_miss = (int64_t)(uint32_t)htot, n_evict = (int64_t)(htot >> 32);
     hpre[T] = n_miss;
     hev[T] = n_evict;
