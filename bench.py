@@ -68,7 +68,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=0, help="timed steps (default: all batches after the warm-up)")
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=2)
-    ap.add_argument("--cpu-baseline-iters", type=int, default=40)
+    ap.add_argument("--cpu-baseline-iters", type=int, default=100)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--value-only", action="store_true",
                     help="run only the placement and schedule `value` is quoted on (for kernel profiles: the other "
