@@ -440,6 +440,27 @@ def test_plan_medium_multi_tile(bp):
     plan_both(bp, tr.ids, tr.iter_offsets, cfg.total_rows, 60, 10 ** 6)         # lookahead beyond the trace
 
 
+@pytest.mark.parametrize("largest", [1, 2, 255, 256, 257, 4096, 4097])
+def test_plan_word_field_boundaries(bp, largest):
+    """The place field of a lookup's word has as many bits as the largest batch needs: sizes at and around powers of
+    two (and the sort tile), the largest batch first, last or in the middle, empty batches between, ids up to the
+    top of the table."""
+    say(f"plan with a largest batch of {largest} lookups")
+    rng = np.random.default_rng(largest)
+    R = (1 << 22) - 5
+    for where in (0, 3, 6):
+        lens = rng.integers(0, max(1, largest // 2) + 1, size=7)
+        lens[where] = largest
+        lens[(where + 2) % 7] = 0
+        off = np.zeros(8, dtype=np.int64)
+        off[1:] = np.cumsum(lens)
+        pool = np.concatenate([rng.integers(0, R, size=40), [R - 1, 0, (1 << 21), (1 << 21) - 1]]).astype(np.int64)
+        ids = pool[rng.integers(0, len(pool), size=int(off[-1]))]
+        umax = max(len(np.unique(ids[off[i]:off[i + 1]])) for i in range(7))
+        plan_both(bp, ids, off, R, 3, umax + 3)
+        plan_both(bp, ids, off, R, 1, umax)
+
+
 def test_plan_many_batches_wide_group_keys(bp):
     """4,100 short batches (13 batch bits) with a capacity of 2^20 (wide slot and batch fields in the lookups' words),
     then with 9 slots: every slot changes hands hundreds of times, so the chains of the free ring are far longer than
