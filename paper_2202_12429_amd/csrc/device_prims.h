@@ -156,16 +156,23 @@ inline int64_t scan_num_tiles(int64_t n) { return n > 0 ? ceil_div(n, kScanTile)
 // partials needed by device_scan: one per tile plus the grand total
 inline size_t scan_partials(int64_t n) { return (size_t)scan_num_tiles(n) + 1; }
 
-// Runs the three passes on `stream`.  partials[scan_num_tiles(n)] holds the grand total afterwards.
+// Runs the three passes on `stream`.  partials[scan_num_tiles(n)] holds the grand total afterwards.  The per-tile
+// reduction reads its values through `in_reduce`, the final pass through `in_apply`: the same values, but the first
+// may leave notes for the second (flags that are costly to derive twice).
+template <typename T, typename Op, typename InReduce, typename InApply, typename Out>
+int device_scan2(InReduce in_reduce, InApply in_apply, Out out, int64_t n, T* partials, Op op, T identity,
+                 hipStream_t stream) {
+    const int64_t tiles = scan_num_tiles(n);
+    BP_LAUNCH(K_SCAN_REDUCE, (scan_reduce_kernel<T, Op, InReduce>), dim3((unsigned)tiles), dim3(kScanBlock), 0, stream,
+              in_reduce, n, partials, op, identity);
+    BP_LAUNCH(K_SCAN_SPINE, (scan_spine_kernel<T, Op>), dim3(1), dim3(1024), 0, stream, partials, tiles, op, identity);
+    BP_LAUNCH(K_SCAN_APPLY, (scan_apply_kernel<T, Op, InApply, Out>), dim3((unsigned)tiles), dim3(kScanBlock), 0, stream,
+              in_apply, out, n, (const T*)partials, op, identity);
+    return BP_OK;
+}
 template <typename T, typename Op, typename In, typename Out>
 int device_scan(In in, Out out, int64_t n, T* partials, Op op, T identity, hipStream_t stream) {
-    const int64_t tiles = scan_num_tiles(n);
-    BP_LAUNCH(K_SCAN_REDUCE, (scan_reduce_kernel<T, Op, In>), dim3((unsigned)tiles), dim3(kScanBlock), 0, stream, in,
-              n, partials, op, identity);
-    BP_LAUNCH(K_SCAN_SPINE, (scan_spine_kernel<T, Op>), dim3(1), dim3(1024), 0, stream, partials, tiles, op, identity);
-    BP_LAUNCH(K_SCAN_APPLY, (scan_apply_kernel<T, Op, In, Out>), dim3((unsigned)tiles), dim3(kScanBlock), 0, stream, in,
-              out, n, (const T*)partials, op, identity);
-    return BP_OK;
+    return device_scan2<T, Op, In, In, Out>(in, in, out, n, partials, op, identity, stream);
 }
 
 // ---------------------------------------------------------------------------------------------

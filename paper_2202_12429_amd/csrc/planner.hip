@@ -566,26 +566,46 @@ struct GroupWordSource {
 // positions counted from the batch's first lookup.  A row is "split" when its lookups go past the next two such
 // multiples, i.e. they span three items or more (a row spanning two items is finished by its first item).
 // Low word: item start flag; high word: first lookup of a split row.
+// The flags need the neighbouring word, the batch's offsets and, for the first lookup of a row, the word two cuts
+// further on.  The scan's first pass derives them and leaves them as bit masks, 64 lookups a word (a round of a
+// wavefront is 64 consecutive lookups starting at a multiple of 64, lane = position % 64, and the lanes past the end
+// are the inactive ones); its last pass reads the masks.
 struct ItemFlagIn {
     const uint64_t* gkeys;
     BatchOfPos where;
     GroupWord gw;
     int64_t first;          // entries below `first` are a chunk's carried residents, not lookups
+    uint64_t* item_mask;
+    uint64_t* split_mask;
     __device__ __forceinline__ uint64_t operator()(int64_t p) const {
-        if (p < first) return 0;
-        const uint64_t k = gkeys[p];
-        const int64_t* iter_off = where.iter_off;
-        const uint32_t i = gw.batch(k);
-        const int64_t base = iter_off[i];
-        const int64_t rel = p - base;
-        const bool first_of_row = rel == 0 || gw.slot(gkeys[p - 1]) != gw.slot(k);      // rel == 0 guards p == 0
-        const bool item = first_of_row || rel % kBwdChunk == 0;
-        bool split = false;
-        if (first_of_row) {
-            const int64_t nb2 = base + (rel / kBwdChunk + 2) * kBwdChunk;              // second cut after p
-            split = nb2 < iter_off[i + 1] && gw.slot(gkeys[nb2]) == gw.slot(k);
+        bool item = false, split = false;
+        if (p >= first) {
+            const uint64_t k = gkeys[p];
+            const int64_t* iter_off = where.iter_off;
+            const uint32_t i = gw.batch(k);
+            const int64_t base = iter_off[i];
+            const int64_t rel = p - base;
+            const bool first_of_row = rel == 0 || gw.slot(gkeys[p - 1]) != gw.slot(k);      // rel == 0 guards p == 0
+            item = first_of_row || rel % kBwdChunk == 0;
+            if (first_of_row) {
+                const int64_t nb2 = base + (rel / kBwdChunk + 2) * kBwdChunk;              // second cut after p
+                split = nb2 < iter_off[i + 1] && gw.slot(gkeys[nb2]) == gw.slot(k);
+            }
+        }
+        const uint64_t mi = __ballot(item), ms = __ballot(split);
+        if ((p & 63) == 0) {
+            item_mask[p >> 6] = mi;
+            split_mask[p >> 6] = ms;
         }
         return (uint64_t)item | ((uint64_t)split << 32);
+    }
+};
+struct ItemFlagFromMask {
+    const uint64_t* item_mask;
+    const uint64_t* split_mask;
+    __device__ __forceinline__ uint64_t operator()(int64_t p) const {
+        const int bit = (int)(p & 63);
+        return ((item_mask[p >> 6] >> bit) & 1u) | (((split_mask[p >> 6] >> bit) & 1u) << 32);
     }
 };
 struct GroupOut {
@@ -711,7 +731,7 @@ PlanWorkspace carve_plan(void* base, size_t cap, int64_t N, int T, int Lcap, boo
     const size_t n = (size_t)(N > 0 ? N : 1);
     w.keys_a = c.take<uint64_t>(n);
     w.keys_b = c.take<uint64_t>(n);
-    w.uq = c.take<uint32_t>(n);
+    w.uq = c.take<uint32_t>(n < 64 ? 64 : n);      // later the flag masks of the grouping step (2 x 8 bytes per 64 lookups)
     w.tile_batch = c.take<int32_t>((n >> kPosTileShift) + 2);
     w.sort_temp = c.take<uint32_t>(sort_temp_words<kPlanSortIPT>(N));
     w.scan_partials32 = c.take<uint32_t>(scan_partials(N));
@@ -1013,8 +1033,11 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
             gup, gsrc, gbuf, no_vals, N, pb, pb + ib, w.sort_temp, stream, &g_in)));
         const uint64_t* gkeys = gbuf[g_in];
         const GroupWord gw{ib, pb};
-        BP_TRY((device_scan<uint64_t, AddOp, ItemFlagIn, GroupOut>(
-            ItemFlagIn{gkeys, where, gw, R0},
+        // the pairs of the sorted lookups are not needed any more: their buffer takes the flag masks
+        uint64_t* item_mask = reinterpret_cast<uint64_t*>(w.uq);
+        uint64_t* split_mask = item_mask + ((size_t)N + 63) / 64;
+        BP_TRY((device_scan2<uint64_t, AddOp, ItemFlagIn, ItemFlagFromMask, GroupOut>(
+            ItemFlagIn{gkeys, where, gw, R0, item_mask, split_mask}, ItemFlagFromMask{item_mask, split_mask},
             GroupOut{gkeys, where, gw, plan->grouped_slots, plan->grouped_lookups, plan->item_starts,
                      plan->split_starts, w.item_off, w.split_off, R0},
             N, w.scan_partials64, AddOp(), uint64_t(0), stream)));
