@@ -577,8 +577,9 @@ struct ItemFlagIn {
     int64_t first;          // entries below `first` are a chunk's carried residents, not lookups
     uint64_t* item_mask;
     uint64_t* split_mask;
+    uint64_t* head_mask;    // first lookup of its row
     __device__ __forceinline__ uint64_t operator()(int64_t p) const {
-        bool item = false, split = false;
+        bool item = false, split = false, head = false;
         if (p >= first) {
             const uint64_t k = gkeys[p];
             const int64_t* iter_off = where.iter_off;
@@ -587,15 +588,17 @@ struct ItemFlagIn {
             const int64_t rel = p - base;
             const bool first_of_row = rel == 0 || gw.slot(gkeys[p - 1]) != gw.slot(k);      // rel == 0 guards p == 0
             item = first_of_row || rel % kBwdChunk == 0;
+            head = first_of_row;
             if (first_of_row) {
                 const int64_t nb2 = base + (rel / kBwdChunk + 2) * kBwdChunk;              // second cut after p
                 split = nb2 < iter_off[i + 1] && gw.slot(gkeys[nb2]) == gw.slot(k);
             }
         }
-        const uint64_t mi = __ballot(item), ms = __ballot(split);
+        const uint64_t mi = __ballot(item), ms = __ballot(split), mh = __ballot(head);
         if ((p & 63) == 0) {
             item_mask[p >> 6] = mi;
             split_mask[p >> 6] = ms;
+            head_mask[p >> 6] = mh;
         }
         return (uint64_t)item | ((uint64_t)split << 32);
     }
@@ -619,21 +622,22 @@ struct GroupOut {
     int64_t* item_off;     // device copies of the CSR offsets, [T+1] each, pre-filled with -1
     int64_t* split_off;
     int64_t first;         // entries below `first` are a chunk's carried residents: skipped, outputs start at `first`
+    const uint64_t* head_mask;
     __device__ __forceinline__ void operator()(int64_t p, uint64_t exc, uint64_t inc) const {
         if (p < first) return;
         const uint64_t k = gkeys[p];
-        const uint32_t i = gw.batch(k);
-        const int64_t base = where.iter_off[i];
         grouped_slots[p - first] = (int32_t)gw.slot(k);
         grouped_lookups[p - first] = (int32_t)gw.place(k);
-        if ((uint32_t)inc != (uint32_t)exc) {
-            const bool first_of_row = p == base || gw.slot(gkeys[p - 1]) != gw.slot(k);
+        if ((uint32_t)inc != (uint32_t)exc) {            // an item starts here (a batch's first lookup always does)
+            const uint32_t i = gw.batch(k);
+            const int64_t base = where.iter_off[i];
+            const bool first_of_row = (head_mask[p >> 6] >> (p & 63)) & 1u;
             item_starts[(uint32_t)exc] = (uint32_t)(p - base) | (first_of_row ? 0x80000000u : 0u);
-        }
-        if ((inc >> 32) != (exc >> 32)) split_starts[exc >> 32] = (uint32_t)(p - base);
-        if (p == base) {
-            item_off[i] = (uint32_t)exc;
-            split_off[i] = (int64_t)(exc >> 32);
+            if ((inc >> 32) != (exc >> 32)) split_starts[exc >> 32] = (uint32_t)(p - base);   // a split row's first lookup starts an item
+            if (p == base) {
+                item_off[i] = (uint32_t)exc;
+                split_off[i] = (int64_t)(exc >> 32);
+            }
         }
     }
 };
@@ -731,7 +735,7 @@ PlanWorkspace carve_plan(void* base, size_t cap, int64_t N, int T, int Lcap, boo
     const size_t n = (size_t)(N > 0 ? N : 1);
     w.keys_a = c.take<uint64_t>(n);
     w.keys_b = c.take<uint64_t>(n);
-    w.uq = c.take<uint32_t>(n < 64 ? 64 : n);      // later the flag masks of the grouping step (2 x 8 bytes per 64 lookups)
+    w.uq = c.take<uint32_t>(n < 64 ? 64 : n);      // later the flag masks of the grouping step (3 x 8 bytes per 64 lookups)
     w.tile_batch = c.take<int32_t>((n >> kPosTileShift) + 2);
     w.sort_temp = c.take<uint32_t>(sort_temp_words<kPlanSortIPT>(N));
     w.scan_partials32 = c.take<uint32_t>(scan_partials(N));
@@ -1036,10 +1040,11 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
         // the pairs of the sorted lookups are not needed any more: their buffer takes the flag masks
         uint64_t* item_mask = reinterpret_cast<uint64_t*>(w.uq);
         uint64_t* split_mask = item_mask + ((size_t)N + 63) / 64;
+        uint64_t* head_mask = split_mask + ((size_t)N + 63) / 64;
         BP_TRY((device_scan2<uint64_t, AddOp, ItemFlagIn, ItemFlagFromMask, GroupOut>(
-            ItemFlagIn{gkeys, where, gw, R0, item_mask, split_mask}, ItemFlagFromMask{item_mask, split_mask},
+            ItemFlagIn{gkeys, where, gw, R0, item_mask, split_mask, head_mask}, ItemFlagFromMask{item_mask, split_mask},
             GroupOut{gkeys, where, gw, plan->grouped_slots, plan->grouped_lookups, plan->item_starts,
-                     plan->split_starts, w.item_off, w.split_off, R0},
+                     plan->split_starts, w.item_off, w.split_off, R0, head_mask},
             N, w.scan_partials64, AddOp(), uint64_t(0), stream)));
         const uint32_t per_xcd = blocks_per_xcd(N);
         BP_LAUNCH(K_PLAN_SLOTS, plan_lookup_slots_grouped_kernel, dim3(per_xcd * kXcds), dim3(kBlock), 0, stream, N, per_xcd,
