@@ -247,7 +247,15 @@ __global__ __launch_bounds__(kSortBlock) void sort_upsweep_kernel(Src src, uint3
 #pragma unroll
         for (int j = 0; j < IPT; ++j) {
             uint32_t i = base + j * kSortBlock + threadIdx.x;
-            if (i < n) atomicAdd(&hist[(uint32_t)(cur.key(i, raw[j]) >> shift) & mask], 1u);
+            if (i < n) {
+                // skewed keys put many lanes on one counter: the lanes that share the first active lane's digit count
+                // themselves with one addition, the others add one by one
+                const uint32_t d = (uint32_t)(cur.key(i, raw[j]) >> shift) & mask;
+                const uint32_t d0 = __builtin_amdgcn_readfirstlane(d);
+                const uint64_t same = __ballot(d == d0);
+                if (d != d0) atomicAdd(&hist[d], 1u);
+                else if ((same & lanemask_lt()) == 0) atomicAdd(&hist[d0], (uint32_t)__popcll(same));
+            }
         }
     }
     __syncthreads();
