@@ -7,8 +7,9 @@
 //   TTL                   =   last use inside [i, i + L_eff - 1]
 // so the planner sorts (id, batch) keys, dedupes them into unique pairs, reads gaps off neighbouring
 // pairs, and derives everything else with scans:
-//   1. keys (id << iter_bits | batch), stable LSD radix sort on the id bits with the lookup position as payload
-//      (the input is batch-major, so equal ids stay in batch order)
+//   1. one 64-bit word per lookup, (id | batch | place inside the batch), made by the first pass of a stable LSD
+//      radix sort on the id bits as it reads the caller's ids (the input is batch-major, so equal ids stay in batch
+//      and lookup order)
 //   2. head flags + scan  -> unique pairs (sorted by id, then batch), pair index of every lookup
 //   3. histogram H[gap][batch] and per-batch unique counts -> occupancy for every candidate lookahead
 //      -> L_eff = largest lookahead whose peak occupancy fits the capacity
@@ -19,8 +20,9 @@
 //      C are the initial slots, position C + e holds the slot freed by the e-th eviction, i.e. the slot
 //      of an earlier miss.  Every miss follows those links to the end of its chain (plan_ring_resolve_kernel).
 //   7. slots of pairs -> list slots and the per-lookup slot map
-//   8. (optional) one more stable pass on the batch bits, with (slot, batch) keys, lists every batch's lookups grouped
-//      by row, with the work-item cuts the grouped backward pass uses, so that the backward pass need not sort
+//   8. (optional) one more stable pass on the batch bits, with the slot in place of the id in every word, lists every
+//      batch's lookups grouped by row, with the work-item cuts the grouped backward pass uses, so that the backward
+//      pass need not sort
 #include <vector>
 
 #include "common.h"
