@@ -62,6 +62,18 @@ def algorithmic_bytes(kernel: str, n: int, bags: int, u: float, row_b: int, stat
     raise KeyError(kernel)
 
 
+def cpu_model() -> str:
+    """The host CPU's name as /proc/cpuinfo gives it (the oracle's figure means little without it)."""
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -188,7 +200,7 @@ def main() -> int:
         cpu = {"value": n_s / (t_train + t_plan), "unit": "lookups/s", "cores": 1, "kind": "oracle",
                "sample": f"first {S_it} of {T} batches ({n_s} lookups): oracle plan {t_plan:.1f} s + uncached "
                          f"forward/backward/update {t_train:.1f} s, single thread",
-               "plan_ids_per_s": n_s / t_plan, "train_lookups_per_s": n_s / t_train}
+               "plan_ids_per_s": n_s / t_plan, "train_lookups_per_s": n_s / t_train, "cpu_model": cpu_model()}
         del Wo, So, grads
         log(f"cpu oracle: {cpu['value']:.3g} lookups/s on {S_it} batches")
 
