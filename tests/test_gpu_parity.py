@@ -461,6 +461,19 @@ def test_plan_word_field_boundaries(bp, largest):
         plan_both(bp, ids, off, R, 1, umax)
 
 
+def test_plan_degenerate_traces(bp):
+    """One id takes every lookup (one pair per batch, one row spanning every work item of a batch); every lookup has
+    an id of its own (no reuse at all: nothing is ever kept); one lookup in the whole trace."""
+    say("plan degenerate traces")
+    off = np.array([0, 700, 700, 1500, 1501], dtype=np.int64)
+    plan_both(bp, np.full(1501, 11, dtype=np.int64), off, 50, 3, 1)
+    plan_both(bp, np.full(1501, 11, dtype=np.int64), off, 50, 1, 4)
+    distinct = np.random.default_rng(5).permutation(5000)[:1501].astype(np.int64)
+    plan_both(bp, distinct, off, 5000, 3, 800)
+    plan_both(bp, distinct, off, 5000, 2, 2000)
+    plan_both(bp, np.array([4], dtype=np.int64), np.array([0, 0, 1, 1], dtype=np.int64), 9, 2, 1)
+
+
 def test_plan_many_batches_wide_group_keys(bp):
     """4,100 short batches (13 batch bits) with a capacity of 2^20 (wide slot and batch fields in the lookups' words),
     then with 9 slots: every slot changes hands hundreds of times, so the chains of the free ring are far longer than
