@@ -370,6 +370,9 @@ __global__ __launch_bounds__(kRowBlock) void bwd_combine_split_kernel(const uint
     const uint32_t slot = keys[start];
     if ((int64_t)slot >= C) return;
     const uint32_t b0 = start / kChunk + 1;           // the row's first item ends at the next cut after `start`
+    // the row itself is asked for now, so that it arrives while the partial sums are added up
+    const bool writer = active && j == 0;
+    const RowPiece<BF16> row = load_row<BF16>(u, cache_w, cache_s, (int64_t)slot, c, writer);
     SumPiece<N> acc;
     acc.zero();
     if (active && j == 0) acc.load(partial + 2 * (size_t)b0 * u.dim, c);
@@ -400,7 +403,7 @@ __global__ __launch_bounds__(kRowBlock) void bwd_combine_split_kernel(const uint
 #pragma unroll
         for (int i = 0; i < N; ++i) acc.v[i] += red[g][i][c];
     }
-    apply_update<GW, BF16>(u, cache_w, cache_s, (int64_t)slot, c, acc.template rounded<BF16>(), j == 0);
+    finish_update<GW, BF16>(u, cache_w, cache_s, (int64_t)slot, c, row, acc.template rounded<BF16>(), writer);
 }
 
 // ---- workspace -------------------------------------------------------------------------------
