@@ -8,6 +8,8 @@
 //        freed by batch i's evictions)                                         -> batch i+1 may start
 //   B_i  write the staged rows back and fetch the EARLY prefetches of batch i+2 (slots free since before batch
 //        i+1), while batch i+1 trains.
+// When batch i+1 has no late prefetches, A_i is empty and B_i is a single launch without staging
+// (bp_cache_apply_handoff): an evicted row leaves and the row that takes its slot arrives through one lane group.
 // A batch without late prefetches (the usual case when the plan keeps a reserve of free slots) is ready as soon as
 // B of two batches earlier is done, so the compute stream never waits for the batch before it.
 // Which prefetches are early follows from the ring order alone: the x-th miss of the trace takes ring position x,
@@ -43,6 +45,12 @@ namespace {
 // Workgroups per maintenance launch: 2 per CU keeps ~2,000 wavefronts of 16-byte accesses in flight, enough for the
 // host link and for a backing table in HBM, and leaves the rest of every CU to the training kernels.
 constexpr int64_t kMaintenanceBlocks = 512;
+// The one-launch step (no staging) runs narrower still.  While rows are in flight over the host link a training kernel
+// beside them crawls, whatever CUs it runs on (the forward pass takes 0.2-0.3 ms instead of 0.03): the requests to
+// host memory hold up everybody's requests somewhere on the way out of the GPU, and how much depends on how many
+// of them are outstanding.  128 workgroups are the measured optimum on a Criteo-shaped step behind PCIe (a step of
+// 0.345 ms; 0.378 with 256 or 512 workgroups, 0.396 with 64, 0.420 with 32).
+constexpr int64_t kHandoffBlocks = 128;
 
 int prefetch_range(bp_pipeline* p, int64_t a, int64_t b) {      // cache <- backing for list entries [a, b)
     if (b <= a) return BP_OK;
@@ -76,6 +84,22 @@ int enqueue_after_batch(bp_pipeline* p, int i) {
         BP_TRY(bp_cache_apply(&p->cfg, p->cache_w, p->cache_s, p->back_w, p->back_s, p->e_ids + ea, p->e_slots + ea, ne,
                               p->p_ids + p1a, p->p_slots + p1a, p1b - p1a, p->maint));
         if (j1 < T) BP_HIP(hipEventRecord(p->ready[j1 & 1], p->maint));
+        return BP_OK;
+    }
+    if (p->L_eff >= 3 && i >= 0 && late_count(p, j1) == 0) {
+        // Nothing of batch i+1 waits for the slots freed now, so no staging: one launch writes the rows evicted after
+        // batch i back and fetches the early prefetches of batch i+2.  By the ring order those of them whose slot was
+        // not free before (miss ordinal x with x - C at or past batch i's first eviction) are the tail of the early
+        // prefix, and they take the slots of batch i's evictions from the first one on, in order: the pairing that
+        // bp_cache_apply_handoff moves through registers.  (With late prefetches of batch i+1 the first evictions
+        // pair with those instead, and the staged path below is taken.)
+        int64_t n_free = p->cfg.capacity + ea - p2a;          // early entries whose slot has been free since before
+        if (n_free > p2b - p2a) n_free = p2b - p2a;
+        if (n_free < 0) return fail(BP_ERR_INVALID_ARG, "internal: batch %d has no late prefetches but its successor's ring positions say otherwise", j1);
+        GridCap narrow(p->grid_cap < kHandoffBlocks ? p->grid_cap : kHandoffBlocks);
+        BP_TRY(bp_cache_apply_handoff(&p->cfg, p->cache_w, p->cache_s, p->back_w, p->back_s, p->e_ids + ea, p->e_slots + ea,
+                                      ne, p->p_ids + p2a, p->p_slots + p2a, p2b - p2a, n_free, nullptr, p->maint));
+        if (j2 < T && late_count(p, j2) == 0) BP_HIP(hipEventRecord(p->ready[j2 & 1], p->maint));
         return BP_OK;
     }
     BP_TRY(bp_cache_stage(&p->cfg, p->cache_w, p->cache_s, p->e_slots + ea, ne, p->staging, p->staging_bytes, p->maint));

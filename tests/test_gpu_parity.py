@@ -574,16 +574,30 @@ def test_end_to_end_variants(bp, optimizer, dtype, bag_max, capacity, pinned, gr
     ("adagrad_rowwise", "bf16", 1, 2400, 700, 20, True),
     ("sgd", "f32", 6, 3000, 600, 20, False),
     ("adagrad", "bf16", 4, 2600, 0, 2, True),             # L_eff == 2: write-back and early fetch take turns
-    ("sgd", "f32", 1, 1400, 0, 1, True)])                 # L_eff == 1: the synchronous order on the other stream
+    ("sgd", "f32", 1, 1400, 0, 1, True),                  # L_eff == 1: the synchronous order on the other stream
+    # nearly uniform ids, a reserve of ~1.4 batches of misses: no late prefetches, and most early prefetches take the
+    # slots of the evictions of two batches before (the one-launch step without staging, with its pairs)
+    ("adagrad", "f32", 1, 8000, 2000, 40, True), ("adagrad_rowwise", "bf16", 1, 8000, 2000, 40, False),
+    ("sgd", "f32", 1, 9000, 2300, 40, True)])
 def test_end_to_end_overlapped(bp, optimizer, dtype, bag_max, capacity, reserve, lookahead, pinned):
     """Same trace, same oracle, maintenance on the library's own stream: outputs and final table as before."""
     say(f"overlapped: {optimizer} {dtype} bag_max={bag_max} C={capacity} reserve={reserve} L={lookahead}")
+    uniform = capacity >= 8000
     cfg = workloads.get_config(0, optimizer=optimizer, weight_dtype=dtype, bag_max=bag_max, capacity=capacity,
-                               batch=128 if bag_max > 1 else 256, iterations=30, lookahead=lookahead)
+                               batch=128 if bag_max > 1 else 256, iterations=30, lookahead=lookahead,
+                               zipf_s=(0.05 if capacity == 8000 else 0.3) if uniform else 1.2)
     plan = run_end_to_end(cfg, workloads.make_trace(cfg), pinned=pinned, overlapped=True, reserve=reserve)
     early = bp.bp_pipeline_early_counts(plan.prefetch_offsets, plan.evict_offsets, capacity, plan.L_eff)
     misses = np.diff(plan.prefetch_offsets)
     say(f"  L_eff={plan.L_eff} early {int(early[1:].sum())} of {int(misses[1:].sum())} prefetches after batch 0")
+    if uniform:     # the case is meant to hand slots over two batches on: make sure it does
+        paired = 0
+        for i in range(len(misses) - 2):
+            if misses[i + 1] == early[i + 1]:
+                free = min(max(capacity + int(plan.evict_offsets[i]) - int(plan.prefetch_offsets[i + 2]), 0), int(early[i + 2]))
+                paired += int(early[i + 2]) - free
+        say(f"  {paired} prefetches take the slot of a row written back in the same launch")
+        assert plan.L_eff >= 3 and paired > 500
     if plan.L_eff == 1:
         assert early.sum() == 0
     if reserve >= misses.max():

@@ -130,3 +130,57 @@ def test_late_prefetches_take_the_evicted_slots_in_order(seed):
             assert 0 <= n_late <= len(e)
             assert np.array_equal(p[int(early[i]):], e[:n_late]), (seed, L, C, i)
             assert not set(p[:int(early[i])].tolist()) & set(e.tolist())
+
+
+def stationary_trace(seed):
+    """Batches of 100 uniform draws from a few thousand rows: the occupancy stays near its peak all along, so with a
+    reserve of about one batch's misses the ring is tight and slots change hands every other batch."""
+    rng = np.random.default_rng(400 + seed)
+    T, B, R = 40, 100, int(rng.integers(600, 3000))
+    off = np.arange(T + 1, dtype=np.int64) * B
+    return rng.integers(0, R, size=T * B).astype(np.int64), off, R, T
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_early_prefetches_two_batches_on_take_the_evicted_slots_in_order(seed):
+    """What the overlapped schedule's one-launch step relies on: when batch i+1 has no late prefetches, the early
+    prefetches of batch i+2 are, in list order, first those whose slot has been free since before batch i ended
+    (capacity + evictions before batch i - misses before batch i+2 of them, never negative), then entries that take
+    the slots of batch i's evictions from the first one on, one by one; and none of the rows fetched is one of the
+    rows written back."""
+    import paper_2202_12429_amd as bp
+    paired_total = 0
+    for make in (stationary_trace, lambda s: random_trace(300 + s)):
+        ids, off, R, T = make(seed)
+        if len(ids) == 0:
+            continue
+        umax = max(len(np.unique(ids[off[i]:off[i + 1]])) for i in range(T))
+        for C, f in ((4 * umax, 1.2), (5 * umax, 1.6), (3 * umax, 1.0), (3 * umax, 0.0)):
+            base = oracle.plan(ids, off, R, T, C)
+            reserve = int(f * np.median(np.diff(base.prefetch_off)[2:])) if T > 3 else 0
+            try:
+                plan = oracle.plan(ids, off, R, T, C, reserve=reserve)
+            except oracle.OracleError:
+                continue
+            if plan.L_eff < 3:
+                continue
+            early = bp.bp_pipeline_early_counts(plan.prefetch_off, plan.evict_off, C, plan.L_eff)
+            misses = np.diff(plan.prefetch_off)
+            for i in range(0, T - 2):
+                if misses[i + 1] - early[i + 1] != 0:
+                    continue                                     # batch i+1 has late prefetches: the staged path
+                a = int(plan.prefetch_off[i + 2])
+                p_slots = plan.prefetch_slots[a:a + int(early[i + 2])]
+                p_ids = plan.prefetch_ids[a:a + int(early[i + 2])]
+                e_slots = plan.evict_slots[plan.evict_off[i]:plan.evict_off[i + 1]]
+                e_ids = plan.evict_ids[plan.evict_off[i]:plan.evict_off[i + 1]]
+                n_free = C + int(plan.evict_off[i]) - a
+                assert n_free >= 0, (seed, C, i)
+                n_free = min(n_free, len(p_slots))
+                paired = len(p_slots) - n_free
+                assert paired <= len(e_slots)
+                assert np.array_equal(p_slots[n_free:], e_slots[:paired]), (seed, C, i)
+                assert not set(p_slots[:n_free].tolist()) & set(e_slots.tolist())
+                assert not set(p_ids.tolist()) & set(e_ids.tolist())
+                paired_total += paired
+    assert paired_total > 100          # the stationary traces do hand slots over two batches on
