@@ -51,6 +51,10 @@ constexpr int64_t kMaintenanceBlocks = 512;
 // of them are outstanding.  128 workgroups are the measured optimum on a Criteo-shaped step behind PCIe (a step of
 // 0.345 ms; 0.378 with 256 or 512 workgroups, 0.396 with 64, 0.420 with 32).
 constexpr int64_t kHandoffBlocks = 128;
+// ... and only for steps of moderate size.  With ten times the rows per step (0.7 M rows of 256 bytes, a multi-hot
+// workload) the staged path, whose second launch keeps both directions of the link busy at once, ends 10 % ahead of
+// the one-launch step at any width (128, 256, 512 workgroups); with 47 K rows of 384 bytes per step it is 8 % behind.
+constexpr int64_t kHandoffMaxRows = int64_t(1) << 17;
 
 int prefetch_range(bp_pipeline* p, int64_t a, int64_t b) {      // cache <- backing for list entries [a, b)
     if (b <= a) return BP_OK;
@@ -86,7 +90,7 @@ int enqueue_after_batch(bp_pipeline* p, int i) {
         if (j1 < T) BP_HIP(hipEventRecord(p->ready[j1 & 1], p->maint));
         return BP_OK;
     }
-    if (p->L_eff >= 3 && i >= 0 && late_count(p, j1) == 0) {
+    if (p->L_eff >= 3 && i >= 0 && late_count(p, j1) == 0 && ne + (p2b - p2a) <= kHandoffMaxRows) {
         // Nothing of batch i+1 waits for the slots freed now, so no staging: one launch writes the rows evicted after
         // batch i back and fetches the early prefetches of batch i+2.  By the ring order those of them whose slot was
         // not free before (miss ordinal x with x - C at or past batch i's first eviction) are the tail of the early
