@@ -431,7 +431,9 @@ def main() -> int:
                    "L_eff": plan_main.L_eff, "peak_occupancy": plan_main.peak_occupancy,
                    "capacity_note": capacity_note, "unique_rows_per_step": u_mean},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "algorithmic_bytes_per_launch": alg,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "traffic_frac": (traffic / dur_s / 1e9 / HBM_PEAK_GBS) if traffic else None,
+                     "algorithmic_bytes_per_launch": alg,
                      "avg_launch_us": dur_s * 1e6, "launches": launches, "empty_kernel_bracket_us": bracket_us,
                      "frac_of_measured_copy": achieved / copy_gbs, "measured_copy_GBps": copy_gbs,
                      "frac_of_random_row_gather": achieved / gather["GBps"], "random_row_gather": gather},
