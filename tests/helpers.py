@@ -7,8 +7,8 @@ import workloads
 
 
 def say(msg):
-    """Progress line of a long test: printed, and appended to gpurun_out/gpu_test_progress.log so that a run whose
-    stdout is captured still shows signs of life."""
+    """Progress line of a long test: printed, and appended to a log file in the run's output folder, so that a run
+    whose stdout is captured still shows signs of life."""
     import os
     import sys
     print(msg, flush=True)
