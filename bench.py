@@ -335,6 +335,8 @@ def main() -> int:
             dt_ = time.perf_counter() - t0
             bp.bp_profile_collect()
             prof = bp.profile_totals()
+            if profile_kernels:                  # the spread of the one kernel this pass records
+                prof["spread_ms"] = bp.profile_spread(profile_kernels[0])
             bp.bp_profile_enable(False)
             bp.bp_profile_select(None)
             for i in range(W + K, T):        # finish the trace: the cache drains, the next pass starts empty
@@ -368,7 +370,7 @@ def main() -> int:
         }
         t_total = t_loop + t_plan * K / T                      # the plan's share of these K batches
         return dict(t_loop=t_loop, t_loop_events=t_loop_events, t_total=t_total, dominant=dominant,
-                    prof_dom=prof_dom[dominant], kernel_ms=kernel_ms)
+                    prof_dom=prof_dom[dominant], spread_ms=prof_dom["spread_ms"], kernel_ms=kernel_ms)
 
     res = {key: measure(tr_, key[1] == "overlapped") for key, tr_ in trainers.items()
            if not args.value_only or key == (main_place, main_sched)}
@@ -434,7 +436,9 @@ def main() -> int:
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "traffic_frac": (traffic / dur_s / 1e9 / HBM_PEAK_GBS) if traffic else None,
                      "algorithmic_bytes_per_launch": alg,
-                     "avg_launch_us": dur_s * 1e6, "launches": launches, "empty_kernel_bracket_us": bracket_us,
+                     "avg_launch_us": dur_s * 1e6, "launches": launches,
+                     "launch_us_min_median_max": [x * 1e3 for x in m["spread_ms"]],
+                     "empty_kernel_bracket_us": bracket_us,
                      "frac_of_measured_copy": achieved / copy_gbs, "measured_copy_GBps": copy_gbs,
                      "frac_of_random_row_gather": achieved / gather["GBps"], "random_row_gather": gather},
         "cpu_baseline": cpu,

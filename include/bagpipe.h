@@ -390,6 +390,9 @@ int bp_profile_select(uint64_t kernel_mask);
  * `stream`, synchronises it): the share of every profiled duration that is the bracket, not the kernel. */
 int bp_profile_bracket_overhead(void* stream, int32_t reps, double* median_us);
 int bp_profile_collect(void);
+/* Shortest, median and longest launch of kernel `id` among those collected since bp_profile_enable(1), in ms
+ * (BP_ERR_INVALID_ARG when none was recorded). */
+int bp_profile_spread(int id, double* min_ms, double* median_ms, double* max_ms);
 int bp_profile_num_kernels(void);
 const char* bp_profile_kernel_name(int id);
 int bp_profile_get(int id, int64_t* launches, double* total_ms);

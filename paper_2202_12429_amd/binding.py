@@ -561,6 +561,20 @@ def bp_profile_get(kernel_id: int):
     return int(n.value), float(ms.value)
 
 
+def profile_spread(name: str):
+    """(min, median, max) launch duration in ms of the kernel called `name`, over the launches collected."""
+    lib = load_library()
+    lib.bp_profile_spread.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
+                                      ctypes.POINTER(ctypes.c_double)]
+    lib.bp_profile_spread.restype = ctypes.c_int
+    for k in range(lib.bp_profile_num_kernels()):
+        if lib.bp_profile_kernel_name(k).decode() == name:
+            lo, med, hi = ctypes.c_double(0), ctypes.c_double(0), ctypes.c_double(0)
+            _check(lib.bp_profile_spread(k, ctypes.byref(lo), ctypes.byref(med), ctypes.byref(hi)))
+            return float(lo.value), float(med.value), float(hi.value)
+    raise KeyError(name)
+
+
 def profile_totals() -> dict:
     """{kernel name: (launches, total_ms)} for every kernel with at least one recorded launch."""
     lib = load_library()

@@ -57,6 +57,7 @@ std::vector<Span> g_spans;          // recorded, not yet collected
 std::vector<hipEvent_t> g_free;     // recycled events
 int64_t g_count[K_NUM_KERNELS];
 double g_ms[K_NUM_KERNELS];
+std::vector<float> g_samples[K_NUM_KERNELS];     // every recorded launch's duration, for the spread
 
 hipEvent_t get_event() {
     if (!g_free.empty()) {
@@ -229,6 +230,7 @@ BP_EXPORT int bp_profile_enable(int on) {
         g_spans.clear();
         std::memset(g_count, 0, sizeof(g_count));
         std::memset(g_ms, 0, sizeof(g_ms));
+        for (auto& v : g_samples) v.clear();
     }
     g_profile_on = on != 0;
     return BP_OK;
@@ -246,10 +248,22 @@ BP_EXPORT int bp_profile_collect(void) {
         BP_HIP(hipEventElapsedTime(&ms, s.a, s.b));
         g_count[s.id] += 1;
         g_ms[s.id] += ms;
+        g_samples[s.id].push_back(ms);
         g_free.push_back(s.a);
         g_free.push_back(s.b);
     }
     g_spans.clear();
+    return BP_OK;
+}
+
+BP_EXPORT int bp_profile_spread(int id, double* min_ms, double* median_ms, double* max_ms) {
+    if (id < 0 || id >= K_NUM_KERNELS) return fail(BP_ERR_INVALID_ARG, "kernel id %d out of range", id);
+    std::vector<float> v = g_samples[id];
+    if (v.empty()) return fail(BP_ERR_INVALID_ARG, "no recorded launch of kernel %d", id);
+    std::sort(v.begin(), v.end());
+    if (min_ms) *min_ms = v.front();
+    if (max_ms) *max_ms = v.back();
+    if (median_ms) *median_ms = v.size() % 2 ? v[v.size() / 2] : 0.5 * (v[v.size() / 2 - 1] + v[v.size() / 2]);
     return BP_OK;
 }
 
