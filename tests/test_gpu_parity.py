@@ -908,3 +908,33 @@ def test_gather_calibration(bp, row_ints, n):
     for k in range(-(-n // 4)):
         sel = table[rows[4 * k:4 * k + 4]].reshape(-1, 4)
         assert np.array_equal(got[k], np.bitwise_xor.reduce(sel, axis=0)), k
+
+
+def test_profiler_totals_and_spread(bp):
+    """The event profiler: launches are counted per kernel, totals add up, the spread brackets the mean, a selection
+    restricts what is recorded, and nothing is recorded once it is switched off."""
+    say("profiler")
+    a = torch.rand(1 << 20, device="cuda")
+    b = torch.empty_like(a)
+    bp.bp_profile_select(None)
+    bp.bp_profile_enable(True)
+    for _ in range(7):
+        bp.bp_copy_calibration(b, a)
+    bp.bp_profile_collect()
+    tot = bp.profile_totals()
+    assert tot["copy_calibration"][0] == 7 and tot["copy_calibration"][1] > 0
+    lo, med, hi = bp.profile_spread("copy_calibration")
+    assert 0 < lo <= med <= hi and lo <= tot["copy_calibration"][1] / 7 <= hi
+    bp.bp_profile_enable(True)                       # clears
+    bp.bp_profile_select(["embbag_fwd"])
+    bp.bp_copy_calibration(b, a)
+    bp.bp_profile_collect()
+    assert "copy_calibration" not in bp.profile_totals()
+    with pytest.raises(bp.BagpipeError):
+        bp.profile_spread("copy_calibration")
+    bp.bp_profile_select(None)
+    bp.bp_profile_enable(False)
+    bp.bp_copy_calibration(b, a)
+    bp.bp_profile_collect()
+    assert "copy_calibration" not in bp.profile_totals()
+    assert torch.equal(a, b)
