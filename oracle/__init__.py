@@ -35,7 +35,7 @@ def build(force: bool = False) -> str:
     """Compile the oracle with gcc (no fused multiply-add contraction, so every operation rounds once)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off", "-fno-fast-math",
-               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+               "-Wall", "-Wextra", "-pthread", "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -64,8 +64,8 @@ def _load():
         _lib.orc_plan.argtypes = [p, p, p, p, i64, i64, i64, i64] + [p] * 11
         _lib.orc_train_iter.restype = i32
         _lib.orc_train_iter.argtypes = [p, p, i64, i64, i32, i32, ctypes.c_float, ctypes.c_float, p, i64, p, i64, p, p]
-        _lib.orc_group_lookups.restype = i64
-        _lib.orc_group_lookups.argtypes = [p, p, i64, p, i64, p, p, p, p, p, p]
+        _lib.orc_train_iter_mt.restype = i32
+        _lib.orc_train_iter_mt.argtypes = _lib.orc_train_iter.argtypes + [i32]
         _lib.orc_cache_apply.restype = i32
         _lib.orc_cache_apply.argtypes = [p, p, p, p, i64, i64, i64, i32, i32, p, p, i64, p, p, i64]
     return _lib
@@ -251,9 +251,20 @@ def state_shape(rows, D, optimizer):
     return (0,)
 
 
-def train_iter(table, state, D, dtype, optimizer, lr, eps, row_idx, bag_off, grad_out, want_out=True):
+def host_threads(limit=16) -> int:
+    """Host threads the multi-threaded leg may use: the cores this process may run on, at most `limit`."""
+    try:
+        n = len(os.sched_getaffinity(0))
+    except (AttributeError, OSError):
+        n = os.cpu_count() or 1
+    return max(1, min(limit, n))
+
+
+def train_iter(table, state, D, dtype, optimizer, lr, eps, row_idx, bag_off, grad_out, want_out=True, threads=1):
     """One iteration of forward / backward / update on `table` in place (parts B and C).  Returns out or None.
-    table: fp32 [rows, D] or uint16 (bf16 bits) [rows, D]; state: fp32 per state_shape()."""
+    table: fp32 [rows, D] or uint16 (bf16 bits) [rows, D]; state: fp32 per state_shape().
+    threads > 1 runs orc_train_iter_mt (same result bit for bit, see its comment); 1 is the serial routine
+    that the pins run."""
     lib = _load()
     rows = table.shape[0]
     assert table.flags.c_contiguous and table.dtype == (np.float32 if dtype == F32 else np.uint16)
@@ -264,8 +275,9 @@ def train_iter(table, state, D, dtype, optimizer, lr, eps, row_idx, bag_off, gra
     if grad_out is not None:
         grad_out = _c(grad_out, np.float32)
         assert grad_out.shape == (bags, D)
-    r = lib.orc_train_iter(_ptr(table), _ptr(state), rows, D, dtype, optimizer, lr, eps, _ptr(row_idx),
-                           row_idx.shape[0], _ptr(bag_off), bags, _ptr(grad_out), _ptr(out))
+    args = (_ptr(table), _ptr(state), rows, D, dtype, optimizer, lr, eps, _ptr(row_idx), row_idx.shape[0],
+            _ptr(bag_off), bags, _ptr(grad_out), _ptr(out))
+    r = lib.orc_train_iter(*args) if threads <= 1 else lib.orc_train_iter_mt(*args, int(threads))
     if r != OK:
         raise OracleError(r, "train_iter")
     return out
@@ -281,22 +293,3 @@ def cache_apply(cache_w, cache_state, host_w, host_state, D, dtype, optimizer, e
                             _ptr(ps), pi.shape[0])
     if r != OK:
         raise OracleError(r, "cache_apply")
-
-
-def group_lookups(ids, iter_off, lookup_slots, chunk=32):
-    """Every batch's lookups grouped by row + work-item cuts (see orc_group_lookups).
-    Returns (grouped_slots, grouped_lookups, item_starts, item_off, split_starts, split_off)."""
-    lib = _load()
-    ids, iter_off = _c(ids, np.int64), _c(iter_off, np.int64)
-    slots = _c(lookup_slots, np.int32)
-    T, N = iter_off.shape[0] - 1, ids.shape[0]
-    gs, gl = np.empty(max(N, 1), np.int32), np.empty(max(N, 1), np.int32)
-    st = np.empty(max(N, 1), np.uint32)
-    off = np.zeros(T + 1, np.int64)
-    sp = np.empty(max(N, 1), np.uint32)
-    soff = np.zeros(T + 1, np.int64)
-    r = lib.orc_group_lookups(_ptr(ids), _ptr(iter_off), T, _ptr(slots), int(chunk), _ptr(gs), _ptr(gl), _ptr(st), _ptr(off),
-                              _ptr(sp), _ptr(soff))
-    if r < 0:
-        raise OracleError(r, "group_lookups")
-    return gs[:N], gl[:N], st[:r].copy(), off, sp[:int(soff[-1])].copy(), soff

@@ -6,9 +6,12 @@
  * only tests, the smoke check and the benchmark's CPU-baseline leg load it.
  *
  * Three parts:
- *   A. the lookahead planner: Algorithm 1 ("Lookahead Algorithm") of the paper, taken step by step,
- *      with the dictionary `LatestTracker` and the set `InCache` held as arrays indexed by embedding id,
- *      plus the two things the paper leaves open and this build fixes:
+ *   A. the lookahead planner (Algorithm 1 and Section 3.2 of the paper).  What it decides, in this
+ *      file's own terms: batch i looks into the window of batches [i, i + L - 1]; an id of batch i is
+ *      kept until its last use inside that window (its TTL) and written back after the batch whose
+ *      number equals that TTL; an id that is not resident when its batch comes up is fetched.  The
+ *      per-id bookkeeping is two arrays indexed by id (last batch of the window that uses the id;
+ *      resident or not / slot).  Two things the paper leaves open are fixed here:
  *        - capacity policy (Section 4, "Automatically Calculating Lookahead": the lookahead is reduced
  *          when the cache would overflow): the effective lookahead is the largest L' <= L whose peak
  *          occupancy fits in the cache;
@@ -24,15 +27,17 @@
  * once on store; with bf16 storage the stored value is a quantised code and the update is carried out in
  * fp32, the arithmetic type fixed for that workload (see update_row_bf16).
  * Parity pins: tests/test_oracle_*.py (paper's worked example, brute force from the plain
- * definitions, invariants, torch CPU library routines).  Row-wise Adagrad is pinned by a closed form
- * on one row, by its equality with element-wise Adagrad at D = 1 and against torch's Adagrad on
- * gradients that are constant along a row: parity unpinned for gradients that vary along a row
- * beyond the one-row closed form.
+ * definitions, invariants, torch CPU library routines).  Row-wise Adagrad is pinned, for fp32 and for
+ * bf16 rows, by hand-computed one-row values, by its equality with element-wise Adagrad at D = 1,
+ * against torch's Adagrad on gradients that are constant along a row, and against the same rule written
+ * with torch tensor operations on gradients that vary along a row (several rows, several steps).
  * Further parts, each with its own pins: the lookahead when none is configured (orc_auto_lookahead),
- * a lookahead that changes from batch to batch (orc_plan_stream), the grouping of a batch's lookups for
- * the backward pass (orc_group_lookups), the trainers that use a row (orc_keep_owners).
+ * a lookahead that changes from batch to batch (orc_plan_stream), the trainers that use a row
+ * (orc_keep_owners), and a multi-threaded leg of the training iteration (orc_train_iter_mt: same
+ * arithmetic in the same order per bag and per row, pinned bit for bit against the serial routine).
  */
 #include <math.h>
+#include <pthread.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -54,7 +59,7 @@ static int cmp_i64(const void *a, const void *b) {
 }
 
 /*
- * Batch.UniqueEmbeddings() of Algorithm 1 for every iteration: sorted distinct ids of each batch.
+ * The distinct ids of every batch (what Algorithm 1 iterates over), sorted.
  * uniq must hold N entries; uniq_off[T+1] receives the CSR offsets.  Returns total count or <0.
  */
 int64_t orc_unique_per_iter(const int64_t *ids, const int64_t *iter_off, int64_t T, int64_t total_rows,
@@ -84,8 +89,8 @@ int64_t orc_unique_per_iter(const int64_t *ids, const int64_t *iter_off, int64_t
  * occ[i] = number of embeddings in the cache while batch i trains (after its prefetches, before its
  * evictions).  Returns the peak, or <0 on error.
  *
- * The queue of Algorithm 1 always holds consecutive batches, so it is kept as the index range
- * [i, pushed).  LatestTracker is `latest[id]`; InCache is `in_cache[id]`.
+ * The window always holds consecutive batches, so it is kept as the index range [i, pushed).
+ * latest[id] = last batch of the window seen so far that uses the id; in_cache[id] = resident or not.
  */
 int64_t orc_peak_occupancy(const int64_t *uniq, const int64_t *uniq_off, int64_t T, int64_t total_rows,
                            int64_t Lp, int64_t *occ) {
@@ -183,7 +188,7 @@ int64_t orc_auto_lookahead(const int64_t *uniq, const int64_t *uniq_off, int64_t
  *
  * Per iteration i (two phases, so that a slot freed by one id of batch i is never handed to another
  * id of the same batch):
- *   phase 1, ids of the batch in ascending order: TTL = LatestTracker[id]; append (id, TTL) to the
+ *   phase 1, ids of the batch in ascending order: TTL = latest[id]; append (id, TTL) to the
  *            keep list; if the id is not cached, pop a slot from the ring head and append (id, slot)
  *            to the prefetch list;
  *   every lookup of the batch gets the slot of its id;
@@ -436,6 +441,39 @@ static int cmp_rowpos(const void *a, const void *b) {
     return (x->pos > y->pos) - (x->pos < y->pos);
 }
 
+/* forward of the bags [b0, b1): out[bag, :] = sum of the bag's rows in lookup order, fp64, rounded once */
+static void forward_bags(const void *table, int dtype, int64_t D, const int64_t *row_idx, const int64_t *bag_off,
+                         int64_t b0, int64_t b1, float *out) {
+    for (int64_t b = b0; b < b1; ++b)
+        for (int64_t d = 0; d < D; ++d) {
+            double acc = 0.0;
+            for (int64_t k = bag_off[b]; k < bag_off[b + 1]; ++k) acc += load_w(table, dtype, row_idx[k], D, d);
+            out[b * D + d] = (float)acc;
+        }
+}
+
+/*
+ * backward + update for the lookups listed in rp[0 .. m), sorted by (row, position): for every distinct row the
+ * gradient rows of its lookups are added in ascending position (fp64), then the row is updated once.
+ * G is scratch for D doubles.
+ */
+static int update_sorted_rows(void *table, float *state, int64_t D, int dtype, int optimizer, float lr, float eps,
+                              const rowpos_t *rp, int64_t m, const int64_t *bag_of, const float *grad_out, double *G) {
+    for (int64_t a = 0; a < m;) {
+        int64_t b = a, row = rp[a].row;
+        for (int64_t d = 0; d < D; ++d) G[d] = 0.0;
+        for (; b < m && rp[b].row == row; ++b) {
+            const float *g = grad_out + bag_of[rp[b].pos] * D;
+            for (int64_t d = 0; d < D; ++d) G[d] += (double)g[d];
+        }
+        int rc = dtype == ORC_F32 ? update_row_f64((float *)table, state, row, D, optimizer, lr, eps, G)
+                                  : update_row_bf16((uint16_t *)table, state, row, D, optimizer, lr, eps, G);
+        if (rc != ORC_OK) return rc;
+        a = b;
+    }
+    return ORC_OK;
+}
+
 /*
  * One training iteration on `table` (the full table with rows = global ids, or the cache with
  * rows = slots):
@@ -453,14 +491,7 @@ int orc_train_iter(void *table, float *state, int64_t rows, int64_t D, int dtype
                    const float *grad_out, float *out) {
     if (bag_off[0] != 0 || bag_off[bags] != n) return ORC_ERR_ARG;
     for (int64_t k = 0; k < n; ++k) if (row_idx[k] < 0 || row_idx[k] >= rows) return ORC_ERR_ID_RANGE;
-    if (out) {
-        for (int64_t b = 0; b < bags; ++b)
-            for (int64_t d = 0; d < D; ++d) {
-                double acc = 0.0;
-                for (int64_t k = bag_off[b]; k < bag_off[b + 1]; ++k) acc += load_w(table, dtype, row_idx[k], D, d);
-                out[b * D + d] = (float)acc;
-            }
-    }
+    if (out) forward_bags(table, dtype, D, row_idx, bag_off, 0, bags, out);
     if (!grad_out || n == 0) return ORC_OK;
     rowpos_t *rp = (rowpos_t *)malloc((size_t)n * sizeof(rowpos_t));
     int64_t *bag_of = (int64_t *)malloc((size_t)n * sizeof(int64_t));
@@ -470,20 +501,85 @@ int orc_train_iter(void *table, float *state, int64_t rows, int64_t D, int dtype
         for (int64_t k = bag_off[b]; k < bag_off[b + 1]; ++k) bag_of[k] = b;
     for (int64_t k = 0; k < n; ++k) { rp[k].row = row_idx[k]; rp[k].pos = k; }
     qsort(rp, (size_t)n, sizeof(rowpos_t), cmp_rowpos);
-    for (int64_t a = 0; a < n;) {
-        int64_t b = a, row = rp[a].row;
-        for (int64_t d = 0; d < D; ++d) G[d] = 0.0;
-        for (; b < n && rp[b].row == row; ++b) {
-            const float *g = grad_out + bag_of[rp[b].pos] * D;
-            for (int64_t d = 0; d < D; ++d) G[d] += (double)g[d];
-        }
-        int rc = dtype == ORC_F32 ? update_row_f64((float *)table, state, row, D, optimizer, lr, eps, G)
-                                  : update_row_bf16((uint16_t *)table, state, row, D, optimizer, lr, eps, G);
-        if (rc != ORC_OK) { free(rp); free(bag_of); free(G); return rc; }
-        a = b;
-    }
+    int rc = update_sorted_rows(table, state, D, dtype, optimizer, lr, eps, rp, n, bag_of, grad_out, G);
     free(rp); free(bag_of); free(G);
-    return ORC_OK;
+    return rc;
+}
+
+/*
+ * The same iteration on several host threads, for tables and traces at the full sizes of the workloads.  Nothing
+ * about the arithmetic changes: a bag is still summed by one thread in lookup order, and a row's gradients are
+ * still added by one thread in ascending position and the row updated once, so the result equals orc_train_iter's
+ * bit for bit (tests compare them).  Thread t takes the bags [t*bags/P, (t+1)*bags/P) in the forward, and the rows
+ * with row % P == t in the backward (it picks its lookups out of the batch in ascending position and sorts them by
+ * row); the forward of all threads ends before any update starts.
+ */
+typedef struct {
+    void *table; float *state; int64_t D; int dtype, optimizer; float lr, eps;
+    const int64_t *row_idx; int64_t n; const int64_t *bag_off; int64_t bags;
+    const float *grad_out; float *out; const int64_t *bag_of;
+    int t, P, phase, rc;
+} mt_job_t;
+
+static void *mt_worker(void *arg) {
+    mt_job_t *j = (mt_job_t *)arg;
+    j->rc = ORC_OK;
+    if (j->phase == 0) {
+        forward_bags(j->table, j->dtype, j->D, j->row_idx, j->bag_off, j->bags * j->t / j->P,
+                     j->bags * (j->t + 1) / j->P, j->out);
+        return NULL;
+    }
+    int64_t m = 0;
+    for (int64_t k = 0; k < j->n; ++k) m += (j->row_idx[k] % j->P) == j->t;
+    rowpos_t *rp = (rowpos_t *)malloc((size_t)(m > 0 ? m : 1) * sizeof(rowpos_t));
+    double *G = (double *)malloc((size_t)j->D * sizeof(double));
+    if (!rp || !G) { free(rp); free(G); j->rc = ORC_ERR_NOMEM; return NULL; }
+    int64_t w = 0;
+    for (int64_t k = 0; k < j->n; ++k)
+        if ((j->row_idx[k] % j->P) == j->t) { rp[w].row = j->row_idx[k]; rp[w].pos = k; ++w; }
+    qsort(rp, (size_t)m, sizeof(rowpos_t), cmp_rowpos);
+    j->rc = update_sorted_rows(j->table, j->state, j->D, j->dtype, j->optimizer, j->lr, j->eps, rp, m, j->bag_of,
+                               j->grad_out, G);
+    free(rp); free(G);
+    return NULL;
+}
+
+int orc_train_iter_mt(void *table, float *state, int64_t rows, int64_t D, int dtype, int optimizer, float lr,
+                      float eps, const int64_t *row_idx, int64_t n, const int64_t *bag_off, int64_t bags,
+                      const float *grad_out, float *out, int threads) {
+    if (threads < 1 || threads > 256) return ORC_ERR_ARG;
+    if (bag_off[0] != 0 || bag_off[bags] != n) return ORC_ERR_ARG;
+    if (optimizer != ORC_SGD && optimizer != ORC_ADAGRAD && optimizer != ORC_ADAGRAD_ROWWISE) return ORC_ERR_ARG;
+    for (int64_t k = 0; k < n; ++k) if (row_idx[k] < 0 || row_idx[k] >= rows) return ORC_ERR_ID_RANGE;
+    int64_t *bag_of = NULL;
+    if (grad_out && n > 0) {
+        bag_of = (int64_t *)malloc((size_t)n * sizeof(int64_t));
+        if (!bag_of) return ORC_ERR_NOMEM;
+        for (int64_t b = 0; b < bags; ++b)
+            for (int64_t k = bag_off[b]; k < bag_off[b + 1]; ++k) bag_of[k] = b;
+    }
+    mt_job_t *jobs = (mt_job_t *)malloc((size_t)threads * sizeof(mt_job_t));
+    pthread_t *tid = (pthread_t *)malloc((size_t)threads * sizeof(pthread_t));
+    if (!jobs || !tid) { free(jobs); free(tid); free(bag_of); return ORC_ERR_NOMEM; }
+    int rc = ORC_OK;
+    for (int phase = 0; phase < 2 && rc == ORC_OK; ++phase) {
+        if (phase == 0 && !out) continue;
+        if (phase == 1 && !bag_of) continue;
+        int started = 0;
+        for (int t = 0; t < threads; ++t) {
+            mt_job_t j = {table, state, D, dtype, optimizer, lr, eps, row_idx, n, bag_off, bags, grad_out, out, bag_of,
+                          t, threads, phase, ORC_OK};
+            jobs[t] = j;
+            if (pthread_create(&tid[t], NULL, mt_worker, &jobs[t]) != 0) { rc = ORC_ERR_INTERNAL; break; }
+            ++started;
+        }
+        for (int t = 0; t < started; ++t) {
+            pthread_join(tid[t], NULL);
+            if (jobs[t].rc != ORC_OK && rc == ORC_OK) rc = jobs[t].rc;
+        }
+    }
+    free(jobs); free(tid); free(bag_of);
+    return rc;
 }
 
 /*
@@ -512,43 +608,4 @@ int orc_cache_apply(void *cache_w, float *cache_state, void *host_w, float *host
         }
     }
     return ORC_OK;
-}
-
-/*
- * Optional by-product of the plan: the lookups of every batch grouped by row (ids ascending, and for one
- * id the lookup positions ascending), the cache slot of each grouped lookup, and the cuts of the grouped
- * list into work items: a new item starts where the id changes and at every multiple of `chunk` positions
- * counted from the batch's first grouped lookup (bit 31 of an item's start marks the first kind).  split_starts lists the first grouped lookup of every id
- * whose lookups span three items or more (they reach the second multiple of `chunk` after the first lookup).  This is bookkeeping for
- * the backward pass, not part of Algorithm 1; the definition is this build's.  Returns the number of items
- * or <0.
- */
-int64_t orc_group_lookups(const int64_t *ids, const int64_t *iter_off, int64_t T, const int32_t *lookup_slots,
-                          int64_t chunk, int32_t *grouped_slots, int32_t *grouped_lookups, uint32_t *item_starts,
-                          int64_t *item_off, uint32_t *split_starts, int64_t *split_off) {
-    int64_t nitems = 0, nsplit = 0;
-    item_off[0] = 0;
-    split_off[0] = 0;
-    for (int64_t i = 0; i < T; ++i) {
-        int64_t a = iter_off[i], n = iter_off[i + 1] - a;
-        rowpos_t *rp = (rowpos_t *)malloc((size_t)(n > 0 ? n : 1) * sizeof(rowpos_t));
-        if (!rp) return ORC_ERR_NOMEM;
-        for (int64_t k = 0; k < n; ++k) { rp[k].row = ids[a + k]; rp[k].pos = k; }
-        qsort(rp, (size_t)n, sizeof(rowpos_t), cmp_rowpos);
-        for (int64_t p = 0; p < n; ++p) {
-            grouped_lookups[a + p] = (int32_t)rp[p].pos;
-            grouped_slots[a + p] = lookup_slots[a + rp[p].pos];
-            int first_of_id = p == 0 || rp[p].row != rp[p - 1].row;
-            if (p % chunk == 0 || first_of_id)                     /* bit 31 marks an item that starts an id */
-                item_starts[nitems++] = (uint32_t)p | (first_of_id ? 0x80000000u : 0u);
-            if (p == 0 || rp[p].row != rp[p - 1].row) {            /* first lookup of an id */
-                int64_t second_cut = (p / chunk + 2) * chunk;
-                if (second_cut < n && rp[second_cut].row == rp[p].row) split_starts[nsplit++] = (uint32_t)p;
-            }
-        }
-        free(rp);
-        item_off[i + 1] = nitems;
-        split_off[i + 1] = nsplit;
-    }
-    return nitems;
 }

@@ -8,11 +8,6 @@
 
 namespace bp {
 
-// Largest grid of the maintenance launches made from this host thread (0: one lane group per list entry).  The
-// overlapped schedule sets it so that its copies leave most of the GPU to the training kernels running beside them;
-// a few hundred wavefronts already keep the host link busy.
-thread_local int64_t g_cache_grid_cap = 0;
-
 namespace {
 
 // TO_BACKING: backing[id] <- cache[slot]; otherwise cache[slot] <- backing[id].
@@ -234,10 +229,11 @@ struct CopyLaunch {
 
 using namespace bp;
 
-BP_EXPORT int bp_cache_apply(const bp_config* cfg, void* cache_w, void* cache_state, void* backing_w, void* backing_state,
+namespace bp {
+int cache_apply_impl(const bp_config* cfg, void* cache_w, void* cache_state, void* backing_w, void* backing_state,
                               const int64_t* evict_ids, const int32_t* evict_slots, int64_t n_evict,
                               const int64_t* prefetch_ids, const int32_t* prefetch_slots, int64_t n_prefetch,
-                              void* stream) {
+                              void* stream, int64_t grid_cap) {
     BP_TRY(check_config(cfg));
     if (n_evict < 0 || n_prefetch < 0) return fail(BP_ERR_INVALID_ARG, "negative list length");
     if (n_evict + n_prefetch == 0) return BP_OK;
@@ -251,15 +247,24 @@ BP_EXPORT int bp_cache_apply(const bp_config* cfg, void* cache_w, void* cache_st
     const int lpr = (int)(row_bytes(cfg) / 16);
     if (n_evict) {
         CopyLaunch l{cfg, cache_w, cache_state, backing_w, backing_state, evict_ids, evict_slots, n_evict, true,
-                     (hipStream_t)stream, g_cache_grid_cap};
+                     (hipStream_t)stream, grid_cap};
         BP_TRY(dispatch_row(lpr, false, l));
     }
     if (n_prefetch) {
         CopyLaunch l{cfg, cache_w, cache_state, backing_w, backing_state, prefetch_ids, prefetch_slots, n_prefetch, false,
-                     (hipStream_t)stream, g_cache_grid_cap};
+                     (hipStream_t)stream, grid_cap};
         BP_TRY(dispatch_row(lpr, false, l));
     }
     return BP_OK;
+}
+}  // namespace bp
+
+BP_EXPORT int bp_cache_apply(const bp_config* cfg, void* cache_w, void* cache_state, void* backing_w, void* backing_state,
+                              const int64_t* evict_ids, const int32_t* evict_slots, int64_t n_evict,
+                              const int64_t* prefetch_ids, const int32_t* prefetch_slots, int64_t n_prefetch,
+                              void* stream) {
+    return bp::cache_apply_impl(cfg, cache_w, cache_state, backing_w, backing_state, evict_ids, evict_slots, n_evict, prefetch_ids,
+                                prefetch_slots, n_prefetch, stream, 0);
 }
 
 BP_EXPORT int bp_cache_apply_duplex_workspace_bytes(const bp_config* cfg, int64_t n_evict, size_t* bytes) {
@@ -291,7 +296,7 @@ BP_EXPORT int bp_cache_apply_duplex(const bp_config* cfg, void* cache_w, void* c
         return fail(BP_ERR_WORKSPACE_TOO_SMALL, "workspace %zu < required %zu bytes", workspace_bytes, need);
     DuplexLaunch l{cfg, cache_w, cache_state, backing_w, backing_state, workspace,
                    workspace ? (char*)workspace + stage_w_bytes(cfg, n_evict) : nullptr, evict_ids, evict_slots, n_evict,
-                   prefetch_ids, prefetch_slots, n_prefetch, (hipStream_t)stream, true, true, g_cache_grid_cap};
+                   prefetch_ids, prefetch_slots, n_prefetch, (hipStream_t)stream, true, true, 0};
     return dispatch_row((int)(row_bytes(cfg) / 16), false, l);
 }
 
@@ -308,8 +313,9 @@ int check_staging(const bp_config* cfg, int64_t n_evict, const void* staging, si
 }  // namespace
 }  // namespace bp
 
-BP_EXPORT int bp_cache_stage(const bp_config* cfg, const void* cache_w, const void* cache_state, const int32_t* evict_slots,
-                             int64_t n_evict, void* staging, size_t staging_bytes, void* stream) {
+namespace bp {
+int cache_stage_impl(const bp_config* cfg, const void* cache_w, const void* cache_state, const int32_t* evict_slots,
+                             int64_t n_evict, void* staging, size_t staging_bytes, void* stream, int64_t grid_cap) {
     BP_TRY(check_config(cfg));
     if (n_evict < 0) return fail(BP_ERR_INVALID_ARG, "negative list length");
     if (n_evict == 0) return BP_OK;
@@ -319,14 +325,21 @@ BP_EXPORT int bp_cache_stage(const bp_config* cfg, const void* cache_w, const vo
     BP_TRY(check_staging(cfg, n_evict, staging, staging_bytes));
     DuplexLaunch l{cfg, const_cast<void*>(cache_w), const_cast<void*>(cache_state), nullptr, nullptr, staging,
                    (char*)staging + stage_w_bytes(cfg, n_evict), nullptr, evict_slots, n_evict, nullptr, nullptr, 0,
-                   (hipStream_t)stream, true, false, g_cache_grid_cap};
+                   (hipStream_t)stream, true, false, grid_cap};
     return dispatch_row((int)(row_bytes(cfg) / 16), false, l);
 }
+}  // namespace bp
 
-BP_EXPORT int bp_cache_apply_staged(const bp_config* cfg, void* cache_w, void* cache_state, void* backing_w,
+BP_EXPORT int bp_cache_stage(const bp_config* cfg, const void* cache_w, const void* cache_state, const int32_t* evict_slots,
+                             int64_t n_evict, void* staging, size_t staging_bytes, void* stream) {
+    return bp::cache_stage_impl(cfg, cache_w, cache_state, evict_slots, n_evict, staging, staging_bytes, stream, 0);
+}
+
+namespace bp {
+int cache_apply_staged_impl(const bp_config* cfg, void* cache_w, void* cache_state, void* backing_w,
                                     void* backing_state, const int64_t* evict_ids, const int32_t* evict_slots,
                                     int64_t n_evict, const void* staging, size_t staging_bytes, const int64_t* prefetch_ids,
-                                    const int32_t* prefetch_slots, int64_t n_prefetch, void* stream) {
+                                    const int32_t* prefetch_slots, int64_t n_prefetch, void* stream, int64_t grid_cap) {
     BP_TRY(check_config(cfg));
     if (n_evict < 0 || n_prefetch < 0) return fail(BP_ERR_INVALID_ARG, "negative list length");
     if (n_evict + n_prefetch == 0) return BP_OK;
@@ -341,8 +354,17 @@ BP_EXPORT int bp_cache_apply_staged(const bp_config* cfg, void* cache_w, void* c
     void* st = const_cast<void*>(staging);
     DuplexLaunch l{cfg, cache_w, cache_state, backing_w, backing_state, st,
                    st ? (char*)st + stage_w_bytes(cfg, n_evict) : nullptr, evict_ids, evict_slots, n_evict, prefetch_ids,
-                   prefetch_slots, n_prefetch, (hipStream_t)stream, false, true, g_cache_grid_cap};
+                   prefetch_slots, n_prefetch, (hipStream_t)stream, false, true, grid_cap};
     return dispatch_row((int)(row_bytes(cfg) / 16), false, l);
+}
+}  // namespace bp
+
+BP_EXPORT int bp_cache_apply_staged(const bp_config* cfg, void* cache_w, void* cache_state, void* backing_w,
+                                    void* backing_state, const int64_t* evict_ids, const int32_t* evict_slots,
+                                    int64_t n_evict, const void* staging, size_t staging_bytes, const int64_t* prefetch_ids,
+                                    const int32_t* prefetch_slots, int64_t n_prefetch, void* stream) {
+    return bp::cache_apply_staged_impl(cfg, cache_w, cache_state, backing_w, backing_state, evict_ids, evict_slots, n_evict,
+                                       staging, staging_bytes, prefetch_ids, prefetch_slots, n_prefetch, stream, 0);
 }
 
 namespace bp {
@@ -358,12 +380,13 @@ struct HandoffLaunch {
     int64_t n_p, n_early;
     uint32_t* mismatch;
     hipStream_t stream;
+    int64_t grid_cap;
     template <int GW, bool BF16>
     int run() {
         const int lpr = (int)(row_bytes(cfg) / 16);
         const int slpr = cfg->optimizer == BP_ADAGRAD ? cfg->dim / 4 : 0;
         const int rowwise = cfg->optimizer == BP_ADAGRAD_ROWWISE;
-        BP_LAUNCH(K_CACHE_DUPLEX, (cache_handoff_kernel<GW>), capped_grid((n_e + n_early) * GW, g_cache_grid_cap),
+        BP_LAUNCH(K_CACHE_DUPLEX, (cache_handoff_kernel<GW>), capped_grid((n_e + n_early) * GW, grid_cap),
                   dim3(kRowBlock), 0, stream, (uint4*)cache_w, (uint4*)cache_s, (uint4*)back_w, (uint4*)back_s, e_ids,
                   e_slots, n_e, p_ids, p_slots, n_p, n_early, cfg->total_rows, cfg->capacity, lpr, slpr, rowwise,
                   mismatch);
@@ -373,10 +396,11 @@ struct HandoffLaunch {
 }  // namespace
 }  // namespace bp
 
-BP_EXPORT int bp_cache_apply_handoff(const bp_config* cfg, void* cache_w, void* cache_state, void* backing_w,
+namespace bp {
+int cache_apply_handoff_impl(const bp_config* cfg, void* cache_w, void* cache_state, void* backing_w,
                                      void* backing_state, const int64_t* evict_ids, const int32_t* evict_slots,
                                      int64_t n_evict, const int64_t* prefetch_ids, const int32_t* prefetch_slots,
-                                     int64_t n_prefetch, int64_t n_early, uint32_t* mismatch_flag, void* stream) {
+                                     int64_t n_prefetch, int64_t n_early, uint32_t* mismatch_flag, void* stream, int64_t grid_cap) {
     BP_TRY(check_config(cfg));
     if (n_evict < 0 || n_prefetch < 0) return fail(BP_ERR_INVALID_ARG, "negative list length");
     if (n_early < 0 || n_early > n_prefetch || n_prefetch - n_early > n_evict)
@@ -391,6 +415,15 @@ BP_EXPORT int bp_cache_apply_handoff(const bp_config* cfg, void* cache_w, void* 
     if ((n_evict && (!evict_ids || !evict_slots)) || (n_prefetch && (!prefetch_ids || !prefetch_slots)))
         return fail(BP_ERR_INVALID_ARG, "a list pointer is NULL");
     HandoffLaunch l{cfg, cache_w, cache_state, backing_w, backing_state, evict_ids, evict_slots, n_evict, prefetch_ids,
-                    prefetch_slots, n_prefetch, n_early, mismatch_flag, (hipStream_t)stream};
+                    prefetch_slots, n_prefetch, n_early, mismatch_flag, (hipStream_t)stream, grid_cap};
     return dispatch_row((int)(row_bytes(cfg) / 16), false, l);
+}
+}  // namespace bp
+
+BP_EXPORT int bp_cache_apply_handoff(const bp_config* cfg, void* cache_w, void* cache_state, void* backing_w,
+                                     void* backing_state, const int64_t* evict_ids, const int32_t* evict_slots,
+                                     int64_t n_evict, const int64_t* prefetch_ids, const int32_t* prefetch_slots,
+                                     int64_t n_prefetch, int64_t n_early, uint32_t* mismatch_flag, void* stream) {
+    return bp::cache_apply_handoff_impl(cfg, cache_w, cache_state, backing_w, backing_state, evict_ids, evict_slots, n_evict,
+                                        prefetch_ids, prefetch_slots, n_prefetch, n_early, mismatch_flag, stream, 0);
 }

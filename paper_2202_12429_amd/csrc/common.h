@@ -43,8 +43,22 @@ int fail(int status, const char* fmt, ...) __attribute__((format(printf, 2, 3)))
 
 int check_config(const bp_config* cfg);
 
-// Grid cap of the cache maintenance launches made from this host thread (cache_apply.hip); 0 = no cap.
-extern thread_local int64_t g_cache_grid_cap;
+// The cache maintenance entry points with an explicit cap on the grid of their launches (0 = one lane group per
+// list entry): the overlapped schedule keeps its copies narrow so that they leave most of the GPU to the training
+// kernels running beside them; a few hundred wavefronts already keep the host link busy.
+int cache_apply_impl(const bp_config* cfg, void* cache_w, void* cache_state, void* backing_w, void* backing_state,
+                     const int64_t* evict_ids, const int32_t* evict_slots, int64_t n_evict, const int64_t* prefetch_ids,
+                     const int32_t* prefetch_slots, int64_t n_prefetch, void* stream, int64_t grid_cap);
+int cache_stage_impl(const bp_config* cfg, const void* cache_w, const void* cache_state, const int32_t* evict_slots,
+                     int64_t n_evict, void* staging, size_t staging_bytes, void* stream, int64_t grid_cap);
+int cache_apply_staged_impl(const bp_config* cfg, void* cache_w, void* cache_state, void* backing_w, void* backing_state,
+                            const int64_t* evict_ids, const int32_t* evict_slots, int64_t n_evict, const void* staging,
+                            size_t staging_bytes, const int64_t* prefetch_ids, const int32_t* prefetch_slots,
+                            int64_t n_prefetch, void* stream, int64_t grid_cap);
+int cache_apply_handoff_impl(const bp_config* cfg, void* cache_w, void* cache_state, void* backing_w, void* backing_state,
+                             const int64_t* evict_ids, const int32_t* evict_slots, int64_t n_evict,
+                             const int64_t* prefetch_ids, const int32_t* prefetch_slots, int64_t n_prefetch,
+                             int64_t n_early, uint32_t* mismatch_flag, void* stream, int64_t grid_cap);
 
 inline size_t elem_bytes(int dtype) { return dtype == BP_F32 ? 4 : 2; }
 inline size_t row_bytes(const bp_config* c) { return (size_t)c->dim * elem_bytes(c->weight_dtype); }

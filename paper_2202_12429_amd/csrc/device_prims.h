@@ -186,26 +186,13 @@ int device_scan(In in, Out out, int64_t n, T* partials, Op op, T identity, hipSt
 // The bits to sort are spread evenly over the fewest passes of at most 9 bits (34 bits: 9+9+8+8).
 // ---------------------------------------------------------------------------------------------
 constexpr int kSortBlock = 256;
-#ifndef BP_SORT_XCD
-#define BP_SORT_XCD 1
-#endif
 // Tile of this workgroup.  Workgroups go to the eight XCDs round-robin; with the mapping below XCD x takes the x-th
 // eighth of the tiles in order, so the tiles whose scattered runs are neighbours in memory meet in one L2.
 __device__ __forceinline__ uint32_t sort_tile_of_block(uint32_t ntiles) {
-#if BP_SORT_XCD
     const uint32_t per = (ntiles + 7u) / 8u;
     return (blockIdx.x % 8u) * per + blockIdx.x / 8u;
-#else
-    return blockIdx.x;
-#endif
 }
-inline uint32_t sort_grid(uint32_t ntiles) {
-#if BP_SORT_XCD
-    return (ntiles + 7u) / 8u * 8u;
-#else
-    return ntiles;
-#endif
-}
+inline uint32_t sort_grid(uint32_t ntiles) { return (ntiles + 7u) / 8u * 8u; }
 constexpr int kMaxRadixBits = 9;
 constexpr int kMaxRadix = 1 << kMaxRadixBits;
 

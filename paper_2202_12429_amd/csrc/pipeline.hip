@@ -58,15 +58,9 @@ constexpr int64_t kHandoffMaxRows = int64_t(1) << 17;
 
 int prefetch_range(bp_pipeline* p, int64_t a, int64_t b) {      // cache <- backing for list entries [a, b)
     if (b <= a) return BP_OK;
-    return bp_cache_apply(&p->cfg, p->cache_w, p->cache_s, p->back_w, p->back_s, nullptr, nullptr, 0, p->p_ids + a,
-                          p->p_slots + a, b - a, p->maint);
+    return cache_apply_impl(&p->cfg, p->cache_w, p->cache_s, p->back_w, p->back_s, nullptr, nullptr, 0, p->p_ids + a,
+                            p->p_slots + a, b - a, p->maint, p->grid_cap);
 }
-
-struct GridCap {          // the maintenance launches of this scope stay narrow
-    explicit GridCap(int64_t cap) : old_(g_cache_grid_cap) { g_cache_grid_cap = cap; }
-    ~GridCap() { g_cache_grid_cap = old_; }
-    int64_t old_;
-};
 
 int64_t late_count(const bp_pipeline* p, int j) {
     return j < p->T ? (p->p_off[j + 1] - p->p_off[j]) - p->early[j] : 0;
@@ -76,7 +70,6 @@ int64_t late_count(const bp_pipeline* p, int j) {
 // its last fetch is enqueued: after A_{j-1} when it has late prefetches, else already after B_{j-2}, in which case
 // it never waits for the batch before it.
 int enqueue_after_batch(bp_pipeline* p, int i) {
-    GridCap cap(p->grid_cap);
     const int T = p->T;
     const int64_t ea = i >= 0 ? p->e_off[i] : 0, eb = i >= 0 ? p->e_off[i + 1] : 0;
     const int64_t ne = eb - ea;
@@ -85,8 +78,8 @@ int enqueue_after_batch(bp_pipeline* p, int i) {
     const int64_t p2a = j2 < T ? p->p_off[j2] : 0, p2b = j2 < T ? p->p_off[j2] + p->early[j2] : 0;       // early of i+2
     if (p->L_eff < 2) {
         // the synchronous order: every write-back of batch i before any fetch for batch i+1
-        BP_TRY(bp_cache_apply(&p->cfg, p->cache_w, p->cache_s, p->back_w, p->back_s, p->e_ids + ea, p->e_slots + ea, ne,
-                              p->p_ids + p1a, p->p_slots + p1a, p1b - p1a, p->maint));
+        BP_TRY(cache_apply_impl(&p->cfg, p->cache_w, p->cache_s, p->back_w, p->back_s, p->e_ids + ea, p->e_slots + ea, ne,
+                                p->p_ids + p1a, p->p_slots + p1a, p1b - p1a, p->maint, p->grid_cap));
         if (j1 < T) BP_HIP(hipEventRecord(p->ready[j1 & 1], p->maint));
         return BP_OK;
     }
@@ -100,24 +93,27 @@ int enqueue_after_batch(bp_pipeline* p, int i) {
         int64_t n_free = p->cfg.capacity + ea - p2a;          // early entries whose slot has been free since before
         if (n_free > p2b - p2a) n_free = p2b - p2a;
         if (n_free < 0) return fail(BP_ERR_INVALID_ARG, "internal: batch %d has no late prefetches but its successor's ring positions say otherwise", j1);
-        GridCap narrow(p->grid_cap < kHandoffBlocks ? p->grid_cap : kHandoffBlocks);
-        BP_TRY(bp_cache_apply_handoff(&p->cfg, p->cache_w, p->cache_s, p->back_w, p->back_s, p->e_ids + ea, p->e_slots + ea,
-                                      ne, p->p_ids + p2a, p->p_slots + p2a, p2b - p2a, n_free, nullptr, p->maint));
+        const int64_t narrow = p->grid_cap < kHandoffBlocks ? p->grid_cap : kHandoffBlocks;
+        BP_TRY(cache_apply_handoff_impl(&p->cfg, p->cache_w, p->cache_s, p->back_w, p->back_s, p->e_ids + ea,
+                                        p->e_slots + ea, ne, p->p_ids + p2a, p->p_slots + p2a, p2b - p2a, n_free, nullptr,
+                                        p->maint, narrow));
         if (j2 < T && late_count(p, j2) == 0) BP_HIP(hipEventRecord(p->ready[j2 & 1], p->maint));
         return BP_OK;
     }
-    BP_TRY(bp_cache_stage(&p->cfg, p->cache_w, p->cache_s, p->e_slots + ea, ne, p->staging, p->staging_bytes, p->maint));
+    BP_TRY(cache_stage_impl(&p->cfg, p->cache_w, p->cache_s, p->e_slots + ea, ne, p->staging, p->staging_bytes, p->maint,
+                            p->grid_cap));
     if (j1 < T && (i < 0 || late_count(p, j1) > 0)) {
         BP_TRY(prefetch_range(p, p1a, p1b));
         BP_HIP(hipEventRecord(p->ready[j1 & 1], p->maint));
     }
     if (p->L_eff >= 3) {     // rows evicted after batch i are not used by batch i+2: one launch, both directions
-        BP_TRY(bp_cache_apply_staged(&p->cfg, p->cache_w, p->cache_s, p->back_w, p->back_s, p->e_ids + ea, p->e_slots + ea,
-                                     ne, p->staging, p->staging_bytes, p->p_ids + p2a, p->p_slots + p2a, p2b - p2a,
-                                     p->maint));
+        BP_TRY(cache_apply_staged_impl(&p->cfg, p->cache_w, p->cache_s, p->back_w, p->back_s, p->e_ids + ea,
+                                       p->e_slots + ea, ne, p->staging, p->staging_bytes, p->p_ids + p2a, p->p_slots + p2a,
+                                       p2b - p2a, p->maint, p->grid_cap));
     } else {
-        BP_TRY(bp_cache_apply_staged(&p->cfg, p->cache_w, p->cache_s, p->back_w, p->back_s, p->e_ids + ea, p->e_slots + ea,
-                                     ne, p->staging, p->staging_bytes, nullptr, nullptr, 0, p->maint));
+        BP_TRY(cache_apply_staged_impl(&p->cfg, p->cache_w, p->cache_s, p->back_w, p->back_s, p->e_ids + ea,
+                                       p->e_slots + ea, ne, p->staging, p->staging_bytes, nullptr, nullptr, 0, p->maint,
+                                       p->grid_cap));
         BP_TRY(prefetch_range(p, p2a, p2b));
     }
     if (j2 < T && late_count(p, j2) == 0) BP_HIP(hipEventRecord(p->ready[j2 & 1], p->maint));

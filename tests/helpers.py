@@ -7,19 +7,8 @@ import workloads
 
 
 def say(msg):
-    """Progress line of a long test: printed, and appended to a log file in the run's output folder, so that a run
-    whose stdout is captured still shows signs of life."""
-    import os
-    import sys
+    """Progress line of a long test, flushed at once so that a captured or piped run still shows signs of life."""
     print(msg, flush=True)
-    try:
-        root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-        os.makedirs(os.path.join(root, "gpurun_out"), exist_ok=True)
-        with open(os.path.join(root, "gpurun_out", "gpu_test_progress.log"), "a") as f:
-            f.write(msg + "\n")
-    except OSError:
-        pass
-    sys.stdout.flush()
 
 
 def table_to_numpy(cfg, w_f32: torch.Tensor) -> np.ndarray:
@@ -62,22 +51,24 @@ class OracleStepper:
     """Oracle part B one batch at a time, for lockstep comparison with the GPU at sizes where keeping every
     pooled output would not fit in memory."""
 
-    def __init__(self, cfg, trace):
+    def __init__(self, cfg, trace, threads=None):
         self.cfg, self.trace = cfg, trace
         self.dt, self.op = oracle_codes(cfg)
         self.W = init_table_host(cfg)
         self.S = np.zeros(oracle.state_shape(cfg.total_rows, cfg.dim, self.op), dtype=np.float32)
         self.bags = trace.bag_offsets.shape[1] - 1
+        self.threads = oracle.host_threads() if threads is None else threads
 
-    def step(self, i):
+    def step(self, i, g=None):
         c = self.cfg
-        g = _grad_host(c, i, self.bags)
+        g = _grad_host(c, i, self.bags) if g is None else g
         return oracle.train_iter(self.W, self.S, c.dim, self.dt, self.op, c.lr, c.eps, self.trace.iter_ids(i),
-                                 self.trace.bag_offsets[i], g)
+                                 self.trace.bag_offsets[i], g, threads=self.threads)
 
 
-def oracle_uncached(cfg, trace, T=None, keep_outputs=True, progress=None):
-    """Oracle part B: synchronous training on the full table.  Returns (W, S, [out_i])."""
+def oracle_uncached(cfg, trace, T=None, keep_outputs=True, progress=None, threads=1):
+    """Oracle part B: synchronous training on the full table.  Returns (W, S, [out_i]).  threads > 1 takes the
+    oracle's multi-threaded leg (bit-identical to the serial routine, tests/test_oracle_training.py)."""
     T = trace.iter_offsets.shape[0] - 1 if T is None else T
     R, D = cfg.total_rows, cfg.dim
     dt, op = oracle_codes(cfg)
@@ -87,7 +78,8 @@ def oracle_uncached(cfg, trace, T=None, keep_outputs=True, progress=None):
     bags = trace.bag_offsets.shape[1] - 1
     for i in range(T):
         g = _grad_host(cfg, i, bags)
-        o = oracle.train_iter(W, S, D, dt, op, cfg.lr, cfg.eps, trace.iter_ids(i), trace.bag_offsets[i], g)
+        o = oracle.train_iter(W, S, D, dt, op, cfg.lr, cfg.eps, trace.iter_ids(i), trace.bag_offsets[i], g,
+                              threads=threads)
         if keep_outputs:
             outs.append(o)
         if progress is not None and (i + 1) % 20 == 0:
@@ -147,9 +139,10 @@ def make_backing(cfg, pinned=True, chunk_rows=1 << 20):
 
 
 def gpu_cached_training(cfg, trace, T=None, pinned=True, capacity=None, check_outputs=None, grouping=True,
-                        duplex=None, overlapped=False, reserve=0, handoff=None):
+                        duplex=None, overlapped=False, reserve=0, handoff=None, pass_grad=False, ids_dev=None):
     """Runs plan + T iterations of cache_apply / fwd / bwd_update + flush through the C ABI.
-    check_outputs(i, out_tensor) is called after every forward.  Returns (trainer, plan, W, S).
+    check_outputs(i, out_tensor) is called after every forward (with pass_grad: check_outputs(i, out_tensor,
+    grad_tensor), the batch's upstream gradient on the device).  Returns (trainer, plan, W, S).
     overlapped=True: cache maintenance runs on the library's maintenance stream (bp_pipeline_*)."""
     from paper_2202_12429_amd.runner import CachedEmbeddingTrainer
     T = trace.iter_offsets.shape[0] - 1 if T is None else T
@@ -158,8 +151,10 @@ def gpu_cached_training(cfg, trace, T=None, pinned=True, capacity=None, check_ou
     # by default the sorting backward (grouping=False) also takes the older maintenance paths, so both stay covered
     tr = CachedEmbeddingTrainer(bcfg, W, S, grouping=grouping, duplex=True if duplex is None else duplex,
                                 handoff=grouping if handoff is None else handoff)
-    ids_dev = torch.from_numpy(trace.ids[:trace.iter_offsets[T]]).cuda()
+    if ids_dev is None:
+        ids_dev = torch.from_numpy(trace.ids[:trace.iter_offsets[T]]).cuda()
     plan = tr.plan(ids_dev, trace.iter_offsets[:T + 1])
+    del ids_dev
     bags = trace.bag_offsets.shape[1] - 1
     if overlapped:
         tr.begin()
@@ -172,12 +167,12 @@ def gpu_cached_training(cfg, trace, T=None, pinned=True, capacity=None, check_ou
             tr.maintain(i)
         out = tr.forward(i, bo, bags)
         if check_outputs is not None and not overlapped:
-            check_outputs(i, out)
+            check_outputs(i, out, g) if pass_grad else check_outputs(i, out)
         tr.backward_update(i, bo, bags, g)
         if overlapped:
             tr.release(i)
             if check_outputs is not None:       # after release: the host waits here while maintenance runs on
-                check_outputs(i, out)
+                check_outputs(i, out, g) if pass_grad else check_outputs(i, out)
     if overlapped:
         tr.end()
     else:
@@ -220,11 +215,35 @@ def assert_outputs_close(got: np.ndarray, want: np.ndarray, max_bag: int, wmax: 
     assert not bad.any(), f"{bad.sum()} outputs off, worst {diff.max()}, worst ratio {(diff / tol).max()}"
 
 
-def assert_weights_close(got: np.ndarray, want: np.ndarray):
+def weight_errors(got: np.ndarray, want: np.ndarray):
+    """Both measures of the distance between two tables, each as a multiple of its 1e-4 bar:
+      row   |a-b| / (1e-4 * max(|b|, max|b_row|, 1e-2))   an embedding vector is the unit (see _row_scale)
+      elem  |a-b| / (1e-4 * max(|b|, 1e-2))               every element against its own magnitude
+    Returns (worst row measure, worst elem measure, index of the worst elem measure)."""
+    diff = np.abs(got.astype(np.float64) - want.astype(np.float64))
+    row = float((diff / (1e-4 * _row_scale(want, 1e-2))).max())
+    e = diff / (1e-4 * np.maximum(np.abs(want.astype(np.float64)), 1e-2))
+    k = int(e.argmax())
+    return row, float(e.flat[k]), np.unravel_index(k, e.shape)
+
+
+def assert_weights_close(got: np.ndarray, want: np.ndarray, elementwise=False):
     """Final table: |a-b| <= 1e-4 * max(|b|, max|b_row|, 1e-2) element-wise.  Returns the worst error relative
-    to that reference magnitude (so 1e-4 is the bound)."""
+    to that reference magnitude (so 1e-4 is the bound).  elementwise=True also holds every element to
+    |a-b| <= 1e-4 * max(|b|, 1e-2), its own magnitude alone."""
     diff = np.abs(got.astype(np.float64) - want.astype(np.float64))
     ref = _row_scale(want, 1e-2)
     bad = diff > 1e-4 * ref
     assert not bad.any(), f"{bad.sum()} weights off, worst {diff.max()} at {np.unravel_index(diff.argmax(), diff.shape)}"
+    if elementwise:
+        own = np.maximum(np.abs(want.astype(np.float64)), 1e-2)
+        bad = diff > 1e-4 * own
+        assert not bad.any(), (f"{bad.sum()} weights off by their own magnitude, worst ratio {(diff / (1e-4 * own)).max()} "
+                               f"at {np.unravel_index((diff / own).argmax(), diff.shape)}")
     return float((diff / ref).max())
+
+
+def state_error(got: np.ndarray, want: np.ndarray) -> float:
+    """Worst relative error of an optimizer state (entries are sums of squares, never negative)."""
+    w = want.astype(np.float64)
+    return float((np.abs(got.astype(np.float64) - w) / np.maximum(w, 1e-30)).max()) if w.size else 0.0

@@ -8,6 +8,7 @@ import numpy as np
 import pytest
 import torch
 
+import grouping
 import helpers
 import oracle
 import workloads
@@ -117,7 +118,7 @@ def run_bwd(bp, cfg, w, state, slots, off, bags, grad, onehot):
 def run_bwd_grouped(bp, cfg, w, state, slots, off, bags, grad, onehot):
     valid = (slots >= 0) & (slots < cfg.capacity)
     assert valid.all()
-    gs, gl, st, ioff, sp, soff = oracle.group_lookups(slots.astype(np.int64), np.array([0, len(slots)]), slots)
+    gs, gl, st, ioff, sp, soff = grouping.build_grouping(slots.astype(np.int64), np.array([0, len(slots)]), slots)
     wd = w.cuda()
     sd = None if state is None else torch.from_numpy(state).cuda()
     ws = torch.empty(bp.bp_embbag_bwd_update_grouped_workspace_bytes(cfg, len(slots), bags, not onehot),
@@ -362,15 +363,14 @@ def assert_plan_equal(got, want, N):
     assert np.array_equal(got.lookup_slots.cpu().numpy(), want.lookup_slots[:N]), "lookup_slots"
 
 
-def assert_grouping_equal(got, want, ids, off):
-    """The plan's optional grouping against the oracle's definition of it (index work: bit-exact)."""
-    gs, gl, st, ioff, sp, soff = oracle.group_lookups(ids, off, want.lookup_slots)
-    assert np.array_equal(got.item_offsets, ioff), "item_offsets"
-    assert np.array_equal(got.split_offsets, soff), "split_offsets"
-    assert np.array_equal(got.split_starts.cpu().numpy().view(np.uint32), sp), "split_starts"
-    assert np.array_equal(got.grouped_slots.cpu().numpy(), gs), "grouped_slots"
-    assert np.array_equal(got.grouped_lookups.cpu().numpy(), gl), "grouped_lookups"
-    assert np.array_equal(got.item_starts.cpu().numpy().view(np.uint32), st), "item_starts"
+def assert_grouping_valid(got, want, ids, off):
+    """The plan's optional grouping held to the contract the header gives a caller (tests/grouping.py); the slots
+    it must carry are the oracle plan's."""
+    grouping.check_grouping(ids, off, want.lookup_slots, got.grouped_slots.cpu().numpy(), got.grouped_lookups.cpu().numpy(),
+                            got.item_starts.cpu().numpy(), got.item_offsets, got.split_starts.cpu().numpy(),
+                            got.split_offsets)
+    assert got.item_offsets[0] == 0 and got.split_offsets[0] == 0
+    assert got.item_offsets[-1] == got.item_starts.numel() and got.split_offsets[-1] == got.split_starts.numel()
 
 
 def plan_both(bp, ids, off, R, L, C):
@@ -378,7 +378,7 @@ def plan_both(bp, ids, off, R, L, C):
     got = bp.bp_oracle_plan(cfg, dev(ids), off, grouping=True)
     want = oracle.plan(ids, off, R, L, C)
     assert_plan_equal(got, want, len(ids))
-    assert_grouping_equal(got, want, ids, off)
+    assert_grouping_valid(got, want, ids, off)
     plain = bp.bp_oracle_plan(cfg, dev(ids), off)                  # without the optional outputs: same plan
     assert_plan_equal(plain, want, len(ids))
     assert plain.grouped_slots is None
@@ -618,7 +618,7 @@ def test_plan_without_configured_lookahead(bp):
                                 tr.iter_offsets, grouping=True)
         assert got.L_requested == want_L
         assert_plan_equal(got, want, len(tr.ids))
-        assert_grouping_equal(got, want, tr.ids, tr.iter_offsets)
+        assert_grouping_valid(got, want, tr.ids, tr.iter_offsets)
         say(f"  C={C} reserve={reserve}: start-up rule {want_L}, L_eff {got.L_eff}")
     with pytest.raises(bp.BagpipeError) as e:            # the first batch alone does not fit
         bp.bp_oracle_plan(bp.make_config(cfg.total_rows, 900, 16, lookahead=0), dev(tr.ids), tr.iter_offsets)
@@ -641,7 +641,7 @@ def test_plan_with_reserve(bp):
             continue
         got = bp.bp_oracle_plan(bc, dev(tr.ids), tr.iter_offsets, grouping=True)
         assert_plan_equal(got, want, len(tr.ids))
-        assert_grouping_equal(got, want, tr.ids, tr.iter_offsets)
+        assert_grouping_valid(got, want, tr.ids, tr.iter_offsets)
         assert got.peak_occupancy <= C - reserve
 
 
@@ -686,16 +686,10 @@ def run_chunked(bp, ids, off, R, L, C, n_emit, reserve=0):
         n_em = int(off[b] - off[a])
         assert np.array_equal(got.lookup_slots[:n_em].cpu().numpy(), want.lookup_slots[off[a]:off[b]])
         if n_em:
-            gs, gl, st, ioff, sp, soff = oracle.group_lookups(sub_ids[:n_em], sub_off[:b - a + 1],
-                                                              want.lookup_slots[off[a]:off[b]])
-            assert np.array_equal(got.grouped_slots[:n_em].cpu().numpy(), gs)
-            assert np.array_equal(got.grouped_lookups[:n_em].cpu().numpy(), gl)
-            assert np.array_equal(got.item_offsets - got.item_offsets[0], ioff)
-            assert np.array_equal(got.split_offsets - got.split_offsets[0], soff)
-            i0, i1 = int(got.item_offsets[0]), int(got.item_offsets[-1])
-            assert np.array_equal(got.item_starts[i0:i1].cpu().numpy().view(np.uint32), st)
-            s0, s1 = int(got.split_offsets[0]), int(got.split_offsets[-1])
-            assert np.array_equal(got.split_starts[s0:s1].cpu().numpy().view(np.uint32), sp)
+            grouping.check_grouping(sub_ids, sub_off, want.lookup_slots[off[a]:off[b]], got.grouped_slots[:n_em].cpu().numpy(),
+                                    got.grouped_lookups[:n_em].cpu().numpy(), got.item_starts.cpu().numpy(),
+                                    got.item_offsets, got.split_starts.cpu().numpy(), got.split_offsets,
+                                    n_batches=b - a)
         # carried state: replay the oracle's lists up to batch b - 1
         held = {}
         free = list(range(C))

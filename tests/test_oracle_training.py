@@ -241,3 +241,184 @@ def test_cached_training_equals_uncached(optimizer, dtype, bag_max, capacity):
     if dtype == "f32":
         assert np.array_equal(Wu[~touched], W0.numpy()[~touched])
         assert np.abs(Wu[touched] - W0.numpy()[touched]).max() > 0
+
+
+# ---------------------------------------------------------------------------------------------------
+# bf16 rows with row-wise Adagrad (the rule of the largest workload): the value that is rounded to bf16 must be
+# formed by single fp32 operations after fp64 sums.  Pinned by hand-computed bit patterns, by the rule written
+# with torch tensor operations, and by showing that slips planted in the oracle's source turn these pins red.
+# ---------------------------------------------------------------------------------------------------
+def bf16_bits(x):
+    return torch.as_tensor(x, dtype=torch.float32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16).copy()
+
+
+def torch_rowwise_bf16_step(w_bits, s, idx, off, g, lr, eps):
+    """One step of the rule on a bf16 table with torch tensor operations only.  w_bits: uint16 [rows, D];
+    s: float32 [rows]; returns (new bits, new state).  fp64 sums rounded once to fp32, then one fp32 operation per
+    line (torch float32 CPU operations are IEEE single operations), round-to-nearest-even on store."""
+    rows, D = w_bits.shape
+    w = torch.from_numpy(w_bits.view(np.int16).copy()).view(torch.bfloat16).float()
+    bag_of = np.repeat(np.arange(len(off) - 1), np.diff(off))
+    G64 = torch.zeros((rows, D), dtype=torch.float64)
+    G64.index_add_(0, torch.from_numpy(idx), torch.from_numpy(g[bag_of]).double())
+    G = G64.float()                                              # gradient sum: fp64 -> fp32, once
+    touched = torch.zeros(rows, dtype=torch.bool)
+    touched[torch.from_numpy(idx)] = True
+    mean = ((G.double() * G.double()).sum(dim=1) / D).float()    # mean of squares of the rounded sum: fp64 -> fp32
+    s_new = torch.from_numpy(s) + mean                           # fp32
+    den = torch.sqrt(s_new) + torch.tensor(eps, dtype=torch.float32)
+    step = (torch.tensor(lr, dtype=torch.float32) * G) / den[:, None]
+    w_new = w - step
+    w_out = torch.where(touched[:, None], w_new, w).to(torch.bfloat16)
+    s_out = torch.where(touched, s_new, torch.from_numpy(s))
+    return w_out.view(torch.int16).numpy().view(np.uint16).copy(), s_out.numpy().copy()
+
+
+def test_bf16_rowwise_adagrad_hand_computed_row():
+    """One row, D = 2, weights (1, 0.5), state 0, lr 0.5, eps 0, two lookups with gradients (1, 1) and (2, 3):
+    G = (3, 4); mean of squares 12.5; state 12.5; den = sqrt(12.5) = 3.5355339 (fp32 0x40624621);
+    steps 1.5/den = 0.42426407 and 2/den = 0.56568545; new weights 0.57573593 and -0.06568545, which round to
+    the bf16 codes 0x3F13 (0.57421875: the fp32 pattern 0x3F136368 drops 0x6368 < 0x8000) and 0xBD87 (the fp32
+    pattern 0xBD8685F4 has 0x85F4 > 0x8000 and rounds up to 0xBD87 = -0.065917969)."""
+    table = bf16_bits([[1.0, 0.5], [0.25, 0.25]])
+    state = np.zeros(2, dtype=np.float32)
+    g = np.array([[1, 1], [2, 3]], dtype=np.float32)
+    oracle.train_iter(table, state, 2, oracle.BF16, oracle.ADAGRAD_ROWWISE, 0.5, 0.0, np.array([0, 0]),
+                      np.array([0, 1, 2]), g, want_out=False)
+    assert state[0] == np.float32(12.5) and state[1] == 0
+    assert table[0].tolist() == [0x3F13, 0xBD87]
+    assert table[1].tolist() == bf16_bits([0.25, 0.25]).tolist()            # untouched row
+    # second step on the same row with gradient (-4, 0): mean 8, state 20.5, den = sqrt(20.5) = 4.5276926,
+    # step0 = -2/den = -0.44172609 -> w0 = 0.57421875 + 0.44172609 = 1.01594484 -> bf16 0x3F82 (1.015625);
+    # step1 = 0 -> w1 stays 0xBD87
+    oracle.train_iter(table, state, 2, oracle.BF16, oracle.ADAGRAD_ROWWISE, 0.5, 0.0, np.array([0]),
+                      np.array([0, 1]), np.array([[-4, 0]], dtype=np.float32), want_out=False)
+    assert state[0] == np.float32(20.5)
+    assert table[0].tolist() == [0x3F82, 0xBD87]
+
+
+def rowwise_bf16_case(seed, rows=37, D=16, steps=6):
+    rng = np.random.default_rng(seed)
+    w_bits = bf16_bits(rng.uniform(-0.05, 0.05, size=(rows, D)).astype(np.float32))
+    batches = []
+    for _ in range(steps):
+        _, idx, off, r2 = rand_problem(int(rng.integers(1 << 30)), rows=rows, D=D, bags=60, max_len=4)
+        # gradients with many significant bits, so that a sum of several of them is not an fp32 number
+        g = (r2.standard_normal((len(off) - 1, D)) * r2.uniform(0.01, 30.0, size=(len(off) - 1, 1))).astype(np.float32)
+        batches.append((idx, off, g))
+    return w_bits, batches
+
+
+def run_rowwise_bf16(train_iter_fn, w_bits, batches, D, lr, eps):
+    table, state = w_bits.copy(), np.zeros(w_bits.shape[0], dtype=np.float32)
+    for idx, off, g in batches:
+        train_iter_fn(table, state, D, oracle.BF16, oracle.ADAGRAD_ROWWISE, lr, eps, idx, off, g, want_out=False)
+    return table, state
+
+
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_bf16_rowwise_adagrad_matches_torch_ops(seed):
+    """Several rows, several steps, duplicate lookups inside and across bags, gradients that vary along the row:
+    weights (bf16 codes) and state (fp32) equal, bit for bit, the rule written with torch tensor operations."""
+    D, lr, eps = 16, 0.01, 1e-8
+    w_bits, batches = rowwise_bf16_case(seed, D=D)
+    table, state = run_rowwise_bf16(oracle.train_iter, w_bits, batches, D, lr, eps)
+    wt, st = w_bits.copy(), np.zeros(w_bits.shape[0], dtype=np.float32)
+    for idx, off, g in batches:
+        wt, st = torch_rowwise_bf16_step(wt, st, idx, off, g, lr, eps)
+    assert np.array_equal(state, st)
+    assert np.array_equal(table, wt)
+    assert (table != w_bits).mean() > 0.5                       # the steps moved most codes
+
+
+def _mutated_oracle(tmp_path, old, new):
+    """The oracle's source with one textual change, compiled with the oracle's own flags into a library of its own."""
+    import ctypes
+    import os
+    import subprocess
+    src = open(os.path.join(os.path.dirname(oracle.__file__), "bagpipe_oracle.c")).read()
+    assert src.count(old) == 1, f"mutation target not unique: {old!r}"
+    c = tmp_path / "mutant.c"
+    c.write_text(src.replace(old, new))
+    so = tmp_path / "libmutant.so"
+    subprocess.run(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off", "-fno-fast-math", "-pthread",
+                    "-o", str(so), str(c), "-lm"], check=True)
+    lib = ctypes.CDLL(str(so))
+    i64, i32, p = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
+    lib.orc_train_iter.restype = i32
+    lib.orc_train_iter.argtypes = [p, p, i64, i64, i32, i32, ctypes.c_float, ctypes.c_float, p, i64, p, i64, p, p]
+
+    def train_iter(table, state, D, dtype, optimizer, lr, eps, row_idx, bag_off, grad_out, want_out=False):
+        row_idx = np.ascontiguousarray(row_idx, dtype=np.int64)
+        bag_off = np.ascontiguousarray(bag_off, dtype=np.int64)
+        grad_out = np.ascontiguousarray(grad_out, dtype=np.float32)
+        vp = lambda a: ctypes.c_void_p(a.ctypes.data)
+        r = lib.orc_train_iter(vp(table), vp(state), table.shape[0], D, dtype, optimizer, lr, eps, vp(row_idx),
+                               row_idx.shape[0], vp(bag_off), bag_off.shape[0] - 1, vp(grad_out), None)
+        assert r == 0
+    return train_iter
+
+
+@pytest.mark.parametrize("old,new", [
+    # the mean of squares divided by D - 1 instead of D
+    ("float mean = (float)(ms / (double)D);", "float mean = (float)(ms / (double)(D - 1));"),
+    # the squares summed over the unrounded fp64 gradient sum instead of its fp32 value
+    ("{ float g = (float)G[d]; ms += (double)g * (double)g; }", "{ ms += G[d] * G[d]; }"),
+    # epsilon added under the root
+    ("den_row = sqrtf(s) + eps;", "den_row = sqrtf(s + eps);"),
+    # the squares added up in fp32 instead of fp64
+    ("double ms = 0.0;\n        for (int64_t d = 0; d < D; ++d) { float g = (float)G[d]; ms += (double)g * (double)g; }",
+     "float ms = 0.0f;\n        for (int64_t d = 0; d < D; ++d) { float g = (float)G[d]; ms += g * g; }"),
+    # the weight stepped by lr * g without the division
+    ("step = step / den_row;", "step = step * den_row;"),
+    # the state not accumulated
+    ("float s = state[row] + mean;\n        state[row] = s;\n        den_row", "float s = mean;\n        state[row] = s;\n        den_row"),
+])
+def test_bf16_rowwise_pins_catch_planted_slips(tmp_path, old, new):
+    """A slip planted in the oracle's bf16 row-wise branch (in a copy of its source, compiled apart) must fail the
+    comparison with the torch-operations form of the rule: this is what shows that the pin above can see them."""
+    D, lr, eps = 16, 0.01, 1e-3          # an epsilon large enough that its place in the formula shows in fp32
+    mutant = _mutated_oracle(tmp_path, old, new)
+    caught = False
+    for seed in (11, 12, 13):
+        w_bits, batches = rowwise_bf16_case(seed, D=D)
+        wt, st = w_bits.copy(), np.zeros(w_bits.shape[0], dtype=np.float32)
+        for idx, off, g in batches:
+            wt, st = torch_rowwise_bf16_step(wt, st, idx, off, g, lr, eps)
+        good_t, good_s = run_rowwise_bf16(oracle.train_iter, w_bits, batches, D, lr, eps)
+        assert np.array_equal(good_t, wt) and np.array_equal(good_s, st)       # the real oracle passes at this epsilon too
+        bad_t, bad_s = run_rowwise_bf16(mutant, w_bits, batches, D, lr, eps)
+        caught = caught or not (np.array_equal(bad_t, wt) and np.array_equal(bad_s, st))
+    assert caught
+
+
+# ---------------------------------------------------------------------------------------------------
+# the multi-threaded leg is the serial routine, bit for bit
+# ---------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("optimizer,dtype", [("sgd", "f32"), ("adagrad", "f32"), ("adagrad_rowwise", "f32"),
+                                             ("sgd", "bf16"), ("adagrad", "bf16"), ("adagrad_rowwise", "bf16")])
+@pytest.mark.parametrize("threads", [2, 3, 8])
+def test_threaded_leg_equals_serial(optimizer, dtype, threads):
+    D, rows = 8, 300
+    dt, op = oracle.DTYPES[dtype], oracle.OPTIMIZERS[optimizer]
+    rng = np.random.default_rng(77)
+    w32 = rng.uniform(-0.05, 0.05, size=(rows, D)).astype(np.float32)
+    W1 = bf16_bits(w32) if dt == oracle.BF16 else w32.copy()
+    W2 = W1.copy()
+    S1 = np.zeros(oracle.state_shape(rows, D, op), dtype=np.float32)
+    S2 = S1.copy()
+    for it in range(5):
+        _, idx, off, r2 = rand_problem(500 + it, rows=rows, D=D, bags=700, max_len=6)
+        g = r2.standard_normal((len(off) - 1, D)).astype(np.float32)
+        o1 = oracle.train_iter(W1, S1, D, dt, op, 0.01, 1e-8, idx, off, g)
+        o2 = oracle.train_iter(W2, S2, D, dt, op, 0.01, 1e-8, idx, off, g, threads=threads)
+        assert np.array_equal(o1, o2)
+        assert np.array_equal(W1, W2) and np.array_equal(S1, S2)
+    # forward only / backward only, and more threads than bags
+    _, idx, off, r2 = rand_problem(900, rows=rows, D=D, bags=5, max_len=3)
+    g = r2.standard_normal((5, D)).astype(np.float32)
+    assert np.array_equal(oracle.train_iter(W1, S1, D, dt, op, 0.01, 1e-8, idx, off, None),
+                          oracle.train_iter(W2, S2, D, dt, op, 0.01, 1e-8, idx, off, None, threads=threads))
+    oracle.train_iter(W1, S1, D, dt, op, 0.01, 1e-8, idx, off, g, want_out=False)
+    oracle.train_iter(W2, S2, D, dt, op, 0.01, 1e-8, idx, off, g, want_out=False, threads=threads)
+    assert np.array_equal(W1, W2) and np.array_equal(S1, S2)

@@ -27,7 +27,7 @@ import numpy as np
 __all__ = [
     "Config", "Trace", "CONFIGS", "get_config", "make_trace", "table_offsets",
     "zipf_cdf", "hot_exp_cdf", "rank_cdf", "skew_config", "top_fraction_mass", "tune_zipf_exponent",
-    "init_weights", "upstream_grad", "hash_u32",
+    "init_weights", "init_weights_rows", "upstream_grad", "upstream_grad_bags", "hash_u32",
 ]
 
 
@@ -343,8 +343,15 @@ def init_weights(cfg: Config, row_begin: int, row_end: int, device="cpu"):
     """Rows [row_begin, row_end) of the initial table, U(-0.05, 0.05), as a pure function of (seed, row, column).
     fp32 tensor [rows, D]; for bf16 storage the caller converts (round-to-nearest-even)."""
     import torch
+    return init_weights_rows(cfg, torch.arange(row_begin, row_end, dtype=torch.int64, device=device))
+
+
+def init_weights_rows(cfg: Config, rows):
+    """The same initial weights for an explicit list of global rows (int64 tensor, on the device the result
+    should live on)."""
+    import torch
     D = cfg.dim
-    rows = torch.arange(row_begin, row_end, dtype=torch.int64, device=device)
+    device = rows.device
     idx = rows[:, None] * D + torch.arange(D, dtype=torch.int64, device=device)[None, :]
     h = _hash_index(idx, cfg.seed, 1)
     k = (h >> 9) - (1 << 22)                    # integer in [-2**22, 2**22)
@@ -356,8 +363,15 @@ def upstream_grad(cfg: Config, iteration: int, bags: int, device="cpu"):
     """Synthetic upstream gradient dOut[bags, D] of one iteration: a centred sum of twelve hashed 16-bit
     uniforms scaled by 2**-16 (unit variance, bell-shaped, every value exact in fp32)."""
     import torch
+    return upstream_grad_bags(cfg, iteration, torch.arange(bags, dtype=torch.int64, device=device))
+
+
+def upstream_grad_bags(cfg: Config, iteration: int, bag_index):
+    """The same upstream gradient rows for an explicit list of bags (int64 tensor)."""
+    import torch
     D = cfg.dim
-    base = (torch.arange(bags, dtype=torch.int64, device=device)[:, None] * D
+    device = bag_index.device
+    base = (bag_index[:, None] * D
             + torch.arange(D, dtype=torch.int64, device=device)[None, :])
     idx = base + (int(iteration) << 40)
     acc = torch.zeros_like(idx)
