@@ -47,8 +47,32 @@ typedef enum bp_status {
     BP_ERR_UNSUPPORTED = -6          /* size beyond a documented limit */
 } bp_status;
 
-/* Lookups per work item of the backward pass at most (shared by the planner's grouping and the backward kernels). */
-#define BP_BWD_CHUNK 32
+/* How the planner's optional grouping cuts a batch's work for the backward pass (shared by the planner and the
+ * backward kernels): a row looked up more than BP_BWD_ROW_MAX times in a batch is a "long row" and is handed out in
+ * pieces of BP_BWD_PIECE lookups at most. */
+#define BP_BWD_ROW_MAX 16
+#define BP_BWD_PIECE 256
+
+/* One distinct row of a batch, in the batch's grouped order (see bp_plan.grouped_lookups). */
+typedef struct bp_row_rec {
+    uint32_t start;   /* grouped position of the row's first lookup, counted from the batch's first grouped lookup;
+                         bit 31 is set for a long row (more than BP_BWD_ROW_MAX lookups) */
+    uint32_t count;   /* lookups of the row in this batch, >= 1 */
+    int32_t slot;     /* the row's cache slot */
+    uint32_t first;   /* lookup position (in the batch) of its first lookup == grouped_lookups[start] */
+} bp_row_rec;
+
+/* One piece of a long row: lookups [start, start + count) of the batch's grouped order. */
+typedef struct bp_piece_rec {
+    uint32_t start;    /* grouped position of the piece's first lookup (relative to the batch) */
+    uint32_t count;    /* 1 .. BP_BWD_PIECE */
+    int32_t slot;      /* the row's cache slot */
+    uint32_t index;    /* which piece of its row, 0 .. pieces - 1 */
+    uint32_t pieces;   /* pieces of the row: ceil(lookups of the row / BP_BWD_PIECE) */
+    uint32_t partial;  /* rows of two or more pieces: the pieces of such rows are numbered through the batch in
+                          grouped order from 0; this is the number of the row's piece 0 (undefined for one piece) */
+    uint32_t reserved0, reserved1;
+} bp_piece_rec;
 
 enum { BP_F32 = 0, BP_BF16 = 1 };
 enum { BP_SGD = 0, BP_ADAGRAD = 1, BP_ADAGRAD_ROWWISE = 2 };
@@ -102,20 +126,16 @@ typedef struct bp_plan {
     int64_t* evict_offsets;    /* [T+1] */
     int64_t* keep_offsets;     /* [T+1] */
     int64_t* occupancy;        /* [T] rows resident while batch i trains */
-    /* optional (all six NULL, or all six set): every batch's lookups grouped by row, which is a by-product of the
+    /* optional (all four NULL, or all four set): every batch's lookups grouped by row, which is a by-product of the
      * planner's sort and lets bp_embbag_bwd_update_grouped skip its own sort.  Inside a batch the lookups are
-     * ordered by id ascending and, for one id, by lookup position ascending.  A work item is a maximal run of
-     * consecutive grouped lookups of one row that does not cross a multiple of BP_BWD_CHUNK positions (counted
-     * from the batch's first grouped lookup). */
-    int32_t* grouped_slots;    /* device [n_lookups] cache slot of each grouped lookup */
-    int32_t* grouped_lookups;  /* device [n_lookups] its position, relative to the batch's first lookup */
-    uint32_t* item_starts;     /* device [n_lookups] first grouped lookup of each work item, relative to the batch,
-                                  with bit 31 set when that lookup is the first of its row */
-    int64_t* item_offsets;     /* host [T+1] CSR offsets of the batches into item_starts */
-    uint32_t* split_starts;    /* device [n_lookups / BP_BWD_CHUNK + 1] first grouped lookup (relative to the batch) of
-                                  every row whose lookups span three work items or more (they reach the second
-                                  multiple of BP_BWD_CHUNK after the row's first lookup) */
-    int64_t* split_offsets;    /* host [T+1] CSR offsets of the batches into split_starts */
+     * ordered by id ascending and, for one id, by lookup position ascending; the batch's distinct rows, in that
+     * order, are its keep-list entries, and row_recs is parallel to the keep list. */
+    int32_t* grouped_lookups;  /* device [n_lookups] position of each grouped lookup, relative to the batch's first lookup */
+    bp_row_rec* row_recs;      /* device [list_capacity], entry k describes the row of keep-list entry k
+                                  (keep_offsets are its CSR offsets too) */
+    bp_piece_rec* piece_recs;  /* device [n_lookups / (BP_BWD_ROW_MAX + 1) + n_lookups / BP_BWD_PIECE + 2]: the pieces of
+                                  every long row, rows in grouped order, pieces of a row in order */
+    int64_t* piece_offsets;    /* host [T+1] CSR offsets of the batches into piece_recs */
     /* optional: which logical trainer uses a row (Section 3.3: rows used by a single trainer need no synchronisation;
      * of the shared rows only those the next batch needs are synchronised on the critical path).  All three set or
      * none.  The lookups of batch i are dealt to n_trainers trainers by position: trainer t owns the positions
@@ -318,7 +338,8 @@ int bp_embbag_fwd(const bp_config* cfg, const void* cache_w, const int32_t* look
 
 /* ------------------------------------------------------------------------------------------------
  * (4) Backward + update, deterministic (bit-identical from run to run): lookups are grouped by slot with
- * a stable radix sort, G[slot, :] = sum of grad_out[bag(k), :] over the slot's lookups is formed in a
+ * a stable radix sort, the same row and piece records as the planner's grouping are built on the device,
+ * G[slot, :] = sum of grad_out[bag(k), :] over the slot's lookups is formed in a
  * fixed order with fp64 accumulators and rounded once to fp32, and each distinct slot is updated once,
  * in place, in fp32 arithmetic (one rounding per operation, no fused multiply-add):
  *   BP_SGD              w -= lr * G
@@ -329,32 +350,43 @@ int bp_embbag_fwd(const bp_config* cfg, const void* cache_w, const int32_t* look
  *
  * grad_out   device, fp32 [bags][dim]
  * workspace  device, at least bp_embbag_bwd_update_workspace_bytes() bytes, 256-byte aligned
+ * tickets    device, at least bp_embbag_bwd_ticket_bytes(n_lookups) bytes of counters (uint32), ALL ZERO when the call
+ *            starts its work on `stream`.  The call leaves them all zero again when that work has finished, so one
+ *            buffer sized for the largest batch, zeroed once when it is allocated, serves every later call on the
+ *            same stream (calls that overlap in time need buffers of their own).  They count, for a row whose
+ *            lookups are spread over several workgroups, how many of those have stored their sum.
  * Limits: n_lookups < 2^31, bags < 2^31.  Slots outside [0, capacity) are ignored.  Asynchronous.
  * ------------------------------------------------------------------------------------------------ */
 int bp_embbag_bwd_update_workspace_bytes(const bp_config* cfg, int64_t n_lookups, int64_t bags, size_t* bytes);
+size_t bp_embbag_bwd_ticket_bytes(int64_t n_lookups);
 int bp_embbag_bwd_update(const bp_config* cfg, void* cache_w, void* cache_state, const int32_t* lookup_slots,
                          const int64_t* bag_offsets, int64_t n_lookups, int64_t bags, const float* grad_out,
-                         void* workspace, size_t workspace_bytes, void* stream);
+                         void* workspace, size_t workspace_bytes, uint32_t* tickets, void* stream);
 
 /*
  * The same backward + update for a batch whose lookups the plan has already grouped by row (bp_plan's
- * optional outputs): no sort and no scan at run time, two kernel launches.  Results are those of
- * bp_embbag_bwd_update up to the order in which a row's gradients enter the fp64 sum.
+ * optional outputs): no sort and no scan at run time, ONE kernel launch (three when bag_offsets is given).  A row of
+ * up to BP_BWD_ROW_MAX lookups is summed and updated by one lane group; every piece of a long row by one workgroup,
+ * and a row of several pieces is finished by whichever of its workgroups ends last, which adds the pieces' sums in
+ * piece order.  Results are those of bp_embbag_bwd_update up to the order in which a row's gradients enter the
+ * fp64 sum; that order is fixed by the records, never by timing.
  *
- * grouped_slots / grouped_lookups  device, the batch's slices [iter_offsets[i], iter_offsets[i+1]) of the plan arrays
- * item_starts, n_items             device, the batch's slice [item_offsets[i], item_offsets[i+1]) and its length
- * split_starts, n_split            device, the batch's slice [split_offsets[i], split_offsets[i+1]) and its length
- *                                  (n_split may be 0)
- * workspace                        device, bp_embbag_bwd_update_grouped_workspace_bytes() bytes (multi_hot != 0 when
- *                                  bag_offsets is not NULL), 256-byte aligned
- * Other arguments, limits and error behaviour as for bp_embbag_bwd_update.  Asynchronous.
+ * grouped_lookups     device, the batch's slice [iter_offsets[i], iter_offsets[i+1]) of the plan array
+ * row_recs, n_rows    device, the batch's slice [keep_offsets[i], keep_offsets[i+1]) and its length
+ * piece_recs, n_pieces device, the batch's slice [piece_offsets[i], piece_offsets[i+1]) and its length (may be 0)
+ * workspace           device, bp_embbag_bwd_update_grouped_workspace_bytes() bytes (multi_hot != 0 when bag_offsets is
+ *                     not NULL), 256-byte aligned
+ * tickets             as for bp_embbag_bwd_update: zeroed counters, left zero
+ * Records that point outside the batch or the workspace are skipped.  Other arguments, limits and error behaviour
+ * as for bp_embbag_bwd_update.  Asynchronous.
  */
 int bp_embbag_bwd_update_grouped_workspace_bytes(const bp_config* cfg, int64_t n_lookups, int64_t bags,
                                                  int32_t multi_hot, size_t* bytes);
-int bp_embbag_bwd_update_grouped(const bp_config* cfg, void* cache_w, void* cache_state, const int32_t* grouped_slots,
-                                 const int32_t* grouped_lookups, const uint32_t* item_starts, int64_t n_items,
-                                 const uint32_t* split_starts, int64_t n_split, const int64_t* bag_offsets, int64_t n_lookups, int64_t bags, const float* grad_out,
-                                 void* workspace, size_t workspace_bytes, void* stream);
+int bp_embbag_bwd_update_grouped(const bp_config* cfg, void* cache_w, void* cache_state, const int32_t* grouped_lookups,
+                                 const bp_row_rec* row_recs, int64_t n_rows, const bp_piece_rec* piece_recs,
+                                 int64_t n_pieces, const int64_t* bag_offsets, int64_t n_lookups, int64_t bags,
+                                 const float* grad_out, void* workspace, size_t workspace_bytes, uint32_t* tickets,
+                                 void* stream);
 
 /* ------------------------------------------------------------------------------------------------
  * Diagnostics.

@@ -40,9 +40,8 @@ class _bp_plan(ctypes.Structure):
                 ("keep_ids", ctypes.c_void_p), ("keep_ttl", ctypes.c_void_p), ("list_capacity", ctypes.c_int64),
                 ("prefetch_offsets", ctypes.c_void_p), ("evict_offsets", ctypes.c_void_p),
                 ("keep_offsets", ctypes.c_void_p), ("occupancy", ctypes.c_void_p),
-                ("grouped_slots", ctypes.c_void_p), ("grouped_lookups", ctypes.c_void_p),
-                ("item_starts", ctypes.c_void_p), ("item_offsets", ctypes.c_void_p),
-                ("split_starts", ctypes.c_void_p), ("split_offsets", ctypes.c_void_p),
+                ("grouped_lookups", ctypes.c_void_p), ("row_recs", ctypes.c_void_p),
+                ("piece_recs", ctypes.c_void_p), ("piece_offsets", ctypes.c_void_p),
                 ("trainer_cuts", ctypes.c_void_p), ("n_trainers", ctypes.c_int32), ("keep_owner", ctypes.c_void_p),
                 ("L_eff", ctypes.c_int32),
                 ("L_requested", ctypes.c_int32), ("peak_occupancy", ctypes.c_int64), ("min_capacity", ctypes.c_int64),
@@ -91,9 +90,11 @@ def load_library():
     lib.bp_pipeline_end.argtypes = [vp, vp]
     lib.bp_embbag_fwd.argtypes = [cfgp, vp, vp, vp, i64, i64, vp, vp]
     lib.bp_embbag_bwd_update_workspace_bytes.argtypes = [cfgp, i64, i64, ctypes.POINTER(sz)]
-    lib.bp_embbag_bwd_update.argtypes = [cfgp, vp, vp, vp, vp, i64, i64, vp, vp, sz, vp]
+    lib.bp_embbag_bwd_update.argtypes = [cfgp, vp, vp, vp, vp, i64, i64, vp, vp, sz, vp, vp]
+    lib.bp_embbag_bwd_ticket_bytes.argtypes = [i64]
+    lib.bp_embbag_bwd_ticket_bytes.restype = sz
     lib.bp_embbag_bwd_update_grouped_workspace_bytes.argtypes = [cfgp, i64, i64, i32, ctypes.POINTER(sz)]
-    lib.bp_embbag_bwd_update_grouped.argtypes = [cfgp, vp, vp, vp, vp, vp, i64, vp, i64, vp, i64, i64, vp, vp, sz, vp]
+    lib.bp_embbag_bwd_update_grouped.argtypes = [cfgp, vp, vp, vp, vp, i64, vp, i64, vp, i64, i64, vp, vp, sz, vp, vp]
     lib.bp_error_string.argtypes = [ctypes.c_int]
     lib.bp_error_string.restype = ctypes.c_char_p
     lib.bp_last_error_message.restype = ctypes.c_char_p
@@ -190,14 +191,22 @@ class Plan:
     evict_offsets: np.ndarray
     keep_offsets: np.ndarray
     occupancy: np.ndarray         # int64 [T] host
-    grouped_slots: "object" = None      # int32 [N] device (optional grouping)
-    grouped_lookups: "object" = None    # int32 [N] device
-    item_starts: "object" = None        # uint32 (as int32 tensor) device, trimmed to the item count
-    item_offsets: Optional[np.ndarray] = None   # int64 [T+1] host
+    grouped_lookups: "object" = None    # int32 [N] device (optional grouping)
+    row_recs: "object" = None           # int32 [pairs, 4] device: bp_row_rec of every keep-list entry (start | long
+                                        # flag, count, slot, first), CSR offsets = keep_offsets
+    piece_recs: "object" = None         # int32 [pieces, 8] device: bp_piece_rec (start, count, slot, index, pieces,
+                                        # partial, 0, 0), trimmed to the piece count
+    piece_offsets: Optional[np.ndarray] = None  # int64 [T+1] host
     L_requested: int = 0                # configured lookahead, or the start-up rule's value when none was configured
-    split_starts: "object" = None       # uint32 (as int32 tensor) device, trimmed
-    split_offsets: Optional[np.ndarray] = None  # int64 [T+1] host
     keep_owner: "object" = None         # int32 device, parallel to keep_ids (optional trainer marking)
+
+
+BWD_ROW_MAX, BWD_PIECE = 16, 256      # BP_BWD_ROW_MAX, BP_BWD_PIECE of the C header
+
+
+def piece_capacity(n_lookups: int) -> int:
+    """Entries bp_plan.piece_recs must hold for n_lookups lookups (the bound the C header states)."""
+    return n_lookups // (BWD_ROW_MAX + 1) + n_lookups // BWD_PIECE + 2
 
 
 def bp_oracle_plan_workspace_bytes(cfg: bp_config, n_lookups: int, n_iters: int, grouping: bool = False) -> int:
@@ -230,9 +239,9 @@ def bp_oracle_plan(cfg: bp_config, ids, iter_offsets, list_capacity: Optional[in
     h = dict(prefetch_offsets=np.zeros(T + 1, np.int64), evict_offsets=np.zeros(T + 1, np.int64),
              keep_offsets=np.zeros(T + 1, np.int64), occupancy=np.zeros(max(T, 1), np.int64))
     if grouping:
-        t.update(grouped_slots=torch.empty(max(N, 1), **i32), grouped_lookups=torch.empty(max(N, 1), **i32),
-                 item_starts=torch.empty(max(N, 1), **i32), split_starts=torch.empty(N // 32 + 2, **i32))
-        h.update(item_offsets=np.zeros(T + 1, np.int64), split_offsets=np.zeros(T + 1, np.int64))
+        t.update(grouped_lookups=torch.empty(max(N, 1), **i32), row_recs=torch.empty((max(cap, 1), 4), **i32),
+                 piece_recs=torch.empty((piece_capacity(N), 8), **i32))
+        h.update(piece_offsets=np.zeros(T + 1, np.int64))
     if trainer_cuts is not None:          # int64 [T, P+1]: which logical trainer owns which lookups of a batch
         trainer_cuts = np.ascontiguousarray(trainer_cuts, dtype=np.int64)
         assert trainer_cuts.shape[0] == T
@@ -257,12 +266,10 @@ def bp_oracle_plan(cfg: bp_config, ids, iter_offsets, list_capacity: Optional[in
                 keep_ids=t["keep_ids"][:n_k], keep_ttl=t["keep_ttl"][:n_k],
                 prefetch_offsets=h["prefetch_offsets"], evict_offsets=h["evict_offsets"],
                 keep_offsets=h["keep_offsets"], occupancy=h["occupancy"][:T],
-                grouped_slots=t["grouped_slots"][:N] if grouping else None,
                 grouped_lookups=t["grouped_lookups"][:N] if grouping else None,
-                item_starts=t["item_starts"][:int(h["item_offsets"][-1])] if grouping else None,
-                item_offsets=h["item_offsets"] if grouping else None,
-                split_starts=t["split_starts"][:int(h["split_offsets"][-1])] if grouping else None,
-                split_offsets=h["split_offsets"] if grouping else None,
+                row_recs=t["row_recs"][:n_k] if grouping else None,
+                piece_recs=t["piece_recs"][:int(h["piece_offsets"][-1])] if grouping else None,
+                piece_offsets=h["piece_offsets"] if grouping else None,
                 keep_owner=t["keep_owner"][:n_k] if trainer_cuts is not None else None)
 
 
@@ -305,9 +312,9 @@ def bp_oracle_plan_chunk(cfg: bp_config, ids, iter_offsets, n_emit: int, state: 
     h = dict(prefetch_offsets=np.zeros(n_emit + 1, np.int64), evict_offsets=np.zeros(n_emit + 1, np.int64),
              keep_offsets=np.zeros(n_emit + 1, np.int64), occupancy=np.zeros(max(n_emit, 1), np.int64))
     if grouping:
-        t.update(grouped_slots=torch.empty(max(N, 1), **i32), grouped_lookups=torch.empty(max(N, 1), **i32),
-                 item_starts=torch.empty(max(N, 1), **i32), split_starts=torch.empty(N // 32 + 2, **i32))
-        h.update(item_offsets=np.zeros(n_emit + 1, np.int64), split_offsets=np.zeros(n_emit + 1, np.int64))
+        t.update(grouped_lookups=torch.empty(max(N, 1), **i32), row_recs=torch.empty((cap, 4), **i32),
+                 piece_recs=torch.empty((piece_capacity(N), 8), **i32))
+        h.update(piece_offsets=np.zeros(n_emit + 1, np.int64))
     p = _bp_plan()
     for k, v in t.items():
         setattr(p, k, v.data_ptr())
@@ -330,12 +337,10 @@ def bp_oracle_plan_chunk(cfg: bp_config, ids, iter_offsets, n_emit: int, state: 
                 evict_slots=t["evict_slots"], keep_ids=t["keep_ids"], keep_ttl=t["keep_ttl"],
                 prefetch_offsets=h["prefetch_offsets"], evict_offsets=h["evict_offsets"],
                 keep_offsets=h["keep_offsets"], occupancy=h["occupancy"][:n_emit],
-                grouped_slots=t["grouped_slots"][:N] if grouping else None,
                 grouped_lookups=t["grouped_lookups"][:N] if grouping else None,
-                item_starts=t["item_starts"] if grouping else None,
-                item_offsets=h["item_offsets"] if grouping else None,
-                split_starts=t["split_starts"] if grouping else None,
-                split_offsets=h["split_offsets"] if grouping else None)
+                row_recs=t["row_recs"] if grouping else None,
+                piece_recs=t["piece_recs"] if grouping else None,
+                piece_offsets=h["piece_offsets"] if grouping else None)
     return plan, out
 
 
@@ -479,11 +484,13 @@ def bp_embbag_bwd_update_workspace_bytes(cfg: bp_config, n_lookups: int, bags: i
 
 
 def bp_embbag_bwd_update(cfg: bp_config, cache_w, cache_state, lookup_slots, bag_offsets, bags: int, grad_out,
-                         workspace, stream=None) -> None:
+                         workspace, tickets, stream=None) -> None:
+    """tickets: see bwd_tickets()."""
     n = int(lookup_slots.numel())
+    assert tickets.numel() * tickets.element_size() >= bp_embbag_bwd_ticket_bytes(n)
     _check(load_library().bp_embbag_bwd_update(ctypes.byref(cfg), _ptr(cache_w), _ptr(cache_state),
                                                _ptr(lookup_slots), _ptr(bag_offsets), n, int(bags), _ptr(grad_out),
-                                               _ptr(workspace), int(workspace.numel()), _stream(stream)))
+                                               _ptr(workspace), int(workspace.numel()), _ptr(tickets), _stream(stream)))
 
 
 def bp_embbag_bwd_update_grouped_workspace_bytes(cfg: bp_config, n_lookups: int, bags: int, multi_hot: bool) -> int:
@@ -493,16 +500,29 @@ def bp_embbag_bwd_update_grouped_workspace_bytes(cfg: bp_config, n_lookups: int,
     return int(out.value)
 
 
-def bp_embbag_bwd_update_grouped(cfg: bp_config, cache_w, cache_state, grouped_slots, grouped_lookups, item_starts,
-                                 split_starts, bag_offsets, bags: int, grad_out, workspace, stream=None) -> None:
-    """grouped_slots / grouped_lookups / item_starts / split_starts: one batch's slices of the plan's grouping
-    arrays (split_starts may be None or empty)."""
-    n = int(grouped_slots.numel())
-    n_split = 0 if split_starts is None else int(split_starts.numel())
+def bp_embbag_bwd_ticket_bytes(n_lookups: int) -> int:
+    return int(load_library().bp_embbag_bwd_ticket_bytes(int(n_lookups)))
+
+
+def bwd_tickets(max_lookups: int, device="cuda"):
+    """The counters of the backward entry points for batches of up to max_lookups lookups: they must be zero when a
+    call starts and every call leaves them zero, so they are allocated zeroed, once."""
+    import torch
+    return torch.zeros(bp_embbag_bwd_ticket_bytes(max_lookups) // 4, dtype=torch.int32, device=device)
+
+
+def bp_embbag_bwd_update_grouped(cfg: bp_config, cache_w, cache_state, grouped_lookups, row_recs, piece_recs,
+                                 bag_offsets, bags: int, grad_out, workspace, tickets, stream=None) -> None:
+    """grouped_lookups / row_recs / piece_recs: one batch's slices of the plan's grouping arrays (piece_recs may be
+    None or empty).  tickets: see bwd_tickets()."""
+    n = int(grouped_lookups.numel())
+    n_pieces = 0 if piece_recs is None else int(piece_recs.shape[0])
+    assert tickets.numel() * tickets.element_size() >= bp_embbag_bwd_ticket_bytes(n)
     _check(load_library().bp_embbag_bwd_update_grouped(
-        ctypes.byref(cfg), _ptr(cache_w), _ptr(cache_state), _ptr(grouped_slots), _ptr(grouped_lookups),
-        _ptr(item_starts), int(item_starts.numel()), _ptr(split_starts) if n_split else None, n_split,
-        _ptr(bag_offsets), n, int(bags), _ptr(grad_out), _ptr(workspace), int(workspace.numel()), _stream(stream)))
+        ctypes.byref(cfg), _ptr(cache_w), _ptr(cache_state), _ptr(grouped_lookups), _ptr(row_recs),
+        int(row_recs.shape[0]), _ptr(piece_recs) if n_pieces else None, n_pieces,
+        _ptr(bag_offsets), n, int(bags), _ptr(grad_out), _ptr(workspace), int(workspace.numel()), _ptr(tickets),
+        _stream(stream)))
 
 
 # ---------------------------------------------------------------------------------------------------

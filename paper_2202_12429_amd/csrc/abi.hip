@@ -74,7 +74,7 @@ const char* const kKernelNames[K_NUM_KERNELS] = {
     "sort_upsweep", "sort_scan", "sort_downsweep", "scan_reduce", "scan_spine", "scan_apply",
     "plan_keys", "plan_pairs", "plan_hist", "plan_occupancy", "plan_flags", "plan_lists", "plan_ring_jump",
     "plan_slots", "plan_group", "cache_evict", "cache_prefetch", "cache_stage", "cache_duplex", "embbag_fwd", "bwd_keys", "bwd_items", "bwd_reduce_update",
-    "bwd_combine_update", "fill", "copy_calibration"};
+    "fill", "copy_calibration"};
 }  // namespace
 
 bool profile_events(int id, hipEvent_t* start, hipEvent_t* stop) {

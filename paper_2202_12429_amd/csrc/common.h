@@ -19,10 +19,6 @@ namespace bp {
 
 constexpr int kWave = 64;   // gfx950 wavefront
 
-// Lookups per work item of the backward pass at most (BP_BWD_CHUNK of the C header): the planner's optional
-// grouping and the backward kernels must cut the sorted lookups at the same places.
-constexpr int kBwdChunk = BP_BWD_CHUNK;
-
 // ---- error reporting ---------------------------------------------------------------------------
 void set_error(const char* fmt, ...) __attribute__((format(printf, 1, 2)));
 int fail(int status, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
@@ -111,7 +107,6 @@ enum KernelId {
     K_BWD_KEYS,
     K_BWD_ITEMS,
     K_BWD_REDUCE_UPDATE,
-    K_BWD_COMBINE_UPDATE,
     K_FILL,
     K_COPY,
     K_NUM_KERNELS

@@ -3,19 +3,20 @@
 // Gradients, not embeddings, are combined (Section 6), so any per-row optimizer can follow; the update
 // rules are SGD, element-wise Adagrad and row-wise Adagrad.
 //
-//   1. keys = slot of every lookup, payload = its bag; stable LSD radix sort on the slot bits, so the
-//      lookups of a slot end up adjacent and in lookup order.
-//   2. the sorted array is cut into work items: a new item starts at every change of slot and at every
-//      multiple of kChunk positions (so a slot hit thousands of times by a skewed batch is shared by
-//      many lane groups); item starts are compacted with a scan.
-//   3. one lane group per item adds its gradient rows in order (fp64 accumulators).  An item that covers its whole
-//      slot applies the update at once; so does the first item of a slot that crosses a single cut (it carries on
-//      to the slot's end and the second item steps aside); otherwise the sum goes to a partial row addressed by
-//      the chunk boundary it touches.
-//   4. for slots split over several items, one wavefront adds the partial rows (lane groups round-robin,
-//      then a butterfly across the groups) and applies the update.
-// Every order of addition is fixed by the data, never by timing: results are bit-identical run to run.
+// The work of a batch is described by two lists of records (the planner emits them with its optional grouping;
+// bp_embbag_bwd_update builds them itself after a stable sort of the lookups by slot):
+//   row records    one per distinct row: where its lookups start in the grouped order, how many they are, its
+//                  slot, its first lookup.  A row of up to BP_BWD_ROW_MAX lookups is summed (fp64) and updated by
+//                  one lane group, which needs nothing but its record to ask for the cache row and the first
+//                  gradient row.
+//   piece records  a row with more lookups is cut into pieces of BP_BWD_PIECE lookups; one workgroup takes a piece,
+//                  its lane groups add their shares and meet in LDS.  A one-piece row is updated at once.  For a
+//                  row of several pieces the workgroup stores the piece's sum, and the one that finds, by a counter,
+//                  that all the others have stored theirs adds the sums in piece order and updates the row.
+// ONE launch does all of it: workgroups [0, piece_blocks) take pieces, the rest take rows.
+// Every order of addition is fixed by the records, never by timing: results are bit-identical run to run.
 // The summed gradient is rounded to fp32 once; the optimizer step itself is fp32 arithmetic.
+#include "bwd_records.h"
 #include "common.h"
 #include "device_prims.h"
 #include "row_access.h"
@@ -23,7 +24,6 @@
 namespace bp {
 namespace {
 
-constexpr int kChunk = kBwdChunk;  // sorted positions per work item at most
 constexpr int kMaxGridBlocks = 8192;
 
 // ---- 1. keys ---------------------------------------------------------------------------------
@@ -69,26 +69,6 @@ __global__ __launch_bounds__(256) void bwd_bags_of_positions_kernel(const int32_
     bag_of[p] = b < (uint64_t)bags ? b : 0u;      // offsets that do not cover every lookup leave holes in the map
 }
 
-// ---- 2. work items ---------------------------------------------------------------------------
-struct ItemStartIn {
-    const uint32_t* keys;
-    __device__ __forceinline__ uint32_t operator()(int64_t p) const {
-        return (p == 0 || (p % kChunk) == 0 || keys[p] != keys[p - 1]) ? 1u : 0u;
-    }
-};
-// An item record is the position of the item's first sorted lookup, with bit 31 set when that lookup is the first
-// of its slot.  Everything else a kernel needs to know about an item follows from its neighbours' records: the item
-// ends where the next one starts, and it is the last of its slot iff the next item is a first.
-constexpr uint32_t kItemHead = 0x80000000u, kItemPos = 0x7fffffffu;
-
-struct ItemStartOut {
-    const uint32_t* keys;
-    uint32_t* item_start;
-    __device__ __forceinline__ void operator()(int64_t p, uint32_t exc, uint32_t inc) const {
-        if (inc != exc) item_start[exc] = (uint32_t)p | ((p == 0 || keys[p] != keys[p - 1]) ? kItemHead : 0u);
-    }
-};
-
 // ---- 3./4. reduce and update -----------------------------------------------------------------
 struct UpdateParams {
     int optimizer;
@@ -130,6 +110,21 @@ struct SumPiece {
         double2* p = reinterpret_cast<double2*>(row + (size_t)c * N);
 #pragma unroll
         for (int i = 0; i < N / 2; ++i) p[i] = make_double2(v[2 * i], v[2 * i + 1]);
+    }
+    // The same through device-coherent accesses: written through to memory and read from it, past the caches that
+    // the GPU's dies do not share, so that a sum stored by one workgroup can be read by any other without either of
+    // them writing back or dropping everything else its cache holds (what a device-wide fence would cost).
+    __device__ __forceinline__ void store_device(double* row, int c) const {
+        uint64_t* p = reinterpret_cast<uint64_t*>(row + (size_t)c * N);
+#pragma unroll
+        for (int i = 0; i < N; ++i)
+            __hip_atomic_store(p + i, (uint64_t)__double_as_longlong(v[i]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __device__ __forceinline__ void load_device(const double* row, int c) {
+        const uint64_t* p = reinterpret_cast<const uint64_t*>(row + (size_t)c * N);
+#pragma unroll
+        for (int i = 0; i < N; ++i)
+            v[i] = __longlong_as_double((long long)__hip_atomic_load(p + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
     }
     template <bool BF16>
     __device__ __forceinline__ Piece<BF16> rounded() const {
@@ -217,202 +212,199 @@ __device__ __forceinline__ void finish_update(const UpdateParams& u, uint4* cach
     if (active) cache_w[slot * u.lpr + c] = w.encode();
 }
 
-template <int GW, bool BF16>
-__device__ __forceinline__ void apply_update(const UpdateParams& u, uint4* cache_w, float* cache_s, int64_t slot, int c,
-                                             const Piece<BF16>& g, bool writer = true) {
-    const bool active = c < u.lpr && writer;
-    const RowPiece<BF16> r = load_row<BF16>(u, cache_w, cache_s, slot, c, active);
-    finish_update<GW, BF16>(u, cache_w, cache_s, slot, c, r, g, active);
-}
-
-// One lane group per work item.  Loads are issued as early as their addresses are known: the item's records
-// together, then its slot and the first gradient indices together, then the cache row and the gradient rows.
-template <int GW, bool BF16>
-__global__ __launch_bounds__(kRowBlock) void bwd_reduce_update_kernel(const uint32_t* __restrict__ keys,
-                                                                     const uint32_t* __restrict__ bag_of,
-                                                                     const uint32_t* __restrict__ item_start,
-                                                                     const uint32_t* __restrict__ n_items_ptr,
-                                                                     uint32_t n_items_host, uint32_t n, int64_t C,
-                                                                     const float* __restrict__ grad,
-                                                                     uint4* cache_w, float* cache_s, double* partial,
-                                                                     UpdateParams u) {
-    constexpr int N = Piece<BF16>::N;
-    const uint32_t W = n_items_ptr ? *n_items_ptr : n_items_host;   // counted on the device, or known to the host
-    const int c = threadIdx.x % GW;
-    const bool active = c < u.lpr;
-    const uint32_t groups = gridDim.x * (kRowBlock / GW);
-    for (uint32_t w = (blockIdx.x * kRowBlock + threadIdx.x) / GW; w < W; w += groups) {
-        const uint32_t rp = item_start[w > 0 ? w - 1 : 0];
-        const uint32_t r0 = item_start[w];
-        const uint32_t r1 = w + 1 < W ? item_start[w + 1] : (n | kItemHead);
-        const uint32_t r2 = w + 2 < W ? item_start[w + 2] : (n | kItemHead);
-        const uint32_t start = r0 & kItemPos, end = r1 & kItemPos;
-        const bool head = (r0 & kItemHead) != 0, tail = (r1 & kItemHead) != 0;
-        // A row that crosses exactly one cut (it starts in one chunk and ends in the next) is finished by its first
-        // item alone: that item carries on to the row's end, the second item steps aside.  Only rows that cross two
-        // cuts or more go through partial sums.
-        const bool takes_next = head && !tail && (r2 & kItemHead);     // the row's second item is its last
-        const bool steps_aside = !head && tail && (rp & kItemHead);    // second of two: the first item does it all
-        const uint32_t last = takes_next ? (r2 & kItemPos) : end;
-        const bool whole = (head && tail) || takes_next;
-        if (start >= n || last > n || last < start) continue;           // a malformed record reads nothing
-        const uint32_t slot = keys[start];
-        uint32_t idx[4];
+// Adds the gradient rows of the grouped lookups [p0, p1) into acc: bursts of four rows, the indices of the next
+// burst loaded while the rows of this one arrive.  idx holds the bag numbers of the first four lookups.
+template <bool BF16, int N>
+__device__ __forceinline__ void add_gradient_rows(SumPiece<N>& acc, uint32_t (&idx)[4], uint32_t p0, uint32_t p1,
+                                                  const uint32_t* __restrict__ bag_of, const float* __restrict__ grad,
+                                                  const UpdateParams& u, int c) {
+    for (uint32_t p = p0; p < p1; p += 4) {
+        Piece<BF16> t[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) idx[j] = start + j < last ? bag_of[start + j] : 0u;
-        if (steps_aside || (int64_t)slot >= C) continue;               // slot C: sentinel of out-of-range slots
-        RowPiece<BF16> row;
-        if (whole) row = load_row<BF16>(u, cache_w, cache_s, (int64_t)slot, c, active);
-        SumPiece<N> acc;
-        acc.zero();
-        if (active) {
-            // bursts of four rows; the indices of the next burst are loaded while the rows of this one arrive
-            for (uint32_t p = start; p < last; p += 4) {
-                Piece<BF16> t[4];
+        for (int j = 0; j < 4; ++j)     // the bag number is clamped where it is used: its load stays in flight until then
+            if (p + j < p1) t[j].load_f32(grad + (size_t)min(idx[j], u.bags - 1u) * u.dim, c);
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (p + j < last) t[j].load_f32(grad + (size_t)min(idx[j], u.bags - 1u) * u.dim, c);   // clamped where it is used: the index load stays in flight until then
+        for (int j = 0; j < 4; ++j) idx[j] = p + 4 + j < p1 ? bag_of[p + 4 + j] : 0u;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) idx[j] = p + 4 + j < last ? bag_of[p + 4 + j] : 0u;
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (p + j < last) acc.add(t[j]);
-            }
-        }
-        if (whole) {
-            finish_update<GW, BF16>(u, cache_w, cache_s, (int64_t)slot, c, row, acc.template rounded<BF16>(), active);
-        } else if (active) {
-            // head item of a split slot ends on a chunk boundary b*kChunk: row 2b; a later item starts on
-            // boundary b*kChunk: row 2b+1
-            const size_t prow = head ? 2 * (size_t)(end / kChunk) : 2 * (size_t)(start / kChunk) + 1;
-            acc.store(partial + prow * u.dim, c);
-        }
+        for (int j = 0; j < 4; ++j)
+            if (p + j < p1) acc.add(t[j]);
     }
 }
 
-// Split slots: one wavefront per slot.  Its 64/GW lane groups take the slot's partial rows round-robin
-// (row 2b of the head item goes to group 0, row 2b'+1 of the item starting at boundary b' to group
-// (b' - b) mod groups), each adds its share in order with four loads in flight, and the group sums are added
-// across the wavefront by a butterfly whose order is fixed by the lane numbers.  Every group then holds the
-// slot's gradient; group 0 writes the update.
-template <int GW, bool BF16>
-__global__ __launch_bounds__(kRowBlock) void bwd_combine_update_kernel(const uint32_t* __restrict__ keys,
-                                                                      const uint32_t* __restrict__ item_start,
-                                                                      const uint32_t* __restrict__ n_items_ptr,
-                                                                      uint32_t n_items_host, uint32_t n, int64_t C,
-                                                                      uint4* cache_w, float* cache_s,
-                                                                      const double* __restrict__ partial, UpdateParams u) {
-    constexpr int N = Piece<BF16>::N;
-    constexpr int G = kWave / GW;                     // lane groups per wavefront
-    const uint32_t W = n_items_ptr ? *n_items_ptr : n_items_host;   // counted on the device, or known to the host
-    const int lane = threadIdx.x % kWave;
-    const int c = lane % GW, j = lane / GW;
-    const bool active = c < u.lpr;
-    const uint32_t waves = gridDim.x * (kRowBlock / kWave);
-    for (uint32_t w = (blockIdx.x * kRowBlock + threadIdx.x) / kWave; w < W; w += waves) {
-        const uint32_t r0 = item_start[w];
-        const uint32_t r1 = w + 1 < W ? item_start[w + 1] : (n | kItemHead);
-        if (!(r0 & kItemHead) || (r1 & kItemHead)) continue;   // only the first item of a split slot works here
-        const uint32_t r2 = w + 2 < W ? item_start[w + 2] : (n | kItemHead);
-        if (r2 & kItemHead) continue;                           // crosses one cut only: done by the reduce kernel
-        const uint32_t start = r0 & kItemPos, end = r1 & kItemPos;
-        const uint32_t slot = keys[start];
-        if ((int64_t)slot >= C) continue;
-        SumPiece<N> acc;
-        acc.zero();
-        const uint32_t b0 = end / kChunk;             // end is a chunk boundary because the slot goes on
-        if (active && j == 0) acc.load(partial + 2 * (size_t)b0 * u.dim, c);
-        // the item starting at boundary b belongs to this slot iff b*kChunk < n and keys[b*kChunk] == slot
-        for (uint64_t b = (uint64_t)b0 + j;; b += 4 * G) {
-            bool ok[4];
-            SumPiece<N> t[4];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const uint64_t bb = b + (uint64_t)k * G;
-                // the key test and the partial row are loaded side by side (row 2bb+1 exists whenever
-                // bb*kChunk < n; a row that turns out not to belong to the slot is dropped): one latency per round
-                const bool inb = bb * kChunk < n;
-                const uint32_t key = inb ? keys[bb * kChunk] : ~0u;
-                t[k].zero();
-                if (inb && active) t[k].load(partial + (2 * bb + 1) * u.dim, c);
-                ok[k] = inb && key == slot;
-            }
-#pragma unroll
-            for (int k = 0; k < 4; ++k)
-                if (ok[k]) acc.add(t[k]);
-            if (!ok[3]) break;                        // the slot's boundaries are consecutive
-        }
-#pragma unroll
-        for (int off = GW; off < kWave; off <<= 1) {
-#pragma unroll
-            for (int i = 0; i < N; ++i) acc.v[i] += __shfl_xor(acc.v[i], off, kWave);
-        }
-        apply_update<GW, BF16>(u, cache_w, cache_s, (int64_t)slot, c, acc.template rounded<BF16>(), j == 0);
-    }
-}
-
-// Split rows when the plan lists them: one workgroup per split row.  Its 256/GW lane groups take the row's partial
-// sums round-robin as above; the group sums meet in LDS and every group adds them in group order, so all hold the
-// row's gradient and group 0 writes the update.  No idle wavefronts: the grid is the list.
-template <int GW, bool BF16>
-__global__ __launch_bounds__(kRowBlock) void bwd_combine_split_kernel(const uint32_t* __restrict__ keys,
-                                                                     const uint32_t* __restrict__ split_starts, uint32_t n,
-                                                                     int64_t C, uint4* cache_w, float* cache_s,
-                                                                     const double* __restrict__ partial, UpdateParams u) {
-    constexpr int N = Piece<BF16>::N;
-    constexpr int G = kRowBlock / GW;                 // lane groups per workgroup
-    constexpr int U = G >= 64 ? 1 : (G >= 32 ? 2 : 4);  // partial rows in flight per group: about 64 per round
-    __shared__ double red[G][N][GW];
-    const int c = threadIdx.x % GW, j = threadIdx.x / GW;
-    const bool active = c < u.lpr;
-    const uint32_t start = split_starts[blockIdx.x];
-    if (start >= n) return;
-    const uint32_t slot = keys[start];
-    if ((int64_t)slot >= C) return;
-    const uint32_t b0 = start / kChunk + 1;           // the row's first item ends at the next cut after `start`
-    // the row itself is asked for now, so that it arrives while the partial sums are added up
-    const bool writer = active && j == 0;
-    const RowPiece<BF16> row = load_row<BF16>(u, cache_w, cache_s, (int64_t)slot, c, writer);
-    SumPiece<N> acc;
-    acc.zero();
-    if (active && j == 0) acc.load(partial + 2 * (size_t)b0 * u.dim, c);
-    for (uint64_t b = (uint64_t)b0 + j;; b += U * G) {
-        bool ok[U];
-        SumPiece<N> t[U];
-#pragma unroll
-        for (int k = 0; k < U; ++k) {
-            const uint64_t bb = b + (uint64_t)k * G;
-            // the key test and the partial row are loaded side by side (row 2bb+1 exists whenever
-            // bb*kChunk < n; a row that turns out not to belong to the slot is dropped): one latency per round
-            const bool inb = bb * kChunk < n;
-            const uint32_t key = inb ? keys[bb * kChunk] : ~0u;
-            t[k].zero();
-            if (inb && active) t[k].load(partial + (2 * bb + 1) * u.dim, c);
-            ok[k] = inb && key == slot;
-        }
-#pragma unroll
-        for (int k = 0; k < U; ++k)
-            if (ok[k]) acc.add(t[k]);
-        if (!ok[U - 1]) break;
-    }
+// Sum over the lane groups of a workgroup, in group order: every group leaves its sum in LDS, group 0 adds them up.
+// Two barriers; `red` may be reused after the call.
+template <int G, int GW, int N>
+__device__ __forceinline__ void workgroup_sum(SumPiece<N>& acc, double (*red)[N][GW], int j, int c) {
 #pragma unroll
     for (int i = 0; i < N; ++i) red[j][i][c] = acc.v[i];
     __syncthreads();
-    acc.zero();
-    for (int g = 0; g < G; ++g) {
+    if (j == 0) {
+        acc.zero();
+        for (int g = 0; g < G; ++g) {
 #pragma unroll
-        for (int i = 0; i < N; ++i) acc.v[i] += red[g][i][c];
+            for (int i = 0; i < N; ++i) acc.v[i] += red[g][i][c];
+        }
     }
-    finish_update<GW, BF16>(u, cache_w, cache_s, (int64_t)slot, c, row, acc.template rounded<BF16>(), writer);
+    __syncthreads();
 }
+
+// counts: the numbers of row and piece records when they were made on the device (bp_embbag_bwd_update), else NULL
+// and the host's numbers hold.  use_first: a row record's `first` is the bag of its first lookup (one lookup per bag,
+// or records made from sorted bag numbers); otherwise every bag number comes from bag_of.
+template <int GW, bool BF16>
+__global__ __launch_bounds__(kRowBlock, BF16 ? 4 : 8) void bwd_rows_kernel(const uint4* __restrict__ row_recs,
+                                                            const uint4* __restrict__ piece_recs,
+                                                            const uint32_t* __restrict__ n_rows_ptr,
+                                                            const uint32_t* __restrict__ n_pieces_ptr,
+                                                            uint32_t n_rows_host, uint32_t n_pieces_host,
+                                                            uint32_t piece_blocks, const uint32_t* __restrict__ bag_of,
+                                                            int use_first, uint32_t n, int64_t C,
+                                                            const float* __restrict__ grad, uint4* cache_w, float* cache_s,
+                                                            double* partial, uint32_t partial_rows, uint32_t* tickets,
+                                                            UpdateParams u) {
+    constexpr int N = Piece<BF16>::N;
+    constexpr int G = kRowBlock / GW;                 // lane groups per workgroup
+    const int c = threadIdx.x % GW, j = threadIdx.x / GW;
+    const bool active = c < u.lpr;
+
+    if (blockIdx.x >= piece_blocks) {
+        // ---- rows of up to kRowMax lookups: one lane group each
+        const uint32_t R = n_rows_ptr ? *n_rows_ptr : n_rows_host;
+        const uint32_t groups = (gridDim.x - piece_blocks) * G;
+        for (uint32_t w = (blockIdx.x - piece_blocks) * G + j; w < R; w += groups) {
+            const uint4 rec = row_recs[w];
+            const uint32_t start = rec.x & kPosMask, count = rec.y, slot = rec.z;
+            if ((rec.x & kLongRow) || (int64_t)slot >= C || count == 0 || start >= n || count > n - start) continue;
+            const RowPiece<BF16> row = load_row<BF16>(u, cache_w, cache_s, (int64_t)slot, c, active);
+            uint32_t idx[4];
+            idx[0] = use_first ? rec.w : bag_of[start];
+#pragma unroll
+            for (int k = 1; k < 4; ++k) idx[k] = (uint32_t)k < count ? bag_of[start + k] : 0u;
+            SumPiece<N> acc;
+            acc.zero();
+            if (active) add_gradient_rows<BF16, N>(acc, idx, start, start + count, bag_of, grad, u, c);
+            finish_update<GW, BF16>(u, cache_w, cache_s, (int64_t)slot, c, row, acc.template rounded<BF16>(), active);
+        }
+        return;
+    }
+
+    // ---- pieces of longer rows: one workgroup each
+    __shared__ double red[G][N][GW];
+    __shared__ uint32_t s_last;
+    const uint32_t P = n_pieces_ptr ? *n_pieces_ptr : n_pieces_host;
+    const bool writer = active && j == 0;
+    for (uint32_t pi = blockIdx.x; pi < P; pi += piece_blocks) {
+        const uint4 r0 = piece_recs[2 * (size_t)pi], r1 = piece_recs[2 * (size_t)pi + 1];
+        const uint32_t start = r0.x, count = r0.y, slot = r0.z, index = r0.w, pieces = r1.x, pbase = r1.y;
+        // a record that points outside the batch or the workspace does nothing (the test is the same in every lane)
+        if ((int64_t)slot >= C || count == 0 || start >= n || count > n - start || pieces == 0 || index >= pieces) continue;
+        const bool direct = pieces == 1;
+        if (!direct && (pbase >= partial_rows || pieces > partial_rows - pbase)) continue;
+        // lane group j takes the j-th stretch of the piece
+        const uint32_t per = (count + G - 1) / G;
+        const uint32_t p0 = start + min((uint32_t)j * per, count), p1 = start + min((uint32_t)(j + 1) * per, count);
+        uint32_t idx[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) idx[k] = p0 + k < p1 ? bag_of[p0 + k] : 0u;
+        SumPiece<N> acc;
+        acc.zero();
+        if (active) add_gradient_rows<BF16, N>(acc, idx, p0, p1, bag_of, grad, u, c);
+        workgroup_sum<G, GW, N>(acc, red, j, c);
+        if (direct) {      // the row is asked for only now: one more round trip after a few hundred gradient rows
+            if (j == 0) {
+                const RowPiece<BF16> row = load_row<BF16>(u, cache_w, cache_s, (int64_t)slot, c, writer);
+                finish_update<GW, BF16>(u, cache_w, cache_s, (int64_t)slot, c, row, acc.template rounded<BF16>(), writer);
+            }
+            continue;
+        }
+        // one of several pieces: leave the sum where the last workgroup of the row will find it, then take a ticket
+        // (device-coherent stores, complete before the barrier lets thread 0 count this piece; the workgroup that
+        // counts the last piece then reads all the sums with device-coherent loads)
+        if (writer) acc.store_device(partial + (size_t)(pbase + index) * u.dim, c);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __syncthreads();
+        if (threadIdx.x == 0)
+            s_last = __hip_atomic_fetch_add(&tickets[pbase], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u == pieces ? 1u : 0u;
+        __syncthreads();
+        const bool last = s_last != 0u;
+        __syncthreads();                               // everybody has read s_last before a later piece rewrites it
+        if (!last) continue;
+        acc.zero();
+        for (uint32_t b = (uint32_t)j; b < pieces; b += 2 * G) {      // lane groups take the pieces round-robin
+            SumPiece<N> t[2];
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                t[k].zero();
+                if (active && b + (uint32_t)k * G < pieces) t[k].load_device(partial + (size_t)(pbase + b + k * G) * u.dim, c);
+            }
+#pragma unroll
+            for (int k = 0; k < 2; ++k) acc.add(t[k]);
+        }
+        workgroup_sum<G, GW, N>(acc, red, j, c);
+        if (j == 0) {
+            const RowPiece<BF16> row = load_row<BF16>(u, cache_w, cache_s, (int64_t)slot, c, writer);
+            finish_update<GW, BF16>(u, cache_w, cache_s, (int64_t)slot, c, row, acc.template rounded<BF16>(), writer);
+        }
+        if (threadIdx.x == 0)                          // the counter is zero again for the next call
+            __hip_atomic_store(&tickets[pbase], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+// ---- records made on the device (bp_embbag_bwd_update: one batch, lookups sorted by slot) -------------------------
+// First scan, over the sorted lookups: a row starts where the slot changes; row r's first sorted position goes to
+// row_pos[r].
+struct RowHeadIn {
+    const uint32_t* keys;
+    __device__ __forceinline__ uint32_t operator()(int64_t p) const { return (p == 0 || keys[p] != keys[p - 1]) ? 1u : 0u; }
+};
+struct RowHeadOut {
+    uint32_t* row_pos;
+    __device__ __forceinline__ void operator()(int64_t p, uint32_t exc, uint32_t inc) const {
+        if (inc != exc) row_pos[exc] = (uint32_t)p;
+    }
+};
+// Second scan, over the rows (RowPiecesIn): every row writes its record, a long row its piece records.
+struct RowRecordOut {
+    const uint32_t* row_pos;
+    const uint32_t* n_rows;
+    uint32_t n;
+    const uint32_t* keys;      // sorted slots
+    const uint32_t* bags;      // bag of every sorted lookup
+    uint4* row_recs;
+    uint4* piece_recs;
+    __device__ __forceinline__ void operator()(int64_t r, uint64_t exc, uint64_t inc) const {
+        const uint32_t R = *n_rows;
+        if (r >= (int64_t)R) return;
+        const uint32_t start = row_pos[r];
+        const uint32_t count = (r + 1 < (int64_t)R ? row_pos[r + 1] : n) - start;
+        const uint32_t slot = keys[start];
+        const uint32_t pc = pieces_of(count);
+        row_recs[r] = make_uint4(start | (pc ? kLongRow : 0u), count, slot, bags[start]);
+        if (pc) write_pieces(piece_recs, (uint32_t)exc, pc, start, count, slot, (uint32_t)(exc >> 32), 0u);
+    }
+};
 
 // ---- workspace -------------------------------------------------------------------------------
 constexpr int kSmallIPT = 4, kLargeIPT = 16;
 constexpr int64_t kLargeSort = int64_t(1) << 21;
 
-struct BwdWorkspace {
-    uint32_t *keys_a, *keys_b, *vals_a, *vals_b, *sort_temp, *item_start, *scan_partials;
+struct ReduceScratch {      // what the reduce kernel itself needs, in both entry points
+    uint32_t* tickets;      // the caller's counters, one per partial row, zero between calls
     double* partial;
+    uint32_t partial_rows;
+};
+ReduceScratch carve_reduce(Carver& c, int64_t n, int dim) {
+    ReduceScratch r{};
+    r.partial_rows = (uint32_t)partial_rows_for(n);
+    r.partial = c.take<double>((size_t)r.partial_rows * (size_t)dim);
+    return r;
+}
+
+struct BwdWorkspace {
+    ReduceScratch red;
+    uint32_t *keys_a, *keys_b, *vals_a, *vals_b, *sort_temp, *row_pos, *scan_partials32;
+    uint64_t* scan_partials64;
+    uint4 *row_recs, *piece_recs;
     size_t bytes;
 };
 
@@ -420,26 +412,29 @@ BwdWorkspace carve_bwd(void* base, size_t cap, int64_t n, int dim) {
     Carver c(base, cap);
     BwdWorkspace w{};
     const size_t m = (size_t)(n > 0 ? n : 1);
+    w.red = carve_reduce(c, n, dim);
     w.keys_a = c.take<uint32_t>(m);
     w.keys_b = c.take<uint32_t>(m);
     w.vals_a = c.take<uint32_t>(m);
     w.vals_b = c.take<uint32_t>(m);
     w.sort_temp = c.take<uint32_t>(n >= kLargeSort ? sort_temp_words<kLargeIPT>(n) : sort_temp_words<kSmallIPT>(n));
-    w.item_start = c.take<uint32_t>(m + 1);
-    w.scan_partials = c.take<uint32_t>(scan_partials(n));
-    w.partial = c.take<double>((2 * (m / kChunk + 2)) * (size_t)dim);
+    w.row_pos = c.take<uint32_t>(m);
+    w.scan_partials32 = c.take<uint32_t>(scan_partials(n));
+    w.scan_partials64 = c.take<uint64_t>(scan_partials(n));
+    w.row_recs = c.take<uint4>(m);
+    w.piece_recs = c.take<uint4>(2 * piece_capacity_for(n));
     w.bytes = c.used();
     return w;
 }
 
 struct BwdLaunch {
     const bp_config* cfg;
-    double* partial;
-    const uint32_t *skeys, *sbags, *item_start;
-    const uint32_t* n_items;       // device count, or NULL when n_items_host is given
-    uint32_t n_items_host;
-    const uint32_t* split_starts;  // list of split rows (grouped path), or NULL: find them item by item
-    uint32_t n_split;
+    ReduceScratch red;
+    const uint4 *row_recs, *piece_recs;
+    const uint32_t *n_rows_ptr, *n_pieces_ptr;     // device counts, or NULL when the host's numbers hold
+    uint32_t n_rows, n_pieces;                     // host counts, or upper bounds when the device counts
+    const uint32_t* bag_of;
+    int use_first;
     int64_t n;
     const float* grad;
     void* cache_w;
@@ -451,26 +446,14 @@ struct BwdLaunch {
         UpdateParams u{cfg->optimizer, cfg->lr, cfg->eps, (int)(row_bytes(cfg) / 16), cfg->dim,
                        (uint32_t)(bags > 0 ? bags : 1)};
         const int groups_per_block = kRowBlock / GW;
-        const int64_t items_bound = n_items ? n : (int64_t)n_items_host;     // at most one item per lookup
-        int64_t blocks = ceil_div(items_bound, groups_per_block);
-        if (blocks > kMaxGridBlocks) blocks = kMaxGridBlocks;
-        if (blocks < 1) blocks = 1;
-        BP_LAUNCH(K_BWD_REDUCE_UPDATE, (bwd_reduce_update_kernel<GW, BF16>), dim3((unsigned)blocks), dim3(kRowBlock), 0, stream,
-                  skeys, sbags, item_start, n_items, n_items_host, (uint32_t)n, cfg->capacity, grad, (uint4*)cache_w,
-                  (float*)cache_s, partial, u);
-        if (n_items == nullptr) {                                            // grouped path: the plan lists the split rows
-            if (n_split)
-                BP_LAUNCH(K_BWD_COMBINE_UPDATE, (bwd_combine_split_kernel<GW, BF16>), dim3(n_split), dim3(kRowBlock), 0,
-                          stream, skeys, split_starts, (uint32_t)n, cfg->capacity, (uint4*)cache_w, (float*)cache_s,
-                          (const double*)partial, u);
-            return BP_OK;
-        }
-        int64_t cblocks = ceil_div(items_bound, kRowBlock / kWave);          // one wavefront per item
-        if (cblocks < 1) cblocks = 1;
-        if (cblocks > kMaxGridBlocks) cblocks = kMaxGridBlocks;
-        BP_LAUNCH(K_BWD_COMBINE_UPDATE, (bwd_combine_update_kernel<GW, BF16>), dim3((unsigned)cblocks), dim3(kRowBlock), 0,
-                  stream, skeys, item_start, n_items, n_items_host, (uint32_t)n, cfg->capacity, (uint4*)cache_w,
-                  (float*)cache_s, (const double*)partial, u);
+        int64_t piece_blocks = n_pieces, row_blocks = ceil_div((int64_t)n_rows, groups_per_block);
+        if (piece_blocks > kMaxGridBlocks / 4) piece_blocks = kMaxGridBlocks / 4;
+        if (row_blocks > kMaxGridBlocks) row_blocks = kMaxGridBlocks;
+        if (row_blocks < 1) row_blocks = 1;
+        BP_LAUNCH(K_BWD_REDUCE_UPDATE, (bwd_rows_kernel<GW, BF16>), dim3((unsigned)(piece_blocks + row_blocks)),
+                  dim3(kRowBlock), 0, stream, row_recs, piece_recs, n_rows_ptr, n_pieces_ptr, n_rows, n_pieces,
+                  (uint32_t)piece_blocks, bag_of, use_first, (uint32_t)n, cfg->capacity, grad, (uint4*)cache_w,
+                  (float*)cache_s, red.partial, red.partial_rows, red.tickets, u);
         return BP_OK;
     }
 };
@@ -487,6 +470,8 @@ int check_bwd_args(const bp_config* cfg, int64_t n, int64_t bags) {
 
 using namespace bp;
 
+BP_EXPORT size_t bp_embbag_bwd_ticket_bytes(int64_t n_lookups) { return partial_rows_for(n_lookups) * sizeof(uint32_t); }
+
 BP_EXPORT int bp_embbag_bwd_update_workspace_bytes(const bp_config* cfg, int64_t n_lookups, int64_t bags, size_t* bytes) {
     if (!bytes) return fail(BP_ERR_INVALID_ARG, "bytes is NULL");
     BP_TRY(check_bwd_args(cfg, n_lookups, bags));
@@ -496,7 +481,7 @@ BP_EXPORT int bp_embbag_bwd_update_workspace_bytes(const bp_config* cfg, int64_t
 
 BP_EXPORT int bp_embbag_bwd_update(const bp_config* cfg, void* cache_w, void* cache_state, const int32_t* lookup_slots,
                                     const int64_t* bag_offsets, int64_t n_lookups, int64_t bags, const float* grad_out,
-                                    void* workspace, size_t workspace_bytes, void* stream_) {
+                                    void* workspace, size_t workspace_bytes, uint32_t* tickets, void* stream_) {
     hipStream_t stream = (hipStream_t)stream_;
     const int64_t n = n_lookups;
     BP_TRY(check_bwd_args(cfg, n, bags));
@@ -508,9 +493,11 @@ BP_EXPORT int bp_embbag_bwd_update(const bp_config* cfg, void* cache_w, void* ca
     if (((uintptr_t)cache_w | (uintptr_t)cache_state | (uintptr_t)grad_out) & 15)
         return fail(BP_ERR_INVALID_ARG, "cache_w, cache_state and grad_out must be 16-byte aligned");
     if (!workspace || ((uintptr_t)workspace & 255)) return fail(BP_ERR_INVALID_ARG, "workspace NULL or not 256-byte aligned");
+    if (!tickets || ((uintptr_t)tickets & 3)) return fail(BP_ERR_INVALID_ARG, "tickets NULL or not 4-byte aligned");
     BwdWorkspace w = carve_bwd(workspace, workspace_bytes, n, cfg->dim);
     if (w.bytes > workspace_bytes)
         return fail(BP_ERR_WORKSPACE_TOO_SMALL, "workspace %zu < required %zu bytes", workspace_bytes, w.bytes);
+    w.red.tickets = tickets;
 
     BP_LAUNCH(K_BWD_KEYS, bwd_keys_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, stream, lookup_slots, bag_offsets, n,
               bags, cfg->capacity, w.keys_a, w.vals_a);
@@ -525,11 +512,18 @@ BP_EXPORT int bp_embbag_bwd_update(const bp_config* cfg, void* cache_w, void* ca
     const uint32_t* skeys = in_b ? w.keys_b : w.keys_a;
     const uint32_t* sbags = in_b ? w.vals_b : w.vals_a;
 
-    BP_TRY((device_scan<uint32_t, AddOp, ItemStartIn, ItemStartOut>(ItemStartIn{skeys}, ItemStartOut{skeys, w.item_start}, n,
-                                                                    w.scan_partials, AddOp(), 0u, stream)));
-    const uint32_t* n_items = w.scan_partials + scan_num_tiles(n);
+    // rows, then their records; the counts stay on the device
+    BP_TRY((device_scan<uint32_t, AddOp, RowHeadIn, RowHeadOut>(RowHeadIn{skeys}, RowHeadOut{w.row_pos}, n, w.scan_partials32,
+                                                               AddOp(), 0u, stream)));
+    const uint32_t* n_rows = w.scan_partials32 + scan_num_tiles(n);
+    BP_TRY((device_scan<uint64_t, AddOp, RowPiecesIn, RowRecordOut>(
+        RowPiecesIn{w.row_pos, n_rows, (uint32_t)n},
+        RowRecordOut{w.row_pos, n_rows, (uint32_t)n, skeys, sbags, w.row_recs, w.piece_recs}, n, w.scan_partials64, AddOp(),
+        uint64_t(0), stream)));
+    const uint32_t* n_pieces = reinterpret_cast<const uint32_t*>(w.scan_partials64 + scan_num_tiles(n));   // low word
 
-    BwdLaunch l{cfg, w.partial, skeys, sbags, w.item_start, n_items, 0u, nullptr, 0u, n, grad_out, cache_w, cache_state, stream, bags};
+    BwdLaunch l{cfg, w.red, w.row_recs, w.piece_recs, n_rows, n_pieces, (uint32_t)n, (uint32_t)piece_capacity_for(n), sbags,
+                1, n, grad_out, cache_w, cache_state, stream, bags};
     return dispatch_row((int)(row_bytes(cfg) / 16), cfg->weight_dtype == BP_BF16, l);
 }
 
@@ -537,18 +531,18 @@ BP_EXPORT int bp_embbag_bwd_update(const bp_config* cfg, void* cache_w, void* ca
 namespace bp {
 namespace {
 struct GroupedWorkspace {
+    ReduceScratch red;
     uint32_t* bag_of;          // bag of every grouped position
     uint32_t* bag_of_lookup;   // bag of every lookup, in lookup order
-    double* partial;
     size_t bytes;
 };
 GroupedWorkspace carve_grouped(void* base, size_t cap, int64_t n, int dim, bool multi_hot) {
     Carver c(base, cap);
     GroupedWorkspace w{};
     const size_t m = (size_t)(n > 0 ? n : 1);
+    w.red = carve_reduce(c, n, dim);
     w.bag_of = multi_hot ? c.take<uint32_t>(m) : nullptr;
     w.bag_of_lookup = multi_hot ? c.take<uint32_t>(m) : nullptr;
-    w.partial = c.take<double>((2 * (m / kChunk + 2)) * (size_t)dim);
     w.bytes = c.used();
     return w;
 }
@@ -564,28 +558,30 @@ BP_EXPORT int bp_embbag_bwd_update_grouped_workspace_bytes(const bp_config* cfg,
 }
 
 BP_EXPORT int bp_embbag_bwd_update_grouped(const bp_config* cfg, void* cache_w, void* cache_state,
-                                           const int32_t* grouped_slots, const int32_t* grouped_lookups,
-                                           const uint32_t* item_starts, int64_t n_items, const uint32_t* split_starts,
-                                           int64_t n_split, const int64_t* bag_offsets,
+                                           const int32_t* grouped_lookups, const bp_row_rec* row_recs, int64_t n_rows,
+                                           const bp_piece_rec* piece_recs, int64_t n_pieces, const int64_t* bag_offsets,
                                            int64_t n_lookups, int64_t bags, const float* grad_out, void* workspace,
-                                           size_t workspace_bytes, void* stream_) {
+                                           size_t workspace_bytes, uint32_t* tickets, void* stream_) {
     hipStream_t stream = (hipStream_t)stream_;
     const int64_t n = n_lookups;
     BP_TRY(check_bwd_args(cfg, n, bags));
     if (n == 0) return BP_OK;
-    if (n_items < 1 || n_items > n) return fail(BP_ERR_INVALID_ARG, "n_items %lld outside [1, n_lookups]", (long long)n_items);
-    if (n_split < 0 || n_split > n_items || (n_split && !split_starts))
-        return fail(BP_ERR_INVALID_ARG, "n_split %lld outside [0, n_items] or split_starts is NULL", (long long)n_split);
+    if (n_rows < 1 || n_rows > n) return fail(BP_ERR_INVALID_ARG, "n_rows %lld outside [1, n_lookups]", (long long)n_rows);
+    if (n_pieces < 0 || n_pieces > (int64_t)piece_capacity_for(n) || (n_pieces && !piece_recs))
+        return fail(BP_ERR_INVALID_ARG, "n_pieces %lld outside [0, %lld] or piece_recs is NULL", (long long)n_pieces,
+                    (long long)piece_capacity_for(n));
     if (!bag_offsets && n != bags)
         return fail(BP_ERR_INVALID_ARG, "bag_offsets is NULL but n_lookups %lld != bags %lld", (long long)n, (long long)bags);
-    if (!cache_w || !grouped_slots || !grouped_lookups || !item_starts || !grad_out) return fail(BP_ERR_INVALID_ARG, "NULL pointer");
+    if (!cache_w || !grouped_lookups || !row_recs || !grad_out) return fail(BP_ERR_INVALID_ARG, "NULL pointer");
     if (cfg->optimizer != BP_SGD && !cache_state) return fail(BP_ERR_INVALID_ARG, "cache_state is NULL");
-    if (((uintptr_t)cache_w | (uintptr_t)cache_state | (uintptr_t)grad_out) & 15)
-        return fail(BP_ERR_INVALID_ARG, "cache_w, cache_state and grad_out must be 16-byte aligned");
+    if (((uintptr_t)cache_w | (uintptr_t)cache_state | (uintptr_t)grad_out | (uintptr_t)row_recs | (uintptr_t)piece_recs) & 15)
+        return fail(BP_ERR_INVALID_ARG, "cache_w, cache_state, grad_out and the records must be 16-byte aligned");
     if (!workspace || ((uintptr_t)workspace & 255)) return fail(BP_ERR_INVALID_ARG, "workspace NULL or not 256-byte aligned");
+    if (!tickets || ((uintptr_t)tickets & 3)) return fail(BP_ERR_INVALID_ARG, "tickets NULL or not 4-byte aligned");
     GroupedWorkspace w = carve_grouped(workspace, workspace_bytes, n, cfg->dim, bag_offsets != nullptr);
     if (w.bytes > workspace_bytes)
         return fail(BP_ERR_WORKSPACE_TOO_SMALL, "workspace %zu < required %zu bytes", workspace_bytes, w.bytes);
+    w.red.tickets = tickets;
     const uint32_t* bag_of = reinterpret_cast<const uint32_t*>(grouped_lookups);   // one lookup per bag: position == bag
     if (bag_offsets) {
         BP_LAUNCH(K_BWD_KEYS, bwd_bag_of_lookup_kernel, dim3((unsigned)ceil_div(bags > 0 ? bags : 1, 256)), dim3(256), 0,
@@ -594,7 +590,8 @@ BP_EXPORT int bp_embbag_bwd_update_grouped(const bp_config* cfg, void* cache_w, 
                   grouped_lookups, (const uint32_t*)w.bag_of_lookup, n, bags, w.bag_of);
         bag_of = w.bag_of;
     }
-    BwdLaunch l{cfg, w.partial, reinterpret_cast<const uint32_t*>(grouped_slots), bag_of, item_starts, nullptr,
-                (uint32_t)n_items, split_starts, (uint32_t)n_split, n, grad_out, cache_w, cache_state, stream, bags};
+    BwdLaunch l{cfg, w.red, reinterpret_cast<const uint4*>(row_recs), reinterpret_cast<const uint4*>(piece_recs), nullptr,
+                nullptr, (uint32_t)n_rows, (uint32_t)n_pieces, bag_of, bag_offsets == nullptr, n, grad_out, cache_w,
+                cache_state, stream, bags};
     return dispatch_row((int)(row_bytes(cfg) / 16), cfg->weight_dtype == BP_BF16, l);
 }

@@ -26,6 +26,7 @@
 #include <vector>
 
 #include "common.h"
+#include "bwd_records.h"
 #include "device_prims.h"
 
 namespace bp {
@@ -564,85 +565,73 @@ struct GroupWordSource {
     };
 };
 
-// A work item of the grouped backward pass starts where the row changes and at every multiple of kBwdChunk
-// positions counted from the batch's first lookup.  A row is "split" when its lookups go past the next two such
-// multiples, i.e. they span three items or more (a row spanning two items is finished by its first item).
-// Low word: item start flag; high word: first lookup of a split row.
-// The flags need the neighbouring word, the batch's offsets and, for the first lookup of a row, the word two cuts
-// further on.  The scan's first pass derives them and leaves them as bit masks, 64 lookups a word (a round of a
-// wavefront is 64 consecutive lookups starting at a multiple of 64, lane = position % 64, and the lanes past the end
-// are the inactive ones); its last pass reads the masks.
-struct ItemFlagIn {
+// Rows of the grouped order.  First scan, over the grouped lookups: a row starts where (slot, batch) changes; the
+// lookup's place goes to grouped_lookups, row r's first grouped position to row_pos[r].
+struct GroupRowIn {
     const uint64_t* gkeys;
-    BatchOfPos where;
-    GroupWord gw;
+    int pb;
     int64_t first;          // entries below `first` are a chunk's carried residents, not lookups
-    uint64_t* item_mask;
-    uint64_t* split_mask;
-    uint64_t* head_mask;    // first lookup of its row
-    __device__ __forceinline__ uint64_t operator()(int64_t p) const {
-        bool item = false, split = false, head = false;
-        if (p >= first) {
-            const uint64_t k = gkeys[p];
-            const int64_t* iter_off = where.iter_off;
-            const uint32_t i = gw.batch(k);
-            const int64_t base = iter_off[i];
-            const int64_t rel = p - base;
-            const bool first_of_row = rel == 0 || gw.slot(gkeys[p - 1]) != gw.slot(k);      // rel == 0 guards p == 0
-            item = first_of_row || rel % kBwdChunk == 0;
-            head = first_of_row;
-            if (first_of_row) {
-                const int64_t nb2 = base + (rel / kBwdChunk + 2) * kBwdChunk;              // second cut after p
-                split = nb2 < iter_off[i + 1] && gw.slot(gkeys[nb2]) == gw.slot(k);
-            }
-        }
-        const uint64_t mi = __ballot(item), ms = __ballot(split), mh = __ballot(head);
-        if ((p & 63) == 0) {
-            item_mask[p >> 6] = mi;
-            split_mask[p >> 6] = ms;
-            head_mask[p >> 6] = mh;
-        }
-        return (uint64_t)item | ((uint64_t)split << 32);
+    __device__ __forceinline__ uint32_t operator()(int64_t p) const {
+        if (p < first) return 0u;
+        return (p == first || (gkeys[p] >> pb) != (gkeys[p - 1] >> pb)) ? 1u : 0u;
     }
 };
-struct ItemFlagFromMask {
-    const uint64_t* item_mask;
-    const uint64_t* split_mask;
-    __device__ __forceinline__ uint64_t operator()(int64_t p) const {
-        const int bit = (int)(p & 63);
-        return ((item_mask[p >> 6] >> bit) & 1u) | (((split_mask[p >> 6] >> bit) & 1u) << 32);
-    }
-};
-struct GroupOut {
+struct GroupRowOut {
     const uint64_t* gkeys;
-    BatchOfPos where;
     GroupWord gw;
-    int32_t* grouped_slots;
     int32_t* grouped_lookups;
-    uint32_t* item_starts;
-    uint32_t* split_starts;
-    int64_t* item_off;     // device copies of the CSR offsets, [T+1] each, pre-filled with -1
-    int64_t* split_off;
-    int64_t first;         // entries below `first` are a chunk's carried residents: skipped, outputs start at `first`
-    const uint64_t* head_mask;
-    __device__ __forceinline__ void operator()(int64_t p, uint64_t exc, uint64_t inc) const {
+    uint32_t* row_pos;
+    int64_t first;          // outputs start at `first`
+    __device__ __forceinline__ void operator()(int64_t p, uint32_t exc, uint32_t inc) const {
         if (p < first) return;
+        grouped_lookups[p - first] = (int32_t)gw.place(gkeys[p]);
+        if (inc != exc) row_pos[exc] = (uint32_t)p;
+    }
+};
+// Second scan, over the rows (RowPiecesIn counts the pieces): every row writes its record beside its keep-list
+// entry (the carried residents of a chunk own the first `first` entries), a long row its piece records, and the
+// first row of a batch the batch's offsets.  A piece's `partial` is counted through the whole trace here and made
+// relative to its batch afterwards; until then its first reserved word holds the batch.
+struct GroupRecordOut {
+    const uint32_t* row_pos;
+    const uint32_t* n_rows;
+    uint32_t n;
+    const uint64_t* gkeys;
+    GroupWord gw;
+    const int64_t* iter_off;
+    int64_t first;
+    uint4* row_recs;
+    uint4* piece_recs;
+    int64_t* piece_off;    // device copies of the CSR offsets, [T+1] each, pre-filled with -1
+    int64_t* multi_off;
+    __device__ __forceinline__ void operator()(int64_t r, uint64_t exc, uint64_t inc) const {
+        const uint32_t R = *n_rows;
+        if (r >= (int64_t)R) return;
+        const uint32_t p = row_pos[r];
+        const uint32_t count = (r + 1 < (int64_t)R ? row_pos[r + 1] : n) - p;
         const uint64_t k = gkeys[p];
-        grouped_slots[p - first] = (int32_t)gw.slot(k);
-        grouped_lookups[p - first] = (int32_t)gw.place(k);
-        if ((uint32_t)inc != (uint32_t)exc) {            // an item starts here (a batch's first lookup always does)
-            const uint32_t i = gw.batch(k);
-            const int64_t base = where.iter_off[i];
-            const bool first_of_row = (head_mask[p >> 6] >> (p & 63)) & 1u;
-            item_starts[(uint32_t)exc] = (uint32_t)(p - base) | (first_of_row ? 0x80000000u : 0u);
-            if ((inc >> 32) != (exc >> 32)) split_starts[exc >> 32] = (uint32_t)(p - base);   // a split row's first lookup starts an item
-            if (p == base) {
-                item_off[i] = (uint32_t)exc;
-                split_off[i] = (int64_t)(exc >> 32);
-            }
+        const uint32_t b = gw.batch(k), slot = gw.slot(k);
+        const int64_t base = iter_off[b];
+        const uint32_t rel = (uint32_t)((int64_t)p - base);
+        const uint32_t pc = pieces_of(count);
+        row_recs[first + r] = make_uint4(rel | (pc ? kLongRow : 0u), count, slot, gw.place(k));
+        if (pc) write_pieces(piece_recs, (uint32_t)exc, pc, rel, count, slot, (uint32_t)(exc >> 32), b);
+        if ((int64_t)p == base) {
+            piece_off[b] = (int64_t)(uint32_t)exc;
+            multi_off[b] = (int64_t)(exc >> 32);
         }
     }
 };
+__global__ __launch_bounds__(kBlock) void plan_piece_partial_kernel(uint4* __restrict__ piece_recs,
+                                                                    const uint32_t* __restrict__ n_pieces, int T,
+                                                                    const int64_t* __restrict__ multi_off) {
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= (int64_t)*n_pieces) return;
+    uint4 r = piece_recs[2 * i + 1];
+    if (r.z < (uint32_t)T) r.y -= (uint32_t)multi_off[r.z];
+    r.z = 0u;
+    piece_recs[2 * i + 1] = r;
+}
 
 // The per-lookup slot map written from the batch-grouped order: the targets of neighbouring grouped lookups lie in
 // their batch's stretch of the map (a few MB at most).
@@ -726,8 +715,8 @@ struct PlanWorkspace {
     int64_t* cuts;           // trainer cuts of every batch, [T][kMaxTrainers + 1] at most
     int32_t* slot_of_pair;
     uint64_t* keys_c;      // grouping only: the other half of the regrouping sort's ping-pong
-    int64_t* item_off;
-    int64_t* split_off;
+    int64_t* piece_off;
+    int64_t* multi_off;
     size_t bytes;
 };
 
@@ -737,7 +726,7 @@ PlanWorkspace carve_plan(void* base, size_t cap, int64_t N, int T, int Lcap, boo
     const size_t n = (size_t)(N > 0 ? N : 1);
     w.keys_a = c.take<uint64_t>(n);
     w.keys_b = c.take<uint64_t>(n);
-    w.uq = c.take<uint32_t>(n < 64 ? 64 : n);      // later the flag masks of the grouping step (3 x 8 bytes per 64 lookups)
+    w.uq = c.take<uint32_t>(n < 64 ? 64 : n);      // later the rows' first positions of the grouping step
     w.tile_batch = c.take<int32_t>((n >> kPosTileShift) + 2);
     w.sort_temp = c.take<uint32_t>(sort_temp_words<kPlanSortIPT>(N));
     w.scan_partials32 = c.take<uint32_t>(scan_partials(N));
@@ -754,8 +743,8 @@ PlanWorkspace carve_plan(void* base, size_t cap, int64_t N, int T, int Lcap, boo
     w.offsets = c.take<int64_t>(5 * (size_t)(T + 1));
     w.prefetch_off = w.offsets;
     w.evict_off = w.offsets + (T + 1);
-    w.item_off = w.offsets + 2 * (size_t)(T + 1);
-    w.split_off = w.offsets + 3 * (size_t)(T + 1);
+    w.piece_off = w.offsets + 2 * (size_t)(T + 1);
+    w.multi_off = w.offsets + 3 * (size_t)(T + 1);
     w.pair_off = reinterpret_cast<uint32_t*>(w.offsets + 4 * (size_t)(T + 1));
     w.iter_off = c.take<int64_t>(T + 1);
     w.rec_a = c.take<uint64_t>(n);
@@ -851,11 +840,11 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
     if (!workspace || ((uintptr_t)workspace & 255)) return fail(BP_ERR_INVALID_ARG, "workspace NULL or not 256-byte aligned");
 
     const int Lcap = cfg->lookahead > 0 && cfg->lookahead < T ? cfg->lookahead : T;   // 0: not configured, any window
-    const bool grouping = plan->grouped_slots || plan->grouped_lookups || plan->item_starts || plan->item_offsets ||
-                          plan->split_starts || plan->split_offsets;
-    if (grouping && !(plan->grouped_slots && plan->grouped_lookups && plan->item_starts && plan->item_offsets &&
-                      plan->split_starts && plan->split_offsets))
+    const bool grouping = plan->grouped_lookups || plan->row_recs || plan->piece_recs || plan->piece_offsets;
+    if (grouping && !(plan->grouped_lookups && plan->row_recs && plan->piece_recs && plan->piece_offsets))
         return fail(BP_ERR_INVALID_ARG, "the grouping outputs of the plan must be all set or all NULL");
+    if (grouping && (((uintptr_t)plan->row_recs | (uintptr_t)plan->piece_recs) & 15))
+        return fail(BP_ERR_INVALID_ARG, "row_recs and piece_recs must be 16-byte aligned");
     PlanWorkspace w = carve_plan(workspace, workspace_bytes, N, T, Lcap, grouping);
     if (w.bytes > workspace_bytes)
         return fail(BP_ERR_WORKSPACE_TOO_SMALL, "workspace %zu < required %zu bytes", workspace_bytes, w.bytes);
@@ -883,7 +872,7 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
         for (int i = 0; i < n_emit; ++i) plan->occupancy[i] = 0;
         plan->L_eff = plan->L_requested = cfg->lookahead ? cfg->lookahead : T_in;
         if (grouping)
-            for (int i = 0; i <= n_emit; ++i) plan->item_offsets[i] = plan->split_offsets[i] = 0;
+            for (int i = 0; i <= n_emit; ++i) plan->piece_offsets[i] = 0;
         if (chunk) {                                      // the ring passes through unchanged
             ch->out->n_resident = 0;
             if (ring0) BP_HIP(hipMemcpyAsync(ch->out->ring, ring0, sizeof(int32_t) * C, hipMemcpyDeviceToDevice, stream));
@@ -1027,7 +1016,7 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
     BP_HIP(hipMemcpyAsync(&htot, totals, sizeof(uint64_t), hipMemcpyDeviceToHost, stream));
 
     // ---- 8. grouping for the backward pass
-    uint64_t n_items_split = 0;
+    uint64_t n_pieces_multi = 0;
     if (grouping) {
         // one pass as a rule (batch bits <= 9): out of the sorted words into the spare buffer; a second pass would
         // come back into the sorted words' own buffer, which nobody reads any more by then
@@ -1039,20 +1028,28 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
             gup, gsrc, gbuf, no_vals, N, pb, pb + ib, w.sort_temp, stream, &g_in)));
         const uint64_t* gkeys = gbuf[g_in];
         const GroupWord gw{ib, pb};
-        // the pairs of the sorted lookups are not needed any more: their buffer takes the flag masks
-        uint64_t* item_mask = reinterpret_cast<uint64_t*>(w.uq);
-        uint64_t* split_mask = item_mask + ((size_t)N + 63) / 64;
-        uint64_t* head_mask = split_mask + ((size_t)N + 63) / 64;
-        BP_TRY((device_scan2<uint64_t, AddOp, ItemFlagIn, ItemFlagFromMask, GroupOut>(
-            ItemFlagIn{gkeys, where, gw, R0, item_mask, split_mask, head_mask}, ItemFlagFromMask{item_mask, split_mask},
-            GroupOut{gkeys, where, gw, plan->grouped_slots, plan->grouped_lookups, plan->item_starts,
-                     plan->split_starts, w.item_off, w.split_off, R0, head_mask},
-            N, w.scan_partials64, AddOp(), uint64_t(0), stream)));
+        // the pairs of the sorted lookups are not needed any more: their buffer takes the rows' first positions
+        uint32_t* row_pos = w.uq;
+        BP_TRY((device_scan<uint32_t, AddOp, GroupRowIn, GroupRowOut>(
+            GroupRowIn{gkeys, pb, R0}, GroupRowOut{gkeys, gw, plan->grouped_lookups, row_pos, R0}, N, w.scan_partials32,
+            AddOp(), 0u, stream)));
+        const uint32_t* n_rows = w.scan_partials32 + scan_num_tiles(N);
+        // at most one row per pair (fewer only where the look-ahead batches of a chunk hold rows without a slot)
+        const int64_t rows_bound = (int64_t)M - R0 > 0 ? (int64_t)M - R0 : 1;
+        BP_TRY((device_scan<uint64_t, AddOp, RowPiecesIn, GroupRecordOut>(
+            RowPiecesIn{row_pos, n_rows, (uint32_t)N},
+            GroupRecordOut{row_pos, n_rows, (uint32_t)N, gkeys, gw, (const int64_t*)w.iter_off, R0,
+                           reinterpret_cast<uint4*>(plan->row_recs), reinterpret_cast<uint4*>(plan->piece_recs),
+                           w.piece_off, w.multi_off},
+            rows_bound, w.scan_partials64, AddOp(), uint64_t(0), stream)));
+        const uint32_t* n_pieces_dev = reinterpret_cast<const uint32_t*>(w.scan_partials64 + scan_num_tiles(rows_bound));
+        BP_LAUNCH(K_PLAN_GROUP, plan_piece_partial_kernel, grid_for((int64_t)piece_capacity_for(N_real)), dim3(kBlock), 0,
+                  stream, reinterpret_cast<uint4*>(plan->piece_recs), n_pieces_dev, T, (const int64_t*)w.multi_off);
         const uint32_t per_xcd = blocks_per_xcd(N);
         BP_LAUNCH(K_PLAN_SLOTS, plan_lookup_slots_grouped_kernel, dim3(per_xcd * kXcds), dim3(kBlock), 0, stream, N, per_xcd,
                   gw, R0, gkeys, where, plan->lookup_slots);
-        BP_HIP(hipMemcpyAsync(&n_items_split, w.scan_partials64 + scan_num_tiles(N), sizeof(uint64_t), hipMemcpyDeviceToHost,
-                              stream));
+        BP_HIP(hipMemcpyAsync(&n_pieces_multi, w.scan_partials64 + scan_num_tiles(rows_bound), sizeof(uint64_t),
+                              hipMemcpyDeviceToHost, stream));
     }
 
     // ---- CSR offsets to the host (in chunk mode: of the emitted batches; positions in the device lists, so the
@@ -1062,8 +1059,7 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
     BP_HIP(hipStreamSynchronize(stream));
     int64_t* const hpre = hoffsets.data();
     int64_t* const hev = hpre + (T + 1);
-    int64_t* const hitem = hpre + 2 * (size_t)(T + 1);
-    int64_t* const hsplit = hpre + 3 * (size_t)(T + 1);
+    int64_t* const hpiece = hpre + 2 * (size_t)(T + 1);
     const uint32_t* const hpair = reinterpret_cast<const uint32_t*>(hpre + 4 * (size_t)(T + 1));
     const int64_t n_miss = (int64_t)(uint32_t)htot, n_evict = (int64_t)(htot >> 32);
     hpre[T] = n_miss;
@@ -1078,16 +1074,10 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
         plan->keep_offsets[i] = (int64_t)hpair[(size_t)i + shift];
     }
     if (grouping) {
-        hitem[T] = (int64_t)(uint32_t)n_items_split;
-        hsplit[T] = (int64_t)(n_items_split >> 32);
-        for (int i = T - 1; i >= 0; --i) {
-            if (hitem[i] < 0) hitem[i] = hitem[i + 1];
-            if (hsplit[i] < 0) hsplit[i] = hsplit[i + 1];
-        }
-        for (int i = 0; i <= n_emit; ++i) {
-            plan->item_offsets[i] = hitem[(size_t)i + shift];
-            plan->split_offsets[i] = hsplit[(size_t)i + shift];
-        }
+        hpiece[T] = (int64_t)(uint32_t)n_pieces_multi;          // pieces of the long rows of all batches
+        for (int i = T - 1; i >= 0; --i)
+            if (hpiece[i] < 0) hpiece[i] = hpiece[i + 1];
+        for (int i = 0; i <= n_emit; ++i) plan->piece_offsets[i] = hpiece[(size_t)i + shift];
     }
     if (!chunk) {
         if (n_miss != n_evict) return fail(BP_ERR_HIP, "internal: %lld prefetches but %lld evictions", (long long)n_miss, (long long)n_evict);

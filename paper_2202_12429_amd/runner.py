@@ -67,6 +67,7 @@ class CachedEmbeddingTrainer:
         self.plan_: Optional[B.Plan] = None
         self.iter_offsets: Optional[np.ndarray] = None
         self._bwd_ws = None
+        self._tickets = None           # counters of the backward pass: zeroed here once, every call leaves them zero
         self._out = None
         self._pipeline = None
         self._plan_state = None        # chunked planning: state of the cache at the last chunk boundary
@@ -81,6 +82,8 @@ class CachedEmbeddingTrainer:
                    B.bp_embbag_bwd_update_grouped_workspace_bytes(self.cfg, n, bags, True))
         if self._bwd_ws is None or self._bwd_ws.numel() < need:
             self._bwd_ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        if self._tickets is None or self._tickets.numel() * 4 < B.bp_embbag_bwd_ticket_bytes(n):
+            self._tickets = B.bwd_tickets(n, device=self.device)
         if self._out is None or self._out.shape[0] < bags:
             self._out = torch.empty((bags, int(self.cfg.dim)), dtype=torch.float32, device=self.device)
 
@@ -205,15 +208,15 @@ class CachedEmbeddingTrainer:
         p = self.plan_
         a, b = int(self.iter_offsets[i]), int(self.iter_offsets[i + 1])
         self._reserve(b - a, bags)
-        use_grouped = (p.grouped_slots is not None) if grouped is None else grouped
+        use_grouped = (p.grouped_lookups is not None) if grouped is None else grouped
         if use_grouped:
             if b == a:
                 return
-            ia, ib = int(p.item_offsets[i]), int(p.item_offsets[i + 1])
-            sa, sb = int(p.split_offsets[i]), int(p.split_offsets[i + 1])
-            B.bp_embbag_bwd_update_grouped(self.cfg, self.cache_w, self.cache_state, p.grouped_slots[a:b],
-                                           p.grouped_lookups[a:b], p.item_starts[ia:ib], p.split_starts[sa:sb],
-                                           bag_offsets_dev, bags, grad_out, self._bwd_ws, stream=stream)
+            ka, kb = int(p.keep_offsets[i]), int(p.keep_offsets[i + 1])       # a batch's rows are its keep-list entries
+            pa, pb = int(p.piece_offsets[i]), int(p.piece_offsets[i + 1])
+            B.bp_embbag_bwd_update_grouped(self.cfg, self.cache_w, self.cache_state, p.grouped_lookups[a:b],
+                                           p.row_recs[ka:kb], p.piece_recs[pa:pb], bag_offsets_dev, bags, grad_out,
+                                           self._bwd_ws, self._tickets, stream=stream)
         else:
             B.bp_embbag_bwd_update(self.cfg, self.cache_w, self.cache_state, p.lookup_slots[a:b], bag_offsets_dev,
-                                   bags, grad_out, self._bwd_ws, stream=stream)
+                                   bags, grad_out, self._bwd_ws, self._tickets, stream=stream)

@@ -110,22 +110,26 @@ def run_bwd(bp, cfg, w, state, slots, off, bags, grad, onehot):
     wd = w.cuda()
     sd = None if state is None else torch.from_numpy(state).cuda()
     ws = torch.empty(bp.bp_embbag_bwd_update_workspace_bytes(cfg, len(slots), bags), dtype=torch.uint8, device="cuda")
-    bp.bp_embbag_bwd_update(cfg, wd, sd, dev(slots), None if onehot else dev(off), bags, dev(grad), ws)
+    tk = bp.bwd_tickets(len(slots))
+    bp.bp_embbag_bwd_update(cfg, wd, sd, dev(slots), None if onehot else dev(off), bags, dev(grad), ws, tk)
     torch.cuda.synchronize()
+    assert not tk.any(), "the call must leave its counters zero"
     return wd.cpu(), None if sd is None else sd.cpu().numpy()
 
 
 def run_bwd_grouped(bp, cfg, w, state, slots, off, bags, grad, onehot):
     valid = (slots >= 0) & (slots < cfg.capacity)
     assert valid.all()
-    gs, gl, st, ioff, sp, soff = grouping.build_grouping(slots.astype(np.int64), np.array([0, len(slots)]), slots)
+    gl, rows, roff, pieces, poff = grouping.build_grouping(slots.astype(np.int64), np.array([0, len(slots)]), slots)
     wd = w.cuda()
     sd = None if state is None else torch.from_numpy(state).cuda()
     ws = torch.empty(bp.bp_embbag_bwd_update_grouped_workspace_bytes(cfg, len(slots), bags, not onehot),
                      dtype=torch.uint8, device="cuda")
-    bp.bp_embbag_bwd_update_grouped(cfg, wd, sd, dev(gs), dev(gl), dev(st.view(np.int32)), dev(sp.view(np.int32)),
-                                    None if onehot else dev(off), bags, dev(grad), ws)
+    tk = bp.bwd_tickets(len(slots))
+    bp.bp_embbag_bwd_update_grouped(cfg, wd, sd, dev(gl), dev(rows), dev(pieces) if len(pieces) else None,
+                                    None if onehot else dev(off), bags, dev(grad), ws, tk)
     torch.cuda.synchronize()
+    assert not tk.any(), "the call must leave its counters zero"
     return wd.cpu(), None if sd is None else sd.cpu().numpy()
 
 
@@ -197,11 +201,12 @@ def test_backward_degenerate(bp):
     assert np.array_equal(np.delete(got.numpy(), 7, axis=0), np.delete(w.numpy(), 7, axis=0))
     # n = 0 is a no-op
     ws = torch.empty(bp.bp_embbag_bwd_update_workspace_bytes(cfg, 0, 0), dtype=torch.uint8, device="cuda")
+    tk = bp.bwd_tickets(n)
     bp.bp_embbag_bwd_update(cfg, w.cuda(), None, torch.zeros(0, dtype=torch.int32, device="cuda"), None, 0,
-                            torch.zeros((0, D), device="cuda"), ws)
+                            torch.zeros((0, D), device="cuda"), ws, tk)
     # workspace too small
     with pytest.raises(bp.BagpipeError) as e:
-        bp.bp_embbag_bwd_update(cfg, w.cuda(), None, dev(slots), None, n, dev(grad), ws[:256])
+        bp.bp_embbag_bwd_update(cfg, w.cuda(), None, dev(slots), None, n, dev(grad), ws[:256], tk)
     assert e.value.status == -3
 
 
@@ -366,11 +371,10 @@ def assert_plan_equal(got, want, N):
 def assert_grouping_valid(got, want, ids, off):
     """The plan's optional grouping held to the contract the header gives a caller (tests/grouping.py); the slots
     it must carry are the oracle plan's."""
-    grouping.check_grouping(ids, off, want.lookup_slots, got.grouped_slots.cpu().numpy(), got.grouped_lookups.cpu().numpy(),
-                            got.item_starts.cpu().numpy(), got.item_offsets, got.split_starts.cpu().numpy(),
-                            got.split_offsets)
-    assert got.item_offsets[0] == 0 and got.split_offsets[0] == 0
-    assert got.item_offsets[-1] == got.item_starts.numel() and got.split_offsets[-1] == got.split_starts.numel()
+    grouping.check_grouping(ids, off, want.lookup_slots, got.grouped_lookups.cpu().numpy(), got.row_recs.cpu().numpy(),
+                            got.keep_offsets, got.piece_recs.cpu().numpy(), got.piece_offsets)
+    assert got.piece_offsets[0] == 0 and got.piece_offsets[-1] == got.piece_recs.shape[0]
+    assert got.row_recs.shape[0] == got.keep_offsets[-1]
 
 
 def plan_both(bp, ids, off, R, L, C):
@@ -381,7 +385,7 @@ def plan_both(bp, ids, off, R, L, C):
     assert_grouping_valid(got, want, ids, off)
     plain = bp.bp_oracle_plan(cfg, dev(ids), off)                  # without the optional outputs: same plan
     assert_plan_equal(plain, want, len(ids))
-    assert plain.grouped_slots is None
+    assert plain.grouped_lookups is None
     return got, want
 
 
@@ -686,10 +690,9 @@ def run_chunked(bp, ids, off, R, L, C, n_emit, reserve=0):
         n_em = int(off[b] - off[a])
         assert np.array_equal(got.lookup_slots[:n_em].cpu().numpy(), want.lookup_slots[off[a]:off[b]])
         if n_em:
-            grouping.check_grouping(sub_ids, sub_off, want.lookup_slots[off[a]:off[b]], got.grouped_slots[:n_em].cpu().numpy(),
-                                    got.grouped_lookups[:n_em].cpu().numpy(), got.item_starts.cpu().numpy(),
-                                    got.item_offsets, got.split_starts.cpu().numpy(), got.split_offsets,
-                                    n_batches=b - a)
+            grouping.check_grouping(sub_ids, sub_off, want.lookup_slots[off[a]:off[b]],
+                                    got.grouped_lookups[:n_em].cpu().numpy(), got.row_recs.cpu().numpy(),
+                                    got.keep_offsets, got.piece_recs.cpu().numpy(), got.piece_offsets, n_batches=b - a)
         # carried state: replay the oracle's lists up to batch b - 1
         held = {}
         free = list(range(C))

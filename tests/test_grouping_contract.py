@@ -6,73 +6,75 @@ import numpy as np
 import pytest
 
 import grouping
-from grouping import HEAD
 
-H = int(HEAD)
+L = 0x80000000
 
 
-def replay(ids, off, slots, chunk):
+def replay(ids, off, slots, row_max, piece):
     """The contract, batch by batch, with Python containers only."""
-    gs, gl, st, ioff, sp, soff = [], [], [], [0], [], [0]
+    gl, rows, roff, pieces, poff = [], [], [0], [], [0]
     for i in range(len(off) - 1):
         a, b = int(off[i]), int(off[i + 1])
         by_id = {}
         for k in range(a, b):
             by_id.setdefault(int(ids[k]), []).append(k - a)          # positions arrive in ascending order
-        order = [(g, pos) for g in sorted(by_id) for pos in by_id[g]]
-        starts = []
-        for p, (g, pos) in enumerate(order):
-            gl.append(pos)
-            gs.append(int(slots[a + pos]))
-            first = p == 0 or order[p - 1][0] != g
-            if first or p % chunk == 0:
-                starts.append(p | (H if first else 0))
         p = 0
-        for g in sorted(by_id):                                       # items of every id: starts inside its stretch
-            n = len(by_id[g])
-            if sum(1 for s in starts if p <= (s & ~H) < p + n) >= 3:
-                sp.append(p)
-            p += n
-        st += starts
-        ioff.append(len(st))
-        soff.append(len(sp))
-    return (np.array(gs, np.int32), np.array(gl, np.int32), np.array(st, np.uint32), np.array(ioff, np.int64),
-            np.array(sp, np.uint32), np.array(soff, np.int64))
+        multi = 0
+        for g in sorted(by_id):
+            pos = by_id[g]
+            m = len(pos)
+            gl += pos
+            slot = int(slots[a + pos[0]])
+            rows.append([p | (L if m > row_max else 0), m, slot, pos[0]])
+            if m > row_max:
+                P = (m + piece - 1) // piece
+                for j in range(P):
+                    pieces.append([p + j * piece, min(piece, m - j * piece), slot, j, P, multi if P > 1 else 0, 0, 0])
+                if P > 1:
+                    multi += P
+            p += m
+        roff.append(len(rows))
+        poff.append(len(pieces))
+    return (np.array(gl, np.int32), np.array(rows, np.uint32).reshape(-1, 4), np.array(roff, np.int64),
+            np.array(pieces, np.uint32).reshape(-1, 8), np.array(poff, np.int64))
 
 
 def test_hand_worked_example():
-    # one batch, chunk 2: ids 5 3 5 5 3 5 at positions 0..5, slot = 10 * id
-    ids = np.array([5, 3, 5, 5, 3, 5], dtype=np.int64)
-    off = np.array([0, 6], dtype=np.int64)
+    # one batch, rows longer than 1 lookup are long, pieces of 2: ids 5 3 5 5 3 5 5 at positions 0..6, slot = 10 * id
+    ids = np.array([5, 3, 5, 5, 3, 5, 5], dtype=np.int64)
+    off = np.array([0, 7], dtype=np.int64)
     slots = (ids * 10).astype(np.int32)
-    # id 3 at positions 1, 4; id 5 at positions 0, 2, 3, 5; grouped position 0 starts id 3, position 2 starts id 5
-    # (and is a multiple of 2), position 4 is a cut inside id 5, which spans two items only: nothing is split
-    gl = np.array([1, 4, 0, 2, 3, 5], np.int32)
-    gs = np.array([30, 30, 50, 50, 50, 50], np.int32)
-    st = np.array([0 | H, 2 | H, 4], np.uint32)
-    none = np.zeros(0, np.uint32)
-    grouping.check_grouping(ids, off, slots, gs, gl, st, [0, 3], none, [0, 0], chunk=2)
-    got = grouping.build_grouping(ids, off, slots, chunk=2)
-    assert got[0].tolist() == gs.tolist() and got[1].tolist() == gl.tolist() and got[2].tolist() == st.tolist()
-    assert got[3].tolist() == [0, 3] and got[4].tolist() == [] and got[5].tolist() == [0, 0]
-    # with chunk 1 every lookup is an item; id 3 spans 2 items, id 5 spans 4: only id 5 is split, it starts at 2
-    st1 = np.array([0 | H, 1, 2 | H, 3, 4, 5], np.uint32)
-    grouping.check_grouping(ids, off, slots, gs, gl, st1, [0, 6], np.array([2], np.uint32), [0, 1], chunk=1)
-    with pytest.raises(AssertionError):                               # the split row left out
-        grouping.check_grouping(ids, off, slots, gs, gl, st1, [0, 6], none, [0, 0], chunk=1)
+    # id 3 at positions 1, 4 (grouped 0..1); id 5 at positions 0, 2, 3, 5, 6 (grouped 2..6)
+    gl = np.array([1, 4, 0, 2, 3, 5, 6], np.int32)
+    rows = np.array([[0 | L, 2, 30, 1], [2 | L, 5, 50, 0]], np.uint32)
+    # id 3: one piece of 2 (no partial number); id 5: pieces of 2, 2, 1 lookups, the batch's first row of several
+    # pieces, so its pieces are numbered from 0
+    pieces = np.array([[0, 2, 30, 0, 1, 0, 0, 0],
+                       [2, 2, 50, 0, 3, 0, 0, 0], [4, 2, 50, 1, 3, 0, 0, 0], [6, 1, 50, 2, 3, 0, 0, 0]], np.uint32)
+    grouping.check_grouping(ids, off, slots, gl, rows, [0, 2], pieces, [0, 4], row_max=1, piece=2)
+    got = grouping.build_grouping(ids, off, slots, row_max=1, piece=2)
+    assert got[0].tolist() == gl.tolist() and got[1].view(np.uint32).tolist() == rows.tolist()
+    assert got[2].tolist() == [0, 2] and got[3].view(np.uint32).tolist() == pieces.tolist() and got[4].tolist() == [0, 4]
+    # with rows of up to 2 lookups taken whole, only id 5 is long; pieces of 4: 4 + 1 lookups
+    rows2 = np.array([[0, 2, 30, 1], [2 | L, 5, 50, 0]], np.uint32)
+    pieces2 = np.array([[2, 4, 50, 0, 2, 0, 0, 0], [6, 1, 50, 1, 2, 0, 0, 0]], np.uint32)
+    grouping.check_grouping(ids, off, slots, gl, rows2, [0, 2], pieces2, [0, 2], row_max=2, piece=4)
+    with pytest.raises(AssertionError):                               # the long row's pieces left out
+        grouping.check_grouping(ids, off, slots, gl, rows2, [0, 2], pieces2[:0], [0, 0], row_max=2, piece=4)
 
 
-def test_two_batches_offsets_are_per_batch():
-    ids = np.array([7, 7, 7, 2, 9, 9], dtype=np.int64)
-    off = np.array([0, 3, 6], dtype=np.int64)
-    slots = np.array([4, 4, 4, 1, 8, 8], dtype=np.int32)
-    gl = np.array([0, 1, 2, 0, 1, 2], np.int32)                       # positions are relative to their batch
-    st = np.array([0 | H, 1, 2, 0 | H, 1 | H, 2], np.uint32)
-    # batch 0: id 7 spans three items; batch 1: none does
-    grouping.check_grouping(ids, off, slots, slots, gl, st, [0, 3, 6], np.array([0], np.uint32), [0, 1, 1], chunk=1)
-    got = grouping.build_grouping(ids, off, slots, chunk=1)
-    assert got[2].tolist() == st.tolist() and got[3].tolist() == [0, 3, 6]
-    assert got[4].tolist() == [0] and got[5].tolist() == [0, 1, 1]
+def test_two_batches_partial_numbers_are_per_batch():
+    ids = np.array([7, 7, 7, 2, 9, 9, 9, 9], dtype=np.int64)
+    off = np.array([0, 3, 8], dtype=np.int64)
+    slots = np.array([4, 4, 4, 1, 8, 8, 8, 8], dtype=np.int32)
+    gl = np.array([0, 1, 2, 0, 1, 2, 3, 4], np.int32)                 # positions are relative to their batch
+    rows = np.array([[0 | L, 3, 4, 0], [0, 1, 1, 0], [1 | L, 4, 8, 1]], np.uint32)
+    pieces = np.array([[0, 2, 4, 0, 2, 0, 0, 0], [2, 1, 4, 1, 2, 0, 0, 0],       # batch 0: id 7 in pieces 2 + 1
+                       [1, 2, 8, 0, 2, 0, 0, 0], [3, 2, 8, 1, 2, 0, 0, 0]], np.uint32)   # batch 1 counts from 0 again
+    grouping.check_grouping(ids, off, slots, gl, rows, [0, 1, 3], pieces, [0, 2, 4], row_max=1, piece=2)
+    got = grouping.build_grouping(ids, off, slots, row_max=1, piece=2)
+    assert got[1].view(np.uint32).tolist() == rows.tolist() and got[3].view(np.uint32).tolist() == pieces.tolist()
+    assert got[2].tolist() == [0, 1, 3] and got[4].tolist() == [0, 2, 4]
 
 
 def random_case(seed):
@@ -91,58 +93,53 @@ def random_case(seed):
 @pytest.mark.parametrize("seed", range(8))
 def test_checker_accepts_replay_and_builder(seed):
     ids, off, slots, _ = random_case(seed)
-    for chunk in (1, 3, 32):
-        want = replay(ids, off, slots, chunk)
-        grouping.check_grouping(ids, off, slots, *want, chunk=chunk)
-        got = grouping.build_grouping(ids, off, slots, chunk=chunk)
-        for g, w, name in zip(got, want, ("grouped_slots", "grouped_lookups", "item_starts", "item_off", "split_starts",
-                                          "split_off")):
-            assert np.array_equal(g, w), (name, chunk)
+    for row_max, piece in ((1, 1), (2, 3), (4, 16), (32, 256)):
+        want = replay(ids, off, slots, row_max, piece)
+        grouping.check_grouping(ids, off, slots, *want, row_max=row_max, piece=piece)
+        got = grouping.build_grouping(ids, off, slots, row_max=row_max, piece=piece)
+        for g, w, name in zip(got, want, ("grouped_lookups", "row_recs", "row_off", "piece_recs", "piece_off")):
+            assert np.array_equal(np.asarray(g).view(np.uint32) if g.dtype == np.int32 and g.ndim == 2 else g, w), (name, row_max)
 
 
 @pytest.mark.parametrize("seed", range(4))
 def test_checker_rejects_planted_damage(seed):
     """Every clause of the contract, broken once."""
     ids, off, slots, rng = random_case(seed)
-    chunk = 3
-    gs, gl, st, ioff, sp, soff = replay(ids, off, slots, chunk)
+    row_max, piece = 2, 3
+    gl, rows, roff, pieces, poff = replay(ids, off, slots, row_max, piece)
     i = int(np.argmax(np.diff(off)))                         # the largest batch
     a, b = int(off[i]), int(off[i + 1])
-    assert b - a >= 20 and ioff[i + 1] - ioff[i] >= 4
+    ra, pa, pb = int(roff[i]), int(poff[i]), int(poff[i + 1])
+    assert b - a >= 20 and roff[i + 1] - ra >= 3 and pb - pa >= 3
 
-    def rejected(gs=gs, gl=gl, st=st, ioff=ioff, sp=sp, soff=soff):
+    def rejected(gl=gl, rows=rows, roff=roff, pieces=pieces, poff=poff):
         with pytest.raises(AssertionError):
-            grouping.check_grouping(ids, off, slots, gs, gl, st, ioff, sp, soff, chunk=chunk)
+            grouping.check_grouping(ids, off, slots, gl, rows, roff, pieces, poff, row_max=row_max, piece=piece)
 
     bad = gl.copy(); bad[a] = bad[a + 1]                     # not a permutation
     rejected(gl=bad)
     gid = ids[a:b][gl[a:b]]
     j = int(np.flatnonzero(np.diff(gid) > 0)[0])             # two neighbours of different ids swapped: order broken
-    bad, bad_s = gl.copy(), gs.copy()
-    bad[[a + j, a + j + 1]] = bad[[a + j + 1, a + j]]
-    bad_s[[a + j, a + j + 1]] = bad_s[[a + j + 1, a + j]]
-    rejected(gl=bad, gs=bad_s)
+    bad = gl.copy(); bad[[a + j, a + j + 1]] = bad[[a + j + 1, a + j]]
+    rejected(gl=bad)
     same = np.flatnonzero(np.diff(gid) == 0)
-    if len(same):                                            # two lookups of one id swapped: positions not ascending
-        j = int(same[0])
-        bad = gl.copy(); bad[[a + j, a + j + 1]] = bad[[a + j + 1, a + j]]
-        rejected(gl=bad)
-    bad = gs.copy(); bad[a + 5] += 1                         # a wrong slot
-    rejected(gs=bad)
-    k = int(ioff[i]) + 2
-    bad = st.copy(); bad[k] ^= H                             # head bit flipped
-    rejected(st=bad)
-    bad = np.delete(st, k); bo = ioff.copy(); bo[i + 1:] -= 1    # an item missing (its neighbour grows past a cut or row)
-    rejected(st=bad, ioff=bo)
-    bad = st.copy(); bad[k] = (bad[k] & H) | ((bad[k] & ~HEAD) + 1 if (bad[k] & ~HEAD) + 1 < (st[k + 1] & ~HEAD) else (bad[k] & ~HEAD) - 1)
-    if not np.array_equal(bad, st):
-        rejected(st=bad)                                     # an item start moved off its place
-    extra = np.insert(sp, int(soff[i]), np.uint32(0)) if not (soff[i + 1] > soff[i] and sp[soff[i]] == 0) else None
-    if extra is not None:                                    # a row listed as split that is not (or listed twice)
-        so = soff.copy(); so[i + 1:] += 1
-        first_row_len = int(np.flatnonzero(np.append(np.diff(gid) != 0, True))[0]) + 1
-        if first_row_len <= 2 * chunk:
-            rejected(sp=extra, soff=so)
-    if soff[i + 1] > soff[i]:                                # a split row dropped
-        so = soff.copy(); so[i + 1:] -= 1
-        rejected(sp=np.delete(sp, int(soff[i])), soff=so)
+    j = int(same[0])                                         # two lookups of one id swapped: positions not ascending
+    bad = gl.copy(); bad[[a + j, a + j + 1]] = bad[[a + j + 1, a + j]]
+    rejected(gl=bad)
+    for col in range(4):                                     # every field of a row record
+        bad = rows.copy(); bad[ra + 1, col] += 1
+        rejected(rows=bad)
+    bad = rows.copy(); bad[ra + 1, 0] ^= L                   # long flag flipped
+    rejected(rows=bad)
+    bad = np.delete(rows, ra + 1, axis=0); bo = roff.copy(); bo[i + 1:] -= 1     # a row record missing
+    rejected(rows=bad, roff=bo)
+    multi_piece = pa + int(np.flatnonzero(pieces[pa:pb, 4] > 1)[0])
+    for col in range(8):                                     # every field of a piece record of a row of several pieces
+        bad = pieces.copy(); bad[multi_piece, col] += 1
+        rejected(pieces=bad)
+    bad = np.delete(pieces, multi_piece, axis=0); bo = poff.copy(); bo[i + 1:] -= 1      # a piece missing
+    rejected(pieces=bad, poff=bo)
+    last_multi = pa + int(np.flatnonzero(pieces[pa:pb, 4] > 1)[-1])
+    if pieces[last_multi, 5] > 0:                            # partial numbers must count the earlier rows' pieces
+        bad = pieces.copy(); bad[pa:pb, 5] = 0
+        rejected(pieces=bad)
