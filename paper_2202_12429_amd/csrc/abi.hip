@@ -98,9 +98,9 @@ __global__ __launch_bounds__(256) void copy_calibration_kernel(const uint4* __re
     if (i < n16) dst[i] = src[i];
 }
 
-// Randomly placed rows fetched four at a time per lane group, as the backward pass reads gradient rows, and folded
-// into one word per lane so that the loads cannot be dropped.
-template <int GW>
+// Randomly placed rows fetched U at a time per lane group (four is how the backward pass reads gradient rows), and
+// folded into one word per lane so that the loads cannot be dropped.
+template <int GW, int U>
 __global__ __launch_bounds__(256) void gather_calibration_kernel(const uint4* __restrict__ table, uint32_t table_rows,
                                                                  int lpr, const uint32_t* __restrict__ rows, uint32_t n,
                                                                  uint4* __restrict__ sink) {
@@ -108,16 +108,16 @@ __global__ __launch_bounds__(256) void gather_calibration_kernel(const uint4* __
     const uint32_t group = t / GW;
     const int c = (int)(t % GW);
     uint4 acc = make_uint4(0, 0, 0, 0);
-    const uint64_t first = (uint64_t)group * 4;
+    const uint64_t first = (uint64_t)group * U;
     if (c < lpr && first < n) {
-        uint32_t r[4];
+        uint32_t r[U];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) r[j] = first + j < n ? min(rows[first + j], table_rows - 1u) : 0u;
-        uint4 v[4];
+        for (int j = 0; j < U; ++j) r[j] = first + j < n ? min(rows[first + j], table_rows - 1u) : 0u;
+        uint4 v[U];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = first + j < n ? table[(size_t)r[j] * lpr + c] : make_uint4(0, 0, 0, 0);
+        for (int j = 0; j < U; ++j) v[j] = first + j < n ? table[(size_t)r[j] * lpr + c] : make_uint4(0, 0, 0, 0);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < U; ++j) {
             acc.x ^= v[j].x; acc.y ^= v[j].y; acc.z ^= v[j].z; acc.w ^= v[j].w;
         }
     }
@@ -137,14 +137,25 @@ struct GatherLaunch {
     int64_t n;
     void* sink;
     hipStream_t stream;
-    template <int GW, bool BF16>
-    int run() {
-        const int64_t threads = ceil_div(n, 4) * GW;
+    int in_flight;
+    template <int GW, int U>
+    int launch() {
+        const int64_t threads = ceil_div(n, U) * GW;
         const int64_t blocks = ceil_div(threads, 256);
         if (blocks >= (int64_t(1) << 24)) return fail(BP_ERR_UNSUPPORTED, "gather of %lld rows is too large for one launch", (long long)n);
-        BP_LAUNCH(K_COPY, (gather_calibration_kernel<GW>), dim3((unsigned)blocks), dim3(256), 0, stream, (const uint4*)table,
-                  (uint32_t)table_rows, lpr, rows, (uint32_t)n, (uint4*)sink);
+        BP_LAUNCH(K_COPY, (gather_calibration_kernel<GW, U>), dim3((unsigned)blocks), dim3(256), 0, stream,
+                  (const uint4*)table, (uint32_t)table_rows, lpr, rows, (uint32_t)n, (uint4*)sink);
         return BP_OK;
+    }
+    template <int GW, bool BF16>
+    int run() {
+        switch (in_flight) {
+            case 1: return launch<GW, 1>();
+            case 2: return launch<GW, 2>();
+            case 4: return launch<GW, 4>();
+            case 8: return launch<GW, 8>();
+            default: return fail(BP_ERR_INVALID_ARG, "rows_in_flight %d: 1, 2, 4 or 8", in_flight);
+        }
     }
 };
 
@@ -209,7 +220,7 @@ BP_EXPORT int bp_copy_calibration(void* dst, const void* src, size_t bytes, void
 }
 
 BP_EXPORT int bp_gather_calibration(void* sink, const void* table, int64_t table_rows, int32_t row_bytes,
-                                    const uint32_t* rows, int64_t n, void* stream) {
+                                    const uint32_t* rows, int64_t n, int32_t rows_in_flight, void* stream) {
     if (!sink || !table || !rows || (((uintptr_t)sink | (uintptr_t)table) & 15))
         return fail(BP_ERR_INVALID_ARG, "gather needs 16-byte aligned table and sink and a row list");
     if (row_bytes < 16 || row_bytes > 1024 || row_bytes % 16 != 0)
@@ -217,7 +228,9 @@ BP_EXPORT int bp_gather_calibration(void* sink, const void* table, int64_t table
     if (table_rows < 1 || table_rows >= (int64_t(1) << 32) || n < 0 || n >= (int64_t(1) << 31))
         return fail(BP_ERR_INVALID_ARG, "table_rows or n out of range");
     if (n == 0) return BP_OK;
-    GatherLaunch l{table, table_rows, row_bytes / 16, rows, n, sink, (hipStream_t)stream};
+    if (rows_in_flight != 1 && rows_in_flight != 2 && rows_in_flight != 4 && rows_in_flight != 8)
+        return fail(BP_ERR_INVALID_ARG, "rows_in_flight %d: 1, 2, 4 or 8", rows_in_flight);
+    GatherLaunch l{table, table_rows, row_bytes / 16, rows, n, sink, (hipStream_t)stream, rows_in_flight};
     return dispatch_row(row_bytes / 16, false, l);
 }
 

@@ -892,19 +892,21 @@ def test_plan_trainer_marking(bp, seed):
         bp.bp_oracle_plan(bp.make_config(R, 4 * R, 16, lookahead=5), dev(ids), off, trainer_cuts=bad)
 
 
-@pytest.mark.parametrize("row_ints,n", [(48, 1000), (16, 4097), (4, 3), (256, 77)])
-def test_gather_calibration(bp, row_ints, n):
-    """The row-gather yardstick folds exactly the rows it is given (so it reads them)."""
+@pytest.mark.parametrize("row_ints,n,u", [(48, 1000, 4), (16, 4097, 1), (4, 3, 8), (256, 77, 2), (64, 999, 8)])
+def test_gather_calibration(bp, row_ints, n, u):
+    """The row-gather yardstick folds exactly the rows it is given (so it reads them), u rows per lane group."""
     rng = np.random.default_rng(row_ints + n)
     table = rng.integers(-2**31, 2**31, size=(500, row_ints), dtype=np.int64).astype(np.int32)
     rows = rng.integers(0, 500, size=n).astype(np.int32)
     rows[0] = 499
-    sink = bp.bp_gather_calibration(torch.from_numpy(table).cuda(), torch.from_numpy(rows).cuda())
+    sink = bp.bp_gather_calibration(torch.from_numpy(table).cuda(), torch.from_numpy(rows).cuda(), rows_in_flight=u)
     torch.cuda.synchronize()
     got = sink.cpu().numpy().reshape(-1, 4)
-    for k in range(-(-n // 4)):
-        sel = table[rows[4 * k:4 * k + 4]].reshape(-1, 4)
+    for k in range(-(-n // u)):
+        sel = table[rows[u * k:u * k + u]].reshape(-1, 4)
         assert np.array_equal(got[k], np.bitwise_xor.reduce(sel, axis=0)), k
+    with pytest.raises(bp.BagpipeError):
+        bp.bp_gather_calibration(torch.from_numpy(table).cuda(), torch.from_numpy(rows).cuda(), rows_in_flight=3)
 
 
 def test_profiler_totals_and_spread(bp):

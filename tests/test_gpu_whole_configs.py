@@ -80,8 +80,8 @@ def run_full(cfg, capacity, elementwise=True):
     touched = np.zeros(cfg.total_rows, dtype=bool)
     touched[trace.ids] = True
     idx = np.flatnonzero(~touched)[:: max(1, (~touched).sum() // 50_000)]
-    W0 = workloads.init_weights(cfg, 0, cfg.total_rows).numpy()
-    assert np.array_equal(W.numpy()[idx], W0[idx])
+    W0 = workloads.init_weights_rows(cfg, torch.from_numpy(idx).cuda()).cpu().numpy()
+    assert np.array_equal(W.numpy()[idx], W0)
     return plan
 
 
