@@ -396,11 +396,12 @@ int bp_embbag_bwd_update_grouped(const bp_config* cfg, void* cache_w, void* cach
 int bp_copy_calibration(void* dst, const void* src, size_t bytes, void* stream);
 /* Reads the n rows `rows[k]` (device uint32; a number >= table_rows reads the last row) of a device table of
  * table_rows rows of row_bytes bytes each (multiple of 16, at most 1024; 16-byte aligned) and folds them into
- * `sink` (device, 16 bytes for every four rows: 16 * (ceil(n / 4) + 256) bytes): lane groups take four consecutive
- * entries of `rows` each, all four loads in flight together, as the backward pass reads gradient rows.  A yardstick for the rate at which randomly placed rows can be
- * fetched with nothing else going on.  Asynchronous. */
+ * `sink` (device, 16 bytes per lane group: 16 * (ceil(n / rows_in_flight) + 256) bytes): lane groups take
+ * rows_in_flight (1, 2, 4 or 8) consecutive entries of `rows` each, all their loads in flight together; four is how
+ * the backward pass reads gradient rows.  A yardstick for the rate at which randomly placed rows can be fetched with
+ * nothing else going on.  Asynchronous. */
 int bp_gather_calibration(void* sink, const void* table, int64_t table_rows, int32_t row_bytes, const uint32_t* rows,
-                          int64_t n, void* stream);
+                          int64_t n, int32_t rows_in_flight, void* stream);
 
 const char* bp_error_string(int status);
 const char* bp_last_error_message(void);   /* thread-local, valid until the thread's next failing call */

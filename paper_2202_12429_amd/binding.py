@@ -103,7 +103,7 @@ def load_library():
     lib.bp_profile_get.argtypes = [ctypes.c_int, ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)]
     lib.bp_copy_calibration.argtypes = [vp, vp, sz, vp]
     lib.bp_copy_calibration.restype = ctypes.c_int
-    lib.bp_gather_calibration.argtypes = [vp, vp, i64, i32, vp, i64, vp]
+    lib.bp_gather_calibration.argtypes = [vp, vp, i64, i32, vp, i64, i32, vp]
     lib.bp_gather_calibration.restype = ctypes.c_int
     lib.bp_profile_bracket_overhead.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double)]
     lib.bp_profile_bracket_overhead.restype = ctypes.c_int
@@ -535,15 +535,16 @@ def bp_copy_calibration(dst, src, stream=None) -> None:
     _check(load_library().bp_copy_calibration(_ptr(dst), _ptr(src), nbytes, _stream(stream)))
 
 
-def bp_gather_calibration(table, rows, stream=None):
+def bp_gather_calibration(table, rows, stream=None, rows_in_flight: int = 4, sink=None):
     """Reads table[rows[k]] for every k (table: 2-D device tensor with rows of a multiple of 16 bytes, rows: int32
-    device tensor holding uint32 row numbers) four rows per lane group at a time; returns the sink tensor."""
+    device tensor holding uint32 row numbers) rows_in_flight rows per lane group at a time; returns the sink tensor."""
     import torch
     row_bytes = table.shape[1] * table.element_size()
     n = int(rows.numel())
-    sink = torch.empty((-(-n // 4) + 256) * 4, dtype=torch.int32, device=table.device)
+    if sink is None:
+        sink = torch.empty((-(-n // rows_in_flight) + 256) * 4, dtype=torch.int32, device=table.device)
     _check(load_library().bp_gather_calibration(_ptr(sink), _ptr(table), int(table.shape[0]), int(row_bytes), _ptr(rows), n,
-                                                _stream(stream)))
+                                                int(rows_in_flight), _stream(stream)))
     return sink
 
 
