@@ -388,6 +388,24 @@ int bp_embbag_bwd_update_grouped(const bp_config* cfg, void* cache_w, void* cach
                                  const float* grad_out, void* workspace, size_t workspace_bytes, uint32_t* tickets,
                                  void* stream);
 
+/*
+ * bp_embbag_bwd_update_grouped for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid allocation.  Same arguments without workspace and tickets: both live in a
+ * fixed array of bp_embbag_bwd_update_grouped_static_max_bytes() bytes (16 MiB) in device memory that belongs to the
+ * library (every GPU the library has run this call on holds its own copy until the process ends).  The call
+ * allocates and frees nothing; the first call on a device looks the array's address up and clears it with one small
+ * kernel on `stream`.  A batch whose scratch (bp_embbag_bwd_update_grouped_static_bytes) does not fit is refused with
+ * BP_ERR_UNSUPPORTED.  All calls on one GPU share the array: calls that overlap in time on one GPU race; calls on
+ * one stream, or ordered by events, do not.  Results are those of bp_embbag_bwd_update_grouped, bit for bit.
+ */
+size_t bp_embbag_bwd_update_grouped_static_max_bytes(void);
+int bp_embbag_bwd_update_grouped_static_bytes(const bp_config* cfg, int64_t n_lookups, int64_t bags, int32_t multi_hot,
+                                              size_t* bytes);
+int bp_embbag_bwd_update_grouped_static(const bp_config* cfg, void* cache_w, void* cache_state,
+                                        const int32_t* grouped_lookups, const bp_row_rec* row_recs, int64_t n_rows,
+                                        const bp_piece_rec* piece_recs, int64_t n_pieces, const int64_t* bag_offsets,
+                                        int64_t n_lookups, int64_t bags, const float* grad_out, void* stream);
+
 /* ------------------------------------------------------------------------------------------------
  * Diagnostics.
  * ------------------------------------------------------------------------------------------------ */

@@ -91,6 +91,12 @@ def load_library():
     lib.bp_embbag_fwd.argtypes = [cfgp, vp, vp, vp, i64, i64, vp, vp]
     lib.bp_embbag_bwd_update_workspace_bytes.argtypes = [cfgp, i64, i64, ctypes.POINTER(sz)]
     lib.bp_embbag_bwd_update.argtypes = [cfgp, vp, vp, vp, vp, i64, i64, vp, vp, sz, vp, vp]
+    lib.bp_embbag_bwd_update_grouped_static.argtypes = [cfgp, vp, vp, vp, vp, i64, vp, i64, vp, i64, i64, vp, vp]
+    lib.bp_embbag_bwd_update_grouped_static.restype = ctypes.c_int
+    lib.bp_embbag_bwd_update_grouped_static_bytes.argtypes = [cfgp, i64, i64, i32, ctypes.POINTER(sz)]
+    lib.bp_embbag_bwd_update_grouped_static_bytes.restype = ctypes.c_int
+    lib.bp_embbag_bwd_update_grouped_static_max_bytes.argtypes = []
+    lib.bp_embbag_bwd_update_grouped_static_max_bytes.restype = sz
     lib.bp_embbag_bwd_ticket_bytes.argtypes = [i64]
     lib.bp_embbag_bwd_ticket_bytes.restype = sz
     lib.bp_embbag_bwd_update_grouped_workspace_bytes.argtypes = [cfgp, i64, i64, i32, ctypes.POINTER(sz)]
@@ -523,6 +529,28 @@ def bp_embbag_bwd_update_grouped(cfg: bp_config, cache_w, cache_state, grouped_l
         int(row_recs.shape[0]), _ptr(piece_recs) if n_pieces else None, n_pieces,
         _ptr(bag_offsets), n, int(bags), _ptr(grad_out), _ptr(workspace), int(workspace.numel()), _ptr(tickets),
         _stream(stream)))
+
+
+def bp_embbag_bwd_update_grouped_static_max_bytes() -> int:
+    return int(load_library().bp_embbag_bwd_update_grouped_static_max_bytes())
+
+
+def bp_embbag_bwd_update_grouped_static_bytes(cfg: bp_config, n_lookups: int, bags: int, multi_hot: bool) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load_library().bp_embbag_bwd_update_grouped_static_bytes(ctypes.byref(cfg), int(n_lookups), int(bags),
+                                                                    int(bool(multi_hot)), ctypes.byref(out)))
+    return int(out.value)
+
+
+def bp_embbag_bwd_update_grouped_static(cfg: bp_config, cache_w, cache_state, grouped_lookups, row_recs, piece_recs,
+                                        bag_offsets, bags: int, grad_out, stream=None) -> None:
+    """bp_embbag_bwd_update_grouped without workspace and tickets: the library's own fixed scratch array serves."""
+    n = int(grouped_lookups.numel())
+    n_pieces = 0 if piece_recs is None else int(piece_recs.shape[0])
+    _check(load_library().bp_embbag_bwd_update_grouped_static(
+        ctypes.byref(cfg), _ptr(cache_w), _ptr(cache_state), _ptr(grouped_lookups), _ptr(row_recs),
+        int(row_recs.shape[0]), _ptr(piece_recs) if n_pieces else None, n_pieces,
+        _ptr(bag_offsets), n, int(bags), _ptr(grad_out), _stream(stream)))
 
 
 # ---------------------------------------------------------------------------------------------------

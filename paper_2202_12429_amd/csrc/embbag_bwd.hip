@@ -595,3 +595,76 @@ BP_EXPORT int bp_embbag_bwd_update_grouped(const bp_config* cfg, void* cache_w, 
                 cache_state, stream, bags};
     return dispatch_row((int)(row_bytes(cfg) / 16), cfg->weight_dtype == BP_BF16, l);
 }
+
+// ---- the grouped variant for callers that cannot allocate ---------------------------------------------------------
+// Same kernels; the scratch (counters, partial sums, the bag numbers of the grouped positions) lives in a fixed array
+// in device memory that belongs to the library.  Every GPU the library runs on holds its own copy of the array at
+// its own address, found once per device with that device current.
+namespace bp {
+namespace {
+constexpr size_t kStaticScratchBytes = size_t(16) << 20;
+// The counters own a stretch of fixed size at the array's start, whatever the batch: partial sums of one call must
+// never land where a later, larger call expects zeroed counters.
+constexpr size_t kStaticTickets = size_t(1) << 16;
+constexpr size_t kStaticTicketBytes = kStaticTickets * sizeof(uint32_t);
+static __device__ __align__(256) unsigned char g_static_scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};     // per device: where its copy of the array lives
+
+__global__ __launch_bounds__(256) void bwd_clear_words_kernel(uint32_t* p, size_t n) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+// The current device's copy of the scratch array.  On the first call for a device the address is looked up and the
+// array cleared once (the counters at its start must be zero; every call leaves them zero).
+int static_scratch(hipStream_t stream, unsigned char** out) {
+    int dev = -1;
+    BP_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(BP_ERR_UNSUPPORTED, "device %d outside [0, %d)", dev, kMaxDevices);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        BP_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_static_scratch)));
+        if (!ptr) return fail(BP_ERR_HIP, "the scratch array has no address on device %d", dev);
+        const size_t words = kStaticScratchBytes / sizeof(uint32_t);
+        BP_LAUNCH(K_FILL, bwd_clear_words_kernel, dim3((unsigned)ceil_div((int64_t)words, 256)), dim3(256), 0, stream,
+                  (uint32_t*)ptr, words);
+        g_scratch_ptr[dev] = (unsigned char*)ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return BP_OK;
+}
+}  // namespace
+}  // namespace bp
+
+BP_EXPORT size_t bp_embbag_bwd_update_grouped_static_max_bytes(void) { return kStaticScratchBytes; }
+
+BP_EXPORT int bp_embbag_bwd_update_grouped_static_bytes(const bp_config* cfg, int64_t n_lookups, int64_t bags,
+                                                        int32_t multi_hot, size_t* bytes) {
+    if (!bytes) return fail(BP_ERR_INVALID_ARG, "bytes is NULL");
+    BP_TRY(check_bwd_args(cfg, n_lookups, bags));
+    if (partial_rows_for(n_lookups) > kStaticTickets)
+        return fail(BP_ERR_UNSUPPORTED, "a batch of %lld lookups needs %zu counters, the library's fixed array holds %zu",
+                    (long long)n_lookups, partial_rows_for(n_lookups), kStaticTickets);
+    *bytes = kStaticTicketBytes + carve_grouped(nullptr, 0, n_lookups, cfg->dim, multi_hot != 0).bytes;
+    return BP_OK;
+}
+
+BP_EXPORT int bp_embbag_bwd_update_grouped_static(const bp_config* cfg, void* cache_w, void* cache_state,
+                                                  const int32_t* grouped_lookups, const bp_row_rec* row_recs,
+                                                  int64_t n_rows, const bp_piece_rec* piece_recs, int64_t n_pieces,
+                                                  const int64_t* bag_offsets, int64_t n_lookups, int64_t bags,
+                                                  const float* grad_out, void* stream) {
+    size_t need = 0;
+    BP_TRY(bp_embbag_bwd_update_grouped_static_bytes(cfg, n_lookups, bags, bag_offsets != nullptr, &need));
+    if (need > kStaticScratchBytes)
+        return fail(BP_ERR_UNSUPPORTED, "a batch of %lld lookups needs %zu bytes of scratch, the library's fixed array holds %zu",
+                    (long long)n_lookups, need, kStaticScratchBytes);
+    if (n_lookups == 0) return BP_OK;
+    unsigned char* base = nullptr;
+    BP_TRY(static_scratch((hipStream_t)stream, &base));
+    return bp_embbag_bwd_update_grouped(cfg, cache_w, cache_state, grouped_lookups, row_recs, n_rows, piece_recs, n_pieces,
+                                        bag_offsets, n_lookups, bags, grad_out, base + kStaticTicketBytes,
+                                        kStaticScratchBytes - kStaticTicketBytes, reinterpret_cast<uint32_t*>(base), stream);
+}
