@@ -95,6 +95,15 @@ typedef struct bp_config {
                              from all `capacity` slots.  With reserve >= the misses of any one batch, every slot a
                              batch's prefetches land in was already free before the previous batch trained, so they
                              can be fetched while that batch trains (Section 3.2: prefetching overlaps training). */
+    int64_t cache_w_stride;     /* bytes from one row of cache_w to the next; 0 = dim * sizeof(element) (rows back to
+                                   back); else a multiple of 16 that is at least that */
+    int64_t cache_state_stride; /* the same for cache_state; 0 = the state's own size (dim * 4 bytes, or 4 for the
+                                   row-wise rule); else a multiple of 16 (of 4 for the row-wise rule) that is at least
+                                   that.  A caller that keeps a row's state right behind its weights allocates one
+                                   array of capacity records of row + state bytes, passes cache_state = cache_w + row
+                                   bytes and the record size as both strides: a 192-byte row and its 192-byte state
+                                   then fill three whole 128-byte lines instead of touching four.  The backing table
+                                   is always dense. */
 } bp_config;
 
 /* ------------------------------------------------------------------------------------------------
@@ -218,7 +227,7 @@ int bp_oracle_plan_chunk(const bp_config* cfg, const int64_t* ids, const int64_t
  * same call, and a row is only fetched after its last update was written back (Section 3.2,
  * "Consistency with the Lookahead algorithm").
  *
- * cache_w / cache_state     device (HBM), [capacity] rows
+ * cache_w / cache_state     device (HBM), [capacity] rows (strides: bp_config.cache_w_stride / cache_state_stride)
  * backing_w / backing_state device-visible backing table [total_rows] rows (pinned host memory, or HBM)
  * evict_* / prefetch_*      device, list slices of one batch from bp_plan; n_* may be 0 (pointers then unused)
  * Entries with id or slot out of range are skipped.  Asynchronous on `stream`.

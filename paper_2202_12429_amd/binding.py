@@ -27,7 +27,8 @@ class BagpipeError(RuntimeError):
 class bp_config(ctypes.Structure):
     _fields_ = [("total_rows", ctypes.c_int64), ("capacity", ctypes.c_int64), ("dim", ctypes.c_int32),
                 ("weight_dtype", ctypes.c_int32), ("optimizer", ctypes.c_int32), ("lookahead", ctypes.c_int32),
-                ("lr", ctypes.c_float), ("eps", ctypes.c_float), ("reserve", ctypes.c_int64)]
+                ("lr", ctypes.c_float), ("eps", ctypes.c_float), ("reserve", ctypes.c_int64),
+                ("cache_w_stride", ctypes.c_int64), ("cache_state_stride", ctypes.c_int64)]
 
 
 class _bp_plan_state(ctypes.Structure):
@@ -138,10 +139,13 @@ def _check(status: int, **info):
 
 
 def make_config(total_rows: int, capacity: int, dim: int, weight_dtype="f32", optimizer="sgd", lookahead: int = 1,
-                lr: float = 0.01, eps: float = 1e-8, reserve: int = 0) -> bp_config:
+                lr: float = 0.01, eps: float = 1e-8, reserve: int = 0, cache_w_stride: int = 0,
+                cache_state_stride: int = 0) -> bp_config:
+    """cache_w_stride / cache_state_stride: bytes between consecutive rows of the cache arrays (0 = rows back to back)."""
     wd = _DTYPES[weight_dtype] if isinstance(weight_dtype, str) else int(weight_dtype)
     op = _OPTIMIZERS[optimizer] if isinstance(optimizer, str) else int(optimizer)
-    return bp_config(int(total_rows), int(capacity), int(dim), wd, op, int(lookahead), float(lr), float(eps), int(reserve))
+    return bp_config(int(total_rows), int(capacity), int(dim), wd, op, int(lookahead), float(lr), float(eps), int(reserve),
+                     int(cache_w_stride), int(cache_state_stride))
 
 
 def _ptr(t) -> Optional[int]:

@@ -41,6 +41,14 @@ int check_config(const bp_config* cfg) {
     const size_t rb = row_bytes(cfg);
     if (rb % 16 != 0) return fail(BP_ERR_INVALID_ARG, "row of %zu bytes is not a multiple of 16 bytes", rb);
     if (rb > 1024) return fail(BP_ERR_UNSUPPORTED, "row of %zu bytes exceeds 1024 bytes", rb);
+    if (cfg->cache_w_stride && (cfg->cache_w_stride < (int64_t)rb || cfg->cache_w_stride % 16 != 0))
+        return fail(BP_ERR_INVALID_ARG, "cache_w_stride %lld: 0, or a multiple of 16 bytes >= the row's %zu bytes",
+                    (long long)cfg->cache_w_stride, rb);
+    const size_t sb = state_row_bytes(cfg);
+    if (cfg->cache_state_stride &&
+        (sb == 0 || cfg->cache_state_stride < (int64_t)sb || cfg->cache_state_stride % (cfg->optimizer == BP_ADAGRAD ? 16 : 4) != 0))
+        return fail(BP_ERR_INVALID_ARG, "cache_state_stride %lld: 0, or a multiple of %d bytes >= the state's %zu bytes",
+                    (long long)cfg->cache_state_stride, cfg->optimizer == BP_ADAGRAD ? 16 : 4, sb);
     return BP_OK;
 }
 

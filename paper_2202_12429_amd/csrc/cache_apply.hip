@@ -16,7 +16,7 @@ __global__ __launch_bounds__(kRowBlock) void cache_copy_rows_kernel(uint4* __res
                                                                     uint4* __restrict__ cache_s, uint4* __restrict__ back_s,
                                                                     const int64_t* __restrict__ ids,
                                                                     const int32_t* __restrict__ slots, int64_t n, int64_t R,
-                                                                    int64_t C, int lpr, int slpr, int rowwise) {
+                                                                    int64_t C, int lpr, int slpr, int rowwise, int64_t wst, int64_t sst) {
     const int c = threadIdx.x % GW;
     const int64_t stride = (int64_t)gridDim.x * (kRowBlock / GW);
     for (int64_t e = ((int64_t)blockIdx.x * kRowBlock + threadIdx.x) / GW; e < n; e += stride) {
@@ -24,17 +24,17 @@ __global__ __launch_bounds__(kRowBlock) void cache_copy_rows_kernel(uint4* __res
         const int64_t s = slots[e];
         if (g < 0 || g >= R || s < 0 || s >= C) continue;
         if (c < lpr) {
-            if (TO_BACKING) back_w[g * lpr + c] = cache_w[s * lpr + c];
-            else cache_w[s * lpr + c] = back_w[g * lpr + c];
+            if (TO_BACKING) back_w[g * lpr + c] = cache_w[s * wst + c];
+            else cache_w[s * wst + c] = back_w[g * lpr + c];
         }
         for (int k = c; k < slpr; k += GW) {          // element-wise state: its own row of slpr pieces
-            if (TO_BACKING) back_s[g * slpr + k] = cache_s[s * slpr + k];
-            else cache_s[s * slpr + k] = back_s[g * slpr + k];
+            if (TO_BACKING) back_s[g * slpr + k] = cache_s[s * sst + k];
+            else cache_s[s * sst + k] = back_s[g * slpr + k];
         }
         if (rowwise && c == 0) {                      // row-wise state: one fp32 per row
             float* cs = reinterpret_cast<float*>(cache_s);
             float* bs = reinterpret_cast<float*>(back_s);
-            if (TO_BACKING) bs[g] = cs[s]; else cs[s] = bs[g];
+            if (TO_BACKING) bs[g] = cs[s * sst]; else cs[s * sst] = bs[g];
         }
     }
 }
@@ -46,15 +46,15 @@ __global__ __launch_bounds__(kRowBlock) void cache_stage_rows_kernel(const uint4
                                                                      const uint4* __restrict__ cache_s,
                                                                      uint4* __restrict__ stage_w, uint4* __restrict__ stage_s,
                                                                      const int32_t* __restrict__ slots, int64_t n, int64_t C,
-                                                                     int lpr, int slpr, int rowwise) {
+                                                                     int lpr, int slpr, int rowwise, int64_t wst, int64_t sst) {
     const int c = threadIdx.x % GW;
     const int64_t stride = (int64_t)gridDim.x * (kRowBlock / GW);
     for (int64_t e = ((int64_t)blockIdx.x * kRowBlock + threadIdx.x) / GW; e < n; e += stride) {
         const int64_t s = slots[e];
         if (s < 0 || s >= C) continue;
-        if (c < lpr) stage_w[e * lpr + c] = cache_w[s * lpr + c];
-        for (int k = c; k < slpr; k += GW) stage_s[e * slpr + k] = cache_s[s * slpr + k];
-        if (rowwise && c == 0) reinterpret_cast<float*>(stage_s)[e] = reinterpret_cast<const float*>(cache_s)[s];
+        if (c < lpr) stage_w[e * lpr + c] = cache_w[s * wst + c];
+        for (int k = c; k < slpr; k += GW) stage_s[e * slpr + k] = cache_s[s * sst + k];
+        if (rowwise && c == 0) reinterpret_cast<float*>(stage_s)[e] = reinterpret_cast<const float*>(cache_s)[s * sst];
     }
 }
 
@@ -70,7 +70,7 @@ __global__ __launch_bounds__(kRowBlock) void cache_duplex_kernel(uint4* __restri
                                                                  const int32_t* __restrict__ e_slots, int64_t n_e,
                                                                  const int64_t* __restrict__ p_ids,
                                                                  const int32_t* __restrict__ p_slots, int64_t n_p, int64_t R,
-                                                                 int64_t C, int lpr, int slpr, int rowwise) {
+                                                                 int64_t C, int lpr, int slpr, int rowwise, int64_t wst, int64_t sst) {
     const int c = threadIdx.x % GW;
     const int64_t stride = (int64_t)gridDim.x * (kRowBlock / GW);
     const int64_t both = 2 * (n_e < n_p ? n_e : n_p);
@@ -95,9 +95,9 @@ __global__ __launch_bounds__(kRowBlock) void cache_duplex_kernel(uint4* __restri
             const int64_t g = p_ids[k];
             const int64_t s = p_slots[k];
             if (g < 0 || g >= R || s < 0 || s >= C) continue;
-            if (c < lpr) cache_w[s * lpr + c] = back_w[g * lpr + c];
-            for (int q = c; q < slpr; q += GW) cache_s[s * slpr + q] = back_s[g * slpr + q];
-            if (rowwise && c == 0) reinterpret_cast<float*>(cache_s)[s] = reinterpret_cast<const float*>(back_s)[g];
+            if (c < lpr) cache_w[s * wst + c] = back_w[g * lpr + c];
+            for (int q = c; q < slpr; q += GW) cache_s[s * sst + q] = back_s[g * slpr + q];
+            if (rowwise && c == 0) reinterpret_cast<float*>(cache_s)[s * sst] = reinterpret_cast<const float*>(back_s)[g];
         }
     }
 }
@@ -115,7 +115,8 @@ __global__ __launch_bounds__(kRowBlock) void cache_handoff_kernel(uint4* __restr
                                                                   const int64_t* __restrict__ p_ids,
                                                                   const int32_t* __restrict__ p_slots, int64_t n_p,
                                                                   int64_t n_early, int64_t R, int64_t C, int lpr, int slpr,
-                                                                  int rowwise, uint32_t* __restrict__ mismatch) {
+                                                                  int rowwise, int64_t wst, int64_t sst,
+                                                                  uint32_t* __restrict__ mismatch) {
     const int c = threadIdx.x % GW;
     const int64_t stride = (int64_t)gridDim.x * (kRowBlock / GW);
     const int64_t n_late = n_p - n_early;
@@ -126,9 +127,9 @@ __global__ __launch_bounds__(kRowBlock) void cache_handoff_kernel(uint4* __restr
             const int64_t s = e_slots[x];
             const bool ok = g >= 0 && g < R && s >= 0 && s < C;
             if (ok) {
-                if (c < lpr) back_w[g * lpr + c] = cache_w[s * lpr + c];
-                for (int q = c; q < slpr; q += GW) back_s[g * slpr + q] = cache_s[s * slpr + q];
-                if (rowwise && c == 0) reinterpret_cast<float*>(back_s)[g] = reinterpret_cast<const float*>(cache_s)[s];
+                if (c < lpr) back_w[g * lpr + c] = cache_w[s * wst + c];
+                for (int q = c; q < slpr; q += GW) back_s[g * slpr + q] = cache_s[s * sst + q];
+                if (rowwise && c == 0) reinterpret_cast<float*>(back_s)[g] = reinterpret_cast<const float*>(cache_s)[s * sst];
             }
             if (x >= n_late) continue;
             const int64_t g2 = p_ids[n_early + x];
@@ -139,17 +140,17 @@ __global__ __launch_bounds__(kRowBlock) void cache_handoff_kernel(uint4* __restr
             }
             if (g2 < 0 || g2 >= R || !ok) continue;
             // the reads of the evicted row above have returned before these writes are issued: same lanes, same addresses
-            if (c < lpr) cache_w[s * lpr + c] = back_w[g2 * lpr + c];
-            for (int q = c; q < slpr; q += GW) cache_s[s * slpr + q] = back_s[g2 * slpr + q];
-            if (rowwise && c == 0) reinterpret_cast<float*>(cache_s)[s] = reinterpret_cast<const float*>(back_s)[g2];
+            if (c < lpr) cache_w[s * wst + c] = back_w[g2 * lpr + c];
+            for (int q = c; q < slpr; q += GW) cache_s[s * sst + q] = back_s[g2 * slpr + q];
+            if (rowwise && c == 0) reinterpret_cast<float*>(cache_s)[s * sst] = reinterpret_cast<const float*>(back_s)[g2];
         } else {
             const int64_t m = x - n_e;
             const int64_t g = p_ids[m];
             const int64_t s = p_slots[m];
             if (g < 0 || g >= R || s < 0 || s >= C) continue;
-            if (c < lpr) cache_w[s * lpr + c] = back_w[g * lpr + c];
-            for (int q = c; q < slpr; q += GW) cache_s[s * slpr + q] = back_s[g * slpr + q];
-            if (rowwise && c == 0) reinterpret_cast<float*>(cache_s)[s] = reinterpret_cast<const float*>(back_s)[g];
+            if (c < lpr) cache_w[s * wst + c] = back_w[g * lpr + c];
+            for (int q = c; q < slpr; q += GW) cache_s[s * sst + q] = back_s[g * slpr + q];
+            if (rowwise && c == 0) reinterpret_cast<float*>(cache_s)[s * sst] = reinterpret_cast<const float*>(back_s)[g];
         }
     }
 }
@@ -180,12 +181,12 @@ struct DuplexLaunch {
         if (stage && n_e)
             BP_LAUNCH(K_CACHE_STAGE, (cache_stage_rows_kernel<GW>), capped_grid(n_e * GW, max_blocks),
                       dim3(kRowBlock), 0, stream, (const uint4*)cache_w, (const uint4*)cache_s, (uint4*)stage_w,
-                      (uint4*)stage_s, e_slots, n_e, cfg->capacity, lpr, slpr, rowwise);
+                      (uint4*)stage_s, e_slots, n_e, cfg->capacity, lpr, slpr, rowwise, cache_w_stride16(cfg), cache_s_stride(cfg));
         if (apply && n_e + n_p)
             BP_LAUNCH(K_CACHE_DUPLEX, (cache_duplex_kernel<GW>), capped_grid((n_e + n_p) * GW, max_blocks),
                       dim3(kRowBlock), 0, stream, (uint4*)cache_w, (uint4*)cache_s, (uint4*)back_w, (uint4*)back_s,
                       (const uint4*)stage_w, (const uint4*)stage_s, e_ids, e_slots, n_e, p_ids, p_slots, n_p,
-                      cfg->total_rows, cfg->capacity, lpr, slpr, rowwise);
+                      cfg->total_rows, cfg->capacity, lpr, slpr, rowwise, cache_w_stride16(cfg), cache_s_stride(cfg));
         return BP_OK;
     }
 };
@@ -215,11 +216,11 @@ struct CopyLaunch {
         if (to_backing)
             BP_LAUNCH(K_CACHE_EVICT, (cache_copy_rows_kernel<GW, true>), grid, dim3(kRowBlock), 0, stream, (uint4*)cache_w,
                       (uint4*)back_w, (uint4*)cache_s, (uint4*)back_s, ids, slots, n, cfg->total_rows, cfg->capacity, lpr,
-                      slpr, rowwise);
+                      slpr, rowwise, cache_w_stride16(cfg), cache_s_stride(cfg));
         else
             BP_LAUNCH(K_CACHE_PREFETCH, (cache_copy_rows_kernel<GW, false>), grid, dim3(kRowBlock), 0, stream,
                       (uint4*)cache_w, (uint4*)back_w, (uint4*)cache_s, (uint4*)back_s, ids, slots, n, cfg->total_rows,
-                      cfg->capacity, lpr, slpr, rowwise);
+                      cfg->capacity, lpr, slpr, rowwise, cache_w_stride16(cfg), cache_s_stride(cfg));
         return BP_OK;
     }
 };
@@ -389,7 +390,7 @@ struct HandoffLaunch {
         BP_LAUNCH(K_CACHE_DUPLEX, (cache_handoff_kernel<GW>), capped_grid((n_e + n_early) * GW, grid_cap),
                   dim3(kRowBlock), 0, stream, (uint4*)cache_w, (uint4*)cache_s, (uint4*)back_w, (uint4*)back_s, e_ids,
                   e_slots, n_e, p_ids, p_slots, n_p, n_early, cfg->total_rows, cfg->capacity, lpr, slpr, rowwise,
-                  mismatch);
+                  cache_w_stride16(cfg), cache_s_stride(cfg), mismatch);
         return BP_OK;
     }
 };

@@ -62,6 +62,18 @@ inline size_t state_row_bytes(const bp_config* c) {
     return c->optimizer == BP_ADAGRAD ? (size_t)c->dim * 4 : c->optimizer == BP_ADAGRAD_ROWWISE ? 4 : 0;
 }
 
+// The cache arrays may be laid out with a stride wider than a row (bp_config.cache_w_stride / cache_state_stride: a
+// caller that keeps a row's optimizer state right behind its weights passes the record size for both).  Stride of a
+// cache row in 16-byte pieces; stride of its state in 16-byte pieces (element-wise state) or in floats (one float
+// per row).
+inline int64_t cache_w_stride16(const bp_config* c) {
+    return (int64_t)((c->cache_w_stride ? (size_t)c->cache_w_stride : row_bytes(c)) / 16);
+}
+inline int64_t cache_s_stride(const bp_config* c) {
+    const size_t b = c->cache_state_stride ? (size_t)c->cache_state_stride : state_row_bytes(c);
+    return (int64_t)(c->optimizer == BP_ADAGRAD ? b / 16 : b / 4);
+}
+
 // ---- workspace carving -------------------------------------------------------------------------
 // Hands out 256-byte aligned pieces of one caller-owned buffer; with base == nullptr it only counts.
 class Carver {

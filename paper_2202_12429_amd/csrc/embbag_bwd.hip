@@ -76,6 +76,8 @@ struct UpdateParams {
     int lpr;
     int dim;
     uint32_t bags;      // rows of the upstream gradient: a bag number beyond them reads row 0 instead
+    int64_t wst;        // stride of a cache row, in 16-byte pieces
+    int64_t sst;        // stride of a row's optimizer state, in floats
 };
 
 // Running sum of one 16-byte piece of gradient rows.  Sums are carried in fp64 and rounded to fp32 once,
@@ -159,10 +161,10 @@ __device__ __forceinline__ RowPiece<BF16> load_row(const UpdateParams& u, const 
     r.s.zero();
     r.s_row = 0.f;
     if (active) {
-        r.w_raw = cache_w[slot * u.lpr + c];
-        if (u.optimizer == BP_ADAGRAD) r.s.load_f32(cache_s + slot * u.dim, c);
+        r.w_raw = cache_w[slot * u.wst + c];
+        if (u.optimizer == BP_ADAGRAD) r.s.load_f32(cache_s + slot * u.sst, c);
     }
-    if (u.optimizer == BP_ADAGRAD_ROWWISE) r.s_row = cache_s[slot];
+    if (u.optimizer == BP_ADAGRAD_ROWWISE) r.s_row = cache_s[slot * u.sst];
     return r;
 }
 
@@ -193,7 +195,7 @@ __device__ __forceinline__ void finish_update(const UpdateParams& u, uint4* cach
             const float step = (u.lr * g.v[i]) / den;
             w.v[i] = w.v[i] - step;
         }
-        if (active) s.store_f32(cache_s + slot * u.dim, c);
+        if (active) s.store_f32(cache_s + slot * u.sst, c);
     } else {
         double ss = 0.0;                       // mean of squares over the row: an fp64 sum, rounded once
 #pragma unroll
@@ -207,9 +209,9 @@ __device__ __forceinline__ void finish_update(const UpdateParams& u, uint4* cach
             const float step = (u.lr * g.v[i]) / den;
             w.v[i] = w.v[i] - step;
         }
-        if (c == 0 && active) cache_s[slot] = s;
+        if (c == 0 && active) cache_s[slot * u.sst] = s;
     }
-    if (active) cache_w[slot * u.lpr + c] = w.encode();
+    if (active) cache_w[slot * u.wst + c] = w.encode();
 }
 
 // Adds the gradient rows of the grouped lookups [p0, p1) into acc: bursts of four rows, the indices of the next
@@ -443,8 +445,9 @@ struct BwdLaunch {
     int64_t bags;
     template <int GW, bool BF16>
     int run() {
+        const size_t sbytes = cfg->cache_state_stride ? (size_t)cfg->cache_state_stride : state_row_bytes(cfg);
         UpdateParams u{cfg->optimizer, cfg->lr, cfg->eps, (int)(row_bytes(cfg) / 16), cfg->dim,
-                       (uint32_t)(bags > 0 ? bags : 1)};
+                       (uint32_t)(bags > 0 ? bags : 1), cache_w_stride16(cfg), (int64_t)(sbytes / 4)};
         const int groups_per_block = kRowBlock / GW;
         int64_t piece_blocks = n_pieces, row_blocks = ceil_div((int64_t)n_rows, groups_per_block);
         if (piece_blocks > kMaxGridBlocks / 4) piece_blocks = kMaxGridBlocks / 4;

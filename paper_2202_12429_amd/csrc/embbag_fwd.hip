@@ -14,7 +14,7 @@ template <int GW, bool BF16>
 __global__ __launch_bounds__(kRowBlock) void embbag_fwd_kernel(const uint4* __restrict__ cache_w,
                                                                const int32_t* __restrict__ slots,
                                                                const int64_t* __restrict__ bag_off, int64_t bags,
-                                                               int64_t n, int64_t C, int lpr, int dim,
+                                                               int64_t n, int64_t C, int lpr, int64_t wst, int dim,
                                                                float* __restrict__ out) {
     const int64_t bag = ((int64_t)blockIdx.x * kRowBlock + threadIdx.x) / GW;
     const int c = threadIdx.x % GW;
@@ -32,7 +32,7 @@ __global__ __launch_bounds__(kRowBlock) void embbag_fwd_kernel(const uint4* __re
 #pragma unroll
             for (int j = 0; j < 4; ++j) s[j] = (uint32_t)slots[k + j];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) raw[j] = s[j] < (uint64_t)C ? cache_w[(int64_t)s[j] * lpr + c] : make_uint4(0, 0, 0, 0);
+            for (int j = 0; j < 4; ++j) raw[j] = s[j] < (uint64_t)C ? cache_w[(int64_t)s[j] * wst + c] : make_uint4(0, 0, 0, 0);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 Piece<BF16> p;
@@ -44,7 +44,7 @@ __global__ __launch_bounds__(kRowBlock) void embbag_fwd_kernel(const uint4* __re
             const uint32_t s = (uint32_t)slots[k];
             if (s < (uint64_t)C) {
                 Piece<BF16> p;
-                p.decode(cache_w[(int64_t)s * lpr + c]);
+                p.decode(cache_w[(int64_t)s * wst + c]);
                 acc.add(p);
             }
         }
@@ -59,8 +59,8 @@ constexpr int kFlatPieces = 4;
 template <bool BF16, int U>
 __global__ __launch_bounds__(kRowBlock) void embbag_fwd_onehot_kernel(const uint4* __restrict__ cache_w,
                                                                       const int32_t* __restrict__ slots, int64_t bags,
-                                                                      int64_t C, uint32_t lpr, uint32_t inv, int dim,
-                                                                      float* __restrict__ out) {
+                                                                      int64_t C, uint32_t lpr, uint32_t inv, int64_t wst,
+                                                                      int dim, float* __restrict__ out) {
     const int64_t base = (int64_t)blockIdx.x * (kRowBlock * U);
     const int64_t bag0 = base / lpr;
     const uint32_t r0 = (uint32_t)(base - bag0 * lpr);
@@ -77,7 +77,7 @@ __global__ __launch_bounds__(kRowBlock) void embbag_fwd_onehot_kernel(const uint
     }
 #pragma unroll
     for (int j = 0; j < U; ++j)
-        raw[j] = s[j] < (uint64_t)C ? cache_w[(int64_t)s[j] * lpr + c[j]] : make_uint4(0, 0, 0, 0);
+        raw[j] = s[j] < (uint64_t)C ? cache_w[(int64_t)s[j] * wst + c[j]] : make_uint4(0, 0, 0, 0);
 #pragma unroll
     for (int j = 0; j < U; ++j) {
         if (bag[j] >= bags) continue;
@@ -102,12 +102,12 @@ struct FwdLaunch {
             const uint32_t inv = lpr == 1 ? 0u : (uint32_t)((uint64_t(1) << 32) / (uint32_t)lpr + 1);
             const dim3 flat((unsigned)ceil_div(bags * lpr, (int64_t)kRowBlock * kFlatPieces));
             BP_LAUNCH(K_FWD, (embbag_fwd_onehot_kernel<BF16, kFlatPieces>), flat, dim3(kRowBlock), 0, stream,
-                      (const uint4*)cache_w, slots, bags, cfg->capacity, (uint32_t)lpr, inv, cfg->dim, out);
+                      (const uint4*)cache_w, slots, bags, cfg->capacity, (uint32_t)lpr, inv, cache_w_stride16(cfg), cfg->dim, out);
             return BP_OK;
         }
         const dim3 grid((unsigned)ceil_div(bags * GW, kRowBlock));
         BP_LAUNCH(K_FWD, (embbag_fwd_kernel<GW, BF16>), grid, dim3(kRowBlock), 0, stream, (const uint4*)cache_w, slots,
-                  bag_off, bags, n_lookups, cfg->capacity, lpr, cfg->dim, out);
+                  bag_off, bags, n_lookups, cfg->capacity, lpr, cache_w_stride16(cfg), cfg->dim, out);
         return BP_OK;
     }
 };

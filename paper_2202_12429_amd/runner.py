@@ -47,8 +47,13 @@ def state_shape(rows: int, dim: int, optimizer: int):
 
 class CachedEmbeddingTrainer:
     def __init__(self, cfg: B.bp_config, backing_w, backing_state=None, device="cuda:0", max_lookups: int = 0,
-                 max_bags: int = 0, grouping: bool = True, duplex: bool = True, handoff: bool = True):
+                 max_bags: int = 0, grouping: bool = True, duplex: bool = True, handoff: bool = True,
+                 interleave: Optional[bool] = None):
+        """interleave: keep a cached row's optimizer state right behind its weights, one record per slot (None: do so
+        for the element-wise rule, whose state is as large as the row: a 192-byte row and its state then fill three
+        whole 128-byte lines where two arrays touch four).  self.cache_w / self.cache_state are then strided views."""
         import torch
+        cfg = B.bp_config.from_buffer_copy(cfg)      # the strides below are this trainer's own
         self.cfg = cfg
         self.device = torch.device(device)
         self.backing_w = backing_w
@@ -61,9 +66,19 @@ class CachedEmbeddingTrainer:
         self._stage = None
         wdt = torch.float32 if cfg.weight_dtype == B.F32 else torch.bfloat16
         C, D = int(cfg.capacity), int(cfg.dim)
-        self.cache_w = torch.zeros((C, D), dtype=wdt, device=self.device)
         ss = state_shape(C, D, cfg.optimizer)
-        self.cache_state = torch.zeros(ss, dtype=torch.float32, device=self.device) if ss != (0,) else None
+        if interleave is None:
+            interleave = cfg.optimizer == B.ADAGRAD
+        if interleave and cfg.optimizer == B.ADAGRAD and cfg.weight_dtype == B.F32:
+            rec = torch.zeros((C, 2 * D), dtype=torch.float32, device=self.device)      # [weights | state] per slot
+            self._cache_buf = rec
+            self.cache_w, self.cache_state = rec[:, :D], rec[:, D:]
+            self._cw, self._cs = rec.data_ptr(), rec.data_ptr() + 4 * D                  # what the library is given
+            cfg.cache_w_stride = cfg.cache_state_stride = 8 * D
+        else:
+            self.cache_w = torch.zeros((C, D), dtype=wdt, device=self.device)
+            self.cache_state = torch.zeros(ss, dtype=torch.float32, device=self.device) if ss != (0,) else None
+            self._cw, self._cs = self.cache_w, self.cache_state
         self.plan_: Optional[B.Plan] = None
         self.iter_offsets: Optional[np.ndarray] = None
         self._bwd_ws = None
@@ -149,13 +164,13 @@ class CachedEmbeddingTrainer:
         p_ids, p_slots = self._slice("prefetch", i)
         if self._early is not None and disjoint and not self._n_emit:
             n_early = int(self._early[i]) if i > 0 else int(p_ids.numel())
-            B.bp_cache_apply_handoff(self.cfg, self.cache_w, self.cache_state, self.backing_w, self.backing_state, e_ids,
+            B.bp_cache_apply_handoff(self.cfg, self._cw, self._cs, self.backing_w, self.backing_state, e_ids,
                                      e_slots, p_ids, p_slots, n_early, self._mismatch, stream=stream)
         elif self.duplex and disjoint:
-            B.bp_cache_apply_duplex(self.cfg, self.cache_w, self.cache_state, self.backing_w, self.backing_state, e_ids,
+            B.bp_cache_apply_duplex(self.cfg, self._cw, self._cs, self.backing_w, self.backing_state, e_ids,
                                     e_slots, p_ids, p_slots, self._stage, stream=stream)
         else:
-            B.bp_cache_apply(self.cfg, self.cache_w, self.cache_state, self.backing_w, self.backing_state, e_ids,
+            B.bp_cache_apply(self.cfg, self._cw, self._cs, self.backing_w, self.backing_state, e_ids,
                              e_slots, p_ids, p_slots, stream=stream)
 
     # ---- (2b) the same maintenance, overlapped with training
@@ -163,7 +178,7 @@ class CachedEmbeddingTrainer:
         if self._n_emit:
             raise RuntimeError("the overlapped schedule takes whole-trace plans (plan()), not chunks (plan_chunk())")
         if self._pipeline is None:
-            self._pipeline = B.bp_pipeline_create(self.cfg, self.cache_w, self.cache_state, self.backing_w,
+            self._pipeline = B.bp_pipeline_create(self.cfg, self._cw, self._cs, self.backing_w,
                                                   self.backing_state, self.plan_, self._stage)
         B.bp_pipeline_begin(self._pipeline, stream)
 
@@ -190,7 +205,7 @@ class CachedEmbeddingTrainer:
     def flush(self, stream=None) -> None:
         T = self._n_emit if self._n_emit else self.iter_offsets.shape[0] - 1
         e_ids, e_slots = self._slice("evict", T - 1)
-        B.bp_cache_apply(self.cfg, self.cache_w, self.cache_state, self.backing_w, self.backing_state, e_ids, e_slots,
+        B.bp_cache_apply(self.cfg, self._cw, self._cs, self.backing_w, self.backing_state, e_ids, e_slots,
                          None, None, stream=stream)
         if self._early is not None and int(self._mismatch.item()) != 0:       # synchronises
             raise RuntimeError("bp_cache_apply_handoff met a slot pairing that is not the plan's: the cache is corrupt")
@@ -200,7 +215,7 @@ class CachedEmbeddingTrainer:
         sl = self.slots(i)
         self._reserve(int(sl.numel()), bags)
         out = self._out[:bags] if out is None else out
-        B.bp_embbag_fwd(self.cfg, self.cache_w, sl, bag_offsets_dev, bags, out, stream=stream)
+        B.bp_embbag_fwd(self.cfg, self._cw, sl, bag_offsets_dev, bags, out, stream=stream)
         return out
 
     # ---- (4)
@@ -214,9 +229,9 @@ class CachedEmbeddingTrainer:
                 return
             ka, kb = int(p.keep_offsets[i]), int(p.keep_offsets[i + 1])       # a batch's rows are its keep-list entries
             pa, pb = int(p.piece_offsets[i]), int(p.piece_offsets[i + 1])
-            B.bp_embbag_bwd_update_grouped(self.cfg, self.cache_w, self.cache_state, p.grouped_lookups[a:b],
+            B.bp_embbag_bwd_update_grouped(self.cfg, self._cw, self._cs, p.grouped_lookups[a:b],
                                            p.row_recs[ka:kb], p.piece_recs[pa:pb], bag_offsets_dev, bags, grad_out,
                                            self._bwd_ws, self._tickets, stream=stream)
         else:
-            B.bp_embbag_bwd_update(self.cfg, self.cache_w, self.cache_state, p.lookup_slots[a:b], bag_offsets_dev,
+            B.bp_embbag_bwd_update(self.cfg, self._cw, self._cs, p.lookup_slots[a:b], bag_offsets_dev,
                                    bags, grad_out, self._bwd_ws, self._tickets, stream=stream)

@@ -44,8 +44,9 @@ def test_binding_has_the_same_names():
 
 def test_config_struct_layout_matches_header():
     import paper_2202_12429_amd as bp
-    assert ctypes.sizeof(bp.bp_config) == 48
+    assert ctypes.sizeof(bp.bp_config) == 64
     assert bp.bp_config.lookahead.offset == 28 and bp.bp_config.lr.offset == 32 and bp.bp_config.reserve.offset == 40
+    assert bp.bp_config.cache_w_stride.offset == 48 and bp.bp_config.cache_state_stride.offset == 56
 
 
 def test_argument_errors_without_gpu(lib):

@@ -210,6 +210,100 @@ def test_backward_degenerate(bp):
     assert e.value.status == -3
 
 
+@pytest.mark.parametrize("D,dtype,optimizer,pad", [(48, "f32", "adagrad", 0), (16, "f32", "adagrad", 64),
+                                                   (128, "bf16", "adagrad_rowwise", 12), (32, "f32", "sgd", 32)])
+def test_strided_cache_equals_dense(bp, D, dtype, optimizer, pad):
+    """A cache whose rows carry their optimizer state right behind the weights (one record per slot, bp_config's two
+    strides), with and without padding: forward, both backward entry points and every maintenance call give, bit for
+    bit, what two dense arrays give."""
+    say(f"strided cache D={D} {dtype} {optimizer} pad={pad}")
+    C, R, bags = 2000, 5000, 6001
+    rng = np.random.default_rng(D + pad)
+    eb = 2 if dtype == "bf16" else 4
+    rb = D * eb
+    sb = D * 4 if optimizer == "adagrad" else 4 if optimizer == "adagrad_rowwise" else 0
+    rec = rb + sb + pad                                       # bytes per slot: [weights | state | padding]
+    dense = bp.make_config(R, C, D, dtype, optimizer, lr=0.01, eps=1e-8)
+    strided = bp.make_config(R, C, D, dtype, optimizer, lr=0.01, eps=1e-8, cache_w_stride=rec,
+                             cache_state_stride=rec if sb else 0)
+    wdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    w0 = torch.from_numpy(rng.uniform(-0.05, 0.05, size=(C, D)).astype(np.float32)).to(wdt).cuda()
+    s0 = None
+    if sb:
+        s0 = torch.from_numpy(rng.uniform(0, 2, size=(C, D) if optimizer == "adagrad" else (C,)).astype(np.float32)).cuda()
+    buf = torch.full((C, rec), 0x5A, dtype=torch.uint8, device="cuda")
+
+    def pack():
+        buf[:, :rb] = w0.contiguous().view(torch.uint8).view(C, rb)
+        if sb:
+            buf[:, rb:rb + sb] = s0.contiguous().view(torch.uint8).view(C, sb)
+    def unpack():
+        w = buf[:, :rb].contiguous().view(wdt).view(C, D)
+        s = buf[:, rb:rb + sb].contiguous().view(torch.float32).view(C, -1).squeeze(-1) if sb else None
+        return w, s
+    def same(a, b):
+        return torch.equal(a.view(torch.int16) if a.dtype == torch.bfloat16 else a, b.view(torch.int16) if b.dtype == torch.bfloat16 else b)
+    pw, ps = buf.data_ptr(), (buf.data_ptr() + rb) if sb else None
+
+    slots = np.minimum(rng.zipf(1.25, size=bags) - 1, C - 1).astype(np.int32)
+    grad = dev(rng.standard_normal((bags, D)).astype(np.float32))
+    # forward
+    pack()
+    out_d = torch.empty((bags, D), device="cuda")
+    out_s = torch.empty((bags, D), device="cuda")
+    bp.bp_embbag_fwd(dense, w0, dev(slots), None, bags, out_d)
+    bp.bp_embbag_fwd(strided, pw, dev(slots), None, bags, out_s)
+    assert torch.equal(out_d, out_s)
+    # backward, sorting and grouped
+    gl, rows, roff, pieces, poff = grouping.build_grouping(slots.astype(np.int64), np.array([0, bags]), slots)
+    for grouped in (False, True):
+        pack()
+        wd, sd = w0.clone(), None if s0 is None else s0.clone()
+        tk = bp.bwd_tickets(bags)
+        if grouped:
+            ws = torch.empty(bp.bp_embbag_bwd_update_grouped_workspace_bytes(dense, bags, bags, False), dtype=torch.uint8, device="cuda")
+            bp.bp_embbag_bwd_update_grouped(dense, wd, sd, dev(gl), dev(rows), dev(pieces), None, bags, grad, ws, tk)
+            bp.bp_embbag_bwd_update_grouped(strided, pw, ps, dev(gl), dev(rows), dev(pieces), None, bags, grad, ws, tk)
+        else:
+            ws = torch.empty(bp.bp_embbag_bwd_update_workspace_bytes(dense, bags, bags), dtype=torch.uint8, device="cuda")
+            bp.bp_embbag_bwd_update(dense, wd, sd, dev(slots), None, bags, grad, ws, tk)
+            bp.bp_embbag_bwd_update(strided, pw, ps, dev(slots), None, bags, grad, ws, tk)
+        torch.cuda.synchronize()
+        w, s = unpack()
+        assert same(w, wd) and (sd is None or torch.equal(s, sd)), ("grouped" if grouped else "sorting")
+        assert not same(wd, w0)
+    assert (buf[:, rb + sb:] == 0x5A).all(), "padding was written"
+    # maintenance: evict 300 rows to a table, fetch 300 others, through each entry point
+    tab_w = torch.from_numpy(rng.uniform(-1, 1, size=(R, D)).astype(np.float32)).to(wdt).cuda()
+    tab_s = None if not sb else torch.from_numpy(rng.uniform(0, 2, size=(R, D) if optimizer == "adagrad" else (R,)).astype(np.float32)).cuda()
+    perm = rng.permutation(C)[:300].astype(np.int32)
+    ids = rng.permutation(R)[:600].astype(np.int64)
+    e_ids, p_ids = dev(np.sort(ids[:300])), dev(np.sort(ids[300:]))
+    e_slots, p_slots = dev(perm), dev(perm)                  # the fetched rows take the evicted rows' slots, in order
+    for call in ("apply", "duplex", "handoff"):
+        pack()
+        wd, sd = w0.clone(), None if s0 is None else s0.clone()
+        td_w, td_s = tab_w.clone(), None if tab_s is None else tab_s.clone()
+        ts_w, ts_s = tab_w.clone(), None if tab_s is None else tab_s.clone()
+        if call == "apply":
+            bp.bp_cache_apply(dense, wd, sd, td_w, td_s, e_ids, e_slots, p_ids, p_slots)
+            bp.bp_cache_apply(strided, pw, ps, ts_w, ts_s, e_ids, e_slots, p_ids, p_slots)
+        elif call == "duplex":
+            st = torch.empty(bp.bp_cache_apply_duplex_workspace_bytes(dense, 300), dtype=torch.uint8, device="cuda")
+            bp.bp_cache_apply_duplex(dense, wd, sd, td_w, td_s, e_ids, e_slots, p_ids, p_slots, st)
+            bp.bp_cache_apply_duplex(strided, pw, ps, ts_w, ts_s, e_ids, e_slots, p_ids, p_slots, st)
+        else:
+            flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+            bp.bp_cache_apply_handoff(dense, wd, sd, td_w, td_s, e_ids, e_slots, p_ids, p_slots, 0, flag)
+            bp.bp_cache_apply_handoff(strided, pw, ps, ts_w, ts_s, e_ids, e_slots, p_ids, p_slots, 0, flag)
+            assert int(flag.item()) == 0
+        torch.cuda.synchronize()
+        w, s = unpack()
+        assert same(w, wd) and same(ts_w, td_w), call
+        assert sd is None or (torch.equal(s, sd) and torch.equal(ts_s, td_s)), call
+        assert not same(wd, w0) and not same(td_w, tab_w)
+
+
 # ---------------------------------------------------------------------------------------------------
 # cache maintenance
 # ---------------------------------------------------------------------------------------------------
