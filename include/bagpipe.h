@@ -87,7 +87,8 @@ typedef struct bp_config {
     int32_t lookahead;    /* requested lookahead value: window of this many batches including the current
                              one (Algorithm 1's LookAheadValue), >= 1.  0 = not configured: the planner takes the
                              number of leading batches whose distinct rows together fit capacity - reserve slots
-                             ("prefetch until the cache is full", Section 4) and applies the capacity policy to it */
+                             (the start-up rule of Section 4, "Automatically Calculating Lookahead": batches are
+                             fetched ahead until no slot is left) and applies the capacity policy to it */
     float lr;             /* learning rate */
     float eps;            /* Adagrad epsilon */
     int64_t reserve;      /* slots the planner's capacity policy leaves free, 0 <= reserve < capacity: L_eff is the
@@ -191,9 +192,12 @@ int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int64_t* iter
  * it is given and carries the state of the cache to the next call.  The batches after the n_emit-th are the window
  * the decisions look into: pass min(lookahead - 1, what the stream still holds) of them.  With the same effective
  * lookahead in every chunk the concatenated plans equal bp_oracle_plan's over the whole stream, slot for slot.
- * The capacity policy is applied per chunk (peak occupancy of the emitted batches, carried rows included), so the
- * effective lookahead may change from chunk to chunk; a row kept under an earlier, larger lookahead stays until
- * its next use.
+ * The capacity policy is applied per chunk, so the effective lookahead may change from chunk to chunk; a row kept
+ * under an earlier, larger lookahead stays until its next use.  The policy looks at every batch the chunk's
+ * decisions reach, not only at the emitted ones: the batches of the window count too (each held to
+ * capacity - reserve rows with the chunk's lookahead behind it and a lookahead of one from there on), so that a chunk
+ * never leaves its successor a cache it cannot plan.  Consequently BP_ERR_CAPACITY, or a lowered L_eff, may be due
+ * to a batch of the window.
  *
  * bp_plan_state   n_resident rows are in the cache at the boundary: resident_ids (device [capacity], ascending)
  *                 and ring (device [capacity]): the residents' slots in the same order, then the free slots in
@@ -205,7 +209,10 @@ int bp_oracle_plan(const bp_config* cfg, const int64_t* ids, const int64_t* iter
  *                 and the grouping cover all n_iters batches given, but past the n_emit-th batch their contents are
  *                 unspecified (slots may be -1 there: the window is planned without a bound on its occupancy);
  *                 list_capacity >= n_unique_pairs, which counts the carried rows too; peak_occupancy and
- *                 min_capacity are taken over the emitted batches.
+ *                 min_capacity are taken over all n_iters batches given, window included: peak_occupancy counts, in
+ *                 a batch of the window, its own rows and what this chunk's decisions and the carried rows leave
+ *                 there; min_capacity is the smallest capacity - reserve that admits a lookahead of one (a batch's
+ *                 distinct rows plus the carried rows still held over it).
  * workspace       bp_oracle_plan_chunk_workspace_bytes(cfg, n_lookups, n_iters, with_grouping) bytes.
  * Errors as for bp_oracle_plan.  Synchronises `stream`.
  */
