@@ -150,11 +150,17 @@ __device__ __forceinline__ uint32_t pair_gap(const uint64_t* ukey, uint32_t q, u
 // Each workgroup walks a contiguous stretch of pairs and keeps its counts in LDS: the per-batch unique counts and
 // the histogram rows of the small gaps [2, 2 + lds_gaps), which take nearly all the hits; larger gaps go to global
 // atomics.  Integer atomics only: the sums do not depend on the order.
-__global__ __launch_bounds__(kBlock) void plan_hist_kernel(const uint64_t* __restrict__ ukey, uint32_t M, int ib, int T,
-                                                           int Lcap, int lds_gaps, uint32_t per_block,
+// The number of pairs is read from the device (the host has not fetched it yet: it comes back together with the
+// lookahead, in one synchronisation instead of two); the grid is sized for the lookups, an upper bound.
+__global__ __launch_bounds__(kBlock) void plan_hist_kernel(const uint64_t* __restrict__ ukey,
+                                                           const uint32_t* __restrict__ n_pairs, int ib, int T,
+                                                           int Lcap, int lds_gaps,
                                                            uint32_t* __restrict__ H, uint32_t* __restrict__ ucount,
                                                            uint32_t* __restrict__ first_use, int chunk,
                                                            uint32_t* __restrict__ V) {
+    const uint32_t M = *n_pairs;
+    const uint32_t per_block = (M + gridDim.x - 1) / gridDim.x;
+    if ((uint64_t)blockIdx.x * per_block >= M) return;
     extern __shared__ uint32_t lds[];   // [T] unique counts, [T] first uses, then [lds_gaps][T] histogram rows
     uint32_t* lds_u = lds;
     uint32_t* lds_f = lds + T;
@@ -565,27 +571,24 @@ struct GroupWordSource {
     };
 };
 
-// Rows of the grouped order.  First scan, over the grouped lookups: a row starts where (slot, batch) changes; the
-// lookup's place goes to grouped_lookups, row r's first grouped position to row_pos[r].
-struct GroupRowIn {
-    const uint64_t* gkeys;
-    int pb;
-    int64_t first;          // entries below `first` are a chunk's carried residents, not lookups
-    __device__ __forceinline__ uint32_t operator()(int64_t p) const {
-        if (p < first) return 0u;
-        return (p == first || (gkeys[p] >> pb) != (gkeys[p - 1] >> pb)) ? 1u : 0u;
-    }
+// Rows of the grouped order.  A row starts where (slot, batch) changes; the kernel that scatters the slot map reads
+// every grouped word anyway and leaves these starts as bit masks, 64 lookups a word.  A scan over the words
+// (population counts) then numbers the rows, and every word writes the first grouped positions of its rows to row_pos.
+struct RowMaskIn {
+    const uint64_t* head_mask;
+    __device__ __forceinline__ uint32_t operator()(int64_t w) const { return (uint32_t)__popcll(head_mask[w]); }
 };
-struct GroupRowOut {
-    const uint64_t* gkeys;
-    GroupWord gw;
-    int32_t* grouped_lookups;
+struct RowMaskOut {
+    const uint64_t* head_mask;
     uint32_t* row_pos;
-    int64_t first;          // outputs start at `first`
-    __device__ __forceinline__ void operator()(int64_t p, uint32_t exc, uint32_t inc) const {
-        if (p < first) return;
-        grouped_lookups[p - first] = (int32_t)gw.place(gkeys[p]);
-        if (inc != exc) row_pos[exc] = (uint32_t)p;
+    __device__ __forceinline__ void operator()(int64_t w, uint32_t exc, uint32_t) const {
+        uint64_t m = head_mask[w];
+        uint32_t r = exc;
+        while (m) {
+            const int bit = __ffsll((unsigned long long)m) - 1;
+            row_pos[r++] = (uint32_t)(w * 64 + bit);
+            m &= m - 1;
+        }
     }
 };
 // Second scan, over the rows (RowPiecesIn counts the pieces): every row writes its record beside its keep-list
@@ -634,16 +637,31 @@ __global__ __launch_bounds__(kBlock) void plan_piece_partial_kernel(uint4* __res
 }
 
 // The per-lookup slot map written from the batch-grouped order: the targets of neighbouring grouped lookups lie in
-// their batch's stretch of the map (a few MB at most).
+// their batch's stretch of the map (a few MB at most).  The same pass over the grouped words writes each lookup's
+// place to grouped_lookups and the row starts as bit masks (a wavefront holds 64 consecutive grouped positions
+// starting at a multiple of 64, lane = position % 64; positions outside [first, N) start no row).
 __global__ __launch_bounds__(kBlock) void plan_lookup_slots_grouped_kernel(int64_t N, uint32_t per_xcd, GroupWord gw,
                                                                            int64_t first,
                                                                            const uint64_t* __restrict__ gkeys,
                                                                            BatchOfPos where,
-                                                                           int32_t* __restrict__ lookup_slots) {
+                                                                           int32_t* __restrict__ lookup_slots,
+                                                                           int32_t* __restrict__ grouped_lookups,
+                                                                           uint64_t* __restrict__ head_mask) {
     const int64_t p = xcd_contiguous_block(per_xcd) * kBlock + threadIdx.x;
-    if (p < first || p >= N) return;
-    const uint64_t k = gkeys[p];
-    lookup_slots[where.iter_off[gw.batch(k)] + gw.place(k) - first] = (int32_t)gw.slot(k);
+    const bool real = p >= first && p < N;
+    const uint64_t k = real ? gkeys[p] : 0;
+    // the word before: the lane below holds it, only a wavefront's first lane has to load it
+    uint64_t before = __shfl_up(k, 1, kWave);
+    if (lane_id() == 0 && real && p > first) before = gkeys[p - 1];
+    bool head = false;
+    if (real) {
+        const uint32_t place = gw.place(k);
+        lookup_slots[where.iter_off[gw.batch(k)] + place - first] = (int32_t)gw.slot(k);
+        grouped_lookups[p - first] = (int32_t)place;
+        head = p == first || (k >> gw.pb) != (before >> gw.pb);
+    }
+    const uint64_t m = __ballot(head);
+    if ((p & 63) == 0 && p < ((N + 63) & ~int64_t(63))) head_mask[p >> 6] = m;
 }
 
 template <typename T>
@@ -920,31 +938,22 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
                                                               w.scan_partials32, AddOp(), 0u, stream)));
     uint32_t M = 0;
     PlanScalars hs{};
-    BP_HIP(hipMemcpyAsync(&M, w.scan_partials32 + scan_num_tiles(N), sizeof(uint32_t), hipMemcpyDeviceToHost, stream));
-    BP_HIP(hipMemcpyAsync(&hs, w.scalars, sizeof(PlanScalars), hipMemcpyDeviceToHost, stream));
-    BP_HIP(hipStreamSynchronize(stream));
-    if (hs.error_flags & 1u) return fail(BP_ERR_ID_OUT_OF_RANGE, "an id lies outside [0, %lld)", (long long)cfg->total_rows);
-    plan->n_unique_pairs = M;
-    if ((int64_t)M > plan->list_capacity)
-        return fail(BP_ERR_WORKSPACE_TOO_SMALL, "list_capacity %lld < %u unique (id, batch) pairs",
-                    (long long)plan->list_capacity, M);
+    const uint32_t* n_pairs_dev = w.scan_partials32 + scan_num_tiles(N);     // stays valid until the next 32-bit scan
+    BP_HIP(hipMemcpyAsync(&M, n_pairs_dev, sizeof(uint32_t), hipMemcpyDeviceToHost, stream));   // read after the sync below
 
     // ---- 3. occupancy for every candidate lookahead, L_eff
-    BP_HIP(hipMemsetAsync(w.H, 0, sizeof(uint32_t) * (size_t)(Lcap + 1) * T, stream));
-    BP_HIP(hipMemsetAsync(w.ucount, 0, sizeof(uint32_t) * T, stream));
-    BP_HIP(hipMemsetAsync(w.first_use, 0, sizeof(uint32_t) * T, stream));
-    BP_HIP(hipMemsetAsync(w.peak, 0, sizeof(uint32_t) * (Lcap + 2), stream));
-    if (chunk) BP_HIP(hipMemsetAsync(w.V, 0, sizeof(uint32_t) * (T + 1), stream));
+    // H, ucount, first_use, V, vcover and peak lie one after the other in the workspace: one clear for all of them
+    BP_HIP(hipMemsetAsync(w.H, 0, (size_t)((char*)(w.peak + (Lcap + 2)) - (char*)w.H), stream));
     {
         int lds_gaps = (int)((48 * 1024 / 4 - 2 * T) / T);              // histogram rows that fit in 48 KiB next to 2 x [T]
         if (lds_gaps > Lcap - 2) lds_gaps = Lcap - 2;
         if (lds_gaps < 0) lds_gaps = 0;
-        int64_t blocks = ceil_div(M, 32 * 1024);                         // >= 32 Ki pairs per workgroup amortise the flush
-        if (blocks > 1024) blocks = 1024;
-        const uint32_t per_block = (uint32_t)ceil_div(M, blocks);
+        int64_t blocks = ceil_div(N, 4 * 32 * 1024);                     // >= 32 Ki pairs per workgroup amortise the flush
+        if (blocks > 1024) blocks = 1024;                                // (about one lookup in four starts a pair)
+        if (blocks < 1) blocks = 1;
         BP_LAUNCH(K_PLAN_HIST, plan_hist_kernel, dim3((unsigned)blocks), dim3(kBlock),
-                  sizeof(uint32_t) * (size_t)(2 + lds_gaps) * T, stream, (const uint64_t*)ukey, M, ib, T, Lcap, lds_gaps,
-                  per_block, w.H, w.ucount, w.first_use, (int)chunk, w.V);
+                  sizeof(uint32_t) * (size_t)(2 + lds_gaps) * T, stream, (const uint64_t*)ukey, n_pairs_dev, ib, T, Lcap,
+                  lds_gaps, w.H, w.ucount, w.first_use, (int)chunk, w.V);
     }
     const uint32_t* vcover = nullptr;
     if (chunk) {
@@ -964,6 +973,11 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
     BP_HIP(hipMemcpyAsync(&hs, w.scalars, sizeof(PlanScalars), hipMemcpyDeviceToHost, stream));
     BP_HIP(hipMemcpyAsync(hocc.data(), w.occ, sizeof(int64_t) * T, hipMemcpyDeviceToHost, stream));
     BP_HIP(hipStreamSynchronize(stream));
+    if (hs.error_flags & 1u) return fail(BP_ERR_ID_OUT_OF_RANGE, "an id lies outside [0, %lld)", (long long)cfg->total_rows);
+    plan->n_unique_pairs = M;
+    if ((int64_t)M > plan->list_capacity)
+        return fail(BP_ERR_WORKSPACE_TOO_SMALL, "list_capacity %lld < %u unique (id, batch) pairs",
+                    (long long)plan->list_capacity, M);
     for (int i = 0; i < n_emit; ++i) plan->occupancy[i] = hocc[(size_t)i + shift];
     plan->min_capacity = hs.min_capacity;
     plan->L_requested = hs.L_requested;
@@ -1028,12 +1042,18 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
             gup, gsrc, gbuf, no_vals, N, pb, pb + ib, w.sort_temp, stream, &g_in)));
         const uint64_t* gkeys = gbuf[g_in];
         const GroupWord gw{ib, pb};
-        // the pairs of the sorted lookups are not needed any more: their buffer takes the rows' first positions
+        // one pass over the grouped words: slot map, grouped_lookups, row starts as bit masks (the masks go to a
+        // pair-level buffer that nobody reads any more); then the rows' first positions, into the buffer of the
+        // sorted lookups' pair numbers, which is free as well
+        const uint32_t per_xcd = blocks_per_xcd(N);
+        uint64_t* head_mask = reinterpret_cast<uint64_t*>(w.par);
         uint32_t* row_pos = w.uq;
-        BP_TRY((device_scan<uint32_t, AddOp, GroupRowIn, GroupRowOut>(
-            GroupRowIn{gkeys, pb, R0}, GroupRowOut{gkeys, gw, plan->grouped_lookups, row_pos, R0}, N, w.scan_partials32,
-            AddOp(), 0u, stream)));
-        const uint32_t* n_rows = w.scan_partials32 + scan_num_tiles(N);
+        const int64_t n_words = (N + 63) / 64;
+        BP_LAUNCH(K_PLAN_SLOTS, plan_lookup_slots_grouped_kernel, dim3(per_xcd * kXcds), dim3(kBlock), 0, stream, N, per_xcd,
+                  gw, R0, gkeys, where, plan->lookup_slots, plan->grouped_lookups, head_mask);
+        BP_TRY((device_scan<uint32_t, AddOp, RowMaskIn, RowMaskOut>(RowMaskIn{head_mask}, RowMaskOut{head_mask, row_pos},
+                                                                   n_words, w.scan_partials32, AddOp(), 0u, stream)));
+        const uint32_t* n_rows = w.scan_partials32 + scan_num_tiles(n_words);
         // at most one row per pair (fewer only where the look-ahead batches of a chunk hold rows without a slot)
         const int64_t rows_bound = (int64_t)M - R0 > 0 ? (int64_t)M - R0 : 1;
         BP_TRY((device_scan<uint64_t, AddOp, RowPiecesIn, GroupRecordOut>(
@@ -1045,9 +1065,6 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
         const uint32_t* n_pieces_dev = reinterpret_cast<const uint32_t*>(w.scan_partials64 + scan_num_tiles(rows_bound));
         BP_LAUNCH(K_PLAN_GROUP, plan_piece_partial_kernel, grid_for((int64_t)piece_capacity_for(N_real)), dim3(kBlock), 0,
                   stream, reinterpret_cast<uint4*>(plan->piece_recs), n_pieces_dev, T, (const int64_t*)w.multi_off);
-        const uint32_t per_xcd = blocks_per_xcd(N);
-        BP_LAUNCH(K_PLAN_SLOTS, plan_lookup_slots_grouped_kernel, dim3(per_xcd * kXcds), dim3(kBlock), 0, stream, N, per_xcd,
-                  gw, R0, gkeys, where, plan->lookup_slots);
         BP_HIP(hipMemcpyAsync(&n_pieces_multi, w.scan_partials64 + scan_num_tiles(rows_bound), sizeof(uint64_t),
                               hipMemcpyDeviceToHost, stream));
     }
