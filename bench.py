@@ -85,6 +85,9 @@ def main() -> int:
     ap.add_argument("--value-only", action="store_true",
                     help="run only the placement and schedule `value` is quoted on (for kernel profiles: the other "
                          "runs launch the same kernels under different conditions and would blur per-kernel averages)")
+    ap.add_argument("--slot-map", action="store_true",
+                    help="plan with a slot per lookup and run bp_embbag_fwd on it also where every bag has one lookup "
+                         "(default there: no slot map, bp_embbag_fwd_grouped walks the plan's row records)")
     ap.add_argument("--skew", type=float, default=None,
                     help="draw the ids from the skew-sensitivity law instead of Zipf: the hottest 1 %% of every "
                          "table's rows take this share of the accesses (0.01 .. 0.9)")
@@ -234,8 +237,13 @@ def main() -> int:
 
     # runs: (placement of the backing table, schedule).  The overlapped runs plan with the reserve, the synchronous ones
     # without.
+    # bags of one lookup: forward and backward both walk the plan's row records, so the plan carries no slot per lookup
+    lean = bool(cfg.one_hot) and not args.slot_map
+    KERNEL_OF["embbag_fwd"] = "embbag_fwd_rows_kernel" if lean else "embbag_fwd_onehot_kernel"
+
     def make_trainer(cfg_, w_, s_):
-        return CachedEmbeddingTrainer(cfg_, w_, s_, device=dev, max_lookups=int(n_per_iter.max()), max_bags=bags)
+        return CachedEmbeddingTrainer(cfg_, w_, s_, device=dev, max_lookups=int(n_per_iter.max()), max_bags=bags,
+                                      slot_map=not lean)
 
     trainers = {}
     if hbm_resident:
@@ -264,6 +272,15 @@ def main() -> int:
         if tr_ is not src:
             tr_.plan_, tr_.iter_offsets, tr_._stage, tr_._early = src.plan_, src.iter_offsets, src._stage, src._early
     t_plan = float(np.median(plan_times))
+    t_plan_slot_map = None
+    if lean:            # for the record: the same plan with a slot per lookup as well
+        times = []
+        for rep in range(3):
+            t0 = time.perf_counter()
+            bp.bp_oracle_plan(bcfg, ids_dev, trace.iter_offsets, workspace=ws, grouping=True)
+            torch.cuda.synchronize()
+            times.append(time.perf_counter() - t0)
+        t_plan_slot_map = float(np.median(times))
     del ws
     early = bp.bp_pipeline_early_counts(plan.prefetch_offsets, plan.evict_offsets, capacity, plan.L_eff)
     log(f"plan: L_eff={plan.L_eff} (without reserve {first_sync.plan_.L_eff}) reserve={reserve} "
@@ -517,7 +534,12 @@ def main() -> int:
                         "gaps and the events' own few microseconds included); by_kernel_time divides by the sum of the "
                         "kernels' own durations instead"},
         "plan": {"ms": t_plan * 1e3, "ids_per_s": trace.n_lookups / t_plan, "n_lookups": trace.n_lookups,
-                 "note": "bp_oracle_plan over the whole trace with the grouping, host synchronisation included, median of 5"},
+                 "slot_map": not lean,
+                 "with_slot_map_ms": None if t_plan_slot_map is None else t_plan_slot_map * 1e3,
+                 "note": "bp_oracle_plan over the whole trace with the grouping, host synchronisation included, median "
+                         "of 5; as the step uses it: without a slot per lookup where every bag has one lookup (both "
+                         "passes then walk the row records); with_slot_map_ms: the same plan with that output too "
+                         "(binding included: it allocates the outputs)"},
         "cache_apply": {"rows_moved_per_step": moved / K, "row_bytes_with_state": row_b + state_b,
                         "hbm_table": apply_rate(m),
                         "pinned_host_table": apply_rate(pin_sync) if pin_sync else None},

@@ -123,7 +123,9 @@ typedef struct bp_config {
  * ------------------------------------------------------------------------------------------------ */
 typedef struct bp_plan {
     /* device outputs, caller-allocated */
-    int32_t* lookup_slots;    /* [n_lookups] */
+    int32_t* lookup_slots;    /* [n_lookups]; may be NULL when the grouping outputs below are asked for: a caller that
+                                 walks the row records (bp_embbag_fwd_grouped, bp_embbag_bwd_update_grouped) needs no
+                                 slot per lookup, and the planner then saves the pass that scatters them */
     int64_t* prefetch_ids;    /* [list_capacity] */
     int32_t* prefetch_slots;  /* [list_capacity] */
     int64_t* evict_ids;       /* [list_capacity] */
@@ -351,6 +353,23 @@ int bp_pipeline_end(bp_pipeline* p, void* compute_stream);
  * ------------------------------------------------------------------------------------------------ */
 int bp_embbag_fwd(const bp_config* cfg, const void* cache_w, const int32_t* lookup_slots,
                   const int64_t* bag_offsets, int64_t n_lookups, int64_t bags, float* out, void* stream);
+
+/*
+ * The forward pass of a batch with ONE lookup per bag, walked by the plan's grouping instead of a slot per lookup:
+ * every row record's row is fetched once and written to out[b, :] for every bag b among the row's grouped lookups
+ * (one lane group per row of up to BP_BWD_ROW_MAX lookups, one workgroup per piece of a longer row).  With a
+ * grouping that holds its contract every bag is named once and `out` equals bp_embbag_fwd's bit for bit; a bag that
+ * no record names keeps whatever `out` held.
+ *
+ * grouped_lookups      device, the batch's slice [iter_offsets[i], iter_offsets[i+1]) of the plan array ([bags])
+ * row_recs, n_rows     device, the batch's slice [keep_offsets[i], keep_offsets[i+1]) and its length
+ * piece_recs, n_pieces device, the batch's slice [piece_offsets[i], piece_offsets[i+1]) and its length (may be 0)
+ * Records that point outside the batch, bags outside [0, bags) and slots outside [0, capacity) write nothing.
+ * Limits and error behaviour as for bp_embbag_fwd.  Asynchronous on `stream`.
+ */
+int bp_embbag_fwd_grouped(const bp_config* cfg, const void* cache_w, const int32_t* grouped_lookups,
+                          const bp_row_rec* row_recs, int64_t n_rows, const bp_piece_rec* piece_recs, int64_t n_pieces,
+                          int64_t bags, float* out, void* stream);
 
 /* ------------------------------------------------------------------------------------------------
  * (4) Backward + update, deterministic (bit-identical from run to run): lookups are grouped by slot with

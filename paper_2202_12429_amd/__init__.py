@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     bp_pipeline_early_counts, bp_pipeline_create, bp_pipeline_destroy, bp_pipeline_early, bp_pipeline_begin,
     bp_pipeline_acquire, bp_pipeline_release, bp_pipeline_end,
     bp_embbag_fwd,
+    bp_embbag_fwd_grouped,
     bp_embbag_bwd_update, bp_embbag_bwd_update_workspace_bytes,
     bp_embbag_bwd_update_grouped, bp_embbag_bwd_update_grouped_workspace_bytes,
     bp_embbag_bwd_ticket_bytes, bwd_tickets, piece_capacity,

@@ -90,6 +90,8 @@ def load_library():
     lib.bp_pipeline_release.argtypes = [vp, i32, vp]
     lib.bp_pipeline_end.argtypes = [vp, vp]
     lib.bp_embbag_fwd.argtypes = [cfgp, vp, vp, vp, i64, i64, vp, vp]
+    lib.bp_embbag_fwd_grouped.argtypes = [cfgp, vp, vp, vp, i64, vp, i64, i64, vp, vp]
+    lib.bp_embbag_fwd_grouped.restype = ctypes.c_int
     lib.bp_embbag_bwd_update_workspace_bytes.argtypes = [cfgp, i64, i64, ctypes.POINTER(sz)]
     lib.bp_embbag_bwd_update.argtypes = [cfgp, vp, vp, vp, vp, i64, i64, vp, vp, sz, vp, vp]
     lib.bp_embbag_bwd_update_grouped_static.argtypes = [cfgp, vp, vp, vp, vp, i64, vp, i64, vp, i64, i64, vp, vp]
@@ -227,9 +229,10 @@ def bp_oracle_plan_workspace_bytes(cfg: bp_config, n_lookups: int, n_iters: int,
 
 
 def bp_oracle_plan(cfg: bp_config, ids, iter_offsets, list_capacity: Optional[int] = None, workspace=None,
-                   stream=None, grouping: bool = False, trainer_cuts=None) -> Plan:
+                   stream=None, grouping: bool = False, trainer_cuts=None, slot_map: bool = True) -> Plan:
     """ids: int64 device tensor [N]; iter_offsets: int64 host array [T+1].  Output and workspace tensors are
-    allocated here with torch (the library itself allocates nothing); list tensors are trimmed views."""
+    allocated here with torch (the library itself allocates nothing); list tensors are trimmed views.
+    slot_map=False (with grouping only): no lookup_slots, for callers that walk the row records."""
     import torch
     lib = load_library()
     iter_offsets = np.ascontiguousarray(iter_offsets, dtype=np.int64)
@@ -242,10 +245,12 @@ def bp_oracle_plan(cfg: bp_config, ids, iter_offsets, list_capacity: Optional[in
         workspace = torch.empty(bp_oracle_plan_workspace_bytes(cfg, N, T, grouping), dtype=torch.uint8, device=dev)
     i32 = dict(dtype=torch.int32, device=dev)
     i64 = dict(dtype=torch.int64, device=dev)
-    t = dict(lookup_slots=torch.empty(max(N, 1), **i32),
-             prefetch_ids=torch.empty(max(cap, 1), **i64), prefetch_slots=torch.empty(max(cap, 1), **i32),
+    assert slot_map or grouping, "a plan without a slot map needs the grouping"
+    t = dict(prefetch_ids=torch.empty(max(cap, 1), **i64), prefetch_slots=torch.empty(max(cap, 1), **i32),
              evict_ids=torch.empty(max(cap, 1), **i64), evict_slots=torch.empty(max(cap, 1), **i32),
              keep_ids=torch.empty(max(cap, 1), **i64), keep_ttl=torch.empty(max(cap, 1), **i32))
+    if slot_map:
+        t.update(lookup_slots=torch.empty(max(N, 1), **i32))
     h = dict(prefetch_offsets=np.zeros(T + 1, np.int64), evict_offsets=np.zeros(T + 1, np.int64),
              keep_offsets=np.zeros(T + 1, np.int64), occupancy=np.zeros(max(T, 1), np.int64))
     if grouping:
@@ -270,7 +275,7 @@ def bp_oracle_plan(cfg: bp_config, ids, iter_offsets, list_capacity: Optional[in
     _check(st, min_capacity=int(p.min_capacity), n_unique_pairs=int(p.n_unique_pairs))
     n_pf, n_k = int(h["prefetch_offsets"][-1]), int(h["keep_offsets"][-1])
     return Plan(L_eff=int(p.L_eff), L_requested=int(p.L_requested), peak_occupancy=int(p.peak_occupancy), min_capacity=int(p.min_capacity),
-                n_unique_pairs=int(p.n_unique_pairs), lookup_slots=t["lookup_slots"][:N],
+                n_unique_pairs=int(p.n_unique_pairs), lookup_slots=t["lookup_slots"][:N] if slot_map else None,
                 prefetch_ids=t["prefetch_ids"][:n_pf], prefetch_slots=t["prefetch_slots"][:n_pf],
                 evict_ids=t["evict_ids"][:n_pf], evict_slots=t["evict_slots"][:n_pf],
                 keep_ids=t["keep_ids"][:n_k], keep_ttl=t["keep_ttl"][:n_k],
@@ -481,6 +486,17 @@ def bp_embbag_fwd(cfg: bp_config, cache_w, lookup_slots, bag_offsets, bags: int,
     n = int(lookup_slots.numel())
     _check(load_library().bp_embbag_fwd(ctypes.byref(cfg), _ptr(cache_w), _ptr(lookup_slots), _ptr(bag_offsets), n,
                                         int(bags), _ptr(out), _stream(stream)))
+
+
+def bp_embbag_fwd_grouped(cfg: bp_config, cache_w, grouped_lookups, row_recs, piece_recs, bags: int, out,
+                          stream=None) -> None:
+    """One lookup per bag.  grouped_lookups / row_recs / piece_recs: one batch's slices of the plan's grouping arrays
+    (piece_recs may be None or empty).  out: fp32 device tensor [bags, dim], written in place."""
+    assert int(grouped_lookups.numel()) == int(bags)
+    n_pieces = 0 if piece_recs is None else int(piece_recs.shape[0])
+    _check(load_library().bp_embbag_fwd_grouped(ctypes.byref(cfg), _ptr(cache_w), _ptr(grouped_lookups), _ptr(row_recs),
+                                                int(row_recs.shape[0]), _ptr(piece_recs) if n_pieces else None, n_pieces,
+                                                int(bags), _ptr(out), _stream(stream)))
 
 
 # ---------------------------------------------------------------------------------------------------

@@ -1,5 +1,5 @@
-// Row and piece records of the backward pass (bp_row_rec / bp_piece_rec of the C header): what both makers of them,
-// the planner's grouping step and bp_embbag_bwd_update's own scans, share.
+// Row and piece records of a batch grouped by row (bp_row_rec / bp_piece_rec of the C header): what both makers of
+// them, the planner's grouping step and bp_embbag_bwd_update's own scans, and the kernels that walk them share.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -13,6 +13,7 @@ namespace bp {
 constexpr uint32_t kRowMax = BP_BWD_ROW_MAX;   // lookups of a row one lane group takes at most
 constexpr uint32_t kPiece = BP_BWD_PIECE;      // lookups per piece of a longer row
 constexpr uint32_t kLongRow = 0x80000000u, kPosMask = 0x7fffffffu;
+constexpr int kMaxGridBlocks = 8192;             // workgroups of a launch that walks the records, at most
 
 static_assert(sizeof(bp_row_rec) == 16 && sizeof(bp_piece_rec) == 32, "records are read and written as 16-byte words");
 

@@ -24,8 +24,6 @@
 namespace bp {
 namespace {
 
-constexpr int kMaxGridBlocks = 8192;
-
 // ---- 1. keys ---------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void bwd_keys_kernel(const int32_t* __restrict__ slots, const int64_t* __restrict__ bag_off,
                                                        int64_t n, int64_t bags, int64_t C, uint32_t* __restrict__ keys,

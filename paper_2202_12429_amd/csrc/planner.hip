@@ -171,18 +171,34 @@ __global__ __launch_bounds__(kBlock) void plan_hist_kernel(const uint64_t* __res
     const uint64_t imask = (uint64_t(1) << ib) - 1;
     const uint64_t begin = (uint64_t)blockIdx.x * per_block;
     const uint64_t end = begin + per_block < M ? begin + per_block : M;
-    for (uint64_t q = begin + threadIdx.x; q < end; q += kBlock) {
-        const uint32_t i = (uint32_t)(ukey[q] & imask);
-        atomicAdd(&lds_u[i], 1u);
-        if (q == 0 || (ukey[q - 1] >> ib) != (ukey[q] >> ib)) atomicAdd(&lds_f[i], 1u);   // the id's first batch
-        const uint32_t gap = pair_gap(ukey, (uint32_t)q, M, ib, imask);
-        if (chunk && i == 0) {      // a carried resident stays until its next use, whatever the lookahead
-            atomicAdd(&V[gap == kGapInf ? (uint32_t)T : gap], 1u);
-            continue;
+    // four pairs per thread and round, their keys and both neighbours' requested before any of them is counted
+    constexpr int kPairsInFlight = 4;
+    for (uint64_t q0 = begin + threadIdx.x; q0 < end; q0 += kBlock * kPairsInFlight) {
+        uint64_t key[kPairsInFlight], prev[kPairsInFlight], next[kPairsInFlight];
+#pragma unroll
+        for (int r = 0; r < kPairsInFlight; ++r) {
+            const uint64_t q = q0 + (uint64_t)r * kBlock;
+            const bool in = q < end;
+            key[r] = in ? ukey[q] : 0;
+            prev[r] = in && q > 0 ? ukey[q - 1] : ~uint64_t(0);        // no id has all bits set
+            next[r] = in && q + 1 < M ? ukey[q + 1] : ~uint64_t(0);
         }
-        if (gap >= 2u && gap < (uint32_t)Lcap) {
-            if (gap < 2u + (uint32_t)lds_gaps) atomicAdd(&lds_h[(gap - 2u) * T + i], 1u);
-            else atomicAdd(&H[(size_t)gap * T + i], 1u);
+#pragma unroll
+        for (int r = 0; r < kPairsInFlight; ++r) {
+            if (q0 + (uint64_t)r * kBlock >= end) break;
+            const uint64_t a = key[r];
+            const uint32_t i = (uint32_t)(a & imask);
+            atomicAdd(&lds_u[i], 1u);
+            if ((prev[r] >> ib) != (a >> ib)) atomicAdd(&lds_f[i], 1u);   // the id's first batch
+            const uint32_t gap = (a >> ib) == (next[r] >> ib) ? (uint32_t)((next[r] & imask) - i) : kGapInf;
+            if (chunk && i == 0) {      // a carried resident stays until its next use, whatever the lookahead
+                atomicAdd(&V[gap == kGapInf ? (uint32_t)T : gap], 1u);
+                continue;
+            }
+            if (gap >= 2u && gap < (uint32_t)Lcap) {
+                if (gap < 2u + (uint32_t)lds_gaps) atomicAdd(&lds_h[(gap - 2u) * T + i], 1u);
+                else atomicAdd(&H[(size_t)gap * T + i], 1u);
+            }
         }
     }
     __syncthreads();
@@ -194,15 +210,17 @@ __global__ __launch_bounds__(kBlock) void plan_hist_kernel(const uint64_t* __res
         if (lds_h[x]) atomicAdd(&H[(size_t)2 * T + x], lds_h[x]);      // row (2 + x / T), column x % T
 }
 
-// H[gap][.] -> inclusive prefix over batches, one thread per gap row
-__global__ void plan_occ_prefix_kernel(uint32_t* H, int T, int Lcap) {
-    const int gap = blockIdx.x * blockDim.x + threadIdx.x;
+// H[gap][.] -> inclusive prefix over batches, one wavefront per gap row
+__global__ __launch_bounds__(kBlock) void plan_occ_prefix_kernel(uint32_t* H, int T, int Lcap) {
+    const int gap = blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
     if (gap < 2 || gap >= Lcap) return;
     uint32_t* row = H + (size_t)gap * T;
     uint32_t run = 0;
-    for (int i = 0; i < T; ++i) {
-        run += row[i];
-        row[i] = run;
+    for (int base = 0; base < T; base += kWave) {
+        const int i = base + lane_id();
+        const uint32_t inc = wave_inclusive_scan(i < T ? row[i] : 0u, AddOp());
+        if (i < T) row[i] = run + inc;
+        run += __shfl(inc, kWave - 1);
     }
 }
 
@@ -636,7 +654,7 @@ __global__ __launch_bounds__(kBlock) void plan_piece_partial_kernel(uint4* __res
     piece_recs[2 * i + 1] = r;
 }
 
-// The per-lookup slot map written from the batch-grouped order: the targets of neighbouring grouped lookups lie in
+// The per-lookup slot map (when the caller wants one) written from the batch-grouped order: the targets of neighbouring grouped lookups lie in
 // their batch's stretch of the map (a few MB at most).  The same pass over the grouped words writes each lookup's
 // place to grouped_lookups and the row starts as bit masks (a wavefront holds 64 consecutive grouped positions
 // starting at a multiple of 64, lane = position % 64; positions outside [first, N) start no row).
@@ -656,7 +674,7 @@ __global__ __launch_bounds__(kBlock) void plan_lookup_slots_grouped_kernel(int64
     bool head = false;
     if (real) {
         const uint32_t place = gw.place(k);
-        lookup_slots[where.iter_off[gw.batch(k)] + place - first] = (int32_t)gw.slot(k);
+        if (lookup_slots) lookup_slots[where.iter_off[gw.batch(k)] + place - first] = (int32_t)gw.slot(k);
         grouped_lookups[p - first] = (int32_t)place;
         head = p == first || (k >> gw.pb) != (before >> gw.pb);
     }
@@ -852,7 +870,7 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
         if (iter_offsets[i + 1] < iter_offsets[i]) return fail(BP_ERR_INVALID_ARG, "iter_offsets decreases at %d", i);
     if (!plan->prefetch_offsets || !plan->evict_offsets || !plan->keep_offsets || !plan->occupancy)
         return fail(BP_ERR_INVALID_ARG, "a host output array of the plan is NULL");
-    if (N > 0 && ((N_real > 0 && (!ids || !plan->lookup_slots)) || !plan->prefetch_ids || !plan->prefetch_slots ||
+    if (N > 0 && ((N_real > 0 && (!ids || (!plan->lookup_slots && !plan->grouped_lookups))) || !plan->prefetch_ids || !plan->prefetch_slots ||
                   !plan->evict_ids || !plan->evict_slots || !plan->keep_ids || !plan->keep_ttl))
         return fail(BP_ERR_INVALID_ARG, "a device array of the plan is NULL");
     if (!workspace || ((uintptr_t)workspace & 255)) return fail(BP_ERR_INVALID_ARG, "workspace NULL or not 256-byte aligned");
@@ -961,7 +979,8 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
         vcover = w.vcover;
     }
     const int j_first = shift, j_last = shift + n_emit - 1;      // the batches whose occupancy counts
-    BP_LAUNCH(K_PLAN_OCC, plan_occ_prefix_kernel, grid_for(Lcap), dim3(kBlock), 0, stream, w.H, T, Lcap);
+    BP_LAUNCH(K_PLAN_OCC, plan_occ_prefix_kernel, dim3((unsigned)ceil_div(Lcap, kBlock / kWave)), dim3(kBlock), 0, stream, w.H,
+              T, Lcap);
     BP_LAUNCH(K_PLAN_OCC, plan_occ_peak_kernel, dim3(T), dim3(kBlock), 0, stream, (const uint32_t*)w.H,
               (const uint32_t*)w.ucount, vcover, j_first, j_last, T, Lcap, w.peak);
     BP_LAUNCH(K_PLAN_OCC, plan_choose_kernel, dim3(1), dim3(64), 0, stream, (const uint32_t*)w.peak,

@@ -48,8 +48,10 @@ def state_shape(rows: int, dim: int, optimizer: int):
 class CachedEmbeddingTrainer:
     def __init__(self, cfg: B.bp_config, backing_w, backing_state=None, device="cuda:0", max_lookups: int = 0,
                  max_bags: int = 0, grouping: bool = True, duplex: bool = True, handoff: bool = True,
-                 interleave: Optional[bool] = None):
-        """interleave: keep a cached row's optimizer state right behind its weights, one record per slot (None: do so
+                 interleave: Optional[bool] = None, slot_map: bool = True):
+        """slot_map=False (with grouping, bags of one lookup): the plan carries no slot per lookup and the forward pass
+        walks the row records like the backward pass (bp_embbag_fwd_grouped), which saves the planner a scattering pass.
+        interleave: keep a cached row's optimizer state right behind its weights, one record per slot (None: do so
         for the element-wise rule, whose state is as large as the row: a 192-byte row and its state then fill three
         whole 128-byte lines where two arrays touch four).  self.cache_w / self.cache_state are then strided views."""
         import torch
@@ -59,6 +61,7 @@ class CachedEmbeddingTrainer:
         self.backing_w = backing_w
         self.backing_state = backing_state
         self.grouping = grouping
+        self.slot_map = slot_map or not grouping
         self.duplex = duplex           # both link directions at once in maintain(); needs a plan with L_eff >= 2
         self.handoff = handoff         # maintenance in one launch; needs a whole-trace plan with L_eff >= 2
         self._early = None
@@ -107,7 +110,7 @@ class CachedEmbeddingTrainer:
         self.iter_offsets = np.ascontiguousarray(iter_offsets, dtype=np.int64)
         self._n_emit, self._plan_state, self._carried_evict = None, None, None
         self.plan_ = B.bp_oracle_plan(self.cfg, ids_dev, self.iter_offsets, list_capacity=list_capacity,
-                                      workspace=workspace, grouping=self.grouping)
+                                      workspace=workspace, grouping=self.grouping, slot_map=self.slot_map)
         self.close()
         self._early = None
         if self.handoff and self.plan_.L_eff >= 2:
@@ -211,11 +214,22 @@ class CachedEmbeddingTrainer:
             raise RuntimeError("bp_cache_apply_handoff met a slot pairing that is not the plan's: the cache is corrupt")
 
     # ---- (3)
-    def forward(self, i: int, bag_offsets_dev, bags: int, out=None, stream=None):
-        sl = self.slots(i)
-        self._reserve(int(sl.numel()), bags)
+    def forward(self, i: int, bag_offsets_dev, bags: int, out=None, stream=None, grouped: Optional[bool] = None):
+        """grouped: walk the plan's row records instead of a slot per lookup (bags of one lookup only); None: do so
+        when the plan carries no slot map."""
+        p = self.plan_
+        a, b = int(self.iter_offsets[i]), int(self.iter_offsets[i + 1])
+        self._reserve(b - a, bags)
         out = self._out[:bags] if out is None else out
-        B.bp_embbag_fwd(self.cfg, self._cw, sl, bag_offsets_dev, bags, out, stream=stream)
+        if (p.lookup_slots is None) if grouped is None else grouped:
+            if bag_offsets_dev is not None:
+                raise ValueError("the forward pass over the row records takes bags of one lookup; plan with slot_map=True")
+            ka, kb = int(p.keep_offsets[i]), int(p.keep_offsets[i + 1])
+            pa, pb = int(p.piece_offsets[i]), int(p.piece_offsets[i + 1])
+            B.bp_embbag_fwd_grouped(self.cfg, self._cw, p.grouped_lookups[a:b], p.row_recs[ka:kb], p.piece_recs[pa:pb],
+                                    bags, out, stream=stream)
+        else:
+            B.bp_embbag_fwd(self.cfg, self._cw, p.lookup_slots[a:b], bag_offsets_dev, bags, out, stream=stream)
         return out
 
     # ---- (4)

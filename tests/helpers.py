@@ -139,11 +139,15 @@ def make_backing(cfg, pinned=True, chunk_rows=1 << 20):
 
 
 def gpu_cached_training(cfg, trace, T=None, pinned=True, capacity=None, check_outputs=None, grouping=True,
-                        duplex=None, overlapped=False, reserve=0, handoff=None, pass_grad=False, ids_dev=None):
+                        duplex=None, overlapped=False, reserve=0, handoff=None, pass_grad=False, ids_dev=None,
+                        forward_grouped=None):
     """Runs plan + T iterations of cache_apply / fwd / bwd_update + flush through the C ABI.
     check_outputs(i, out_tensor) is called after every forward (with pass_grad: check_outputs(i, out_tensor,
     grad_tensor), the batch's upstream gradient on the device).  Returns (trainer, plan, W, S).
-    overlapped=True: cache maintenance runs on the library's maintenance stream (bp_pipeline_*)."""
+    overlapped=True: cache maintenance runs on the library's maintenance stream (bp_pipeline_*).
+    forward_grouped: the forward pass walks the plan's row records (bp_embbag_fwd_grouped) instead of the slot map;
+    None: wherever that entry point applies (a plan with the grouping, bags of one lookup), so that the runs with
+    grouping=False and the bags of several lookups keep bp_embbag_fwd's kernels covered."""
     from paper_2202_12429_amd.runner import CachedEmbeddingTrainer
     T = trace.iter_offsets.shape[0] - 1 if T is None else T
     bcfg = bp_config_of(cfg, capacity, reserve)
@@ -156,6 +160,8 @@ def gpu_cached_training(cfg, trace, T=None, pinned=True, capacity=None, check_ou
     plan = tr.plan(ids_dev, trace.iter_offsets[:T + 1])
     del ids_dev
     bags = trace.bag_offsets.shape[1] - 1
+    if forward_grouped is None:
+        forward_grouped = bool(grouping and cfg.one_hot)
     if overlapped:
         tr.begin()
     for i in range(T):
@@ -165,7 +171,7 @@ def gpu_cached_training(cfg, trace, T=None, pinned=True, capacity=None, check_ou
             tr.acquire(i)
         else:
             tr.maintain(i)
-        out = tr.forward(i, bo, bags)
+        out = tr.forward(i, bo, bags, grouped=forward_grouped)
         if check_outputs is not None and not overlapped:
             check_outputs(i, out, g) if pass_grad else check_outputs(i, out)
         tr.backward_update(i, bo, bags, g)

@@ -103,6 +103,84 @@ def test_forward_edge_cases(bp):
     assert e.value.status == -1
 
 
+def one_hot_grouping(slots, C):
+    """Row and piece records of one batch of single-lookup bags whose rows are the slots themselves."""
+    off = np.array([0, len(slots)], dtype=np.int64)
+    gl, rows, _, pieces, _ = grouping.build_grouping(slots.astype(np.int64), off, slots)
+    return gl, rows, pieces
+
+
+@pytest.mark.parametrize("D,dtype,pad", [(16, "f32", 0), (48, "f32", 0), (48, "f32", 192), (64, "f32", 0), (128, "bf16", 0),
+                                         (8, "bf16", 16), (4, "f32", 0), (256, "f32", 0)])
+def test_forward_grouped(bp, D, dtype, pad):
+    """bp_embbag_fwd_grouped against the oracle's row copies and against bp_embbag_fwd, bit for bit: short rows, rows
+    of one piece and of several pieces, a ragged tail; dense and strided cache rows."""
+    say(f"forward over row records D={D} {dtype} pad={pad}")
+    C, bags = 5000, 30011
+    rng = np.random.default_rng(D * 11 + pad)
+    w = random_cache(C, D, dtype, D + 1)
+    slots = np.minimum(rng.zipf(1.25, size=bags) - 1, C - 1).astype(np.int32)       # slot 0: thousands of lookups
+    assert np.bincount(slots).max() > 3 * grouping.PIECE
+    gl, rows, pieces = one_hot_grouping(slots, C)
+    esz = 2 if dtype == "bf16" else 4
+    if pad:
+        buf = torch.zeros((C, D * esz + pad), dtype=torch.uint8)
+        buf[:, :D * esz] = w.view(torch.uint8).reshape(C, D * esz)
+        cfg = bp.make_config(10 * C, C, D, dtype, cache_w_stride=D * esz + pad)
+        wd = buf.cuda()
+    else:
+        cfg = bp.make_config(10 * C, C, D, dtype)
+        wd = w.cuda()
+    out = torch.full((bags, D), float("nan"), device="cuda")
+    bp.bp_embbag_fwd_grouped(cfg, wd, dev(gl), dev(rows), dev(pieces), bags, out)
+    ref = torch.full((bags, D), float("nan"), device="cuda")
+    bp.bp_embbag_fwd(cfg, wd, dev(slots), None, bags, ref)
+    torch.cuda.synchronize()
+    off = np.arange(bags + 1, dtype=np.int64)
+    want = oracle.train_iter(cache_numpy(w), None, D, oracle.DTYPES[dtype], oracle.SGD, 0.0, 0.0, slots, off, None)
+    got = out.cpu().numpy()
+    assert np.array_equal(got, want.astype(np.float32))
+    assert np.array_equal(got, ref.cpu().numpy())
+
+
+def test_forward_grouped_edge_cases(bp):
+    say("forward over row records: edge cases")
+    C, D, bags = 64, 16, 40
+    w = random_cache(C, D, "f32", 3)
+    cfg = bp.make_config(1000, C, D)
+    empty_i32 = torch.zeros(0, dtype=torch.int32, device="cuda")
+    bp.bp_embbag_fwd_grouped(cfg, w.cuda(), empty_i32, torch.zeros((0, 4), dtype=torch.int32, device="cuda"), None, 0,
+                             torch.zeros((0, D), device="cuda"))
+    rng = np.random.default_rng(5)
+    slots = rng.integers(0, 8, size=bags).astype(np.int32)
+    gl, rows, pieces = one_hot_grouping(slots, C)
+    rows = rows.copy()
+    u = rows.view(np.uint32)
+    # records that name a slot outside the cache, lookups outside the batch or no lookups write nothing
+    dead = {0: (2, 1 << 30), 1: (1, bags + 5), 2: (1, 0)}
+    skipped = np.zeros(bags, dtype=bool)
+    for r, (col, val) in dead.items():
+        a, n = int(u[r, 0] & 0x7fffffff), int(u[r, 1])
+        skipped[gl[a:a + n]] = True
+        u[r, col] = val
+    gl2 = gl.copy()
+    a5, n5 = int(u[5, 0] & 0x7fffffff), int(u[5, 1])
+    assert n5 >= 2
+    skipped[gl[a5 + 1]] = True
+    gl2[a5 + 1] = bags + 7                                   # a grouped lookup that names no bag of the batch
+    skipped[u[3, 3]] = True
+    u[3, 3] = bags + 9                                       # nor does this row's first lookup
+    out = torch.full((bags, D), 7.0, device="cuda")
+    bp.bp_embbag_fwd_grouped(cfg, w.cuda(), dev(gl2), dev(rows), dev(pieces), bags, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert np.array_equal(got[~skipped], w.numpy()[slots[~skipped]])
+    assert (got[skipped] == 7.0).all()
+    with pytest.raises(bp.BagpipeError) as e:                # more rows than lookups cannot be a batch's records
+        bp.bp_embbag_fwd_grouped(cfg, w.cuda(), dev(gl[:3]), dev(rows), None, 3, out)
+    assert e.value.status == -1
+
+
 # ---------------------------------------------------------------------------------------------------
 # backward + update
 # ---------------------------------------------------------------------------------------------------
@@ -459,7 +537,8 @@ def assert_plan_equal(got, want, N):
         assert np.array_equal(getattr(got, name), getattr(want, oname)), name
     for name in ("prefetch_ids", "prefetch_slots", "evict_ids", "evict_slots", "keep_ids", "keep_ttl"):
         assert np.array_equal(getattr(got, name).cpu().numpy(), getattr(want, name)), name
-    assert np.array_equal(got.lookup_slots.cpu().numpy(), want.lookup_slots[:N]), "lookup_slots"
+    if got.lookup_slots is not None:
+        assert np.array_equal(got.lookup_slots.cpu().numpy(), want.lookup_slots[:N]), "lookup_slots"
 
 
 def assert_grouping_valid(got, want, ids, off):
@@ -480,6 +559,10 @@ def plan_both(bp, ids, off, R, L, C):
     plain = bp.bp_oracle_plan(cfg, dev(ids), off)                  # without the optional outputs: same plan
     assert_plan_equal(plain, want, len(ids))
     assert plain.grouped_lookups is None
+    lean = bp.bp_oracle_plan(cfg, dev(ids), off, grouping=True, slot_map=False)   # grouping without the slot map
+    assert lean.lookup_slots is None
+    assert_plan_equal(lean, want, len(ids))
+    assert_grouping_valid(lean, want, ids, off)
     return got, want
 
 
