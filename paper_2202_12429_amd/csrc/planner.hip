@@ -23,6 +23,7 @@
 //   8. (optional) one more stable pass on the batch bits, with the slot in place of the id in every word, lists every
 //      batch's lookups grouped by row, with the work-item cuts the grouped backward pass uses, so that the backward
 //      pass need not sort
+#include <cstring>
 #include <vector>
 
 #include "common.h"
@@ -45,6 +46,8 @@ struct PlanScalars {
     int32_t L_requested;    // configured lookahead, or the start-up rule's value when none is configured
     int64_t peak;
     int64_t min_capacity;
+    uint32_t n_pairs;       // unique (id, batch) pairs
+    uint32_t reserved;
 };
 
 // ---- 1. keys ---------------------------------------------------------------------------------
@@ -278,8 +281,10 @@ __global__ __launch_bounds__(kBlock) void plan_occ_peak_kernel(const uint32_t* _
 // one thread: pick L_eff, exclusive scan of the per-batch unique counts
 __global__ void plan_choose_kernel(const uint32_t* __restrict__ peak, const uint32_t* __restrict__ ucount,
                                    const uint32_t* __restrict__ first_use, int T, int Lcap, int lookahead, int64_t budget,
-                                   int carried_batches, PlanScalars* sc, uint32_t* __restrict__ pair_off) {
+                                   int carried_batches, const uint32_t* __restrict__ n_pairs, PlanScalars* sc,
+                                   uint32_t* __restrict__ pair_off) {
     if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    sc->n_pairs = *n_pairs;          // comes back to the host with the lookahead, in one copy
     int requested = lookahead, top = Lcap;
     if (lookahead == 0) {
         // no lookahead configured (Section 4): batches are prefetched at start-up until the cache is full; the
@@ -527,9 +532,11 @@ __global__ __launch_bounds__(kBlock) void plan_list_slots_kernel(const uint64_t*
                                                                  const int32_t* __restrict__ slot_of_pair,
                                                                  const int32_t* __restrict__ ring0, int64_t C,
                                                                  int32_t* __restrict__ prefetch_slots,
-                                                                 int32_t* __restrict__ evict_slots) {
+                                                                 int32_t* __restrict__ evict_slots,
+                                                                 uint64_t* __restrict__ totals_out) {
     const uint32_t n_miss = (uint32_t)*totals, n_evict = (uint32_t)(*totals >> 32);
     const uint32_t x = blockIdx.x * kBlock + threadIdx.x;
+    if (x == 0) *totals_out = *totals;               // where the host's one copy at the end finds them
     if (x < n_miss) prefetch_slots[x] = resolved_slot(par[x], ring0, C);
     if (x < n_evict) evict_slots[x] = slot_of_pair[evict_pair[x]];
 }
@@ -645,8 +652,10 @@ struct GroupRecordOut {
 };
 __global__ __launch_bounds__(kBlock) void plan_piece_partial_kernel(uint4* __restrict__ piece_recs,
                                                                     const uint32_t* __restrict__ n_pieces, int T,
-                                                                    const int64_t* __restrict__ multi_off) {
+                                                                    const int64_t* __restrict__ multi_off,
+                                                                    uint64_t* __restrict__ totals_out) {
     const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i == 0) *totals_out = *reinterpret_cast<const uint64_t*>(n_pieces);    // pieces | pieces of rows of several
     if (i >= (int64_t)*n_pieces) return;
     uint4 r = piece_recs[2 * i + 1];
     if (r.z < (uint32_t)T) r.y -= (uint32_t)multi_off[r.z];
@@ -776,7 +785,7 @@ PlanWorkspace carve_plan(void* base, size_t cap, int64_t N, int T, int Lcap, boo
     w.scalars = c.take<PlanScalars>(1);
     w.occ = c.take<int64_t>(T);
     // the per-batch offsets the host reads at the end, side by side so that one copy fetches them all
-    w.offsets = c.take<int64_t>(5 * (size_t)(T + 1));
+    w.offsets = c.take<int64_t>(5 * (size_t)(T + 1) + 2);       // + the totals of the lists and of the pieces
     w.prefetch_off = w.offsets;
     w.evict_off = w.offsets + (T + 1);
     w.piece_off = w.offsets + 2 * (size_t)(T + 1);
@@ -954,10 +963,7 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
     // ---- 2. unique pairs
     BP_TRY((device_scan<uint32_t, AddOp, HeadFlagIn, PairOut>(HeadFlagIn{skeys, pb}, PairOut{skeys, pb, ukey, uq, w.pair_start}, N,
                                                               w.scan_partials32, AddOp(), 0u, stream)));
-    uint32_t M = 0;
-    PlanScalars hs{};
     const uint32_t* n_pairs_dev = w.scan_partials32 + scan_num_tiles(N);     // stays valid until the next 32-bit scan
-    BP_HIP(hipMemcpyAsync(&M, n_pairs_dev, sizeof(uint32_t), hipMemcpyDeviceToHost, stream));   // read after the sync below
 
     // ---- 3. occupancy for every candidate lookahead, L_eff
     // H, ucount, first_use, V, vcover and peak lie one after the other in the workspace: one clear for all of them
@@ -985,13 +991,19 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
               (const uint32_t*)w.ucount, vcover, j_first, j_last, T, Lcap, w.peak);
     BP_LAUNCH(K_PLAN_OCC, plan_choose_kernel, dim3(1), dim3(64), 0, stream, (const uint32_t*)w.peak,
               (const uint32_t*)w.ucount, (const uint32_t*)w.first_use, T, Lcap, cfg->lookahead, C - cfg->reserve, shift,
-              w.scalars, w.pair_off);
+              n_pairs_dev, w.scalars, w.pair_off);
     BP_LAUNCH(K_PLAN_OCC, plan_occ_final_kernel, grid_for(T), dim3(kBlock), 0, stream, (const uint32_t*)w.H,
               (const uint32_t*)w.ucount, vcover, T, (const PlanScalars*)w.scalars, w.occ);
-    std::vector<int64_t> hocc((size_t)T);
-    BP_HIP(hipMemcpyAsync(&hs, w.scalars, sizeof(PlanScalars), hipMemcpyDeviceToHost, stream));
-    BP_HIP(hipMemcpyAsync(hocc.data(), w.occ, sizeof(int64_t) * T, hipMemcpyDeviceToHost, stream));
+    // the scalars and the occupancies lie side by side: one copy (every copy to pageable memory holds the host up
+    // until the stream has drained, and the stream then idles until the next launch arrives)
+    const size_t report_bytes = (size_t)((const char*)(w.occ + T) - (const char*)w.scalars);
+    std::vector<char> report(report_bytes);
+    BP_HIP(hipMemcpyAsync(report.data(), w.scalars, report_bytes, hipMemcpyDeviceToHost, stream));
     BP_HIP(hipStreamSynchronize(stream));
+    PlanScalars hs;
+    std::memcpy(&hs, report.data(), sizeof(hs));
+    const int64_t* hocc = reinterpret_cast<const int64_t*>(report.data() + ((const char*)w.occ - (const char*)w.scalars));
+    const uint32_t M = hs.n_pairs;
     if (hs.error_flags & 1u) return fail(BP_ERR_ID_OUT_OF_RANGE, "an id lies outside [0, %lld)", (long long)cfg->total_rows);
     plan->n_unique_pairs = M;
     if ((int64_t)M > plan->list_capacity)
@@ -1040,16 +1052,12 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
               (const uint32_t*)w.missord, (const uint32_t*)w.par, ring0, C, w.slot_of_pair);
     BP_LAUNCH(K_PLAN_SLOTS, plan_list_slots_kernel, grid_for(M), dim3(kBlock), 0, stream, totals, (const uint32_t*)w.par,
               (const uint32_t*)w.evict_pair, (const int32_t*)w.slot_of_pair, ring0, C, plan->prefetch_slots,
-              plan->evict_slots);
+              plan->evict_slots, reinterpret_cast<uint64_t*>(w.offsets + 5 * (size_t)(T + 1)));
     if (!grouping && N_real)      // with grouping the slot map is written from the batch-grouped order (step 8)
         BP_LAUNCH(K_PLAN_SLOTS, plan_lookup_slots_kernel, grid_for(N), dim3(kBlock), 0, stream, N, R0, ib, pb, skeys,
                   (const int64_t*)w.iter_off, (const uint32_t*)uq, (const int32_t*)w.slot_of_pair, plan->lookup_slots);
 
-    uint64_t htot = 0;     // miss / evict totals: fetched now, the grouping scan below reuses the partials buffer
-    BP_HIP(hipMemcpyAsync(&htot, totals, sizeof(uint64_t), hipMemcpyDeviceToHost, stream));
-
     // ---- 8. grouping for the backward pass
-    uint64_t n_pieces_multi = 0;
     if (grouping) {
         // one pass as a rule (batch bits <= 9): out of the sorted words into the spare buffer; a second pass would
         // come back into the sorted words' own buffer, which nobody reads any more by then
@@ -1083,20 +1091,21 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
             rows_bound, w.scan_partials64, AddOp(), uint64_t(0), stream)));
         const uint32_t* n_pieces_dev = reinterpret_cast<const uint32_t*>(w.scan_partials64 + scan_num_tiles(rows_bound));
         BP_LAUNCH(K_PLAN_GROUP, plan_piece_partial_kernel, grid_for((int64_t)piece_capacity_for(N_real)), dim3(kBlock), 0,
-                  stream, reinterpret_cast<uint4*>(plan->piece_recs), n_pieces_dev, T, (const int64_t*)w.multi_off);
-        BP_HIP(hipMemcpyAsync(&n_pieces_multi, w.scan_partials64 + scan_num_tiles(rows_bound), sizeof(uint64_t),
-                              hipMemcpyDeviceToHost, stream));
+                  stream, reinterpret_cast<uint4*>(plan->piece_recs), n_pieces_dev, T, (const int64_t*)w.multi_off,
+                  reinterpret_cast<uint64_t*>(w.offsets + 5 * (size_t)(T + 1) + 1));
     }
 
     // ---- CSR offsets to the host (in chunk mode: of the emitted batches; positions in the device lists, so the
     // first offset is where the carried residents' own entries end)
-    std::vector<int64_t> hoffsets(5 * (size_t)(T + 1));     // one copy: the five arrays lie side by side
+    std::vector<int64_t> hoffsets(5 * (size_t)(T + 1) + 2);     // one copy: the five arrays and the totals lie side by side
     BP_HIP(hipMemcpyAsync(hoffsets.data(), w.offsets, sizeof(int64_t) * hoffsets.size(), hipMemcpyDeviceToHost, stream));
     BP_HIP(hipStreamSynchronize(stream));
     int64_t* const hpre = hoffsets.data();
     int64_t* const hev = hpre + (T + 1);
     int64_t* const hpiece = hpre + 2 * (size_t)(T + 1);
     const uint32_t* const hpair = reinterpret_cast<const uint32_t*>(hpre + 4 * (size_t)(T + 1));
+    const uint64_t htot = (uint64_t)hoffsets[5 * (size_t)(T + 1)];
+    const uint64_t n_pieces_multi = grouping ? (uint64_t)hoffsets[5 * (size_t)(T + 1) + 1] : 0;
     const int64_t n_miss = (int64_t)(uint32_t)htot, n_evict = (int64_t)(htot >> 32);
     hpre[T] = n_miss;
     hev[T] = n_evict;
