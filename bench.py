@@ -237,8 +237,10 @@ def main() -> int:
 
     # runs: (placement of the backing table, schedule).  The overlapped runs plan with the reserve, the synchronous ones
     # without.
-    # bags of one lookup: forward and backward both walk the plan's row records, so the plan carries no slot per lookup
-    lean = bool(cfg.one_hot) and not args.slot_map
+    # bags of one lookup: forward and backward both walk the plan's row records, so the plan carries no slot per lookup.
+    # Not where an output row is a whole number of 128-byte lines: the flat forward kernel's streaming stores are then
+    # at their best and leave the L2 to the table rows (configs[4]: 2.10 against 2.07 G lookups/s)
+    lean = bool(cfg.one_hot) and (D * 4) % 128 != 0 and not args.slot_map
     KERNEL_OF["embbag_fwd"] = "embbag_fwd_rows_kernel" if lean else "embbag_fwd_onehot_kernel"
 
     def make_trainer(cfg_, w_, s_):

@@ -1030,7 +1030,7 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
                                                      &ord_in_b)));
     const uint64_t* srec = ord_in_b ? w.rec_b : w.rec_a;
     const uint32_t* ord = ord_in_b ? w.val2_b : w.val2_a;
-    // prefetch, evict, item and split offsets start at -1 ("this batch owns no entry")
+    // prefetch, evict, piece and several-piece offsets start at -1 ("this batch owns no entry")
     BP_LAUNCH(K_FILL, fill_kernel<int64_t>, grid_for(4 * (T + 1)), dim3(kBlock), 0, stream, w.offsets, (int64_t)(4 * (T + 1)),
               (int64_t)-1);
     BP_TRY((device_scan<uint64_t, AddOp, ListCountIn, ListOut>(

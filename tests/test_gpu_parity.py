@@ -643,7 +643,7 @@ def test_plan_word_field_boundaries(bp, largest):
 
 
 def test_plan_degenerate_traces(bp):
-    """One id takes every lookup (one pair per batch, one row spanning every work item of a batch); every lookup has
+    """One id takes every lookup (one pair per batch, one row of many pieces per batch); every lookup has
     an id of its own (no reuse at all: nothing is ever kept); one lookup in the whole trace."""
     say("plan degenerate traces")
     off = np.array([0, 700, 700, 1500, 1501], dtype=np.int64)
