@@ -539,9 +539,8 @@ def main() -> int:
                  "slot_map": not lean,
                  "with_slot_map_ms": None if t_plan_slot_map is None else t_plan_slot_map * 1e3,
                  "note": "bp_oracle_plan over the whole trace with the grouping, host synchronisation included, median "
-                         "of 5; as the step uses it: without a slot per lookup where every bag has one lookup (both "
-                         "passes then walk the row records); with_slot_map_ms: the same plan with that output too "
-                         "(binding included: it allocates the outputs)"},
+                         "of 5; as the step uses it: without a slot per lookup where both passes walk the row records "
+                         "(slot_map false); with_slot_map_ms: the same plan with that output too"},
         "cache_apply": {"rows_moved_per_step": moved / K, "row_bytes_with_state": row_b + state_b,
                         "hbm_table": apply_rate(m),
                         "pinned_host_table": apply_rate(pin_sync) if pin_sync else None},
