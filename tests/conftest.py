@@ -10,6 +10,8 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu on the GPU box)")
+    import helpers
+    helpers.CAPTURE = config.pluginmanager.getplugin("capturemanager")     # helpers.say() prints past the capture
 
 
 @pytest.fixture(scope="session")

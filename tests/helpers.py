@@ -6,9 +6,17 @@ import oracle
 import workloads
 
 
+CAPTURE = None      # pytest's capture manager, set by conftest.py
+
+
 def say(msg):
-    """Progress line of a long test, flushed at once so that a captured or piped run still shows signs of life."""
-    print(msg, flush=True)
+    """Progress line of a long test, written past pytest's output capture and flushed at once, so that a run of
+    several minutes shows signs of life also without -s."""
+    if CAPTURE is not None:
+        with CAPTURE.global_and_fixture_disabled():
+            print(msg, flush=True)
+    else:
+        print(msg, flush=True)
 
 
 def table_to_numpy(cfg, w_f32: torch.Tensor) -> np.ndarray:
