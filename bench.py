@@ -8,12 +8,15 @@ rows = 92 % of accesses), batch 16,384 (425,984 lookups per step), lookahead 400
 the rows in HBM, element-wise Adagrad.  All inputs are seeded and synthetic.
 
 A step is one pass of the whole hot path over one batch: cache maintenance (write back the previous batch's
-evictions, load this batch's prefetches), bp_embbag_fwd, bp_embbag_bwd_update_grouped, plus the batch's share of the
-plan (bp_oracle_plan over the whole trace, median of 5, timed apart).  `value` is lookups/s of that whole step with
-every input (ids, upstream gradients, backing table) resident in HBM before the timed region starts.  Beside it:
+evictions, load this batch's prefetches), forward (bp_embbag_fwd_grouped or bp_embbag_fwd), backward + update
+(bp_embbag_bwd_update_grouped), plus the batch's share of the plan (bp_oracle_plan over the whole trace, median of 5,
+timed apart).  The K steps run that whole loop, and `ms_per_step` is its time.  `value` is the metric the benchmark spec
+names, forward + backward + update lookups/s: n / the median over the timed steps of the stream time between an
+event before the forward call and one after the backward call, taken inside that running loop, with every input
+(ids, upstream gradients, backing table) resident in HBM before the timed region starts.  Beside it:
 
-  fwd_bwd_update          lookups/s of forward + backward + update alone: n / median wall per step, the wall taken by
-                          events on the stream around the two calls of every timed step
+  whole_hot_path          lookups/s of the whole step (n / ms_per_step)
+  fwd_bwd_update          the details of `value` (spread over the steps, the same by the kernels' own durations)
   plan                    ids/s of bp_oracle_plan
   cache_apply             rows/s and GB/s of the cache maintenance, table in HBM and behind the host link
   pinned_host_end_to_end  the same trace with the backing table in pinned host memory (the workload as stated): whole
@@ -23,9 +26,9 @@ every input (ids, upstream gradients, backing table) resident in HBM before the 
   cpu_baseline            the CPU oracle on a bounded sample of the same workload, on the host's cores
 
 Every run executes the same K timed steps several times: with events on every kernel (breakdown), with events on
-the dominant kernel only (its duration inside the running loop), with no events (`value`: a launch that carries
-events costs a few microseconds on the host and on the stream), and with a pair of stream events around forward +
-backward of every step.  Prints ONE JSON line.
+the dominant kernel only (its duration inside the running loop), with no events (`ms_per_step`: a launch that
+carries events costs a few microseconds on the host and on the stream), and with a pair of stream events around
+forward + backward of every step (`value`).  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -207,12 +210,16 @@ def main() -> int:
         t0 = time.time()
         oracle.plan(trace.ids[:n_s], trace.iter_offsets[:S_it + 1], cfg.total_rows, cfg.lookahead, capacity)
         t_plan = time.time() - t0
-        cpu = {"value": n_s / (t_train_mt + t_plan), "unit": "lookups/s", "cores": threads, "kind": "oracle",
-               "sample": f"first {S_it} of {T} batches ({n_s} lookups): oracle plan {t_plan:.1f} s (one thread: a walk over "
-                         f"the batches in order) + uncached forward/backward/update {t_train_mt:.1f} s on {threads} threads",
-               "plan_ids_per_s": n_s / t_plan, "train_lookups_per_s": n_s / t_train_mt,
-               "single_thread": {"value": n_s / (t_train_1 + t_plan), "cores": 1, "train_lookups_per_s": n_s / t_train_1,
-                                 "train_s": t_train_1},
+        cpu = {"value": n_s / t_train_mt, "unit": "lookups/s", "cores": threads, "kind": "oracle",
+               "what": "the metric's part of the oracle: uncached forward + backward + update of the same batches "
+                       "(oracle.train_iter on the whole table), on the host's cores",
+               "sample": f"first {S_it} of {T} batches ({n_s} lookups): uncached forward/backward/update {t_train_mt:.1f} s on "
+                         f"{threads} threads ({t_train_1:.1f} s on one); oracle plan {t_plan:.1f} s (one thread: a walk over "
+                         f"the batches in order)",
+               "plan_ids_per_s": n_s / t_plan, "plan_cores": 1,
+               "whole_hot_path_lookups_per_s": n_s / (t_train_mt + t_plan),
+               "single_thread": {"value": n_s / t_train_1, "cores": 1, "train_s": t_train_1,
+                                 "whole_hot_path_lookups_per_s": n_s / (t_train_1 + t_plan)},
                "cpu_model": cpu_model(), "host_cores_visible": os.cpu_count()}
         del grads
         log(f"cpu oracle: {cpu['value']:.3g} lookups/s on {threads} threads, {cpu['single_thread']['value']:.3g} on one "
@@ -498,15 +505,24 @@ def main() -> int:
         return dict(best, other_schedule=other, overlapped_over_synchronous=over["value"] / sync["value"],
                     backing_table="pinned host DRAM (the workload as stated; stands in for the embedding servers)")
 
+    fbu_value = n_mean / (wall_median_us * 1e-6) if wall_median_us else None
+    place = "HBM" if hbm_resident else "pinned host DRAM"
     result = {
-        "metric": "cached EmbeddingBag lookups/s over the whole hot path (plan share + cache apply + fwd + bwd + update), "
-                  f"backing table resident in {'HBM' if hbm_resident else 'pinned host DRAM'}",
-        "value": value,
+        "metric": "cached EmbeddingBag fwd+bwd+update lookups/s: n / median stream time of forward + backward + update of "
+                  "a step, taken inside the running loop over the whole hot path (plan, cache apply, forward, backward + "
+                  f"update per batch); backing table resident in {place}",
+        "value": fbu_value if fbu_value else value,
         "unit": "lookups/s",
         "n_gpus": 1,
         "steps": K,
         "warmup": W,
         "ms_per_step": m["t_total"] / K * 1e3,
+        "ms_per_step_covers": "the whole hot path of a batch: its share of bp_oracle_plan + cache apply + forward + backward "
+                              "+ update (the loop the K steps run); `value` divides by the forward + backward + update "
+                              "part of it, `whole_hot_path` by all of it",
+        "whole_hot_path": {"value": value, "unit": "lookups/s", "ms_per_step": m["t_total"] / K * 1e3,
+                           "loop_ms_per_step": m["t_loop"] / K * 1e3, "plan_share_ms_per_step": t_plan / T * 1e3,
+                           "backing_table": place},
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -516,7 +532,7 @@ def main() -> int:
         "config": {"workload": f"configs[{cfg.index}] {cfg.name}: {cfg.num_tables} tables, {cfg.total_rows} rows, D={D} "
                                f"{cfg.weight_dtype}, batch {cfg.batch} ({int(n_mean)} lookups/step), {T} batches, "
                                f"lookahead {cfg.lookahead}, cache {capacity} rows, {cfg.optimizer}",
-                   "backing_table": "HBM-resident for `value` (every input in HBM before the timed region); pinned host "
+                   "backing_table": "HBM-resident for `value` and `whole_hot_path` (every input in HBM before the timed region); pinned host "
                                     "DRAM, as the workload states it, for `pinned_host_end_to_end`" if hbm_resident
                                     else "pinned host DRAM (too large to mirror in HBM)",
                    "schedule": f"`value`: {main_sched}; `pinned_host_end_to_end`: the faster of the synchronous schedule "
@@ -526,7 +542,7 @@ def main() -> int:
                    "capacity_note": capacity_note, "unique_rows_per_step": u_mean,
                    "kernel_sources": digest_now},
         "fwd_bwd_update": {
-            "value": n_mean / (wall_median_us * 1e-6) if wall_median_us else None, "unit": "lookups/s",
+            "value": fbu_value, "unit": "lookups/s",
             "median_wall_us_per_step": wall_median_us,
             "wall_us_min_max": [wall[0], wall[-1]] if wall else None,
             "kernel_us_per_step": fbu_ms * 1e3,
