@@ -148,21 +148,22 @@ def make_backing(cfg, pinned=True, chunk_rows=1 << 20):
 
 def gpu_cached_training(cfg, trace, T=None, pinned=True, capacity=None, check_outputs=None, grouping=True,
                         duplex=None, overlapped=False, reserve=0, handoff=None, pass_grad=False, ids_dev=None,
-                        forward_grouped=None):
+                        forward_grouped=None, slot_map=True):
     """Runs plan + T iterations of cache_apply / fwd / bwd_update + flush through the C ABI.
     check_outputs(i, out_tensor) is called after every forward (with pass_grad: check_outputs(i, out_tensor,
     grad_tensor), the batch's upstream gradient on the device).  Returns (trainer, plan, W, S).
     overlapped=True: cache maintenance runs on the library's maintenance stream (bp_pipeline_*).
     forward_grouped: the forward pass walks the plan's row records (bp_embbag_fwd_grouped) instead of the slot map;
     None: wherever that entry point applies (a plan with the grouping, bags of one lookup), so that the runs with
-    grouping=False and the bags of several lookups keep bp_embbag_fwd's kernels covered."""
+    grouping=False and the bags of several lookups keep bp_embbag_fwd's kernels covered.
+    slot_map=False: the plan carries no slot per lookup (bags of one lookup, grouping on)."""
     from paper_2202_12429_amd.runner import CachedEmbeddingTrainer
     T = trace.iter_offsets.shape[0] - 1 if T is None else T
     bcfg = bp_config_of(cfg, capacity, reserve)
     W, S = make_backing(cfg, pinned)
     # by default the sorting backward (grouping=False) also takes the older maintenance paths, so both stay covered
     tr = CachedEmbeddingTrainer(bcfg, W, S, grouping=grouping, duplex=True if duplex is None else duplex,
-                                handoff=grouping if handoff is None else handoff)
+                                handoff=grouping if handoff is None else handoff, slot_map=slot_map)
     if ids_dev is None:
         ids_dev = torch.from_numpy(trace.ids[:trace.iter_offsets[T]]).cuda()
     plan = tr.plan(ids_dev, trace.iter_offsets[:T + 1])

@@ -698,7 +698,7 @@ def test_plan_errors(bp):
 # ---------------------------------------------------------------------------------------------------
 # whole path
 # ---------------------------------------------------------------------------------------------------
-def run_end_to_end(cfg, trace, pinned=True, capacity=None, grouping=True, overlapped=False, reserve=0):
+def run_end_to_end(cfg, trace, pinned=True, capacity=None, grouping=True, overlapped=False, reserve=0, slot_map=True):
     T = trace.iter_offsets.shape[0] - 1
     Wo, So, outs = helpers.oracle_uncached(cfg, trace)
     max_bag = cfg.bag_max
@@ -707,7 +707,9 @@ def run_end_to_end(cfg, trace, pinned=True, capacity=None, grouping=True, overla
         helpers.assert_outputs_close(out.cpu().numpy(), outs[i], max_bag, same_table=(i == 0))
 
     tr, plan, W, S = helpers.gpu_cached_training(cfg, trace, pinned=pinned, capacity=capacity, check_outputs=check,
-                                                 grouping=grouping, overlapped=overlapped, reserve=reserve)
+                                                 grouping=grouping, overlapped=overlapped, reserve=reserve,
+                                                 slot_map=slot_map)
+    assert (plan.lookup_slots is None) == (not slot_map)
     C = cfg.capacity if capacity is None else capacity
     want_plan = oracle.plan(trace.ids, trace.iter_offsets, cfg.total_rows, cfg.lookahead, C, reserve=reserve)
     assert_plan_equal(plan, want_plan, trace.n_lookups)
@@ -733,6 +735,9 @@ def test_end_to_end_tiny_config(bp):
     assert plan.L_eff == 20
     plan = run_end_to_end(cfg, workloads.make_trace(cfg), grouping=False)       # backward sorts the slots itself
     assert plan.L_eff == 20
+    plan = run_end_to_end(cfg, workloads.make_trace(cfg), slot_map=False)       # no slot per lookup: both passes walk
+    assert plan.L_eff == 20                                                     # the row records
+    run_end_to_end(cfg, workloads.make_trace(cfg), slot_map=False, overlapped=True, reserve=1200)
 
 
 @pytest.mark.parametrize("grouping", [True, False])
