@@ -1,0 +1,45 @@
+"""Random-row gather yardstick of the GPU this runs on (bp_gather_calibration): how fast rows of 64 .. 512 bytes come
+out of a table far larger than the caches when nothing else runs, with 1 / 2 / 4 / 8 rows in flight per lane group.
+The ceiling any kernel that gathers rows of that size can reach; prints one table.
+
+    python -m paper_2202_12429_amd.gather_yardstick
+"""
+import math
+
+import torch
+
+import paper_2202_12429_amd as bp
+
+
+def main():
+    bp.load_library()
+    dev = "cuda:0"
+    n = 1 << 21                                          # rows fetched per launch
+    print(f"{'row B':>6s} {'in flight':>9s} {'us':>8s} {'rows/us':>8s} {'GB/s rows':>10s} {'GB/s 128B lines':>16s}", flush=True)
+    for rb in (64, 128, 192, 256, 384, 512):
+        rows_total = (2 << 30) // rb                     # a 2 GiB table
+        table = torch.empty((rows_total, rb // 4), dtype=torch.float32, device=dev).normal_()
+        g = torch.Generator(device=dev).manual_seed(rb)
+        lists = [torch.randint(0, rows_total, (n,), device=dev, generator=g, dtype=torch.int64).to(torch.int32)
+                 for _ in range(4)]
+        # 128-byte lines a row of rb bytes touches at an rb-byte stride, averaged over the alignments that occur
+        offs = {(k * rb) % 128 for k in range(128)}
+        lines = sum(math.ceil((o + rb) / 128) for o in offs) / len(offs)
+        for u in (1, 2, 4, 8):
+            sink = torch.empty((-(-n // u) + 256) * 4, dtype=torch.int32, device=dev)
+            bp.bp_gather_calibration(table, lists[0], rows_in_flight=u, sink=sink)
+            torch.cuda.synchronize()
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(12)]
+            for k, (a, b) in enumerate(ev):
+                a.record()
+                bp.bp_gather_calibration(table, lists[k % 4], rows_in_flight=u, sink=sink)
+                b.record()
+            torch.cuda.synchronize()
+            us = sorted(a.elapsed_time(b) * 1e3 for a, b in ev)[len(ev) // 2]
+            print(f"{rb:6d} {u:9d} {us:8.1f} {n / us:8.1f} {n * rb / us / 1e3:10.0f} {n * lines * 128 / us / 1e3:16.0f}",
+                  flush=True)
+        del table, lists
+
+
+if __name__ == "__main__":
+    main()
