@@ -334,6 +334,21 @@ def main() -> int:
               "note": "bp_gather_calibration: every row of one upstream-gradient buffer read once in random order, "
                       "wall clock over back-to-back launches on different buffers"}
     log(f"random row gather: {bags} rows of {D * 4} B in {gather_s * 1e6:.1f} us ({gather['GBps']:.0f} GB/s)")
+    # ---- and written: every row of an output-sized buffer once, in the same random order, nothing read but the order
+    s_bufs = [torch.empty((bags, D), dtype=torch.float32, device=dev) for _ in range(4)]
+    bp.bp_scatter_calibration(s_bufs[0], g_rows)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for r in range(40):
+        bp.bp_scatter_calibration(s_bufs[r % 4], g_rows)
+    torch.cuda.synchronize()
+    scatter_s = (time.perf_counter() - t0) / 40
+    del s_bufs
+    scatter = {"rows": bags, "row_bytes": D * 4, "us_per_launch_wall": scatter_s * 1e6, "rows_per_s": bags / scatter_s,
+               "GBps": bags * D * 4 / scatter_s / 1e9,
+               "note": "bp_scatter_calibration: every row of an output-sized buffer written once in random order, nothing "
+                       "read but the order, wall clock over back-to-back launches on four buffers in turn"}
+    log(f"random row scatter: {bags} rows of {D * 4} B in {scatter_s * 1e6:.1f} us ({scatter['GBps']:.0f} GB/s)")
     n_timed = int(n_per_iter[W:W + K].sum())
     n_mean = n_timed / K
     u_mean = float(np.diff(first_sync.plan_.keep_offsets)[W:W + K].mean())
@@ -464,6 +479,8 @@ def main() -> int:
     roofline["frac_of_measured_copy"] = roofline["achieved"] / copy_gbs
     roofline["frac_of_random_row_gather"] = roofline["achieved"] / gather["GBps"]
     roofline_fwd = roof("embbag_fwd", kernel_ms["fwd"] * 1e-3) if kernel_ms["fwd"] > 0 else None
+    if roofline_fwd is not None:
+        roofline_fwd["random_row_scatter"] = scatter
     fbu_ms = kernel_ms["fwd"] + kernel_ms["bwd_sort_and_records"] + kernel_ms["bwd_reduce_update"]
     alg_fbu = (algorithmic_bytes("embbag_fwd", n_mean, bags, u_mean, row_b, 0, D, cfg.one_hot) +
                algorithmic_bytes("bwd_reduce_update", n_mean, bags, u_mean, row_b, state_b, D, cfg.one_hot))

@@ -456,6 +456,15 @@ int bp_copy_calibration(void* dst, const void* src, size_t bytes, void* stream);
 int bp_gather_calibration(void* sink, const void* table, int64_t table_rows, int32_t row_bytes, const uint32_t* rows,
                           int64_t n, int32_t rows_in_flight, void* stream);
 
+/* Writes the n rows `rows[k]` (device uint32; a number >= table_rows is skipped; a row listed twice keeps either
+ * writer's pieces) of a device table of table_rows rows of row_bytes bytes each (multiple of 16, at most 1024; 16-byte
+ * aligned), rows_in_flight (1, 2 or 4) list entries per lane group, reading nothing but the list: the 16-byte piece
+ * c of row r written for list entry k holds the uint32 words {r, c, k, 0x5ca77e25}.  A yardstick for the rate at
+ * which randomly placed rows can be written with nothing else going on, which bounds the forward pass over one-lookup
+ * bags (one output row per lookup).  Asynchronous. */
+int bp_scatter_calibration(void* table, int64_t table_rows, int32_t row_bytes, const uint32_t* rows, int64_t n,
+                           int32_t rows_in_flight, void* stream);
+
 const char* bp_error_string(int status);
 const char* bp_last_error_message(void);   /* thread-local, valid until the thread's next failing call */
 int bp_version(void);

@@ -20,5 +20,5 @@ from .binding import (  # noqa: F401
     bp_embbag_bwd_update_grouped_static, bp_embbag_bwd_update_grouped_static_bytes,
     bp_embbag_bwd_update_grouped_static_max_bytes,
     bp_error_string, bp_last_error_message, bp_version,
-    bp_copy_calibration, bp_gather_calibration, bp_profile_enable, bp_profile_select, bp_profile_bracket_overhead, bp_profile_collect, bp_profile_get, profile_totals, profile_spread,
+    bp_copy_calibration, bp_gather_calibration, bp_scatter_calibration, bp_profile_enable, bp_profile_select, bp_profile_bracket_overhead, bp_profile_collect, bp_profile_get, profile_totals, profile_spread,
 )

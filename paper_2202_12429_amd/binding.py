@@ -114,6 +114,8 @@ def load_library():
     lib.bp_copy_calibration.restype = ctypes.c_int
     lib.bp_gather_calibration.argtypes = [vp, vp, i64, i32, vp, i64, i32, vp]
     lib.bp_gather_calibration.restype = ctypes.c_int
+    lib.bp_scatter_calibration.argtypes = [vp, i64, i32, vp, i64, i32, vp]
+    lib.bp_scatter_calibration.restype = ctypes.c_int
     lib.bp_profile_bracket_overhead.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double)]
     lib.bp_profile_bracket_overhead.restype = ctypes.c_int
     lib.bp_profile_select.argtypes = [ctypes.c_uint64]
@@ -594,6 +596,15 @@ def bp_gather_calibration(table, rows, stream=None, rows_in_flight: int = 4, sin
     _check(load_library().bp_gather_calibration(_ptr(sink), _ptr(table), int(table.shape[0]), int(row_bytes), _ptr(rows), n,
                                                 int(rows_in_flight), _stream(stream)))
     return sink
+
+
+def bp_scatter_calibration(table, rows, stream=None, rows_in_flight: int = 4) -> None:
+    """Writes table[rows[k]] for every k (table: 2-D device tensor with rows of a multiple of 16 bytes, rows: int32
+    device tensor holding uint32 row numbers), rows_in_flight list entries per lane group; piece c of row r written for
+    entry k holds the int32 words {r, c, k, 0x5ca77e25}."""
+    row_bytes = table.shape[1] * table.element_size()
+    _check(load_library().bp_scatter_calibration(_ptr(table), int(table.shape[0]), int(row_bytes), _ptr(rows),
+                                                 int(rows.numel()), int(rows_in_flight), _stream(stream)))
 
 
 def bp_profile_enable(on: bool) -> None:

@@ -167,6 +167,54 @@ struct GatherLaunch {
     }
 };
 
+// The mirror image: rows written to randomly chosen places, U per lane group, with nothing read but the row numbers
+// (how the forward pass over the plan's grouping writes the output rows of one-lookup bags).  A piece says which row,
+// which piece and which list entry wrote it.
+constexpr uint32_t kScatterMark = 0x5ca77e25u;
+template <int GW, int U>
+__global__ __launch_bounds__(256) void scatter_calibration_kernel(uint4* __restrict__ table, uint32_t table_rows, int lpr,
+                                                                  const uint32_t* __restrict__ rows, uint32_t n) {
+    const uint32_t t = blockIdx.x * 256u + threadIdx.x;
+    const uint32_t group = t / GW;
+    const int c = (int)(t % GW);
+    const uint64_t first = (uint64_t)group * U;
+    if (c >= lpr || first >= n) return;
+    uint32_t r[U];
+#pragma unroll
+    for (int j = 0; j < U; ++j) r[j] = first + j < n ? rows[first + j] : table_rows;
+#pragma unroll
+    for (int j = 0; j < U; ++j)
+        if (r[j] < table_rows) table[(size_t)r[j] * lpr + c] = make_uint4(r[j], (uint32_t)c, (uint32_t)(first + j), kScatterMark);
+}
+
+struct ScatterLaunch {
+    void* table;
+    int64_t table_rows;
+    int lpr;
+    const uint32_t* rows;
+    int64_t n;
+    hipStream_t stream;
+    int in_flight;
+    template <int GW, int U>
+    int launch() {
+        const int64_t threads = ceil_div(n, U) * GW;
+        const int64_t blocks = ceil_div(threads, 256);
+        if (blocks >= (int64_t(1) << 24)) return fail(BP_ERR_UNSUPPORTED, "scatter of %lld rows is too large for one launch", (long long)n);
+        BP_LAUNCH(K_COPY, (scatter_calibration_kernel<GW, U>), dim3((unsigned)blocks), dim3(256), 0, stream, (uint4*)table,
+                  (uint32_t)table_rows, lpr, rows, (uint32_t)n);
+        return BP_OK;
+    }
+    template <int GW, bool BF16>
+    int run() {
+        switch (in_flight) {
+            case 1: return launch<GW, 1>();
+            case 2: return launch<GW, 2>();
+            case 4: return launch<GW, 4>();
+            default: return fail(BP_ERR_INVALID_ARG, "rows_in_flight %d: 1, 2 or 4", in_flight);
+        }
+    }
+};
+
 // Does nothing: what a pair of bracketing events reads around it is the cost of the bracket itself.
 __global__ __launch_bounds__(64) void bracket_probe_kernel() {}
 
@@ -239,6 +287,21 @@ BP_EXPORT int bp_gather_calibration(void* sink, const void* table, int64_t table
     if (rows_in_flight != 1 && rows_in_flight != 2 && rows_in_flight != 4 && rows_in_flight != 8)
         return fail(BP_ERR_INVALID_ARG, "rows_in_flight %d: 1, 2, 4 or 8", rows_in_flight);
     GatherLaunch l{table, table_rows, row_bytes / 16, rows, n, sink, (hipStream_t)stream, rows_in_flight};
+    return dispatch_row(row_bytes / 16, false, l);
+}
+
+BP_EXPORT int bp_scatter_calibration(void* table, int64_t table_rows, int32_t row_bytes, const uint32_t* rows, int64_t n,
+                                     int32_t rows_in_flight, void* stream) {
+    if (!table || !rows || ((uintptr_t)table & 15))
+        return fail(BP_ERR_INVALID_ARG, "scatter needs a 16-byte aligned table and a row list");
+    if (row_bytes < 16 || row_bytes > 1024 || row_bytes % 16 != 0)
+        return fail(BP_ERR_INVALID_ARG, "row_bytes %d: a multiple of 16 in [16, 1024]", row_bytes);
+    if (table_rows < 1 || table_rows >= (int64_t(1) << 32) || n < 0 || n >= (int64_t(1) << 31))
+        return fail(BP_ERR_INVALID_ARG, "table_rows or n out of range");
+    if (n == 0) return BP_OK;
+    if (rows_in_flight != 1 && rows_in_flight != 2 && rows_in_flight != 4)
+        return fail(BP_ERR_INVALID_ARG, "rows_in_flight %d: 1, 2 or 4", rows_in_flight);
+    ScatterLaunch l{table, table_rows, row_bytes / 16, rows, n, (hipStream_t)stream, rows_in_flight};
     return dispatch_row(row_bytes / 16, false, l);
 }
 

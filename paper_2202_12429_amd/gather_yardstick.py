@@ -1,6 +1,8 @@
-"""Random-row gather yardstick of the GPU this runs on (bp_gather_calibration): how fast rows of 64 .. 512 bytes come
-out of a table far larger than the caches when nothing else runs, with 1 / 2 / 4 / 8 rows in flight per lane group.
-The ceiling any kernel that gathers rows of that size can reach; prints one table.
+"""Random-row yardsticks of the GPU this runs on.  Gather (bp_gather_calibration): how fast rows of 64 .. 512 bytes
+come out of a table far larger than the caches when nothing else runs, with 1 / 2 / 4 / 8 rows in flight per lane
+group: the ceiling any kernel that gathers rows of that size can reach.  Scatter (bp_scatter_calibration): how fast
+every row of a table is written once, in a random order and in ascending order, with nothing read but the order: the
+ceiling of a forward pass over one-lookup bags, which writes one output row per lookup.  Prints two tables.
 
     python -m paper_2202_12429_amd.gather_yardstick
 """
@@ -39,6 +41,28 @@ def main():
             print(f"{rb:6d} {u:9d} {us:8.1f} {n / us:8.1f} {n * rb / us / 1e3:10.0f} {n * lines * 128 / us / 1e3:16.0f}",
                   flush=True)
         del table, lists
+    print()
+    print(f"{'row B':>6s} {'rows':>9s} {'order':>10s} {'in flight':>9s} {'us':>8s} {'rows/us':>8s} {'GB/s rows':>10s}", flush=True)
+    for rb in (64, 128, 192, 256, 512):
+        for rows_total in (425984, 1 << 21):             # one Criteo-shaped batch of one-lookup bags; 2 M rows
+            tables = [torch.empty((rows_total, rb // 4), dtype=torch.int32, device=dev) for _ in range(4)]
+            g = torch.Generator(device=dev).manual_seed(rb)
+            orders = {"random": [torch.randperm(rows_total, device=dev, generator=g).to(torch.int32) for _ in range(4)],
+                      "ascending": [torch.arange(rows_total, device=dev, dtype=torch.int32)] * 4}
+            for name, lists in orders.items():
+                for u in (1, 2, 4):
+                    bp.bp_scatter_calibration(tables[0], lists[0], rows_in_flight=u)
+                    torch.cuda.synchronize()
+                    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(12)]
+                    for k, (a, b) in enumerate(ev):
+                        a.record()
+                        bp.bp_scatter_calibration(tables[k % 4], lists[k % 4], rows_in_flight=u)
+                        b.record()
+                    torch.cuda.synchronize()
+                    us = sorted(a.elapsed_time(b) * 1e3 for a, b in ev)[len(ev) // 2]
+                    print(f"{rb:6d} {rows_total:9d} {name:>10s} {u:9d} {us:8.1f} {rows_total / us:8.1f} "
+                          f"{rows_total * rb / us / 1e3:10.0f}", flush=True)
+            del tables, orders
 
 
 if __name__ == "__main__":

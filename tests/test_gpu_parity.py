@@ -1091,6 +1091,30 @@ def test_gather_calibration(bp, row_ints, n, u):
         bp.bp_gather_calibration(torch.from_numpy(table).cuda(), torch.from_numpy(rows).cuda(), rows_in_flight=3)
 
 
+@pytest.mark.parametrize("row_ints,n,u", [(48, 1000, 4), (16, 4097, 1), (4, 3, 2), (256, 77, 2), (64, 999, 4)])
+def test_scatter_calibration(bp, row_ints, n, u):
+    """The row-scatter yardstick writes exactly the rows it is given, every 16-byte piece of them, and nothing else."""
+    rng = np.random.default_rng(row_ints * n)
+    R = 5000
+    rows = rng.permutation(R)[:n].astype(np.int32)
+    rows[n // 2] = R + 7                                                 # out of range: skipped
+    before = rng.integers(0, 1000, size=(R, row_ints)).astype(np.int32)
+    table = torch.from_numpy(before.copy()).cuda()
+    bp.bp_scatter_calibration(table, torch.from_numpy(rows).cuda(), rows_in_flight=u)
+    torch.cuda.synchronize()
+    got = table.cpu().numpy()
+    want = before.copy().reshape(R, row_ints // 4, 4)
+    for k, r in enumerate(rows):
+        if r < R:
+            want[r, :, 0] = r
+            want[r, :, 1] = np.arange(row_ints // 4)
+            want[r, :, 2] = k
+            want[r, :, 3] = 0x5ca77e25
+    assert np.array_equal(got, want.reshape(R, row_ints))
+    with pytest.raises(bp.BagpipeError):
+        bp.bp_scatter_calibration(table, torch.from_numpy(rows).cuda(), rows_in_flight=8)
+
+
 def test_profiler_totals_and_spread(bp):
     """The event profiler: launches are counted per kernel, totals add up, the spread brackets the mean, a selection
     restricts what is recorded, and nothing is recorded once it is switched off."""
