@@ -170,6 +170,15 @@ int device_scan2(InReduce in_reduce, InApply in_apply, Out out, int64_t n, T* pa
               in_apply, out, n, (const T*)partials, op, identity);
     return BP_OK;
 }
+// Passes 2 and 3 alone, for a caller whose own kernel has left the per-tile reductions in `partials`.
+template <typename T, typename Op, typename InApply, typename Out>
+int device_scan_reduced(InApply in_apply, Out out, int64_t n, T* partials, Op op, T identity, hipStream_t stream) {
+    const int64_t tiles = scan_num_tiles(n);
+    BP_LAUNCH(K_SCAN_SPINE, (scan_spine_kernel<T, Op>), dim3(1), dim3(1024), 0, stream, partials, tiles, op, identity);
+    BP_LAUNCH(K_SCAN_APPLY, (scan_apply_kernel<T, Op, InApply, Out>), dim3((unsigned)tiles), dim3(kScanBlock), 0, stream,
+              in_apply, out, n, (const T*)partials, op, identity);
+    return BP_OK;
+}
 template <typename T, typename Op, typename In, typename Out>
 int device_scan(In in, Out out, int64_t n, T* partials, Op op, T identity, hipStream_t stream) {
     return device_scan2<T, Op, In, In, Out>(in, in, out, n, partials, op, identity, stream);
@@ -386,15 +395,18 @@ inline size_t sort_temp_words(int64_t n) {
 
 // One pass.  The histogram reads `up`, the scatter reads `src`: the same elements, but a source that has to fetch
 // more than the digit needs may leave that to the scatter alone.
+// `ready`: the pass's histogram (counts[digit][tile], as the upsweep writes it) made by a kernel of the caller's that
+// read the same elements anyway; NULL: the upsweep makes it.
 template <typename K, int IPT, int RB, typename Up, typename Src, bool VALS>
 int radix_sort_pass(const Up& up, const Src& src, K* kout, uint32_t* vout, int64_t n, int bit, int nb, uint32_t* counts,
-                    uint32_t* partials, uint32_t ntiles, hipStream_t stream) {
+                    uint32_t* partials, uint32_t ntiles, hipStream_t stream, const uint32_t* ready) {
     const int64_t ncounts = (int64_t)(1 << RB) * ntiles;
     const uint32_t mask = (1u << nb) - 1u;
-    BP_LAUNCH(K_SORT_UPSWEEP, (sort_upsweep_kernel<K, IPT, RB, Up>), dim3(sort_grid(ntiles)), dim3(kSortBlock), 0, stream,
-              up, (uint32_t)n, bit, mask, counts, ntiles);
-    BP_TRY((device_scan<uint32_t, AddOp, LoadU32, StoreExclusiveU32>(LoadU32{counts}, StoreExclusiveU32{counts}, ncounts,
-                                                                     partials, AddOp(), 0u, stream)));
+    if (!ready)
+        BP_LAUNCH(K_SORT_UPSWEEP, (sort_upsweep_kernel<K, IPT, RB, Up>), dim3(sort_grid(ntiles)), dim3(kSortBlock), 0, stream,
+                  up, (uint32_t)n, bit, mask, counts, ntiles);
+    BP_TRY((device_scan<uint32_t, AddOp, LoadU32, StoreExclusiveU32>(LoadU32{ready ? ready : counts}, StoreExclusiveU32{counts},
+                                                                     ncounts, partials, AddOp(), 0u, stream)));
     BP_LAUNCH(K_SORT_DOWNSWEEP, (sort_downsweep_kernel<K, IPT, RB, Src, VALS>), dim3(sort_grid(ntiles)), dim3(kSortBlock), 0,
               stream, src, kout, vout, (uint32_t)n, bit, mask, (const uint32_t*)counts, ntiles);
     return BP_OK;
@@ -402,19 +414,31 @@ int radix_sort_pass(const Up& up, const Src& src, K* kout, uint32_t* vout, int64
 
 template <typename K, int IPT, typename Up, typename Src, bool VALS>
 int radix_sort_one_pass(const Up& up, const Src& src, K* kout, uint32_t* vout, int64_t n, int bit, int nb,
-                        uint32_t* counts, uint32_t* partials, uint32_t ntiles, hipStream_t stream) {
+                        uint32_t* counts, uint32_t* partials, uint32_t ntiles, hipStream_t stream,
+                        const uint32_t* ready = nullptr) {
     if (nb > 8)
-        return radix_sort_pass<K, IPT, 9, Up, Src, VALS>(up, src, kout, vout, n, bit, nb, counts, partials, ntiles, stream);
-    return radix_sort_pass<K, IPT, 8, Up, Src, VALS>(up, src, kout, vout, n, bit, nb, counts, partials, ntiles, stream);
+        return radix_sort_pass<K, IPT, 9, Up, Src, VALS>(up, src, kout, vout, n, bit, nb, counts, partials, ntiles, stream,
+                                                         ready);
+    return radix_sort_pass<K, IPT, 8, Up, Src, VALS>(up, src, kout, vout, n, bit, nb, counts, partials, ntiles, stream, ready);
+}
+
+// Bits the first pass of a sort over [begin_bit, end_bit) takes (the passes share the bits evenly).
+inline int radix_first_pass_bits(int begin_bit, int end_bit) {
+    const int total = end_bit - begin_bit;
+    if (total <= 0) return 0;
+    const int passes = (total + kMaxRadixBits - 1) / kMaxRadixBits;
+    return (total + passes - 1) / passes;
 }
 
 // Stable sort of n elements by key bits [begin_bit, end_bit).  The first pass reads `first` (any source; its
 // histogram reads `first_up`, which must give the same sorted bits) and writes buffer 0, every later pass reads the
 // buffer the one before wrote and writes the other one; *result says which buffer holds the sorted output (-1: no
 // pass ran, nothing was written).  VALS: 32-bit values travel with the keys.  n < 2^32 - kSortBlock*IPT.
+// first_counts: the first pass's histogram where a kernel of the caller's has made it already (radix_sort_pass).
 template <typename K, int IPT, typename Up, typename Src, bool VALS>
 int radix_sort_from(const Up& first_up, const Src& first, K* const kbuf[2], uint32_t* const vbuf[2], int64_t n,
-                    int begin_bit, int end_bit, uint32_t* temp, hipStream_t stream, int* result) {
+                    int begin_bit, int end_bit, uint32_t* temp, hipStream_t stream, int* result,
+                    const uint32_t* first_counts = nullptr) {
     *result = -1;
     if (n <= 0 || end_bit <= begin_bit) return BP_OK;
     const uint32_t ntiles = sort_num_tiles<IPT>(n);
@@ -429,7 +453,7 @@ int radix_sort_from(const Up& first_up, const Src& first, K* const kbuf[2], uint
         const int out = p & 1;
         if (p == 0) {
             BP_TRY((radix_sort_one_pass<K, IPT, Up, Src, VALS>(first_up, first, kbuf[out], VALS ? vbuf[out] : nullptr, n, bit,
-                                                               nb, counts, partials, ntiles, stream)));
+                                                               nb, counts, partials, ntiles, stream, first_counts)));
         } else {
             const SortArrays<K> in{kbuf[out ^ 1], VALS ? vbuf[out ^ 1] : nullptr};
             BP_TRY((radix_sort_one_pass<K, IPT, SortArrays<K>, SortArrays<K>, VALS>(in, in, kbuf[out],

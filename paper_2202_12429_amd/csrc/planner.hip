@@ -143,6 +143,68 @@ struct PairOut {
     }
 };
 
+// With the grouping asked for, the regrouping sort at the end of the plan reads these same sorted words for its first
+// histogram (the batch bits).  One kernel then makes both: a workgroup takes one tile of that sort, which is a whole
+// number of the scan's tiles, counts the heads of each of them (what scan_reduce_kernel would leave in `partials`)
+// and the tile's batch digits (what sort_upsweep_kernel would leave in `counts`).  Elements are dealt to lanes as in
+// the scan, so a lane's left neighbour is the lane below it, the round before, or one word fetched per wavefront.
+template <int RB>
+__global__ __launch_bounds__(kSortBlock) void plan_head_hist_kernel(const uint64_t* __restrict__ keys, uint32_t n, int pb,
+                                                                    uint32_t* __restrict__ partials, uint32_t scan_tiles,
+                                                                    uint32_t mask, uint32_t* __restrict__ counts,
+                                                                    uint32_t ntiles) {
+    constexpr int RADIX = 1 << RB;
+    constexpr int TILE = kSortBlock * kPlanSortIPT;
+    constexpr int PARTS = TILE / kScanTile;
+    constexpr int WAVES = kSortBlock / kWave;
+    static_assert(kSortBlock == kScanBlock && TILE % kScanTile == 0, "a tile of the sort is a whole number of scan tiles");
+    __shared__ uint32_t hist[RADIX];
+    __shared__ uint32_t wave_tot[PARTS][WAVES];
+    const uint32_t tile = blockIdx.x;
+    const int w = threadIdx.x / kWave, lane = lane_id();
+    for (int d = threadIdx.x; d < RADIX; d += kSortBlock) hist[d] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int h = 0; h < PARTS; ++h) {
+        const int64_t first = (int64_t)tile * TILE + h * kScanTile + w * kScanWaveStretch;      // of this wavefront
+        uint64_t k[kScanRounds];
+#pragma unroll
+        for (int r = 0; r < kScanRounds; ++r) {
+            const int64_t i = first + r * kWave + lane;
+            k[r] = i < (int64_t)n ? keys[i] : 0;
+        }
+        uint64_t before = first > 0 && first <= (int64_t)n ? keys[first - 1] : 0;               // left of lane 0, round 0
+        uint32_t heads = 0;
+#pragma unroll
+        for (int r = 0; r < kScanRounds; ++r) {
+            const int64_t i = first + r * kWave + lane;
+            uint64_t left = __shfl_up(k[r], 1, kWave);
+            if (lane == 0) left = before;
+            before = __shfl(k[r], kWave - 1, kWave);
+            if (i < (int64_t)n) {
+                heads += (i == 0 || (k[r] >> pb) != (left >> pb)) ? 1u : 0u;
+                // as in sort_upsweep_kernel: the lanes that share the first active lane's digit count themselves at once
+                const uint32_t d = (uint32_t)(k[r] >> pb) & mask;
+                const uint32_t d0 = __builtin_amdgcn_readfirstlane(d);
+                const uint64_t same = __ballot(d == d0);
+                if (d != d0) atomicAdd(&hist[d], 1u);
+                else if ((same & lanemask_lt()) == 0) atomicAdd(&hist[d0], (uint32_t)__popcll(same));
+            }
+        }
+        heads = wave_reduce(heads, AddOp());
+        if (lane == 0) wave_tot[h][w] = heads;
+    }
+    __syncthreads();
+    if (threadIdx.x < PARTS) {
+        const uint32_t st = tile * PARTS + threadIdx.x;
+        uint32_t total = 0;
+#pragma unroll
+        for (int i = 0; i < WAVES; ++i) total += wave_tot[threadIdx.x][i];
+        if (st < scan_tiles) partials[st] = total;
+    }
+    for (int d = threadIdx.x; d < RADIX; d += kSortBlock) counts[(size_t)d * ntiles + tile] = hist[d];
+}
+
 // ---- 3. gaps, histogram, occupancy -----------------------------------------------------------
 __device__ __forceinline__ uint32_t pair_gap(const uint64_t* ukey, uint32_t q, uint32_t M, int ib, uint64_t imask) {
     if (q + 1 >= M) return kGapInf;
@@ -760,6 +822,7 @@ struct PlanWorkspace {
     int64_t* cuts;           // trainer cuts of every batch, [T][kMaxTrainers + 1] at most
     int32_t* slot_of_pair;
     uint64_t* keys_c;      // grouping only: the other half of the regrouping sort's ping-pong
+    uint32_t* group_counts;   // grouping only: the regrouping sort's first histogram, made by the head scan's first pass
     int64_t* piece_off;
     int64_t* multi_off;
     size_t bytes;
@@ -805,6 +868,7 @@ PlanWorkspace carve_plan(void* base, size_t cap, int64_t N, int T, int Lcap, boo
     w.slot_of_pair = c.take<int32_t>(n);
     if (grouping) {
         w.keys_c = c.take<uint64_t>(n);
+        w.group_counts = c.take<uint32_t>((size_t)kMaxRadix * sort_num_tiles<kPlanSortIPT>(N));
     }
     w.bytes = c.used();
     return w;
@@ -961,8 +1025,22 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
     uint32_t* uq = w.uq;
 
     // ---- 2. unique pairs
-    BP_TRY((device_scan<uint32_t, AddOp, HeadFlagIn, PairOut>(HeadFlagIn{skeys, pb}, PairOut{skeys, pb, ukey, uq, w.pair_start}, N,
-                                                              w.scan_partials32, AddOp(), 0u, stream)));
+    const int group_bits = grouping ? radix_first_pass_bits(pb, pb + ib) : 0;     // of the regrouping sort's first pass
+    if (grouping) {
+        const uint32_t ntiles = sort_num_tiles<kPlanSortIPT>(N);
+        const uint32_t mask = (1u << group_bits) - 1u;
+        if (group_bits > 8)
+            BP_LAUNCH(K_SCAN_REDUCE, plan_head_hist_kernel<9>, dim3(ntiles), dim3(kSortBlock), 0, stream, skeys, (uint32_t)N, pb,
+                      w.scan_partials32, (uint32_t)scan_num_tiles(N), mask, w.group_counts, ntiles);
+        else
+            BP_LAUNCH(K_SCAN_REDUCE, plan_head_hist_kernel<8>, dim3(ntiles), dim3(kSortBlock), 0, stream, skeys, (uint32_t)N, pb,
+                      w.scan_partials32, (uint32_t)scan_num_tiles(N), mask, w.group_counts, ntiles);
+        BP_TRY((device_scan_reduced<uint32_t, AddOp, HeadFlagIn, PairOut>(
+            HeadFlagIn{skeys, pb}, PairOut{skeys, pb, ukey, uq, w.pair_start}, N, w.scan_partials32, AddOp(), 0u, stream)));
+    } else {
+        BP_TRY((device_scan<uint32_t, AddOp, HeadFlagIn, PairOut>(HeadFlagIn{skeys, pb}, PairOut{skeys, pb, ukey, uq, w.pair_start},
+                                                                  N, w.scan_partials32, AddOp(), 0u, stream)));
+    }
     const uint32_t* n_pairs_dev = w.scan_partials32 + scan_num_tiles(N);     // stays valid until the next 32-bit scan
 
     // ---- 3. occupancy for every candidate lookahead, L_eff
@@ -1066,7 +1144,7 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
         uint64_t* const gbuf[2] = {w.keys_c, const_cast<uint64_t*>(skeys)};
         int g_in = -1;
         BP_TRY((radix_sort_from<uint64_t, kPlanSortIPT, SortArrays<uint64_t>, GroupWordSource, false>(
-            gup, gsrc, gbuf, no_vals, N, pb, pb + ib, w.sort_temp, stream, &g_in)));
+            gup, gsrc, gbuf, no_vals, N, pb, pb + ib, w.sort_temp, stream, &g_in, w.group_counts)));
         const uint64_t* gkeys = gbuf[g_in];
         const GroupWord gw{ib, pb};
         // one pass over the grouped words: slot map, grouped_lookups, row starts as bit masks (the masks go to a

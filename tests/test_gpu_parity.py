@@ -668,6 +668,13 @@ def test_plan_many_batches_wide_group_keys(bp):
     ids = np.minimum(rng.zipf(1.3, size=int(off[-1])) - 1, R - 1).astype(np.int64)
     plan_both(bp, ids, off, R, 50, 1 << 20)
     plan_both(bp, ids, off, R, 7, 9)                       # same trace, narrow keys, capacity binds
+    # 300 batches: nine batch bits, which the regrouping sort takes in one pass of 512 digits; several sort tiles
+    T = 300
+    lens = rng.integers(0, 120, size=T)
+    off = np.zeros(T + 1, dtype=np.int64)
+    off[1:] = np.cumsum(lens)
+    ids = np.minimum(rng.zipf(1.2, size=int(off[-1])) - 1, 4999).astype(np.int64)
+    plan_both(bp, ids, off, 5000, 12, 1500)
 
 
 def test_plan_errors(bp):
