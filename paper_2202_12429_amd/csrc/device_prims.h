@@ -222,6 +222,19 @@ struct SortArrays {
     };
 };
 
+// Keys whose values are their own places in the array (a sort that is to return the permutation it applied).
+template <typename K>
+struct SortKeysNumbered {
+    const K* keys;
+    typedef K Raw;
+    __device__ __forceinline__ K load(uint32_t i) const { return keys[i]; }
+    __device__ __forceinline__ uint32_t val(uint32_t i) const { return i; }
+    struct Cursor {
+        __device__ __forceinline__ Cursor(const SortKeysNumbered&, uint32_t) {}
+        __device__ __forceinline__ K key(uint32_t, K raw) { return raw; }
+    };
+};
+
 template <typename K, int IPT, int RB, typename Src>
 __global__ __launch_bounds__(kSortBlock) void sort_upsweep_kernel(Src src, uint32_t n, int shift, uint32_t mask,
                                                                   uint32_t* __restrict__ counts, uint32_t ntiles) {
@@ -478,6 +491,21 @@ int radix_sort_pairs(K* keys_a, K* keys_b, uint32_t* vals_a, uint32_t* vals_b, i
     const SortArrays<K> in{keys_a, vals_a};
     BP_TRY((radix_sort_from<K, IPT, SortArrays<K>, SortArrays<K>, true>(in, in, kbuf, vbuf, n, begin_bit, end_bit, temp, stream,
                                                                         &result)));
+    *result_in_b = result == 0;
+    return BP_OK;
+}
+
+// The same with the values 0 .. n-1 in the order of the input: vals_a is scratch, nobody has to fill it.
+template <typename K, int IPT>
+int radix_sort_numbered(K* keys_a, K* keys_b, uint32_t* vals_a, uint32_t* vals_b, int64_t n, int begin_bit, int end_bit,
+                        uint32_t* temp, hipStream_t stream, bool* result_in_b) {
+    K* const kbuf[2] = {keys_b, keys_a};
+    uint32_t* const vbuf[2] = {vals_b, vals_a};
+    int result = -1;
+    const SortArrays<K> up{keys_a, nullptr};
+    const SortKeysNumbered<K> in{keys_a};
+    BP_TRY((radix_sort_from<K, IPT, SortArrays<K>, SortKeysNumbered<K>, true>(up, in, kbuf, vbuf, n, begin_bit, end_bit, temp,
+                                                                              stream, &result)));
     *result_in_b = result == 0;
     return BP_OK;
 }

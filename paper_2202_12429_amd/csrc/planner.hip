@@ -404,22 +404,42 @@ struct PairRecord {
     __device__ __forceinline__ int64_t id(uint64_t r) const { return (int64_t)(r >> (2 * ib + 2)); }
 };
 
+// The search for the TTL probes up to L_eff - 1 pairs ahead, one probe behind the other: the workgroup first copies
+// its own pairs, the one before them and the next kFlagsWindow into LDS, where a probe costs a fraction of a trip to
+// L2 (probes beyond that window go to memory as before).
+constexpr int kFlagsWindow = 1024;
 __global__ __launch_bounds__(kBlock) void plan_flags_kernel(const uint64_t* __restrict__ ukey, uint32_t M, int ib,
-                                                            const PlanScalars* sc, int chunk, uint64_t* __restrict__ rec,
-                                                            uint32_t* __restrict__ val2) {
-    const uint32_t q = blockIdx.x * kBlock + threadIdx.x;
-    if (q >= M) return;
+                                                            const PlanScalars* sc, int chunk, uint64_t* __restrict__ rec) {
+    __shared__ uint64_t win[kBlock + 1 + kFlagsWindow];
     const uint64_t imask = (uint64_t(1) << ib) - 1;
     const int64_t Leff = sc->L_eff;
-    const uint64_t k = ukey[q];
+    const int64_t win_first = (int64_t)blockIdx.x * kBlock - 1;                 // pair number of win[0]
+    const int ahead = (int)(Leff - 1 < kFlagsWindow ? (Leff > 1 ? Leff - 1 : 0) : kFlagsWindow);
+    const int span = kBlock + 1 + ahead;
+    for (int t = threadIdx.x; t < span; t += kBlock) {
+        const int64_t p = win_first + t;
+        win[t] = p >= 0 && p < (int64_t)M ? ukey[p] : ~uint64_t(0);
+    }
+    __syncthreads();
+    const uint32_t q = blockIdx.x * kBlock + threadIdx.x;
+    if (q >= M) return;
+    const auto key_at = [&](int64_t p) -> uint64_t {                            // q - 1 <= p < M
+        const int64_t t = p - win_first;
+        return t < span ? win[t] : ukey[p];
+    };
+    const uint64_t k = key_at(q);
     const uint64_t g = k >> ib;
     const int64_t i = (int64_t)(k & imask);
-    const uint32_t gap = pair_gap(ukey, q, M, ib, imask);
+    uint32_t gap = kGapInf;
+    if (q + 1 < M) {
+        const uint64_t kn = key_at((int64_t)q + 1);
+        if ((kn >> ib) == g) gap = (uint32_t)((kn & imask) - (k & imask));
+    }
     const bool carried = chunk && i == 0;              // resident since before the chunk: stays until its next use
     const bool keep = carried || (int64_t)gap < Leff;
     bool miss = true;
     if (q > 0) {
-        const uint64_t kp = ukey[q - 1];
+        const uint64_t kp = key_at((int64_t)q - 1);
         if ((kp >> ib) == g && ((chunk && (kp & imask) == 0) || i - (int64_t)(kp & imask) < Leff)) miss = false;
     }
     uint32_t t = (uint32_t)i;
@@ -427,16 +447,15 @@ __global__ __launch_bounds__(kBlock) void plan_flags_kernel(const uint64_t* __re
         // last pair of this id whose batch is <= i + L_eff - 1: it lies within L_eff - 1 pairs of q
         const int64_t last_iter = i + Leff - 1 < (int64_t)imask ? i + Leff - 1 : (int64_t)imask;
         const uint64_t bound = (g << ib) | (uint64_t)last_iter;
-        int64_t lo = q, hi = (int64_t)q + Leff - 1;     // ukey[lo] <= bound; answer in [lo, hi]
+        int64_t lo = q, hi = (int64_t)q + Leff - 1;     // pair lo <= bound; answer in [lo, hi]
         if (hi > (int64_t)M - 1) hi = (int64_t)M - 1;
         while (lo < hi) {
             const int64_t mid = (lo + hi + 1) >> 1;
-            if (ukey[mid] <= bound) lo = mid; else hi = mid - 1;
+            if (key_at(mid) <= bound) lo = mid; else hi = mid - 1;
         }
-        t = (uint32_t)(ukey[lo] & imask);
+        t = (uint32_t)(key_at(lo) & imask);
     }
     rec[q] = PairRecord{ib}.pack(g, t, (miss ? kMiss : 0) | (keep ? 0 : kEvict), (uint32_t)i);
-    val2[q] = q;
 }
 
 struct MissIndexIn {
@@ -1098,13 +1117,13 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
 
     // ---- 4. flags, TTL, fetching pair of every pair
     BP_LAUNCH(K_PLAN_FLAGS, plan_flags_kernel, grid_for(M), dim3(kBlock), 0, stream, (const uint64_t*)ukey, M, ib,
-              (const PlanScalars*)w.scalars, (int)chunk, w.rec_a, w.val2_a);
+              (const PlanScalars*)w.scalars, (int)chunk, w.rec_a);
     BP_TRY((device_scan<uint32_t, MaxOp, MissIndexIn, StoreInclusiveU32>(MissIndexIn{w.rec_a, ib}, StoreInclusiveU32{w.chain},
                                                                          M, w.scan_partials32, MaxOp(), 0u, stream)));
 
     // ---- 5. regroup by batch (the records travel as keys), lists
     bool ord_in_b = false;
-    BP_TRY((radix_sort_pairs<uint64_t, kPlanSortIPT>(w.rec_a, w.rec_b, w.val2_a, w.val2_b, M, 0, ib, w.sort_temp, stream,
+    BP_TRY((radix_sort_numbered<uint64_t, kPlanSortIPT>(w.rec_a, w.rec_b, w.val2_a, w.val2_b, M, 0, ib, w.sort_temp, stream,
                                                      &ord_in_b)));
     const uint64_t* srec = ord_in_b ? w.rec_b : w.rec_a;
     const uint32_t* ord = ord_in_b ? w.val2_b : w.val2_a;
