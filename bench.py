@@ -329,11 +329,27 @@ def main() -> int:
         bp.bp_gather_calibration(grads_dev[r], g_rows)
     torch.cuda.synchronize()
     gather_s = (time.perf_counter() - t0) / reps
-    gather = {"rows": bags, "row_bytes": D * 4, "us_per_launch_wall": gather_s * 1e6, "rows_per_s": bags / gather_s,
+
+    def median_us_by_events(launch, n_launches):
+        """Median duration of the yardstick's launches by the event brackets that time the kernels of the step."""
+        bp.bp_profile_select(["copy_calibration"])
+        bp.bp_profile_enable(True)
+        for r in range(n_launches):
+            launch(r)
+        torch.cuda.synchronize()
+        bp.bp_profile_collect()
+        med = bp.profile_spread("copy_calibration")[1] * 1e3
+        bp.bp_profile_enable(False)
+        bp.bp_profile_select(None)
+        return med
+    gather_ev_us = median_us_by_events(lambda r: bp.bp_gather_calibration(grads_dev[r % reps], g_rows), 40)
+    gather = {"rows": bags, "row_bytes": D * 4, "us_per_launch_wall": gather_s * 1e6, "us_per_launch_events": gather_ev_us,
+              "rows_per_s": bags / gather_s,
               "GBps": bags * D * 4 / gather_s / 1e9,
               "note": "bp_gather_calibration: every row of one upstream-gradient buffer read once in random order, "
-                      "wall clock over back-to-back launches on different buffers"}
-    log(f"random row gather: {bags} rows of {D * 4} B in {gather_s * 1e6:.1f} us ({gather['GBps']:.0f} GB/s)")
+                      "us_per_launch_wall: wall clock over back-to-back launches on different buffers; us_per_launch_events: median by the event brackets that time the kernels"}
+    log(f"random row gather: {bags} rows of {D * 4} B in {gather_s * 1e6:.1f} us back to back, {gather_ev_us:.1f} us by "
+        f"events ({gather['GBps']:.0f} GB/s)")
     # ---- and written: every row of an output-sized buffer once, in the same random order, nothing read but the order
     s_bufs = [torch.empty((bags, D), dtype=torch.float32, device=dev) for _ in range(4)]
     bp.bp_scatter_calibration(s_bufs[0], g_rows)
@@ -343,12 +359,15 @@ def main() -> int:
         bp.bp_scatter_calibration(s_bufs[r % 4], g_rows)
     torch.cuda.synchronize()
     scatter_s = (time.perf_counter() - t0) / 40
+    scatter_ev_us = median_us_by_events(lambda r: bp.bp_scatter_calibration(s_bufs[r % 4], g_rows), 40)
     del s_bufs
-    scatter = {"rows": bags, "row_bytes": D * 4, "us_per_launch_wall": scatter_s * 1e6, "rows_per_s": bags / scatter_s,
+    scatter = {"rows": bags, "row_bytes": D * 4, "us_per_launch_wall": scatter_s * 1e6, "us_per_launch_events": scatter_ev_us,
+               "rows_per_s": bags / scatter_s,
                "GBps": bags * D * 4 / scatter_s / 1e9,
                "note": "bp_scatter_calibration: every row of an output-sized buffer written once in random order, nothing "
-                       "read but the order, wall clock over back-to-back launches on four buffers in turn"}
-    log(f"random row scatter: {bags} rows of {D * 4} B in {scatter_s * 1e6:.1f} us ({scatter['GBps']:.0f} GB/s)")
+                       "read but the order; us_per_launch_wall: wall clock over back-to-back launches on four buffers in turn; us_per_launch_events: median by the event brackets that time the kernels"}
+    log(f"random row scatter: {bags} rows of {D * 4} B in {scatter_s * 1e6:.1f} us back to back, {scatter_ev_us:.1f} us by "
+        f"events ({scatter['GBps']:.0f} GB/s)")
     n_timed = int(n_per_iter[W:W + K].sum())
     n_mean = n_timed / K
     u_mean = float(np.diff(first_sync.plan_.keep_offsets)[W:W + K].mean())
@@ -481,6 +500,8 @@ def main() -> int:
     roofline_fwd = roof("embbag_fwd", kernel_ms["fwd"] * 1e-3) if kernel_ms["fwd"] > 0 else None
     if roofline_fwd is not None:
         roofline_fwd["random_row_scatter"] = scatter
+        # the forward kernel's own time over the time of its stores alone, both by the same event brackets
+        roofline_fwd["kernel_us_over_scatter_us"] = kernel_ms["fwd"] * 1e3 / scatter_ev_us if cfg.one_hot else None
     fbu_ms = kernel_ms["fwd"] + kernel_ms["bwd_sort_and_records"] + kernel_ms["bwd_reduce_update"]
     alg_fbu = (algorithmic_bytes("embbag_fwd", n_mean, bags, u_mean, row_b, 0, D, cfg.one_hot) +
                algorithmic_bytes("bwd_reduce_update", n_mean, bags, u_mean, row_b, state_b, D, cfg.one_hot))

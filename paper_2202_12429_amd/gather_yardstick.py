@@ -13,6 +13,23 @@ import torch
 import paper_2202_12429_amd as bp
 
 
+def median_us(launch, launches=12):
+    """Median duration of `launches` launches by the library's own event brackets (the kernel's begin and end, as for
+    the kernels of a training step), after one launch that is not counted."""
+    launch(0)
+    torch.cuda.synchronize()
+    bp.bp_profile_select(["copy_calibration"])
+    bp.bp_profile_enable(True)
+    for k in range(launches):
+        launch(k)
+    torch.cuda.synchronize()
+    bp.bp_profile_collect()
+    med = bp.profile_spread("copy_calibration")[1] * 1e3
+    bp.bp_profile_enable(False)
+    bp.bp_profile_select(None)
+    return med
+
+
 def main():
     bp.load_library()
     dev = "cuda:0"
@@ -29,15 +46,7 @@ def main():
         lines = sum(math.ceil((o + rb) / 128) for o in offs) / len(offs)
         for u in (1, 2, 4, 8):
             sink = torch.empty((-(-n // u) + 256) * 4, dtype=torch.int32, device=dev)
-            bp.bp_gather_calibration(table, lists[0], rows_in_flight=u, sink=sink)
-            torch.cuda.synchronize()
-            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(12)]
-            for k, (a, b) in enumerate(ev):
-                a.record()
-                bp.bp_gather_calibration(table, lists[k % 4], rows_in_flight=u, sink=sink)
-                b.record()
-            torch.cuda.synchronize()
-            us = sorted(a.elapsed_time(b) * 1e3 for a, b in ev)[len(ev) // 2]
+            us = median_us(lambda k: bp.bp_gather_calibration(table, lists[k % 4], rows_in_flight=u, sink=sink))
             print(f"{rb:6d} {u:9d} {us:8.1f} {n / us:8.1f} {n * rb / us / 1e3:10.0f} {n * lines * 128 / us / 1e3:16.0f}",
                   flush=True)
         del table, lists
@@ -51,15 +60,7 @@ def main():
                       "ascending": [torch.arange(rows_total, device=dev, dtype=torch.int32)] * 4}
             for name, lists in orders.items():
                 for u in (1, 2, 4):
-                    bp.bp_scatter_calibration(tables[0], lists[0], rows_in_flight=u)
-                    torch.cuda.synchronize()
-                    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(12)]
-                    for k, (a, b) in enumerate(ev):
-                        a.record()
-                        bp.bp_scatter_calibration(tables[k % 4], lists[k % 4], rows_in_flight=u)
-                        b.record()
-                    torch.cuda.synchronize()
-                    us = sorted(a.elapsed_time(b) * 1e3 for a, b in ev)[len(ev) // 2]
+                    us = median_us(lambda k: bp.bp_scatter_calibration(tables[k % 4], lists[k % 4], rows_in_flight=u))
                     print(f"{rb:6d} {rows_total:9d} {name:>10s} {u:9d} {us:8.1f} {rows_total / us:8.1f} "
                           f"{rows_total * rb / us / 1e3:10.0f}", flush=True)
             del tables, orders
