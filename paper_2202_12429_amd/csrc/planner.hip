@@ -47,7 +47,7 @@ struct PlanScalars {
     int64_t peak;
     int64_t min_capacity;
     uint32_t n_pairs;       // unique (id, batch) pairs
-    uint32_t reserved;
+    uint32_t ring_open;     // bit k: the k-th launch of the ring's chain walk left a chain short of its end
 };
 
 // ---- 1. keys ---------------------------------------------------------------------------------
@@ -405,57 +405,62 @@ struct PairRecord {
 };
 
 // The search for the TTL probes up to L_eff - 1 pairs ahead, one probe behind the other: the workgroup first copies
-// its own pairs, the one before them and the next kFlagsWindow into LDS, where a probe costs a fraction of a trip to
-// L2 (probes beyond that window go to memory as before).
+// its own pairs (kFlagsPerThread per thread), the one before them and the next kFlagsWindow into LDS, where a probe
+// costs a fraction of a trip to L2 (probes beyond that window go to memory as before).
 constexpr int kFlagsWindow = 1024;
+constexpr int kFlagsPerThread = 4;
+constexpr int kFlagsTile = kBlock * kFlagsPerThread;
 __global__ __launch_bounds__(kBlock) void plan_flags_kernel(const uint64_t* __restrict__ ukey, uint32_t M, int ib,
                                                             const PlanScalars* sc, int chunk, uint64_t* __restrict__ rec) {
-    __shared__ uint64_t win[kBlock + 1 + kFlagsWindow];
+    __shared__ uint64_t win[kFlagsTile + 1 + kFlagsWindow];
     const uint64_t imask = (uint64_t(1) << ib) - 1;
     const int64_t Leff = sc->L_eff;
-    const int64_t win_first = (int64_t)blockIdx.x * kBlock - 1;                 // pair number of win[0]
+    const int64_t win_first = (int64_t)blockIdx.x * kFlagsTile - 1;             // pair number of win[0]
     const int ahead = (int)(Leff - 1 < kFlagsWindow ? (Leff > 1 ? Leff - 1 : 0) : kFlagsWindow);
-    const int span = kBlock + 1 + ahead;
+    const int span = kFlagsTile + 1 + ahead;
     for (int t = threadIdx.x; t < span; t += kBlock) {
         const int64_t p = win_first + t;
         win[t] = p >= 0 && p < (int64_t)M ? ukey[p] : ~uint64_t(0);
     }
     __syncthreads();
-    const uint32_t q = blockIdx.x * kBlock + threadIdx.x;
-    if (q >= M) return;
-    const auto key_at = [&](int64_t p) -> uint64_t {                            // q - 1 <= p < M
+    const auto key_at = [&](int64_t p) -> uint64_t {                            // first pair of the tile - 1 <= p < M
         const int64_t t = p - win_first;
         return t < span ? win[t] : ukey[p];
     };
-    const uint64_t k = key_at(q);
-    const uint64_t g = k >> ib;
-    const int64_t i = (int64_t)(k & imask);
-    uint32_t gap = kGapInf;
-    if (q + 1 < M) {
-        const uint64_t kn = key_at((int64_t)q + 1);
-        if ((kn >> ib) == g) gap = (uint32_t)((kn & imask) - (k & imask));
-    }
-    const bool carried = chunk && i == 0;              // resident since before the chunk: stays until its next use
-    const bool keep = carried || (int64_t)gap < Leff;
-    bool miss = true;
-    if (q > 0) {
-        const uint64_t kp = key_at((int64_t)q - 1);
-        if ((kp >> ib) == g && ((chunk && (kp & imask) == 0) || i - (int64_t)(kp & imask) < Leff)) miss = false;
-    }
-    uint32_t t = (uint32_t)i;
-    if (keep && !carried) {
-        // last pair of this id whose batch is <= i + L_eff - 1: it lies within L_eff - 1 pairs of q
-        const int64_t last_iter = i + Leff - 1 < (int64_t)imask ? i + Leff - 1 : (int64_t)imask;
-        const uint64_t bound = (g << ib) | (uint64_t)last_iter;
-        int64_t lo = q, hi = (int64_t)q + Leff - 1;     // pair lo <= bound; answer in [lo, hi]
-        if (hi > (int64_t)M - 1) hi = (int64_t)M - 1;
-        while (lo < hi) {
-            const int64_t mid = (lo + hi + 1) >> 1;
-            if (key_at(mid) <= bound) lo = mid; else hi = mid - 1;
+#pragma unroll
+    for (int e = 0; e < kFlagsPerThread; ++e) {
+        const uint32_t q = blockIdx.x * kFlagsTile + e * kBlock + threadIdx.x;
+        if (q >= M) break;
+        const uint64_t k = key_at(q);
+        const uint64_t g = k >> ib;
+        const int64_t i = (int64_t)(k & imask);
+        uint32_t gap = kGapInf;
+        if (q + 1 < M) {
+            const uint64_t kn = key_at((int64_t)q + 1);
+            if ((kn >> ib) == g) gap = (uint32_t)((kn & imask) - (k & imask));
         }
-        t = (uint32_t)(key_at(lo) & imask);
+        const bool carried = chunk && i == 0;              // resident since before the chunk: stays until its next use
+        const bool keep = carried || (int64_t)gap < Leff;
+        bool miss = true;
+        if (q > 0) {
+            const uint64_t kp = key_at((int64_t)q - 1);
+            if ((kp >> ib) == g && ((chunk && (kp & imask) == 0) || i - (int64_t)(kp & imask) < Leff)) miss = false;
+        }
+        uint32_t t = (uint32_t)i;
+        if (keep && !carried) {
+            // last pair of this id whose batch is <= i + L_eff - 1: it lies within L_eff - 1 pairs of q
+            const int64_t last_iter = i + Leff - 1 < (int64_t)imask ? i + Leff - 1 : (int64_t)imask;
+            const uint64_t bound = (g << ib) | (uint64_t)last_iter;
+            int64_t lo = q, hi = (int64_t)q + Leff - 1;     // pair lo <= bound; answer in [lo, hi]
+            if (hi > (int64_t)M - 1) hi = (int64_t)M - 1;
+            while (lo < hi) {
+                const int64_t mid = (lo + hi + 1) >> 1;
+                if (key_at(mid) <= bound) lo = mid; else hi = mid - 1;
+            }
+            t = (uint32_t)(key_at(lo) & imask);
+        }
+        rec[q] = PairRecord{ib}.pack(g, t, (miss ? kMiss : 0) | (keep ? 0 : kEvict), (uint32_t)i);
     }
-    rec[q] = PairRecord{ib}.pack(g, t, (miss ? kMiss : 0) | (keep ? 0 : kEvict), (uint32_t)i);
 }
 
 struct MissIndexIn {
@@ -572,18 +577,25 @@ __global__ __launch_bounds__(kBlock) void plan_ring_init_kernel(const uint64_t* 
 // times over a trace and the first launch does it all).  Lanes read entries that other lanes may have advanced
 // already: either value lies on the same chain, the newer one nearer to its end.
 constexpr int kRingHops = 64;
+// A launch that follows one which brought every chain to its end has nothing to do and says so at once.
 __global__ __launch_bounds__(kBlock) void plan_ring_resolve_kernel(const uint64_t* __restrict__ totals, int max_hops,
-                                                                   uint32_t* par) {
+                                                                   uint32_t* par, PlanScalars* sc, int launch) {
+    if (launch > 0 && ((sc->ring_open >> (launch - 1)) & 1u) == 0u) return;
     const uint32_t n_miss = (uint32_t)*totals;
     const uint32_t x = blockIdx.x * kBlock + threadIdx.x;
     if (x >= n_miss) return;
     uint32_t p = par[x];
+    bool ended = false;
     for (int hop = 0; hop < max_hops; ++hop) {
         const uint32_t pp = p < n_miss ? par[p] : 0u;
-        if (pp == p) break;
+        if (pp == p) {
+            ended = true;
+            break;
+        }
         p = pp;
     }
     par[x] = p;
+    if (!ended) atomicOr(&sc->ring_open, 1u << launch);
 }
 
 // ---- 7. slots --------------------------------------------------------------------------------
@@ -1116,7 +1128,8 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
     plan->peak_occupancy = hs.peak;
 
     // ---- 4. flags, TTL, fetching pair of every pair
-    BP_LAUNCH(K_PLAN_FLAGS, plan_flags_kernel, grid_for(M), dim3(kBlock), 0, stream, (const uint64_t*)ukey, M, ib,
+    BP_LAUNCH(K_PLAN_FLAGS, plan_flags_kernel, dim3((unsigned)(M > 0 ? ceil_div((int64_t)M, kFlagsTile) : 1)), dim3(kBlock), 0,
+              stream, (const uint64_t*)ukey, M, ib,
               (const PlanScalars*)w.scalars, (int)chunk, w.rec_a);
     BP_TRY((device_scan<uint32_t, MaxOp, MissIndexIn, StoreInclusiveU32>(MissIndexIn{w.rec_a, ib}, StoreInclusiveU32{w.chain},
                                                                          M, w.scan_partials32, MaxOp(), 0u, stream)));
@@ -1141,8 +1154,10 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
     // ---- 6. ring
     BP_LAUNCH(K_PLAN_JUMP, plan_ring_init_kernel, grid_for(M), dim3(kBlock), 0, stream, totals, C,
               (const uint32_t*)w.evict_pair, (const uint32_t*)w.chain, (const uint32_t*)w.missord, w.par);
+    int ring_launch = 0;
     for (int64_t reach = 1; reach < (int64_t)T + 1; reach *= kRingHops)
-        BP_LAUNCH(K_PLAN_JUMP, plan_ring_resolve_kernel, grid_for(M), dim3(kBlock), 0, stream, totals, kRingHops, w.par);
+        BP_LAUNCH(K_PLAN_JUMP, plan_ring_resolve_kernel, grid_for(M), dim3(kBlock), 0, stream, totals, kRingHops, w.par,
+                  w.scalars, ring_launch++);
 
     // ---- 7. slots
     BP_LAUNCH(K_PLAN_SLOTS, plan_pair_slots_kernel, grid_for(M), dim3(kBlock), 0, stream, M, (const uint32_t*)w.chain,
