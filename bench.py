@@ -94,6 +94,9 @@ def main() -> int:
     ap.add_argument("--skew", type=float, default=None,
                     help="draw the ids from the skew-sensitivity law instead of Zipf: the hottest 1 %% of every "
                          "table's rows take this share of the accesses (0.01 .. 0.9)")
+    ap.add_argument("--lookahead", type=int, default=None,
+                    help="plan with this lookahead instead of the configuration's (the paper's sensitivity study: the "
+                         "planner's rate does not depend on it, the cache the plan needs does)")
     ap.add_argument("--reserve", type=int, default=-1,
                     help="cache slots the capacity policy keeps free for fetches that overlap training "
                          "(-1: 1.5 x the median per-batch miss count of the plan without reserve)")
@@ -117,6 +120,9 @@ def main() -> int:
     torch.cuda.set_device(dev)
 
     cfg = workloads.CONFIGS[args.config] if args.skew is None else workloads.skew_config(args.config, args.skew)
+    if args.lookahead is not None:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, lookahead=args.lookahead)
     T = cfg.iterations
     W = max(0, min(args.warmup, T - 1))
     K = args.steps if args.steps > 0 else T - W
