@@ -696,19 +696,29 @@ struct RowMaskIn {
     const uint64_t* head_mask;
     __device__ __forceinline__ uint32_t operator()(int64_t w) const { return (uint32_t)__popcll(head_mask[w]); }
 };
-struct RowMaskOut {
-    const uint64_t* head_mask;
-    uint32_t* row_pos;
-    __device__ __forceinline__ void operator()(int64_t w, uint32_t exc, uint32_t) const {
-        uint64_t m = head_mask[w];
-        uint32_t r = exc;
-        while (m) {
-            const int bit = __ffsll((unsigned long long)m) - 1;
-            row_pos[r++] = (uint32_t)(w * 64 + bit);
-            m &= m - 1;
-        }
+// A wavefront takes 64 mask words and goes through them one by one: lane b owns bit b of the word in hand, and the
+// lanes whose bit is set write their positions side by side, behind the rows that the scan counted before the word.
+// (Every word writing its own rows from one lane, inside the scan's last pass, scatters 64 short runs per store.)
+__global__ __launch_bounds__(kBlock) void plan_row_starts_kernel(const uint64_t* __restrict__ head_mask,
+                                                                 const uint32_t* __restrict__ rows_before, int64_t n_words,
+                                                                 uint32_t* __restrict__ row_pos) {
+    const int lane = lane_id();
+    const int64_t w0 = ((int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave) * kWave;    // wave-uniform
+    if (w0 >= n_words) return;
+    const int64_t mine = w0 + lane;
+    const uint64_t m = mine < n_words ? head_mask[mine] : 0;
+    const uint32_t before = mine < n_words ? rows_before[mine] : 0u;
+    uint64_t left = __ballot(m != 0);                                // words of this wavefront that hold a row start
+    while (left) {
+        const int t = __ffsll((unsigned long long)left) - 1;
+        left &= left - 1;
+        const uint64_t word = __shfl(m, t, kWave);
+        const uint32_t base = __shfl(before, t, kWave);
+        if ((word >> lane) & 1u)
+            row_pos[base + (uint32_t)__popcll(word & lanemask_lt())] = (uint32_t)((w0 + t) * 64 + lane);
     }
-};
+}
+
 // Second scan, over the rows (RowPiecesIn counts the pieces): every row writes its record beside its keep-list
 // entry (the carried residents of a chunk own the first `first` entries), a long row its piece records, and the
 // first row of a batch the batch's offsets.  A piece's `partial` is counted through the whole trace here and made
@@ -1190,8 +1200,11 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
         const int64_t n_words = (N + 63) / 64;
         BP_LAUNCH(K_PLAN_SLOTS, plan_lookup_slots_grouped_kernel, dim3(per_xcd * kXcds), dim3(kBlock), 0, stream, N, per_xcd,
                   gw, R0, gkeys, where, plan->lookup_slots, plan->grouped_lookups, head_mask);
-        BP_TRY((device_scan<uint32_t, AddOp, RowMaskIn, RowMaskOut>(RowMaskIn{head_mask}, RowMaskOut{head_mask, row_pos},
-                                                                   n_words, w.scan_partials32, AddOp(), 0u, stream)));
+        uint32_t* rows_before = w.val2_a;                      // free since the lists were written
+        BP_TRY((device_scan<uint32_t, AddOp, RowMaskIn, StoreExclusiveU32>(RowMaskIn{head_mask}, StoreExclusiveU32{rows_before},
+                                                                          n_words, w.scan_partials32, AddOp(), 0u, stream)));
+        BP_LAUNCH(K_PLAN_GROUP, plan_row_starts_kernel, dim3((unsigned)ceil_div(n_words, (int64_t)kBlock)), dim3(kBlock), 0,
+                  stream, (const uint64_t*)head_mask, (const uint32_t*)rows_before, n_words, row_pos);
         const uint32_t* n_rows = w.scan_partials32 + scan_num_tiles(n_words);
         // at most one row per pair (fewer only where the look-ahead batches of a chunk hold rows without a slot)
         const int64_t rows_bound = (int64_t)M - R0 > 0 ? (int64_t)M - R0 : 1;
