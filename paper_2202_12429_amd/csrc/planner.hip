@@ -340,42 +340,55 @@ __global__ __launch_bounds__(kBlock) void plan_occ_peak_kernel(const uint32_t* _
     }
 }
 
-// one thread: pick L_eff, exclusive scan of the per-batch unique counts
-__global__ void plan_choose_kernel(const uint32_t* __restrict__ peak, const uint32_t* __restrict__ ucount,
-                                   const uint32_t* __restrict__ first_use, int T, int Lcap, int lookahead, int64_t budget,
-                                   int carried_batches, const uint32_t* __restrict__ n_pairs, PlanScalars* sc,
-                                   uint32_t* __restrict__ pair_off) {
-    if (blockIdx.x != 0 || threadIdx.x != 0) return;
-    sc->n_pairs = *n_pairs;          // comes back to the host with the lookahead, in one copy
+// One wavefront: pick L_eff, exclusive scan of the per-batch unique counts.  64 candidates, or 64 batches, per step.
+__global__ __launch_bounds__(kWave) void plan_choose_kernel(const uint32_t* __restrict__ peak,
+                                                            const uint32_t* __restrict__ ucount,
+                                                            const uint32_t* __restrict__ first_use, int T, int Lcap,
+                                                            int lookahead, int64_t budget, int carried_batches,
+                                                            const uint32_t* __restrict__ n_pairs, PlanScalars* sc,
+                                                            uint32_t* __restrict__ pair_off) {
+    if (blockIdx.x != 0) return;
+    const int lane = lane_id();
     int requested = lookahead, top = Lcap;
     if (lookahead == 0) {
         // no lookahead configured (Section 4): batches are prefetched at start-up until the cache is full; the
-        // distinct rows of batches 0..k-1 are the ids whose first use lies in those batches
+        // distinct rows of batches 0..k-1 are the ids whose first use lies in those batches.  The running total
+        // never falls, so the batches that fit are a prefix and counting them finds its end.
         int64_t held = 0;
         int k = 0;
-        for (int i = 0; i < T; ++i) {
-            held += first_use[i];
+        for (int i0 = 0; i0 < T; i0 += kWave) {
+            const int i = i0 + lane;
+            const int64_t inc = held + wave_inclusive_scan<int64_t>(i < T ? (int64_t)first_use[i] : 0, AddOp());
+            k += (int)__popcll(__ballot(i < T && inc <= budget));
+            held = __shfl(inc, kWave - 1, kWave);
             if (held > budget) break;
-            k = i + 1;
         }
         requested = k - carried_batches;             // a chunk's batch 0 holds the carried residents, not lookups
         if (requested < 0) requested = 0;
         top = requested < Lcap ? requested : Lcap;
     }
-    int sel = 0;
-    for (int Lp = top; Lp >= 1; --Lp)
-        if ((int64_t)peak[Lp] <= budget) { sel = Lp; break; }
-    sc->L_sel = sel;
-    sc->L_eff = (sel == top && sel > 0) ? requested : sel;   // windows of T or more batches are all alike
-    sc->L_requested = requested;
-    sc->peak = sel ? peak[sel] : 0;
-    sc->min_capacity = peak[1];
-    uint32_t run = 0;
-    for (int i = 0; i < T; ++i) {
-        pair_off[i] = run;
-        run += ucount[i];
+    int sel = 0;                                     // the largest candidate whose peak occupancy fits
+    for (int hi = top; hi >= 1 && sel == 0; hi -= kWave) {
+        const int Lp = hi - lane;
+        const uint64_t fits = __ballot(Lp >= 1 && (int64_t)peak[Lp >= 1 ? Lp : 1] <= budget);
+        if (fits) sel = hi - (__ffsll((unsigned long long)fits) - 1);
     }
-    pair_off[T] = run;
+    uint32_t run = 0;
+    for (int i0 = 0; i0 <= T; i0 += kWave) {
+        const int i = i0 + lane;
+        const uint32_t x = i < T ? ucount[i] : 0u;
+        const uint32_t inc = run + wave_inclusive_scan<uint32_t>(x, AddOp());
+        if (i <= T) pair_off[i] = inc - x;
+        run = __shfl(inc, kWave - 1, kWave);
+    }
+    if (lane == 0) {
+        sc->n_pairs = *n_pairs;          // comes back to the host with the lookahead, in one copy
+        sc->L_sel = sel;
+        sc->L_eff = (sel == top && sel > 0) ? requested : sel;   // windows of T or more batches are all alike
+        sc->L_requested = requested;
+        sc->peak = sel ? peak[sel] : 0;
+        sc->min_capacity = peak[1];
+    }
 }
 
 __global__ void plan_occ_final_kernel(const uint32_t* __restrict__ Hc, const uint32_t* __restrict__ ucount,
