@@ -23,6 +23,7 @@
 //   8. (optional) one more stable pass on the batch bits, with the slot in place of the id in every word, lists every
 //      batch's lookups grouped by row, with the work-item cuts the grouped backward pass uses, so that the backward
 //      pass need not sort
+#include <algorithm>
 #include <cstring>
 #include <vector>
 
@@ -499,7 +500,8 @@ struct ListCountIn {
 };
 struct ListOut {
     const uint64_t* srec;
-    const uint32_t* ord;      // pair index of the k-th sorted record
+    const uint32_t* ord;      // what travelled with the k-th sorted record: its pair's number (numbered) or the
+                              // number of the pair that fetched its row, which for a miss is the pair itself
     const uint32_t* pair_off;
     int ib;
     int64_t* keep_ids;
@@ -507,7 +509,7 @@ struct ListOut {
     int64_t* prefetch_ids;
     int64_t* evict_ids;
     uint32_t* missord;
-    uint32_t* evict_pair;
+    uint32_t* evict_pair;    // for every eviction, the pair that fetched the evicted row
     int64_t* prefetch_off;   // device copies of the CSR offsets, [T+1], pre-filled with -1
     int64_t* evict_off;
     int32_t ttl_shift;       // 1 in chunk mode: the chunk's batches count from 1 inside the planner
@@ -521,6 +523,8 @@ struct ListOut {
     int pb;
     const int64_t* cuts;      // device [real batches][P + 1]
     int P;
+    const uint32_t* chain;    // the pair that fetched the row a pair uses
+    bool numbered;
     __device__ __forceinline__ int trainer_of(const int64_t* c, int64_t rel) const {
         int lo = 0, hi = P;                               // largest t < P with c[t] <= rel
         while (hi - lo > 1) {
@@ -544,7 +548,7 @@ struct ListOut {
     __device__ __forceinline__ void operator()(int64_t k, uint64_t exc, uint64_t) const {
         const PairRecord pr{ib};
         const uint64_t r = srec[k];
-        const uint32_t q = ord[k];
+        const uint32_t q = ord[k];           // not numbered: the pair's own number only where the pair is a miss
         const int64_t g = pr.id(r);
         const uint32_t i = pr.batch(r);
         const uint32_t x = (uint32_t)exc, e = (uint32_t)(exc >> 32);
@@ -558,7 +562,7 @@ struct ListOut {
         }
         if (f & kEvict) {
             evict_ids[e] = g;
-            evict_pair[e] = q;
+            evict_pair[e] = numbered ? chain[q] : q;       // the pair that fetched the row: same residency, same slot
         }
         if ((uint32_t)k == pair_off[i]) {
             prefetch_off[i] = x;
@@ -570,7 +574,6 @@ struct ListOut {
 // ---- 6. FIFO ring: chains of links ------------------------------------------------------------
 __global__ __launch_bounds__(kBlock) void plan_ring_init_kernel(const uint64_t* __restrict__ totals, int64_t C,
                                                                 const uint32_t* __restrict__ evict_pair,
-                                                                const uint32_t* __restrict__ chain,
                                                                 const uint32_t* __restrict__ missord,
                                                                 uint32_t* __restrict__ par) {
     const uint32_t n_miss = (uint32_t)*totals, n_evict = (uint32_t)(*totals >> 32);
@@ -580,7 +583,7 @@ __global__ __launch_bounds__(kBlock) void plan_ring_init_kernel(const uint64_t* 
         par[x] = x;                                   // initial ring content: slot x at position x
     } else {
         const uint32_t e = (uint32_t)((int64_t)x - C);   // ring position C + e was pushed by eviction e
-        par[x] = e < n_evict ? missord[chain[evict_pair[e]]] : 0u;
+        par[x] = e < n_evict ? missord[evict_pair[e]] : 0u;
     }
 }
 
@@ -595,20 +598,21 @@ __global__ __launch_bounds__(kBlock) void plan_ring_resolve_kernel(const uint64_
                                                                    uint32_t* par, PlanScalars* sc, int launch) {
     if (launch > 0 && ((sc->ring_open >> (launch - 1)) & 1u) == 0u) return;
     const uint32_t n_miss = (uint32_t)*totals;
-    const uint32_t x = blockIdx.x * kBlock + threadIdx.x;
-    if (x >= n_miss) return;
-    uint32_t p = par[x];
-    bool ended = false;
-    for (int hop = 0; hop < max_hops; ++hop) {
-        const uint32_t pp = p < n_miss ? par[p] : 0u;
-        if (pp == p) {
-            ended = true;
-            break;
+    for (uint64_t x64 = (uint64_t)blockIdx.x * kBlock + threadIdx.x; x64 < n_miss; x64 += (uint64_t)gridDim.x * kBlock) {
+        const uint32_t x = (uint32_t)x64;
+        uint32_t p = par[x];
+        bool ended = false;
+        for (int hop = 0; hop < max_hops; ++hop) {
+            const uint32_t pp = p < n_miss ? par[p] : 0u;
+            if (pp == p) {
+                ended = true;
+                break;
+            }
+            p = pp;
         }
-        p = pp;
+        par[x] = p;
+        if (!ended) atomicOr(&sc->ring_open, 1u << launch);
     }
-    par[x] = p;
-    if (!ended) atomicOr(&sc->ring_open, 1u << launch);
 }
 
 // ---- 7. slots --------------------------------------------------------------------------------
@@ -644,7 +648,12 @@ __global__ __launch_bounds__(kBlock) void plan_list_slots_kernel(const uint64_t*
     const uint32_t x = blockIdx.x * kBlock + threadIdx.x;
     if (x == 0) *totals_out = *totals;               // where the host's one copy at the end finds them
     if (x < n_miss) prefetch_slots[x] = resolved_slot(par[x], ring0, C);
-    if (x < n_evict) evict_slots[x] = slot_of_pair[evict_pair[x]];
+    if (x < n_evict) {
+        // The x-th eviction pushed ring position C + x.  Where a later miss took that position, its resolved link is
+        // the evicted row's own slot, read in list order; only the evictions nobody reused go through their pair.
+        const int64_t pos = C + (int64_t)x;
+        evict_slots[x] = pos < (int64_t)n_miss ? resolved_slot(par[pos], ring0, C) : slot_of_pair[evict_pair[x]];
+    }
 }
 
 // Workgroups are handed to the eight XCDs round-robin, and each XCD has an L2 of its own.  The kernels below write
@@ -1158,9 +1167,22 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
                                                                          M, w.scan_partials32, MaxOp(), 0u, stream)));
 
     // ---- 5. regroup by batch (the records travel as keys), lists
+    // What travels with a record: the number of the pair that fetched its row (for a miss that is the pair itself,
+    // which is all the lists need); with the trainer marking asked for, the pair's own number instead, and the list
+    // pass then looks the fetching pair up.
     bool ord_in_b = false;
-    BP_TRY((radix_sort_numbered<uint64_t, kPlanSortIPT>(w.rec_a, w.rec_b, w.val2_a, w.val2_b, M, 0, ib, w.sort_temp, stream,
-                                                     &ord_in_b)));
+    if (owners) {
+        BP_TRY((radix_sort_numbered<uint64_t, kPlanSortIPT>(w.rec_a, w.rec_b, w.val2_a, w.val2_b, M, 0, ib, w.sort_temp,
+                                                            stream, &ord_in_b)));
+    } else {
+        uint64_t* const rbuf[2] = {w.rec_b, w.rec_a};
+        uint32_t* const vbuf[2] = {w.val2_b, w.val2_a};
+        const SortArrays<uint64_t> rup{w.rec_a, nullptr}, rsrc{w.rec_a, w.chain};
+        int r_in = -1;
+        BP_TRY((radix_sort_from<uint64_t, kPlanSortIPT, SortArrays<uint64_t>, SortArrays<uint64_t>, true>(
+            rup, rsrc, rbuf, vbuf, M, 0, ib, w.sort_temp, stream, &r_in)));
+        ord_in_b = r_in == 0;
+    }
     const uint64_t* srec = ord_in_b ? w.rec_b : w.rec_a;
     const uint32_t* ord = ord_in_b ? w.val2_b : w.val2_a;
     // prefetch, evict, piece and several-piece offsets start at -1 ("this batch owns no entry")
@@ -1170,17 +1192,23 @@ int plan_impl(const bp_config* cfg, const int64_t* ids, const int64_t* iter_offs
         ListCountIn{srec, ib},
         ListOut{srec, ord, w.pair_off, ib, plan->keep_ids, plan->keep_ttl, plan->prefetch_ids, plan->evict_ids, w.missord,
                 w.evict_pair, w.prefetch_off, w.evict_off, shift, owners ? plan->keep_owner : nullptr, ukey, M,
-                w.pair_start, (uint32_t)N, skeys, pb, w.cuts, P},
+                w.pair_start, (uint32_t)N, skeys, pb, w.cuts, P, w.chain, owners},
         M, w.scan_partials64, AddOp(), uint64_t(0), stream)));
     const uint64_t* totals = w.scan_partials64 + scan_num_tiles(M);
 
     // ---- 6. ring
     BP_LAUNCH(K_PLAN_JUMP, plan_ring_init_kernel, grid_for(M), dim3(kBlock), 0, stream, totals, C,
-              (const uint32_t*)w.evict_pair, (const uint32_t*)w.chain, (const uint32_t*)w.missord, w.par);
+              (const uint32_t*)w.evict_pair, (const uint32_t*)w.missord, w.par);
     int ring_launch = 0;
-    for (int64_t reach = 1; reach < (int64_t)T + 1; reach *= kRingHops)
-        BP_LAUNCH(K_PLAN_JUMP, plan_ring_resolve_kernel, grid_for(M), dim3(kBlock), 0, stream, totals, kRingHops, w.par,
-                  w.scalars, ring_launch++);
+    // the first launch one thread per miss; the others, which as a rule find nothing left and are over at once, a
+    // small grid that strides over the misses
+    const int64_t ring_blocks = M > 0 ? ceil_div((int64_t)M, kBlock) : 1;
+    for (int64_t reach = 1; reach < (int64_t)T + 1; reach *= kRingHops) {
+        const dim3 ring_grid((unsigned)(ring_launch == 0 ? ring_blocks : std::min<int64_t>(ring_blocks, 2048)));
+        BP_LAUNCH(K_PLAN_JUMP, plan_ring_resolve_kernel, ring_grid, dim3(kBlock), 0, stream, totals, kRingHops, w.par,
+                  w.scalars, ring_launch);
+        ++ring_launch;
+    }
 
     // ---- 7. slots
     BP_LAUNCH(K_PLAN_SLOTS, plan_pair_slots_kernel, grid_for(M), dim3(kBlock), 0, stream, M, (const uint32_t*)w.chain,
