@@ -45,16 +45,23 @@ __global__ __launch_bounds__(256) void bwd_keys_kernel(const int32_t* __restrict
 }
 
 // Grouped variant: the plan lists lookup positions grouped by row; the gradient row of a position is its bag.
-// First every bag writes its number over its own stretch of positions (neighbouring lanes write neighbouring
-// stretches), then the grouped positions pick their bag up from that map, which stays in L2.
+// First every bag writes its number over its own stretch of positions -- a wavefront takes 64 bags and goes through
+// them one by one, its lanes writing side by side (one lane per bag would scatter 64 short runs per store) --, then
+// the grouped positions pick their bag up from that map, which stays in L2.
 __global__ __launch_bounds__(256) void bwd_bag_of_lookup_kernel(const int64_t* __restrict__ bag_off, int64_t bags, int64_t n,
                                                                 uint32_t* __restrict__ bag_of_lookup) {
-    const int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (b >= bags) return;
-    int64_t k = bag_off[b], end = bag_off[b + 1];
+    const int lane = threadIdx.x % kWave;
+    const int64_t b0 = ((int64_t)blockIdx.x * (256 / kWave) + threadIdx.x / kWave) * kWave;      // wave-uniform
+    if (b0 >= bags) return;
+    const int64_t b = b0 + lane;
+    int64_t k = b < bags ? bag_off[b] : 0, end = b < bags ? bag_off[b + 1] : 0;
     if (k < 0) k = 0;
     if (end > n) end = n;
-    for (; k < end; ++k) bag_of_lookup[k] = (uint32_t)b;
+    const int here = (int)(bags - b0 < kWave ? bags - b0 : kWave);
+    for (int t = 0; t < here; ++t) {
+        const int64_t first = __shfl(k, t, kWave), stop = __shfl(end, t, kWave);
+        for (int64_t q = first + lane; q < stop; q += kWave) bag_of_lookup[q] = (uint32_t)(b0 + t);
+    }
 }
 
 __global__ __launch_bounds__(256) void bwd_bags_of_positions_kernel(const int32_t* __restrict__ positions,
